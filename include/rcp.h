@@ -1,0 +1,184 @@
+/*
+ * rcp.h - C ABI of the MI355X (gfx950) W2A4 look-up-table GEMV path of RCP
+ * ("Rotate, Clip, and Partition", arXiv 2502.15779).
+ *
+ * The library implements the decode-time linear layer of the paper's Section 4.4
+ * ("Look-up Table (LUT) Inference for Non-uniform W2A4 GEMV") and the two steps
+ * that feed it:
+ *
+ *   rcp_pack_weights      offline export: LDP thresholds -> 2-bit indices, and the
+ *                         per-output-channel 4-entry dequantisation LUT
+ *                         (Section 4.3, Eqns. for p_i / t_i / Q_LDP / w_i, and the
+ *                         LUT equation of Section 4.4)
+ *   rcp_rotate_quant_act  online Hadamard rotation (Appendix, definition of the
+ *                         normalised Hadamard matrix; Section 2.1 for where online
+ *                         rotations sit) + per-token symmetric int4 quantisation
+ *                         (Appendix table "Quantization configurations")
+ *   rcp_w2a4_gemv         O = S * sum_k LUT[h][W_q[h][k]] * X_q[k]  (Section 4.4,
+ *                         "Fast GEMV via Latency Hiding": tensor list and shapes)
+ *
+ * General rules
+ *   - Every pointer named below is a DEVICE pointer unless it is marked "host".
+ *     All device buffers are owned by the caller; the library allocates nothing
+ *     that outlives a call and frees nothing the caller passed in.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Work
+ *     is enqueued on it and the call returns without synchronising.
+ *   - Return value: RCP_OK (0) or a negative rcp_status. On error nothing has
+ *     been enqueued and no output byte has been written; rcp_last_error() holds
+ *     a message.
+ *   - Device buffers must be 16-byte aligned (anything a GPU allocator returns).
+ *
+ * Shapes and names: the weight matrix is N (output channels, the paper's H) by
+ * K (input channels, the paper's C). M is the number of tokens (1 for GEMV).
+ *
+ * ---------------------------------------------------------------------------
+ * Data layouts
+ *
+ * Packed weight indices ("W_q"), N*K/4 bytes.  The paper stores four 2-bit
+ * indices per byte in row-major order; this library stores the same N*K 2-bit
+ * indices as bit planes so that a CDNA4 lane can feed them to the packed-int4
+ * dot instruction without per-weight shifts:
+ *   - rows are grouped four at a time: g = h / 4, r = h % 4
+ *   - columns eight at a time:         o = k / 8, j = k % 8
+ *   - a "cell" (g, o) is two little-endian uint32 words (B0, B1), 8 bytes, stored
+ *     at byte offset 8 * (g * (K/8) + o)
+ *   - bit (4*j + r) of B0 is bit 0 of idx[4g+r][8o+j]; the same bit of B1 is
+ *     bit 1 of that index.  (idx = 0..3 selects the LUT entry.)
+ *
+ * LUT / codebook ("W-hat"): fp16 [N][4], entry l of row h at half-word 4*h + l,
+ * ascending in l.
+ *
+ * Quantised activation ("X_q"): M * K/2 bytes; token m starts at byte m*K/2.
+ * Byte b holds q[2b] in its low nibble and q[2b+1] in its high nibble, each a
+ * two's-complement int4 in [-8, 7].  Scale ("S"): fp16 [M].
+ *
+ * Output ("O"): row-major M x N, fp16 or fp32.
+ * Partial sums (verification output): int32 [M][N][4],
+ *   P[m][h][l] = sum over k with idx[h][k] == l of q[m][k].
+ */
+#ifndef RCP_H
+#define RCP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RCP_OK = 0,
+    RCP_ERR_NULL = -1,        /* a required pointer is NULL                         */
+    RCP_ERR_SHAPE = -2,       /* N, K, M out of range or not a supported multiple   */
+    RCP_ERR_ALIGN = -3,       /* a device buffer is not 16-byte aligned             */
+    RCP_ERR_UNSUPPORTED = -4, /* dtype / rotation / M outside the compiled set      */
+    RCP_ERR_WORKSPACE = -5,   /* workspace missing or too small                     */
+    RCP_ERR_HIP = -6          /* the HIP runtime reported an error (see last error) */
+} rcp_status;
+
+typedef enum { RCP_F16 = 0, RCP_F32 = 1, RCP_BF16 = 2 } rcp_dtype;
+
+typedef enum {
+    RCP_ROT_NONE = 0, /* y = x (the rotation was fused into the weights offline)   */
+    RCP_ROT_WHT = 1,  /* y = H_K x, K a power of two                               */
+    RCP_ROT_KRON = 2  /* y = (H_{n_wht} (x) Q) x, K = n_wht * m                    */
+} rcp_rot_kind;
+
+/* Rotation descriptor (a host struct).  For RCP_ROT_KRON, x is viewed as an
+ * n_wht x m row-major matrix X (k = i*m + j) and Y = H_{n_wht} X Q^T, which is
+ * the standard Kronecker product H (x) Q applied to x.  Q is a DEVICE pointer to
+ * an m x m row-major fp32 orthogonal matrix; it is ignored for the other kinds. */
+typedef struct {
+    int kind;       /* rcp_rot_kind                                                */
+    int n_wht;      /* power of two: K for RCP_ROT_WHT, the Hadamard factor for KRON */
+    int m;          /* order of Q (1 for RCP_ROT_WHT)                              */
+    const float* Q; /* device, m*m floats, row-major                               */
+} rcp_rotation;
+
+/* Limits of this build. */
+#define RCP_MAX_M 16          /* tokens per call                                    */
+#define RCP_MAX_K 32768       /* input channels                                     */
+#define RCP_MAX_WHT 16384     /* largest Hadamard order of a pure WHT rotation      */
+#define RCP_MAX_KRON_M 256    /* largest order of Q                                 */
+
+/* Library version, major*10000 + minor*100 + patch. */
+int rcp_version(void);
+
+/* Message for the last error on the calling thread (host string, never NULL). */
+const char* rcp_last_error(void);
+
+/* N*K/4, the size of the packed index buffer; 0 if the shape is not supported
+ * (N must be a positive multiple of 4, K a positive multiple of 32). */
+size_t rcp_packed_bytes(int N, int K);
+
+/* Bytes of device scratch rcp_rotate_quant_act needs for this call shape
+ * (0 when none is needed).  `rot` is a host pointer and may be NULL (= NONE). */
+size_t rcp_act_workspace_bytes(int M, int K, const rcp_rotation* rot);
+
+/*
+ * Offline export (Section 4.3 "Partition"; LUT equation of Section 4.4).
+ *
+ * Per output row h with clip range [lo, hi] = [clip_lo[h], clip_hi[h]] (the
+ * learned sigma(beta)*min and sigma(gamma)*max) and partition fractions
+ * (p1, p2, p3) = part[3h .. 3h+2] (the learned sigma(s1), (1-p1)sigma(s2),
+ * (1-p1)(1-sigma(s2)); they arrive as fractions so that no transcendental
+ * function sits on the bit-exact path):
+ *     range   = hi - lo
+ *     t1 = p1/2,  t2 = t1 + (p1+p2)/2,  t3 = t2 + (p2+p3)/2      (grid t_i)
+ *     w1 = (t1+t2)/2,  w2 = (t2+t3)/2                            (grid w_i)
+ *     T_i = lo + range*t_i, rounded once to fp32
+ *     idx[h][k] = [W >= T_1] + [W >= T_2] + [W >= T_3]           (Q_LDP, u(0)=1)
+ *     LUT[h] = fp16( lo, lo + range*w1, lo + range*w2, hi )
+ * All of the above is evaluated in IEEE double in the written order without
+ * fused multiply-add, then rounded once (to nearest even).
+ *
+ * W: row-major N x K in `w_dtype`.  clip_lo, clip_hi: fp32 [N], lo < hi.
+ * part: fp32 [N][3], each > 0.  packed_out: rcp_packed_bytes(N, K) bytes.
+ * codebook_out: fp16 [N][4].  Values are not range-checked on the device.
+ */
+int rcp_pack_weights(const void* W, rcp_dtype w_dtype, int N, int K,
+                     const float* clip_lo, const float* clip_hi, const float* part,
+                     void* packed_out, void* codebook_out, void* stream);
+
+/*
+ * Online activation preparation.
+ *     y      = R x                      (fp32 arithmetic; R from `rot`)
+ *     a      = max_k |y_k|
+ *     S      = fp16( clip_ratio * a / 7 ),  S = 1 when a == 0
+ *     q_k    = clamp( round_half_even( y_k / S ), -8, 7 )
+ * The Hadamard factor is the Sylvester matrix in natural order scaled by
+ * 1/sqrt(n) (Appendix definition), with no random sign vector.
+ *
+ * x: row-major M x K in `x_dtype`.  rot: host pointer, NULL = RCP_ROT_NONE.
+ * clip_ratio in (0, 1] (the paper's table uses 0.9).  xq_out: M*K/2 bytes.
+ * scale_out: fp16 [M].  workspace: at least rcp_act_workspace_bytes(M, K, rot)
+ * bytes of device scratch, may be NULL when that is 0.
+ */
+int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K,
+                         const rcp_rotation* rot, float clip_ratio,
+                         void* xq_out, void* scale_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Non-uniform W2A4 GEMV (M = 1) / skinny GEMM (M <= RCP_MAX_M), Section 4.4.
+ *     P[m][h][l] = sum_{k : idx[h][k] = l} q[m][k]                (int32, exact)
+ *     O[m][h]    = S[m] * sum_l LUT[h][l] * P[m][h][l]            (fp32)
+ * which equals the paper's sum_k LUT[h][W_q[h][k]] * (S * X_q[k]).
+ *
+ * packed, codebook: as written by rcp_pack_weights.  xq, scale: as written by
+ * rcp_rotate_quant_act.  out: M x N of `out_dtype` (RCP_F16 or RCP_F32).
+ * partial_sums_or_null: when non-NULL receives int32 [M][N][4].
+ */
+int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
+                  const void* xq, const void* scale, int M,
+                  void* out, rcp_dtype out_dtype,
+                  int32_t* partial_sums_or_null, void* stream);
+
+/* Verification helper: expand the packed indices to one byte per weight,
+ * idx_out[h*K + k] in 0..3 (device, N*K bytes). */
+int rcp_unpack_indices(const void* packed, int N, int K, uint8_t* idx_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RCP_H */

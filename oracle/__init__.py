@@ -1,0 +1,167 @@
+"""ctypes front end of the plain CPU oracle (oracle/rcp_oracle.c).
+
+TEST INFRASTRUCTURE, NOT PRODUCT CODE: only tests/, __graft_entry__.smoke() and
+bench.py's cpu_baseline leg may import this package.  It never imports the HIP
+package and takes numpy (host) arrays only.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+ROT_NONE, ROT_WHT, ROT_KRON = 0, 1, 2
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = ctypes.CDLL(path)
+        L.rcp_ref_f64_to_f16_bits.restype = ctypes.c_uint16
+        L.rcp_ref_f64_to_f16_bits.argtypes = [ctypes.c_double]
+        L.rcp_ref_f16_bits_to_f64.restype = ctypes.c_double
+        L.rcp_ref_f16_bits_to_f64.argtypes = [ctypes.c_uint16]
+        L.rcp_ref_ldp_grid.restype = None
+        L.rcp_ref_ldp_grid.argtypes = [ctypes.c_float] * 5 + [ctypes.c_void_p, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def max_threads() -> int:
+    return int(lib().rcp_ref_max_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().rcp_ref_set_threads(ctypes.c_int(n))
+
+
+def f64_to_f16_bits(v: float) -> int:
+    return int(lib().rcp_ref_f64_to_f16_bits(float(v)))
+
+
+def f16_bits_to_f64(bits: int) -> float:
+    return float(lib().rcp_ref_f16_bits_to_f64(int(bits)))
+
+
+def hadamard_matrix(n: int) -> np.ndarray:
+    out = np.empty((n, n), dtype=np.int8)
+    _check(lib().rcp_ref_hadamard_matrix(ctypes.c_int(n), _p(out)), "hadamard_matrix")
+    return out
+
+
+def rotate(x, kind=ROT_NONE, n_wht=0, m=1, Q=None) -> np.ndarray:
+    """y = R x in fp64 by the dense definition. x: (M, K) or (K,)."""
+    x2 = _c(np.atleast_2d(x), np.float64)
+    M, K = x2.shape
+    y = np.empty_like(x2)
+    Qc = _c(Q, np.float64) if Q is not None else None
+    _check(lib().rcp_ref_rotate(_p(x2), M, K, int(kind), int(n_wht), int(m),
+                                _p(Qc) if Qc is not None else None, _p(y)), "rotate")
+    return y.reshape(np.shape(x))
+
+
+def fwht_f32(v) -> np.ndarray:
+    """Binary32 ascending-stride butterfly + scaling by (float)(1/sqrt n)."""
+    out = _c(v, np.float32).copy()
+    flat = out.reshape(-1, out.shape[-1])
+    for row in flat:
+        _check(lib().rcp_ref_fwht_f32(_p(row), int(row.shape[0])), "fwht_f32")
+    return out
+
+
+def ldp_grid(clip_lo, clip_hi, p1, p2, p3):
+    """-> (thresholds float32[3], level bit patterns uint16[4]) for one unit."""
+    T = np.empty(3, dtype=np.float32)
+    Lv = np.empty(4, dtype=np.uint16)
+    lib().rcp_ref_ldp_grid(float(np.float32(clip_lo)), float(np.float32(clip_hi)),
+                           float(np.float32(p1)), float(np.float32(p2)), float(np.float32(p3)),
+                           _p(T), _p(Lv))
+    return T, Lv
+
+
+def pack_weights(W, clip_lo, clip_hi, part, want_idx=False):
+    """-> packed uint8[N*K/4], codebook uint16[N,4] (fp16 bits) [, idx uint8[N,K]]."""
+    Wc = _c(W, np.float32)
+    N, K = Wc.shape
+    lo, hi, pt = _c(clip_lo, np.float32), _c(clip_hi, np.float32), _c(part, np.float32)
+    assert lo.shape == (N,) and hi.shape == (N,) and pt.shape == (N, 3)
+    packed = np.empty(N * K // 4, dtype=np.uint8)
+    cb = np.empty((N, 4), dtype=np.uint16)
+    idx = np.empty((N, K), dtype=np.uint8) if want_idx else None
+    _check(lib().rcp_ref_pack_weights(_p(Wc), N, K, _p(lo), _p(hi), _p(pt), _p(packed), _p(cb),
+                                      _p(idx) if want_idx else None), "pack_weights")
+    return (packed, cb, idx) if want_idx else (packed, cb)
+
+
+def unpack_indices(packed, N, K) -> np.ndarray:
+    pk = _c(packed, np.uint8)
+    assert pk.size == N * K // 4
+    idx = np.empty((N, K), dtype=np.uint8)
+    _check(lib().rcp_ref_unpack_indices(_p(pk), N, K, _p(idx)), "unpack_indices")
+    return idx
+
+
+def pack_indices(idx) -> np.ndarray:
+    ic = _c(idx, np.uint8)
+    N, K = ic.shape
+    packed = np.empty(N * K // 4, dtype=np.uint8)
+    _check(lib().rcp_ref_pack_indices(_p(ic), N, K, _p(packed)), "pack_indices")
+    return packed
+
+
+def quantize_act(y, clip_ratio=1.0):
+    """y: (M, K) float32 -> (xq uint8[M, K/2], scale fp16 bits uint16[M], q int8[M, K])."""
+    yc = _c(np.atleast_2d(y), np.float32)
+    M, K = yc.shape
+    xq = np.empty((M, K // 2), dtype=np.uint8)
+    sc = np.empty(M, dtype=np.uint16)
+    q = np.empty((M, K), dtype=np.int8)
+    _check(lib().rcp_ref_quantize_act(_p(yc), M, K, ctypes.c_float(clip_ratio), _p(xq), _p(sc),
+                                      _p(q)), "quantize_act")
+    return xq, sc, q
+
+
+def unpack_act(xq, M, K) -> np.ndarray:
+    xc = _c(xq, np.uint8)
+    assert xc.size == M * K // 2
+    q = np.empty((M, K), dtype=np.int8)
+    _check(lib().rcp_ref_unpack_act(_p(xc), M, K, _p(q)), "unpack_act")
+    return q
+
+
+def w2a4_gemv(packed, codebook, N, K, xq, scale_bits, M=1):
+    """-> (O float64[M, N], P int32[M, N, 4])."""
+    pk, cb = _c(packed, np.uint8), _c(codebook, np.uint16)
+    xc, sc = _c(xq, np.uint8), _c(scale_bits, np.uint16)
+    assert pk.size == N * K // 4 and cb.size == N * 4 and xc.size == M * K // 2 and sc.size == M
+    out = np.empty((M, N), dtype=np.float64)
+    P = np.empty((M, N, 4), dtype=np.int32)
+    _check(lib().rcp_ref_w2a4_gemv(_p(pk), _p(cb), N, K, _p(xc), _p(sc), M, _p(out), _p(P)),
+           "w2a4_gemv")
+    return out, P
+
+
+def dequant_dot(packed, codebook, N, K, xq, scale_bits, M=1) -> np.ndarray:
+    pk, cb = _c(packed, np.uint8), _c(codebook, np.uint16)
+    xc, sc = _c(xq, np.uint8), _c(scale_bits, np.uint16)
+    out = np.empty((M, N), dtype=np.float64)
+    _check(lib().rcp_ref_dequant_dot(_p(pk), _p(cb), N, K, _p(xc), _p(sc), M, _p(out)),
+           "dequant_dot")
+    return out

@@ -1,0 +1,103 @@
+"""Seeded synthetic inputs for the W2A4 GEMV path (numpy only).
+
+This module is the one thing the CPU oracle's tests and the HIP path's tests
+share.  It draws random tensors with the shapes and value distributions of the
+workloads and holds none of the method's arithmetic (no thresholds, no packing,
+no rotation, no quantisation).  The recipe:
+
+  weights      W ~ N(0, 0.02^2) in fp32, rounded to fp16, N x K (LLaMA-shaped)
+  clip range   per output row: the row's 1 % and 99 % quantiles (a stand-in for
+               the learned sigma(beta)*min / sigma(gamma)*max)
+  partitions   per output row: softmax of three N(0,1) logits -> (p1, p2, p3)
+               (a stand-in for the learned partition fractions)
+  activations  fp16 N(0,1); 1 % of the entries, chosen uniformly, multiplied by 20
+  Q            m x m orthogonal: QR of a Gaussian matrix, signs fixed so that the
+               diagonal of the triangular factor is positive, rounded to fp32
+
+Every tensor has its own random stream derived from (seed, tensor name).
+"""
+import zlib
+
+import numpy as np
+
+# Layer shapes as (name, N out, K in, rotation) ; rotation is None, ("wht", n) or
+# ("kron", n_wht, m).  Only inputs whose rotation cannot be fused into the
+# previous weights offline are rotated online (the FFN down-projection input).
+CONFIGS = {
+    "tiny": [("tiny", 256, 512, ("wht", 512))],
+    "llama32_1b": [
+        ("qo", 2048, 2048, None),
+        ("gate_up", 8192, 2048, None),
+        ("down", 2048, 8192, ("wht", 8192)),
+    ],
+    "llama2_7b": [
+        ("qkvo", 4096, 4096, None),
+        ("gate_up", 11008, 4096, None),
+        ("down", 4096, 11008, ("kron", 64, 172)),
+    ],
+    "llama3_8b": [
+        ("qo", 4096, 4096, None),
+        ("kv", 1024, 4096, None),
+        ("gate_up", 14336, 4096, None),
+        ("down", 4096, 14336, ("kron", 512, 28)),
+    ],
+}
+
+
+def _rng(seed: int, name: str) -> np.random.Generator:
+    return np.random.default_rng([int(seed), zlib.crc32(name.encode())])
+
+
+def weights(seed: int, name: str, N: int, K: int) -> np.ndarray:
+    """fp16 N x K, N(0, 0.02^2)."""
+    w = _rng(seed, "W:" + name).standard_normal((N, K), dtype=np.float32) * np.float32(0.02)
+    return w.astype(np.float16)
+
+
+def clip_range(W: np.ndarray):
+    """Row-wise 1 % / 99 % quantiles as float32 (lo, hi)."""
+    Wf = W.astype(np.float32)
+    lo = np.quantile(Wf, 0.01, axis=1).astype(np.float32)
+    hi = np.quantile(Wf, 0.99, axis=1).astype(np.float32)
+    return lo, hi
+
+
+def partitions(seed: int, name: str, N: int) -> np.ndarray:
+    """float32 [N, 3], rows on the open 2-simplex."""
+    z = _rng(seed, "part:" + name).standard_normal((N, 3))
+    e = np.exp(z - z.max(axis=1, keepdims=True))
+    return (e / e.sum(axis=1, keepdims=True)).astype(np.float32)
+
+
+def activation(seed: int, name: str, M: int, K: int) -> np.ndarray:
+    """fp16 M x K, N(0,1) with 1 % of entries scaled by 20."""
+    g = _rng(seed, "x:" + name)
+    x = g.standard_normal((M, K), dtype=np.float32)
+    outlier = g.random((M, K)) < 0.01
+    x = np.where(outlier, x * np.float32(20.0), x)
+    return x.astype(np.float16)
+
+
+def orthogonal(seed: int, m: int) -> np.ndarray:
+    """float32 m x m orthogonal matrix."""
+    a = _rng(seed, f"Q:{m}").standard_normal((m, m))
+    q, r = np.linalg.qr(a)
+    q = q * np.sign(np.diag(r))[None, :]
+    return np.ascontiguousarray(q.astype(np.float32))
+
+
+def random_indices(seed: int, name: str, N: int, K: int) -> np.ndarray:
+    """uint8 N x K uniform in 0..3 (for tests that start from indices)."""
+    return _rng(seed, "idx:" + name).integers(0, 4, size=(N, K), dtype=np.uint8)
+
+
+def random_int4(seed: int, name: str, M: int, K: int) -> np.ndarray:
+    """int8 M x K uniform in -8..7."""
+    return _rng(seed, "q:" + name).integers(-8, 8, size=(M, K), dtype=np.int8)
+
+
+def linear_layer(seed: int, name: str, N: int, K: int):
+    """All offline inputs of one linear layer: (W fp16, lo, hi, part)."""
+    W = weights(seed, name, N, K)
+    lo, hi = clip_range(W)
+    return W, lo, hi, partitions(seed, name, N)
