@@ -1,0 +1,281 @@
+#!/usr/bin/env python3
+"""Benchmark of the W2A4 GEMV path on one MI355X.
+
+Workload ("llama2_7b_decode_bs1"): one decode token through the linear layers of a
+LLaMA-2-7B-shaped model, 32 distinct decoder layers, batch 1.  Per layer the step runs
+
+    quantise(x_attn)            -> GEMV q|k|v  (12288 x 4096: three 4096 x 4096 stacked)
+    quantise(x_o)               -> GEMV o      ( 4096 x 4096)
+    quantise(x_mlp)             -> GEMV gate|up (22016 x 4096: two 11008 x 4096 stacked)
+    rotate H_64 (x) Q_172 + quantise(x_down) -> GEMV down (4096 x 11008)
+
+i.e. the seven linears of the layer in four GEMV launches (projections that read the same
+input share one launch; with one LUT per output channel stacking rows changes nothing).
+The 32 layers hold different weights (1.6 GB packed), so every weight byte comes from HBM:
+the working set is far larger than the 256 MB memory-side cache.  Weight packing is the
+offline export step and is done once, outside the timed region.
+
+One JSON line is printed: value = algorithmic bytes of the step / step time (GB/s).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+HIDDEN, INTER = 4096, 11008
+KRON = (64, 172)
+
+
+def gemv_bytes(N, K, M=1):
+    """Algorithmic bytes of one GEMV: packed indices + LUT + x_q + S + fp16 output."""
+    return N * K // 4 + 8 * N + M * K // 2 + 2 * M + 2 * M * N
+
+
+def layer_launches():
+    """(name, N, K, rotated) of the four GEMV launches of one decoder layer."""
+    return [("qkv", 3 * HIDDEN, HIDDEN, False), ("o", HIDDEN, HIDDEN, False),
+            ("gate_up", 2 * INTER, HIDDEN, False), ("down", HIDDEN, INTER, True)]
+
+
+def make_layer(torch, rcp, dev, seed, layer):
+    """Synthetic weights of one layer (same recipe as rcp_synth, drawn on the GPU), packed."""
+    out = []
+    for i, (name, N, K, _) in enumerate(layer_launches()):
+        g = torch.Generator(device=dev)
+        g.manual_seed(seed * 100003 + layer * 16 + i)
+        W = (torch.randn((N, K), generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
+        Wf = W.float()
+        k_lo = max(1, int(round(0.01 * K)))
+        lo = torch.kthvalue(Wf, k_lo, dim=1).values.contiguous()
+        hi = torch.kthvalue(Wf, K - k_lo + 1, dim=1).values.contiguous()
+        part = torch.softmax(torch.randn((N, 3), generator=g, device=dev, dtype=torch.float32), dim=1).contiguous()
+        packed, cb = rcp.pack_weights(W, lo, hi, part)
+        out.append((packed, cb))
+        del W, Wf
+    return out
+
+
+def make_activation(torch, dev, seed, K):
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    x = torch.randn((1, K), generator=g, device=dev, dtype=torch.float32)
+    outlier = torch.rand((1, K), generator=g, device=dev) < 0.01
+    return torch.where(outlier, x * 20.0, x).to(torch.float16).contiguous()
+
+
+def timed(torch, fn, reps):
+    """Seconds per call of fn(), events on the current stream, synchronised on both sides."""
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
+def cpu_baseline():
+    """The oracle as it stands, on the host cores: one GEMV of each LLaMA-2-7B shape plus the
+    activation preparation, scaled to one decoder layer (4 x qkvo + 2 x gate/up + 1 x down)."""
+    import numpy as np
+
+    import oracle
+    import rcp_synth
+    cores = oracle.max_threads()
+    t_layer, b_layer = 0.0, 0
+    for (name, N, K, rot), count in zip(rcp_synth.CONFIGS["llama2_7b"], (4, 2, 1)):
+        W, lo, hi, part = rcp_synth.linear_layer(0, "bench/" + name, N, K)
+        packed, cb = oracle.pack_weights(W.astype(np.float32), lo, hi, part)
+        x = rcp_synth.activation(0, "bench/" + name, 1, K)
+        t0 = time.perf_counter()
+        if rot is None:
+            y = x.astype(np.float64)
+        else:
+            Q = rcp_synth.orthogonal(0, rot[2]).astype(np.float64)
+            y = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=rot[1], m=rot[2], Q=Q)
+        xq, sc, _ = oracle.quantize_act(y.astype(np.float32), 1.0)
+        t_act = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.w2a4_gemv(packed, cb, N, K, xq, sc, 1)
+        t_gemv = time.perf_counter() - t0
+        t_layer += count * t_gemv + t_act
+        b_layer += count * gemv_bytes(N, K)
+    return {"value": round(b_layer / t_layer / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": "one GEMV of each llama2_7b shape (4096x4096, 11008x4096, 4096x11008) + activation "
+                      "preparation, scaled to one decoder layer (4+2+1 linears); oracle C code, fp64, OpenMP",
+            "ms_per_layer": round(t_layer * 1e3, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--layers", type=int, default=32)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly from python instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2502_15779_amd as rcp
+    import rcp_synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    rcp.lib()  # raises if librcp.so is missing: there is no fallback
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    L = args.layers
+
+    t_setup = time.perf_counter()
+    layers = [make_layer(torch, rcp, dev, args.seed, l) for l in range(L)]
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+
+    launches = layer_launches()
+    Q = torch.from_numpy(rcp_synth.orthogonal(args.seed, KRON[1])).to(dev)
+    rot_down = rcp.Rotation.kron(KRON[0], Q)
+    xs = [make_activation(torch, dev, args.seed * 7 + i, K) for i, (_, _, K, _) in enumerate(launches)]
+    xqs = [torch.empty((1, K // 2), dtype=torch.uint8, device=dev) for (_, _, K, _) in launches]
+    scs = [torch.empty((1,), dtype=torch.float16, device=dev) for _ in launches]
+    outs = [torch.empty((1, N), dtype=torch.float16, device=dev) for (_, N, _, _) in launches]
+    ws = torch.empty(rcp.act_workspace_bytes(1, INTER, rot_down), dtype=torch.uint8, device=dev)
+
+    def act(i):
+        rot = rot_down if launches[i][3] else None
+        rcp.rotate_quant_act(xs[i], rot, 1.0, xq_out=xqs[i], scale_out=scs[i], workspace=ws if rot else None)
+
+    def gemv(l, i):
+        _, N, K, _ = launches[i]
+        packed, cb = layers[l][i]
+        rcp.w2a4_gemv(packed, cb, N, K, xqs[i], scs[i], 1, out=outs[i])
+
+    def step_eager():
+        for l in range(L):
+            for i in range(4):
+                act(i)
+                gemv(l, i)
+
+    def gemv_only_eager():
+        for l in range(L):
+            for i in range(4):
+                gemv(l, i)
+
+    def act_only_eager():
+        for l in range(L):
+            for i in range(4):
+                act(i)
+
+    def capture(fn):
+        if args.no_graph:
+            return fn
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g.replay
+
+    step_eager()  # warm every code path before capture
+    torch.cuda.synchronize()
+    step = capture(step_eager)
+    gemv_only = capture(gemv_only_eager)
+    act_only = capture(act_only_eager)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # ---- the timed region: exactly args.steps steps ------------------------------------------
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    sec_per_step = e0.elapsed_time(e1) * 1e-3 / args.steps
+    # ------------------------------------------------------------------------------------------
+
+    step_bytes = L * sum(gemv_bytes(N, K) for (_, N, K, _) in launches)
+    value = step_bytes / sec_per_step / 1e9
+
+    # dominant kernel: the GEMV.  Average launch duration over the same 32-layer sweep,
+    # GEMV launches only, events on the launch stream.
+    reps = max(3, args.steps // 5)
+    sec_gemv_sweep = timed(torch, gemv_only, reps)
+    sec_act_sweep = timed(torch, act_only, reps)
+    n_gemv = 4 * L
+    gemv_avg_s = sec_gemv_sweep / n_gemv
+    achieved = (step_bytes / n_gemv) / gemv_avg_s / 1e9
+
+    # per-shape GEMV latency on the paper's own layer sizes, cold (32 different weight buffers):
+    # the stacked buffers start with the q (resp. gate) rows, so a prefix is the single matrix
+    per_shape = {}
+    for label, i, N in (("4096x4096", 1, HIDDEN), ("11008x4096", 2, INTER), ("4096x11008", 3, HIDDEN),
+                        ("12288x4096_qkv", 0, 3 * HIDDEN), ("22016x4096_gate_up", 2, 2 * INTER)):
+        K = launches[i][2]
+
+        def sweep(i=i, N=N, K=K):
+            for l in range(L):
+                packed, cb = layers[l][i]
+                rcp.w2a4_gemv(packed, cb, N, K, xqs[i], scs[i], 1, out=outs[i])
+        fn = capture(sweep)
+        fn()
+        s = timed(torch, fn, reps) / L
+        b = gemv_bytes(N, K)
+        per_shape[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1),
+                            "pct_hbm_peak": round(100.0 * b / s / 1e9 / HBM_PEAK_GBPS, 2)}
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    line = {
+        "metric": "w2a4_gemv_effective_hbm_bandwidth_llama2_7b_bs1",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int4 x 2-bit LUT index, int32 accumulate, fp32 epilogue",
+        "data": "synthetic",
+        "config": {"workload": "llama2_7b_decode_bs1", "layers": L, "linears_per_layer": 7,
+                   "gemv_launches_per_layer": 4, "batch": 1, "graph": not args.no_graph,
+                   "down_rotation": "H_64 (x) Q_172"},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "us_per_gemv_launch": round(gemv_avg_s * 1e6, 3),
+        "us_per_linear": round(sec_gemv_sweep / (7 * L) * 1e6, 3),
+        "us_act_prep_per_layer": round(sec_act_sweep / L * 1e6, 3),
+        "gemv_only_GBps": round(step_bytes / sec_gemv_sweep / 1e9, 1),
+        "per_shape": per_shape,
+        "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+        "setup_s": round(t_setup, 1),
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,198 @@
+"""Python binding of librcp.so, the MI355X W2A4 GEMV path of RCP (arXiv 2502.15779).
+
+Argument marshalling only: every function takes torch tensors that already live on the
+GPU, hands their device pointers and the current HIP stream to the C ABI declared in
+include/rcp.h, and returns torch tensors.  PyTorch supplies device memory and streams;
+all arithmetic runs in the library's HIP kernels.  There is no CPU fallback: if the
+shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librcp.so")
+
+F16, F32, BF16 = 0, 1, 2
+ROT_NONE, ROT_WHT, ROT_KRON = 0, 1, 2
+MAX_M = 16
+
+_DTYPES = {torch.float16: F16, torch.float32: F32, torch.bfloat16: BF16}
+
+
+class RcpError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"librcp error {code}: {message}")
+        self.code = code
+
+
+class _Rotation(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("n_wht", ctypes.c_int), ("m", ctypes.c_int), ("Q", ctypes.c_void_p)]
+
+
+class Rotation:
+    """Host-side rotation descriptor; keeps the device tensor Q alive."""
+
+    def __init__(self, kind=ROT_NONE, n_wht=0, m=1, Q=None):
+        self.kind, self.n_wht, self.m, self.Q = int(kind), int(n_wht), int(m), Q
+        if Q is not None:
+            assert Q.is_cuda and Q.dtype == torch.float32 and Q.is_contiguous() and Q.shape == (m, m)
+        self._c = _Rotation(self.kind, self.n_wht, self.m, Q.data_ptr() if Q is not None else None)
+
+    @staticmethod
+    def none():
+        return Rotation(ROT_NONE)
+
+    @staticmethod
+    def wht(n):
+        return Rotation(ROT_WHT, n_wht=n)
+
+    @staticmethod
+    def kron(n_wht, Q):
+        return Rotation(ROT_KRON, n_wht=n_wht, m=Q.shape[0], Q=Q)
+
+
+_lib = None
+
+
+def build():
+    """Compile librcp.so from csrc/ (hipcc, gfx950)."""
+    global _lib
+    from . import _build
+    _lib = None
+    return _build.build()
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RcpError(-100, f"{LIB_PATH} is missing: run __graft_entry__.build() first (no CPU fallback exists)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci, cz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.rcp_version.restype = ci
+        L.rcp_last_error.restype = ctypes.c_char_p
+        L.rcp_set_option.restype = ci
+        L.rcp_set_option.argtypes = [ctypes.c_char_p, ci]
+        L.rcp_packed_bytes.restype = cz
+        L.rcp_packed_bytes.argtypes = [ci, ci]
+        L.rcp_act_workspace_bytes.restype = cz
+        L.rcp_act_workspace_bytes.argtypes = [ci, ci, ctypes.POINTER(_Rotation)]
+        L.rcp_pack_weights.restype = ci
+        L.rcp_pack_weights.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.rcp_unpack_indices.restype = ci
+        L.rcp_unpack_indices.argtypes = [vp, ci, ci, vp, vp]
+        L.rcp_rotate_quant_act.restype = ci
+        L.rcp_rotate_quant_act.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, vp, vp, cz, vp]
+        L.rcp_w2a4_gemv.restype = ci
+        L.rcp_w2a4_gemv.argtypes = [vp, vp, ci, ci, vp, vp, ci, vp, ci, vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise RcpError(rc, lib().rcp_last_error().decode())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise ValueError(f"{what} must be a contiguous CUDA tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def version() -> int:
+    return int(lib().rcp_version())
+
+
+def set_option(name: str, value: int) -> None:
+    _check(lib().rcp_set_option(name.encode(), int(value)))
+
+
+def packed_bytes(N: int, K: int) -> int:
+    return int(lib().rcp_packed_bytes(N, K))
+
+
+def act_workspace_bytes(M: int, K: int, rot: Rotation = None) -> int:
+    return int(lib().rcp_act_workspace_bytes(M, K, ctypes.byref(rot._c) if rot is not None else None))
+
+
+def pack_weights(W, clip_lo, clip_hi, part, packed_out=None, codebook_out=None):
+    """W [N, K] (fp16 / bf16 / fp32), clip_lo / clip_hi [N] fp32, part [N, 3] fp32
+    -> (packed uint8 [N*K/4], codebook fp16 [N, 4])."""
+    N, K = W.shape
+    nbytes = packed_bytes(N, K)
+    if packed_out is None:
+        packed_out = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=W.device)
+    if codebook_out is None:
+        codebook_out = torch.empty((N, 4), dtype=torch.float16, device=W.device)
+    for t, name in ((clip_lo, "clip_lo"), (clip_hi, "clip_hi"), (part, "part")):
+        if t.dtype != torch.float32:
+            raise ValueError(f"{name} must be float32")
+    if clip_lo.numel() != N or clip_hi.numel() != N or part.numel() != 3 * N:
+        raise ValueError("clip_lo / clip_hi / part do not match N")
+    if W.dtype not in _DTYPES:
+        raise ValueError("W must be float16, bfloat16 or float32")
+    _check(lib().rcp_pack_weights(_dev(W, "W"), _DTYPES[W.dtype], N, K, _dev(clip_lo, "clip_lo"),
+                                  _dev(clip_hi, "clip_hi"), _dev(part, "part"), _dev(packed_out, "packed_out"),
+                                  _dev(codebook_out, "codebook_out"), _stream()))
+    return packed_out, codebook_out
+
+
+def unpack_indices(packed, N, K, idx_out=None):
+    if idx_out is None:
+        idx_out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    if packed.numel() * packed.element_size() < N * K // 4:
+        raise ValueError("packed buffer too small")
+    _check(lib().rcp_unpack_indices(_dev(packed, "packed"), N, K, _dev(idx_out, "idx_out"), _stream()))
+    return idx_out
+
+
+def rotate_quant_act(x, rot: Rotation = None, clip_ratio: float = 1.0, xq_out=None, scale_out=None, workspace=None):
+    """x [M, K] (fp16 / bf16 / fp32) -> (xq uint8 [M, K/2], scale fp16 [M])."""
+    if x.dim() == 1:
+        x = x.unsqueeze(0)
+    M, K = x.shape
+    if x.dtype not in _DTYPES:
+        raise ValueError("x must be float16, bfloat16 or float32")
+    if xq_out is None:
+        xq_out = torch.empty((M, max(K // 2, 1)), dtype=torch.uint8, device=x.device)
+    if scale_out is None:
+        scale_out = torch.empty((M,), dtype=torch.float16, device=x.device)
+    need = act_workspace_bytes(M, K, rot)
+    if need and workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    ws_ptr = _dev(workspace, "workspace") if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().rcp_rotate_quant_act(_dev(x, "x"), _DTYPES[x.dtype], M, K,
+                                      ctypes.byref(rot._c) if rot is not None else None,
+                                      ctypes.c_float(clip_ratio), _dev(xq_out, "xq_out"), _dev(scale_out, "scale_out"),
+                                      ws_ptr, ws_bytes, _stream()))
+    return xq_out, scale_out
+
+
+def w2a4_gemv(packed, codebook, N, K, xq, scale, M=1, out=None, out_dtype=torch.float16, partial_sums=None,
+              want_partial_sums=False):
+    """-> out [M, N] (and the int32 [M, N, 4] per-level partial sums when asked for)."""
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=packed.device)
+    if out.dtype not in (torch.float16, torch.float32):
+        raise ValueError("out must be float16 or float32")
+    if want_partial_sums and partial_sums is None:
+        partial_sums = torch.empty((M, N, 4), dtype=torch.int32, device=packed.device)
+    if packed.numel() * packed.element_size() < N * K // 4 or codebook.numel() < 4 * N:
+        raise ValueError("packed / codebook buffers do not match N, K")
+    if xq.numel() * xq.element_size() < M * K // 2 or scale.numel() < M or out.numel() < M * N:
+        raise ValueError("xq / scale / out buffers do not match M, N, K")
+    if partial_sums is not None and (partial_sums.dtype != torch.int32 or partial_sums.numel() < 4 * M * N):
+        raise ValueError("partial_sums must be int32 [M, N, 4]")
+    _check(lib().rcp_w2a4_gemv(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, _dev(xq, "xq"),
+                               _dev(scale, "scale"), M, _dev(out, "out"), _DTYPES[out.dtype],
+                               _dev(partial_sums, "partial_sums") if partial_sums is not None else None, _stream()))
+    return (out, partial_sums) if partial_sums is not None else out

@@ -1,0 +1,195 @@
+// C ABI of librcp.so: argument validation, error strings, dispatch to the launchers.
+// Every rule checked here is stated in include/rcp.h.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "rcp_internal.hpp"
+
+namespace rcp {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_launch(const char* what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(RCP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return RCP_OK;
+}
+
+Options& options()
+{
+    static Options o = {0, 0, 0};
+    return o;
+}
+
+int num_compute_units()
+{
+    static thread_local int cached_dev = -1, cached_cus = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (dev != cached_dev) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        cached_dev = dev;
+        cached_cus = cus;
+    }
+    return cached_cus;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static bool pow2(int n) { return n > 0 && (n & (n - 1)) == 0; }
+
+static int check_shape(const char* fn, int N, int K)
+{
+    if (N <= 0 || N % 4 != 0) return fail(RCP_ERR_SHAPE, "%s: N=%d must be a positive multiple of 4", fn, N);
+    if (K <= 0 || K % 32 != 0) return fail(RCP_ERR_SHAPE, "%s: K=%d must be a positive multiple of 32", fn, K);
+    if (K > RCP_MAX_K) return fail(RCP_ERR_SHAPE, "%s: K=%d exceeds RCP_MAX_K=%d", fn, K, RCP_MAX_K);
+    if (static_cast<long long>(N) * K / 4 > 0x7fffffffLL * 4)
+        return fail(RCP_ERR_SHAPE, "%s: N*K too large", fn);
+    return RCP_OK;
+}
+
+static int check_rotation(const char* fn, int K, const rcp_rotation* rot)
+{
+    if (rot == nullptr || rot->kind == RCP_ROT_NONE) return RCP_OK;
+    if (rot->kind == RCP_ROT_WHT) {
+        if (!pow2(rot->n_wht) || rot->n_wht != K)
+            return fail(RCP_ERR_SHAPE, "%s: WHT needs n_wht == K == power of two (n_wht=%d, K=%d)", fn, rot->n_wht, K);
+        if (K > RCP_MAX_WHT) return fail(RCP_ERR_UNSUPPORTED, "%s: WHT order %d exceeds RCP_MAX_WHT=%d", fn, K, RCP_MAX_WHT);
+        return RCP_OK;
+    }
+    if (rot->kind == RCP_ROT_KRON) {
+        if (!pow2(rot->n_wht) || rot->m < 1 || static_cast<long long>(rot->n_wht) * rot->m != K)
+            return fail(RCP_ERR_SHAPE, "%s: KRON needs n_wht (power of two) * m == K (n_wht=%d, m=%d, K=%d)", fn,
+                        rot->n_wht, rot->m, K);
+        if (rot->m > RCP_MAX_KRON_M) return fail(RCP_ERR_UNSUPPORTED, "%s: m=%d exceeds RCP_MAX_KRON_M=%d", fn, rot->m, RCP_MAX_KRON_M);
+        if (rot->n_wht > 1024) return fail(RCP_ERR_UNSUPPORTED, "%s: KRON Hadamard factor %d exceeds 1024", fn, rot->n_wht);
+        if (rot->Q == nullptr) return fail(RCP_ERR_NULL, "%s: KRON rotation with Q == NULL", fn);
+        if (!aligned16(rot->Q)) return fail(RCP_ERR_ALIGN, "%s: Q is not 16-byte aligned", fn);
+        return RCP_OK;
+    }
+    return fail(RCP_ERR_UNSUPPORTED, "%s: unknown rotation kind %d", fn, rot->kind);
+}
+
+}  // namespace rcp
+
+using namespace rcp;
+
+extern "C" {
+
+int rcp_version(void) { return 100; }
+
+const char* rcp_last_error(void) { return g_err; }
+
+size_t rcp_packed_bytes(int N, int K)
+{
+    if (N <= 0 || N % 4 != 0 || K <= 0 || K % 32 != 0 || K > RCP_MAX_K) return 0;
+    return static_cast<size_t>(N) * static_cast<size_t>(K) / 4;
+}
+
+size_t rcp_act_workspace_bytes(int M, int K, const rcp_rotation* rot)
+{
+    if (M <= 0 || K <= 0) return 0;
+    return act_workspace_bytes(M, K, rot);
+}
+
+int rcp_set_option(const char* name, int value)
+{
+    if (name == nullptr) return fail(RCP_ERR_NULL, "rcp_set_option: name is NULL");
+    Options& o = options();
+    if (strcmp(name, "gemv_lpg") == 0) {
+        if (value != 0 && value != 16 && value != 32 && value != 64)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_lpg must be 0, 16, 32 or 64");
+        o.gemv_lpg = value;
+    } else if (strcmp(name, "gemv_blocks") == 0) {
+        if (value < 0 || value > (1 << 20)) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_blocks out of range");
+        o.gemv_blocks = value;
+    } else if (strcmp(name, "gemv_variant") == 0) {
+        if (value < 0 || value > 8) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_variant out of range");
+        o.gemv_variant = value;
+    } else
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: unknown option '%s'", name);
+    return RCP_OK;
+}
+
+int rcp_pack_weights(const void* W, rcp_dtype w_dtype, int N, int K, const float* clip_lo,
+                     const float* clip_hi, const float* part, void* packed_out, void* codebook_out,
+                     void* stream)
+{
+    if (!W || !clip_lo || !clip_hi || !part || !packed_out || !codebook_out)
+        return fail(RCP_ERR_NULL, "rcp_pack_weights: NULL pointer argument");
+    if (int rc = check_shape("rcp_pack_weights", N, K)) return rc;
+    if (w_dtype != RCP_F16 && w_dtype != RCP_F32 && w_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_pack_weights: unknown dtype %d", static_cast<int>(w_dtype));
+    if (!aligned16(W) || !aligned16(packed_out) || !aligned16(codebook_out) || !aligned16(clip_lo) ||
+        !aligned16(clip_hi) || !aligned16(part))
+        return fail(RCP_ERR_ALIGN, "rcp_pack_weights: device buffers must be 16-byte aligned");
+    return launch_pack(W, w_dtype, N, K, clip_lo, clip_hi, part, packed_out, codebook_out,
+                       static_cast<hipStream_t>(stream));
+}
+
+int rcp_unpack_indices(const void* packed, int N, int K, uint8_t* idx_out, void* stream)
+{
+    if (!packed || !idx_out) return fail(RCP_ERR_NULL, "rcp_unpack_indices: NULL pointer argument");
+    if (int rc = check_shape("rcp_unpack_indices", N, K)) return rc;
+    if (!aligned16(packed) || !aligned16(idx_out))
+        return fail(RCP_ERR_ALIGN, "rcp_unpack_indices: device buffers must be 16-byte aligned");
+    return launch_unpack(packed, N, K, idx_out, static_cast<hipStream_t>(stream));
+}
+
+int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K, const rcp_rotation* rot,
+                         float clip_ratio, void* xq_out, void* scale_out, void* workspace,
+                         size_t workspace_bytes, void* stream)
+{
+    if (!x || !xq_out || !scale_out) return fail(RCP_ERR_NULL, "rcp_rotate_quant_act: NULL pointer argument");
+    if (M <= 0 || M > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_rotate_quant_act: M=%d outside 1..%d", M, RCP_MAX_M);
+    if (K <= 0 || K % 32 != 0 || K > RCP_MAX_K)
+        return fail(RCP_ERR_SHAPE, "rcp_rotate_quant_act: K=%d must be a positive multiple of 32, at most %d", K, RCP_MAX_K);
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act: unknown dtype %d", static_cast<int>(x_dtype));
+    if (!(clip_ratio > 0.0f) || !(clip_ratio <= 1.0f))
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act: clip_ratio %g outside (0, 1]", static_cast<double>(clip_ratio));
+    if (int rc = check_rotation("rcp_rotate_quant_act", K, rot)) return rc;
+    if (!aligned16(x) || !aligned16(xq_out) || !aligned16(workspace))
+        return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_act: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale_out) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_act: scale_out must be 2-byte aligned");
+    size_t need = act_workspace_bytes(M, K, rot);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need))
+        return fail(RCP_ERR_WORKSPACE, "rcp_rotate_quant_act: workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : static_cast<size_t>(0));
+    return launch_act(x, x_dtype, M, K, rot, clip_ratio, xq_out, scale_out, workspace, workspace_bytes,
+                      static_cast<hipStream_t>(stream));
+}
+
+int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
+                  const void* scale, int M, void* out, rcp_dtype out_dtype,
+                  int32_t* partial_sums_or_null, void* stream)
+{
+    if (!packed || !codebook || !xq || !scale || !out)
+        return fail(RCP_ERR_NULL, "rcp_w2a4_gemv: NULL pointer argument");
+    if (int rc = check_shape("rcp_w2a4_gemv", N, K)) return rc;
+    if (M <= 0 || M > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv: M=%d outside 1..%d", M, RCP_MAX_M);
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a4_gemv: out_dtype must be RCP_F16 or RCP_F32");
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(xq) || !aligned16(out) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemv: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemv: scale must be 2-byte aligned");
+    return launch_gemv(packed, codebook, N, K, xq, scale, M, out, out_dtype, partial_sums_or_null,
+                       static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

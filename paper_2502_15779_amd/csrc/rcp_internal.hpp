@@ -1,0 +1,85 @@
+// Internal declarations shared by the translation units of librcp.so.
+// Nothing here is part of the C ABI (that is include/rcp.h).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rcp.h"
+
+namespace rcp {
+
+// ---- error plumbing (api.hip) -------------------------------------------------
+int fail(int code, const char* fmt, ...);
+int check_launch(const char* what);  // hipGetLastError() -> RCP_ERR_HIP / RCP_OK
+
+// ---- tuning knobs (api.hip), 0 = automatic --------------------------------------
+struct Options {
+    int gemv_lpg;        // lanes that share one group of four rows: 16, 32 or 64
+    int gemv_blocks;     // workgroups launched by the GEMV
+    int gemv_variant;    // kernel variant selector
+};
+Options& options();
+int num_compute_units();
+
+// ---- launchers (one per .hip file) -------------------------------------------------
+int launch_pack(const void* W, rcp_dtype dt, int N, int K, const float* lo, const float* hi,
+                const float* part, void* packed, void* codebook, hipStream_t st);
+int launch_unpack(const void* packed, int N, int K, uint8_t* idx, hipStream_t st);
+
+size_t act_workspace_bytes(int M, int K, const rcp_rotation* rot);
+int launch_act(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float clip_ratio,
+               void* xq, void* scale, void* ws, size_t ws_bytes, hipStream_t st);
+
+int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
+                const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
+
+// ---- small device helpers ------------------------------------------------------------
+__device__ __forceinline__ float half_bits_to_float(uint16_t h)
+{
+    return __half2float(__ushort_as_half(h));
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b)
+{
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// Load element i of a tensor of 16- or 32-bit floats as fp32 (the widening is exact).
+template <int DT>
+__device__ __forceinline__ float load_as_float(const void* p, size_t i)
+{
+    if constexpr (DT == RCP_F32) return static_cast<const float*>(p)[i];
+    else if constexpr (DT == RCP_F16) return half_bits_to_float(static_cast<const uint16_t*>(p)[i]);
+    else return bf16_bits_to_float(static_cast<const uint16_t*>(p)[i]);
+}
+
+// Eight consecutive elements starting at element index i (a multiple of 8).
+template <int DT>
+__device__ __forceinline__ void load8_as_float(const void* p, size_t i, float (&v)[8])
+{
+    if constexpr (DT == RCP_F32) {
+        const float4* q = reinterpret_cast<const float4*>(static_cast<const float*>(p) + i);
+        float4 a = q[0], b = q[1];
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    } else {
+        uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p) + i);
+        uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint16_t lo16 = static_cast<uint16_t>(w[e] & 0xffffu), hi16 = static_cast<uint16_t>(w[e] >> 16);
+            if constexpr (DT == RCP_F16) {
+                v[2 * e] = half_bits_to_float(lo16);
+                v[2 * e + 1] = half_bits_to_float(hi16);
+            } else {
+                v[2 * e] = bf16_bits_to_float(lo16);
+                v[2 * e + 1] = bf16_bits_to_float(hi16);
+            }
+        }
+    }
+}
+
+}  // namespace rcp

@@ -1,0 +1,103 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every function that
+include/rcp.h declares, and turns bad arguments into error codes before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "rcp.h")
+LIB = os.path.join(ROOT, "paper_2502_15779_amd", "librcp.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        import __graft_entry__
+        __graft_entry__.build()
+    return ctypes.CDLL(LIB)
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rcp_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(lib):
+    names = _declared_functions()
+    assert {"rcp_pack_weights", "rcp_rotate_quant_act", "rcp_w2a4_gemv", "rcp_unpack_indices",
+            "rcp_packed_bytes", "rcp_act_workspace_bytes", "rcp_last_error", "rcp_version",
+            "rcp_set_option"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_size_queries(lib):
+    lib.rcp_packed_bytes.restype = ctypes.c_size_t
+    assert lib.rcp_packed_bytes(4096, 4096) == 4096 * 4096 // 4
+    assert lib.rcp_packed_bytes(4096, 11008) == 11272192
+    assert lib.rcp_packed_bytes(6, 32) == 0 and lib.rcp_packed_bytes(8, 24) == 0 and lib.rcp_packed_bytes(0, 32) == 0
+
+
+class Rot(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_int), ("n_wht", ctypes.c_int), ("m", ctypes.c_int), ("Q", ctypes.c_void_p)]
+
+
+def test_argument_errors_need_no_gpu(lib):
+    lib.rcp_last_error.restype = ctypes.c_char_p
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)  # aligned, never dereferenced: every call below must fail validation first
+    odd = vp(0x1004)
+    gemv = lib.rcp_w2a4_gemv
+    gemv.argtypes = [vp, vp, ctypes.c_int, ctypes.c_int, vp, vp, ctypes.c_int, vp, ctypes.c_int, vp, vp]
+    assert gemv(None, fake, 8, 32, fake, fake, 1, fake, 0, None, None) == -1
+    assert b"NULL" in lib.rcp_last_error()
+    assert gemv(fake, fake, 6, 32, fake, fake, 1, fake, 0, None, None) == -2
+    assert gemv(fake, fake, 8, 48, fake, fake, 1, fake, 0, None, None) == -2
+    assert gemv(fake, fake, 8, 32, fake, fake, 0, fake, 0, None, None) == -2
+    assert gemv(fake, fake, 8, 32, fake, fake, 17, fake, 0, None, None) == -2
+    assert gemv(fake, fake, 8, 32, fake, fake, 1, fake, 2, None, None) == -4
+    assert gemv(odd, fake, 8, 32, fake, fake, 1, fake, 0, None, None) == -3
+    pack = lib.rcp_pack_weights
+    pack.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp, vp, vp, vp, vp]
+    assert pack(fake, 0, 8, 32, fake, fake, None, fake, fake, None) == -1
+    assert pack(fake, 7, 8, 32, fake, fake, fake, fake, fake, None) == -4
+    assert pack(fake, 0, 8, 40, fake, fake, fake, fake, fake, None) == -2
+    act = lib.rcp_rotate_quant_act
+    act.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot), ctypes.c_float, vp, vp, vp,
+                    ctypes.c_size_t, vp]
+    assert act(fake, 0, 1, 64, None, 1.5, fake, fake, None, 0, None) == -4      # clip ratio
+    assert act(fake, 0, 1, 96, ctypes.byref(Rot(1, 96, 1, None)), 1.0, fake, fake, None, 0, None) == -2
+    assert act(fake, 0, 1, 64, ctypes.byref(Rot(1, 32, 1, None)), 1.0, fake, fake, None, 0, None) == -2
+    assert act(fake, 0, 1, 96, ctypes.byref(Rot(2, 32, 4, fake)), 1.0, fake, fake, None, 0, None) == -2
+    assert act(fake, 0, 1, 96, ctypes.byref(Rot(2, 32, 3, None)), 1.0, fake, fake, None, 0, None) == -1
+    assert act(fake, 0, 1, 96, ctypes.byref(Rot(2, 32, 3, fake)), 1.0, fake, fake, None, 0, None) == -5
+    assert b"workspace" in lib.rcp_last_error()
+    assert act(fake, 0, 1, 64, ctypes.byref(Rot(9, 0, 0, None)), 1.0, fake, fake, None, 0, None) == -4
+    lib.rcp_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
+    assert lib.rcp_set_option(b"gemv_lpg", 48) == -4
+    assert lib.rcp_set_option(b"nonsense", 1) == -4
+    assert lib.rcp_set_option(b"gemv_lpg", 0) == 0
+    ws = lib.rcp_act_workspace_bytes
+    ws.restype = ctypes.c_size_t
+    ws.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot)]
+    assert ws(1, 4096, None) == 0
+    assert ws(2, 11008, ctypes.byref(Rot(2, 64, 172, fake))) == 2 * 11008 * 4
+
+
+def test_product_path_has_no_cpu_fallback():
+    """The binding must not import the oracle, and a missing library must raise."""
+    src = open(os.path.join(ROOT, "paper_2502_15779_amd", "__init__.py")).read()
+    assert "import oracle" not in src and "from oracle" not in src
+    for name in os.listdir(os.path.join(ROOT, "paper_2502_15779_amd", "csrc")):
+        assert "oracle" not in open(os.path.join(ROOT, "paper_2502_15779_amd", "csrc", name)).read().lower()
+    import paper_2502_15779_amd as rcp
+    saved, rcp._lib, rcp.LIB_PATH = rcp._lib, None, rcp.LIB_PATH + ".absent"
+    try:
+        with pytest.raises(rcp.RcpError):
+            rcp.lib()
+    finally:
+        rcp.LIB_PATH = rcp.LIB_PATH[: -len(".absent")]
+        rcp._lib = saved

@@ -1,0 +1,282 @@
+"""GPU-vs-oracle parity through the C ABI (python binding = argument marshalling only).
+
+Bars: packed bytes, LUT bit patterns, per-level int32 partial sums and (for pure Hadamard
+sizes) the quantised activations are bit-exact; floating-point outputs are within 1e-3
+(norm-wise, and per element relative to s * sum_l |LUT_l| |P_l|) of the fp64 oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_15779_amd as rcp
+import rcp_synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _t(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _f16(bits):
+    return np.asarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _auto_options():
+    yield
+    for k in ("gemv_lpg", "gemv_blocks", "gemv_variant"):
+        rcp.set_option(k, 0)
+
+
+# ------------------------------------------------------------------------------------------
+# pack / unpack
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,K,dtype", [(256, 512, "f16"), (12, 96, "f16"), (4, 32, "f32"), (36, 2080, "bf16"),
+                                       (1024, 4096, "f16"), (64, 11008, "f16")])
+def test_pack_weights_bit_exact(N, K, dtype):
+    _say(f"pack N={N} K={K} {dtype}")
+    W, lo, hi, part = rcp_synth.linear_layer(1, f"pack{N}x{K}", N, K)
+    if dtype == "f16":
+        Wd, W32 = _t(W), W.astype(np.float32)
+    elif dtype == "f32":
+        W32 = (W.astype(np.float32) * np.float32(1.0009765))  # values off the fp16 grid
+        Wd = _t(W32)
+    else:
+        Wd = _t(W.astype(np.float32)).to(torch.bfloat16)
+        W32 = Wd.to(torch.float32).cpu().numpy()
+    packed, cb = rcp.pack_weights(Wd, _t(lo), _t(hi), _t(part))
+    idx = rcp.unpack_indices(packed, N, K)
+    torch.cuda.synchronize()
+    ref_packed, ref_cb, ref_idx = oracle.pack_weights(W32, lo, hi, part, want_idx=True)
+    assert np.array_equal(cb.cpu().numpy().view(np.uint16), ref_cb)
+    assert np.array_equal(packed.cpu().numpy(), ref_packed)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+
+
+def test_pack_grid_edge_values():
+    """Weights sitting exactly on thresholds, LUT values that are fp16 ties, subnormal levels."""
+    N, K = 8, 64
+    rng = np.random.default_rng(5)
+    lo = np.array([0, -1, -3e-6, -0.3333, 0, -65000, -1e-3, -2.0], np.float32)
+    hi = np.array([1, 1, 5e-6, 0.6667, 2049.0 / 1024, 65000, 1e-3, 2.0], np.float32)
+    part = np.array([[0.5, 0.25, 0.25]] * 4 + [[0.25, 0.5, 0.25]] * 4, np.float32)
+    W = rng.uniform(-1, 1, size=(N, K)).astype(np.float32) * (hi - lo)[:, None]
+    for h in range(N):
+        T, _ = oracle.ldp_grid(lo[h], hi[h], *part[h])
+        W[h, :3] = T
+        W[h, 3:6] = np.nextafter(T, np.float32(-np.inf))
+    packed, cb = rcp.pack_weights(_t(W), _t(lo), _t(hi), _t(part))
+    torch.cuda.synchronize()
+    ref_packed, ref_cb = oracle.pack_weights(W, lo, hi, part)
+    assert np.array_equal(cb.cpu().numpy().view(np.uint16), ref_cb)
+    assert np.array_equal(packed.cpu().numpy(), ref_packed)
+
+
+# ------------------------------------------------------------------------------------------
+# GEMV
+# ------------------------------------------------------------------------------------------
+def _gemv_case(seed, N, K, M):
+    idx = rcp_synth.random_indices(seed, f"gemv{N}x{K}", N, K)
+    q = rcp_synth.random_int4(seed, f"gemv{M}x{K}", M, K)
+    rng = np.random.default_rng(seed)
+    cb = np.sort(rng.standard_normal((N, 4)) * 0.03, axis=1).astype(np.float16).view(np.uint16)
+    sc = (np.abs(rng.standard_normal(M)) * 0.2 + 0.05).astype(np.float16).view(np.uint16)
+    xq = ((q[:, 0::2].astype(np.uint8) & 0xF) | ((q[:, 1::2].astype(np.uint8) & 0xF) << 4)).astype(np.uint8)
+    return oracle.pack_indices(idx), cb, xq, sc
+
+
+def _check_gemv(packed, cb, N, K, xq, sc, M, out_dtype):
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, xq, sc, M)
+    out, P = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)), M,
+                           out_dtype=out_dtype, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P), "per-level partial sums are not bit-exact"
+    got = out.cpu().numpy().astype(np.float64)
+    cond = _f16(sc)[:, None] * (np.abs(_f16(cb))[None, :, :] * np.abs(ref_P)).sum(axis=2)
+    half = 2.0 ** -11 * np.abs(ref_O) if out_dtype == torch.float16 else 0.0
+    assert np.all(np.abs(got - ref_O) <= 1e-3 * cond + half + 1e-30)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O) + 1e-30
+    # the call without the verification output must give the same numbers
+    out2 = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)), M,
+                         out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("lpg", [0, 16, 32, 64])
+@pytest.mark.parametrize("N,K", [(256, 512), (4, 32), (12, 96), (20, 2080), (1028, 4096), (72, 11008), (40, 14336),
+                                 (2048, 2048)])
+def test_gemv_partial_sums_bit_exact_and_output_close(N, K, lpg):
+    _say(f"gemv N={N} K={K} lpg={lpg}")
+    rcp.set_option("gemv_lpg", lpg)
+    packed, cb, xq, sc = _gemv_case(N + K, N, K, 1)
+    _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32)
+    _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float16)
+
+
+@pytest.mark.parametrize("blocks", [1, 3, 64])
+def test_gemv_grid_stride_with_few_workgroups(blocks):
+    _say(f"gemv grid-stride blocks={blocks}")
+    rcp.set_option("gemv_blocks", blocks)
+    N, K = 1028, 1024
+    packed, cb, xq, sc = _gemv_case(3, N, K, 1)
+    _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32)
+
+
+def test_gemv_extreme_activations_and_integer_codebook():
+    """q = -8 everywhere with index 3 everywhere drives the accumulators to their largest
+    magnitude; an integer codebook makes the fp32 epilogue exact."""
+    N, K = 16, 14336
+    idx = np.full((N, K), 3, np.uint8)
+    idx[1::2] = rcp_synth.random_indices(0, "ext", N // 2, K)
+    cb = np.tile(np.array([0, 1, 2, 3], np.float16).view(np.uint16), (N, 1))
+    xq = np.full((1, K // 2), 0x88, np.uint8)
+    one = np.array([1.0], np.float16).view(np.uint16)
+    packed = oracle.pack_indices(idx)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, xq, one, 1)
+    out, P = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(one.view(np.float16)), 1,
+                           out_dtype=torch.float32, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), ref_O)
+    assert ref_P[0, 0, 3] == -8 * K
+
+
+@pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 16])
+@pytest.mark.parametrize("N,K", [(256, 512), (44, 2080), (256, 4096), (32, 11008)])
+def test_small_batch_matches_oracle(N, K, M):
+    _say(f"skinny gemm N={N} K={K} M={M}")
+    packed, cb, xq, sc = _gemv_case(M * 1000 + N, N, K, M)
+    _check_gemv(packed, cb, N, K, xq, sc, M, torch.float32)
+    _check_gemv(packed, cb, N, K, xq, sc, M, torch.float16)
+
+
+# ------------------------------------------------------------------------------------------
+# activation preparation
+# ------------------------------------------------------------------------------------------
+def _check_act_against_rotated(y64, xq, sc, ratio):
+    """Tie-band criterion: with the kernel's own scale, every code is within 1/2 (+ slack for
+    the binary32 rotation) of the exactly rotated value divided by the scale."""
+    M, K = y64.shape
+    s = _f16(sc)
+    a = np.abs(y64).max(axis=1)
+    target = ratio * a / 7.0
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(s, 2.0 ** -14))) - 10)
+    assert np.all(np.abs(s - target) <= 0.5 * ulp + 1e-5 * target + 1e-12), "scale is not fp16(ratio*amax/7)"
+    q = oracle.unpack_act(xq, M, K).astype(np.float64)
+    z = np.clip(y64 / s[:, None], -8.5, 7.5)
+    slack = 2e-5 * (np.abs(z) + 1.0) * np.sqrt(np.log2(K) + 1)
+    assert np.all(np.abs(q - z) <= 0.5 + slack)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("M,K,ratio", [(1, 512, 1.0), (1, 4096, 1.0), (3, 2080, 0.9), (1, 11008, 1.0), (16, 4096, 1.0),
+                                       (2, 32768, 1.0), (1, 32, 1.0)])
+def test_quantise_without_rotation_bit_exact(M, K, ratio, dtype):
+    _say(f"quant M={M} K={K} ratio={ratio} {dtype}")
+    x16 = rcp_synth.activation(2, f"q{M}x{K}", M, K)
+    if dtype == "f16":
+        xd = _t(x16)
+    elif dtype == "bf16":
+        xd = _t(x16.astype(np.float32)).to(torch.bfloat16)
+    else:
+        xd = _t(x16.astype(np.float32) * np.float32(1.00037))
+    x32 = xd.to(torch.float32).cpu().numpy()
+    xq, sc = rcp.rotate_quant_act(xd, None, ratio)
+    torch.cuda.synchronize()
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, ratio)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+
+
+def test_quantise_degenerate_inputs():
+    K = 4096
+    x = np.zeros((3, K), np.float16)
+    x[1, 77] = -12.5
+    x[2, :] = 6e-8  # fp16 subnormal: the scale underflows and falls back to 1
+    xq, sc = rcp.rotate_quant_act(_t(x), None, 1.0)
+    torch.cuda.synchronize()
+    ref_xq, ref_sc, _ = oracle.quantize_act(x.astype(np.float32), 1.0)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+    big = np.full((1, K), 3e6, np.float32)
+    xq, sc = rcp.rotate_quant_act(_t(big), None, 1.0)
+    torch.cuda.synchronize()
+    ref_xq, ref_sc, _ = oracle.quantize_act(big, 1.0)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc) and np.array_equal(xq.cpu().numpy(), ref_xq)
+
+
+@pytest.mark.parametrize("M,n", [(1, 32), (1, 64), (2, 256), (1, 512), (1, 2048), (3, 4096), (1, 8192), (1, 16384)])
+def test_hadamard_rotation_bit_exact_against_binary32_butterfly(M, n):
+    _say(f"wht M={M} n={n}")
+    x = rcp_synth.activation(3, f"wht{M}x{n}", M, n)
+    xq, sc = rcp.rotate_quant_act(_t(x), rcp.Rotation.wht(n), 1.0)
+    torch.cuda.synchronize()
+    y32 = oracle.fwht_f32(x.astype(np.float32))
+    ref_xq, ref_sc, _ = oracle.quantize_act(y32, 1.0)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+    if n <= 8192:  # and against the dense fp64 definition, within the tie band
+        y64 = oracle.rotate(x.astype(np.float64), oracle.ROT_WHT, n_wht=n)
+        _check_act_against_rotated(np.atleast_2d(y64), xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16), 1.0)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("M,n,m,ratio", [(1, 64, 172, 1.0), (1, 512, 28, 1.0), (2, 8, 12, 0.9), (1, 2, 16, 1.0),
+                                         (3, 64, 172, 1.0)])
+def test_kronecker_rotation_within_tie_band(M, n, m, ratio, dtype):
+    _say(f"kron M={M} n={n} m={m} {dtype}")
+    K = n * m
+    Q = rcp_synth.orthogonal(1, m)
+    x = rcp_synth.activation(4, f"kron{M}x{K}", M, K)
+    xd = _t(x) if dtype == "f16" else _t(x.astype(np.float32))
+    xq, sc = rcp.rotate_quant_act(xd, rcp.Rotation.kron(n, _t(Q)), ratio)
+    torch.cuda.synchronize()
+    y64 = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=n, m=m, Q=Q.astype(np.float64))
+    _check_act_against_rotated(np.atleast_2d(y64), xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16), ratio)
+
+
+# ------------------------------------------------------------------------------------------
+# whole path
+# ------------------------------------------------------------------------------------------
+def _rotation(rot, seed):
+    if rot is None:
+        return None, dict(kind=oracle.ROT_NONE)
+    if rot[0] == "wht":
+        return rcp.Rotation.wht(rot[1]), dict(kind=oracle.ROT_WHT, n_wht=rot[1])
+    Q = rcp_synth.orthogonal(seed, rot[2])
+    return rcp.Rotation.kron(rot[1], _t(Q)), dict(kind=oracle.ROT_KRON, n_wht=rot[1], m=rot[2], Q=Q.astype(np.float64))
+
+
+@pytest.mark.parametrize("config,rows", [("tiny", None), ("llama32_1b", 96), ("llama2_7b", 64), ("llama3_8b", 64)])
+def test_whole_path_on_config_shapes(config, rows):
+    """pack -> rotate+quantise -> GEMV on the GPU; the oracle takes the same steps, except that
+    its GEMV consumes the GPU's (x_q, S) so that a legal tie flip upstream cannot leak in.
+    Full K always; `rows` output rows of each layer (None = all) keep the CPU side short."""
+    for name, N, K, rot in rcp_synth.CONFIGS[config]:
+        n = N if rows is None else rows
+        _say(f"path {config}/{name} N={n} (of {N}) K={K} rot={rot}")
+        W, lo, hi, part = rcp_synth.linear_layer(0, f"{config}/{name}", n, K)
+        x = rcp_synth.activation(0, f"{config}/{name}", 1, K)
+        grot, orot = _rotation(rot, 0)
+        packed, cb = rcp.pack_weights(_t(W), _t(lo), _t(hi), _t(part))
+        xq, sc = rcp.rotate_quant_act(_t(x), grot, 1.0)
+        out, P = rcp.w2a4_gemv(packed, cb, n, K, xq, sc, 1, out_dtype=torch.float16, want_partial_sums=True)
+        torch.cuda.synchronize()
+        ref_packed, ref_cb = oracle.pack_weights(W.astype(np.float32), lo, hi, part)
+        assert np.array_equal(packed.cpu().numpy(), ref_packed)
+        assert np.array_equal(cb.cpu().numpy().view(np.uint16), ref_cb)
+        xq_h, sc_h = xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16)
+        y64 = oracle.rotate(x.astype(np.float64), **orot)
+        _check_act_against_rotated(np.atleast_2d(y64), xq_h, sc_h, 1.0)
+        ref_O, ref_P = oracle.w2a4_gemv(ref_packed, ref_cb, n, K, xq_h, sc_h, 1)
+        assert np.array_equal(P.cpu().numpy(), ref_P)
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
