@@ -107,7 +107,7 @@ int rcp_version(void);
 /* Tuning knobs for benchmarks and sweeps; they change how work is spread over the
  * GPU, never a result.  Value 0 restores the automatic choice.  Process-wide, not
  * thread-safe against concurrent launches.
- *   "gemv_lpg"     lanes of a wavefront that share one group of four rows: 16, 32, 64
+ *   "gemv_lanes"   lanes of a workgroup that share one group of four rows: 64, 128, 256
  *   "gemv_blocks"  number of workgroups the GEMV launches
  *   "gemv_variant" kernel variant (0 = automatic)
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */

@@ -108,10 +108,10 @@ int rcp_set_option(const char* name, int value)
 {
     if (name == nullptr) return fail(RCP_ERR_NULL, "rcp_set_option: name is NULL");
     Options& o = options();
-    if (strcmp(name, "gemv_lpg") == 0) {
-        if (value != 0 && value != 16 && value != 32 && value != 64)
-            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_lpg must be 0, 16, 32 or 64");
-        o.gemv_lpg = value;
+    if (strcmp(name, "gemv_lanes") == 0) {
+        if (value != 0 && value != 64 && value != 128 && value != 256)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_lanes must be 0, 64, 128 or 256");
+        o.gemv_lanes = value;
     } else if (strcmp(name, "gemv_blocks") == 0) {
         if (value < 0 || value > (1 << 20)) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_blocks out of range");
         o.gemv_blocks = value;

@@ -17,7 +17,7 @@ int check_launch(const char* what);  // hipGetLastError() -> RCP_ERR_HIP / RCP_O
 
 // ---- tuning knobs (api.hip), 0 = automatic --------------------------------------
 struct Options {
-    int gemv_lpg;        // lanes that share one group of four rows: 16, 32 or 64
+    int gemv_lanes;      // lanes that share one group of four rows: 64, 128 or 256
     int gemv_blocks;     // workgroups launched by the GEMV
     int gemv_variant;    // kernel variant selector
 };

@@ -77,9 +77,9 @@ def test_argument_errors_need_no_gpu(lib):
     assert b"workspace" in lib.rcp_last_error()
     assert act(fake, 0, 1, 64, ctypes.byref(Rot(9, 0, 0, None)), 1.0, fake, fake, None, 0, None) == -4
     lib.rcp_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
-    assert lib.rcp_set_option(b"gemv_lpg", 48) == -4
+    assert lib.rcp_set_option(b"gemv_lanes", 48) == -4
     assert lib.rcp_set_option(b"nonsense", 1) == -4
-    assert lib.rcp_set_option(b"gemv_lpg", 0) == 0
+    assert lib.rcp_set_option(b"gemv_lanes", 0) == 0
     ws = lib.rcp_act_workspace_bytes
     ws.restype = ctypes.c_size_t
     ws.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot)]

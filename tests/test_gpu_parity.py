@@ -31,7 +31,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lpg", "gemv_blocks", "gemv_variant"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_variant"):
         rcp.set_option(k, 0)
 
 
@@ -110,12 +110,12 @@ def _check_gemv(packed, cb, N, K, xq, sc, M, out_dtype):
     assert torch.equal(out, out2)
 
 
-@pytest.mark.parametrize("lpg", [0, 16, 32, 64])
+@pytest.mark.parametrize("lanes", [0, 64, 128, 256])
 @pytest.mark.parametrize("N,K", [(256, 512), (4, 32), (12, 96), (20, 2080), (1028, 4096), (72, 11008), (40, 14336),
                                  (2048, 2048)])
-def test_gemv_partial_sums_bit_exact_and_output_close(N, K, lpg):
-    _say(f"gemv N={N} K={K} lpg={lpg}")
-    rcp.set_option("gemv_lpg", lpg)
+def test_gemv_partial_sums_bit_exact_and_output_close(N, K, lanes):
+    _say(f"gemv N={N} K={K} lanes={lanes}")
+    rcp.set_option("gemv_lanes", lanes)
     packed, cb, xq, sc = _gemv_case(N + K, N, K, 1)
     _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32)
     _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float16)
