@@ -107,7 +107,8 @@ int rcp_version(void);
 /* Tuning knobs for benchmarks and sweeps; they change how work is spread over the
  * GPU, never a result.  Value 0 restores the automatic choice.  Process-wide, not
  * thread-safe against concurrent launches.
- *   "gemv_lanes"   lanes of a workgroup that share one group of four rows: 64, 128, 256
+ *   "gemv_lanes"   lanes that share one group of four rows: 16, 32, 64, 128, 256
+ *   "gemv_unroll"  16-byte loads per lane and pipeline stage: 2, 4
  *   "gemv_blocks"  number of workgroups the GEMV launches
  *   "gemv_variant" kernel variant (0 = automatic)
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */
@@ -182,6 +183,21 @@ int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
                   const void* xq, const void* scale, int M,
                   void* out, rcp_dtype out_dtype,
                   int32_t* partial_sums_or_null, void* stream);
+
+/*
+ * One-token fusion of the two calls above for an input that needs no online rotation
+ * (or that is already rotated): the result is bit-identical to
+ *     rcp_rotate_quant_act(x, 1 token, RCP_ROT_NONE, clip_ratio) -> rcp_w2a4_gemv(M = 1)
+ * but the quantiser runs in the prologue of the GEMV kernel, so one launch is saved.
+ * x: K values of `x_dtype`.  xq_out_or_null (K/2 bytes) and scale_out_or_null (one fp16)
+ * receive the quantised activation the kernel used; both may be NULL for K <= 16384, for
+ * larger K they are required (the call then runs the two kernels through them).
+ */
+int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
+                        const void* x, rcp_dtype x_dtype, float clip_ratio,
+                        void* out, rcp_dtype out_dtype,
+                        void* xq_out_or_null, void* scale_out_or_null,
+                        int32_t* partial_sums_or_null, void* stream);
 
 /* Verification helper: expand the packed indices to one byte per weight,
  * idx_out[h*K + k] in 0..3 (device, N*K bytes). */

@@ -34,29 +34,6 @@ __device__ __forceinline__ float block_max(float v, float* red)
     return r;
 }
 
-// S = fp16((ratio * a) / 7); 1 when that is zero, capped at the largest finite half.
-__device__ __forceinline__ uint16_t scale_bits_from_amax(float a, float clip_ratio)
-{
-    const float raw = __fdiv_rn(__fmul_rn(clip_ratio, a), 7.0f);
-    uint16_t b = __half_as_ushort(__float2half_rn(raw));
-    if ((b & 0x7fffu) == 0) b = 0x3c00u;
-    if ((b & 0x7fffu) >= 0x7c00u) b = 0x7bffu;
-    return b;
-}
-
-// Eight values -> one dword of int4: nibble j = clamp(rint(y[j] / s), -8, 7).
-__device__ __forceinline__ uint32_t quantize8(const float (&y)[8], float s)
-{
-    uint32_t w = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        float r = rintf(__fdiv_rn(y[j], s));
-        r = fminf(fmaxf(r, -8.0f), 7.0f);
-        w |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xfu) << (4 * j);
-    }
-    return w;
-}
-
 // ---------------------------------------------------------------------------------------
 // no rotation (or an fp32 vector that is already rotated): amax, scale, quantise
 // One workgroup per token; a thread owns ITERS groups of eight consecutive elements.

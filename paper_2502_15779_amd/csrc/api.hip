@@ -28,7 +28,7 @@ int check_launch(const char* what)
 
 Options& options()
 {
-    static Options o = {0, 0, 0};
+    static Options o = {0, 0, 0, 0};
     return o;
 }
 
@@ -109,9 +109,13 @@ int rcp_set_option(const char* name, int value)
     if (name == nullptr) return fail(RCP_ERR_NULL, "rcp_set_option: name is NULL");
     Options& o = options();
     if (strcmp(name, "gemv_lanes") == 0) {
-        if (value != 0 && value != 64 && value != 128 && value != 256)
-            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_lanes must be 0, 64, 128 or 256");
+        if (value != 0 && value != 16 && value != 32 && value != 64 && value != 128 && value != 256)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_lanes must be 0, 16, 32, 64, 128 or 256");
         o.gemv_lanes = value;
+    } else if (strcmp(name, "gemv_unroll") == 0) {
+        if (value != 0 && value != 2 && value != 4)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_unroll must be 0, 2 or 4");
+        o.gemv_unroll = value;
     } else if (strcmp(name, "gemv_blocks") == 0) {
         if (value < 0 || value > (1 << 20)) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_blocks out of range");
         o.gemv_blocks = value;
@@ -190,6 +194,35 @@ int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K, const 
         return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemv: scale must be 2-byte aligned");
     return launch_gemv(packed, codebook, N, K, xq, scale, M, out, out_dtype, partial_sums_or_null,
                        static_cast<hipStream_t>(stream));
+}
+
+int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K, const void* x,
+                        rcp_dtype x_dtype, float clip_ratio, void* out, rcp_dtype out_dtype,
+                        void* xq_out_or_null, void* scale_out_or_null, int32_t* partial_sums_or_null,
+                        void* stream)
+{
+    if (!packed || !codebook || !x || !out) return fail(RCP_ERR_NULL, "rcp_quant_w2a4_gemv: NULL pointer argument");
+    if (int rc = check_shape("rcp_quant_w2a4_gemv", N, K)) return rc;
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w2a4_gemv: unknown dtype %d", static_cast<int>(x_dtype));
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w2a4_gemv: out_dtype must be RCP_F16 or RCP_F32");
+    if (!(clip_ratio > 0.0f) || !(clip_ratio <= 1.0f))
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w2a4_gemv: clip_ratio %g outside (0, 1]", static_cast<double>(clip_ratio));
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(x) || !aligned16(out) || !aligned16(xq_out_or_null) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_quant_w2a4_gemv: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale_out_or_null) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_quant_w2a4_gemv: scale_out must be 2-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (quant_gemv_supported(K))
+        return launch_quant_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
+                                 scale_out_or_null, partial_sums_or_null, st);
+    // K too large for the in-kernel quantiser: two launches through the caller's x_q / S buffers
+    if (!xq_out_or_null || !scale_out_or_null)
+        return fail(RCP_ERR_WORKSPACE, "rcp_quant_w2a4_gemv: K=%d needs xq_out and scale_out as scratch", K);
+    if (int rc = launch_act(x, x_dtype, 1, K, nullptr, clip_ratio, xq_out_or_null, scale_out_or_null, nullptr, 0, st)) return rc;
+    return launch_gemv(packed, codebook, N, K, xq_out_or_null, scale_out_or_null, 1, out, out_dtype, partial_sums_or_null, st);
 }
 
 }  // extern "C"

@@ -16,19 +16,23 @@
 // look-up and no float conversion in the loop.  The LUT is touched only in the epilogue.
 //
 // Work decomposition.  A group of four rows is K/16 units of 16 bytes (4 rows x 16
-// columns).  LG = 64*WS lanes (WS = 1, 2 or 4 wavefronts of a 256-thread workgroup) share
-// one row group: lane t takes units t, t + LG, t + 2 LG, ...  so every load instruction of
-// a wavefront reads 1 KiB of consecutive bytes.  The kernel is latency bound at LLaMA
-// sizes (a 4096 x 4096 matrix is 4 MiB, less than what must be in flight to fill HBM), so
-// a lane issues the loads of its first row group before anything else, and the loads of
-// the next row group before it reduces the current one.
+// columns).  LG = LW*WS lanes share one row group: LW = 16, 32 or 64 lanes of a wavefront
+// (a wavefront then works on 64/LW row groups side by side), and for LW = 64 optionally
+// WS = 2 or 4 wavefronts of the 256-thread workgroup.  Lane t of the LG takes units
+// t, t + LG, t + 2 LG, ...  Few lanes per row group make the cross-lane reduction cheap
+// (it is paid once per row group) and suit tall matrices; many lanes put a small matrix on
+// enough wavefronts.  The kernel is latency bound at LLaMA sizes, so the loop is software
+// pipelined over (row group, chunk of UNR units): the loads of the next step are in flight
+// while the current one is computed and reduced, and the very first loads are issued
+// before the activations are staged.
 #include "rcp_internal.hpp"
 
 namespace rcp {
 
 constexpr int GEMV_THREADS = 256;
 constexpr int GEMV_WAVES = GEMV_THREADS / 64;
-constexpr int GEMV_UNROLL = 4;  // 16-byte loads in flight per lane and buffer
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int dot8(uint32_t a, uint32_t b, int c)
 {
@@ -53,25 +57,66 @@ __device__ __forceinline__ int wave_sum(int v)
     return v;
 }
 
-// Sum twelve per-lane values over the 64 lanes of a wavefront, scattering the results:
-// afterwards every lane of 16-lane row rho holds in t[k] the total of g[4k + perm(rho)],
-// perm = (0, 2, 1, 3).  Halving steps use the gfx950 lane-swap instructions: swapping the
-// upper half of one register with the lower half of another and adding folds two
-// registers into one.
-__device__ __forceinline__ void reduce_scatter12(const int (&g)[12], int (&t)[3])
+// Adds the upper 32 lanes of a and b onto their lower 32: lanes 0..31 get a + a(lane^32),
+// lanes 32..63 get b + b(lane^32)  (v_permlane32_swap folds two registers into one).
+__device__ __forceinline__ int fold32(int a, int b)
 {
-    int s[6];
+    auto r = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
+    return static_cast<int>(r[0]) + static_cast<int>(r[1]);
+}
+
+// Same for neighbouring 16-lane rows: even rows get a + a(row^1), odd rows b + b(row^1).
+__device__ __forceinline__ int fold16(int a, int b)
+{
+    auto r = __builtin_amdgcn_permlane16_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
+    return static_cast<int>(r[0]) + static_cast<int>(r[1]);
+}
+
+// The row (0..3 within its row group) whose sums lane `lane` ends up holding after
+// reduce_rows<LW>, and whether the lane is one of those that write a result.
+template <int LW>
+__device__ __forceinline__ int lane_row(int lane)
+{
+    const int rho = lane >> 4;
+    if constexpr (LW == 64) return ((rho & 1) << 1) | (rho >> 1);
+    else if constexpr (LW == 32) return (rho & 1) + 2 * (lane & 1);
+    else return lane & 3;
+}
+template <int LW>
+__device__ __forceinline__ bool lane_writes(int lane)
+{
+    if constexpr (LW == 64) return (lane & 15) == 0;
+    else if constexpr (LW == 32) return (lane & 15) < 2;
+    else return (lane & 15) < 4;
+}
+
+// g[4p + r] is this lane's share of 2^r * f_r of plane p.  Sums over the LW lanes that
+// share the row group and leaves in f[p] the total for row lane_row<LW>(lane).
+template <int LW>
+__device__ __forceinline__ void reduce_rows(const int (&g)[12], int lane, int (&f)[3])
+{
+    if constexpr (LW == 64) {
+        int s[6];
 #pragma unroll
-    for (int i = 0; i < 6; ++i) {
-        // lanes 0..31 <- g[2i] (own + lane^32), lanes 32..63 <- g[2i+1]
-        auto r = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(g[2 * i]), static_cast<unsigned>(g[2 * i + 1]), false, false);
-        s[i] = static_cast<int>(r[0]) + static_cast<int>(r[1]);
-    }
+        for (int i = 0; i < 6; ++i) s[i] = fold32(g[2 * i], g[2 * i + 1]);
 #pragma unroll
-    for (int k = 0; k < 3; ++k) {
-        // rows 0 and 2 <- s[2k] (own + row^1), rows 1 and 3 <- s[2k+1]
-        auto r = __builtin_amdgcn_permlane16_swap(static_cast<unsigned>(s[2 * k]), static_cast<unsigned>(s[2 * k + 1]), false, false);
-        t[k] = row_sum16(static_cast<int>(r[0]) + static_cast<int>(r[1]));
+        for (int p = 0; p < 3; ++p) f[p] = row_sum16(fold16(s[2 * p], s[2 * p + 1]));
+    } else if constexpr (LW == 32) {
+        const bool odd = lane & 1;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int lo = row_sum16(fold16(g[4 * p + 0], g[4 * p + 1]));  // rows r = 0 | 1
+            const int hi = row_sum16(fold16(g[4 * p + 2], g[4 * p + 3]));  // rows r = 2 | 3
+            f[p] = odd ? hi : lo;
+        }
+    } else {
+        const int j = lane & 3;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a0 = row_sum16(g[4 * p + 0]), a1 = row_sum16(g[4 * p + 1]);
+            const int a2 = row_sum16(g[4 * p + 2]), a3 = row_sum16(g[4 * p + 3]);
+            f[p] = (j == 0) ? a0 : (j == 1) ? a1 : (j == 2) ? a2 : a3;
+        }
     }
 }
 
@@ -93,81 +138,112 @@ __device__ __forceinline__ void cell_update(uint32_t b0, uint32_t b1, const uint
     }
 }
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
 // LDS: quantised activations, token t at dword t*(K/8), padded so that the reads of a
 // lane whose unit lies beyond K stay inside the allocation (their weights are zero);
 // then 4*MT ints of per-wavefront sums of q; then, for WS > 1, the cross-wavefront
 // reduction slots int[2][4 waves][4 rows][3*MT].
-template <int MT>
-__host__ __device__ constexpr int gemv_x_bytes(int K, int M, int lanes)
+__host__ __device__ constexpr int gemv_x_bytes(int K, int M, int span /* LG * UNR */)
 {
     const int U = K / 16;
-    const int span = lanes * GEMV_UNROLL;
     const int padded_units = ((U + span - 1) / span) * span;
     return ((M - 1) * U + padded_units) * 8;
 }
 
-// Weight loads go through a buffer resource that covers exactly one row group, so a unit
-// beyond K (or a whole row group beyond N) reads as zero without a branch in the loop.
-template <int WS, int MT, bool OUT_F16>
+// XDT < 0: `xq` / `scale` are the quantised activations.  XDT = RCP_F16 / RCP_F32 / RCP_BF16
+// (one token only): `xraw` is the raw activation of that type and the workgroup quantises it
+// itself, exactly as quant_kernel would (amax, S = fp16(ratio*amax/7), q = rint(x/S)); the
+// first workgroup also writes x_q and S to xq_out / scale_out when those are given.
+constexpr int GEMV_XG = 8;  // groups of eight raw activations a thread can hold: K <= 16384
+
+template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT>
 __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restrict__ packed,
                                                             const uint2* __restrict__ codebook, int N, int K,
                                                             const uint4* __restrict__ xq,
                                                             const uint16_t* __restrict__ scale, int M,
-                                                            void* __restrict__ out, int32_t* __restrict__ Pout, int dbg)
+                                                            void* __restrict__ out, int32_t* __restrict__ Pout,
+                                                            const void* __restrict__ xraw, float clip_ratio,
+                                                            uint32_t* __restrict__ xq_out, uint16_t* __restrict__ scale_out)
 {
+    static_assert(WS == 1 || LW == 64, "several wavefronts per row group only with whole wavefronts");
+    static_assert(XDT < 0 || MT == 1, "the fused quantiser handles one token");
     extern __shared__ uint4 smem4[];
-    constexpr int SLOTS = GEMV_WAVES / WS;  // row groups a workgroup works on at a time
-    constexpr int LG = 64 * WS;             // lanes per row group
+    constexpr int SW = 64 / LW;                     // row groups side by side in a wavefront
+    constexpr int SLOTS = (GEMV_WAVES / WS) * SW;   // row groups a workgroup works on at a time
+    constexpr int LG = LW * WS;                     // lanes per row group
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int slot = wave / WS, wsub = wave % WS;
-    const int tg = wsub * 64 + lane;  // this lane's position among the LG lanes
+    const int wsub = wave % WS;
+    const int slot = (wave / WS) * SW + lane / LW;
+    const int tg = wsub * 64 + lane % LW;  // this lane's position among the LG lanes
     const int U = K / 16, G = N / 4;
     const int xdw = K / 8;  // activation dwords per token
     const int nbatch = (G + SLOTS - 1) / SLOTS;
-    const int nchunk = (U + LG * GEMV_UNROLL - 1) / (LG * GEMV_UNROLL);
-    const int rho = lane >> 4;
-    const int my_row = ((rho & 1) << 1) | (rho >> 1);  // perm(rho): the row this lane's sums belong to
+    const int nchunk = (U + LG * UNR - 1) / (LG * UNR);
+    const int my_row = lane_row<LW>(lane);
 
-    auto row_group = [&](int g) {
-        const bool ok = g < G;
-        return __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint4*>(packed + static_cast<size_t>(ok && dbg != 2 ? g : (g & 7)) * U), 0, ok ? U * 16 : 0, 0x00020000);
+    // One buffer resource over the whole matrix; a unit beyond K or a row group beyond N
+    // gets an offset past the end, which the hardware answers with zeros: no branch and no
+    // select on the data in the loop.
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
+    const int nblk = gridDim.x;
+    // Lane t owns units t, t + LG, ... of a row group: my_units of them.  When K fills every
+    // chunk exactly no lane ever runs past K and the test below is always true.
+    const int my_units = (U % (LG * UNR)) != 0 ? (U - tg + LG - 1) / LG : 0x7fffffff;
+    // Byte offset of this lane's first unit in a batch, and its step from one batch of this
+    // workgroup to the next.  A row group beyond N lands beyond the end of the resource (the
+    // overshoot is less than the matrix size, which is below 2 GiB, so nothing wraps).
+    auto batch_offset = [&](int bb) -> unsigned {
+        return (static_cast<unsigned>(bb * SLOTS + slot) * U + tg) * 16u;
     };
-    auto load_chunk = [&](__amdgpu_buffer_rsrc_t rg, int ch, u32x4 (&w)[GEMV_UNROLL]) {
-        const int voff = (tg + ch * GEMV_UNROLL * LG) * 16;
+    const unsigned batch_stride = static_cast<unsigned>(nblk) * SLOTS * U * 16u;
+    auto load_chunk = [&](unsigned base, int ch, u32x4 (&w)[UNR]) {
 #pragma unroll
-        for (int i = 0; i < GEMV_UNROLL; ++i) w[i] = __builtin_amdgcn_raw_buffer_load_b128(rg, voff, i * LG * 16, 0);
+        for (int i = 0; i < UNR; ++i) {
+            const int it = ch * UNR + i;
+            const unsigned off = it < my_units ? base : 0x80000000u;
+            w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), it * LG * 16, 0);
+        }
     };
 
     // Memory returns loads in issue order, so the small ones the prologue needs go first:
     // the activations (first 4 KiB per token straight into registers) and the scales; then
-    // the weight loads of the first row group, before any other work.
+    // the weight loads of the first step, before any other work.
     const int per_token = xdw / 4;  // 16-byte pieces of one token's activations
     u32x4 xfirst[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint4*>(xq + static_cast<size_t>(t < M ? t : 0) * per_token), 0, t < M ? per_token * 16 : 0, 0x00020000);
-        xfirst[t] = __builtin_amdgcn_raw_buffer_load_b128(xr, static_cast<int>(threadIdx.x) * 16, 0, 0);
-    }
     float sc[MT];
+    float xr8[XDT >= 0 ? GEMV_XG : 1][8];  // raw activations of the fused path
+    if constexpr (XDT < 0) {
 #pragma unroll
-    for (int t = 0; t < MT; ++t) sc[t] = half_bits_to_float(scale[t < M ? t : 0]);
+        for (int t = 0; t < MT; ++t) {
+            const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<uint4*>(xq + static_cast<size_t>(t < M ? t : 0) * per_token), 0, t < M ? per_token * 16 : 0, 0x00020000);
+            xfirst[t] = __builtin_amdgcn_raw_buffer_load_b128(xr, static_cast<int>(threadIdx.x) * 16, 0, 0);
+        }
+#pragma unroll
+        for (int t = 0; t < MT; ++t) sc[t] = half_bits_to_float(scale[t < M ? t : 0]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < GEMV_XG; ++i) {
+            const int u8 = threadIdx.x + i * GEMV_THREADS;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) xr8[i][j] = 0.0f;
+            if (u8 < xdw) load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u8) * 8, xr8[i]);
+        }
+    }
 
-    int b = blockIdx.x;
-    u32x4 wnext[GEMV_UNROLL];
-    __amdgpu_buffer_rsrc_t rg_cur = row_group(b * SLOTS + slot);
-    load_chunk(rg_cur, 0, wnext);
-    uint2 lut_next = codebook[4 * min(b * SLOTS + slot, G - 1) + my_row];
+    int b = blockIdx.x;  // this workgroup's current batch of SLOTS row groups
+    unsigned base = batch_offset(b);
+    u32x4 wA[UNR], wB[UNR];  // the two pipeline stages alternate between these
+    load_chunk(base, 0, wA);
+    int lut_row = min(4 * (b * SLOTS + slot) + my_row, N - 1);  // clamped: lanes past N read a valid row
+    uint2 lut_cur = codebook[lut_row];
 
     // stage the activations and sum them: T[t] = sum_k q[t][k], the same for every row
-    const int x_bytes = gemv_x_bytes<MT>(K, M, LG);
+    const int x_bytes = gemv_x_bytes(K, M, LG * UNR);
     int* tsum = reinterpret_cast<int*>(reinterpret_cast<char*>(smem4) + x_bytes);  // [GEMV_WAVES][MT]
-    int* red = tsum + GEMV_WAVES * MT;
-    {
+    int* red = tsum + GEMV_WAVES * MT + 4;  // 4 slots in between serve the fused quantiser's maximum
+    if constexpr (XDT < 0) {
         u32x4* sx4 = reinterpret_cast<u32x4*>(smem4);
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
@@ -191,6 +267,38 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
             s = wave_sum(s);
             if (lane == 0) tsum[wave * MT + t] = s;
         }
+    } else {
+        // per-token symmetric int4 quantiser, the same arithmetic as quant_kernel
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < GEMV_XG; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(xr8[i][j]));
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) a = fmaxf(a, __shfl_xor(a, d, 64));
+        float* amax_slots = reinterpret_cast<float*>(tsum + GEMV_WAVES * MT);  // 4 floats after the sums
+        if (lane == 0) amax_slots[wave] = a;
+        __syncthreads();
+        a = fmaxf(fmaxf(amax_slots[0], amax_slots[1]), fmaxf(amax_slots[2], amax_slots[3]));
+        const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
+        const float sq = half_bits_to_float(sb);
+        sc[0] = sq;
+        uint32_t* sx1 = reinterpret_cast<uint32_t*>(smem4);
+        const bool publish = blockIdx.x == 0 && xq_out != nullptr;
+        int s = 0;
+#pragma unroll
+        for (int i = 0; i < GEMV_XG; ++i) {
+            const int u8 = threadIdx.x + i * GEMV_THREADS;
+            if (u8 < xdw) {
+                const uint32_t qd = quantize8(xr8[i], sq);
+                sx1[u8] = qd;
+                if (publish) xq_out[u8] = qd;
+                s = dot8(qd, 0x11111111u, s);
+            }
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out != nullptr) scale_out[0] = sb;
+        s = wave_sum(s);
+        if (lane == 0) tsum[wave] = s;
     }
     __syncthreads();
     const uint2* sx2 = reinterpret_cast<const uint2*>(smem4);
@@ -198,189 +306,256 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
 #pragma unroll
     for (int t = 0; t < MT; ++t) T[t] = tsum[t] + tsum[MT + t] + tsum[2 * MT + t] + tsum[3 * MT + t];
 
+    int acc[MT][3][4];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int m = 0; m < 4; ++m) acc[t][p][m] = 0;
+
     int parity = 0;
-    for (; b < nbatch; b += gridDim.x) {
-        const int g = b * SLOTS + slot;
-        const int gn = (b + static_cast<int>(gridDim.x)) * SLOTS + slot;  // >= G past the end: reads as zero
-        const __amdgpu_buffer_rsrc_t rg_next = row_group(gn);
-        const uint2 lut_raw = lut_next;
-        int acc[MT][3][4];
-#pragma unroll
-        for (int t = 0; t < MT; ++t)
-#pragma unroll
-            for (int p = 0; p < 3; ++p)
-#pragma unroll
-                for (int m = 0; m < 4; ++m) acc[t][p][m] = 0;
+    int ch = 0;
+    // One pipeline step: start the loads of the next step (the following chunk of this
+    // batch, else the first chunk of this workgroup's next batch; past the end the loads
+    // read zeros and cost no traffic), then compute the current chunk from `w`.
+    auto step = [&](u32x4 (&w)[UNR], u32x4 (&wnext)[UNR]) {
+        const bool last = ch + 1 == nchunk;
+        const int b2 = last ? b + nblk : b;
+        const int ch2 = last ? 0 : ch + 1;
+        const unsigned base2 = base + (last ? batch_stride : 0u);
+        load_chunk(base2, ch2, wnext);
+        // keep the compiler from hoisting work on `w` above the loads just issued: it
+        // would have to wait for `w` to arrive first and the loads would start late
+        __builtin_amdgcn_sched_barrier(0);
 
-        for (int ch = 0; ch < nchunk; ++ch) {
-            u32x4 w[GEMV_UNROLL];
+        const uint2* xrow = sx2 + tg + ch * UNR * LG;
 #pragma unroll
-            for (int i = 0; i < GEMV_UNROLL; ++i) w[i] = wnext[i];
-            // keep the memory pipe busy: next chunk of this row group, else the first chunk
-            // of this workgroup's next row group
-            const bool last = ch + 1 == nchunk;
-            load_chunk(last ? rg_next : rg_cur, last ? 0 : ch + 1, wnext);
-            const uint2* xrow = sx2 + tg + ch * GEMV_UNROLL * LG;
+        for (int i = 0; i < UNR; ++i) {
+            uint32_t xa[MT], xb[MT];
 #pragma unroll
-            for (int i = 0; i < GEMV_UNROLL; ++i) {
-                uint32_t xa[MT], xb[MT];
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    const uint2 xv = xrow[(MT == 1 ? 0 : min(t, M - 1)) * (xdw / 2) + i * LG];
-                    xa[t] = xv.x;
-                    xb[t] = xv.y;
-                }
-                if (dbg == 1) {
-                    acc[0][0][0] ^= w[i].x ^ w[i].y ^ w[i].z ^ w[i].w ^ xa[0] ^ xb[0];
-                    continue;
-                }
-                cell_update<MT>(w[i].x, w[i].y, xa, acc);
-                cell_update<MT>(w[i].z, w[i].w, xb, acc);
+            for (int t = 0; t < MT; ++t) {
+                const uint2 xv = xrow[(MT == 1 ? 0 : min(t, M - 1)) * (xdw / 2) + i * LG];
+                xa[t] = xv.x;
+                xb[t] = xv.y;
             }
-        }
-        rg_cur = rg_next;
-        lut_next = codebook[4 * min(gn, G - 1) + my_row];
-
-        // The triangular solve is linear, so it is applied per lane before the reduction
-        // (the power-of-two divisions wait until the sums are complete):
-        // gsum[p] of the lanes of row rho = 2^r * f_r of plane p, r = perm(rho).
-        int gsum[MT][3];
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            int g12[12];
-#pragma unroll
-            for (int p = 0; p < 3; ++p) {
-                g12[4 * p + 0] = acc[t][p][0];
-                g12[4 * p + 1] = acc[t][p][1] - acc[t][p][0];
-                g12[4 * p + 2] = acc[t][p][2] - acc[t][p][1];
-                g12[4 * p + 3] = acc[t][p][2] - acc[t][p][3];
-            }
-            reduce_scatter12(g12, gsum[t]);
+            cell_update<MT>(w[i].x, w[i].y, xa, acc);
+            cell_update<MT>(w[i].z, w[i].w, xb, acc);
         }
 
-        if constexpr (WS > 1) {
-            // one lane per 16-lane row publishes its wavefront's sums; the first wavefront
-            // of the slot adds the others.  Two buffers alternate so that one barrier per
-            // row group is enough.
-            int* mine = red + ((parity * GEMV_WAVES + wave) * 4 + rho) * (3 * MT);
-            if ((lane & 15) == 0) {
+        if (last) {
+            // The triangular solve is linear, so it is applied per lane before the reduction
+            // (the power-of-two divisions wait until the sums are complete).
+            const int g = b * SLOTS + slot;
+            int fsum[MT][3];
 #pragma unroll
-                for (int t = 0; t < MT; ++t)
+            for (int t = 0; t < MT; ++t) {
+                int g12[12];
 #pragma unroll
-                    for (int p = 0; p < 3; ++p) mine[3 * t + p] = gsum[t][p];
+                for (int p = 0; p < 3; ++p) {
+                    g12[4 * p + 0] = acc[t][p][0];
+                    g12[4 * p + 1] = acc[t][p][1] - acc[t][p][0];
+                    g12[4 * p + 2] = acc[t][p][2] - acc[t][p][1];
+                    g12[4 * p + 3] = acc[t][p][2] - acc[t][p][3];
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) acc[t][p][m] = 0;
+                }
+                reduce_rows<LW>(g12, lane, fsum[t]);
             }
-            __syncthreads();
-            if (wsub == 0 && (lane & 15) == 0) {
-#pragma unroll
-                for (int ws = 1; ws < WS; ++ws) {
-                    const int* other = red + ((parity * GEMV_WAVES + wave + ws) * 4 + rho) * (3 * MT);
+
+            if constexpr (WS > 1) {
+                // one lane per 16-lane row publishes its wavefront's sums; the first
+                // wavefront of the slot adds the others.  Two buffers alternate so that one
+                // barrier per batch is enough.
+                const int rho = lane >> 4;
+                int* mine = red + ((parity * GEMV_WAVES + wave) * 4 + rho) * (3 * MT);
+                if ((lane & 15) == 0) {
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
 #pragma unroll
-                        for (int p = 0; p < 3; ++p) gsum[t][p] += other[3 * t + p];
+                        for (int p = 0; p < 3; ++p) mine[3 * t + p] = fsum[t][p];
+                }
+                __syncthreads();
+                if (wsub == 0 && (lane & 15) == 0) {
+#pragma unroll
+                    for (int ws = 1; ws < WS; ++ws) {
+                        const int* other = red + ((parity * GEMV_WAVES + wave + ws) * 4 + rho) * (3 * MT);
+#pragma unroll
+                        for (int t = 0; t < MT; ++t)
+#pragma unroll
+                            for (int p = 0; p < 3; ++p) fsum[t][p] += other[3 * t + p];
+                    }
+                }
+                parity ^= 1;
+            }
+
+            if (g < G && wsub == 0 && lane_writes<LW>(lane)) {
+                const int r = my_row;
+                const int h = 4 * g + r;
+                const float c0 = half_bits_to_float(static_cast<uint16_t>(lut_cur.x & 0xffffu));
+                const float c1 = half_bits_to_float(static_cast<uint16_t>(lut_cur.x >> 16));
+                const float c2 = half_bits_to_float(static_cast<uint16_t>(lut_cur.y & 0xffffu));
+                const float c3 = half_bits_to_float(static_cast<uint16_t>(lut_cur.y >> 16));
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    if (t >= M) continue;
+                    const int F0 = fsum[t][0] >> r, F1 = fsum[t][1] >> r, F3 = fsum[t][2] >> r;
+                    const int P3 = F3, P1 = F0 - F3, P2 = F1 - F3;
+                    const int P0 = T[t] - F0 - F1 + F3;
+                    float o = c0 * static_cast<float>(P0);
+                    o = fmaf(c1, static_cast<float>(P1), o);
+                    o = fmaf(c2, static_cast<float>(P2), o);
+                    o = fmaf(c3, static_cast<float>(P3), o);
+                    o *= sc[t];
+                    const size_t oi = static_cast<size_t>(t) * N + h;
+                    if constexpr (OUT_F16) static_cast<__half*>(out)[oi] = __float2half_rn(o);
+                    else static_cast<float*>(out)[oi] = o;
+                    if (Pout != nullptr)
+                        reinterpret_cast<int4*>(Pout)[oi] = make_int4(P0, P1, P2, P3);
                 }
             }
-            parity ^= 1;
+            // LUT of this lane's row in the next batch; its previous value has just been used
+            lut_row = min(lut_row + 4 * nblk * SLOTS, N - 1);
+            lut_cur = codebook[lut_row];
         }
-
-        if (g < G && wsub == 0 && (lane & 15) == 0) {
-            const int r = my_row;
-            const int h = 4 * g + r;
-            const float c0 = half_bits_to_float(static_cast<uint16_t>(lut_raw.x & 0xffffu));
-            const float c1 = half_bits_to_float(static_cast<uint16_t>(lut_raw.x >> 16));
-            const float c2 = half_bits_to_float(static_cast<uint16_t>(lut_raw.y & 0xffffu));
-            const float c3 = half_bits_to_float(static_cast<uint16_t>(lut_raw.y >> 16));
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                if (t >= M) continue;
-                const int F0 = gsum[t][0] >> r, F1 = gsum[t][1] >> r, F3 = gsum[t][2] >> r;
-                const int P3 = F3, P1 = F0 - F3, P2 = F1 - F3;
-                const int P0 = T[t] - F0 - F1 + F3;
-                float o = c0 * static_cast<float>(P0);
-                o = fmaf(c1, static_cast<float>(P1), o);
-                o = fmaf(c2, static_cast<float>(P2), o);
-                o = fmaf(c3, static_cast<float>(P3), o);
-                o *= sc[t];
-                const size_t oi = static_cast<size_t>(t) * N + h;
-                if constexpr (OUT_F16) static_cast<__half*>(out)[oi] = __float2half_rn(o);
-                else static_cast<float*>(out)[oi] = o;
-                if (Pout != nullptr)
-                    reinterpret_cast<int4*>(Pout)[oi] = make_int4(P0, P1, P2, P3);
-            }
-        }
+        b = b2;
+        ch = ch2;
+        base = base2;
+    };
+    while (true) {
+        step(wA, wB);
+        if (b >= nbatch) break;
+        step(wB, wA);
+        if (b >= nbatch) break;
     }
 }
 
-template <int WS, int MT, bool OUT_F16>
-static int launch_one(const void* packed, const void* codebook, int N, int K, const void* xq,
-                      const void* scale, int M, void* out, int32_t* P, int blocks, size_t lds, hipStream_t st)
+struct GemvPlan {
+    int lw, ws, unr, blocks;
+};
+
+struct GemvArgs {
+    const void *packed, *codebook;
+    int N, K;
+    const void *xq, *scale;
+    int M;
+    void* out;
+    rcp_dtype out_dt;
+    int32_t* P;
+    // fused quantiser (xraw != nullptr): raw activation of one token
+    const void* xraw;
+    rcp_dtype x_dt;
+    float clip_ratio;
+    void *xq_out, *scale_out;
+};
+
+template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT>
+static int launch_one(const GemvArgs& a, int blocks, hipStream_t st)
 {
+    const size_t lds = gemv_x_bytes(a.K, a.M, LW * WS * UNR) + (GEMV_WAVES * MT + 4) * sizeof(int) +
+                       (WS > 1 ? 2 * GEMV_WAVES * 4 * 3 * MT * sizeof(int) : 0);
+    if (lds > 160 * 1024)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a4_gemv: M*K/2 = %d bytes of activations exceed the LDS budget", a.M * (a.K / 2));
+    auto kernel = &gemv_kernel<LW, WS, UNR, MT, OUT_F16, XDT>;
     if (lds > 65536) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<WS, MT, OUT_F16>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_w2a4_gemv: LDS opt-in failed: %s", hipGetErrorString(e));
     }
-    gemv_kernel<WS, MT, OUT_F16><<<blocks, GEMV_THREADS, lds, st>>>(
-        static_cast<const uint4*>(packed), static_cast<const uint2*>(codebook), N, K, static_cast<const uint4*>(xq),
-        static_cast<const uint16_t*>(scale), M, out, P, options().gemv_variant);
+    kernel<<<blocks, GEMV_THREADS, lds, st>>>(
+        static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K,
+        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.M, a.out, a.P, a.xraw, a.clip_ratio,
+        static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
     return check_launch("rcp_w2a4_gemv");
 }
 
-template <int WS>
-static int launch_ws(const void* packed, const void* codebook, int N, int K, const void* xq,
-                     const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, int blocks,
-                     size_t lds_x, hipStream_t st)
+template <int LW, int WS, int UNR>
+static int launch_mt(const GemvArgs& a, int blocks, hipStream_t st)
 {
-#define RCP_GO(MT)                                                                                              \
-    do {                                                                                                        \
-        const size_t lds = gemv_x_bytes<MT>(K, M, 64 * WS) + GEMV_WAVES * MT * sizeof(int) +                  \
-                           (WS > 1 ? 2 * GEMV_WAVES * 4 * 3 * MT * sizeof(int) : 0);                          \
-        return out_dt == RCP_F16                                                                                \
-                   ? launch_one<WS, MT, true>(packed, codebook, N, K, xq, scale, M, out, P, blocks, lds, st)   \
-                   : launch_one<WS, MT, false>(packed, codebook, N, K, xq, scale, M, out, P, blocks, lds, st); \
-    } while (0)
-    if (M == 1) RCP_GO(1);
-    if (M == 2) RCP_GO(2);
-    if (M <= 4) RCP_GO(4);
-    if (M <= 8) RCP_GO(8);
-    RCP_GO(16);
+#define RCP_GO(MT, XDT)                                                                   \
+    return a.out_dt == RCP_F16 ? launch_one<LW, WS, UNR, MT, true, XDT>(a, blocks, st)    \
+                               : launch_one<LW, WS, UNR, MT, false, XDT>(a, blocks, st)
+    if (a.xraw != nullptr) {
+        if (a.x_dt == RCP_F16) RCP_GO(1, RCP_F16);
+        if (a.x_dt == RCP_F32) RCP_GO(1, RCP_F32);
+        RCP_GO(1, RCP_BF16);
+    }
+    if (a.M == 1) RCP_GO(1, -1);
+    if (a.M == 2) RCP_GO(2, -1);
+    if (a.M <= 4) RCP_GO(4, -1);
+    if (a.M <= 8) RCP_GO(8, -1);
+    RCP_GO(16, -1);
 #undef RCP_GO
+}
+
+// Shape -> (lanes per row group, loads in flight, workgroups).
+static GemvPlan plan_gemv(int N, int K, int M)
+{
+    const Options& opt = options();
+    const int G = N / 4, U = K / 16;
+    const int cus = num_compute_units();
+    GemvPlan p;
+    int lanes = opt.gemv_lanes;
+    if (lanes == 0) {
+        // one wavefront per row group; more only when there are fewer row groups than
+        // compute units (sweeps: the cross-wavefront step costs more than it gains otherwise)
+        lanes = 64;
+        if (G < cus) lanes = 128;
+        if (2 * G < cus) lanes = 256;
+        while (lanes > 16 && U < lanes) lanes /= 2;  // never more lanes than a row group has units
+    }
+    p.lw = lanes < 64 ? lanes : 64;
+    p.ws = lanes < 64 ? 1 : lanes / 64;
+    p.unr = (opt.gemv_unroll == 2 || opt.gemv_unroll == 4) ? opt.gemv_unroll : (U > lanes * 4 ? 4 : 2);
+    if (M > 2) p.unr = 2;  // the token dimension multiplies the accumulators; keep registers in check
+    const int slots = (GEMV_WAVES / p.ws) * (64 / p.lw);
+    const int nbatch = (G + slots - 1) / slots;
+    int blocks = opt.gemv_blocks;
+    if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    if (blocks > nbatch) blocks = nbatch;
+    if (blocks < 1) blocks = 1;
+    p.blocks = blocks;
+    return p;
+}
+
+static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
+{
+    if (static_cast<long long>(a.N) * a.K / 4 >= (1LL << 31))
+        return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(a.N) * a.K / 4);
+    const GemvPlan p = plan_gemv(a.N, a.K, a.M);
+    if (p.unr == 2) {
+        switch (p.lw * p.ws) {
+            case 16: return launch_mt<16, 1, 2>(a, p.blocks, st);
+            case 32: return launch_mt<32, 1, 2>(a, p.blocks, st);
+            case 64: return launch_mt<64, 1, 2>(a, p.blocks, st);
+            case 128: return launch_mt<64, 2, 2>(a, p.blocks, st);
+            default: return launch_mt<64, 4, 2>(a, p.blocks, st);
+        }
+    }
+    switch (p.lw * p.ws) {
+        case 16: return launch_mt<16, 1, 4>(a, p.blocks, st);
+        case 32: return launch_mt<32, 1, 4>(a, p.blocks, st);
+        case 64: return launch_mt<64, 1, 4>(a, p.blocks, st);
+        case 128: return launch_mt<64, 2, 4>(a, p.blocks, st);
+        default: return launch_mt<64, 4, 4>(a, p.blocks, st);
+    }
 }
 
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
 {
-    const size_t lds_x = static_cast<size_t>(M) * K / 2;
-    if (lds_x > 150 * 1024)
-        return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a4_gemv: M*K/2 = %zu bytes of activations exceed the LDS budget", lds_x);
-    const Options& opt = options();
-    const int G = N / 4, U = K / 16;
-    const int cus = num_compute_units();
+    const GemvArgs a = {packed, codebook, N, K, xq, scale, M, out, out_dt, P, nullptr, RCP_F16, 1.0f, nullptr, nullptr};
+    return dispatch_gemv(a, st);
+}
 
-    // Wavefronts per row group.  More of them put a small matrix on more wavefronts and cut
-    // the number of loads a lane has to issue one after the other; fewer save the
-    // cross-wavefront reduction.  Prefer the smallest split that (a) lets a lane cover its
-    // share of a row group with one batch of loads and (b) gives every SIMD a few wavefronts.
-    int ws = opt.gemv_lanes / 64;
-    if (ws == 0) {
-        ws = 1;
-        while (ws < 4 && (U > 64 * ws * GEMV_UNROLL || static_cast<long long>(G) * ws < 8LL * cus)) ws *= 2;
-        while (ws > 1 && U <= 32 * ws) ws /= 2;
-    }
-    const int slots = GEMV_WAVES / ws;
-    const int nbatch = (G + slots - 1) / slots;
-    int blocks = opt.gemv_blocks;
-    if (blocks == 0) {
-        const int cap = cus * 8;
-        blocks = nbatch < cap ? nbatch : cap;
-    }
-    if (blocks > nbatch) blocks = nbatch;
-    if (blocks < 1) blocks = 1;
-    switch (ws) {
-        case 1: return launch_ws<1>(packed, codebook, N, K, xq, scale, M, out, out_dt, P, blocks, lds_x, st);
-        case 2: return launch_ws<2>(packed, codebook, N, K, xq, scale, M, out, out_dt, P, blocks, lds_x, st);
-        default: return launch_ws<4>(packed, codebook, N, K, xq, scale, M, out, out_dt, P, blocks, lds_x, st);
-    }
+bool quant_gemv_supported(int K) { return K / 8 <= GEMV_XG * GEMV_THREADS; }
+
+int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                      float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                      hipStream_t st)
+{
+    const GemvArgs a = {packed, codebook, N, K, nullptr, nullptr, 1, out, out_dt, P, x, x_dt, clip_ratio, xq_out, scale_out};
+    return dispatch_gemv(a, st);
 }
 
 }  // namespace rcp

@@ -17,7 +17,8 @@ int check_launch(const char* what);  // hipGetLastError() -> RCP_ERR_HIP / RCP_O
 
 // ---- tuning knobs (api.hip), 0 = automatic --------------------------------------
 struct Options {
-    int gemv_lanes;      // lanes that share one group of four rows: 64, 128 or 256
+    int gemv_lanes;      // lanes that share one group of four rows: 16 .. 256
+    int gemv_unroll;     // 16-byte loads per lane and pipeline stage: 2 or 4
     int gemv_blocks;     // workgroups launched by the GEMV
     int gemv_variant;    // kernel variant selector
 };
@@ -35,6 +36,11 @@ int launch_act(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* ro
 
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
+// fused quantise + GEMV for one token; x is the raw activation, xq_out / scale_out optional
+int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                      float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                      hipStream_t st);
+bool quant_gemv_supported(int K);
 
 // ---- small device helpers ------------------------------------------------------------
 __device__ __forceinline__ float half_bits_to_float(uint16_t h)
@@ -80,6 +86,30 @@ __device__ __forceinline__ void load8_as_float(const void* p, size_t i, float (&
             }
         }
     }
+}
+
+// ---- the int4 quantiser (shared by the activation kernels and the fused GEMV prologue) ----
+// S = fp16((ratio * a) / 7); 1 when that is zero, capped at the largest finite half.
+__device__ __forceinline__ uint16_t scale_bits_from_amax(float a, float clip_ratio)
+{
+    const float raw = __fdiv_rn(__fmul_rn(clip_ratio, a), 7.0f);
+    uint16_t b = __half_as_ushort(__float2half_rn(raw));
+    if ((b & 0x7fffu) == 0) b = 0x3c00u;
+    if ((b & 0x7fffu) >= 0x7c00u) b = 0x7bffu;
+    return b;
+}
+
+// Eight values -> one dword of int4: nibble j = clamp(rint(y[j] / s), -8, 7).
+__device__ __forceinline__ uint32_t quantize8(const float (&y)[8], float s)
+{
+    uint32_t w = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        float r = rintf(__fdiv_rn(y[j], s));
+        r = fminf(fmaxf(r, -8.0f), 7.0f);
+        w |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xfu) << (4 * j);
+    }
+    return w;
 }
 
 }  // namespace rcp

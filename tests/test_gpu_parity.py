@@ -31,7 +31,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lanes", "gemv_blocks", "gemv_variant"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant"):
         rcp.set_option(k, 0)
 
 
@@ -110,7 +110,7 @@ def _check_gemv(packed, cb, N, K, xq, sc, M, out_dtype):
     assert torch.equal(out, out2)
 
 
-@pytest.mark.parametrize("lanes", [0, 64, 128, 256])
+@pytest.mark.parametrize("lanes", [0, 16, 32, 64, 128, 256])
 @pytest.mark.parametrize("N,K", [(256, 512), (4, 32), (12, 96), (20, 2080), (1028, 4096), (72, 11008), (40, 14336),
                                  (2048, 2048)])
 def test_gemv_partial_sums_bit_exact_and_output_close(N, K, lanes):
@@ -121,10 +121,13 @@ def test_gemv_partial_sums_bit_exact_and_output_close(N, K, lanes):
     _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float16)
 
 
+@pytest.mark.parametrize("lanes,unroll", [(16, 2), (32, 4), (64, 2), (256, 4)])
 @pytest.mark.parametrize("blocks", [1, 3, 64])
-def test_gemv_grid_stride_with_few_workgroups(blocks):
-    _say(f"gemv grid-stride blocks={blocks}")
+def test_gemv_grid_stride_with_few_workgroups(blocks, lanes, unroll):
+    _say(f"gemv grid-stride blocks={blocks} lanes={lanes} unroll={unroll}")
     rcp.set_option("gemv_blocks", blocks)
+    rcp.set_option("gemv_lanes", lanes)
+    rcp.set_option("gemv_unroll", unroll)
     N, K = 1028, 1024
     packed, cb, xq, sc = _gemv_case(3, N, K, 1)
     _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32)
@@ -156,6 +159,39 @@ def test_small_batch_matches_oracle(N, K, M):
     packed, cb, xq, sc = _gemv_case(M * 1000 + N, N, K, M)
     _check_gemv(packed, cb, N, K, xq, sc, M, torch.float32)
     _check_gemv(packed, cb, N, K, xq, sc, M, torch.float16)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("N,K,ratio", [(256, 512, 1.0), (1028, 4096, 1.0), (40, 2080, 0.9), (64, 11008, 1.0),
+                                       (24, 16384, 1.0), (16, 32768, 1.0), (4, 32, 1.0)])
+def test_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype):
+    """rcp_quant_w2a4_gemv: x_q, S and P bit-exact against the oracle's quantiser + GEMV."""
+    _say(f"fused N={N} K={K} ratio={ratio} {dtype}")
+    packed, cb, _, _ = _gemv_case(N * 3 + K, N, K, 1)
+    x16 = rcp_synth.activation(5, f"fused{K}", 1, K)
+    if dtype == "f16":
+        xd = _t(x16)
+    elif dtype == "bf16":
+        xd = _t(x16.astype(np.float32)).to(torch.bfloat16)
+    else:
+        xd = _t(x16.astype(np.float32) * np.float32(0.99963))
+    x32 = xd.to(torch.float32).cpu().numpy()
+    xq = torch.zeros((1, K // 2), dtype=torch.uint8, device=DEV)
+    sc = torch.zeros((1,), dtype=torch.float16, device=DEV)
+    out, P = rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, ratio, out_dtype=torch.float32,
+                                 xq_out=xq, scale_out=sc, want_partial_sums=True)
+    torch.cuda.synchronize()
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, ratio)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, ref_xq, ref_sc, 1)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O) + 1e-30
+    if K <= 16384:  # the scratch outputs are optional there, and the result must not depend on them
+        out2 = rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, ratio, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2)
 
 
 # ------------------------------------------------------------------------------------------
