@@ -121,6 +121,8 @@ def main():
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly from python instead of replaying a HIP graph")
+    ap.add_argument("--split", action="store_true",
+                    help="separate rcp_rotate_quant_act + rcp_w2a4_gemv launches instead of the fused quantise+GEMV call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -155,14 +157,25 @@ def main():
     outs = [torch.empty((1, N), dtype=torch.float16, device=dev) for (_, N, _, _) in launches]
     ws = torch.empty(rcp.act_workspace_bytes(1, INTER, rot_down), dtype=torch.uint8, device=dev)
 
+    ybuf = torch.empty((1, INTER), dtype=torch.float32, device=dev)
+    fused = not args.split
+
     def act(i):
+        """Activation preparation of linear i as its own launch(es)."""
+        if fused:
+            if launches[i][3]:
+                rcp.rotate_act(xs[i], rot_down, y_out=ybuf)  # rotation only; quantised inside the GEMV
+            return
         rot = rot_down if launches[i][3] else None
         rcp.rotate_quant_act(xs[i], rot, 1.0, xq_out=xqs[i], scale_out=scs[i], workspace=ws if rot else None)
 
     def gemv(l, i):
-        _, N, K, _ = launches[i]
+        _, N, K, rotated = launches[i]
         packed, cb = layers[l][i]
-        rcp.w2a4_gemv(packed, cb, N, K, xqs[i], scs[i], 1, out=outs[i])
+        if fused:
+            rcp.quant_w2a4_gemv(packed, cb, N, K, ybuf if rotated else xs[i], 1.0, out=outs[i])
+        else:
+            rcp.w2a4_gemv(packed, cb, N, K, xqs[i], scs[i], 1, out=outs[i])
 
     def step_eager():
         for l in range(L):
@@ -188,6 +201,10 @@ def main():
             fn()
         return g.replay
 
+    if not fused:
+        for i in range(4):  # the GEMV-only sweeps of the split path read these
+            rot = rot_down if launches[i][3] else None
+            rcp.rotate_quant_act(xs[i], rot, 1.0, xq_out=xqs[i], scale_out=scs[i], workspace=ws if rot else None)
     step_eager()  # warm every code path before capture
     torch.cuda.synchronize()
     step = capture(step_eager)
@@ -230,7 +247,10 @@ def main():
         def sweep(i=i, N=N, K=K):
             for l in range(L):
                 packed, cb = layers[l][i]
-                rcp.w2a4_gemv(packed, cb, N, K, xqs[i], scs[i], 1, out=outs[i])
+                if fused:
+                    rcp.quant_w2a4_gemv(packed, cb, N, K, ybuf if launches[i][3] else xs[i], 1.0, out=outs[i])
+                else:
+                    rcp.w2a4_gemv(packed, cb, N, K, xqs[i], scs[i], 1, out=outs[i])
         fn = capture(sweep)
         fn()
         s = timed(torch, fn, reps) / L
@@ -261,6 +281,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "llama2_7b_decode_bs1", "layers": L, "linears_per_layer": 7,
                    "gemv_launches_per_layer": 4, "batch": 1, "graph": not args.no_graph,
+                   "activation_quantiser": "fused into the GEMV prologue" if fused else "separate launch",
                    "down_rotation": "H_64 (x) Q_172"},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "us_per_gemv_launch": round(gemv_avg_s * 1e6, 3),

@@ -170,6 +170,14 @@ int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The rotation step alone: y = R x in fp32 (the same kernels and arithmetic as the first half
+ * of rcp_rotate_quant_act).  y_out: fp32 [M][K].  Meant to be followed by
+ * rcp_quant_w2a4_gemv, which quantises in the prologue of the GEMV kernel.
+ */
+int rcp_rotate_act(const void* x, rcp_dtype x_dtype, int M, int K,
+                   const rcp_rotation* rot, float* y_out, void* stream);
+
+/*
  * Non-uniform W2A4 GEMV (M = 1) / skinny GEMM (M <= RCP_MAX_M), Section 4.4.
  *     P[m][h][l] = sum_{k : idx[h][k] = l} q[m][k]                (int32, exact)
  *     O[m][h]    = S[m] * sum_l LUT[h][l] * P[m][h][l]            (fp32)

@@ -86,6 +86,8 @@ def lib():
         L.rcp_unpack_indices.argtypes = [vp, ci, ci, vp, vp]
         L.rcp_rotate_quant_act.restype = ci
         L.rcp_rotate_quant_act.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, vp, vp, cz, vp]
+        L.rcp_rotate_act.restype = ci
+        L.rcp_rotate_act.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), vp, vp]
         L.rcp_w2a4_gemv.restype = ci
         L.rcp_w2a4_gemv.argtypes = [vp, vp, ci, ci, vp, vp, ci, vp, ci, vp, vp]
         L.rcp_quant_w2a4_gemv.restype = ci
@@ -223,3 +225,19 @@ def quant_w2a4_gemv(packed, codebook, N, K, x, clip_ratio=1.0, out=None, out_dty
                                      opt(xq_out, "xq_out"), opt(scale_out, "scale_out"), opt(partial_sums, "partial_sums"),
                                      _stream()))
     return (out, partial_sums) if partial_sums is not None else out
+
+
+def rotate_act(x, rot: Rotation = None, y_out=None):
+    """x [M, K] -> y = R x as float32 [M, K] (rotation only)."""
+    if x.dim() == 1:
+        x = x.unsqueeze(0)
+    M, K = x.shape
+    if x.dtype not in _DTYPES:
+        raise ValueError("x must be float16, bfloat16 or float32")
+    if y_out is None:
+        y_out = torch.empty((M, K), dtype=torch.float32, device=x.device)
+    if y_out.dtype != torch.float32 or y_out.numel() < M * K:
+        raise ValueError("y_out must be float32 [M, K]")
+    _check(lib().rcp_rotate_act(_dev(x, "x"), _DTYPES[x.dtype], M, K,
+                                ctypes.byref(rot._c) if rot is not None else None, _dev(y_out, "y_out"), _stream()))
+    return y_out

@@ -91,10 +91,10 @@ __device__ __forceinline__ void register_stages(float (&v)[1 << LE], int first_b
     }
 }
 
-template <int DT, int LE>
+template <int DT, int LE, bool QUANT>
 __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict__ x, int n, int log2n, float norm,
                                                          float clip_ratio, uint32_t* __restrict__ xq,
-                                                         uint16_t* __restrict__ scale)
+                                                         uint16_t* __restrict__ scale, float* __restrict__ y_out)
 {
     constexpr int EPT = 1 << LE;
     extern __shared__ float sy[];  // n floats
@@ -147,6 +147,15 @@ __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict_
             v[e] = __fmul_rn(sy[tid * EPT + e], norm);
             a = fmaxf(a, fabsf(v[e]));
         }
+    }
+    if constexpr (!QUANT) {  // rotation only: y in binary32
+        if (active) {
+#pragma unroll
+            for (int c = 0; c < EPT / 4; ++c)
+                reinterpret_cast<float4*>(y_out + static_cast<size_t>(token) * n + static_cast<size_t>(tid) * EPT)[c] =
+                    make_float4(v[4 * c], v[4 * c + 1], v[4 * c + 2], v[4 * c + 3]);
+        }
+        return;
     }
     a = block_max(a, red);
     const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
@@ -240,6 +249,98 @@ __global__ __launch_bounds__(KRON_THREADS) void kron_rotate_kernel(const void* _
     }
 }
 
+// Faster form for n = 64 * RPL (64 .. 1024): one wavefront per column j' of Y.  Lane l owns
+// rows i = l*RPL + e of that column: it forms Z[i][j'] = sum_j X[i][j] Q[j'][j] from LDS
+// (Q row shared by the wavefront, X rows read four elements at a time), then the Hadamard
+// transform over i runs in registers (strides below RPL) and across lanes (the rest), with no
+// barrier after the staging one.
+template <int DT, int RPL>
+__global__ __launch_bounds__(KRON_THREADS) void kron_wave_kernel(const void* __restrict__ x, int n, int m,
+                                                                 const float* __restrict__ Q, float norm,
+                                                                 float* __restrict__ y)
+{
+    extern __shared__ float smem[];
+    const int K = n * m;
+    using XT = typename XStore<DT>::type;
+    float* sQ = smem;                                   // 4 rows of Q, m floats each
+    XT* sX = reinterpret_cast<XT*>(sQ + 4 * m);         // K elements in the input's storage type (m % 4 == 0)
+    const int token = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int jcol = blockIdx.x * 4 + wave;
+    {
+        constexpr int PER16 = 16 / static_cast<int>(sizeof(XT));
+        const uint4* src = reinterpret_cast<const uint4*>(static_cast<const XT*>(x) + static_cast<size_t>(token) * K);
+        uint4* dst = reinterpret_cast<uint4*>(sX);
+        for (int u = tid; u < K / PER16; u += KRON_THREADS) dst[u] = src[u];
+    }
+    for (int i = tid; i < 4 * m; i += KRON_THREADS) {
+        const int jj = i / m, j = i % m;
+        sQ[i] = (blockIdx.x * 4 + jj < m) ? Q[static_cast<size_t>(blockIdx.x * 4 + jj) * m + j] : 0.0f;
+    }
+    __syncthreads();
+
+    float z[RPL];
+    const float4* qr = reinterpret_cast<const float4*>(sQ + wave * m);
+#pragma unroll
+    for (int e = 0; e < RPL; ++e) {
+        const XT* xr = sX + static_cast<size_t>(lane * RPL + e) * m;
+        float acc = 0.0f;
+        for (int j4 = 0; j4 < m / 4; ++j4) {
+            const float4 q4 = qr[j4];
+            float x0, x1, x2, x3;
+            if constexpr (sizeof(XT) == 4) {
+                const float4 x4 = reinterpret_cast<const float4*>(xr)[j4];
+                x0 = x4.x; x1 = x4.y; x2 = x4.z; x3 = x4.w;
+            } else {
+                const uint2 raw = reinterpret_cast<const uint2*>(xr)[j4];
+                x0 = XStore<DT>::widen(static_cast<uint16_t>(raw.x & 0xffffu));
+                x1 = XStore<DT>::widen(static_cast<uint16_t>(raw.x >> 16));
+                x2 = XStore<DT>::widen(static_cast<uint16_t>(raw.y & 0xffffu));
+                x3 = XStore<DT>::widen(static_cast<uint16_t>(raw.y >> 16));
+            }
+            acc = fmaf(x0, q4.x, acc);
+            acc = fmaf(x1, q4.y, acc);
+            acc = fmaf(x2, q4.z, acc);
+            acc = fmaf(x3, q4.w, acc);
+        }
+        z[e] = acc;
+    }
+    // Hadamard transform over the row index i = lane*RPL + e
+#pragma unroll
+    for (int s = 1; s < RPL; s <<= 1)
+#pragma unroll
+        for (int e = 0; e < RPL; ++e)
+            if ((e & s) == 0) {
+                const float a = z[e], b = z[e + s];
+                z[e] = a + b;
+                z[e + s] = a - b;
+            }
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1)
+#pragma unroll
+        for (int e = 0; e < RPL; ++e) {
+            const float p = __shfl_xor(z[e], s, 64);
+            z[e] = (lane & s) ? (p - z[e]) : (z[e] + p);
+        }
+    if (jcol < m) {
+#pragma unroll
+        for (int e = 0; e < RPL; ++e)
+            y[static_cast<size_t>(token) * K + static_cast<size_t>(lane * RPL + e) * m + jcol] = z[e] * norm;
+    }
+}
+
+// x -> binary32 copy (rotation "none" of the rotation-only entry point)
+template <int DT>
+__global__ __launch_bounds__(256) void widen_kernel(const void* __restrict__ x, size_t groups, float* __restrict__ y)
+{
+    const size_t g = static_cast<size_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (g >= groups) return;
+    float v[8];
+    load8_as_float<DT>(x, g * 8, v);
+    reinterpret_cast<float4*>(y)[2 * g] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4*>(y)[2 * g + 1] = make_float4(v[4], v[5], v[6], v[7]);
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
@@ -265,8 +366,8 @@ static int launch_quant(const void* x, int M, int K, float clip_ratio, void* xq,
     return check_launch("rcp_rotate_quant_act(quantise)");
 }
 
-template <int DT>
-static int launch_wht(const void* x, int M, int n, float clip_ratio, void* xq, void* scale, hipStream_t st)
+template <int DT, bool QUANT>
+static int launch_wht(const void* x, int M, int n, float clip_ratio, void* xq, void* scale, float* y, hipStream_t st)
 {
     int log2n = 0;
     while ((1 << log2n) < n) ++log2n;
@@ -276,30 +377,54 @@ static int launch_wht(const void* x, int M, int n, float clip_ratio, void* xq, v
     const size_t lds = static_cast<size_t>(n) * sizeof(float);
     if (n <= 8192) {
         const int threads = ((n / 8 + 63) / 64) * 64;
-        wht_quant_kernel<DT, 3><<<M, threads, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s);
+        wht_quant_kernel<DT, 3, QUANT><<<M, threads, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s, y);
     } else {
         // 64 KiB of dynamic LDS plus the static reduction slots: above the default limit
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wht_quant_kernel<DT, 4>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wht_quant_kernel<DT, 4, QUANT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));
-        wht_quant_kernel<DT, 4><<<M, n / 16, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s);
+        wht_quant_kernel<DT, 4, QUANT><<<M, n / 16, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s, y);
     }
     return check_launch("rcp_rotate_quant_act(wht)");
+}
+
+template <int DT, int RPL>
+static int launch_kron_wave(const void* x, int M, int K, const rcp_rotation* rot, float* y, float norm, hipStream_t st)
+{
+    const int n = rot->n_wht, m = rot->m;
+    const size_t lds = static_cast<size_t>(4) * m * sizeof(float) + static_cast<size_t>(K) * sizeof(typename XStore<DT>::type);
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kron_wave_kernel<DT, RPL>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));
+    }
+    dim3 grid((m + 3) / 4, M);
+    kron_wave_kernel<DT, RPL><<<grid, KRON_THREADS, lds, st>>>(x, n, m, rot->Q, norm, y);
+    return check_launch("rcp_rotate_quant_act(kron)");
 }
 
 template <int DT>
 static int launch_kron(const void* x, int M, int K, const rcp_rotation* rot, float* y, hipStream_t st)
 {
     const int n = rot->n_wht, m = rot->m;
-    const size_t lds = (static_cast<size_t>(KRON_JB) * m + static_cast<size_t>(n) * KRON_JB) * sizeof(float) +
-                       static_cast<size_t>(K) * sizeof(typename XStore<DT>::type);
+    const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(n)));
+    const size_t xbytes = static_cast<size_t>(K) * sizeof(typename XStore<DT>::type);
+    if (m % 4 == 0 && n >= 64 && n <= 1024 && xbytes + 16 * m <= 160 * 1024) {
+        switch (n / 64) {
+            case 1: return launch_kron_wave<DT, 1>(x, M, K, rot, y, norm, st);
+            case 2: return launch_kron_wave<DT, 2>(x, M, K, rot, y, norm, st);
+            case 4: return launch_kron_wave<DT, 4>(x, M, K, rot, y, norm, st);
+            case 8: return launch_kron_wave<DT, 8>(x, M, K, rot, y, norm, st);
+            default: return launch_kron_wave<DT, 16>(x, M, K, rot, y, norm, st);
+        }
+    }
+    const size_t lds = (static_cast<size_t>(KRON_JB) * m + static_cast<size_t>(n) * KRON_JB) * sizeof(float) + xbytes;
     if (lds > 160 * 1024) return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act: K=%d too large for the Kronecker kernel", K);
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&kron_rotate_kernel<DT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));
     }
-    const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(n)));
     dim3 grid((m + KRON_JB - 1) / KRON_JB, M);
     kron_rotate_kernel<DT><<<grid, KRON_THREADS, lds, st>>>(x, n, m, rot->Q, norm, y);
     return check_launch("rcp_rotate_quant_act(kron)");
@@ -311,7 +436,7 @@ static int launch_act_typed(const void* x, int M, int K, const rcp_rotation* rot
 {
     const int kind = rot ? rot->kind : RCP_ROT_NONE;
     if (kind == RCP_ROT_NONE) return launch_quant<DT>(x, M, K, clip_ratio, xq, scale, st);
-    if (kind == RCP_ROT_WHT) return launch_wht<DT>(x, M, K, clip_ratio, xq, scale, st);
+    if (kind == RCP_ROT_WHT) return launch_wht<DT, true>(x, M, K, clip_ratio, xq, scale, nullptr, st);
     if (int rc = launch_kron<DT>(x, M, K, rot, static_cast<float*>(ws), st)) return rc;
     return launch_quant<RCP_F32>(ws, M, K, clip_ratio, xq, scale, st);
 }
@@ -323,6 +448,26 @@ int launch_act(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* ro
         case RCP_F16: return launch_act_typed<RCP_F16>(x, M, K, rot, clip_ratio, xq, scale, ws, st);
         case RCP_F32: return launch_act_typed<RCP_F32>(x, M, K, rot, clip_ratio, xq, scale, ws, st);
         default: return launch_act_typed<RCP_BF16>(x, M, K, rot, clip_ratio, xq, scale, ws, st);
+    }
+}
+
+template <int DT>
+static int launch_rotate_typed(const void* x, int M, int K, const rcp_rotation* rot, float* y, hipStream_t st)
+{
+    const int kind = rot ? rot->kind : RCP_ROT_NONE;
+    if (kind == RCP_ROT_WHT) return launch_wht<DT, false>(x, M, K, 1.0f, nullptr, nullptr, y, st);
+    if (kind == RCP_ROT_KRON) return launch_kron<DT>(x, M, K, rot, y, st);
+    const size_t groups = static_cast<size_t>(M) * K / 8;
+    widen_kernel<DT><<<static_cast<unsigned>((groups + 255) / 256), 256, 0, st>>>(x, groups, y);
+    return check_launch("rcp_rotate_act");
+}
+
+int launch_rotate(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float* y, hipStream_t st)
+{
+    switch (dt) {
+        case RCP_F16: return launch_rotate_typed<RCP_F16>(x, M, K, rot, y, st);
+        case RCP_F32: return launch_rotate_typed<RCP_F32>(x, M, K, rot, y, st);
+        default: return launch_rotate_typed<RCP_BF16>(x, M, K, rot, y, st);
     }
 }
 

@@ -177,6 +177,19 @@ int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K, const r
                       static_cast<hipStream_t>(stream));
 }
 
+int rcp_rotate_act(const void* x, rcp_dtype x_dtype, int M, int K, const rcp_rotation* rot, float* y_out, void* stream)
+{
+    if (!x || !y_out) return fail(RCP_ERR_NULL, "rcp_rotate_act: NULL pointer argument");
+    if (M <= 0 || M > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_rotate_act: M=%d outside 1..%d", M, RCP_MAX_M);
+    if (K <= 0 || K % 32 != 0 || K > RCP_MAX_K)
+        return fail(RCP_ERR_SHAPE, "rcp_rotate_act: K=%d must be a positive multiple of 32, at most %d", K, RCP_MAX_K);
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_act: unknown dtype %d", static_cast<int>(x_dtype));
+    if (int rc = check_rotation("rcp_rotate_act", K, rot)) return rc;
+    if (!aligned16(x) || !aligned16(y_out)) return fail(RCP_ERR_ALIGN, "rcp_rotate_act: device buffers must be 16-byte aligned");
+    return launch_rotate(x, x_dtype, M, K, rot, y_out, static_cast<hipStream_t>(stream));
+}
+
 int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                   const void* scale, int M, void* out, rcp_dtype out_dtype,
                   int32_t* partial_sums_or_null, void* stream)

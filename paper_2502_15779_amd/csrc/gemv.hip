@@ -225,10 +225,9 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
     } else {
 #pragma unroll
         for (int i = 0; i < GEMV_XG; ++i) {
-            const int u8 = threadIdx.x + i * GEMV_THREADS;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) xr8[i][j] = 0.0f;
-            if (u8 < xdw) load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u8) * 8, xr8[i]);
+            if (i * GEMV_THREADS >= xdw) break;  // uniform: whole blocks of 256 groups
+            const int u8 = min(static_cast<int>(threadIdx.x) + i * GEMV_THREADS, xdw - 1);  // clamped: duplicates are harmless
+            load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u8) * 8, xr8[i]);
         }
     }
 
@@ -271,9 +270,11 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         // per-token symmetric int4 quantiser, the same arithmetic as quant_kernel
         float a = 0.0f;
 #pragma unroll
-        for (int i = 0; i < GEMV_XG; ++i)
+        for (int i = 0; i < GEMV_XG; ++i) {
+            if (i * GEMV_THREADS >= xdw) break;
 #pragma unroll
             for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(xr8[i][j]));
+        }
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) a = fmaxf(a, __shfl_xor(a, d, 64));
         float* amax_slots = reinterpret_cast<float*>(tsum + GEMV_WAVES * MT);  // 4 floats after the sums
@@ -288,6 +289,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         int s = 0;
 #pragma unroll
         for (int i = 0; i < GEMV_XG; ++i) {
+            if (i * GEMV_THREADS >= xdw) break;
             const int u8 = threadIdx.x + i * GEMV_THREADS;
             if (u8 < xdw) {
                 const uint32_t qd = quantize8(xr8[i], sq);
@@ -489,7 +491,7 @@ static int launch_mt(const GemvArgs& a, int blocks, hipStream_t st)
 }
 
 // Shape -> (lanes per row group, loads in flight, workgroups).
-static GemvPlan plan_gemv(int N, int K, int M)
+static GemvPlan plan_gemv(int N, int K, int M, bool fused)
 {
     const Options& opt = options();
     const int G = N / 4, U = K / 16;
@@ -512,6 +514,7 @@ static GemvPlan plan_gemv(int N, int K, int M)
     const int nbatch = (G + slots - 1) / slots;
     int blocks = opt.gemv_blocks;
     if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    if (opt.gemv_blocks == 0 && fused && blocks > cus * 2) blocks = cus * 2;  // every workgroup quantises x itself
     if (blocks > nbatch) blocks = nbatch;
     if (blocks < 1) blocks = 1;
     p.blocks = blocks;
@@ -522,7 +525,7 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
 {
     if (static_cast<long long>(a.N) * a.K / 4 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(a.N) * a.K / 4);
-    const GemvPlan p = plan_gemv(a.N, a.K, a.M);
+    const GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
     if (p.unr == 2) {
         switch (p.lw * p.ws) {
             case 16: return launch_mt<16, 1, 2>(a, p.blocks, st);

@@ -34,6 +34,8 @@ size_t act_workspace_bytes(int M, int K, const rcp_rotation* rot);
 int launch_act(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float clip_ratio,
                void* xq, void* scale, void* ws, size_t ws_bytes, hipStream_t st);
 
+int launch_rotate(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float* y, hipStream_t st);
+
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 // fused quantise + GEMV for one token; x is the raw activation, xq_out / scale_out optional
@@ -99,14 +101,30 @@ __device__ __forceinline__ uint16_t scale_bits_from_amax(float a, float clip_rat
     return b;
 }
 
-// Eight values -> one dword of int4: nibble j = clamp(rint(y[j] / s), -8, 7).
+// Eight values -> one dword of int4: nibble j = clamp(rint(y[j] / s), -8, 7), where y/s is
+// the correctly rounded binary32 quotient.  t = y * (1/s) lies within a few units in the last
+// place of that quotient, so rint(t) is already the answer unless t sits within 1e-4 of a
+// rounding boundary n + 1/2 (|t| <= 16 matters only: the error is below 4e-6 there); in that
+// rare case the eight values are redone with the IEEE division.
 __device__ __forceinline__ uint32_t quantize8(const float (&y)[8], float s)
 {
+    const float rs = __frcp_rn(s);
+    float n[8];
+    bool doubt = false;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float t = __fmul_rn(y[j], rs);
+        n[j] = rintf(t);
+        doubt |= fabsf(t - n[j]) > 0.4999f;
+    }
+    if (__builtin_expect(doubt, 0)) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) n[j] = rintf(__fdiv_rn(y[j], s));
+    }
     uint32_t w = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        float r = rintf(__fdiv_rn(y[j], s));
-        r = fminf(fmaxf(r, -8.0f), 7.0f);
+        const float r = fminf(fmaxf(n[j], -8.0f), 7.0f);
         w |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xfu) << (4 * j);
     }
     return w;

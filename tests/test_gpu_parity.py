@@ -232,6 +232,38 @@ def test_quantise_without_rotation_bit_exact(M, K, ratio, dtype):
     assert np.array_equal(xq.cpu().numpy(), ref_xq)
 
 
+@pytest.mark.parametrize("scale_to", [7.0, 7.0 * 0.37109375, 7.0 * 1.3330078125, 7.0 * 3.0e-3])
+def test_quantise_at_rounding_boundaries(scale_to):
+    """Inputs whose quotient by S sits exactly on n + 1/2 or one or two binary32 steps beside it:
+    ties must go to even, neighbours to their side, exactly as the correctly rounded division says."""
+    K = 4096
+    s = np.float32(np.float16(scale_to / 7.0))            # the S the kernel will derive (amax = scale_to)
+    half = np.arange(-8.5, 8.0, 1.0, dtype=np.float32)    # -8.5 .. 7.5
+    base = (half * s).astype(np.float32)
+    cand = [base]
+    for k in (1, 2, 3):
+        up, dn = base.copy(), base.copy()
+        for _ in range(k):
+            up, dn = np.nextafter(up, np.float32(np.inf)), np.nextafter(dn, np.float32(-np.inf))
+        cand += [up, dn]
+    vals = np.concatenate(cand)
+    x = np.zeros((1, K), np.float32)
+    x[0, :vals.size] = vals
+    x[0, K - 1] = np.float32(scale_to)                    # fixes amax, hence S
+    x[0, :vals.size] = np.clip(x[0, :vals.size], -scale_to, scale_to)
+    xq, sc = rcp.rotate_quant_act(_t(x), None, 1.0)
+    torch.cuda.synchronize()
+    ref_xq, ref_sc, _ = oracle.quantize_act(x, 1.0)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+    packed, cb, _, _ = _gemv_case(77, 8, K, 1)
+    xq2 = torch.zeros((1, K // 2), dtype=torch.uint8, device=DEV)
+    rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), 8, K, _t(x), 1.0, xq_out=xq2,
+                        scale_out=torch.zeros((1,), dtype=torch.float16, device=DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(xq2.cpu().numpy(), ref_xq)
+
+
 def test_quantise_degenerate_inputs():
     K = 4096
     x = np.zeros((3, K), np.float16)
@@ -277,6 +309,31 @@ def test_kronecker_rotation_within_tie_band(M, n, m, ratio, dtype):
     torch.cuda.synchronize()
     y64 = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=n, m=m, Q=Q.astype(np.float64))
     _check_act_against_rotated(np.atleast_2d(y64), xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16), ratio)
+
+
+@pytest.mark.parametrize("kind,M,n,m", [("none", 2, 2080, 1), ("wht", 1, 64, 1), ("wht", 2, 4096, 1), ("wht", 1, 16384, 1),
+                                        ("kron", 1, 64, 172), ("kron", 2, 512, 28), ("kron", 1, 128, 12),
+                                        ("kron", 1, 1024, 8), ("kron", 1, 8, 12), ("kron", 1, 64, 7)])
+def test_rotation_only_entry_point(kind, M, n, m):
+    _say(f"rotate-only {kind} M={M} n={n} m={m}")
+    K = n * m
+    x = rcp_synth.activation(6, f"rot{kind}{K}", M, K)
+    if kind == "none":
+        y = rcp.rotate_act(_t(x), None)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), x.astype(np.float32))
+        return
+    if kind == "wht":
+        y = rcp.rotate_act(_t(x), rcp.Rotation.wht(n))
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), oracle.fwht_f32(x.astype(np.float32)))  # same binary32 butterfly
+        return
+    Q = rcp_synth.orthogonal(2, m)
+    y = rcp.rotate_act(_t(x), rcp.Rotation.kron(n, _t(Q)))
+    torch.cuda.synchronize()
+    y64 = np.atleast_2d(oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=n, m=m, Q=Q.astype(np.float64)))
+    scale = np.linalg.norm(x.astype(np.float64), axis=1, keepdims=True)
+    assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - y64) <= 2e-6 * scale)
 
 
 # ------------------------------------------------------------------------------------------
