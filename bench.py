@@ -124,6 +124,8 @@ def main():
     ap.add_argument("--split", action="store_true",
                     help="separate rcp_rotate_quant_act + rcp_w2a4_gemv launches instead of the fused quantise+GEMV call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--step-only", action="store_true",
+                    help="skip the per-shape, plain-read and small-batch side measurements (used for profiles)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -240,8 +242,9 @@ def main():
     # per-shape GEMV latency on the paper's own layer sizes, cold (32 different weight buffers):
     # the stacked buffers start with the q (resp. gate) rows, so a prefix is the single matrix
     per_shape = {}
-    for label, i, N in (("4096x4096", 1, HIDDEN), ("11008x4096", 2, INTER), ("4096x11008", 3, HIDDEN),
-                        ("12288x4096_qkv", 0, 3 * HIDDEN), ("22016x4096_gate_up", 2, 2 * INTER)):
+    side = () if args.step_only else (("4096x4096", 1, HIDDEN), ("11008x4096", 2, INTER), ("4096x11008", 3, HIDDEN),
+                                      ("12288x4096_qkv", 0, 3 * HIDDEN), ("22016x4096_gate_up", 2, 2 * INTER))
+    for label, i, N in side:
         K = launches[i][2]
 
         def sweep(i=i, N=N, K=K):
@@ -257,6 +260,51 @@ def main():
         b = gemv_bytes(N, K)
         per_shape[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1),
                             "pct_hbm_peak": round(100.0 * b / s / 1e9 / HBM_PEAK_GBPS, 2)}
+
+    # the machine's streaming-read ceiling for buffers of these sizes: a plain 128-bit-load
+    # kernel over the same packed weights (same cold 32-layer sweep), beside each shape
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    for label, i, N in side:
+        K = launches[i][2]
+
+        def rsweep(i=i, N=N, K=K):
+            for l in range(L):
+                rcp.stream_read(layers[l][i][0], N * K // 4, sink)
+        fn = capture(rsweep)
+        fn()
+        s = timed(torch, fn, reps) / L
+        per_shape[label]["plain_read_us"] = round(s * 1e6, 3)
+        per_shape[label]["plain_read_GBps"] = round(N * K // 4 / s / 1e9, 1)
+
+    # small-batch decode (M = 4, 8, 16 tokens): the same four launches per layer with M tokens,
+    # activations prepared by rcp_rotate_quant_act; bound by plain integer ALU work, not by HBM
+    small_batch = {}
+    for M in (() if args.step_only else (4, 8, 16)):
+        xm = [make_activation(torch, dev, 1000 + M * 7 + i, K).repeat(M, 1).contiguous() for i, (_, _, K, _) in enumerate(launches)]
+        for i in range(4):
+            xm[i] += torch.randn(xm[i].shape, device=dev, dtype=torch.float16) * 0.1
+        xqm = [torch.empty((M, K // 2), dtype=torch.uint8, device=dev) for (_, _, K, _) in launches]
+        scm = [torch.empty((M,), dtype=torch.float16, device=dev) for _ in launches]
+        outm = [torch.empty((M, N), dtype=torch.float16, device=dev) for (_, N, _, _) in launches]
+        wsm = torch.empty(rcp.act_workspace_bytes(M, INTER, rot_down), dtype=torch.uint8, device=dev)
+
+        def mstep(M=M, xm=xm, xqm=xqm, scm=scm, outm=outm, wsm=wsm):
+            for l in range(L):
+                for i in range(4):
+                    _, N, K, rotated = launches[i]
+                    rot = rot_down if rotated else None
+                    rcp.rotate_quant_act(xm[i], rot, 1.0, xq_out=xqm[i], scale_out=scm[i], workspace=wsm if rot else None)
+                    packed, cb = layers[l][i]
+                    rcp.w2a4_gemv(packed, cb, N, K, xqm[i], scm[i], M, out=outm[i])
+        mstep()
+        fn = capture(mstep)
+        fn()
+        s = timed(torch, fn, max(2, reps // 2))
+        macs = M * L * sum(N * K for (_, N, K, _) in launches)
+        small_batch[f"M{M}"] = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2),
+                                "int4_TMAC_per_s": round(macs / s / 1e12, 2),
+                                "tokens_per_s": round(M / s, 1)}
+        del xm, xqm, scm, outm, wsm
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
@@ -289,6 +337,7 @@ def main():
         "us_act_prep_per_layer": round(sec_act_sweep / L * 1e6, 3),
         "gemv_only_GBps": round(step_bytes / sec_gemv_sweep / 1e9, 1),
         "per_shape": per_shape,
+        "small_batch": small_batch,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),

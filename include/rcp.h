@@ -207,6 +207,12 @@ int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
                         void* xq_out_or_null, void* scale_out_or_null,
                         int32_t* partial_sums_or_null, void* stream);
 
+/* Measurement helper: read `bytes` (rounded down to 16) of a device buffer once with plain
+ * 128-bit loads and discard them.  Timing it on a buffer of a GEMV's size gives the
+ * streaming-read ceiling of the machine for a kernel of that size.  sink_or_null: 4 bytes of
+ * device memory that are practically never written. */
+int rcp_stream_read(const void* buffer, size_t bytes, void* sink_or_null, void* stream);
+
 /* Verification helper: expand the packed indices to one byte per weight,
  * idx_out[h*K + k] in 0..3 (device, N*K bytes). */
 int rcp_unpack_indices(const void* packed, int N, int K, uint8_t* idx_out, void* stream);

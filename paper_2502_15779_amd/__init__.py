@@ -86,6 +86,8 @@ def lib():
         L.rcp_unpack_indices.argtypes = [vp, ci, ci, vp, vp]
         L.rcp_rotate_quant_act.restype = ci
         L.rcp_rotate_quant_act.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, vp, vp, cz, vp]
+        L.rcp_stream_read.restype = ci
+        L.rcp_stream_read.argtypes = [vp, cz, vp, vp]
         L.rcp_rotate_act.restype = ci
         L.rcp_rotate_act.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), vp, vp]
         L.rcp_w2a4_gemv.restype = ci
@@ -241,3 +243,10 @@ def rotate_act(x, rot: Rotation = None, y_out=None):
     _check(lib().rcp_rotate_act(_dev(x, "x"), _DTYPES[x.dtype], M, K,
                                 ctypes.byref(rot._c) if rot is not None else None, _dev(y_out, "y_out"), _stream()))
     return y_out
+
+
+def stream_read(buffer, nbytes=None, sink=None):
+    """Measurement helper: stream `nbytes` of `buffer` through plain 128-bit loads."""
+    total = buffer.numel() * buffer.element_size()
+    nbytes = total if nbytes is None else min(int(nbytes), total)
+    _check(lib().rcp_stream_read(_dev(buffer, "buffer"), nbytes, _dev(sink, "sink") if sink is not None else None, _stream()))

@@ -177,6 +177,14 @@ int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K, const r
                       static_cast<hipStream_t>(stream));
 }
 
+int rcp_stream_read(const void* buffer, size_t bytes, void* sink_or_null, void* stream)
+{
+    if (!buffer) return fail(RCP_ERR_NULL, "rcp_stream_read: NULL pointer argument");
+    if (!aligned16(buffer) || (reinterpret_cast<uintptr_t>(sink_or_null) & 3u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_stream_read: buffer must be 16-byte and sink 4-byte aligned");
+    return launch_stream_read(buffer, bytes, static_cast<uint32_t*>(sink_or_null), static_cast<hipStream_t>(stream));
+}
+
 int rcp_rotate_act(const void* x, rcp_dtype x_dtype, int M, int K, const rcp_rotation* rot, float* y_out, void* stream)
 {
     if (!x || !y_out) return fail(RCP_ERR_NULL, "rcp_rotate_act: NULL pointer argument");

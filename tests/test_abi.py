@@ -29,7 +29,7 @@ def test_every_declared_function_is_exported(lib):
     names = _declared_functions()
     assert {"rcp_pack_weights", "rcp_rotate_quant_act", "rcp_w2a4_gemv", "rcp_unpack_indices",
             "rcp_packed_bytes", "rcp_act_workspace_bytes", "rcp_last_error", "rcp_version",
-            "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act"} <= set(names)
+            "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act", "rcp_stream_read"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
