@@ -44,9 +44,13 @@ def layer_launches():
 
 
 def make_layer(torch, rcp, dev, seed, layer):
-    """Synthetic weights of one layer (same recipe as rcp_synth, drawn on the GPU), packed."""
-    out = []
-    for i, (name, N, K, _) in enumerate(layer_launches()):
+    """Synthetic weights of one layer (same recipe as rcp_synth, drawn on the GPU), packed.
+    The packed indices and LUTs of the layer's four launches sit in one contiguous buffer."""
+    shapes = layer_launches()
+    total = sum(N * K // 4 + 8 * N for (_, N, K, _) in shapes)
+    blob = torch.empty(total, dtype=torch.uint8, device=dev)
+    out, off = [], 0
+    for i, (name, N, K, _) in enumerate(shapes):
         g = torch.Generator(device=dev)
         g.manual_seed(seed * 100003 + layer * 16 + i)
         W = (torch.randn((N, K), generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.float16)
@@ -55,10 +59,13 @@ def make_layer(torch, rcp, dev, seed, layer):
         lo = torch.kthvalue(Wf, k_lo, dim=1).values.contiguous()
         hi = torch.kthvalue(Wf, K - k_lo + 1, dim=1).values.contiguous()
         part = torch.softmax(torch.randn((N, 3), generator=g, device=dev, dtype=torch.float32), dim=1).contiguous()
-        packed, cb = rcp.pack_weights(W, lo, hi, part)
+        packed = blob[off:off + N * K // 4]
+        cb = blob[off + N * K // 4:off + N * K // 4 + 8 * N].view(torch.float16).view(N, 4)
+        off += N * K // 4 + 8 * N
+        rcp.pack_weights(W, lo, hi, part, packed_out=packed, codebook_out=cb)
         out.append((packed, cb))
         del W, Wf
-    return out
+    return out, blob
 
 
 def make_activation(torch, dev, seed, K):
@@ -146,7 +153,9 @@ def main():
     L = args.layers
 
     t_setup = time.perf_counter()
-    layers = [make_layer(torch, rcp, dev, args.seed, l) for l in range(L)]
+    made = [make_layer(torch, rcp, dev, args.seed, l) for l in range(L)]
+    layers = [m[0] for m in made]
+    blobs = [m[1] for m in made]
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
 
@@ -242,9 +251,9 @@ def main():
     # per-shape GEMV latency on the paper's own layer sizes, cold (32 different weight buffers):
     # the stacked buffers start with the q (resp. gate) rows, so a prefix is the single matrix
     per_shape = {}
-    side = () if args.step_only else (("4096x4096", 1, HIDDEN), ("11008x4096", 2, INTER), ("4096x11008", 3, HIDDEN),
-                                      ("12288x4096_qkv", 0, 3 * HIDDEN), ("22016x4096_gate_up", 2, 2 * INTER))
-    for label, i, N in side:
+    side_shapes = () if args.step_only else (("4096x4096", 1, HIDDEN), ("11008x4096", 2, INTER), ("4096x11008", 3, HIDDEN),
+                                             ("12288x4096_qkv", 0, 3 * HIDDEN), ("22016x4096_gate_up", 2, 2 * INTER))
+    for label, i, N in side_shapes:
         K = launches[i][2]
 
         def sweep(i=i, N=N, K=K):
@@ -264,7 +273,7 @@ def main():
     # the machine's streaming-read ceiling for buffers of these sizes: a plain 128-bit-load
     # kernel over the same packed weights (same cold 32-layer sweep), beside each shape
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
-    for label, i, N in side:
+    for label, i, N in side_shapes:
         K = launches[i][2]
 
         def rsweep(i=i, N=N, K=K):

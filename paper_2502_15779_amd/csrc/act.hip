@@ -15,13 +15,6 @@ namespace rcp {
 // ---------------------------------------------------------------------------------------
 // shared pieces
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ float wave_max(float v)
-{
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
-    return v;
-}
-
 // Maximum over the workgroup; every thread gets the result.  `red` holds 16 floats.
 __device__ __forceinline__ float block_max(float v, float* red)
 {

@@ -39,24 +39,6 @@ __device__ __forceinline__ int dot8(uint32_t a, uint32_t b, int c)
     return __builtin_amdgcn_sdot8(static_cast<int>(a), static_cast<int>(b), c, false);
 }
 
-__device__ __forceinline__ int row_sum16(int v)
-{
-    // rotations inside a row of 16 lanes: after ror 8, 4, 2, 1 every lane holds the row sum
-    v += __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false);
-    v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xf, 0xf, false);
-    v += __builtin_amdgcn_update_dpp(0, v, 0x122, 0xf, 0xf, false);
-    v += __builtin_amdgcn_update_dpp(0, v, 0x121, 0xf, 0xf, false);
-    return v;
-}
-
-__device__ __forceinline__ int wave_sum(int v)
-{
-    v = row_sum16(v);
-    v += __shfl_xor(v, 16, 64);
-    v += __shfl_xor(v, 32, 64);
-    return v;
-}
-
 // Adds the upper 32 lanes of a and b onto their lower 32: lanes 0..31 get a + a(lane^32),
 // lanes 32..63 get b + b(lane^32)  (v_permlane32_swap folds two registers into one).
 __device__ __forceinline__ int fold32(int a, int b)
@@ -275,8 +257,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
 #pragma unroll
             for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(xr8[i][j]));
         }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) a = fmaxf(a, __shfl_xor(a, d, 64));
+        a = wave_max(a);
         float* amax_slots = reinterpret_cast<float*>(tsum + GEMV_WAVES * MT);  // 4 floats after the sums
         if (lane == 0) amax_slots[wave] = a;
         __syncthreads();

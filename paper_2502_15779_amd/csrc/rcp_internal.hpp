@@ -91,6 +91,38 @@ __device__ __forceinline__ void load8_as_float(const void* p, size_t i, float (&
     }
 }
 
+// ---- wavefront-wide reductions without LDS traffic: DPP rotations inside each row of 16
+// lanes, then the four row results are read into scalar registers ----------------------------
+__device__ __forceinline__ int row_sum16(int v)
+{
+    // rotations inside a row of 16 lanes: after ror 8, 4, 2, 1 every lane holds the row sum
+    v += __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x124, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x122, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x121, 0xf, 0xf, false);
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum(int v)
+{
+    v = row_sum16(v);
+    return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) + __builtin_amdgcn_readlane(v, 32) +
+           __builtin_amdgcn_readlane(v, 48);
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#define RCP_ROW_MAX(ctrl) v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, false)))
+    RCP_ROW_MAX(0x128);
+    RCP_ROW_MAX(0x124);
+    RCP_ROW_MAX(0x122);
+    RCP_ROW_MAX(0x121);
+#undef RCP_ROW_MAX
+    const int b = __float_as_int(v);
+    return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 0)), __int_as_float(__builtin_amdgcn_readlane(b, 16))),
+                 fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 32)), __int_as_float(__builtin_amdgcn_readlane(b, 48))));
+}
+
 // ---- the int4 quantiser (shared by the activation kernels and the fused GEMV prologue) ----
 // S = fp16((ratio * a) / 7); 1 when that is zero, capped at the largest finite half.
 __device__ __forceinline__ uint16_t scale_bits_from_amax(float a, float clip_ratio)
