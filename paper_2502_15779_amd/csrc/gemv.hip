@@ -485,6 +485,11 @@ static GemvPlan plan_gemv(int N, int K, int M, bool fused)
         lanes = 64;
         if (G < cus) lanes = 128;
         if (2 * G < cus) lanes = 256;
+        // Several tokens multiply the per-row-group reduction and epilogue: tall matrices then
+        // do better with fewer lanes per row group, which pay them once for 2 or 4 row groups
+        // (sweeps on 12288 x 4096 and 22016 x 4096 at M = 4, 8, 16).
+        if (M >= 4 && G >= 16 * cus) lanes = 32;
+        else if (M > 8 && G >= 8 * cus) lanes = 16;
         while (lanes > 16 && U < lanes) lanes /= 2;  // never more lanes than a row group has units
     }
     p.lw = lanes < 64 ? lanes : 64;
@@ -495,7 +500,8 @@ static GemvPlan plan_gemv(int N, int K, int M, bool fused)
     const int nbatch = (G + slots - 1) / slots;
     int blocks = opt.gemv_blocks;
     if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
-    if (opt.gemv_blocks == 0 && fused && blocks > cus * 2) blocks = cus * 2;  // every workgroup quantises x itself
+    // every workgroup quantises x itself (fused) or stages M tokens: fewer, longer-lived workgroups
+    if (opt.gemv_blocks == 0 && (fused || M >= 4) && blocks > cus * 2) blocks = cus * 2;
     if (blocks > nbatch) blocks = nbatch;
     if (blocks < 1) blocks = 1;
     p.blocks = blocks;
