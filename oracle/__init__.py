@@ -165,3 +165,53 @@ def dequant_dot(packed, codebook, N, K, xq, scale_bits, M=1) -> np.ndarray:
     _check(lib().rcp_ref_dequant_dot(_p(pk), _p(cb), N, K, _p(xc), _p(sc), M, _p(out)),
            "dequant_dot")
     return out
+
+
+# ---- group-wise quantisation units (group size 128) ----------------------------------------
+def grouped_lut_index(h, g, NG):
+    """Half-word index of level 0 of row h, group g in the grouped LUT layout."""
+    return (((h // 4) * NG + g) * 4 + (h % 4)) * 4
+
+
+def pack_weights_grouped(W, clip_lo, clip_hi, part, group=128, want_idx=False):
+    """W [N,K]; clip_lo/hi [N,NG]; part [N,NG,3] -> packed uint8[N*K/4], codebook uint16[N*NG*4] (grouped layout)."""
+    Wc = _c(W, np.float32)
+    N, K = Wc.shape
+    NG = K // group
+    lo, hi, pt = _c(clip_lo, np.float32), _c(clip_hi, np.float32), _c(part, np.float32)
+    assert lo.shape == (N, NG) and hi.shape == (N, NG) and pt.shape == (N, NG, 3)
+    packed = np.empty(N * K // 4, dtype=np.uint8)
+    cb = np.empty(N * NG * 4, dtype=np.uint16)
+    idx = np.empty((N, K), dtype=np.uint8) if want_idx else None
+    _check(lib().rcp_ref_pack_weights_grouped(_p(Wc), N, K, group, _p(lo), _p(hi), _p(pt), _p(packed), _p(cb),
+                                              _p(idx) if want_idx else None), "pack_weights_grouped")
+    return (packed, cb, idx) if want_idx else (packed, cb)
+
+
+def pack_indices_grouped(idx, group=128) -> np.ndarray:
+    ic = _c(idx, np.uint8)
+    N, K = ic.shape
+    packed = np.empty(N * K // 4, dtype=np.uint8)
+    _check(lib().rcp_ref_pack_indices_grouped(_p(ic), N, K, group, _p(packed)), "pack_indices_grouped")
+    return packed
+
+
+def unpack_indices_grouped(packed, N, K, group=128) -> np.ndarray:
+    pk = _c(packed, np.uint8)
+    assert pk.size == N * K // 4
+    idx = np.empty((N, K), dtype=np.uint8)
+    _check(lib().rcp_ref_unpack_indices_grouped(_p(pk), N, K, group, _p(idx)), "unpack_indices_grouped")
+    return idx
+
+
+def w2a4_gemv_grouped(packed, codebook, N, K, xq, scale_bits, group=128):
+    """-> (O float64[N], P int32[N, NG, 4]) for one token."""
+    pk, cb = _c(packed, np.uint8), _c(codebook, np.uint16)
+    xc, sc = _c(xq, np.uint8), _c(scale_bits, np.uint16)
+    NG = K // group
+    assert pk.size == N * K // 4 and cb.size == N * NG * 4 and xc.size == K // 2 and sc.size >= 1
+    out = np.empty(N, dtype=np.float64)
+    P = np.empty((N, NG, 4), dtype=np.int32)
+    _check(lib().rcp_ref_w2a4_gemv_grouped(_p(pk), _p(cb), N, K, group, _p(xc), _p(sc), _p(out), _p(P)),
+           "w2a4_gemv_grouped")
+    return out, P

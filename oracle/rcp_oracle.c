@@ -424,3 +424,131 @@ int rcp_ref_dequant_dot(const uint8_t* packed, const uint16_t* codebook, int N, 
     free(q);
     return RCP_REF_OK;
 }
+
+/* ------------------------------------------------------------------------
+ * Group-wise quantisation units (Appendix table "Quantization configurations": weights are
+ * quantised in groups of 128 input channels; Section 4.4: the LUT is H x N*4 with N groups
+ * per channel).  Every (row, group) has its own clip range, partition and 4-entry LUT.
+ *
+ * Grouped packed layout (restated from include/rcp.h): the same 8-byte cells as above, but
+ * inside a group of four rows the 16-byte units (two cells = 16 columns) are stored in
+ * "lane-major" order.  With NG = K/128 groups, group g belongs to round g/32 and lane g%32;
+ * a round holds R = min(32, NG - 32*(g/32)) groups; unit i (0..7) of group g, i.e. columns
+ * 128g + 16i .. 128g + 16i + 15, sits at unit position 256*(g/32) + i*R + g%32.
+ * Grouped LUT layout: fp16 [N/4][NG][4 rows][4 levels].
+ * ---------------------------------------------------------------------- */
+#define RCP_REF_GROUP 128
+
+static inline size_t grouped_cell_byte(int h, int k, int K)
+{
+    int NG = K / RCP_REF_GROUP;
+    int u = k / 16, g = u / 8, i = u % 8;
+    int round = g / 32, lane = g % 32;
+    int R = NG - 32 * round;
+    if (R > 32) R = 32;
+    size_t pos = (size_t)256 * round + (size_t)i * R + lane;
+    size_t rowgroup_base = (size_t)(h / 4) * (size_t)(K / 16) * 16u;
+    return rowgroup_base + pos * 16u + (size_t)((k % 16) / 8) * 8u;
+}
+
+static inline int grouped_get(const uint8_t* packed, int h, int k, int K)
+{
+    size_t cb = grouped_cell_byte(h, k, K);
+    int bit = 4 * (k % 8) + (h % 4);
+    int b0 = (packed[cb + (size_t)(bit / 8)] >> (bit % 8)) & 1;
+    int b1 = (packed[cb + 4 + (size_t)(bit / 8)] >> (bit % 8)) & 1;
+    return b0 + 2 * b1;
+}
+
+static inline void grouped_set(uint8_t* packed, int h, int k, int K, int idx)
+{
+    size_t cb = grouped_cell_byte(h, k, K);
+    int bit = 4 * (k % 8) + (h % 4);
+    if (idx & 1) packed[cb + (size_t)(bit / 8)] |= (uint8_t)(1u << (bit % 8));
+    if (idx & 2) packed[cb + 4 + (size_t)(bit / 8)] |= (uint8_t)(1u << (bit % 8));
+}
+
+static inline size_t grouped_lut_index(int h, int g, int NG) /* half-word index of level 0 */
+{
+    return (((size_t)(h / 4) * NG + g) * 4u + (size_t)(h % 4)) * 4u;
+}
+
+static int grouped_shape_ok(int N, int K, int group)
+{
+    return group == RCP_REF_GROUP && N >= 4 && N % 4 == 0 && K >= group && K % group == 0;
+}
+
+/* clip_lo, clip_hi: [N][NG]; part: [N][NG][3]; codebook: N*NG*4 half-words in the grouped
+ * LUT layout; idx_or_null: plain N x K indices. */
+int rcp_ref_pack_weights_grouped(const float* W, int N, int K, int group, const float* clip_lo,
+                                 const float* clip_hi, const float* part, uint8_t* packed,
+                                 uint16_t* codebook, uint8_t* idx_or_null)
+{
+    if (!grouped_shape_ok(N, K, group)) return RCP_REF_ERR_SHAPE;
+    int NG = K / group;
+    memset(packed, 0, (size_t)N * K / 4);
+#pragma omp parallel for schedule(static)
+    for (int g4 = 0; g4 < N / 4; ++g4)
+        for (int r = 0; r < 4; ++r) {
+            int h = 4 * g4 + r;
+            for (int g = 0; g < NG; ++g) {
+                float T[3];
+                size_t q = (size_t)h * NG + g;
+                rcp_ref_ldp_grid(clip_lo[q], clip_hi[q], part[3 * q], part[3 * q + 1], part[3 * q + 2], T,
+                                 codebook + grouped_lut_index(h, g, NG));
+                for (int k = g * group; k < (g + 1) * group; ++k) {
+                    int idx = ldp_index(W[(size_t)h * K + k], T);
+                    grouped_set(packed, h, k, K, idx);
+                    if (idx_or_null) idx_or_null[(size_t)h * K + k] = (uint8_t)idx;
+                }
+            }
+        }
+    return RCP_REF_OK;
+}
+
+int rcp_ref_pack_indices_grouped(const uint8_t* idx, int N, int K, int group, uint8_t* packed)
+{
+    if (!grouped_shape_ok(N, K, group)) return RCP_REF_ERR_SHAPE;
+    memset(packed, 0, (size_t)N * K / 4);
+    for (int h = 0; h < N; ++h)
+        for (int k = 0; k < K; ++k) grouped_set(packed, h, k, K, idx[(size_t)h * K + k] & 3);
+    return RCP_REF_OK;
+}
+
+int rcp_ref_unpack_indices_grouped(const uint8_t* packed, int N, int K, int group, uint8_t* idx)
+{
+    if (!grouped_shape_ok(N, K, group)) return RCP_REF_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < N; ++h)
+        for (int k = 0; k < K; ++k) idx[(size_t)h * K + k] = (uint8_t)grouped_get(packed, h, k, K);
+    return RCP_REF_OK;
+}
+
+/* O[h] = S * sum_g sum_l LUT[h][g][l] * P[h][g][l],  P[h][g][l] = sum of q over the columns of
+ * group g whose index is l.  One token.  P_or_null: int32 [N][NG][4]. */
+int rcp_ref_w2a4_gemv_grouped(const uint8_t* packed, const uint16_t* codebook, int N, int K, int group,
+                              const uint8_t* xq, const uint16_t* scale_bits, double* out, int32_t* P_or_null)
+{
+    if (!grouped_shape_ok(N, K, group)) return RCP_REF_ERR_SHAPE;
+    int NG = K / group;
+    int8_t* q = (int8_t*)malloc((size_t)K);
+    if (!q) return RCP_REF_ERR_SHAPE;
+    rcp_ref_unpack_act(xq, 1, K, q);
+    double s = rcp_ref_f16_bits_to_f64(scale_bits[0]);
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < N; ++h) {
+        double acc = 0.0;
+        for (int g = 0; g < NG; ++g) {
+            int64_t P[4] = {0, 0, 0, 0};
+            for (int k = g * group; k < (g + 1) * group; ++k) P[grouped_get(packed, h, k, K)] += q[k];
+            const uint16_t* lut = codebook + grouped_lut_index(h, g, NG);
+            for (int l = 0; l < 4; ++l) {
+                if (P_or_null) P_or_null[((size_t)h * NG + g) * 4 + l] = (int32_t)P[l];
+                acc += rcp_ref_f16_bits_to_f64(lut[l]) * (double)P[l];
+            }
+        }
+        out[h] = s * acc;
+    }
+    free(q);
+    return RCP_REF_OK;
+}
