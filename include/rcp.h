@@ -55,6 +55,22 @@
  * Output ("O"): row-major M x N, fp16 or fp32.
  * Partial sums (verification output): int32 [M][N][4],
  *   P[m][h][l] = sum over k with idx[h][k] == l of q[m][k].
+ *
+ * Group-wise quantisation units (the *_grouped calls; the paper's deployed setting,
+ * Appendix table "Quantization configurations": weight group size 128).  Columns
+ * 128g .. 128g+127 of a row form group g, NG = K/128 groups per row; every (row, group)
+ * has its own clip range, partition fractions and four levels.
+ *   Grouped packed indices, N*K/4 bytes: the same 8-byte cells, a "unit" being the two
+ *   cells of 16 consecutive columns (16 bytes).  The K/16 units of a group of four rows
+ *   g4 = h/4 start at byte g4 * (K/16) * 16 and are ordered so that the lanes of a
+ *   wavefront that each own one quantisation group read consecutive units: group g
+ *   belongs to round g/32 and lane g%32, a round holds R = min(32, NG - 32*(g/32))
+ *   groups, and unit i (0..7: columns 128g + 16i .. 128g + 16i + 15) of group g sits at
+ *   unit position 256*(g/32) + i*R + g%32.  Inside a unit the cell of the lower eight
+ *   columns comes first.
+ *   Grouped LUT: fp16 [N/4][NG][4 rows][4 levels]: level l of row h, group g at half-word
+ *   (((h/4)*NG + g)*4 + h%4)*4 + l.  N*NG*8 bytes.
+ *   Grouped partial sums: int32 [N][NG][4].
  */
 #ifndef RCP_H
 #define RCP_H
@@ -100,6 +116,7 @@ typedef struct {
 #define RCP_MAX_K 32768       /* input channels                                     */
 #define RCP_MAX_WHT 16384     /* largest Hadamard order of a pure WHT rotation      */
 #define RCP_MAX_KRON_M 256    /* largest order of Q                                 */
+#define RCP_GROUP 128         /* input channels per unit of the group-wise calls    */
 
 /* Library version, major*10000 + minor*100 + patch. */
 int rcp_version(void);
@@ -216,6 +233,33 @@ int rcp_stream_read(const void* buffer, size_t bytes, void* sink_or_null, void* 
 /* Verification helper: expand the packed indices to one byte per weight,
  * idx_out[h*K + k] in 0..3 (device, N*K bytes). */
 int rcp_unpack_indices(const void* packed, int N, int K, uint8_t* idx_out, void* stream);
+
+/*
+ * Group-wise variants (Appendix table "Quantization configurations": weights quantised in
+ * groups of 128 input channels; Section 4.4: LUT of N*4 entries per row for N groups).
+ * `group` must be RCP_GROUP (RCP_ERR_UNSUPPORTED otherwise) and K a multiple of it.
+ *
+ * rcp_pack_weights_grouped: the export of rcp_pack_weights with one LDP grid per
+ * (row, group).  clip_lo, clip_hi: fp32 [N][NG]; part: fp32 [N][NG][3]; packed_out: N*K/4
+ * bytes in the grouped packed layout; codebook_out: N*NG*8 bytes in the grouped LUT layout.
+ *
+ * rcp_unpack_indices_grouped: grouped packed layout -> idx_out[h*K + k] in 0..3.
+ *
+ * rcp_w2a4_gemv_grouped (one token):
+ *     P[h][g][l] = sum_{k in group g : idx[h][k] = l} q[k]              (int32, exact)
+ *     O[h]       = S * sum_g sum_l LUT[h][g][l] * P[h][g][l]            (fp32 accumulation)
+ * xq, scale: one token as written by rcp_rotate_quant_act.  out: N values of `out_dtype`.
+ * partial_sums_or_null: when non-NULL receives int32 [N][NG][4].
+ */
+int rcp_pack_weights_grouped(const void* W, rcp_dtype w_dtype, int N, int K, int group,
+                             const float* clip_lo, const float* clip_hi, const float* part,
+                             void* packed_out, void* codebook_out, void* stream);
+int rcp_unpack_indices_grouped(const void* packed, int N, int K, int group,
+                               uint8_t* idx_out, void* stream);
+int rcp_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K, int group,
+                          const void* xq, const void* scale,
+                          void* out, rcp_dtype out_dtype,
+                          int32_t* partial_sums_or_null, void* stream);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "librcp.so")
 F16, F32, BF16 = 0, 1, 2
 ROT_NONE, ROT_WHT, ROT_KRON = 0, 1, 2
 MAX_M = 16
+GROUP = 128  # input channels per quantisation unit of the *_grouped calls
 
 _DTYPES = {torch.float16: F16, torch.float32: F32, torch.bfloat16: BF16}
 
@@ -94,6 +95,12 @@ def lib():
         L.rcp_w2a4_gemv.argtypes = [vp, vp, ci, ci, vp, vp, ci, vp, ci, vp, vp]
         L.rcp_quant_w2a4_gemv.restype = ci
         L.rcp_quant_w2a4_gemv.argtypes = [vp, vp, ci, ci, vp, ci, ctypes.c_float, vp, ci, vp, vp, vp, vp]
+        L.rcp_pack_weights_grouped.restype = ci
+        L.rcp_pack_weights_grouped.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.rcp_unpack_indices_grouped.restype = ci
+        L.rcp_unpack_indices_grouped.argtypes = [vp, ci, ci, ci, vp, vp]
+        L.rcp_w2a4_gemv_grouped.restype = ci
+        L.rcp_w2a4_gemv_grouped.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, ci, vp, vp]
         _lib = L
     return _lib
 
@@ -250,3 +257,59 @@ def stream_read(buffer, nbytes=None, sink=None):
     total = buffer.numel() * buffer.element_size()
     nbytes = total if nbytes is None else min(int(nbytes), total)
     _check(lib().rcp_stream_read(_dev(buffer, "buffer"), nbytes, _dev(sink, "sink") if sink is not None else None, _stream()))
+
+
+def pack_weights_grouped(W, clip_lo, clip_hi, part, group=GROUP, packed_out=None, codebook_out=None):
+    """W [N, K], clip_lo / clip_hi [N, K/group] fp32, part [N, K/group, 3] fp32
+    -> (packed uint8 [N*K/4] in the grouped layout, codebook fp16 [N/4, K/group, 4, 4])."""
+    N, K = W.shape
+    NG = K // group
+    if packed_out is None:
+        packed_out = torch.empty(max(N * K // 4, 1), dtype=torch.uint8, device=W.device)
+    if codebook_out is None:
+        codebook_out = torch.empty((max(N // 4, 1), max(NG, 1), 4, 4), dtype=torch.float16, device=W.device)
+    for t, name in ((clip_lo, "clip_lo"), (clip_hi, "clip_hi"), (part, "part")):
+        if t.dtype != torch.float32:
+            raise ValueError(f"{name} must be float32")
+    if clip_lo.numel() != N * NG or clip_hi.numel() != N * NG or part.numel() != 3 * N * NG:
+        raise ValueError("clip_lo / clip_hi / part do not match N, K/group")
+    if W.dtype not in _DTYPES:
+        raise ValueError("W must be float16, bfloat16 or float32")
+    if packed_out.numel() * packed_out.element_size() < N * K // 4 or codebook_out.numel() < 4 * N * NG:
+        raise ValueError("packed_out / codebook_out too small")
+    _check(lib().rcp_pack_weights_grouped(_dev(W, "W"), _DTYPES[W.dtype], N, K, group, _dev(clip_lo, "clip_lo"),
+                                          _dev(clip_hi, "clip_hi"), _dev(part, "part"), _dev(packed_out, "packed_out"),
+                                          _dev(codebook_out, "codebook_out"), _stream()))
+    return packed_out, codebook_out
+
+
+def unpack_indices_grouped(packed, N, K, group=GROUP, idx_out=None):
+    if idx_out is None:
+        idx_out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    if packed.numel() * packed.element_size() < N * K // 4 or idx_out.numel() < N * K:
+        raise ValueError("packed / idx_out buffer too small")
+    _check(lib().rcp_unpack_indices_grouped(_dev(packed, "packed"), N, K, group, _dev(idx_out, "idx_out"), _stream()))
+    return idx_out
+
+
+def w2a4_gemv_grouped(packed, codebook, N, K, xq, scale, group=GROUP, out=None, out_dtype=torch.float16,
+                      partial_sums=None, want_partial_sums=False):
+    """One token -> out [1, N] (and the int32 [N, K/group, 4] per-group partial sums when asked for)."""
+    NG = max(K // group, 1)
+    if out is None:
+        out = torch.empty((1, N), dtype=out_dtype, device=packed.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < N:
+        raise ValueError("out must be float16 or float32 with N elements")
+    if want_partial_sums and partial_sums is None:
+        partial_sums = torch.empty((N, NG, 4), dtype=torch.int32, device=packed.device)
+    if packed.numel() * packed.element_size() < N * K // 4 or codebook.numel() < 4 * N * NG:
+        raise ValueError("packed / codebook buffers do not match N, K, group")
+    if xq.numel() * xq.element_size() < K // 2 or scale.numel() < 1:
+        raise ValueError("xq / scale buffers do not match K")
+    if partial_sums is not None and (partial_sums.dtype != torch.int32 or partial_sums.numel() < 4 * N * NG):
+        raise ValueError("partial_sums must be int32 [N, K/group, 4]")
+    _check(lib().rcp_w2a4_gemv_grouped(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, group,
+                                       _dev(xq, "xq"), _dev(scale, "scale"), _dev(out, "out"), _DTYPES[out.dtype],
+                                       _dev(partial_sums, "partial_sums") if partial_sums is not None else None,
+                                       _stream()))
+    return (out, partial_sums) if partial_sums is not None else out

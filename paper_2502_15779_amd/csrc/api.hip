@@ -82,6 +82,13 @@ static int check_rotation(const char* fn, int K, const rcp_rotation* rot)
     return fail(RCP_ERR_UNSUPPORTED, "%s: unknown rotation kind %d", fn, rot->kind);
 }
 
+static int check_group(const char* fn, int K, int group)
+{
+    if (group != RCP_GROUP) return fail(RCP_ERR_UNSUPPORTED, "%s: group=%d, this build supports %d only", fn, group, RCP_GROUP);
+    if (K % RCP_GROUP != 0) return fail(RCP_ERR_SHAPE, "%s: K=%d must be a multiple of the group size %d", fn, K, RCP_GROUP);
+    return RCP_OK;
+}
+
 }  // namespace rcp
 
 using namespace rcp;
@@ -244,6 +251,52 @@ int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K, 
         return fail(RCP_ERR_WORKSPACE, "rcp_quant_w2a4_gemv: K=%d needs xq_out and scale_out as scratch", K);
     if (int rc = launch_act(x, x_dtype, 1, K, nullptr, clip_ratio, xq_out_or_null, scale_out_or_null, nullptr, 0, st)) return rc;
     return launch_gemv(packed, codebook, N, K, xq_out_or_null, scale_out_or_null, 1, out, out_dtype, partial_sums_or_null, st);
+}
+
+int rcp_pack_weights_grouped(const void* W, rcp_dtype w_dtype, int N, int K, int group, const float* clip_lo,
+                             const float* clip_hi, const float* part, void* packed_out, void* codebook_out,
+                             void* stream)
+{
+    if (!W || !clip_lo || !clip_hi || !part || !packed_out || !codebook_out)
+        return fail(RCP_ERR_NULL, "rcp_pack_weights_grouped: NULL pointer argument");
+    if (int rc = check_shape("rcp_pack_weights_grouped", N, K)) return rc;
+    if (int rc = check_group("rcp_pack_weights_grouped", K, group)) return rc;
+    if (w_dtype != RCP_F16 && w_dtype != RCP_F32 && w_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_pack_weights_grouped: unknown dtype %d", static_cast<int>(w_dtype));
+    if (!aligned16(W) || !aligned16(packed_out) || !aligned16(codebook_out) || !aligned16(clip_lo) ||
+        !aligned16(clip_hi) || !aligned16(part))
+        return fail(RCP_ERR_ALIGN, "rcp_pack_weights_grouped: device buffers must be 16-byte aligned");
+    return launch_pack_grouped(W, w_dtype, N, K, clip_lo, clip_hi, part, packed_out, codebook_out,
+                               static_cast<hipStream_t>(stream));
+}
+
+int rcp_unpack_indices_grouped(const void* packed, int N, int K, int group, uint8_t* idx_out, void* stream)
+{
+    if (!packed || !idx_out) return fail(RCP_ERR_NULL, "rcp_unpack_indices_grouped: NULL pointer argument");
+    if (int rc = check_shape("rcp_unpack_indices_grouped", N, K)) return rc;
+    if (int rc = check_group("rcp_unpack_indices_grouped", K, group)) return rc;
+    if (!aligned16(packed) || !aligned16(idx_out))
+        return fail(RCP_ERR_ALIGN, "rcp_unpack_indices_grouped: device buffers must be 16-byte aligned");
+    return launch_unpack_grouped(packed, N, K, idx_out, static_cast<hipStream_t>(stream));
+}
+
+int rcp_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K, int group, const void* xq,
+                          const void* scale, void* out, rcp_dtype out_dtype, int32_t* partial_sums_or_null,
+                          void* stream)
+{
+    if (!packed || !codebook || !xq || !scale || !out)
+        return fail(RCP_ERR_NULL, "rcp_w2a4_gemv_grouped: NULL pointer argument");
+    if (int rc = check_shape("rcp_w2a4_gemv_grouped", N, K)) return rc;
+    if (int rc = check_group("rcp_w2a4_gemv_grouped", K, group)) return rc;
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a4_gemv_grouped: out_dtype must be RCP_F16 or RCP_F32");
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(xq) || !aligned16(out) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemv_grouped: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemv_grouped: scale must be 2-byte aligned");
+    return launch_gemv_grouped(packed, codebook, N, K, xq, scale, out, out_dtype, partial_sums_or_null,
+                               static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

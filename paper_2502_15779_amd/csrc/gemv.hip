@@ -32,28 +32,6 @@ namespace rcp {
 constexpr int GEMV_THREADS = 256;
 constexpr int GEMV_WAVES = GEMV_THREADS / 64;
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ int dot8(uint32_t a, uint32_t b, int c)
-{
-    return __builtin_amdgcn_sdot8(static_cast<int>(a), static_cast<int>(b), c, false);
-}
-
-// Adds the upper 32 lanes of a and b onto their lower 32: lanes 0..31 get a + a(lane^32),
-// lanes 32..63 get b + b(lane^32)  (v_permlane32_swap folds two registers into one).
-__device__ __forceinline__ int fold32(int a, int b)
-{
-    auto r = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
-    return static_cast<int>(r[0]) + static_cast<int>(r[1]);
-}
-
-// Same for neighbouring 16-lane rows: even rows get a + a(row^1), odd rows b + b(row^1).
-__device__ __forceinline__ int fold16(int a, int b)
-{
-    auto r = __builtin_amdgcn_permlane16_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
-    return static_cast<int>(r[0]) + static_cast<int>(r[1]);
-}
-
 // The row (0..3 within its row group) whose sums lane `lane` ends up holding after
 // reduce_rows<LW>, and whether the lane is one of those that write a result.
 template <int LW>
@@ -98,24 +76,6 @@ __device__ __forceinline__ void reduce_rows(const int (&g)[12], int lane, int (&
             const int a0 = row_sum16(g[4 * p + 0]), a1 = row_sum16(g[4 * p + 1]);
             const int a2 = row_sum16(g[4 * p + 2]), a3 = row_sum16(g[4 * p + 3]);
             f[p] = (j == 0) ? a0 : (j == 1) ? a1 : (j == 2) ? a2 : a3;
-        }
-    }
-}
-
-// acc[p][m]: plane p in {b0, b1, b0&b1}, nibble mask m in {1, 3, 7, F}
-template <int MT>
-__device__ __forceinline__ void cell_update(uint32_t b0, uint32_t b1, const uint32_t (&x)[MT], int (&acc)[MT][3][4])
-{
-    const uint32_t pl[3] = {b0, b1, b0 & b1};
-#pragma unroll
-    for (int p = 0; p < 3; ++p) {
-        const uint32_t m1 = pl[p] & 0x11111111u, m3 = pl[p] & 0x33333333u, m7 = pl[p] & 0x77777777u;
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-            acc[t][p][0] = dot8(x[t], m1, acc[t][p][0]);
-            acc[t][p][1] = dot8(x[t], m3, acc[t][p][1]);
-            acc[t][p][2] = dot8(x[t], m7, acc[t][p][2]);
-            acc[t][p][3] = dot8(x[t], pl[p], acc[t][p][3]);
         }
     }
 }

@@ -1,0 +1,246 @@
+// W2A4 GEMV with group-wise look-up tables: every (output row, 128 input channels) has its own
+// four levels (Appendix table of quantisation configurations: weight group size 128; Section
+// 4.4: the LUT has N*4 entries per row for N groups per channel).  One token.
+//
+//     P[h][g][l] = sum_{k in group g : idx[h][k] = l} q[k]            (int32, exact)
+//     O[h]       = S * sum_g sum_l LUT[h][g][l] * P[h][g][l]          (fp32)
+//
+// The integer part is the bit-plane / v_dot8 scheme of gemv.hip.  What changes is where a
+// sum may cross lanes: levels differ from group to group, so a lane keeps a whole group to
+// itself, turns its twelve dot-product accumulators into the per-level sums of the four rows,
+// multiplies them with the group's levels and adds the four fp32 results to running row
+// totals.  Only those four floats per lane are reduced across lanes, once per row group.
+//
+// Work decomposition.  32 lanes share one group of four rows, so a wavefront works on two row
+// groups and a workgroup on eight.  Lane l takes the groups l, l + 32, l + 64, ... ("rounds").
+// The grouped packed layout stores unit i (0..7) of the R groups of a round at unit position
+// 256*round + i*R + l, so the eight 16-byte loads of a lane are each contiguous across the
+// lanes; the quantised activations are staged into LDS in the same order.  The loop over
+// (row-group batch, round) is software pipelined exactly like the per-channel kernel: the
+// eight weight loads and the 32 bytes of levels of the next step are in flight while the
+// current step is computed.
+#include "rcp_internal.hpp"
+
+namespace rcp {
+
+constexpr int GG_THREADS = 256;
+constexpr int GG_SLOTS = 8;     // row groups a workgroup works on at a time
+constexpr int GG_GROUP = 128;   // input channels per quantisation unit
+constexpr int GG_UNITS = 8;     // 16-byte units per (row group, quantisation group)
+
+__device__ __forceinline__ float fold16f(float a, float b)
+{
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ float row_sum16f(float v)
+{
+#define RCP_ROW_ADD(ctrl) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, false))
+    RCP_ROW_ADD(0x128);
+    RCP_ROW_ADD(0x124);
+    RCP_ROW_ADD(0x122);
+    RCP_ROW_ADD(0x121);
+#undef RCP_ROW_ADD
+    return v;
+}
+
+struct GroupStep {
+    u32x4 w[GG_UNITS];  // the eight units of this lane's group: 4 rows x 128 columns
+    u32x4 lut[2];       // levels of rows 0,1 | rows 2,3 (four fp16 each)
+};
+
+// LDS: activations in grouped unit order (one uint2 per unit, padded by 32 so that idle lanes
+// of a short round read inside the allocation), then the per-group sums of q.
+__host__ __device__ constexpr size_t gemv_grouped_lds_bytes(int K)
+{
+    return static_cast<size_t>(K / 16 + 32) * 8 + static_cast<size_t>(K / GG_GROUP) * 4;
+}
+
+template <bool OUT_F16>
+__global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* __restrict__ packed,
+                                                                  const uint4* __restrict__ codebook, int N, int K,
+                                                                  const uint4* __restrict__ xq,
+                                                                  const uint16_t* __restrict__ scale,
+                                                                  void* __restrict__ out, int32_t* __restrict__ Pout)
+{
+    extern __shared__ uint2 sx2[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ln = lane & 31;
+    const int slot = wave * 2 + (lane >> 5);
+    const int U = K / 16, G = N / 4, NG = K / GG_GROUP;
+    const int nround = (NG + 31) >> 5;
+    const int nbatch = (G + GG_SLOTS - 1) / GG_SLOTS;
+    const int nblk = gridDim.x;
+    int* tgs = reinterpret_cast<int*>(sx2 + U + 32);
+
+    // Buffer resources: an offset past the end is answered with zeros, so neither idle lanes
+    // nor row groups beyond N need a branch.
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t cres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint4*>(codebook), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(NG) * 32u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t xres =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(xq), 0, K / 2, 0x00020000);
+
+    auto load_step = [&](int b, int rd, GroupStep& s) {
+        const int rg = b * GG_SLOTS + slot;
+        const int R = min(32, NG - 32 * rd);
+        const bool valid = ln < R && rg < G;
+        const unsigned woff = valid ? (static_cast<unsigned>(rg) * U + 256u * rd + ln) * 16u : 0x80000000u;
+#pragma unroll
+        for (int i = 0; i < GG_UNITS; ++i)
+            s.w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(woff), i * R * 16, 0);
+        const unsigned coff = valid ? (static_cast<unsigned>(rg) * NG + 32u * rd + ln) * 32u : 0x80000000u;
+        s.lut[0] = __builtin_amdgcn_raw_buffer_load_b128(cres, static_cast<int>(coff), 0, 0);
+        s.lut[1] = __builtin_amdgcn_raw_buffer_load_b128(cres, static_cast<int>(coff), 16, 0);
+    };
+
+    // Small loads first (memory answers in issue order): this thread's group of activations
+    // (64 bytes; NG <= 256 threads take part) and the scale, then the first weight step.
+    u32x4 xg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        xg[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, static_cast<int>(threadIdx.x) * 64, i * 16, 0);
+    const float S = half_bits_to_float(scale[0]);
+
+    int b = blockIdx.x, rd = 0;
+    GroupStep sA, sB;
+    load_step(b, rd, sA);
+
+    if (static_cast<int>(threadIdx.x) < NG) {
+        const int g = threadIdx.x;
+        const int r0 = g >> 5;
+        const int R = min(32, NG - 32 * r0);
+        uint2* dst = sx2 + 256 * r0 + (g & 31);
+        int t = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            dst[(2 * i) * R] = make_uint2(xg[i].x, xg[i].y);
+            dst[(2 * i + 1) * R] = make_uint2(xg[i].z, xg[i].w);
+            t = dot8(xg[i].x, 0x11111111u, t);
+            t = dot8(xg[i].y, 0x11111111u, t);
+            t = dot8(xg[i].z, 0x11111111u, t);
+            t = dot8(xg[i].w, 0x11111111u, t);
+        }
+        tgs[g] = t;
+    }
+    __syncthreads();
+
+    float o[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    // One pipeline step: start the loads of the next step, then compute the current one.
+    auto step = [&](GroupStep& cur, GroupStep& next) {
+        const bool last = rd + 1 == nround;
+        const int b2 = last ? b + nblk : b;
+        const int rd2 = last ? 0 : rd + 1;
+        load_step(b2, rd2, next);
+        // no work on `cur` may move above the loads just issued (it would wait for `cur`
+        // first and start the loads late)
+        __builtin_amdgcn_sched_barrier(0);
+
+        const int R = min(32, NG - 32 * rd);
+        const uint2* xp = sx2 + 256 * rd + ln;
+        int acc[1][3][4];
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int m = 0; m < 4; ++m) acc[0][p][m] = 0;
+#pragma unroll
+        for (int i = 0; i < GG_UNITS; ++i) {
+            const uint2 xv = xp[i * R];
+            const uint32_t xa[1] = {xv.x}, xb[1] = {xv.y};
+            cell_update<1>(cur.w[i].x, cur.w[i].y, xa, acc);
+            cell_update<1>(cur.w[i].z, cur.w[i].w, xb, acc);
+        }
+        const bool valid = ln < R;
+        const int g = 32 * rd + ln;
+        const int Tg = valid ? tgs[g] : 0;
+        const int rg = b * GG_SLOTS + slot;
+        const uint32_t lw[8] = {cur.lut[0].x, cur.lut[0].y, cur.lut[0].z, cur.lut[0].w,
+                                cur.lut[1].x, cur.lut[1].y, cur.lut[1].z, cur.lut[1].w};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            // the triangular system of the four nibble masks, solved for row r of each plane
+            int F[3];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                const int v = r == 0 ? acc[0][p][0]
+                            : r == 1 ? acc[0][p][1] - acc[0][p][0]
+                            : r == 2 ? acc[0][p][2] - acc[0][p][1]
+                                     : acc[0][p][2] - acc[0][p][3];
+                F[p] = v >> r;
+            }
+            const int P3 = F[2], P1 = F[0] - F[2], P2 = F[1] - F[2];
+            const int P0 = Tg - F[0] - F[1] + F[2];
+            const float c0 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r] & 0xffffu));
+            const float c1 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r] >> 16));
+            const float c2 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r + 1] & 0xffffu));
+            const float c3 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r + 1] >> 16));
+            float v = o[r];
+            v = fmaf(c0, static_cast<float>(P0), v);
+            v = fmaf(c1, static_cast<float>(P1), v);
+            v = fmaf(c2, static_cast<float>(P2), v);
+            v = fmaf(c3, static_cast<float>(P3), v);
+            o[r] = v;
+            if (Pout != nullptr && valid && rg < G)
+                reinterpret_cast<int4*>(Pout)[static_cast<size_t>(4 * rg + r) * NG + g] = make_int4(P0, P1, P2, P3);
+        }
+
+        if (last) {
+            // row totals over the 32 lanes of the row group: even 16-lane rows end up with
+            // rows 0 and 2, odd ones with rows 1 and 3
+            const float s01 = row_sum16f(fold16f(o[0], o[1]));
+            const float s23 = row_sum16f(fold16f(o[2], o[3]));
+            if (rg < G && (lane & 15) == 0) {
+                const int odd = (lane >> 4) & 1;
+                const int h = 4 * rg + odd;
+                const float v0 = s01 * S, v1 = s23 * S;
+                if constexpr (OUT_F16) {
+                    static_cast<__half*>(out)[h] = __float2half_rn(v0);
+                    static_cast<__half*>(out)[h + 2] = __float2half_rn(v1);
+                } else {
+                    static_cast<float*>(out)[h] = v0;
+                    static_cast<float*>(out)[h + 2] = v1;
+                }
+            }
+            o[0] = o[1] = o[2] = o[3] = 0.0f;
+        }
+        b = b2;
+        rd = rd2;
+    };
+    while (true) {
+        step(sA, sB);
+        if (b >= nbatch) break;
+        step(sB, sA);
+        if (b >= nbatch) break;
+    }
+}
+
+int launch_gemv_grouped(const void* packed, const void* codebook, int N, int K, const void* xq,
+                        const void* scale, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
+{
+    if (static_cast<long long>(N) * K / 4 >= (1LL << 31))
+        return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv_grouped: packed matrix of %lld bytes exceeds 2 GiB",
+                    static_cast<long long>(N) * K / 4);
+    const int G = N / 4;
+    const int nbatch = (G + GG_SLOTS - 1) / GG_SLOTS;
+    const int cus = num_compute_units();
+    int blocks = options().gemv_blocks;
+    if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    if (blocks > nbatch) blocks = nbatch;
+    if (blocks < 1) blocks = 1;
+    const size_t lds = gemv_grouped_lds_bytes(K);
+    auto* pk = static_cast<const uint4*>(packed);
+    auto* cb = static_cast<const uint4*>(codebook);
+    auto* x4 = static_cast<const uint4*>(xq);
+    auto* sc = static_cast<const uint16_t*>(scale);
+    if (out_dt == RCP_F16)
+        gemv_grouped_kernel<true><<<blocks, GG_THREADS, lds, st>>>(pk, cb, N, K, x4, sc, out, P);
+    else
+        gemv_grouped_kernel<false><<<blocks, GG_THREADS, lds, st>>>(pk, cb, N, K, x4, sc, out, P);
+    return check_launch("rcp_w2a4_gemv_grouped");
+}
+
+}  // namespace rcp

@@ -157,4 +157,121 @@ int launch_unpack(const void* packed, int N, int K, uint8_t* idx, hipStream_t st
     return check_launch("rcp_unpack_indices");
 }
 
+// ---------------------------------------------------------------------------------------------
+// Group-wise quantisation units (128 input channels per unit; Appendix table of quantisation
+// configurations, LUT shape H x N*4 of Section 4.4).  Same cells, but the 16-byte units of a
+// row group are stored lane-major (layout in include/rcp.h) so that lane g%32 of the GEMV
+// finds the eight units of "its" group at a fixed stride.
+// ---------------------------------------------------------------------------------------------
+constexpr int GROUP = 128;
+
+// unit position of unit i (0..7) of group g inside its row group
+__device__ __forceinline__ int grouped_unit_pos(int g, int i, int NG)
+{
+    const int round = g >> 5;
+    const int R = min(32, NG - 32 * round);
+    return 256 * round + i * R + (g & 31);
+}
+
+// One workgroup: one group of four rows x 16 quantisation groups (256 cells); the first 64
+// threads derive the (row, group) grids, every thread then packs one cell.
+template <int DT>
+__global__ __launch_bounds__(PACK_THREADS) void pack_grouped_kernel(const void* __restrict__ W, int N, int K,
+                                                                    const float* __restrict__ clip_lo,
+                                                                    const float* __restrict__ clip_hi,
+                                                                    const float* __restrict__ part,
+                                                                    uint2* __restrict__ packed,
+                                                                    uint16_t* __restrict__ codebook)
+{
+    __shared__ float sT[16][4][3];
+    const int g4 = blockIdx.y;
+    const int NG = K / GROUP;
+    const int cells = K / 8;
+    if (threadIdx.x < 64) {
+        const int r = threadIdx.x & 3, gl = threadIdx.x >> 2;
+        const int g = blockIdx.x * 16 + gl;
+        if (g < NG) {
+            const int h = 4 * g4 + r;
+            const size_t q = static_cast<size_t>(h) * NG + g;
+            LdpGrid grid = ldp_grid(clip_lo[q], clip_hi[q], part[3 * q], part[3 * q + 1], part[3 * q + 2]);
+            sT[gl][r][0] = grid.T[0];
+            sT[gl][r][1] = grid.T[1];
+            sT[gl][r][2] = grid.T[2];
+            uint2 lut;
+            lut.x = static_cast<uint32_t>(grid.L[0]) | (static_cast<uint32_t>(grid.L[1]) << 16);
+            lut.y = static_cast<uint32_t>(grid.L[2]) | (static_cast<uint32_t>(grid.L[3]) << 16);
+            // grouped LUT layout [N/4][NG][4 rows][4 levels]
+            reinterpret_cast<uint2*>(codebook)[(static_cast<size_t>(g4) * NG + g) * 4 + r] = lut;
+        }
+    }
+    __syncthreads();
+    const int o = blockIdx.x * PACK_THREADS + threadIdx.x;  // logical cell: columns 8o .. 8o+7
+    if (o >= cells) return;
+    const int gl = threadIdx.x >> 4;  // 16 cells per quantisation group
+    uint32_t b0 = 0, b1 = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        float w[8];
+        load8_as_float<DT>(W, static_cast<size_t>(4 * g4 + r) * K + static_cast<size_t>(o) * 8, w);
+        const float T1 = sT[gl][r][0], T2 = sT[gl][r][1], T3 = sT[gl][r][2];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t idx = static_cast<uint32_t>(w[j] >= T1) + static_cast<uint32_t>(w[j] >= T2) +
+                                 static_cast<uint32_t>(w[j] >= T3);
+            b0 |= (idx & 1u) << (4 * j + r);
+            b1 |= (idx >> 1) << (4 * j + r);
+        }
+    }
+    const int u = o >> 1;
+    const int pos = grouped_unit_pos(u >> 3, u & 7, NG);
+    packed[static_cast<size_t>(g4) * cells + 2 * pos + (o & 1)] = make_uint2(b0, b1);
+}
+
+__global__ __launch_bounds__(PACK_THREADS) void unpack_grouped_kernel(const uint2* __restrict__ packed, int N, int K,
+                                                                      uint8_t* __restrict__ idx)
+{
+    const int g4 = blockIdx.y;
+    const int cells = K / 8;
+    const int o = blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (o >= cells) return;
+    const int u = o >> 1;
+    const int pos = grouped_unit_pos(u >> 3, u & 7, K / GROUP);
+    const uint2 c = packed[static_cast<size_t>(g4) * cells + 2 * pos + (o & 1)];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        uint32_t lo4 = 0, hi4 = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t v = ((c.x >> (4 * j + r)) & 1u) | (((c.y >> (4 * j + r)) & 1u) << 1);
+            if (j < 4) lo4 |= v << (8 * j);
+            else hi4 |= v << (8 * (j - 4));
+        }
+        *reinterpret_cast<uint2*>(idx + static_cast<size_t>(4 * g4 + r) * K + static_cast<size_t>(o) * 8) =
+            make_uint2(lo4, hi4);
+    }
+}
+
+int launch_pack_grouped(const void* W, rcp_dtype dt, int N, int K, const float* lo, const float* hi,
+                        const float* part, void* packed, void* codebook, hipStream_t st)
+{
+    if (N / 4 > 65535) return fail(RCP_ERR_SHAPE, "rcp_pack_weights_grouped: N=%d exceeds 262140", N);
+    dim3 grid((K / 8 + PACK_THREADS - 1) / PACK_THREADS, N / 4);
+    auto* pk = static_cast<uint2*>(packed);
+    auto* cb = static_cast<uint16_t*>(codebook);
+    switch (dt) {
+        case RCP_F16: pack_grouped_kernel<RCP_F16><<<grid, PACK_THREADS, 0, st>>>(W, N, K, lo, hi, part, pk, cb); break;
+        case RCP_F32: pack_grouped_kernel<RCP_F32><<<grid, PACK_THREADS, 0, st>>>(W, N, K, lo, hi, part, pk, cb); break;
+        default: pack_grouped_kernel<RCP_BF16><<<grid, PACK_THREADS, 0, st>>>(W, N, K, lo, hi, part, pk, cb); break;
+    }
+    return check_launch("rcp_pack_weights_grouped");
+}
+
+int launch_unpack_grouped(const void* packed, int N, int K, uint8_t* idx, hipStream_t st)
+{
+    if (N / 4 > 65535) return fail(RCP_ERR_SHAPE, "rcp_unpack_indices_grouped: N=%d exceeds 262140", N);
+    dim3 grid((K / 8 + PACK_THREADS - 1) / PACK_THREADS, N / 4);
+    unpack_grouped_kernel<<<grid, PACK_THREADS, 0, st>>>(static_cast<const uint2*>(packed), N, K, idx);
+    return check_launch("rcp_unpack_indices_grouped");
+}
+
 }  // namespace rcp

@@ -29,6 +29,12 @@ int num_compute_units();
 int launch_pack(const void* W, rcp_dtype dt, int N, int K, const float* lo, const float* hi,
                 const float* part, void* packed, void* codebook, hipStream_t st);
 int launch_unpack(const void* packed, int N, int K, uint8_t* idx, hipStream_t st);
+// group-wise quantisation units (128 input channels per LUT)
+int launch_pack_grouped(const void* W, rcp_dtype dt, int N, int K, const float* lo, const float* hi,
+                        const float* part, void* packed, void* codebook, hipStream_t st);
+int launch_unpack_grouped(const void* packed, int N, int K, uint8_t* idx, hipStream_t st);
+int launch_gemv_grouped(const void* packed, const void* codebook, int N, int K, const void* xq,
+                        const void* scale, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 
 size_t act_workspace_bytes(int M, int K, const rcp_rotation* rot);
 int launch_act(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float clip_ratio,
@@ -121,6 +127,48 @@ __device__ __forceinline__ float wave_max(float v)
     const int b = __float_as_int(v);
     return fmaxf(fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 0)), __int_as_float(__builtin_amdgcn_readlane(b, 16))),
                  fmaxf(__int_as_float(__builtin_amdgcn_readlane(b, 32)), __int_as_float(__builtin_amdgcn_readlane(b, 48))));
+}
+
+// ---- packed-int4 dot product and two-register folds (GEMV kernels) ---------------------------
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int dot8(uint32_t a, uint32_t b, int c)
+{
+    return __builtin_amdgcn_sdot8(static_cast<int>(a), static_cast<int>(b), c, false);
+}
+
+// Adds the upper 32 lanes of a and b onto their lower 32: lanes 0..31 get a + a(lane^32),
+// lanes 32..63 get b + b(lane^32)  (v_permlane32_swap folds two registers into one).
+__device__ __forceinline__ int fold32(int a, int b)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
+    return static_cast<int>(r[0]) + static_cast<int>(r[1]);
+}
+
+// Same for neighbouring 16-lane rows: even rows get a + a(row^1), odd rows b + b(row^1).
+__device__ __forceinline__ int fold16(int a, int b)
+{
+    auto r = __builtin_amdgcn_permlane16_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
+    return static_cast<int>(r[0]) + static_cast<int>(r[1]);
+}
+
+// One cell (4 rows x 8 columns, bit planes b0 and b1) against the matching int4 dword of MT tokens.
+// acc[p][m]: plane p in {b0, b1, b0&b1}, nibble mask m in {1, 3, 7, F}
+template <int MT>
+__device__ __forceinline__ void cell_update(uint32_t b0, uint32_t b1, const uint32_t (&x)[MT], int (&acc)[MT][3][4])
+{
+    const uint32_t pl[3] = {b0, b1, b0 & b1};
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        const uint32_t m1 = pl[p] & 0x11111111u, m3 = pl[p] & 0x33333333u, m7 = pl[p] & 0x77777777u;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            acc[t][p][0] = dot8(x[t], m1, acc[t][p][0]);
+            acc[t][p][1] = dot8(x[t], m3, acc[t][p][1]);
+            acc[t][p][2] = dot8(x[t], m7, acc[t][p][2]);
+            acc[t][p][3] = dot8(x[t], pl[p], acc[t][p][3]);
+        }
+    }
 }
 
 // ---- the int4 quantiser (shared by the activation kernels and the fused GEMV prologue) ----

@@ -101,3 +101,15 @@ def linear_layer(seed: int, name: str, N: int, K: int):
     W = weights(seed, name, N, K)
     lo, hi = clip_range(W)
     return W, lo, hi, partitions(seed, name, N)
+
+
+def linear_layer_grouped(seed: int, name: str, N: int, K: int, group: int = 128):
+    """Offline inputs of one linear layer quantised in groups of `group` input channels:
+    (W fp16, lo [N, K/group], hi [N, K/group], part [N, K/group, 3]); 2 % / 98 % quantiles per group."""
+    W = weights(seed, name, N, K)
+    NG = K // group
+    Wg = W.astype(np.float32).reshape(N, NG, group)
+    lo = np.quantile(Wg, 0.02, axis=2).astype(np.float32)
+    hi = np.quantile(Wg, 0.98, axis=2).astype(np.float32)
+    part = partitions(seed, name + ":grouped", N * NG).reshape(N, NG, 3)
+    return W, np.ascontiguousarray(lo), np.ascontiguousarray(hi), np.ascontiguousarray(part)

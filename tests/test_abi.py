@@ -29,7 +29,8 @@ def test_every_declared_function_is_exported(lib):
     names = _declared_functions()
     assert {"rcp_pack_weights", "rcp_rotate_quant_act", "rcp_w2a4_gemv", "rcp_unpack_indices",
             "rcp_packed_bytes", "rcp_act_workspace_bytes", "rcp_last_error", "rcp_version",
-            "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act", "rcp_stream_read"} <= set(names)
+            "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act", "rcp_stream_read",
+            "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -76,6 +77,23 @@ def test_argument_errors_need_no_gpu(lib):
     assert act(fake, 0, 1, 96, ctypes.byref(Rot(2, 32, 3, fake)), 1.0, fake, fake, None, 0, None) == -5
     assert b"workspace" in lib.rcp_last_error()
     assert act(fake, 0, 1, 64, ctypes.byref(Rot(9, 0, 0, None)), 1.0, fake, fake, None, 0, None) == -4
+    ci = ctypes.c_int
+    gg = lib.rcp_w2a4_gemv_grouped
+    gg.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, ci, vp, vp]
+    assert gg(fake, fake, 8, 256, 128, fake, None, fake, 0, None, None) == -1
+    assert gg(fake, fake, 8, 256, 64, fake, fake, fake, 0, None, None) == -4     # group size other than 128
+    assert b"128" in lib.rcp_last_error()
+    assert gg(fake, fake, 8, 160, 128, fake, fake, fake, 0, None, None) == -2    # K not a multiple of the group
+    assert gg(fake, fake, 6, 256, 128, fake, fake, fake, 0, None, None) == -2
+    assert gg(fake, fake, 8, 256, 128, odd, fake, fake, 0, None, None) == -3
+    pg = lib.rcp_pack_weights_grouped
+    pg.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+    assert pg(fake, 0, 8, 256, 128, fake, None, fake, fake, fake, None) == -1
+    assert pg(fake, 0, 8, 256, 32, fake, fake, fake, fake, fake, None) == -4
+    assert pg(fake, 5, 8, 256, 128, fake, fake, fake, fake, fake, None) == -4
+    ug = lib.rcp_unpack_indices_grouped
+    ug.argtypes = [vp, ci, ci, ci, vp, vp]
+    assert ug(fake, 8, 96, 128, fake, None) == -2
     lib.rcp_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
     assert lib.rcp_set_option(b"gemv_lanes", 48) == -4
     assert lib.rcp_set_option(b"nonsense", 1) == -4

@@ -80,6 +80,113 @@ def test_pack_grid_edge_values():
 
 
 # ------------------------------------------------------------------------------------------
+# group-wise quantisation units (128 input channels per LUT)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("N,K,dtype", [(8, 128, "f16"), (12, 256, "f32"), (64, 4096, "f16"), (36, 4224, "bf16"),
+                                       (16, 11008, "f16"), (8, 14336, "f16"), (4, 32768, "f16")])
+def test_grouped_pack_bit_exact(N, K, dtype):
+    _say(f"grouped pack N={N} K={K} {dtype}")
+    W, lo, hi, part = rcp_synth.linear_layer_grouped(3, f"gpack{N}x{K}", N, K)
+    if dtype == "f16":
+        Wd, W32 = _t(W), W.astype(np.float32)
+    elif dtype == "f32":
+        W32 = (W.astype(np.float32) * np.float32(1.0009765))
+        Wd = _t(W32)
+    else:
+        Wd = _t(W.astype(np.float32)).to(torch.bfloat16)
+        W32 = Wd.to(torch.float32).cpu().numpy()
+    packed, cb = rcp.pack_weights_grouped(Wd, _t(lo), _t(hi), _t(part))
+    idx = rcp.unpack_indices_grouped(packed, N, K)
+    torch.cuda.synchronize()
+    ref_packed, ref_cb, ref_idx = oracle.pack_weights_grouped(W32, lo, hi, part, want_idx=True)
+    assert np.array_equal(cb.cpu().numpy().view(np.uint16).ravel(), ref_cb)
+    assert np.array_equal(packed.cpu().numpy(), ref_packed)
+    assert np.array_equal(idx.cpu().numpy(), ref_idx)
+
+
+def _grouped_gemv_case(seed, N, K):
+    NG = K // 128
+    idx = rcp_synth.random_indices(seed, f"ggemv{N}x{K}", N, K)
+    q = rcp_synth.random_int4(seed, f"ggemv{K}", 1, K)
+    rng = np.random.default_rng(seed)
+    # levels in the grouped layout [N/4][NG][4 rows][4], ascending per (row, group)
+    cb = np.sort(rng.standard_normal((N // 4, NG, 4, 4)) * 0.03, axis=3).astype(np.float16).view(np.uint16)
+    sc = (np.abs(rng.standard_normal(1)) * 0.2 + 0.05).astype(np.float16).view(np.uint16)
+    xq = ((q[:, 0::2].astype(np.uint8) & 0xF) | ((q[:, 1::2].astype(np.uint8) & 0xF) << 4)).astype(np.uint8)
+    return oracle.pack_indices_grouped(idx), cb, xq, sc
+
+
+def _check_grouped_gemv(packed, cb, N, K, xq, sc, out_dtype):
+    NG = K // 128
+    ref_O, ref_P = oracle.w2a4_gemv_grouped(packed, cb.ravel(), N, K, xq, sc)
+    out, P = rcp.w2a4_gemv_grouped(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)),
+                                   out_dtype=out_dtype, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P), "per-group partial sums are not bit-exact"
+    got = out.cpu().numpy().astype(np.float64).ravel()
+    lut = np.abs(_f16(cb)).reshape(N // 4, NG, 4, 4).transpose(0, 2, 1, 3).reshape(N, NG, 4)
+    cond = _f16(sc)[0] * (lut * np.abs(ref_P)).sum(axis=(1, 2))
+    half = 2.0 ** -11 * np.abs(ref_O) if out_dtype == torch.float16 else 0.0
+    assert np.all(np.abs(got - ref_O) <= 1e-3 * cond + half + 1e-30)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O) + 1e-30
+    out2 = rcp.w2a4_gemv_grouped(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)),
+                                 out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("blocks", [0, 1, 5])
+@pytest.mark.parametrize("N,K", [(4, 128), (8, 256), (36, 4096), (1028, 4096), (72, 11008), (40, 14336), (20, 4224),
+                                 (12, 32768)])
+def test_grouped_gemv_partial_sums_bit_exact_and_output_close(N, K, blocks):
+    _say(f"grouped gemv N={N} K={K} blocks={blocks}")
+    rcp.set_option("gemv_blocks", blocks)
+    packed, cb, xq, sc = _grouped_gemv_case(21, N, K)
+    _check_grouped_gemv(packed, cb, N, K, xq, sc, torch.float32 if blocks else torch.float16)
+
+
+def test_grouped_gemv_extreme_activations_and_integer_levels():
+    """q = -8 everywhere (largest magnitude sums) and integer levels: the output is an exact integer."""
+    N, K = 24, 11008
+    NG = K // 128
+    idx = rcp_synth.random_indices(22, "gext", N, K)
+    packed = oracle.pack_indices_grouped(idx)
+    xq = np.full((1, K // 2), 0x88, np.uint8)
+    rng = np.random.default_rng(22)
+    cb = np.sort(rng.integers(-3, 4, size=(N // 4, NG, 4, 4)), axis=3).astype(np.float16).view(np.uint16)
+    sc = np.array([1.0], np.float16).view(np.uint16)
+    ref_O, ref_P = oracle.w2a4_gemv_grouped(packed, cb.ravel(), N, K, xq, sc)
+    out, P = rcp.w2a4_gemv_grouped(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)),
+                                   out_dtype=torch.float32, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64).ravel(), ref_O)
+
+
+@pytest.mark.parametrize("N,K", [(64, 4096), (32, 11008)])
+def test_grouped_whole_path(N, K):
+    """export -> quantise -> grouped GEMV against the oracle doing the same from the same inputs."""
+    _say(f"grouped whole path N={N} K={K}")
+    W, lo, hi, part = rcp_synth.linear_layer_grouped(4, f"gwhole{N}x{K}", N, K)
+    x = rcp_synth.activation(4, f"gwhole{K}", 1, K)
+    packed, cb = rcp.pack_weights_grouped(_t(W), _t(lo), _t(hi), _t(part))
+    xq, sc = rcp.rotate_quant_act(_t(x))
+    out, P = rcp.w2a4_gemv_grouped(packed, cb, N, K, xq, sc, out_dtype=torch.float32, want_partial_sums=True)
+    torch.cuda.synchronize()
+    ref_packed, ref_cb = oracle.pack_weights_grouped(W.astype(np.float32), lo, hi, part)
+    ref_xq, ref_sc, _ = oracle.quantize_act(x.astype(np.float32))
+    assert np.array_equal(xq.cpu().numpy(), ref_xq) and np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    ref_O, ref_P = oracle.w2a4_gemv_grouped(ref_packed, ref_cb, N, K, ref_xq, ref_sc)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64).ravel()
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
+    # and close to the unquantised product in the sense the 2-bit grid allows
+    exact = W.astype(np.float64) @ x.astype(np.float64).ravel()
+    cos = float(got @ exact / (np.linalg.norm(got) * np.linalg.norm(exact)))
+    assert cos > 0.7
+
+
+# ------------------------------------------------------------------------------------------
 # GEMV
 # ------------------------------------------------------------------------------------------
 def _gemv_case(seed, N, K, M):
