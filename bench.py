@@ -315,6 +315,33 @@ def main():
                                 "tokens_per_s": round(M / s, 1)}
         del xm, xqm, scm, outm, wsm
 
+    # group-wise LUTs (128 input channels per LUT, the paper's deployed setting): the grouped GEMV
+    # on the same shapes, cold over L different buffers; indices and levels are random (the
+    # kernel's time does not depend on their values), activations quantised by a separate launch
+    grouped = {}
+    for label, i, N in side_shapes:
+        K = launches[i][2]
+        NG = K // rcp.GROUP
+        rot = rot_down if launches[i][3] else None
+        rcp.rotate_quant_act(xs[i], rot, 1.0, xq_out=xqs[i], scale_out=scs[i], workspace=ws if rot else None)
+        bufs = []
+        for l in range(L):
+            pk = torch.randint(0, 256, (N * K // 4,), dtype=torch.uint8, device=dev)
+            lv = (torch.randn((N // 4, NG, 4, 4), device=dev) * 0.03).sort(dim=3).values.to(torch.float16).contiguous()
+            bufs.append((pk, lv))
+        og = torch.empty((1, N), dtype=torch.float16, device=dev)
+
+        def gsweep(i=i, N=N, K=K, bufs=bufs, og=og):
+            for pk, lv in bufs:
+                rcp.w2a4_gemv_grouped(pk, lv, N, K, xqs[i], scs[i], out=og)
+        gsweep()
+        fn = capture(gsweep)
+        fn()
+        s = timed(torch, fn, reps) / L
+        b = N * K // 4 + 8 * N * NG + K // 2 + 2 + 2 * N
+        grouped[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1), "bytes": b}
+        del bufs, og
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
     if os.path.exists(tpath):
@@ -347,6 +374,7 @@ def main():
         "gemv_only_GBps": round(step_bytes / sec_gemv_sweep / 1e9, 1),
         "per_shape": per_shape,
         "small_batch": small_batch,
+        "grouped_128": grouped,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),
