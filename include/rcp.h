@@ -127,7 +127,8 @@ int rcp_version(void);
  *   "gemv_lanes"   lanes that share one group of four rows: 16, 32, 64, 128, 256
  *   "gemv_unroll"  16-byte loads per lane and pipeline stage: 2, 4
  *   "gemv_blocks"  number of workgroups the GEMV launches
- *   "gemv_variant" kernel variant (0 = automatic)
+ *   "gemv_variant" 1 = plain-ALU kernel for every M, 2 = matrix-core kernel for every M
+ *   "gemm_waves"   wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */
 int rcp_set_option(const char* name, int value);
 

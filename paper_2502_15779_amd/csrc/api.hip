@@ -28,7 +28,7 @@ int check_launch(const char* what)
 
 Options& options()
 {
-    static Options o = {0, 0, 0, 0};
+    static Options o = {0, 0, 0, 0, 0};
     return o;
 }
 
@@ -127,8 +127,12 @@ int rcp_set_option(const char* name, int value)
         if (value < 0 || value > (1 << 20)) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_blocks out of range");
         o.gemv_blocks = value;
     } else if (strcmp(name, "gemv_variant") == 0) {
-        if (value < 0 || value > 8) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_variant out of range");
+        if (value < 0 || value > 2) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_variant must be 0, 1 or 2");
         o.gemv_variant = value;
+    } else if (strcmp(name, "gemm_waves") == 0) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_waves must be 0, 1, 2, 4 or 8");
+        o.gemm_waves = value;
     } else
         return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: unknown option '%s'", name);
     return RCP_OK;

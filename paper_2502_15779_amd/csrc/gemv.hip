@@ -373,6 +373,8 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
     }
 }
 
+constexpr int GEMM_MFMA_MIN_M = 4;  // fewer tokens stay on the plain-ALU kernel
+
 struct GemvPlan {
     int lw, ws, unr, blocks;
 };
@@ -472,6 +474,10 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
 {
     if (static_cast<long long>(a.N) * a.K / 4 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(a.N) * a.K / 4);
+    // several tokens: the contraction goes to the matrix cores (the fused quantiser is one token only)
+    const int variant = options().gemv_variant;
+    if (a.xraw == nullptr && variant != 1 && (variant == 2 || a.M >= GEMM_MFMA_MIN_M))
+        return launch_gemm_mfma(a.packed, a.codebook, a.N, a.K, a.xq, a.scale, a.M, a.out, a.out_dt, a.P, st);
     const GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
     if (p.unr == 2) {
         switch (p.lw * p.ws) {

@@ -20,7 +20,8 @@ struct Options {
     int gemv_lanes;      // lanes that share one group of four rows: 16 .. 256
     int gemv_unroll;     // 16-byte loads per lane and pipeline stage: 2 or 4
     int gemv_blocks;     // workgroups launched by the GEMV
-    int gemv_variant;    // kernel variant selector
+    int gemv_variant;    // 0 automatic, 1 plain-ALU kernel for every M, 2 matrix-core kernel for every M
+    int gemm_waves;      // wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
 };
 Options& options();
 int num_compute_units();
@@ -45,6 +46,9 @@ int launch_rotate(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation*
 
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
+// matrix-core kernel for several tokens (gemm_mfma.hip)
+int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
+                     int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 // fused quantise + GEMV for one token; x is the raw activation, xq_out / scale_out optional
 int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
                       float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,

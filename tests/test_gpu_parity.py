@@ -31,7 +31,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves"):
         rcp.set_option(k, 0)
 
 
@@ -259,13 +259,47 @@ def test_gemv_extreme_activations_and_integer_codebook():
     assert ref_P[0, 0, 3] == -8 * K
 
 
+@pytest.mark.parametrize("variant", [0, 1, 2])
 @pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 16])
 @pytest.mark.parametrize("N,K", [(256, 512), (44, 2080), (256, 4096), (32, 11008)])
-def test_small_batch_matches_oracle(N, K, M):
-    _say(f"skinny gemm N={N} K={K} M={M}")
+def test_small_batch_matches_oracle(N, K, M, variant):
+    """variant 1: plain-ALU kernel, 2: matrix-core kernel, 0: the library's own choice."""
+    _say(f"skinny gemm N={N} K={K} M={M} variant={variant}")
+    rcp.set_option("gemv_variant", variant)
     packed, cb, xq, sc = _gemv_case(M * 1000 + N, N, K, M)
     _check_gemv(packed, cb, N, K, xq, sc, M, torch.float32)
     _check_gemv(packed, cb, N, K, xq, sc, M, torch.float16)
+
+
+@pytest.mark.parametrize("waves", [1, 2, 4, 8])
+@pytest.mark.parametrize("N,K,M", [(4, 32, 1), (68, 96, 5), (1028, 4096, 16), (132, 14336, 9), (64, 32768, 16), (200, 160, 2)])
+def test_matrix_core_kernel_shapes_and_workgroup_sizes(N, K, M, waves):
+    """Ragged N (not a multiple of 64), K not a multiple of 128, fewer K steps than wavefronts, M = 1."""
+    _say(f"mfma gemm N={N} K={K} M={M} waves={waves}")
+    rcp.set_option("gemv_variant", 2)
+    rcp.set_option("gemm_waves", waves)
+    packed, cb, xq, sc = _gemv_case(77 + M, N, K, M)
+    _check_gemv(packed, cb, N, K, xq, sc, M, torch.float32)
+
+
+def test_matrix_core_kernel_extreme_activations():
+    """q = -8 everywhere and q = 7 everywhere: the largest sums the fp32 accumulators must hold exactly."""
+    N, K, M = 64, 32768, 16
+    rcp.set_option("gemv_variant", 2)
+    idx = rcp_synth.random_indices(31, "mfma_ext", N, K)
+    packed = oracle.pack_indices(idx)
+    xq = np.empty((M, K // 2), np.uint8)
+    xq[0::2] = 0x88
+    xq[1::2] = 0x77
+    rng = np.random.default_rng(31)
+    cb = np.sort(rng.integers(-3, 4, size=(N, 4)), axis=1).astype(np.float16).view(np.uint16)
+    sc = np.full(M, 1.0, np.float16).view(np.uint16)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, xq, sc, M)
+    out, P = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)), M,
+                           out_dtype=torch.float32, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), ref_O)
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
