@@ -9,12 +9,14 @@
 // holds one column of four rows; masked down to one bit it is, read as an FP4 (E2M1) number,
 //     bit 0 -> 0.5,  bit 1 -> 1.0,  bit 2 -> 2.0   (bit 3 is the sign: it is shifted to bit 2)
 // so a plane word ANDed with 0x1111.., 0x2222.., 0x4444.. is the A operand of
-// v_mfma_scale_f32_16x16x128_f8f6f4 for rows r = 0, 1, 2 (and (w >> 1) & 0x4444.. for r = 3)
-// without any expansion; the per-lane E8M0 scale of the instruction (2^1, 2^0, 2^-1) turns the
-// 0.5 / 1 / 2 back into 1.  The int4 activation q = 4*hi + lo, lo in {0..3}, hi in {-2..1}, is
-// recoded into two FP4 operands (lo, and hi with scale 2^2); both accumulate into the same
-// registers.  Every product and every sum is a small integer, so the fp32 accumulators hold
-// the exact integer F_p (|F_p| <= 8K < 2^24) and the per-level sums stay bit-exact.
+// v_mfma_f32_16x16x128_f8f6f4 for rows r = 0, 1, 2 (and (w >> 1) & 0x4444.. for r = 3) without
+// any expansion; the factors 0.5 / 1 / 2 are taken out again when the sums leave the registers.
+// The int4 activation q = 4*hi + lo, lo in {0..3}, hi in {-2..1}, is recoded into two FP4
+// operands.  Up to 8 tokens they share one B operand (columns 0..7 carry lo, columns 8..15 hi of
+// the same tokens); beyond that lo and hi are two B operands, hi weighted by the instruction's
+// per-lane E8M0 scale (2^2), accumulating into the same registers.
+// Every product and every sum is a small multiple of 1/2, so the fp32 accumulators are exact
+// (|F_p| <= 8K < 2^24) and the per-level sums stay bit-exact.
 //
 // Work decomposition.  A workgroup owns 16 groups of four rows (64 output rows): lane l of a
 // wavefront supplies row group l%16 and the 32 columns of K-block l/16 of a 128-column step
@@ -26,10 +28,11 @@
 namespace rcp {
 
 constexpr int MM_MAX_THREADS = 512;
-constexpr int MM_PF = 4;            // K steps in flight per wavefront
+constexpr int MM_NS = 2;             // K steps per pipeline stage
 constexpr int MM_STRIDE = 65;       // LDS row stride (ints): conflict-free for both phases
 constexpr int MM_PLANE = 16 * MM_STRIDE;
-constexpr int MM_LDS_INTS = 3 * MM_PLANE + 16;
+constexpr int MM_SUMS = 3 * MM_PLANE + 16;          // ints that are accumulated into (zeroed first)
+constexpr int MM_LDS_INTS = MM_SUMS + 2 * 64 + 16;  // + the 64 LUT rows of the block and the scales
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -54,14 +57,15 @@ __device__ __forceinline__ uint32_t fp4_hi(uint32_t x)
     return n3 | ((n3 >> 1) & ~n2) | (n2 >> 1);
 }
 
-template <bool OUT_F16>
+// PACKED: M <= 8, lo and hi of token n in columns n and n + 8 of one B operand.
+template <bool OUT_F16, bool PACKED>
 __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* __restrict__ packed,
                                                                    const uint2* __restrict__ codebook, int N, int K,
                                                                    const uint4* __restrict__ xq,
                                                                    const uint16_t* __restrict__ scale, int M,
                                                                    void* __restrict__ out, int32_t* __restrict__ Pout)
 {
-    __shared__ int red[MM_LDS_INTS];  // F sums [plane][token][row of the block], then T[token]
+    __shared__ int red[MM_LDS_INTS];  // F sums [plane][token][row of the block], T[token]; LUT rows, scales
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     const int KS = (K + 127) >> 7;  // steps of 128 columns
     const int rg = blockIdx.x * 16 + i;
 
-    for (int j = tid; j < MM_LDS_INTS; j += blockDim.x) red[j] = 0;
+    for (int j = tid; j < MM_SUMS; j += blockDim.x) red[j] = 0;
 
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
@@ -79,9 +83,12 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     const __amdgpu_buffer_rsrc_t xres =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(xq), 0, M * (K / 2), 0x00020000);
     const unsigned wbase = rg < G ? (static_cast<unsigned>(rg) * U + 2u * kb) * 16u : 0x80000000u;
-    const unsigned xbase = static_cast<unsigned>(i) * (K / 2) + kb * 16u;
+    const int token = PACKED ? (i & 7) : i;  // the token whose activations this lane feeds into B
+    const bool hi_lane = PACKED && i >= 8;
+    const unsigned xbase = static_cast<unsigned>(token) * (K / 2) + kb * 16u;
 
-    auto load = [&](int s, MmStage& st) {
+    auto load = [&](int step_index, MmStage& st) {
+        const int s = __builtin_amdgcn_readfirstlane(step_index);  // the same for the whole wavefront: scalar offsets
         const bool ok = 8 * s + 2 * kb < U;  // false for the K tail and for steps past the end
         const unsigned wo = ok ? wbase : 0x80000000u;
         const unsigned xo = ok ? xbase : 0x80000000u;
@@ -90,11 +97,19 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
         st.xq = __builtin_amdgcn_raw_buffer_load_b128(xres, static_cast<int>(xo), s * 64, 0);
     };
 
-    MmStage st[MM_PF];
+    // Two register sets of MM_NS steps each alternate: one is in flight while the other is computed.
+    MmStage sA[MM_NS], sB[MM_NS];
+    int s = wave;  // this wavefront's current step; the launcher guarantees wave < KS
 #pragma unroll
-    for (int j = 0; j < MM_PF; ++j) load(wave + j * W, st[j]);
+    for (int j = 0; j < MM_NS; ++j) load(s + j * W, sA[j]);
+    // what the epilogue needs from memory is fetched now and parked in LDS after the loop
+    uint2 lut_pre = make_uint2(0u, 0u);
+    uint32_t scale_pre = 0;
+    if (tid < 64) lut_pre = codebook[min(static_cast<int>(blockIdx.x) * 64 + tid, N - 1)];
+    if (tid < M) scale_pre = scale[tid];
     __syncthreads();  // LDS is zero before anyone adds to it
 
+    constexpr int NB = PACKED ? 1 : 2;  // B operands per A operand
     v4f acc[3][4];
 #pragma unroll
     for (int p = 0; p < 3; ++p)
@@ -102,64 +117,105 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
         for (int r = 0; r < 4; ++r) acc[p][r] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
     int tsum = 0;
 
-    // E8M0 scales (byte 0 is used): 2^1, 2^0, 2^-1 undo the 0.5 / 1 / 2 of the masked nibbles;
-    // 2^2 weighs the high part of the activation
-    constexpr int SC_A[4] = {0x80, 0x7f, 0x7e, 0x7e};
-    constexpr int SC_LO = 0x7f, SC_HI = 0x81;
-
-    for (int s0 = wave; s0 < KS; s0 += MM_PF * W) {
+    auto compute = [&](const MmStage& cur) {
+        const uint32_t xw[4] = {cur.xq.x, cur.xq.y, cur.xq.z, cur.xq.w};
+        v8i bop[NB];
 #pragma unroll
-        for (int j = 0; j < MM_PF; ++j) {
-            const int s = s0 + j * W;
-            if (s < KS) {  // uniform per wavefront
-            const MmStage cur = st[j];
-            load(s + MM_PF * W, st[j]);
-
-            const uint32_t xw[4] = {cur.xq.x, cur.xq.y, cur.xq.z, cur.xq.w};
-            v8i blo = {0, 0, 0, 0, 0, 0, 0, 0}, bhi = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int h = 0; h < NB; ++h) bop[h] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = fp4_lo(xw[d]), hi = fp4_hi(xw[d]);
+            if constexpr (PACKED) {
+                bop[0][d] = static_cast<int>(hi_lane ? hi : lo);
+            } else {
+                bop[0][d] = static_cast<int>(lo);
+                bop[1][d] = static_cast<int>(hi);
+            }
+            tsum = dot8(xw[d], 0x11111111u, tsum);
+        }
+        const uint32_t p0[4] = {cur.wa.x, cur.wa.z, cur.wb.x, cur.wb.z};
+        const uint32_t p1[4] = {cur.wa.y, cur.wa.w, cur.wb.y, cur.wb.w};
+        // plane by plane, so that only two sets of masks are alive at a time
+        v8i a[3][4];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) a[p][r] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                blo[d] = static_cast<int>(fp4_lo(xw[d]));
-                bhi[d] = static_cast<int>(fp4_hi(xw[d]));
-                tsum = dot8(xw[d], 0x11111111u, tsum);
-            }
-            const uint32_t p0[4] = {cur.wa.x, cur.wa.z, cur.wb.x, cur.wb.z};
-            const uint32_t p1[4] = {cur.wa.y, cur.wa.w, cur.wb.y, cur.wb.w};
+                if (p < 2) {
+                    const uint32_t w = p == 0 ? p0[d] : p1[d];
+                    a[p][0][d] = static_cast<int>(w & 0x11111111u);
+                    a[p][1][d] = static_cast<int>(w & 0x22222222u);
+                    a[p][2][d] = static_cast<int>(w & 0x44444444u);
+                    a[p][3][d] = static_cast<int>((w >> 1) & 0x44444444u);
+                } else {
 #pragma unroll
-            for (int p = 0; p < 3; ++p) {
-                v8i a[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) a[r] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const uint32_t w = p == 0 ? p0[d] : p == 1 ? p1[d] : (p0[d] & p1[d]);
-                    a[0][d] = static_cast<int>(w & 0x11111111u);
-                    a[1][d] = static_cast<int>(w & 0x22222222u);
-                    a[2][d] = static_cast<int>(w & 0x44444444u);
-                    a[3][d] = static_cast<int>((w >> 1) & 0x44444444u);
+                    for (int r = 0; r < 4; ++r) a[2][r][d] = a[0][r][d] & a[1][r][d];  // the masks of b0 & b1
                 }
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[r], blo, acc[p][r], 4, 4, 0, SC_A[r], 0, SC_LO);
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[r], bhi, acc[p][r], 4, 4, 0, SC_A[r], 0, SC_HI);
             }
+            if constexpr (PACKED) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[0], acc[p][r], 4, 4, 0, 0, 0, 0);
+            } else {
+                // E8M0 scales (byte 0): 2^0 for A and lo, 2^2 for hi
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[0], acc[p][r], 4, 4, 0, 0x7f, 0, 0x7f);
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[1], acc[p][r], 4, 4, 0, 0x7f, 0, 0x81);
             }
         }
+    };
+    // Steps past the end of K read zeros (no traffic) and add zeros.
+    auto stage = [&](const MmStage (&cur)[MM_NS], MmStage (&next)[MM_NS]) {
+#pragma unroll
+        for (int j = 0; j < MM_NS; ++j) load(s + (MM_NS + j) * W, next[j]);
+        // nothing that needs `cur` may move above the loads just issued
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < MM_NS; ++j) compute(cur[j]);
+        s += MM_NS * W;
+    };
+    while (true) {
+        stage(sA, sB);
+        if (s >= KS) break;
+        stage(sB, sA);
+        if (s >= KS) break;
     }
+    // The last stage loaded (zeros, past the end of K) is "used" here on purpose: without a use
+    // on the exit path the optimiser sinks each stage's loads below the exit test, next to their
+    // use in the following stage, and the loop is no longer pipelined.
+    uint32_t keep = 0;
+#pragma unroll
+    for (int j = 0; j < MM_NS; ++j) keep |= sA[j].wa.x | sA[j].wb.x | sA[j].xq.x | sB[j].wa.x | sB[j].wb.x | sB[j].xq.x;
+    if (__builtin_expect(K < 0, 0)) red[0] = static_cast<int>(keep);  // never true
 
-    // acc[p][r][v] = F_p of row 4*(16*block + 4*kb + v) + r and token i: add over the wavefronts
+    // acc[p][r][v] = 2^(r - 1) (r < 3) or 2 (r = 3) times F_p (packed: its lo or hi part) of row
+    // 4*(16*block + 4*kb + v) + r and this lane's token: rescale, add over the wavefronts (and,
+    // when packed, lo + 4 hi over the two columns of a token).
     {
-        int* dst = red + i * MM_STRIDE + 16 * kb;
+        int* dst = red + token * MM_STRIDE + 16 * kb;
 #pragma unroll
         for (int p = 0; p < 3; ++p)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+            for (int r = 0; r < 4; ++r) {
+                const float unmask = r == 0 ? 2.0f : r == 1 ? 1.0f : 0.5f;
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    atomicAdd(dst + p * MM_PLANE + 4 * v + r, static_cast<int>(acc[p][r][v]));
-        atomicAdd(red + 3 * MM_PLANE + i, tsum);
+                for (int v = 0; v < 4; ++v) {
+                    int f = static_cast<int>(acc[p][r][v] * unmask);
+                    if (hi_lane) f *= 4;
+                    atomicAdd(dst + p * MM_PLANE + 4 * v + r, f);
+                }
+            }
+        if (!hi_lane) atomicAdd(red + 3 * MM_PLANE + token, tsum);
+        if (tid < 64) {
+            red[MM_SUMS + 2 * tid] = static_cast<int>(lut_pre.x);
+            red[MM_SUMS + 2 * tid + 1] = static_cast<int>(lut_pre.y);
+        }
+        if (tid < 16) red[MM_SUMS + 128 + tid] = static_cast<int>(scale_pre);
     }
     __syncthreads();
 
@@ -171,7 +227,7 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
         const int F3 = red[2 * MM_PLANE + n * MM_STRIDE + hh];
         const int T = red[3 * MM_PLANE + n];
         const int P3 = F3, P1 = F0 - F3, P2 = F1 - F3, P0 = T - F0 - F1 + F3;
-        const uint2 lut = codebook[h];
+        const uint2 lut = make_uint2(static_cast<uint32_t>(red[MM_SUMS + 2 * hh]), static_cast<uint32_t>(red[MM_SUMS + 2 * hh + 1]));
         const float c0 = half_bits_to_float(static_cast<uint16_t>(lut.x & 0xffffu));
         const float c1 = half_bits_to_float(static_cast<uint16_t>(lut.x >> 16));
         const float c2 = half_bits_to_float(static_cast<uint16_t>(lut.y & 0xffffu));
@@ -180,7 +236,7 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
         val = fmaf(c1, static_cast<float>(P1), val);
         val = fmaf(c2, static_cast<float>(P2), val);
         val = fmaf(c3, static_cast<float>(P3), val);
-        val *= half_bits_to_float(scale[n]);
+        val *= half_bits_to_float(static_cast<uint16_t>(red[MM_SUMS + 128 + n]));
         const size_t oi = static_cast<size_t>(n) * N + h;
         if constexpr (OUT_F16) static_cast<__half*>(out)[oi] = __float2half_rn(val);
         else static_cast<float*>(out)[oi] = val;
@@ -201,10 +257,14 @@ int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, con
     auto* cb = static_cast<const uint2*>(codebook);
     auto* x4 = static_cast<const uint4*>(xq);
     auto* sc = static_cast<const uint16_t*>(scale);
-    if (out_dt == RCP_F16)
-        gemm_mfma_kernel<true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
-    else
-        gemm_mfma_kernel<false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+    const dim3 grid(blocks), block(waves * 64);
+    if (M <= 8) {
+        if (out_dt == RCP_F16) gemm_mfma_kernel<true, true><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+        else gemm_mfma_kernel<false, true><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+    } else {
+        if (out_dt == RCP_F16) gemm_mfma_kernel<true, false><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+        else gemm_mfma_kernel<false, false><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+    }
     return check_launch("rcp_w2a4_gemv");
 }
 
