@@ -305,12 +305,23 @@ def main():
                     rcp.rotate_quant_act(xm[i], rot, 1.0, xq_out=xqm[i], scale_out=scm[i], workspace=wsm if rot else None)
                     packed, cb = layers[l][i]
                     rcp.w2a4_gemv(packed, cb, N, K, xqm[i], scm[i], M, out=outm[i])
+        def mgemm(M=M, xqm=xqm, scm=scm, outm=outm):
+            for l in range(L):
+                for i in range(4):
+                    _, N, K, _ = launches[i]
+                    packed, cb = layers[l][i]
+                    rcp.w2a4_gemv(packed, cb, N, K, xqm[i], scm[i], M, out=outm[i])
         mstep()
         fn = capture(mstep)
         fn()
         s = timed(torch, fn, max(2, reps // 2))
+        fng = capture(mgemm)
+        fng()
+        sg = timed(torch, fng, max(2, reps // 2))
         macs = M * L * sum(N * K for (_, N, K, _) in launches)
         small_batch[f"M{M}"] = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2),
+                                "gemm_only_us_per_layer": round(sg / L * 1e6, 2),
+                                "gemm_only_GBps": round(L * sum(gemv_bytes(N, K, M) for (_, N, K, _) in launches) / sg / 1e9, 1),
                                 "int4_TMAC_per_s": round(macs / s / 1e12, 2),
                                 "tokens_per_s": round(M / s, 1)}
         del xm, xqm, scm, outm, wsm

@@ -28,7 +28,7 @@
 namespace rcp {
 
 constexpr int MM_MAX_THREADS = 512;
-constexpr int MM_NS = 2;             // K steps per pipeline stage
+constexpr int MM_NS = 1;             // K steps per pipeline stage
 constexpr int MM_STRIDE = 65;       // LDS row stride (ints): conflict-free for both phases
 constexpr int MM_PLANE = 16 * MM_STRIDE;
 constexpr int MM_SUMS = 3 * MM_PLANE + 16;          // ints that are accumulated into (zeroed first)
@@ -249,8 +249,9 @@ int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, con
 {
     const int blocks = (N + 63) / 64;
     const int KS = (K + 127) / 128;
-    // enough wavefronts to occupy the chip: 4 or 8 per workgroup, never more than there are K steps
-    int waves = blocks * 4 >= 4 * num_compute_units() ? 4 : 8;
+    // 8 wavefronts per workgroup share the K steps of a row block (sweeps: 8 with one step per
+    // pipeline stage beats 4 with deeper stages on every LLaMA shape), never more than there are steps
+    int waves = 8;
     if (options().gemm_waves != 0) waves = options().gemm_waves;
     while (waves > 1 && waves > KS) waves /= 2;
     auto* pk = static_cast<const uint4*>(packed);

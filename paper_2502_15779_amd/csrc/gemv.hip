@@ -373,7 +373,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
     }
 }
 
-constexpr int GEMM_MFMA_MIN_M = 4;  // fewer tokens stay on the plain-ALU kernel
+constexpr int GEMM_MFMA_MIN_M = 4;  // fewer tokens always stay on the plain-ALU kernel
 
 struct GemvPlan {
     int lw, ws, unr, blocks;
@@ -476,7 +476,10 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(a.N) * a.K / 4);
     // several tokens: the contraction goes to the matrix cores (the fused quantiser is one token only)
     const int variant = options().gemv_variant;
-    if (a.xraw == nullptr && variant != 1 && (variant == 2 || a.M >= GEMM_MFMA_MIN_M))
+    // (measured crossover on LLaMA-sized layers: 5 tokens, or 4 when the matrix is tall enough to
+    // fill the chip with 64-row blocks)
+    const bool many = a.M > GEMM_MFMA_MIN_M || (a.M == GEMM_MFMA_MIN_M && a.N >= 8192);
+    if (a.xraw == nullptr && variant != 1 && (variant == 2 || many))
         return launch_gemm_mfma(a.packed, a.codebook, a.N, a.K, a.xq, a.scale, a.M, a.out, a.out_dt, a.P, st);
     const GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
     if (p.unr == 2) {
