@@ -167,6 +167,17 @@ def dequant_dot(packed, codebook, N, K, xq, scale_bits, M=1) -> np.ndarray:
     return out
 
 
+def w2a16_gemv(packed, codebook, N, K, x) -> np.ndarray:
+    """Weight-only product: x (M, K) of any float type (taken exactly) -> O float64 (M, N)."""
+    pk, cb = _c(packed, np.uint8), _c(codebook, np.uint16)
+    xc = _c(np.atleast_2d(x), np.float64)
+    M = xc.shape[0]
+    assert pk.size == N * K // 4 and cb.size == 4 * N and xc.shape[1] == K
+    out = np.empty((M, N), dtype=np.float64)
+    _check(lib().rcp_ref_w2a16_gemv(_p(pk), _p(cb), N, K, _p(xc), M, _p(out)), "w2a16_gemv")
+    return out
+
+
 # ---- group-wise quantisation units (group size 128) ----------------------------------------
 def grouped_lut_index(h, g, NG):
     """Half-word index of level 0 of row h, group g in the grouped LUT layout."""

@@ -426,6 +426,29 @@ int rcp_ref_dequant_dot(const uint8_t* packed, const uint16_t* codebook, int N, 
 }
 
 /* ------------------------------------------------------------------------
+ * Weight-only variant (the W2-only decode measurement of the paper's inference-latency
+ * section: non-uniform dequantisation of the weights merged with a 16-bit linear layer):
+ *   O[t][h] = sum_k LUT[h][idx[h][k]] * x[t][k]                   (binary64)
+ * x: M x K doubles holding the exact values of the 16-bit (or 32-bit) activations.
+ * ---------------------------------------------------------------------- */
+int rcp_ref_w2a16_gemv(const uint8_t* packed, const uint16_t* codebook, int N, int K, const double* x, int M,
+                       double* out)
+{
+    if (N < 4 || N % 4 || K < 32 || K % 32 || M < 1) return RCP_REF_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < N; ++h) {
+        double lut[4];
+        for (int l = 0; l < 4; ++l) lut[l] = rcp_ref_f16_bits_to_f64(codebook[4 * (size_t)h + l]);
+        for (int t = 0; t < M; ++t) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) acc += lut[packed_get(packed, h, k, K)] * x[(size_t)t * K + k];
+            out[(size_t)t * N + h] = acc;
+        }
+    }
+    return RCP_REF_OK;
+}
+
+/* ------------------------------------------------------------------------
  * Group-wise quantisation units (Appendix table "Quantization configurations": weights are
  * quantised in groups of 128 input channels; Section 4.4: the LUT is H x N*4 with N groups
  * per channel).  Every (row, group) has its own clip range, partition and 4-entry LUT.
