@@ -225,6 +225,19 @@ int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
                         void* xq_out_or_null, void* scale_out_or_null,
                         int32_t* partial_sums_or_null, void* stream);
 
+/*
+ * Weight-only GEMV (the W2-only decode variant of the paper's inference-latency section:
+ * non-uniform dequantisation merged into a 16-bit linear layer), one token:
+ *     O[h] = sum_k LUT[h][idx[h][k]] * x[k]          (binary32 accumulation)
+ * packed, codebook: as written by rcp_pack_weights.  x: K values of `x_dtype` (fp16 uses the
+ * packed-fp16 dot instruction, bf16 / fp32 are widened to binary32).  out: N values of
+ * `out_dtype` (RCP_F16 or RCP_F32).  K is limited by the activations having to fit in LDS:
+ * K <= RCP_MAX_K for fp16, about 40000 values for the widened types (RCP_ERR_UNSUPPORTED).
+ */
+int rcp_w2a16_gemv(const void* packed, const void* codebook, int N, int K,
+                   const void* x, rcp_dtype x_dtype,
+                   void* out, rcp_dtype out_dtype, void* stream);
+
 /* Measurement helper: read `bytes` (rounded down to 16) of a device buffer once with plain
  * 128-bit loads and discard them.  Timing it on a buffer of a GEMV's size gives the
  * streaming-read ceiling of the machine for a kernel of that size.  sink_or_null: 4 bytes of

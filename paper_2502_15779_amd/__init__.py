@@ -101,6 +101,8 @@ def lib():
         L.rcp_unpack_indices_grouped.argtypes = [vp, ci, ci, ci, vp, vp]
         L.rcp_w2a4_gemv_grouped.restype = ci
         L.rcp_w2a4_gemv_grouped.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, ci, vp, vp]
+        L.rcp_w2a16_gemv.restype = ci
+        L.rcp_w2a16_gemv.argtypes = [vp, vp, ci, ci, vp, ci, vp, ci, vp]
         _lib = L
     return _lib
 
@@ -313,3 +315,18 @@ def w2a4_gemv_grouped(packed, codebook, N, K, xq, scale, group=GROUP, out=None, 
                                        _dev(partial_sums, "partial_sums") if partial_sums is not None else None,
                                        _stream()))
     return (out, partial_sums) if partial_sums is not None else out
+
+
+def w2a16_gemv(packed, codebook, N, K, x, out=None, out_dtype=torch.float16):
+    """Weight-only product for one token: x holds K values (fp16 / bf16 / fp32) -> out [1, N]."""
+    if x.numel() != K or x.dtype not in _DTYPES:
+        raise ValueError("x must hold K values of float16, bfloat16 or float32")
+    if out is None:
+        out = torch.empty((1, N), dtype=out_dtype, device=packed.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < N:
+        raise ValueError("out must be float16 or float32 with N elements")
+    if packed.numel() * packed.element_size() < N * K // 4 or codebook.numel() < 4 * N:
+        raise ValueError("packed / codebook buffers do not match N, K")
+    _check(lib().rcp_w2a16_gemv(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, _dev(x, "x"),
+                                _DTYPES[x.dtype], _dev(out, "out"), _DTYPES[out.dtype], _stream()))
+    return out

@@ -257,6 +257,20 @@ int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K, 
     return launch_gemv(packed, codebook, N, K, xq_out_or_null, scale_out_or_null, 1, out, out_dtype, partial_sums_or_null, st);
 }
 
+int rcp_w2a16_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dtype,
+                   void* out, rcp_dtype out_dtype, void* stream)
+{
+    if (!packed || !codebook || !x || !out) return fail(RCP_ERR_NULL, "rcp_w2a16_gemv: NULL pointer argument");
+    if (int rc = check_shape("rcp_w2a16_gemv", N, K)) return rc;
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a16_gemv: unknown dtype %d", static_cast<int>(x_dtype));
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a16_gemv: out_dtype must be RCP_F16 or RCP_F32");
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(x) || !aligned16(out))
+        return fail(RCP_ERR_ALIGN, "rcp_w2a16_gemv: device buffers must be 16-byte aligned");
+    return launch_w2a16_gemv(packed, codebook, N, K, x, x_dtype, out, out_dtype, static_cast<hipStream_t>(stream));
+}
+
 int rcp_pack_weights_grouped(const void* W, rcp_dtype w_dtype, int N, int K, int group, const float* clip_lo,
                              const float* clip_hi, const float* part, void* packed_out, void* codebook_out,
                              void* stream)

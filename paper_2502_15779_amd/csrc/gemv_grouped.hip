@@ -28,23 +28,6 @@ constexpr int GG_SLOTS = 8;     // row groups a workgroup works on at a time
 constexpr int GG_GROUP = 128;   // input channels per quantisation unit
 constexpr int GG_UNITS = 8;     // 16-byte units per (row group, quantisation group)
 
-__device__ __forceinline__ float fold16f(float a, float b)
-{
-    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-__device__ __forceinline__ float row_sum16f(float v)
-{
-#define RCP_ROW_ADD(ctrl) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, false))
-    RCP_ROW_ADD(0x128);
-    RCP_ROW_ADD(0x124);
-    RCP_ROW_ADD(0x122);
-    RCP_ROW_ADD(0x121);
-#undef RCP_ROW_ADD
-    return v;
-}
-
 struct GroupStep {
     u32x4 w[GG_UNITS];  // the eight units of this lane's group: 4 rows x 128 columns
     u32x4 lut[2];       // levels of rows 0,1 | rows 2,3 (four fp16 each)

@@ -46,6 +46,9 @@ int launch_rotate(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation*
 
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
+// weight-only GEMV: 16- or 32-bit activations, no activation quantiser (w2a16_gemv.hip)
+int launch_w2a16_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                      void* out, rcp_dtype out_dt, hipStream_t st);
 // matrix-core kernel for several tokens (gemm_mfma.hip)
 int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
                      int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
@@ -154,6 +157,30 @@ __device__ __forceinline__ int fold16(int a, int b)
 {
     auto r = __builtin_amdgcn_permlane16_swap(static_cast<unsigned>(a), static_cast<unsigned>(b), false, false);
     return static_cast<int>(r[0]) + static_cast<int>(r[1]);
+}
+
+// The same folds and row sums for binary32 values.
+__device__ __forceinline__ float fold32f(float a, float b)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ float fold16f(float a, float b)
+{
+    auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ __forceinline__ float row_sum16f(float v)
+{
+#define RCP_ROW_ADD(ctrl) v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, false))
+    RCP_ROW_ADD(0x128);
+    RCP_ROW_ADD(0x124);
+    RCP_ROW_ADD(0x122);
+    RCP_ROW_ADD(0x121);
+#undef RCP_ROW_ADD
+    return v;
 }
 
 // One cell (4 rows x 8 columns, bit planes b0 and b1) against the matching int4 dword of MT tokens.

@@ -30,7 +30,8 @@ def test_every_declared_function_is_exported(lib):
     assert {"rcp_pack_weights", "rcp_rotate_quant_act", "rcp_w2a4_gemv", "rcp_unpack_indices",
             "rcp_packed_bytes", "rcp_act_workspace_bytes", "rcp_last_error", "rcp_version",
             "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act", "rcp_stream_read",
-            "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped"} <= set(names)
+            "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped",
+            "rcp_w2a16_gemv"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -86,6 +87,13 @@ def test_argument_errors_need_no_gpu(lib):
     assert gg(fake, fake, 8, 160, 128, fake, fake, fake, 0, None, None) == -2    # K not a multiple of the group
     assert gg(fake, fake, 6, 256, 128, fake, fake, fake, 0, None, None) == -2
     assert gg(fake, fake, 8, 256, 128, odd, fake, fake, 0, None, None) == -3
+    wo = lib.rcp_w2a16_gemv
+    wo.argtypes = [vp, vp, ci, ci, vp, ci, vp, ci, vp]
+    assert wo(fake, fake, 8, 64, None, 0, fake, 0, None) == -1
+    assert wo(fake, fake, 8, 72, fake, 0, fake, 0, None) == -2
+    assert wo(fake, fake, 8, 64, fake, 3, fake, 0, None) == -4
+    assert wo(fake, fake, 8, 64, fake, 0, fake, 2, None) == -4
+    assert wo(fake, fake, 8, 64, odd, 0, fake, 0, None) == -3
     pg = lib.rcp_pack_weights_grouped
     pg.argtypes = [vp, ci, ci, ci, ci, vp, vp, vp, vp, vp, vp]
     assert pg(fake, 0, 8, 256, 128, fake, None, fake, fake, fake, None) == -1

@@ -80,6 +80,54 @@ def test_pack_grid_edge_values():
 
 
 # ------------------------------------------------------------------------------------------
+# weight-only GEMV (16- / 32-bit activations)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("blocks", [0, 2])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("N,K", [(4, 32), (12, 96), (256, 512), (20, 2080), (1028, 4096), (72, 11008), (40, 14336),
+                                 (8, 32768)])
+def test_weight_only_gemv_close_to_oracle(N, K, dtype, blocks):
+    _say(f"weight-only gemv N={N} K={K} {dtype} blocks={blocks}")
+    rcp.set_option("gemv_blocks", blocks)
+    idx = rcp_synth.random_indices(41, f"wo{N}x{K}", N, K)
+    packed = oracle.pack_indices(idx)
+    rng = np.random.default_rng(41)
+    cb = np.sort(rng.standard_normal((N, 4)) * 0.03, axis=1).astype(np.float16).view(np.uint16)
+    x16 = rcp_synth.activation(41, f"wo{K}", 1, K)
+    if dtype == "f16":
+        xd = _t(x16)
+    elif dtype == "bf16":
+        xd = _t(x16.astype(np.float32)).to(torch.bfloat16)
+    else:
+        xd = _t(x16.astype(np.float32) * np.float32(1.0009765))
+    x64 = xd.to(torch.float64).cpu().numpy()
+    ref = oracle.w2a16_gemv(packed, cb, N, K, x64)[0]
+    lut = np.abs(_f16(cb))
+    cond = (np.take_along_axis(lut, idx.astype(np.int64), axis=1) * np.abs(x64)).sum(axis=1)
+    for out_dtype in (torch.float32, torch.float16):
+        out = rcp.w2a16_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64).ravel()
+        half = 2.0 ** -11 * np.abs(ref) if out_dtype == torch.float16 else 0.0
+        assert np.all(np.abs(got - ref) <= 1e-3 * cond + half + 1e-30)
+        assert np.linalg.norm(got - ref) <= 1e-3 * np.linalg.norm(ref) + 1e-30
+
+
+def test_weight_only_gemv_equals_w2a4_on_dequantised_int4_activations():
+    """x = S*q (S a power of two) is exact in fp16: the weight-only kernel must then agree with the W2A4 kernel."""
+    N, K = 512, 4096
+    packed, cb, xq, sc = _gemv_case(43, N, K, 1)
+    sc[:] = np.array([0.25], np.float16).view(np.uint16)
+    q = oracle.unpack_act(xq, 1, K)
+    x = (q.astype(np.float32) * 0.25).astype(np.float16)
+    o4 = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)), 1, out_dtype=torch.float32)
+    o16 = rcp.w2a16_gemv(_t(packed), _t(cb.view(np.float16)), N, K, _t(x), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    a, b = o4.cpu().numpy().astype(np.float64).ravel(), o16.cpu().numpy().astype(np.float64).ravel()
+    assert np.linalg.norm(a - b) <= 1e-4 * np.linalg.norm(a)
+
+
+# ------------------------------------------------------------------------------------------
 # group-wise quantisation units (128 input channels per LUT)
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("N,K,dtype", [(8, 128, "f16"), (12, 256, "f32"), (64, 4096, "f16"), (36, 4224, "bf16"),
