@@ -353,6 +353,23 @@ def main():
         grouped[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1), "bytes": b}
         del bufs, og
 
+    # weight-only variant (fp16 activations, no quantiser): same packed weights, same cold sweep
+    weight_only = {}
+    for label, i, N in side_shapes:
+        K = launches[i][2]
+        xw = xs[i] if xs[i].dtype == torch.float16 else xs[i].to(torch.float16)
+
+        def wsweep(i=i, N=N, K=K, xw=xw):
+            for l in range(L):
+                packed, cb = layers[l][i]
+                rcp.w2a16_gemv(packed, cb, N, K, xw, out=outs[i])
+        wsweep()
+        fn = capture(wsweep)
+        fn()
+        s = timed(torch, fn, reps) / L
+        b = N * K // 4 + 8 * N + 2 * K + 2 * N
+        weight_only[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1)}
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
     if os.path.exists(tpath):
@@ -386,6 +403,7 @@ def main():
         "per_shape": per_shape,
         "small_batch": small_batch,
         "grouped_128": grouped,
+        "weight_only_fp16": weight_only,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),

@@ -7,13 +7,15 @@
 // time as a packed fp16 pair, ready for v_dot2_f32_f16 against a packed pair of activations:
 //   - for row r of a cell, E_r = ((B0 >> r) & 0x1111..) | (((B1 >> r) & 0x1111..) << 1) holds
 //     the eight 2-bit indices of the row, one per nibble (5 operations for 8 weights);
+//     (built for two rows at once, about 12 operations per 32 weights);
 //   - a byte of E_r is the index pair of two neighbouring columns, t = lo + 16*hi;
 //   - the wavefront keeps, for its current group of four rows, the 4 x 16 pairs
 //     (LUT[r][lo], LUT[r][hi]) at dword 4*r + t of a 64-dword table: the 64 entries fall into
 //     64 different LDS banks, so the 64 lanes' look-ups never conflict (equal addresses are
-//     broadcast);
+//     broadcast); the two free top bits of every byte of E_r carry the wavefront's table number,
+//     so a byte times four IS the LDS address;
 //   - one byte-select-and-shift (SDWA), one ds_read_b32 and one dot2 per two weights.
-// About 1.6 vector-ALU and 0.5 LDS operations per weight, against 0.69 for the W2A4 kernel.
+// About 1.4 vector-ALU and 0.5 LDS operations per weight, against 0.69 for the W2A4 kernel.
 // For bfloat16 / binary32 activations the pairs are multiplied with binary32 activations by
 // mixed-precision FMAs instead of dot2.  Accumulation is binary32 throughout.
 //
@@ -38,6 +40,20 @@ __host__ __device__ constexpr int wo_padded_units(int K)
     return ((U + span - 1) / span) * span;
 }
 
+// ((v >> 8*byte) & 0xff) << 2 in one instruction: a shift whose source operand selects a byte
+__device__ __forceinline__ uint32_t byte_times4(uint32_t v, int byte)
+{
+    uint32_t d;
+    const uint32_t two = 2;
+    switch (byte) {
+        case 0: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(d) : "v"(two), "v"(v)); break;
+        case 1: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(d) : "v"(two), "v"(v)); break;
+        case 2: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(d) : "v"(two), "v"(v)); break;
+        default: asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(d) : "v"(two), "v"(v)); break;
+    }
+    return d;
+}
+
 __device__ __forceinline__ uint32_t lut_half(uint2 row, int l)
 {
     const uint32_t w = (l & 2) ? row.y : row.x;
@@ -58,6 +74,7 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     const int nchunk = (U + 64 * WO_UNR - 1) / (64 * WO_UNR);
     const int nblk = gridDim.x;
     uint32_t* tab = wo_smem + wave * WO_TABLE_DWORDS;
+    const uint32_t wave_bits = 0x40404040u * static_cast<uint32_t>(wave);
     uint32_t* sx = wo_smem + WO_WAVES * WO_TABLE_DWORDS;
     constexpr int XD = XF32 ? 16 : 8;  // dwords of activations per unit
 
@@ -107,8 +124,30 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     int ch = 0;
 
-    // one cell (4 rows x 8 columns) against its 8 activations
-    auto cell = [&](uint32_t B0, uint32_t B1, const uint32_t* xs) {
+    // One cell (4 rows x 8 columns) in two phases, so that the 16 look-ups of the next cell can be
+    // in flight while the products of the current one are taken.
+    // Phase 1: the 16 pairs (LUT[r][idx of column 2jp], LUT[r][idx of column 2jp+1]).
+    auto cell_lookup = [&](uint32_t B0, uint32_t B1, uint32_t (&pair)[4][4]) {
+        // C02 / C13: per nibble the 2-bit indices of rows 0 and 2 (1 and 3) of one column; wave_bits
+        // puts this wavefront's table number into the two free top bits of every byte
+        const uint32_t C02 = (B0 & 0x55555555u) | ((B1 & 0x55555555u) << 1);
+        const uint32_t C13 = ((B0 >> 1) & 0x55555555u) | (B1 & 0xaaaaaaaau);
+        const uint32_t E[4] = {(C02 & 0x33333333u) | wave_bits, (C13 & 0x33333333u) | wave_bits,
+                               ((C02 >> 2) & 0x33333333u) | wave_bits, ((C13 >> 2) & 0x33333333u) | wave_bits};
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                // byte jp of E[r] = lo | hi << 4 | wave << 6; times 4 it is the byte address of the
+                // pair in this wavefront's table, up to the row's 16 bytes.  The read uses the
+                // absolute LDS address: the tables start at LDS offset 0 (this kernel has no static
+                // LDS, which the launcher verifies), so no base has to be added.
+                const uint32_t addr = byte_times4(E[r], jp);
+                pair[r][jp] = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(addr + 16 * r);
+            }
+    };
+    // Phase 2: products with the cell's 8 activations.
+    auto cell_dot = [&](const uint32_t (&pair)[4][4], const uint32_t* xs) {
         uint32_t xv[XF32 ? 8 : 4];
         {
             const uint4 v = *reinterpret_cast<const uint4*>(xs);  // 16-byte aligned by construction
@@ -119,20 +158,16 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
             }
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const uint32_t E = ((B0 >> r) & 0x11111111u) | (((B1 >> r) & 0x11111111u) << 1);
+        for (int jp = 0; jp < 4; ++jp)
 #pragma unroll
-            for (int jp = 0; jp < 4; ++jp) {
-                const uint32_t t = (E >> (8 * jp)) & 0xffu;
-                const uint32_t pair = tab[4 * r + t];
+            for (int r = 0; r < 4; ++r) {
                 if constexpr (!XF32) {
-                    acc[r] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, pair), __builtin_bit_cast(half2_t, xv[jp]), acc[r], false);
+                    acc[r] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, pair[r][jp]), __builtin_bit_cast(half2_t, xv[jp]), acc[r], false);
                 } else {
-                    acc[r] = fmaf(half_bits_to_float(static_cast<uint16_t>(pair & 0xffffu)), __uint_as_float(xv[2 * jp]), acc[r]);
-                    acc[r] = fmaf(half_bits_to_float(static_cast<uint16_t>(pair >> 16)), __uint_as_float(xv[2 * jp + 1]), acc[r]);
+                    acc[r] = fmaf(half_bits_to_float(static_cast<uint16_t>(pair[r][jp] & 0xffffu)), __uint_as_float(xv[2 * jp]), acc[r]);
+                    acc[r] = fmaf(half_bits_to_float(static_cast<uint16_t>(pair[r][jp] >> 16)), __uint_as_float(xv[2 * jp + 1]), acc[r]);
                 }
             }
-        }
     };
 
     auto step = [&](u32x4 (&w)[WO_UNR], u32x4 (&wnext)[WO_UNR]) {
@@ -146,10 +181,16 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
         __builtin_amdgcn_sched_barrier(0);
 
         const uint32_t* xrow = sx + (lane + ch * WO_UNR * 64) * XD;
+        uint32_t pA[4][4], pB[4][4];
+        cell_lookup(w[0].x, w[0].y, pA);
 #pragma unroll
         for (int i = 0; i < WO_UNR; ++i) {
-            cell(w[i].x, w[i].y, xrow + i * 64 * XD);
-            cell(w[i].z, w[i].w, xrow + i * 64 * XD + XD / 2);
+            cell_lookup(w[i].z, w[i].w, pB);
+            __builtin_amdgcn_sched_barrier(0);
+            cell_dot(pA, xrow + i * 64 * XD);
+            if (i + 1 < WO_UNR) cell_lookup(w[i + 1].x, w[i + 1].y, pA);
+            __builtin_amdgcn_sched_barrier(0);
+            cell_dot(pB, xrow + i * 64 * XD + XD / 2);
         }
 
         if (last) {
@@ -194,6 +235,10 @@ static int launch_wo(const void* packed, const void* codebook, int N, int K, con
     if (lds > 160 * 1024)
         return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a16_gemv: K=%d needs %zu bytes of LDS for the activations", K, lds);
     auto launch = [&](auto kernel) -> int {
+        // the look-ups address the tables by absolute LDS offset: dynamic LDS must start at 0
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) != hipSuccess || attr.sharedSizeBytes != 0)
+            return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: kernel has static LDS, table addressing would be wrong");
         if (lds > 65536) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                                static_cast<int>(lds));
