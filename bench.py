@@ -353,6 +353,37 @@ def main():
         grouped[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1), "bytes": b}
         del bufs, og
 
+    # the whole one-token step with group-wise LUTs (the paper's deployed setting): same launch
+    # structure as the headline step (rotation kernel + four fused quantise+GEMV launches per
+    # layer), 32 different layers of random indices and levels
+    grouped_step = None
+    if not args.step_only:
+        gl = []
+        for l in range(L):
+            per = []
+            for (_, N, K, _) in launches:
+                NG = K // rcp.GROUP
+                pk = torch.randint(0, 256, (N * K // 4,), dtype=torch.uint8, device=dev)
+                lv = (torch.randn((N // 4, NG, 4, 4), device=dev) * 0.03).sort(dim=3).values.to(torch.float16).contiguous()
+                per.append((pk, lv))
+            gl.append(per)
+
+        def gstep():
+            for l in range(L):
+                for i, (_, N, K, rotated) in enumerate(launches):
+                    if rotated:
+                        rcp.rotate_act(xs[i], rot_down, y_out=ybuf)
+                    pk, lv = gl[l][i]
+                    rcp.quant_w2a4_gemv_grouped(pk, lv, N, K, ybuf if rotated else xs[i], 1.0, out=outs[i])
+        gstep()
+        fn = capture(gstep)
+        fn()
+        s = timed(torch, fn, max(3, args.steps // 2))
+        gbytes = L * sum(N * K // 4 + 8 * N * (K // rcp.GROUP) + K // 2 + 2 + 2 * N for (_, N, K, _) in launches)
+        grouped_step = {"ms_per_step": round(s * 1e3, 4), "GBps": round(gbytes / s / 1e9, 1),
+                        "pct_of_hbm_peak": round(100.0 * gbytes / s / 1e9 / HBM_PEAK_GBPS, 2), "bytes_per_step": gbytes}
+        del gl
+
     # weight-only variant (fp16 activations, no quantiser): same packed weights, same cold sweep
     weight_only = {}
     for label, i, N in side_shapes:
@@ -403,6 +434,7 @@ def main():
         "per_shape": per_shape,
         "small_batch": small_batch,
         "grouped_128": grouped,
+        "grouped_128_step": grouped_step,
         "weight_only_fp16": weight_only,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},

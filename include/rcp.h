@@ -274,6 +274,14 @@ int rcp_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K
                           const void* xq, const void* scale,
                           void* out, rcp_dtype out_dtype,
                           int32_t* partial_sums_or_null, void* stream);
+/* rcp_quant_w2a4_gemv_grouped: the one-token fusion of rcp_quant_w2a4_gemv for group-wise LUTs,
+ * bit-identical to rcp_rotate_quant_act (no rotation) followed by rcp_w2a4_gemv_grouped.
+ * xq_out_or_null / scale_out_or_null as there (optional for K <= 16384, required beyond). */
+int rcp_quant_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K, int group,
+                                const void* x, rcp_dtype x_dtype, float clip_ratio,
+                                void* out, rcp_dtype out_dtype,
+                                void* xq_out_or_null, void* scale_out_or_null,
+                                int32_t* partial_sums_or_null, void* stream);
 
 #ifdef __cplusplus
 }

@@ -317,4 +317,35 @@ int rcp_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K
                                static_cast<hipStream_t>(stream));
 }
 
+int rcp_quant_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K, int group, const void* x,
+                                rcp_dtype x_dtype, float clip_ratio, void* out, rcp_dtype out_dtype,
+                                void* xq_out_or_null, void* scale_out_or_null, int32_t* partial_sums_or_null,
+                                void* stream)
+{
+    if (!packed || !codebook || !x || !out)
+        return fail(RCP_ERR_NULL, "rcp_quant_w2a4_gemv_grouped: NULL pointer argument");
+    if (int rc = check_shape("rcp_quant_w2a4_gemv_grouped", N, K)) return rc;
+    if (int rc = check_group("rcp_quant_w2a4_gemv_grouped", K, group)) return rc;
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w2a4_gemv_grouped: unknown dtype %d", static_cast<int>(x_dtype));
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w2a4_gemv_grouped: out_dtype must be RCP_F16 or RCP_F32");
+    if (!(clip_ratio > 0.0f) || !(clip_ratio <= 1.0f))
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w2a4_gemv_grouped: clip_ratio %g outside (0, 1]", static_cast<double>(clip_ratio));
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(x) || !aligned16(out) || !aligned16(xq_out_or_null) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_quant_w2a4_gemv_grouped: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale_out_or_null) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_quant_w2a4_gemv_grouped: scale_out must be 2-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (quant_gemv_grouped_supported(K))
+        return launch_quant_gemv_grouped(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
+                                         scale_out_or_null, partial_sums_or_null, st);
+    // K too large for the in-kernel quantiser: two launches through the caller's x_q / S buffers
+    if (!xq_out_or_null || !scale_out_or_null)
+        return fail(RCP_ERR_WORKSPACE, "rcp_quant_w2a4_gemv_grouped: K=%d needs xq_out and scale_out as scratch", K);
+    if (int rc = launch_act(x, x_dtype, 1, K, nullptr, clip_ratio, xq_out_or_null, scale_out_or_null, nullptr, 0, st)) return rc;
+    return launch_gemv_grouped(packed, codebook, N, K, xq_out_or_null, scale_out_or_null, out, out_dtype, partial_sums_or_null, st);
+}
+
 }  // extern "C"

@@ -40,12 +40,21 @@ __host__ __device__ constexpr size_t gemv_grouped_lds_bytes(int K)
     return static_cast<size_t>(K / 16 + 32) * 8 + static_cast<size_t>(K / GG_GROUP) * 4;
 }
 
-template <bool OUT_F16>
+// XDT < 0: `xq` / `scale` are the quantised activations.  XDT = RCP_F16 / RCP_F32 / RCP_BF16:
+// `xraw` is the raw activation (K <= 16384) and every workgroup quantises it itself with the
+// arithmetic of quant_kernel (amax, S = fp16(ratio*amax/7), q = rint(x/S)); the first
+// workgroup also writes x_q and S to xq_out / scale_out when those are given.
+constexpr int GG_XU = 4;  // 16-value units of raw activations per thread: K <= 16384
+
+template <bool OUT_F16, int XDT>
 __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* __restrict__ packed,
                                                                   const uint4* __restrict__ codebook, int N, int K,
                                                                   const uint4* __restrict__ xq,
                                                                   const uint16_t* __restrict__ scale,
-                                                                  void* __restrict__ out, int32_t* __restrict__ Pout)
+                                                                  void* __restrict__ out, int32_t* __restrict__ Pout,
+                                                                  const void* __restrict__ xraw, float clip_ratio,
+                                                                  uint32_t* __restrict__ xq_out,
+                                                                  uint16_t* __restrict__ scale_out)
 {
     extern __shared__ uint2 sx2[];
     const int lane = threadIdx.x & 63;
@@ -80,36 +89,95 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
         s.lut[1] = __builtin_amdgcn_raw_buffer_load_b128(cres, static_cast<int>(coff), 16, 0);
     };
 
-    // Small loads first (memory answers in issue order): this thread's group of activations
-    // (64 bytes; NG <= 256 threads take part) and the scale, then the first weight step.
-    u32x4 xg[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        xg[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, static_cast<int>(threadIdx.x) * 64, i * 16, 0);
-    const float S = half_bits_to_float(scale[0]);
-
     int b = blockIdx.x, rd = 0;
     GroupStep sA, sB;
-    load_step(b, rd, sA);
-
-    if (static_cast<int>(threadIdx.x) < NG) {
-        const int g = threadIdx.x;
-        const int r0 = g >> 5;
-        const int R = min(32, NG - 32 * r0);
-        uint2* dst = sx2 + 256 * r0 + (g & 31);
-        int t = 0;
+    float S;
+    if constexpr (XDT < 0) {
+        // Small loads first (memory answers in issue order): this thread's group of activations
+        // (64 bytes; NG <= 256 threads take part) and the scale, then the first weight step.
+        u32x4 xg[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            dst[(2 * i) * R] = make_uint2(xg[i].x, xg[i].y);
-            dst[(2 * i + 1) * R] = make_uint2(xg[i].z, xg[i].w);
-            t = dot8(xg[i].x, 0x11111111u, t);
-            t = dot8(xg[i].y, 0x11111111u, t);
-            t = dot8(xg[i].z, 0x11111111u, t);
-            t = dot8(xg[i].w, 0x11111111u, t);
+        for (int i = 0; i < 4; ++i)
+            xg[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, static_cast<int>(threadIdx.x) * 64, i * 16, 0);
+        S = half_bits_to_float(scale[0]);
+        load_step(b, rd, sA);
+
+        if (static_cast<int>(threadIdx.x) < NG) {
+            const int g = threadIdx.x;
+            const int r0 = g >> 5;
+            const int R = min(32, NG - 32 * r0);
+            uint2* dst = sx2 + 256 * r0 + (g & 31);
+            int t = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                dst[(2 * i) * R] = make_uint2(xg[i].x, xg[i].y);
+                dst[(2 * i + 1) * R] = make_uint2(xg[i].z, xg[i].w);
+                t = dot8(xg[i].x, 0x11111111u, t);
+                t = dot8(xg[i].y, 0x11111111u, t);
+                t = dot8(xg[i].z, 0x11111111u, t);
+                t = dot8(xg[i].w, 0x11111111u, t);
+            }
+            tgs[g] = t;
         }
-        tgs[g] = t;
+        __syncthreads();
+    } else {
+        // Fused quantiser.  Thread t takes the 16-value units t, t + 256, ...; the first one stays
+        // in registers between the two passes (maximum, then quantisation), further ones (K > 4096)
+        // are read again from cache.
+        __shared__ float amax_slots[GG_THREADS / 64];
+        float first[2][8];
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < GG_XU; ++i) {
+            if (i * GG_THREADS >= U) break;  // uniform
+            const int u = min(static_cast<int>(threadIdx.x) + i * GG_THREADS, U - 1);  // clamped: duplicates are harmless
+            float v[2][8];
+            load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16, v[0]);
+            load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16 + 8, v[1]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                a = fmaxf(a, fmaxf(fabsf(v[0][j]), fabsf(v[1][j])));
+                if (i == 0) {
+                    first[0][j] = v[0][j];
+                    first[1][j] = v[1][j];
+                }
+            }
+        }
+        load_step(b, rd, sA);
+        for (int g = threadIdx.x; g < NG; g += GG_THREADS) tgs[g] = 0;
+        a = wave_max(a);
+        if (lane == 0) amax_slots[wave] = a;
+        __syncthreads();
+        a = fmaxf(fmaxf(amax_slots[0], amax_slots[1]), fmaxf(amax_slots[2], amax_slots[3]));
+        const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
+        S = half_bits_to_float(sb);
+        const bool publish = blockIdx.x == 0 && xq_out != nullptr;
+#pragma unroll
+        for (int i = 0; i < GG_XU; ++i) {
+            if (i * GG_THREADS >= U) break;
+            const int u = threadIdx.x + i * GG_THREADS;
+            if (u < U) {
+                uint32_t q0, q1;
+                if (i == 0) {
+                    q0 = quantize8(first[0], S);
+                    q1 = quantize8(first[1], S);
+                } else {
+                    float v[2][8];
+                    load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16, v[0]);
+                    load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16 + 8, v[1]);
+                    q0 = quantize8(v[0], S);
+                    q1 = quantize8(v[1], S);
+                }
+                const int g = u >> 3, r0 = g >> 5;
+                const int R = min(32, NG - 32 * r0);
+                sx2[256 * r0 + (u & 7) * R + (g & 31)] = make_uint2(q0, q1);
+                atomicAdd(&tgs[g], dot8(q1, 0x11111111u, dot8(q0, 0x11111111u, 0)));
+                if (publish) reinterpret_cast<uint2*>(xq_out)[u] = make_uint2(q0, q1);
+            }
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out != nullptr) scale_out[0] = sb;
+        __syncthreads();
     }
-    __syncthreads();
 
     float o[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 
@@ -201,29 +269,68 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
     }
 }
 
-int launch_gemv_grouped(const void* packed, const void* codebook, int N, int K, const void* xq,
-                        const void* scale, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
+struct GroupedArgs {
+    const void *packed, *codebook;
+    int N, K;
+    const void *xq, *scale;
+    void* out;
+    rcp_dtype out_dt;
+    int32_t* P;
+    const void* xraw;  // fused quantiser when non-null
+    rcp_dtype x_dt;
+    float clip_ratio;
+    void *xq_out, *scale_out;
+};
+
+template <bool OUT_F16, int XDT>
+static int launch_grouped_one(const GroupedArgs& a, int blocks, size_t lds, hipStream_t st)
 {
-    if (static_cast<long long>(N) * K / 4 >= (1LL << 31))
+    gemv_grouped_kernel<OUT_F16, XDT><<<blocks, GG_THREADS, lds, st>>>(
+        static_cast<const uint4*>(a.packed), static_cast<const uint4*>(a.codebook), a.N, a.K,
+        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.out, a.P, a.xraw, a.clip_ratio,
+        static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
+    return check_launch("rcp_w2a4_gemv_grouped");
+}
+
+static int dispatch_grouped(const GroupedArgs& a, hipStream_t st)
+{
+    if (static_cast<long long>(a.N) * a.K / 4 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv_grouped: packed matrix of %lld bytes exceeds 2 GiB",
-                    static_cast<long long>(N) * K / 4);
-    const int G = N / 4;
+                    static_cast<long long>(a.N) * a.K / 4);
+    const int G = a.N / 4;
     const int nbatch = (G + GG_SLOTS - 1) / GG_SLOTS;
     const int cus = num_compute_units();
     int blocks = options().gemv_blocks;
     if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    // every workgroup quantises x itself: fewer, longer-lived workgroups
+    if (options().gemv_blocks == 0 && a.xraw != nullptr && blocks > cus * 2) blocks = cus * 2;
     if (blocks > nbatch) blocks = nbatch;
     if (blocks < 1) blocks = 1;
-    const size_t lds = gemv_grouped_lds_bytes(K);
-    auto* pk = static_cast<const uint4*>(packed);
-    auto* cb = static_cast<const uint4*>(codebook);
-    auto* x4 = static_cast<const uint4*>(xq);
-    auto* sc = static_cast<const uint16_t*>(scale);
-    if (out_dt == RCP_F16)
-        gemv_grouped_kernel<true><<<blocks, GG_THREADS, lds, st>>>(pk, cb, N, K, x4, sc, out, P);
-    else
-        gemv_grouped_kernel<false><<<blocks, GG_THREADS, lds, st>>>(pk, cb, N, K, x4, sc, out, P);
-    return check_launch("rcp_w2a4_gemv_grouped");
+    const size_t lds = gemv_grouped_lds_bytes(a.K);
+#define RCP_GG(XDT) \
+    return a.out_dt == RCP_F16 ? launch_grouped_one<true, XDT>(a, blocks, lds, st) : launch_grouped_one<false, XDT>(a, blocks, lds, st)
+    if (a.xraw == nullptr) RCP_GG(-1);
+    if (a.x_dt == RCP_F16) RCP_GG(RCP_F16);
+    if (a.x_dt == RCP_F32) RCP_GG(RCP_F32);
+    RCP_GG(RCP_BF16);
+#undef RCP_GG
+}
+
+int launch_gemv_grouped(const void* packed, const void* codebook, int N, int K, const void* xq,
+                        const void* scale, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
+{
+    const GroupedArgs a = {packed, codebook, N, K, xq, scale, out, out_dt, P, nullptr, RCP_F16, 1.0f, nullptr, nullptr};
+    return dispatch_grouped(a, st);
+}
+
+bool quant_gemv_grouped_supported(int K) { return K / 16 <= GG_XU * GG_THREADS; }
+
+int launch_quant_gemv_grouped(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                              float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                              hipStream_t st)
+{
+    const GroupedArgs a = {packed, codebook, N, K, nullptr, nullptr, out, out_dt, P, x, x_dt, clip_ratio, xq_out, scale_out};
+    return dispatch_grouped(a, st);
 }
 
 }  // namespace rcp

@@ -46,6 +46,10 @@ int launch_rotate(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation*
 
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
+bool quant_gemv_grouped_supported(int K);
+int launch_quant_gemv_grouped(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                              float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                              hipStream_t st);
 // weight-only GEMV: 16- or 32-bit activations, no activation quantiser (w2a16_gemv.hip)
 int launch_w2a16_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
                       void* out, rcp_dtype out_dt, hipStream_t st);

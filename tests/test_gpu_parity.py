@@ -211,6 +211,36 @@ def test_grouped_gemv_extreme_activations_and_integer_levels():
     assert np.array_equal(out.cpu().numpy().astype(np.float64).ravel(), ref_O)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("N,K,ratio", [(8, 128, 1.0), (36, 4096, 1.0), (1028, 4096, 0.9), (72, 11008, 1.0), (40, 14336, 1.0),
+                                       (16, 16384, 1.0), (8, 32768, 1.0)])
+def test_grouped_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype):
+    """One launch (quantiser in the prologue of the grouped GEMV) must give the bits of the two calls."""
+    _say(f"grouped fused quant+gemv N={N} K={K} ratio={ratio} {dtype}")
+    packed, cb, _, _ = _grouped_gemv_case(61, N, K)
+    x16 = rcp_synth.activation(61, f"gfq{K}", 1, K)
+    xd = {"f16": _t(x16), "bf16": _t(x16.astype(np.float32)).to(torch.bfloat16),
+          "f32": _t(x16.astype(np.float32) * np.float32(1.0009765))}[dtype]
+    pk, lv = _t(packed), _t(cb.view(np.float16))
+    xq, sc = rcp.rotate_quant_act(xd, None, ratio)
+    ref_out, ref_P = rcp.w2a4_gemv_grouped(pk, lv, N, K, xq, sc, out_dtype=torch.float32, want_partial_sums=True)
+    xq2 = torch.zeros_like(xq)
+    sc2 = torch.zeros_like(sc)
+    out, P = rcp.quant_w2a4_gemv_grouped(pk, lv, N, K, xd, ratio, out_dtype=torch.float32, xq_out=xq2, scale_out=sc2,
+                                         want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert torch.equal(xq2, xq) and torch.equal(sc2.view(torch.int16), sc.view(torch.int16))
+    assert torch.equal(P, ref_P)
+    assert torch.equal(out, ref_out)
+    # against the oracle too (x_q, S of non-rotated inputs are bit-exact)
+    oxq, osc, _ = oracle.quantize_act(xd.to(torch.float32).cpu().numpy(), ratio)
+    assert np.array_equal(xq2.cpu().numpy(), oxq) and np.array_equal(sc2.cpu().numpy().view(np.uint16), osc)
+    if K <= 16384:
+        out3 = rcp.quant_w2a4_gemv_grouped(pk, lv, N, K, xd, ratio, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(out3, ref_out)
+
+
 @pytest.mark.parametrize("N,K", [(64, 4096), (32, 11008)])
 def test_grouped_whole_path(N, K):
     """export -> quantise -> grouped GEMV against the oracle doing the same from the same inputs."""
