@@ -306,6 +306,28 @@ def test_gemv_partial_sums_bit_exact_and_output_close(N, K, lanes):
     _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float16)
 
 
+def test_largest_row_count_the_packer_accepts():
+    """N = 262140 (the packer's grid limit) at the smallest K; one more group of rows is refused."""
+    N, K = 262140, 32
+    idx = rcp_synth.random_indices(9, "maxN", N, K)
+    rng = np.random.default_rng(9)
+    W = rng.standard_normal((N, K)).astype(np.float16)
+    lo = np.full(N, -1.0, np.float32)
+    hi = np.full(N, 1.0, np.float32)
+    part = np.tile(np.array([0.25, 0.5, 0.25], np.float32), (N, 1))
+    packed, cb = rcp.pack_weights(_t(W), _t(lo), _t(hi), _t(part))
+    ref_packed, ref_cb = oracle.pack_weights(W.astype(np.float32), lo, hi, part)
+    torch.cuda.synchronize()
+    assert np.array_equal(packed.cpu().numpy(), ref_packed) and np.array_equal(cb.cpu().numpy().view(np.uint16).ravel(), ref_cb.ravel())
+    q = rcp_synth.random_int4(9, "maxN", 1, K)
+    xq = ((q[:, 0::2].astype(np.uint8) & 0xF) | ((q[:, 1::2].astype(np.uint8) & 0xF) << 4)).astype(np.uint8)
+    sc = np.array([0.5], np.float16).view(np.uint16)
+    _check_gemv(ref_packed, ref_cb.reshape(N, 4), N, K, xq, sc, 1, torch.float32)
+    with pytest.raises(rcp.RcpError):
+        rcp.pack_weights(torch.zeros((N + 4, K), dtype=torch.float16, device=DEV), _t(np.zeros(N + 4, np.float32)),
+                         _t(np.ones(N + 4, np.float32)), _t(np.tile(np.array([0.25, 0.5, 0.25], np.float32), (N + 4, 1))))
+
+
 @pytest.mark.parametrize("lanes,unroll", [(16, 2), (32, 4), (64, 2), (256, 4)])
 @pytest.mark.parametrize("blocks", [1, 3, 64])
 def test_gemv_grid_stride_with_few_workgroups(blocks, lanes, unroll):
