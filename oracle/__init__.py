@@ -215,14 +215,14 @@ def unpack_indices_grouped(packed, N, K, group=128) -> np.ndarray:
     return idx
 
 
-def w2a4_gemv_grouped(packed, codebook, N, K, xq, scale_bits, group=128):
-    """-> (O float64[N], P int32[N, NG, 4]) for one token."""
+def w2a4_gemv_grouped(packed, codebook, N, K, xq, scale_bits, group=128, M=1):
+    """-> (O float64 [N] and P int32 [N, NG, 4] for M = 1; [M, N] and [M, N, NG, 4] otherwise)."""
     pk, cb = _c(packed, np.uint8), _c(codebook, np.uint16)
     xc, sc = _c(xq, np.uint8), _c(scale_bits, np.uint16)
     NG = K // group
-    assert pk.size == N * K // 4 and cb.size == N * NG * 4 and xc.size == K // 2 and sc.size >= 1
-    out = np.empty(N, dtype=np.float64)
-    P = np.empty((N, NG, 4), dtype=np.int32)
-    _check(lib().rcp_ref_w2a4_gemv_grouped(_p(pk), _p(cb), N, K, group, _p(xc), _p(sc), _p(out), _p(P)),
+    assert pk.size == N * K // 4 and cb.size == N * NG * 4 and xc.size == M * K // 2 and sc.size >= M
+    out = np.empty((M, N), dtype=np.float64)
+    P = np.empty((M, N, NG, 4), dtype=np.int32)
+    _check(lib().rcp_ref_w2a4_gemv_grouped(_p(pk), _p(cb), N, K, group, _p(xc), _p(sc), M, _p(out), _p(P)),
            "w2a4_gemv_grouped")
-    return out, P
+    return (out[0], P[0]) if M == 1 else (out, P)

@@ -547,31 +547,33 @@ int rcp_ref_unpack_indices_grouped(const uint8_t* packed, int N, int K, int grou
     return RCP_REF_OK;
 }
 
-/* O[h] = S * sum_g sum_l LUT[h][g][l] * P[h][g][l],  P[h][g][l] = sum of q over the columns of
- * group g whose index is l.  One token.  P_or_null: int32 [N][NG][4]. */
+/* O[t][h] = S[t] * sum_g sum_l LUT[h][g][l] * P[t][h][g][l],  P[t][h][g][l] = sum of q[t] over the
+ * columns of group g whose index is l.  M tokens.  out: M x N; P_or_null: int32 [M][N][NG][4]. */
 int rcp_ref_w2a4_gemv_grouped(const uint8_t* packed, const uint16_t* codebook, int N, int K, int group,
-                              const uint8_t* xq, const uint16_t* scale_bits, double* out, int32_t* P_or_null)
+                              const uint8_t* xq, const uint16_t* scale_bits, int M, double* out,
+                              int32_t* P_or_null)
 {
-    if (!grouped_shape_ok(N, K, group)) return RCP_REF_ERR_SHAPE;
+    if (!grouped_shape_ok(N, K, group) || M < 1) return RCP_REF_ERR_SHAPE;
     int NG = K / group;
-    int8_t* q = (int8_t*)malloc((size_t)K);
+    int8_t* q = (int8_t*)malloc((size_t)M * K);
     if (!q) return RCP_REF_ERR_SHAPE;
-    rcp_ref_unpack_act(xq, 1, K, q);
-    double s = rcp_ref_f16_bits_to_f64(scale_bits[0]);
+    rcp_ref_unpack_act(xq, M, K, q);
 #pragma omp parallel for schedule(static)
-    for (int h = 0; h < N; ++h) {
-        double acc = 0.0;
-        for (int g = 0; g < NG; ++g) {
-            int64_t P[4] = {0, 0, 0, 0};
-            for (int k = g * group; k < (g + 1) * group; ++k) P[grouped_get(packed, h, k, K)] += q[k];
-            const uint16_t* lut = codebook + grouped_lut_index(h, g, NG);
-            for (int l = 0; l < 4; ++l) {
-                if (P_or_null) P_or_null[((size_t)h * NG + g) * 4 + l] = (int32_t)P[l];
-                acc += rcp_ref_f16_bits_to_f64(lut[l]) * (double)P[l];
+    for (int h = 0; h < N; ++h)
+        for (int t = 0; t < M; ++t) {
+            double acc = 0.0;
+            for (int g = 0; g < NG; ++g) {
+                int64_t P[4] = {0, 0, 0, 0};
+                for (int k = g * group; k < (g + 1) * group; ++k)
+                    P[grouped_get(packed, h, k, K)] += q[(size_t)t * K + k];
+                const uint16_t* lut = codebook + grouped_lut_index(h, g, NG);
+                for (int l = 0; l < 4; ++l) {
+                    if (P_or_null) P_or_null[(((size_t)t * N + h) * NG + g) * 4 + l] = (int32_t)P[l];
+                    acc += rcp_ref_f16_bits_to_f64(lut[l]) * (double)P[l];
+                }
             }
+            out[(size_t)t * N + h] = rcp_ref_f16_bits_to_f64(scale_bits[t]) * acc;
         }
-        out[h] = s * acc;
-    }
     free(q);
     return RCP_REF_OK;
 }

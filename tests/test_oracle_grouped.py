@@ -99,6 +99,29 @@ def test_gemv_matches_numpy_dequantise_and_dot(N, K):
         assert np.array_equal(P[:, :, l], (onehot * q[0].astype(np.int64).reshape(1, NG, G)).sum(axis=2))
 
 
+@pytest.mark.parametrize("N,K,M", [(8, 256, 3), (12, 4096, 16), (8, 11008, 5)])
+def test_several_tokens_match_numpy_dequantise_and_matmul(N, K, M):
+    W, lo, hi, part = _params(5, N, K)
+    NG = K // G
+    packed, cb, idx = oracle.pack_weights_grouped(W.astype(np.float32), lo, hi, part, want_idx=True)
+    x = rcp_synth.activation(5, f"xm{K}", M, K).astype(np.float32) * np.linspace(0.5, 2.0, M, dtype=np.float32)[:, None]
+    xq, sc, q = oracle.quantize_act(x)
+    O, P = oracle.w2a4_gemv_grouped(packed, cb, N, K, xq, sc, M=M)
+    assert O.shape == (M, N) and P.shape == (M, N, NG, 4)
+    lut = _lut(cb, N, NG)
+    Wd = np.take_along_axis(np.repeat(lut, G, axis=1), idx.astype(np.int64)[:, :, None], axis=2)[:, :, 0]
+    xd = q.astype(np.float64) * _f16(sc)[:, None]                           # [M, K]
+    want = xd @ Wd.T
+    assert np.all(np.abs(O - want) <= 1e-13 * (np.abs(xd) @ np.abs(Wd).T) + 1e-300)
+    for l in range(4):
+        onehot = (idx == l).astype(np.int64).reshape(1, N, NG, G)
+        assert np.array_equal(P[..., l], (onehot * q.astype(np.int64).reshape(M, 1, NG, G)).sum(axis=3))
+    # token by token it is the one-token call
+    for t in (0, M - 1):
+        O1, P1 = oracle.w2a4_gemv_grouped(packed, cb, N, K, xq[t:t + 1], sc[t:t + 1])
+        assert np.array_equal(O1, O[t]) and np.array_equal(P1, P[t])
+
+
 def test_shape_errors():
     with pytest.raises(RuntimeError):
         oracle.pack_indices_grouped(np.zeros((4, 192), np.uint8))
