@@ -274,6 +274,13 @@ int rcp_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K
                           const void* xq, const void* scale,
                           void* out, rcp_dtype out_dtype,
                           int32_t* partial_sums_or_null, void* stream);
+/* rcp_w2a4_gemm_grouped: the same product for M <= RCP_MAX_M tokens (xq: M x K/2 bytes, scale: fp16 [M],
+ * out: M x N); several tokens run on the matrix cores, one step of the matrix instruction per
+ * quantisation group.  partial_sums_or_null: int32 [M][N][NG][4]. */
+int rcp_w2a4_gemm_grouped(const void* packed, const void* codebook, int N, int K, int group,
+                          const void* xq, const void* scale, int M,
+                          void* out, rcp_dtype out_dtype,
+                          int32_t* partial_sums_or_null, void* stream);
 /* rcp_quant_w2a4_gemv_grouped: the one-token fusion of rcp_quant_w2a4_gemv for group-wise LUTs,
  * bit-identical to rcp_rotate_quant_act (no rotation) followed by rcp_w2a4_gemv_grouped.
  * xq_out_or_null / scale_out_or_null as there (optional for K <= 16384, required beyond). */

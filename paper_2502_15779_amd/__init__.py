@@ -101,6 +101,8 @@ def lib():
         L.rcp_unpack_indices_grouped.argtypes = [vp, ci, ci, ci, vp, vp]
         L.rcp_w2a4_gemv_grouped.restype = ci
         L.rcp_w2a4_gemv_grouped.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, ci, vp, vp]
+        L.rcp_w2a4_gemm_grouped.restype = ci
+        L.rcp_w2a4_gemm_grouped.argtypes = [vp, vp, ci, ci, ci, vp, vp, ci, vp, ci, vp, vp]
         L.rcp_quant_w2a4_gemv_grouped.restype = ci
         L.rcp_quant_w2a4_gemv_grouped.argtypes = [vp, vp, ci, ci, ci, vp, ci, ctypes.c_float, vp, ci, vp, vp, vp, vp]
         L.rcp_w2a16_gemv.restype = ci
@@ -357,4 +359,27 @@ def quant_w2a4_gemv_grouped(packed, codebook, N, K, x, clip_ratio=1.0, group=GRO
                                              _dev(x, "x"), _DTYPES[x.dtype], ctypes.c_float(clip_ratio), _dev(out, "out"),
                                              _DTYPES[out.dtype], opt(xq_out, "xq_out"), opt(scale_out, "scale_out"),
                                              opt(partial_sums, "partial_sums"), _stream()))
+    return (out, partial_sums) if partial_sums is not None else out
+
+
+def w2a4_gemm_grouped(packed, codebook, N, K, xq, scale, M, group=GROUP, out=None, out_dtype=torch.float16,
+                      partial_sums=None, want_partial_sums=False):
+    """Group-wise LUTs, M tokens -> out [M, N] (and int32 [M, N, K/group, 4] partial sums when asked for)."""
+    NG = max(K // group, 1)
+    if out is None:
+        out = torch.empty((M, N), dtype=out_dtype, device=packed.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < M * N:
+        raise ValueError("out must be float16 or float32 with M*N elements")
+    if want_partial_sums and partial_sums is None:
+        partial_sums = torch.empty((M, N, NG, 4), dtype=torch.int32, device=packed.device)
+    if packed.numel() * packed.element_size() < N * K // 4 or codebook.numel() < 4 * N * NG:
+        raise ValueError("packed / codebook buffers do not match N, K, group")
+    if xq.numel() * xq.element_size() < M * K // 2 or scale.numel() < M:
+        raise ValueError("xq / scale buffers do not match M, K")
+    if partial_sums is not None and (partial_sums.dtype != torch.int32 or partial_sums.numel() < 4 * M * N * NG):
+        raise ValueError("partial_sums must be int32 [M, N, K/group, 4]")
+    _check(lib().rcp_w2a4_gemm_grouped(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, group,
+                                       _dev(xq, "xq"), _dev(scale, "scale"), M, _dev(out, "out"), _DTYPES[out.dtype],
+                                       _dev(partial_sums, "partial_sums") if partial_sums is not None else None,
+                                       _stream()))
     return (out, partial_sums) if partial_sums is not None else out

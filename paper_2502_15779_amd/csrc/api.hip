@@ -317,6 +317,28 @@ int rcp_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K
                                static_cast<hipStream_t>(stream));
 }
 
+int rcp_w2a4_gemm_grouped(const void* packed, const void* codebook, int N, int K, int group, const void* xq,
+                          const void* scale, int M, void* out, rcp_dtype out_dtype, int32_t* partial_sums_or_null,
+                          void* stream)
+{
+    if (!packed || !codebook || !xq || !scale || !out)
+        return fail(RCP_ERR_NULL, "rcp_w2a4_gemm_grouped: NULL pointer argument");
+    if (int rc = check_shape("rcp_w2a4_gemm_grouped", N, K)) return rc;
+    if (int rc = check_group("rcp_w2a4_gemm_grouped", K, group)) return rc;
+    if (M <= 0 || M > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemm_grouped: M=%d outside 1..%d", M, RCP_MAX_M);
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a4_gemm_grouped: out_dtype must be RCP_F16 or RCP_F32");
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(xq) || !aligned16(out) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemm_grouped: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemm_grouped: scale must be 2-byte aligned");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M == 1 && options().gemv_variant != 2)
+        return launch_gemv_grouped(packed, codebook, N, K, xq, scale, out, out_dtype, partial_sums_or_null, st);
+    return launch_gemm_mfma_grouped(packed, codebook, N, K, xq, scale, M, out, out_dtype, partial_sums_or_null, st);
+}
+
 int rcp_quant_w2a4_gemv_grouped(const void* packed, const void* codebook, int N, int K, int group, const void* x,
                                 rcp_dtype x_dtype, float clip_ratio, void* out, rcp_dtype out_dtype,
                                 void* xq_out_or_null, void* scale_out_or_null, int32_t* partial_sums_or_null,

@@ -34,28 +34,10 @@ constexpr int MM_PLANE = 16 * MM_STRIDE;
 constexpr int MM_SUMS = 3 * MM_PLANE + 16;          // ints that are accumulated into (zeroed first)
 constexpr int MM_LDS_INTS = MM_SUMS + 2 * 64 + 16;  // + the 64 LUT rows of the block and the scales
 
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-
 struct MmStage {
     u32x4 wa, wb;  // two units: 4 rows x 32 columns, bit planes b0 / b1 interleaved per cell
     u32x4 xq;      // 32 int4 activations of this lane's token
 };
-
-// eight int4 (two's complement) -> eight FP4 codes of lo = q & 3 in {0, 1, 2, 3}
-__device__ __forceinline__ uint32_t fp4_lo(uint32_t x)
-{
-    const uint32_t n0 = x & 0x11111111u, n1 = x & 0x22222222u;
-    const uint32_t both = n0 & (n1 >> 1);            // lo == 3 -> code 0101 (3.0): bit 0
-    return both | (((n0 ^ both) | n1) << 1);         // lo == 1 -> 0010 (1.0), lo >= 2 -> bit 2 (2.0)
-}
-
-// eight int4 -> eight FP4 codes of hi = q >> 2 in {-2, -1, 0, 1}: 1100, 1010, 0000, 0010
-__device__ __forceinline__ uint32_t fp4_hi(uint32_t x)
-{
-    const uint32_t n3 = x & 0x88888888u, n2 = x & 0x44444444u;
-    return n3 | ((n3 >> 1) & ~n2) | (n2 >> 1);
-}
 
 // PACKED: M <= 8, lo and hi of token n in columns n and n + 8 of one B operand.
 template <bool OUT_F16, bool PACKED>

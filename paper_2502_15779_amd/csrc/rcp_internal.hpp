@@ -56,6 +56,8 @@ int launch_w2a16_gemv(const void* packed, const void* codebook, int N, int K, co
 // matrix-core kernel for several tokens (gemm_mfma.hip)
 int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
                      int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
+int launch_gemm_mfma_grouped(const void* packed, const void* codebook, int N, int K, const void* xq,
+                             const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 // fused quantise + GEMV for one token; x is the raw activation, xq_out / scale_out optional
 int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
                       float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
@@ -204,6 +206,25 @@ __device__ __forceinline__ void cell_update(uint32_t b0, uint32_t b1, const uint
             acc[t][p][3] = dot8(x[t], pl[p], acc[t][p][3]);
         }
     }
+}
+
+// ---- FP4 (E2M1) operands of the 16x16x128 matrix instruction -------------------------------
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// eight int4 (two's complement) -> eight FP4 codes of lo = q & 3 in {0, 1, 2, 3}
+__device__ __forceinline__ uint32_t fp4_lo(uint32_t x)
+{
+    const uint32_t n0 = x & 0x11111111u, n1 = x & 0x22222222u;
+    const uint32_t both = n0 & (n1 >> 1);            // lo == 3 -> code 0101 (3.0): bit 0
+    return both | (((n0 ^ both) | n1) << 1);         // lo == 1 -> 0010 (1.0), lo >= 2 -> bit 2 (2.0)
+}
+
+// eight int4 -> eight FP4 codes of hi = q >> 2 in {-2, -1, 0, 1}: 1100, 1010, 0000, 0010
+__device__ __forceinline__ uint32_t fp4_hi(uint32_t x)
+{
+    const uint32_t n3 = x & 0x88888888u, n2 = x & 0x44444444u;
+    return n3 | ((n3 >> 1) & ~n2) | (n2 >> 1);
 }
 
 // ---- the int4 quantiser (shared by the activation kernels and the fused GEMV prologue) ----

@@ -193,6 +193,62 @@ def test_grouped_gemv_partial_sums_bit_exact_and_output_close(N, K, blocks):
     _check_grouped_gemv(packed, cb, N, K, xq, sc, torch.float32 if blocks else torch.float16)
 
 
+@pytest.mark.parametrize("waves", [0, 2])
+@pytest.mark.parametrize("M", [1, 2, 5, 8, 16])
+@pytest.mark.parametrize("N,K", [(4, 128), (68, 256), (1028, 4096), (72, 11008), (40, 14336), (12, 32768)])
+def test_grouped_gemm_several_tokens(N, K, M, waves):
+    """Group-wise LUTs with M tokens (matrix-core kernel; M = 1 takes the GEMV unless forced)."""
+    _say(f"grouped gemm N={N} K={K} M={M} waves={waves}")
+    rcp.set_option("gemm_waves", waves)
+    if waves:
+        rcp.set_option("gemv_variant", 2)   # the matrix-core kernel also for one token
+    NG = K // 128
+    idx = rcp_synth.random_indices(71, f"ggemm{N}x{K}", N, K)
+    q = rcp_synth.random_int4(71 + M, f"ggemm{K}", M, K)
+    rng = np.random.default_rng(71)
+    cb = np.sort(rng.standard_normal((N // 4, NG, 4, 4)) * 0.03, axis=3).astype(np.float16).view(np.uint16)
+    sc = (np.abs(rng.standard_normal(M)) * 0.2 + 0.05).astype(np.float16).view(np.uint16)
+    xq = ((q[:, 0::2].astype(np.uint8) & 0xF) | ((q[:, 1::2].astype(np.uint8) & 0xF) << 4)).astype(np.uint8)
+    packed = oracle.pack_indices_grouped(idx)
+    ref_O, ref_P = oracle.w2a4_gemv_grouped(packed, cb.ravel(), N, K, xq, sc, M=M)
+    ref_O, ref_P = ref_O.reshape(M, N), ref_P.reshape(M, N, NG, 4)
+    lut = np.abs(_f16(cb)).reshape(N // 4, NG, 4, 4).transpose(0, 2, 1, 3).reshape(N, NG, 4)
+    cond = _f16(sc)[:, None] * (lut[None] * np.abs(ref_P)).sum(axis=(2, 3))
+    for out_dtype in (torch.float32, torch.float16):
+        out, P = rcp.w2a4_gemm_grouped(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)), M,
+                                       out_dtype=out_dtype, want_partial_sums=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(P.cpu().numpy(), ref_P), "per-group partial sums are not bit-exact"
+        got = out.cpu().numpy().astype(np.float64)
+        half = 2.0 ** -11 * np.abs(ref_O) if out_dtype == torch.float16 else 0.0
+        assert np.all(np.abs(got - ref_O) <= 1e-3 * cond + half + 1e-30)
+        assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O) + 1e-30
+        out2 = rcp.w2a4_gemm_grouped(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)), M,
+                                     out_dtype=out_dtype)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2)
+
+
+def test_grouped_gemm_extreme_activations():
+    """q = -8 / +7 everywhere with integer levels: exact integer outputs for all 16 tokens."""
+    N, K, M = 64, 14336, 16
+    NG = K // 128
+    idx = rcp_synth.random_indices(73, "ggext", N, K)
+    packed = oracle.pack_indices_grouped(idx)
+    xq = np.empty((M, K // 2), np.uint8)
+    xq[0::2] = 0x88
+    xq[1::2] = 0x77
+    rng = np.random.default_rng(73)
+    cb = np.sort(rng.integers(-3, 4, size=(N // 4, NG, 4, 4)), axis=3).astype(np.float16).view(np.uint16)
+    sc = np.full(M, 1.0, np.float16).view(np.uint16)
+    ref_O, ref_P = oracle.w2a4_gemv_grouped(packed, cb.ravel(), N, K, xq, sc, M=M)
+    out, P = rcp.w2a4_gemm_grouped(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(sc.view(np.float16)), M,
+                                   out_dtype=torch.float32, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), ref_O)
+
+
 def test_grouped_gemv_extreme_activations_and_integer_levels():
     """q = -8 everywhere (largest magnitude sums) and integer levels: the output is an exact integer."""
     N, K = 24, 11008
