@@ -399,6 +399,23 @@ def main():
         gbytes = L * sum(N * K // 4 + 8 * N * (K // rcp.GROUP) + K // 2 + 2 + 2 * N for (_, N, K, _) in launches)
         grouped_step = {"ms_per_step": round(s * 1e3, 4), "GBps": round(gbytes / s / 1e9, 1),
                         "pct_of_hbm_peak": round(100.0 * gbytes / s / 1e9 / HBM_PEAK_GBPS, 2), "bytes_per_step": gbytes}
+        # several tokens with group-wise LUTs: the four GEMMs of a layer, activations already quantised
+        grouped_step["small_batch_gemm_only_us_per_layer"] = {}
+        for M in (4, 8, 16):
+            xqm = [torch.randint(0, 256, (M, K // 2), dtype=torch.uint8, device=dev) for (_, _, K, _) in launches]
+            scm = [(torch.rand(M, device=dev) * 0.1 + 0.05).to(torch.float16) for _ in launches]
+            outm = [torch.empty((M, N), dtype=torch.float16, device=dev) for (_, N, _, _) in launches]
+
+            def ggemm(M=M, xqm=xqm, scm=scm, outm=outm):
+                for l in range(L):
+                    for i, (_, N, K, _) in enumerate(launches):
+                        pk, lv = gl[l][i]
+                        rcp.w2a4_gemm_grouped(pk, lv, N, K, xqm[i], scm[i], M, out=outm[i])
+            ggemm()
+            fn = capture(ggemm)
+            fn()
+            sg = timed(torch, fn, max(2, reps // 2))
+            grouped_step["small_batch_gemm_only_us_per_layer"][f"M{M}"] = round(sg / L * 1e6, 2)
         del gl
 
     # weight-only variant (fp16 activations, no quantiser): same packed weights, same cold sweep

@@ -10,18 +10,22 @@
 // accumulators are not carried from step to step: after the 24 instructions of a step (three
 // bit planes x four rows of a nibble x lo / hi part of the int4 activation, hi weighted 2^2 and
 // the 0.5 / 1 / 2 of the masks undone by the instruction's E8M0 scales) a lane holds the exact
-// plane sums F_p of 16 rows for one token, turns them into the per-level sums, multiplies with
-// the group's levels and adds to 16 running fp32 outputs.  The per-group sum of q that P_0
-// needs comes from two more instructions with an all-ones A operand.
+// plane sums F_p of 16 rows for one token and adds their products with the group's levels to 16
+// running fp32 outputs.  The per-group sum of q that level 0 needs comes from two more
+// instructions with an all-ones A operand.
 //
 // Work decomposition: a workgroup owns 64 output rows, its 8 wavefronts take the groups of K in
 // turn.  Lane l supplies row group l%16 and the two 16-byte units 2*(l/16), 2*(l/16)+1 of the
 // group (the grouped packed layout keeps the same unit of neighbouring groups side by side, so
 // the wavefronts of a workgroup, which work on neighbouring groups, share cache lines), and
 // token l%16 for the B operand.  The 512 bytes of levels a step needs are fetched once per
-// wavefront (16 bytes per lane), passed through a wavefront-private LDS buffer and read back
-// as broadcasts.  At the end every wavefront parks its 16 x 64 partial outputs in LDS and the
-// workgroup adds them in a fixed order (deterministic), scales and stores.
+// wavefront (16 bytes = two rows per lane); the fetching lane turns the four levels of a row
+// into the coefficients of (sum of q, F_b0, F_b1, F_b0&b1),
+//     O += L0*T + (L1-L0)*F0 + (L2-L0)*F1 + (L3-L2-L1+L0)*F3      (= sum_l L_l * P_l),
+// once for all 16 token lanes, and passes them through a wavefront-private LDS buffer from which
+// they are read back as broadcasts: four FMAs per (row, token) and group.  At the end every
+// wavefront parks its 16 x 64 partial outputs in LDS and the workgroup adds them in a fixed
+// order (deterministic), scales and stores.
 #include "rcp_internal.hpp"
 
 namespace rcp {
@@ -44,7 +48,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
                                                                        void* __restrict__ out, int32_t* __restrict__ Pout)
 {
     __shared__ float slab[MG_WAVES * 16 * MG_STRIDE];  // [wavefront][token][row of the block]
-    __shared__ uint4 lut_lds[MG_WAVES][32];            // [wavefront][row group of the block][rows 0,1 | rows 2,3]
+    __shared__ float4 coef_lds[MG_WAVES][64];          // [wavefront][row of the block]: coefficients of (T, F0, F1, F3)
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -96,7 +100,18 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     constexpr int SC_ONE = 0x7f, SC_HI = 0x81;
 
     auto compute = [&](const MgStage& cur, int gcur) {
-        if (lane < 32) lut_lds[wave][lane] = __builtin_bit_cast(uint4, cur.lut);
+        if (lane < 32) {
+            // two rows: 4 * (lane / 2) + 2 * (lane & 1) and the next one
+            const uint32_t lw[4] = {cur.lut.x, cur.lut.y, cur.lut.z, cur.lut.w};
+#pragma unroll
+            for (int rr = 0; rr < 2; ++rr) {
+                const float c0 = half_bits_to_float(static_cast<uint16_t>(lw[2 * rr] & 0xffffu));
+                const float c1 = half_bits_to_float(static_cast<uint16_t>(lw[2 * rr] >> 16));
+                const float c2 = half_bits_to_float(static_cast<uint16_t>(lw[2 * rr + 1] & 0xffffu));
+                const float c3 = half_bits_to_float(static_cast<uint16_t>(lw[2 * rr + 1] >> 16));
+                coef_lds[wave][2 * lane + rr] = make_float4(c0, c1 - c0, c2 - c0, ((c3 - c2) - c1) + c0);
+            }
+        }
         const uint32_t xw[4] = {cur.xq.x, cur.xq.y, cur.xq.z, cur.xq.w};
         v8i blo = {0, 0, 0, 0, 0, 0, 0, 0}, bhi = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -139,31 +154,26 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
                 acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bhi, acc[p][r], 4, 4, 0, SC_A[r], 0, SC_HI);
         }
 
-        // per-level sums (exact small integers in binary32) times the levels of (row, group)
+        // plane sums (exact small integers in binary32) times the coefficients of (row, group)
         const bool store_p = Pout != nullptr && i < M && gcur < NG;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            const uint4 l01 = lut_lds[wave][2 * (4 * kb + v)], l23 = lut_lds[wave][2 * (4 * kb + v) + 1];
-            const uint32_t lw[8] = {l01.x, l01.y, l01.z, l01.w, l23.x, l23.y, l23.z, l23.w};
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
+                const float4 c = coef_lds[wave][4 * (4 * kb + v) + r];
                 const float F0 = acc[0][r][v], F1 = acc[1][r][v], F3 = acc[2][r][v];
-                const float P3 = F3, P1 = F0 - F3, P2 = F1 - F3, P0 = tq[v] - F0 - F1 + F3;
-                const float c0 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r] & 0xffffu));
-                const float c1 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r] >> 16));
-                const float c2 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r + 1] & 0xffffu));
-                const float c3 = half_bits_to_float(static_cast<uint16_t>(lw[2 * r + 1] >> 16));
                 float val = o[v][r];
-                val = fmaf(c0, P0, val);
-                val = fmaf(c1, P1, val);
-                val = fmaf(c2, P2, val);
-                val = fmaf(c3, P3, val);
+                val = fmaf(c.x, tq[v], val);
+                val = fmaf(c.y, F0, val);
+                val = fmaf(c.z, F1, val);
+                val = fmaf(c.w, F3, val);
                 o[v][r] = val;
                 if (store_p) {
                     const int h = 4 * (blockIdx.x * 16 + 4 * kb + v) + r;
                     if (h < N)
                         reinterpret_cast<int4*>(Pout)[(static_cast<size_t>(i) * N + h) * NG + gcur] =
-                            make_int4(static_cast<int>(P0), static_cast<int>(P1), static_cast<int>(P2), static_cast<int>(P3));
+                            make_int4(static_cast<int>(tq[v] - F0 - F1 + F3), static_cast<int>(F0 - F3),
+                                      static_cast<int>(F1 - F3), static_cast<int>(F3));
                 }
             }
         }
