@@ -106,6 +106,18 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.rcp_set_option(b"gemv_lanes", 48) == -4
     assert lib.rcp_set_option(b"nonsense", 1) == -4
     assert lib.rcp_set_option(b"gemv_lanes", 0) == 0
+    assert lib.rcp_set_option(b"gemm_waves", 3) == -4
+    assert lib.rcp_set_option(b"gemm_waves", 8) == 0 and lib.rcp_set_option(b"gemm_waves", 0) == 0
+    assert lib.rcp_set_option(b"gemv_variant", 3) == -4
+    gmm = lib.rcp_w2a4_gemm_grouped
+    gmm.argtypes = [vp, vp, ci, ci, ci, vp, vp, ci, vp, ci, vp, vp]
+    assert gmm(fake, fake, 8, 256, 128, fake, fake, 0, fake, 0, None, None) == -2
+    assert gmm(fake, fake, 8, 256, 128, fake, fake, 17, fake, 0, None, None) == -2
+    assert gmm(fake, fake, 8, 256, 96, fake, fake, 4, fake, 0, None, None) == -4
+    qg = lib.rcp_quant_w2a4_gemv_grouped
+    qg.argtypes = [vp, vp, ci, ci, ci, vp, ci, ctypes.c_float, vp, ci, vp, vp, vp, vp]
+    assert qg(fake, fake, 8, 256, 128, fake, 0, 0.0, fake, 0, None, None, None, None) == -4   # clip ratio
+    assert qg(fake, fake, 8, 256, 128, None, 0, 1.0, fake, 0, None, None, None, None) == -1
     ws = lib.rcp_act_workspace_bytes
     ws.restype = ctypes.c_size_t
     ws.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot)]
