@@ -7,15 +7,16 @@
 // time as a packed fp16 pair, ready for v_dot2_f32_f16 against a packed pair of activations:
 //   - for row r of a cell, E_r = ((B0 >> r) & 0x1111..) | (((B1 >> r) & 0x1111..) << 1) holds
 //     the eight 2-bit indices of the row, one per nibble (5 operations for 8 weights);
-//     (built for two rows at once, about 12 operations per 32 weights);
-//   - a byte of E_r is the index pair of two neighbouring columns, t = lo + 16*hi;
+//     (built for two rows at once, about 20 operations per 32 weights);
+//   - a byte of E_r is made the index pair of two neighbouring columns, t = lo + 4*hi;
 //   - the wavefront keeps, for its current group of four rows, the 4 x 16 pairs
-//     (LUT[r][lo], LUT[r][hi]) at dword 4*r + t of a 64-dword table: the 64 entries fall into
-//     64 different LDS banks, so the 64 lanes' look-ups never conflict (equal addresses are
-//     broadcast); the two free top bits of every byte of E_r carry the wavefront's table number,
-//     so a byte times four IS the LDS address;
+//     (LUT[r][lo], LUT[r][hi]) at dword t + 16*r of a 64-dword table: the 16 entries one
+//     instruction can touch (all lanes look up the same row r) lie in 16 different LDS banks, so
+//     the look-ups never conflict (equal addresses are broadcast); the four free top bits of
+//     every byte of E_r carry r and the wavefront's table number, so a byte times four IS the
+//     LDS address;
 //   - one byte-select-and-shift (SDWA), one ds_read_b32 and one dot2 per two weights.
-// About 1.4 vector-ALU and 0.5 LDS operations per weight, against 0.69 for the W2A4 kernel.
+// About 1.6 vector-ALU and 0.5 LDS operations per weight, against 0.69 for the W2A4 kernel.
 // For bfloat16 / binary32 activations the pairs are multiplied with binary32 activations by
 // mixed-precision FMAs instead of dot2.  Accumulation is binary32 throughout.
 //
@@ -29,14 +30,13 @@ namespace rcp {
 
 constexpr int WO_THREADS = 256;
 constexpr int WO_WAVES = WO_THREADS / 64;
-constexpr int WO_UNR = 4;          // 16-byte loads per lane and pipeline stage
 constexpr int WO_TABLE_DWORDS = 64;
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-__host__ __device__ constexpr int wo_padded_units(int K)
+__host__ __device__ constexpr int wo_padded_units(int K, int span /* lanes per row group x loads per stage */)
 {
-    const int U = K / 16, span = 64 * WO_UNR;
+    const int U = K / 16;
     return ((U + span - 1) / span) * span;
 }
 
@@ -61,17 +61,26 @@ __device__ __forceinline__ uint32_t lut_half(uint2 row, int l)
 }
 
 // XF32: activations are held in LDS as binary32 (bf16 / fp32 input), else as fp16 pairs.
-template <bool XF32, int XDT, bool OUT_F16>
+// WS wavefronts share one row group (each with a table of its own; one LDS exchange of the four
+// row totals per row group): short, wide matrices would otherwise put a single wavefront on a
+// SIMD, which issues an instruction only every ~7 cycles.  UNR: 16-byte loads per lane and stage.
+template <bool XF32, int XDT, int WS, int UNR>
 __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restrict__ packed,
                                                            const uint2* __restrict__ codebook, int N, int K,
-                                                           const void* __restrict__ x, void* __restrict__ out)
+                                                           const void* __restrict__ x, void* __restrict__ out,
+                                                           int out_f16)
 {
+    constexpr int WO_UNR = UNR;
+    constexpr int SLOTS = WO_WAVES / WS;  // row groups a workgroup works on at a time
+    constexpr int LG = 64 * WS;           // lanes per row group
     extern __shared__ uint32_t wo_smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int U = K / 16, G = N / 4;
-    const int nbatch = (G + WO_WAVES - 1) / WO_WAVES;
-    const int nchunk = (U + 64 * WO_UNR - 1) / (64 * WO_UNR);
+    const int slot = wave / WS, wsub = wave % WS;
+    const int tg = wsub * 64 + lane;  // this lane's position among the LG lanes of its row group
+    const int nbatch = (G + SLOTS - 1) / SLOTS;
+    const int nchunk = (U + LG * WO_UNR - 1) / (LG * WO_UNR);
     const int nblk = gridDim.x;
     uint32_t* tab = wo_smem + wave * WO_TABLE_DWORDS;
     const uint32_t wave_bits = 0x40404040u * static_cast<uint32_t>(wave);
@@ -80,21 +89,21 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
 
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
-    const int my_units = (U % (64 * WO_UNR)) != 0 ? (U - lane + 63) / 64 : 0x7fffffff;
-    auto batch_offset = [&](int bb) -> unsigned { return (static_cast<unsigned>(bb * WO_WAVES + wave) * U + lane) * 16u; };
-    const unsigned batch_stride = static_cast<unsigned>(nblk) * WO_WAVES * U * 16u;
+    const int my_units = (U % (LG * WO_UNR)) != 0 ? (U - tg + LG - 1) / LG : 0x7fffffff;
+    auto batch_offset = [&](int bb) -> unsigned { return (static_cast<unsigned>(bb * SLOTS + slot) * U + tg) * 16u; };
+    const unsigned batch_stride = static_cast<unsigned>(nblk) * SLOTS * U * 16u;
     auto load_chunk = [&](unsigned base, int ch, int bb, u32x4 (&w)[WO_UNR]) {
-        const bool row_ok = bb * WO_WAVES + wave < G;
+        const bool row_ok = bb * SLOTS + slot < G;
 #pragma unroll
         for (int i = 0; i < WO_UNR; ++i) {
             const int it = ch * WO_UNR + i;
             const unsigned off = (it < my_units && row_ok) ? base : 0x80000000u;
-            w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), it * 64 * 16, 0);
+            w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), it * LG * 16, 0);
         }
     };
     // the four LUT rows of a row group, one per 16 table entries: lane d builds entry d
-    const int ent_r = (lane >> 2) & 3, ent_lo = lane & 3, ent_hi = lane >> 4;
-    auto load_lut = [&](int bb) -> uint2 { return codebook[min(4 * (bb * WO_WAVES + wave) + ent_r, N - 1)]; };
+    const int ent_lo = lane & 3, ent_hi = (lane >> 2) & 3, ent_r = lane >> 4;
+    auto load_lut = [&](int bb) -> uint2 { return codebook[min(4 * (bb * SLOTS + slot) + ent_r, N - 1)]; };
     auto build_table = [&](uint2 row) { tab[lane] = lut_half(row, ent_lo) | (lut_half(row, ent_hi) << 16); };
 
     int b = blockIdx.x;
@@ -104,7 +113,10 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     uint2 lut_row = load_lut(b);
 
     // stage the activations, zero beyond K
-    const int padded = wo_padded_units(K);
+    const int padded = wo_padded_units(K, LG * WO_UNR);
+    // behind the activations: the exchange slots of the row totals (WS > 1), two sets that alternate
+    float* red = reinterpret_cast<float*>(sx + padded * XD);
+    int parity = 0;
     if constexpr (!XF32) {
         const uint4* x4 = static_cast<const uint4*>(x);  // eight fp16 per uint4: two per unit
         uint4* s4 = reinterpret_cast<uint4*>(sx);
@@ -128,22 +140,24 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     // in flight while the products of the current one are taken.
     // Phase 1: the 16 pairs (LUT[r][idx of column 2jp], LUT[r][idx of column 2jp+1]).
     auto cell_lookup = [&](uint32_t B0, uint32_t B1, uint32_t (&pair)[4][4]) {
-        // C02 / C13: per nibble the 2-bit indices of rows 0 and 2 (1 and 3) of one column; wave_bits
-        // puts this wavefront's table number into the two free top bits of every byte
+        // C02 / C13: per nibble the 2-bit indices of rows 0 and 2 (1 and 3) of one column.  E[r]: per
+        // byte lo | hi << 2 (the indices of two neighbouring columns) | r << 4 | wavefront << 6, which
+        // times 4 is the byte address of the pair in LDS.
         const uint32_t C02 = (B0 & 0x55555555u) | ((B1 & 0x55555555u) << 1);
         const uint32_t C13 = ((B0 >> 1) & 0x55555555u) | (B1 & 0xaaaaaaaau);
-        const uint32_t E[4] = {(C02 & 0x33333333u) | wave_bits, (C13 & 0x33333333u) | wave_bits,
-                               ((C02 >> 2) & 0x33333333u) | wave_bits, ((C13 >> 2) & 0x33333333u) | wave_bits};
+        const uint32_t E[4] = {
+            (C02 & 0x03030303u) | ((C02 >> 2) & 0x0c0c0c0cu) | (wave_bits | 0x00000000u),
+            (C13 & 0x03030303u) | ((C13 >> 2) & 0x0c0c0c0cu) | (wave_bits | 0x10101010u),
+            ((C02 >> 2) & 0x03030303u) | ((C02 >> 4) & 0x0c0c0c0cu) | (wave_bits | 0x20202020u),
+            ((C13 >> 2) & 0x03030303u) | ((C13 >> 4) & 0x0c0c0c0cu) | (wave_bits | 0x30303030u)};
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int jp = 0; jp < 4; ++jp) {
-                // byte jp of E[r] = lo | hi << 4 | wave << 6; times 4 it is the byte address of the
-                // pair in this wavefront's table, up to the row's 16 bytes.  The read uses the
-                // absolute LDS address: the tables start at LDS offset 0 (this kernel has no static
-                // LDS, which the launcher verifies), so no base has to be added.
+                // The read uses the absolute LDS address: the tables start at LDS offset 0 (this
+                // kernel has no static LDS, which the launcher verifies), so no base has to be added.
                 const uint32_t addr = byte_times4(E[r], jp);
-                pair[r][jp] = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(addr + 16 * r);
+                pair[r][jp] = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(addr);
             }
     };
     // Phase 2: products with the cell's 8 activations.
@@ -180,29 +194,40 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
         // no work on `w` may move above the loads just issued
         __builtin_amdgcn_sched_barrier(0);
 
-        const uint32_t* xrow = sx + (lane + ch * WO_UNR * 64) * XD;
+        const uint32_t* xrow = sx + (tg + ch * WO_UNR * LG) * XD;
         uint32_t pA[4][4], pB[4][4];
         cell_lookup(w[0].x, w[0].y, pA);
 #pragma unroll
         for (int i = 0; i < WO_UNR; ++i) {
             cell_lookup(w[i].z, w[i].w, pB);
             __builtin_amdgcn_sched_barrier(0);
-            cell_dot(pA, xrow + i * 64 * XD);
+            cell_dot(pA, xrow + i * LG * XD);
             if (i + 1 < WO_UNR) cell_lookup(w[i + 1].x, w[i + 1].y, pA);
             __builtin_amdgcn_sched_barrier(0);
-            cell_dot(pB, xrow + i * 64 * XD + XD / 2);
+            cell_dot(pB, xrow + i * LG * XD + XD / 2);
         }
 
         if (last) {
             // row totals over the 64 lanes: 16-lane row rho ends up with output row 2*(rho&1) + (rho>>1)
             const float s01 = fold32f(acc[0], acc[1]);
             const float s23 = fold32f(acc[2], acc[3]);
-            const float tot = row_sum16f(fold16f(s01, s23));
-            const int rg = b * WO_WAVES + wave;
-            if (rg < G && (lane & 15) == 0) {
-                const int rho = lane >> 4;
+            float tot = row_sum16f(fold16f(s01, s23));
+            const int rho = lane >> 4;
+            if constexpr (WS > 1) {
+                // the wavefronts of a row group exchange their four totals; the first one adds them
+                float* mine = red + (parity * WO_WAVES + wave) * 4;
+                if ((lane & 15) == 0) mine[rho] = tot;
+                __syncthreads();
+                if (wsub == 0 && (lane & 15) == 0) {
+#pragma unroll
+                    for (int ws = 1; ws < WS; ++ws) tot += red[(parity * WO_WAVES + wave + ws) * 4 + rho];
+                }
+                parity ^= 1;
+            }
+            const int rg = b * SLOTS + slot;
+            if (rg < G && wsub == 0 && (lane & 15) == 0) {
                 const int h = 4 * rg + (((rho & 1) << 1) | (rho >> 1));
-                if constexpr (OUT_F16) static_cast<__half*>(out)[h] = __float2half_rn(tot);
+                if (out_f16) static_cast<__half*>(out)[h] = __float2half_rn(tot);
                 else static_cast<float*>(out)[h] = tot;
             }
             acc[0] = acc[1] = acc[2] = acc[3] = 0.0f;
@@ -220,35 +245,64 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     }
 }
 
-template <bool XF32, int XDT>
-static int launch_wo(const void* packed, const void* codebook, int N, int K, const void* x, void* out, rcp_dtype out_dt,
-                     hipStream_t st)
+template <bool XF32, int XDT, int WS, int UNR>
+static int launch_wo_one(const void* packed, const void* codebook, int N, int K, const void* x, void* out, rcp_dtype out_dt,
+                         hipStream_t st)
 {
+    constexpr int SLOTS = WO_WAVES / WS;
     const int G = N / 4;
-    const int nbatch = (G + WO_WAVES - 1) / WO_WAVES;
+    const int nbatch = (G + SLOTS - 1) / SLOTS;
     const int cus = num_compute_units();
     int blocks = options().gemv_blocks;
     if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
     if (blocks > nbatch) blocks = nbatch;
     if (blocks < 1) blocks = 1;
-    const size_t lds = (static_cast<size_t>(WO_WAVES) * WO_TABLE_DWORDS + static_cast<size_t>(wo_padded_units(K)) * (XF32 ? 16 : 8)) * 4;
+    const size_t lds = (static_cast<size_t>(WO_WAVES) * WO_TABLE_DWORDS +
+                        static_cast<size_t>(wo_padded_units(K, 64 * WS * UNR)) * (XF32 ? 16 : 8) + 2 * WO_WAVES * 4) * 4;
     if (lds > 160 * 1024)
         return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a16_gemv: K=%d needs %zu bytes of LDS for the activations", K, lds);
-    auto launch = [&](auto kernel) -> int {
-        // the look-ups address the tables by absolute LDS offset: dynamic LDS must start at 0
-        hipFuncAttributes attr;
-        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) != hipSuccess || attr.sharedSizeBytes != 0)
-            return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: kernel has static LDS, table addressing would be wrong");
-        if (lds > 65536) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               static_cast<int>(lds));
-            if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: LDS opt-in failed: %s", hipGetErrorString(e));
-        }
-        kernel<<<blocks, WO_THREADS, lds, st>>>(static_cast<const uint4*>(packed), static_cast<const uint2*>(codebook), N, K, x, out);
-        return check_launch("rcp_w2a16_gemv");
-    };
-    if (out_dt == RCP_F16) return launch(&w2a16_kernel<XF32, XDT, true>);
-    return launch(&w2a16_kernel<XF32, XDT, false>);
+    auto kernel = &w2a16_kernel<XF32, XDT, WS, UNR>;
+    // the look-ups address the tables by absolute LDS offset: dynamic LDS must start at 0
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) != hipSuccess || attr.sharedSizeBytes != 0)
+        return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: kernel has static LDS, table addressing would be wrong");
+    if (lds > 65536) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           static_cast<int>(lds));
+        if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: LDS opt-in failed: %s", hipGetErrorString(e));
+    }
+    kernel<<<blocks, WO_THREADS, lds, st>>>(static_cast<const uint4*>(packed), static_cast<const uint2*>(codebook), N, K, x, out,
+                                            out_dt == RCP_F16 ? 1 : 0);
+    return check_launch("rcp_w2a16_gemv");
+}
+
+// Shape -> (wavefronts per row group, loads per stage): enough wavefronts to give every SIMD
+// several, and no more loads per stage than a lane has units.
+template <bool XF32, int XDT>
+static int launch_wo(const void* packed, const void* codebook, int N, int K, const void* x, void* out, rcp_dtype out_dt,
+                     hipStream_t st)
+{
+    const int G = N / 4, U = K / 16;
+    const int cus = num_compute_units();
+    int ws = G <= cus * 4 ? 4 : (G <= cus * 8 ? 2 : 1);
+    const int forced = options().gemv_lanes;  // 64, 128, 256 lanes per row group
+    if (forced == 64) ws = 1;
+    if (forced == 128) ws = 2;
+    if (forced == 256) ws = 4;
+    while (ws > 1 && U < 64 * ws) ws /= 2;
+    // loads per stage: the largest of 4, 2, 1 that pads a lane's units by at most a tenth (padding
+    // units are computed on like real ones, and the kernel is bound by instruction issue)
+    const int per_lane = (U + 64 * ws - 1) / (64 * ws);
+    int unr = 1;
+    for (int c = 2; c <= 4; c *= 2)
+        if (((per_lane + c - 1) / c) * c * 10 <= per_lane * 11) unr = c;
+#define RCP_WO(WS, UNR) return launch_wo_one<XF32, XDT, WS, UNR>(packed, codebook, N, K, x, out, out_dt, st)
+    if (ws == 1) { if (unr == 4) RCP_WO(1, 4); if (unr == 2) RCP_WO(1, 2); RCP_WO(1, 1); }
+    if (ws == 2) { if (unr == 4) RCP_WO(2, 4); if (unr == 2) RCP_WO(2, 2); RCP_WO(2, 1); }
+    if (unr == 4) RCP_WO(4, 4);
+    if (unr == 2) RCP_WO(4, 2);
+    RCP_WO(4, 1);
+#undef RCP_WO
 }
 
 int launch_w2a16_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,

@@ -82,13 +82,15 @@ def test_pack_grid_edge_values():
 # ------------------------------------------------------------------------------------------
 # weight-only GEMV (16- / 32-bit activations)
 # ------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("blocks", [0, 2])
+@pytest.mark.parametrize("blocks,lanes", [(0, 0), (2, 64), (0, 128), (3, 256)])
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
 @pytest.mark.parametrize("N,K", [(4, 32), (12, 96), (256, 512), (20, 2080), (1028, 4096), (72, 11008), (40, 14336),
                                  (8, 32768)])
-def test_weight_only_gemv_close_to_oracle(N, K, dtype, blocks):
-    _say(f"weight-only gemv N={N} K={K} {dtype} blocks={blocks}")
+def test_weight_only_gemv_close_to_oracle(N, K, dtype, blocks, lanes):
+    """lanes = 64 / 128 / 256: one, two or four wavefronts per row group; 0: the library's choice."""
+    _say(f"weight-only gemv N={N} K={K} {dtype} blocks={blocks} lanes={lanes}")
     rcp.set_option("gemv_blocks", blocks)
+    rcp.set_option("gemv_lanes", lanes)
     idx = rcp_synth.random_indices(41, f"wo{N}x{K}", N, K)
     packed = oracle.pack_indices(idx)
     rng = np.random.default_rng(41)
