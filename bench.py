@@ -418,6 +418,33 @@ def main():
             grouped_step["small_batch_gemm_only_us_per_layer"][f"M{M}"] = round(sg / L * 1e6, 2)
         del gl
 
+    # activation preparation alone (latency-bound: microseconds only): rotation + int4 quantiser
+    # as one call, one token, at the rotation sizes of the BASELINE configs
+    act_us = {}
+    if not args.step_only:
+        cases = [("quant_only_4096", 4096, None), ("wht_512", 512, ("wht", 512, 1)), ("wht_2048", 2048, ("wht", 2048, 1)),
+                 ("wht_4096", 4096, ("wht", 4096, 1)), ("wht_8192", 8192, ("wht", 8192, 1)),
+                 ("kron_64x172", 11008, ("kron", 64, 172)), ("kron_512x28", 14336, ("kron", 512, 28))]
+        for label, K, r in cases:
+            xa = make_activation(torch, dev, 4242 + K, K)
+            if r is None:
+                rot = None
+            elif r[0] == "wht":
+                rot = rcp.Rotation.wht(K)
+            else:
+                rot = rcp.Rotation.kron(r[1], torch.from_numpy(rcp_synth.orthogonal(args.seed, r[2])).to(dev))
+            wsa = torch.empty(max(rcp.act_workspace_bytes(1, K, rot), 16), dtype=torch.uint8, device=dev)
+            xqa = torch.empty((1, K // 2), dtype=torch.uint8, device=dev)
+            sca = torch.empty((1,), dtype=torch.float16, device=dev)
+
+            def asweep(xa=xa, rot=rot, wsa=wsa, xqa=xqa, sca=sca):
+                for _ in range(L):
+                    rcp.rotate_quant_act(xa, rot, 1.0, xq_out=xqa, scale_out=sca, workspace=wsa)
+            asweep()
+            fn = capture(asweep)
+            fn()
+            act_us[label] = round(timed(torch, fn, reps) / L * 1e6, 3)
+
     # weight-only variant (fp16 activations, no quantiser): same packed weights, same cold sweep
     weight_only = {}
     for label, i, N in side_shapes:
@@ -467,6 +494,7 @@ def main():
         "gemv_only_GBps": round(step_bytes / sec_gemv_sweep / 1e9, 1),
         "per_shape": per_shape,
         "small_batch": small_batch,
+        "act_prep_us": act_us,
         "grouped_128": grouped,
         "grouped_128_step": grouped_step,
         "weight_only_fp16": weight_only,

@@ -84,6 +84,16 @@ __device__ __forceinline__ void register_stages(float (&v)[1 << LE], int first_b
     }
 }
 
+// Where element a of the transform lives in LDS.  Every access pattern of the kernel (EPT
+// consecutive elements per thread, and elements 2^lo apart per thread with neighbouring threads
+// on neighbouring low bits) has some index bits fixed across the lanes of a wavefront; folding
+// bits 3..5 into bits 0..2 and bits 6..7 into bits 3..4 makes each of them hit 32 different
+// banks per half wavefront (without it the first and last pass are 8- to 16-way conflicted).
+__device__ __forceinline__ int wht_slot(int a)
+{
+    return a ^ ((a >> 3) & 7) ^ (((a >> 6) & 3) << 3);
+}
+
 template <int DT, int LE, bool QUANT>
 __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict__ x, int n, int log2n, float norm,
                                                          float clip_ratio, uint32_t* __restrict__ xq,
@@ -110,7 +120,7 @@ __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict_
         }
         register_stages<LE>(v, 0);
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) sy[tid * EPT + e] = v[e];
+        for (int e = 0; e < EPT; ++e) sy[wht_slot(tid * EPT + e)] = v[e];
     }
 
     int done = LE;  // index bits whose stage is finished
@@ -123,11 +133,11 @@ __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict_
         __syncthreads();
         if (active) {
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) v[e] = sy[base | (e << lo)];
+            for (int e = 0; e < EPT; ++e) v[e] = sy[wht_slot(base | (e << lo))];
             register_stages<LE>(v, done - lo);
             // a thread writes back exactly the slots it read, so no barrier is needed here
 #pragma unroll
-            for (int e = 0; e < EPT; ++e) sy[base | (e << lo)] = v[e];
+            for (int e = 0; e < EPT; ++e) sy[wht_slot(base | (e << lo))] = v[e];
         }
         done = lo + LE;
     }
@@ -137,7 +147,7 @@ __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict_
     if (active) {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            v[e] = __fmul_rn(sy[tid * EPT + e], norm);
+            v[e] = __fmul_rn(sy[wht_slot(tid * EPT + e)], norm);
             a = fmaxf(a, fabsf(v[e]));
         }
     }
@@ -368,14 +378,15 @@ static int launch_wht(const void* x, int M, int n, float clip_ratio, void* xq, v
     auto* q = static_cast<uint32_t*>(xq);
     auto* s = static_cast<uint16_t*>(scale);
     const size_t lds = static_cast<size_t>(n) * sizeof(float);
-    if (n <= 8192) {
+    if (n <= 8192) {  // (16 elements per thread save an LDS pass but are not faster at 4096 / 8192 points)
         const int threads = ((n / 8 + 63) / 64) * 64;
         wht_quant_kernel<DT, 3, QUANT><<<M, threads, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s, y);
     } else {
-        // 64 KiB of dynamic LDS plus the static reduction slots: above the default limit
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wht_quant_kernel<DT, 4, QUANT>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));
+        if (lds + 64 > 65536) {  // 64 KiB of dynamic LDS plus the static reduction slots: above the default limit
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wht_quant_kernel<DT, 4, QUANT>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));
+        }
         wht_quant_kernel<DT, 4, QUANT><<<M, n / 16, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s, y);
     }
     return check_launch("rcp_rotate_quant_act(wht)");
