@@ -109,14 +109,17 @@ def cpu_baseline():
             y = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=rot[1], m=rot[2], Q=Q)
         xq, sc, _ = oracle.quantize_act(y.astype(np.float32), 1.0)
         t_act = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        oracle.w2a4_gemv(packed, cb, N, K, xq, sc, 1)
-        t_gemv = time.perf_counter() - t0
+        reps = []
+        for _ in range(5):  # median of five: the machine's cores are shared and single timings scatter
+            t0 = time.perf_counter()
+            oracle.w2a4_gemv(packed, cb, N, K, xq, sc, 1)
+            reps.append(time.perf_counter() - t0)
+        t_gemv = sorted(reps)[2]
         t_layer += count * t_gemv + t_act
         b_layer += count * gemv_bytes(N, K)
     return {"value": round(b_layer / t_layer / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": "one GEMV of each llama2_7b shape (4096x4096, 11008x4096, 4096x11008) + activation "
-                      "preparation, scaled to one decoder layer (4+2+1 linears); oracle C code, fp64, OpenMP",
+            "sample": "one GEMV of each llama2_7b shape (4096x4096, 11008x4096, 4096x11008; median of 5 runs each) + "
+                      "activation preparation, scaled to one decoder layer (4+2+1 linears); oracle C code, fp64, OpenMP",
             "ms_per_layer": round(t_layer * 1e3, 2)}
 
 
