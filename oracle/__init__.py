@@ -13,7 +13,7 @@ from . import build as _build
 
 _lib = None
 
-ROT_NONE, ROT_WHT, ROT_KRON = 0, 1, 2
+ROT_NONE, ROT_WHT, ROT_KRON, ROT_HEADS = 0, 1, 2, 3
 
 
 def lib():

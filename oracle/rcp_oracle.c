@@ -124,7 +124,9 @@ int rcp_ref_hadamard_matrix(int n, int8_t* out)
  *   kind 1: R = H_K                         (K = n_wht, a power of two)
  *   kind 2: R = H_{n_wht} (x) Q, K = n_wht*m: with k = i*m + j,
  *           R[(i',j'),(i,j)] = H[i'][i] * Q[j'][j]   (Kronecker product)
- * Q: m x m row-major doubles.
+ *   kind 3: R = H_{n_wht} (x) I_m, K = n_wht*m: the Hadamard matrix across n_wht heads of m
+ *           channels (Section 2.1: the online factor of R_2 applied to the self-attention output)
+ * Q: m x m row-major doubles (kind 2 only).
  */
 int rcp_ref_rotate(const double* x, int M, int K, int kind, int n_wht, int m,
                    const double* Q, double* y)
@@ -139,6 +141,8 @@ int rcp_ref_rotate(const double* x, int M, int K, int kind, int n_wht, int m,
         m = 1;
     } else if (kind == 2) {
         if (m < 1 || (long long)n_wht * m != K || Q == NULL) return RCP_REF_ERR_SHAPE;
+    } else if (kind == 3) {
+        if (m < 1 || (long long)n_wht * m != K) return RCP_REF_ERR_SHAPE;
     } else
         return RCP_REF_ERR_SHAPE;
     if (n_wht < 1 || (n_wht & (n_wht - 1)) != 0) return RCP_REF_ERR_SHAPE;
@@ -160,8 +164,12 @@ int rcp_ref_rotate(const double* x, int M, int K, int kind, int n_wht, int m,
             double acc = 0.0;
             for (int i = 0; i < n; ++i) {
                 double hij = (double)Hp[(size_t)io * n + i];
-                for (int j = 0; j < m; ++j)
-                    acc += hij * qrow[j] * xt[(size_t)i * m + j];
+                if (kind == 3) {
+                    acc += hij * xt[(size_t)i * m + jo];
+                } else {
+                    for (int j = 0; j < m; ++j)
+                        acc += hij * qrow[j] * xt[(size_t)i * m + j];
+                }
             }
             yt[ko] = acc * norm;
         }

@@ -116,3 +116,36 @@ def test_rotation_preserves_componentwise_variance():
     kurt = lambda v: ((v - v.mean()) ** 4).mean() / v.var() ** 2 - 3.0
     assert kurt(x.ravel()) < -1.0          # uniform: excess kurtosis -1.2
     assert abs(kurt(y.ravel())) < 0.05     # Kurt(Y_i) = Kurt(X)/n -> ~0
+
+
+# ---- Hadamard across heads: R = H_n (x) I_m (the online factor of R_2, Section 2.1) ------------
+@pytest.mark.parametrize("n,m", [(2, 8), (8, 16), (32, 128), (64, 24)])
+def test_heads_rotation_is_kron_of_hadamard_and_identity(n, m):
+    from scipy.linalg import hadamard
+    rng = np.random.default_rng(n * 1000 + m)
+    x = rng.standard_normal((2, n * m))
+    y = oracle.rotate(x, oracle.ROT_HEADS, n_wht=n, m=m)
+    R = np.kron(hadamard(n).astype(np.float64), np.eye(m)) / np.sqrt(n)
+    assert np.allclose(y, x @ R.T, rtol=1e-12, atol=1e-12)
+    # the general Kronecker kind with Q = I is the same operator
+    y2 = oracle.rotate(x, oracle.ROT_KRON, n_wht=n, m=m, Q=np.eye(m))
+    assert np.allclose(y, y2, rtol=1e-13, atol=1e-13)
+    # involution (H_n is symmetric and orthogonal after scaling) and norm preservation
+    assert np.allclose(oracle.rotate(y, oracle.ROT_HEADS, n_wht=n, m=m), x, rtol=1e-12, atol=1e-12)
+    assert np.allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-12)
+
+
+def test_heads_rotation_special_cases():
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal(64)
+    # one channel per head: the plain transform
+    assert np.allclose(oracle.rotate(x, oracle.ROT_HEADS, n_wht=64, m=1), oracle.rotate(x, oracle.ROT_WHT, n_wht=64))
+    # head 0 of the output is the scaled sum of the heads, channel by channel
+    X = rng.standard_normal((8, 16))
+    y = oracle.rotate(X.ravel(), oracle.ROT_HEADS, n_wht=8, m=16).reshape(8, 16)
+    assert np.allclose(y[0], X.sum(axis=0) / np.sqrt(8))
+    # binary32 butterflies column by column stay within binary32 bounds of the definition
+    y32 = oracle.fwht_f32(X.T.astype(np.float32)).T
+    assert np.allclose(y32, y, rtol=0, atol=8 * 2.0 ** -24 * np.abs(X).sum(axis=0).max())
+    with pytest.raises(RuntimeError):
+        oracle.rotate(x, oracle.ROT_HEADS, n_wht=8, m=7)
