@@ -427,13 +427,16 @@ def main():
     if not args.step_only:
         cases = [("quant_only_4096", 4096, None), ("wht_512", 512, ("wht", 512, 1)), ("wht_2048", 2048, ("wht", 2048, 1)),
                  ("wht_4096", 4096, ("wht", 4096, 1)), ("wht_8192", 8192, ("wht", 8192, 1)),
-                 ("kron_64x172", 11008, ("kron", 64, 172)), ("kron_512x28", 14336, ("kron", 512, 28))]
+                 ("kron_64x172", 11008, ("kron", 64, 172)), ("kron_512x28", 14336, ("kron", 512, 28)),
+                 ("heads_32x128", 4096, ("heads", 32, 128))]
         for label, K, r in cases:
             xa = make_activation(torch, dev, 4242 + K, K)
             if r is None:
                 rot = None
             elif r[0] == "wht":
                 rot = rcp.Rotation.wht(K)
+            elif r[0] == "heads":
+                rot = rcp.Rotation.heads(r[1], r[2])
             else:
                 rot = rcp.Rotation.kron(r[1], torch.from_numpy(rcp_synth.orthogonal(args.seed, r[2])).to(dev))
             wsa = torch.empty(max(rcp.act_workspace_bytes(1, K, rot), 16), dtype=torch.uint8, device=dev)

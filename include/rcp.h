@@ -97,7 +97,10 @@ typedef enum { RCP_F16 = 0, RCP_F32 = 1, RCP_BF16 = 2 } rcp_dtype;
 typedef enum {
     RCP_ROT_NONE = 0, /* y = x (the rotation was fused into the weights offline)   */
     RCP_ROT_WHT = 1,  /* y = H_K x, K a power of two                               */
-    RCP_ROT_KRON = 2  /* y = (H_{n_wht} (x) Q) x, K = n_wht * m                    */
+    RCP_ROT_KRON = 2, /* y = (H_{n_wht} (x) Q) x, K = n_wht * m                    */
+    RCP_ROT_HEADS = 3 /* y = (H_{n_wht} (x) I_m) x: Hadamard across n_wht heads of m channels (the online
+                         rotation of the self-attention output before the out-projection, Section 2.1);
+                         2 <= n_wht <= 64, m a multiple of 8, K <= RCP_MAX_WHT; Q is ignored              */
 } rcp_rot_kind;
 
 /* Rotation descriptor (a host struct).  For RCP_ROT_KRON, x is viewed as an
@@ -106,8 +109,8 @@ typedef enum {
  * an m x m row-major fp32 orthogonal matrix; it is ignored for the other kinds. */
 typedef struct {
     int kind;       /* rcp_rot_kind                                                */
-    int n_wht;      /* power of two: K for RCP_ROT_WHT, the Hadamard factor for KRON */
-    int m;          /* order of Q (1 for RCP_ROT_WHT)                              */
+    int n_wht;      /* power of two: K for RCP_ROT_WHT, the Hadamard factor for KRON, the number of heads for HEADS */
+    int m;          /* order of Q (1 for RCP_ROT_WHT); channels per head for HEADS   */
     const float* Q; /* device, m*m floats, row-major                               */
 } rcp_rotation;
 

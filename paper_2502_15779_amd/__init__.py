@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "librcp.so")
 
 F16, F32, BF16 = 0, 1, 2
-ROT_NONE, ROT_WHT, ROT_KRON = 0, 1, 2
+ROT_NONE, ROT_WHT, ROT_KRON, ROT_HEADS = 0, 1, 2, 3
 MAX_M = 16
 GROUP = 128  # input channels per quantisation unit of the *_grouped calls
 
@@ -48,6 +48,11 @@ class Rotation:
     @staticmethod
     def wht(n):
         return Rotation(ROT_WHT, n_wht=n)
+
+    @staticmethod
+    def heads(n_heads, head_dim):
+        """Hadamard across heads: y = (H_{n_heads} (x) I_{head_dim}) x."""
+        return Rotation(ROT_HEADS, n_wht=n_heads, m=head_dim)
 
     @staticmethod
     def kron(n_wht, Q):

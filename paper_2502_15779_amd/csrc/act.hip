@@ -332,6 +332,68 @@ __global__ __launch_bounds__(KRON_THREADS) void kron_wave_kernel(const void* __r
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Hadamard rotation across heads: y = (H_n (x) I_m) x, x viewed as n heads of m channels
+// (the online rotation of the self-attention output in front of the out-projection; Section 2.1:
+// R_2 is split into a per-head factor that is folded into the V projection and this
+// across-heads factor).  One workgroup per token: the token is widened into LDS, a thread takes
+// whole columns j (the n values x[i*m + j]), transforms them in registers in ascending stride
+// order -- the same butterflies as the order-n transform of a contiguous vector -- and the
+// quantiser tail is that of the other kernels.
+// ---------------------------------------------------------------------------------------
+constexpr int HEADS_THREADS = 256;
+
+template <int DT, int NH, bool QUANT>
+__global__ __launch_bounds__(HEADS_THREADS) void heads_wht_kernel(const void* __restrict__ x, int m, float norm,
+                                                                  float clip_ratio, uint32_t* __restrict__ xq,
+                                                                  uint16_t* __restrict__ scale, float* __restrict__ y_out)
+{
+    extern __shared__ float sy[];  // K floats
+    __shared__ float red[16];
+    const int token = blockIdx.x;
+    const int K = NH * m;
+    for (int u = threadIdx.x; u < K / 8; u += HEADS_THREADS) {
+        float t8[8];
+        load8_as_float<DT>(x, static_cast<size_t>(token) * K + static_cast<size_t>(u) * 8, t8);
+        reinterpret_cast<float4*>(sy)[2 * u] = make_float4(t8[0], t8[1], t8[2], t8[3]);
+        reinterpret_cast<float4*>(sy)[2 * u + 1] = make_float4(t8[4], t8[5], t8[6], t8[7]);
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < m; j += HEADS_THREADS) {
+        float v[NH];
+#pragma unroll
+        for (int i = 0; i < NH; ++i) v[i] = sy[i * m + j];
+#pragma unroll
+        for (int s = 1; s < NH; s <<= 1)
+#pragma unroll
+            for (int i = 0; i < NH; ++i)
+                if ((i & s) == 0) {
+                    const float p = v[i], q = v[i + s];
+                    v[i] = p + q;
+                    v[i + s] = p - q;
+                }
+#pragma unroll
+        for (int i = 0; i < NH; ++i) sy[i * m + j] = __fmul_rn(v[i], norm);
+    }
+    __syncthreads();
+    if constexpr (!QUANT) {
+        for (int u = threadIdx.x; u < K / 4; u += HEADS_THREADS)
+            reinterpret_cast<float4*>(y_out + static_cast<size_t>(token) * K)[u] = reinterpret_cast<const float4*>(sy)[u];
+        return;
+    }
+    float a = 0.0f;
+    for (int u = threadIdx.x; u < K; u += HEADS_THREADS) a = fmaxf(a, fabsf(sy[u]));
+    a = block_max(a, red);
+    const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
+    const float sc = half_bits_to_float(sb);
+    for (int u = threadIdx.x; u < K / 8; u += HEADS_THREADS) {
+        const float4 lo4 = reinterpret_cast<const float4*>(sy)[2 * u], hi4 = reinterpret_cast<const float4*>(sy)[2 * u + 1];
+        const float t8[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+        xq[static_cast<size_t>(token) * (K / 8) + u] = quantize8(t8, sc);
+    }
+    if (threadIdx.x == 0) scale[token] = sb;
+}
+
 // x -> binary32 copy (rotation "none" of the rotation-only entry point)
 template <int DT>
 __global__ __launch_bounds__(256) void widen_kernel(const void* __restrict__ x, size_t groups, float* __restrict__ y)
@@ -434,6 +496,40 @@ static int launch_kron(const void* x, int M, int K, const rcp_rotation* rot, flo
     return check_launch("rcp_rotate_quant_act(kron)");
 }
 
+template <int DT, bool QUANT>
+static int launch_heads(const void* x, int M, int K, const rcp_rotation* rot, float clip_ratio, void* xq, void* scale,
+                        float* y, hipStream_t st)
+{
+    const int n = rot->n_wht, m = rot->m;
+    const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(n)));
+    const size_t lds = static_cast<size_t>(K) * sizeof(float);
+    auto* q = static_cast<uint32_t*>(xq);
+    auto* s = static_cast<uint16_t*>(scale);
+#define RCP_HEADS(NH)                                                                                              \
+    case NH: {                                                                                                     \
+        auto kernel = &heads_wht_kernel<DT, NH, QUANT>;                                                            \
+        if (lds + 64 > 65536) {                                                                                    \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),                              \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)); \
+            if (e != hipSuccess)                                                                                   \
+                return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));     \
+        }                                                                                                          \
+        kernel<<<M, HEADS_THREADS, lds, st>>>(x, m, norm, clip_ratio, q, s, y);                                    \
+        break;                                                                                                     \
+    }
+    switch (n) {
+        RCP_HEADS(2)
+        RCP_HEADS(4)
+        RCP_HEADS(8)
+        RCP_HEADS(16)
+        RCP_HEADS(32)
+        RCP_HEADS(64)
+        default: return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act: %d heads not supported (2 .. 64)", n);
+    }
+#undef RCP_HEADS
+    return check_launch("rcp_rotate_quant_act(heads)");
+}
+
 template <int DT>
 static int launch_act_typed(const void* x, int M, int K, const rcp_rotation* rot, float clip_ratio, void* xq,
                             void* scale, void* ws, hipStream_t st)
@@ -441,6 +537,7 @@ static int launch_act_typed(const void* x, int M, int K, const rcp_rotation* rot
     const int kind = rot ? rot->kind : RCP_ROT_NONE;
     if (kind == RCP_ROT_NONE) return launch_quant<DT>(x, M, K, clip_ratio, xq, scale, st);
     if (kind == RCP_ROT_WHT) return launch_wht<DT, true>(x, M, K, clip_ratio, xq, scale, nullptr, st);
+    if (kind == RCP_ROT_HEADS) return launch_heads<DT, true>(x, M, K, rot, clip_ratio, xq, scale, nullptr, st);
     if (int rc = launch_kron<DT>(x, M, K, rot, static_cast<float*>(ws), st)) return rc;
     return launch_quant<RCP_F32>(ws, M, K, clip_ratio, xq, scale, st);
 }
@@ -461,6 +558,7 @@ static int launch_rotate_typed(const void* x, int M, int K, const rcp_rotation* 
     const int kind = rot ? rot->kind : RCP_ROT_NONE;
     if (kind == RCP_ROT_WHT) return launch_wht<DT, false>(x, M, K, 1.0f, nullptr, nullptr, y, st);
     if (kind == RCP_ROT_KRON) return launch_kron<DT>(x, M, K, rot, y, st);
+    if (kind == RCP_ROT_HEADS) return launch_heads<DT, false>(x, M, K, rot, 1.0f, nullptr, nullptr, y, st);
     const size_t groups = static_cast<size_t>(M) * K / 8;
     widen_kernel<DT><<<static_cast<unsigned>((groups + 255) / 256), 256, 0, st>>>(x, groups, y);
     return check_launch("rcp_rotate_act");

@@ -79,6 +79,15 @@ static int check_rotation(const char* fn, int K, const rcp_rotation* rot)
         if (!aligned16(rot->Q)) return fail(RCP_ERR_ALIGN, "%s: Q is not 16-byte aligned", fn);
         return RCP_OK;
     }
+    if (rot->kind == RCP_ROT_HEADS) {
+        if (!pow2(rot->n_wht) || rot->m < 1 || static_cast<long long>(rot->n_wht) * rot->m != K)
+            return fail(RCP_ERR_SHAPE, "%s: HEADS needs n_wht (power of two) * m == K (n_wht=%d, m=%d, K=%d)", fn,
+                        rot->n_wht, rot->m, K);
+        if (rot->n_wht < 2 || rot->n_wht > 64) return fail(RCP_ERR_UNSUPPORTED, "%s: HEADS with %d heads (2 .. 64 supported)", fn, rot->n_wht);
+        if (rot->m % 8 != 0) return fail(RCP_ERR_SHAPE, "%s: HEADS needs a head size that is a multiple of 8 (m=%d)", fn, rot->m);
+        if (K > RCP_MAX_WHT) return fail(RCP_ERR_UNSUPPORTED, "%s: HEADS rotation of K=%d exceeds %d", fn, K, RCP_MAX_WHT);
+        return RCP_OK;
+    }
     return fail(RCP_ERR_UNSUPPORTED, "%s: unknown rotation kind %d", fn, rot->kind);
 }
 

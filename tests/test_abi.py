@@ -78,6 +78,11 @@ def test_argument_errors_need_no_gpu(lib):
     assert act(fake, 0, 1, 96, ctypes.byref(Rot(2, 32, 3, fake)), 1.0, fake, fake, None, 0, None) == -5
     assert b"workspace" in lib.rcp_last_error()
     assert act(fake, 0, 1, 64, ctypes.byref(Rot(9, 0, 0, None)), 1.0, fake, fake, None, 0, None) == -4
+    # across-heads Hadamard: heads a power of two in 2..64, head size a multiple of 8, heads * size == K
+    assert act(fake, 0, 1, 4096, ctypes.byref(Rot(3, 32, 64, None)), 1.0, fake, fake, None, 0, None) == -2
+    assert act(fake, 0, 1, 4096, ctypes.byref(Rot(3, 128, 32, None)), 1.0, fake, fake, None, 0, None) == -4
+    assert act(fake, 0, 1, 96, ctypes.byref(Rot(3, 8, 12, None)), 1.0, fake, fake, None, 0, None) == -2
+    assert act(fake, 0, 1, 96, ctypes.byref(Rot(3, 6, 16, None)), 1.0, fake, fake, None, 0, None) == -2
     ci = ctypes.c_int
     gg = lib.rcp_w2a4_gemv_grouped
     gg.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, ci, vp, vp]

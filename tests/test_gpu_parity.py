@@ -638,6 +638,42 @@ def test_rotation_only_entry_point(kind, M, n, m):
 # ------------------------------------------------------------------------------------------
 # whole path
 # ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("M,n,m,ratio", [(1, 32, 128, 1.0), (3, 8, 64, 0.9), (1, 64, 128, 1.0), (2, 2, 16, 1.0), (1, 32, 64, 1.0),
+                                         (16, 32, 128, 1.0), (1, 64, 256, 1.0)])
+def test_heads_rotation_bit_exact_against_binary32_butterfly(M, n, m, ratio, dtype):
+    """y = (H_n (x) I_m) x with binary32 butterflies in ascending stride order per column: x_q, S and
+    the rotation-only output must equal the oracle's bit for bit."""
+    _say(f"heads rotation M={M} n={n} m={m} ratio={ratio} {dtype}")
+    K = n * m
+    x16 = rcp_synth.activation(81, f"heads{K}", M, K)
+    xd = {"f16": _t(x16), "bf16": _t(x16.astype(np.float32)).to(torch.bfloat16),
+          "f32": _t(x16.astype(np.float32) * np.float32(1.0009765))}[dtype]
+    x32 = xd.to(torch.float32).cpu().numpy()
+    rot = rcp.Rotation.heads(n, m)
+    xq, sc = rcp.rotate_quant_act(xd, rot, ratio)
+    y = rcp.rotate_act(xd, rot)
+    torch.cuda.synchronize()
+    # oracle: order-n butterflies on every column of the n x m view
+    y32 = np.stack([oracle.fwht_f32(x32[t].reshape(n, m).T.copy()).T.reshape(K) for t in range(M)])
+    assert np.array_equal(y.cpu().numpy(), y32)
+    ref_xq, ref_sc, _ = oracle.quantize_act(y32, ratio)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+    # and the binary32 result is the dense binary64 definition within binary32 bounds
+    y64 = oracle.rotate(x32.astype(np.float64), oracle.ROT_HEADS, n_wht=n, m=m)
+    assert np.all(np.abs(y32 - y64) <= 16 * 2.0 ** -24 * np.abs(x32).reshape(M, n, m).sum(axis=1).max())
+
+
+def test_heads_rotation_argument_errors():
+    x = torch.zeros((1, 4096), dtype=torch.float16, device=DEV)
+    for n, m in ((128, 32), (32, 100), (3, 1024)):
+        with pytest.raises((rcp.RcpError, AssertionError)):
+            rcp.rotate_quant_act(torch.zeros((1, n * m), dtype=torch.float16, device=DEV), rcp.Rotation.heads(n, m))
+    with pytest.raises(rcp.RcpError):
+        rcp.rotate_quant_act(x, rcp.Rotation.heads(32, 64))       # 32 * 64 != 4096
+
+
 def _rotation(rot, seed):
     if rot is None:
         return None, dict(kind=oracle.ROT_NONE)
