@@ -229,6 +229,19 @@ int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
                         int32_t* partial_sums_or_null, void* stream);
 
 /*
+ * rcp_quant_w2a4_gemv with an online rotation inside the same launch: rot = NULL / RCP_ROT_NONE is
+ * rcp_quant_w2a4_gemv; RCP_ROT_HEADS (K <= 16384) applies the Hadamard matrix across heads in
+ * the prologue of the GEMV kernel and is bit-identical to rcp_rotate_quant_act(RCP_ROT_HEADS)
+ * followed by rcp_w2a4_gemv.  The other kinds return RCP_ERR_UNSUPPORTED: a transform over all of
+ * K would be repeated by every workgroup; run rcp_rotate_act first.  rot: host pointer.
+ */
+int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
+                               const void* x, rcp_dtype x_dtype, const rcp_rotation* rot, float clip_ratio,
+                               void* out, rcp_dtype out_dtype,
+                               void* xq_out_or_null, void* scale_out_or_null,
+                               int32_t* partial_sums_or_null, void* stream);
+
+/*
  * Weight-only GEMV (the W2-only decode variant of the paper's inference-latency section:
  * non-uniform dequantisation merged into a 16-bit linear layer), one token:
  *     O[h] = sum_k LUT[h][idx[h][k]] * x[k]          (binary32 accumulation)

@@ -110,6 +110,9 @@ def lib():
         L.rcp_w2a4_gemm_grouped.argtypes = [vp, vp, ci, ci, ci, vp, vp, ci, vp, ci, vp, vp]
         L.rcp_quant_w2a4_gemv_grouped.restype = ci
         L.rcp_quant_w2a4_gemv_grouped.argtypes = [vp, vp, ci, ci, ci, vp, ci, ctypes.c_float, vp, ci, vp, vp, vp, vp]
+        L.rcp_rotate_quant_w2a4_gemv.restype = ci
+        L.rcp_rotate_quant_w2a4_gemv.argtypes = [vp, vp, ci, ci, vp, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, ci,
+                                                 vp, vp, vp, vp]
         L.rcp_w2a16_gemv.restype = ci
         L.rcp_w2a16_gemv.argtypes = [vp, vp, ci, ci, vp, ci, vp, ci, vp]
         _lib = L
@@ -387,4 +390,30 @@ def w2a4_gemm_grouped(packed, codebook, N, K, xq, scale, M, group=GROUP, out=Non
                                        _dev(xq, "xq"), _dev(scale, "scale"), M, _dev(out, "out"), _DTYPES[out.dtype],
                                        _dev(partial_sums, "partial_sums") if partial_sums is not None else None,
                                        _stream()))
+    return (out, partial_sums) if partial_sums is not None else out
+
+
+def rotate_quant_w2a4_gemv(packed, codebook, N, K, x, rot=None, clip_ratio=1.0, out=None, out_dtype=torch.float16,
+                           xq_out=None, scale_out=None, partial_sums=None, want_partial_sums=False):
+    """One token: rotation (none or across heads), quantiser and GEMV in a single launch -> out [1, N]."""
+    if x.numel() != K or x.dtype not in _DTYPES:
+        raise ValueError("x must hold K values of float16, bfloat16 or float32")
+    if out is None:
+        out = torch.empty((1, N), dtype=out_dtype, device=packed.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < N:
+        raise ValueError("out must be float16 or float32 with N elements")
+    if want_partial_sums and partial_sums is None:
+        partial_sums = torch.empty((1, N, 4), dtype=torch.int32, device=packed.device)
+    if packed.numel() * packed.element_size() < N * K // 4 or codebook.numel() < 4 * N:
+        raise ValueError("packed / codebook buffers do not match N, K")
+    if xq_out is not None and xq_out.numel() * xq_out.element_size() < K // 2:
+        raise ValueError("xq_out too small")
+    if partial_sums is not None and (partial_sums.dtype != torch.int32 or partial_sums.numel() < 4 * N):
+        raise ValueError("partial_sums must be int32 [1, N, 4]")
+    opt = lambda t, name: _dev(t, name) if t is not None else None
+    _check(lib().rcp_rotate_quant_w2a4_gemv(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, _dev(x, "x"),
+                                            _DTYPES[x.dtype], ctypes.byref(rot._c) if rot is not None else None,
+                                            ctypes.c_float(clip_ratio), _dev(out, "out"), _DTYPES[out.dtype],
+                                            opt(xq_out, "xq_out"), opt(scale_out, "scale_out"),
+                                            opt(partial_sums, "partial_sums"), _stream()))
     return (out, partial_sums) if partial_sums is not None else out

@@ -258,12 +258,41 @@ int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (quant_gemv_supported(K))
         return launch_quant_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
-                                 scale_out_or_null, partial_sums_or_null, st);
+                                 scale_out_or_null, partial_sums_or_null, 0, 0, st);
     // K too large for the in-kernel quantiser: two launches through the caller's x_q / S buffers
     if (!xq_out_or_null || !scale_out_or_null)
         return fail(RCP_ERR_WORKSPACE, "rcp_quant_w2a4_gemv: K=%d needs xq_out and scale_out as scratch", K);
     if (int rc = launch_act(x, x_dtype, 1, K, nullptr, clip_ratio, xq_out_or_null, scale_out_or_null, nullptr, 0, st)) return rc;
     return launch_gemv(packed, codebook, N, K, xq_out_or_null, scale_out_or_null, 1, out, out_dtype, partial_sums_or_null, st);
+}
+
+int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K, const void* x,
+                               rcp_dtype x_dtype, const rcp_rotation* rot, float clip_ratio, void* out,
+                               rcp_dtype out_dtype, void* xq_out_or_null, void* scale_out_or_null,
+                               int32_t* partial_sums_or_null, void* stream)
+{
+    if (rot == nullptr || rot->kind == RCP_ROT_NONE)
+        return rcp_quant_w2a4_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
+                                   scale_out_or_null, partial_sums_or_null, stream);
+    if (!packed || !codebook || !x || !out) return fail(RCP_ERR_NULL, "rcp_rotate_quant_w2a4_gemv: NULL pointer argument");
+    if (int rc = check_shape("rcp_rotate_quant_w2a4_gemv", N, K)) return rc;
+    if (rot->kind != RCP_ROT_HEADS)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_w2a4_gemv: only RCP_ROT_NONE and RCP_ROT_HEADS run inside the "
+                                         "GEMV; use rcp_rotate_act + rcp_quant_w2a4_gemv for kind %d", rot->kind);
+    if (int rc = check_rotation("rcp_rotate_quant_w2a4_gemv", K, rot)) return rc;
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_w2a4_gemv: unknown dtype %d", static_cast<int>(x_dtype));
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_w2a4_gemv: out_dtype must be RCP_F16 or RCP_F32");
+    if (!(clip_ratio > 0.0f) || !(clip_ratio <= 1.0f))
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_w2a4_gemv: clip_ratio %g outside (0, 1]", static_cast<double>(clip_ratio));
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(x) || !aligned16(out) || !aligned16(xq_out_or_null) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_w2a4_gemv: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale_out_or_null) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_w2a4_gemv: scale_out must be 2-byte aligned");
+    return launch_quant_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
+                             scale_out_or_null, partial_sums_or_null, rot->n_wht, rot->m, static_cast<hipStream_t>(stream));
 }
 
 int rcp_w2a16_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dtype,

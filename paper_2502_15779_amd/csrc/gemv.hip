@@ -25,6 +25,8 @@
 // pipelined over (row group, chunk of UNR units): the loads of the next step are in flight
 // while the current one is computed and reduced, and the very first loads are issued
 // before the activations are staged.
+#include <math.h>
+
 #include "rcp_internal.hpp"
 
 namespace rcp {
@@ -95,7 +97,33 @@ __host__ __device__ constexpr int gemv_x_bytes(int K, int M, int span /* LG * UN
 // (one token only): `xraw` is the raw activation of that type and the workgroup quantises it
 // itself, exactly as quant_kernel would (amax, S = fp16(ratio*amax/7), q = rint(x/S)); the
 // first workgroup also writes x_q and S to xq_out / scale_out when those are given.
+// XDT = 4 + type: before quantising, the workgroup also applies the Hadamard rotation across
+// heads, y = (H_n (x) I_m) x (rot_n heads of rot_m channels), with the butterflies and the final
+// scaling of heads_wht_kernel, i.e. bit-identical to rcp_rotate_quant_act with RCP_ROT_HEADS.
 constexpr int GEMV_XG = 8;  // groups of eight raw activations a thread can hold: K <= 16384
+
+// Order-NH Hadamard transform down the columns of the NH x m matrix in LDS (ascending stride, one
+// IEEE add / sub per butterfly, one multiply by `norm` at the end): a thread takes whole columns.
+template <int NH>
+__device__ __forceinline__ void heads_columns(float* sy, int m, float norm)
+{
+    for (int j = threadIdx.x; j < m; j += GEMV_THREADS) {
+        float v[NH];
+#pragma unroll
+        for (int i = 0; i < NH; ++i) v[i] = sy[i * m + j];
+#pragma unroll
+        for (int st = 1; st < NH; st <<= 1)
+#pragma unroll
+            for (int i = 0; i < NH; ++i)
+                if ((i & st) == 0) {
+                    const float p = v[i], q = v[i + st];
+                    v[i] = p + q;
+                    v[i + st] = p - q;
+                }
+#pragma unroll
+        for (int i = 0; i < NH; ++i) sy[i * m + j] = __fmul_rn(v[i], norm);
+    }
+}
 
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT>
 __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restrict__ packed,
@@ -104,10 +132,13 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
                                                             const uint16_t* __restrict__ scale, int M,
                                                             void* __restrict__ out, int32_t* __restrict__ Pout,
                                                             const void* __restrict__ xraw, float clip_ratio,
-                                                            uint32_t* __restrict__ xq_out, uint16_t* __restrict__ scale_out)
+                                                            uint32_t* __restrict__ xq_out, uint16_t* __restrict__ scale_out,
+                                                            int rot_n, int rot_m, float rot_norm)
 {
     static_assert(WS == 1 || LW == 64, "several wavefronts per row group only with whole wavefronts");
     static_assert(XDT < 0 || MT == 1, "the fused quantiser handles one token");
+    constexpr bool ROT = XDT >= 4;              // Hadamard across heads in the prologue
+    constexpr int XT = XDT >= 0 ? (XDT & 3) : 0;  // storage type of the raw activation
     extern __shared__ uint4 smem4[];
     constexpr int SW = 64 / LW;                     // row groups side by side in a wavefront
     constexpr int SLOTS = (GEMV_WAVES / WS) * SW;   // row groups a workgroup works on at a time
@@ -169,7 +200,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         for (int i = 0; i < GEMV_XG; ++i) {
             if (i * GEMV_THREADS >= xdw) break;  // uniform: whole blocks of 256 groups
             const int u8 = min(static_cast<int>(threadIdx.x) + i * GEMV_THREADS, xdw - 1);  // clamped: duplicates are harmless
-            load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u8) * 8, xr8[i]);
+            load8_as_float<XT>(xraw, static_cast<size_t>(u8) * 8, xr8[i]);
         }
     }
 
@@ -209,6 +240,38 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
             if (lane == 0) tsum[wave * MT + t] = s;
         }
     } else {
+        if constexpr (ROT) {
+            // y = (H_n (x) I_m) x through LDS: every thread parks its values, then takes whole columns
+            // (the rot_n values x[i*m + j]) through the butterflies in ascending stride order
+            float* sy = reinterpret_cast<float*>(red + (WS > 1 ? 2 * GEMV_WAVES * 4 * 3 * MT : 0));
+#pragma unroll
+            for (int i = 0; i < GEMV_XG; ++i) {
+                if (i * GEMV_THREADS >= xdw) break;
+                const int u8 = threadIdx.x + i * GEMV_THREADS;
+                if (u8 < xdw) {
+                    reinterpret_cast<float4*>(sy)[2 * u8] = make_float4(xr8[i][0], xr8[i][1], xr8[i][2], xr8[i][3]);
+                    reinterpret_cast<float4*>(sy)[2 * u8 + 1] = make_float4(xr8[i][4], xr8[i][5], xr8[i][6], xr8[i][7]);
+                }
+            }
+            __syncthreads();
+            switch (rot_n) {  // uniform; the head count must be a compile-time constant for the registers
+                case 2: heads_columns<2>(sy, rot_m, rot_norm); break;
+                case 4: heads_columns<4>(sy, rot_m, rot_norm); break;
+                case 8: heads_columns<8>(sy, rot_m, rot_norm); break;
+                case 16: heads_columns<16>(sy, rot_m, rot_norm); break;
+                case 32: heads_columns<32>(sy, rot_m, rot_norm); break;
+                default: heads_columns<64>(sy, rot_m, rot_norm); break;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < GEMV_XG; ++i) {
+                if (i * GEMV_THREADS >= xdw) break;
+                const int u8 = min(static_cast<int>(threadIdx.x) + i * GEMV_THREADS, xdw - 1);
+                const float4 lo4 = reinterpret_cast<const float4*>(sy)[2 * u8], hi4 = reinterpret_cast<const float4*>(sy)[2 * u8 + 1];
+                xr8[i][0] = lo4.x; xr8[i][1] = lo4.y; xr8[i][2] = lo4.z; xr8[i][3] = lo4.w;
+                xr8[i][4] = hi4.x; xr8[i][5] = hi4.y; xr8[i][6] = hi4.z; xr8[i][7] = hi4.w;
+            }
+        }
         // per-token symmetric int4 quantiser, the same arithmetic as quant_kernel
         float a = 0.0f;
 #pragma unroll
@@ -392,13 +455,15 @@ struct GemvArgs {
     rcp_dtype x_dt;
     float clip_ratio;
     void *xq_out, *scale_out;
+    int rot_n, rot_m;  // Hadamard across rot_n heads of rot_m channels in the prologue (0: none)
 };
 
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT>
 static int launch_one(const GemvArgs& a, int blocks, hipStream_t st)
 {
     const size_t lds = gemv_x_bytes(a.K, a.M, LW * WS * UNR) + (GEMV_WAVES * MT + 4) * sizeof(int) +
-                       (WS > 1 ? 2 * GEMV_WAVES * 4 * 3 * MT * sizeof(int) : 0);
+                       (WS > 1 ? 2 * GEMV_WAVES * 4 * 3 * MT * sizeof(int) : 0) +
+                       (XDT >= 4 ? static_cast<size_t>(a.K) * sizeof(float) + 16 : 0);
     if (lds > 160 * 1024)
         return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a4_gemv: M*K/2 = %d bytes of activations exceed the LDS budget", a.M * (a.K / 2));
     auto kernel = &gemv_kernel<LW, WS, UNR, MT, OUT_F16, XDT>;
@@ -410,7 +475,8 @@ static int launch_one(const GemvArgs& a, int blocks, hipStream_t st)
     kernel<<<blocks, GEMV_THREADS, lds, st>>>(
         static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K,
         static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.M, a.out, a.P, a.xraw, a.clip_ratio,
-        static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
+        static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out), a.rot_n, a.rot_m,
+        a.rot_n > 0 ? static_cast<float>(1.0 / sqrt(static_cast<double>(a.rot_n))) : 1.0f);
     return check_launch("rcp_w2a4_gemv");
 }
 
@@ -421,6 +487,13 @@ static int launch_mt(const GemvArgs& a, int blocks, hipStream_t st)
     return a.out_dt == RCP_F16 ? launch_one<LW, WS, UNR, MT, true, XDT>(a, blocks, st)    \
                                : launch_one<LW, WS, UNR, MT, false, XDT>(a, blocks, st)
     if (a.xraw != nullptr) {
+        if constexpr (LW == 64 && WS == 1) {  // the rotating prologue exists for one wavefront per row group only
+            if (a.rot_n > 0) {
+                if (a.x_dt == RCP_F16) RCP_GO(1, 4 + RCP_F16);
+                if (a.x_dt == RCP_F32) RCP_GO(1, 4 + RCP_F32);
+                RCP_GO(1, 4 + RCP_BF16);
+            }
+        }
         if (a.x_dt == RCP_F16) RCP_GO(1, RCP_F16);
         if (a.x_dt == RCP_F32) RCP_GO(1, RCP_F32);
         RCP_GO(1, RCP_BF16);
@@ -481,7 +554,13 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
     const bool many = a.M > GEMM_MFMA_MIN_M || (a.M == GEMM_MFMA_MIN_M && a.N >= 8192);
     if (a.xraw == nullptr && variant != 1 && (variant == 2 || many))
         return launch_gemm_mfma(a.packed, a.codebook, a.N, a.K, a.xq, a.scale, a.M, a.out, a.out_dt, a.P, st);
-    const GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
+    GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
+    if (a.rot_n > 0) {  // rotating prologue: one wavefront per row group
+        p.lw = 64;
+        p.ws = 1;
+        const int nbatch = (a.N / 4 + GEMV_WAVES - 1) / GEMV_WAVES;
+        if (p.blocks > nbatch) p.blocks = nbatch;
+    }
     if (p.unr == 2) {
         switch (p.lw * p.ws) {
             case 16: return launch_mt<16, 1, 2>(a, p.blocks, st);
@@ -503,7 +582,7 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
 {
-    const GemvArgs a = {packed, codebook, N, K, xq, scale, M, out, out_dt, P, nullptr, RCP_F16, 1.0f, nullptr, nullptr};
+    const GemvArgs a = {packed, codebook, N, K, xq, scale, M, out, out_dt, P, nullptr, RCP_F16, 1.0f, nullptr, nullptr, 0, 0};
     return dispatch_gemv(a, st);
 }
 
@@ -511,9 +590,10 @@ bool quant_gemv_supported(int K) { return K / 8 <= GEMV_XG * GEMV_THREADS; }
 
 int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
                       float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
-                      hipStream_t st)
+                      int rot_heads, int rot_head_dim, hipStream_t st)
 {
-    const GemvArgs a = {packed, codebook, N, K, nullptr, nullptr, 1, out, out_dt, P, x, x_dt, clip_ratio, xq_out, scale_out};
+    const GemvArgs a = {packed, codebook, N, K, nullptr, nullptr, 1, out, out_dt, P, x, x_dt, clip_ratio, xq_out, scale_out,
+                        rot_heads, rot_head_dim};
     return dispatch_gemv(a, st);
 }
 

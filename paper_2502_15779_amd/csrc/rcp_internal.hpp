@@ -58,10 +58,11 @@ int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, con
                      int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 int launch_gemm_mfma_grouped(const void* packed, const void* codebook, int N, int K, const void* xq,
                              const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
-// fused quantise + GEMV for one token; x is the raw activation, xq_out / scale_out optional
+// fused quantise + GEMV for one token; x is the raw activation, xq_out / scale_out optional;
+// rot_heads > 0: Hadamard across rot_heads heads of rot_head_dim channels applied in the prologue
 int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
                       float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
-                      hipStream_t st);
+                      int rot_heads, int rot_head_dim, hipStream_t st);
 bool quant_gemv_supported(int K);
 
 // ---- small device helpers ------------------------------------------------------------

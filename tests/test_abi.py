@@ -31,7 +31,8 @@ def test_every_declared_function_is_exported(lib):
             "rcp_packed_bytes", "rcp_act_workspace_bytes", "rcp_last_error", "rcp_version",
             "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act", "rcp_stream_read",
             "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped",
-            "rcp_w2a16_gemv", "rcp_quant_w2a4_gemv_grouped", "rcp_w2a4_gemm_grouped"} <= set(names)
+            "rcp_w2a16_gemv", "rcp_quant_w2a4_gemv_grouped", "rcp_w2a4_gemm_grouped",
+            "rcp_rotate_quant_w2a4_gemv"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

@@ -665,6 +665,37 @@ def test_heads_rotation_bit_exact_against_binary32_butterfly(M, n, m, ratio, dty
     assert np.all(np.abs(y32 - y64) <= 16 * 2.0 ** -24 * np.abs(x32).reshape(M, n, m).sum(axis=1).max())
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("N,n,m,ratio", [(1028, 32, 128, 1.0), (64, 8, 64, 0.9), (256, 64, 128, 1.0), (16, 2, 16, 1.0),
+                                         (4096, 32, 128, 1.0), (40, 64, 256, 1.0)])
+def test_fused_heads_rotation_quantise_gemv_equals_the_separate_calls(N, n, m, ratio, dtype):
+    """Rotation across heads + quantiser + GEMV in one launch: the bits of rcp_rotate_quant_act + rcp_w2a4_gemv."""
+    _say(f"fused heads rotation N={N} n={n} m={m} ratio={ratio} {dtype}")
+    K = n * m
+    packed, cb, _, _ = _gemv_case(91, N, K, 1)
+    x16 = rcp_synth.activation(91, f"fh{K}", 1, K)
+    xd = {"f16": _t(x16), "bf16": _t(x16.astype(np.float32)).to(torch.bfloat16),
+          "f32": _t(x16.astype(np.float32) * np.float32(1.0009765))}[dtype]
+    pk, lv = _t(packed), _t(cb.view(np.float16))
+    rot = rcp.Rotation.heads(n, m)
+    xq, sc = rcp.rotate_quant_act(xd, rot, ratio)
+    ref_out, ref_P = rcp.w2a4_gemv(pk, lv, N, K, xq, sc, 1, out_dtype=torch.float32, want_partial_sums=True)
+    xq2, sc2 = torch.zeros_like(xq), torch.zeros_like(sc)
+    out, P = rcp.rotate_quant_w2a4_gemv(pk, lv, N, K, xd, rot, ratio, out_dtype=torch.float32, xq_out=xq2, scale_out=sc2,
+                                        want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert torch.equal(xq2, xq) and torch.equal(sc2.view(torch.int16), sc.view(torch.int16))
+    assert torch.equal(P, ref_P) and torch.equal(out, ref_out)
+    # no rotation given: the plain fused call
+    o1 = rcp.rotate_quant_w2a4_gemv(pk, lv, N, K, xd, None, ratio, out_dtype=torch.float32)
+    o2 = rcp.quant_w2a4_gemv(pk, lv, N, K, xd, ratio, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    if n * m == 4096:
+        with pytest.raises(rcp.RcpError):
+            rcp.rotate_quant_w2a4_gemv(pk, lv, N, K, xd, rcp.Rotation.wht(K), ratio)
+
+
 def test_heads_rotation_argument_errors():
     x = torch.zeros((1, 4096), dtype=torch.float16, device=DEV)
     for n, m in ((128, 32), (32, 100), (3, 1024)):
