@@ -207,6 +207,9 @@ int rcp_rotate_act(const void* x, rcp_dtype x_dtype, int M, int K,
  * packed, codebook: as written by rcp_pack_weights.  xq, scale: as written by
  * rcp_rotate_quant_act.  out: M x N of `out_dtype` (RCP_F16 or RCP_F32).
  * partial_sums_or_null: when non-NULL receives int32 [M][N][4].
+ * Up to 4 tokens run on the vector ALUs (packed-int4 dot products on the bit planes); from
+ * 4-5 tokens on the plane sums are formed on the matrix cores (the masked plane words are
+ * FP4 operands); the per-level sums are exact integers either way.
  */
 int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
                   const void* xq, const void* scale, int M,
