@@ -288,6 +288,7 @@ __global__ __launch_bounds__(KRON_THREADS) void kron_wave_kernel(const void* __r
     for (int e = 0; e < RPL; ++e) {
         const XT* xr = sX + static_cast<size_t>(lane * RPL + e) * m;
         float acc = 0.0f;
+#pragma unroll 8
         for (int j4 = 0; j4 < m / 4; ++j4) {
             const float4 q4 = qr[j4];
             float x0, x1, x2, x3;
