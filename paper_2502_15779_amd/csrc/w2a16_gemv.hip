@@ -262,9 +262,16 @@ static int launch_wo_one(const void* packed, const void* codebook, int N, int K,
     if (lds > 160 * 1024)
         return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a16_gemv: K=%d needs %zu bytes of LDS for the activations", K, lds);
     auto kernel = &w2a16_kernel<XF32, XDT, WS, UNR>;
-    // the look-ups address the tables by absolute LDS offset: dynamic LDS must start at 0
-    hipFuncAttributes attr;
-    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) != hipSuccess || attr.sharedSizeBytes != 0)
+    // the look-ups address the tables by absolute LDS offset: dynamic LDS must start at 0 (checked once
+    // per kernel variant; the answer is a property of the compiled code)
+    static int lds_checked = 0;  // 1 once the variant is known to have no static LDS
+    if (lds_checked == 0) {
+        hipFuncAttributes attr;
+        if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel)) != hipSuccess)
+            return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: cannot query the kernel's attributes");
+        lds_checked = attr.sharedSizeBytes == 0 ? 1 : -1;
+    }
+    if (lds_checked < 0)
         return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: kernel has static LDS, table addressing would be wrong");
     if (lds > 65536) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
