@@ -739,3 +739,68 @@ def test_whole_path_on_config_shapes(config, rows):
         assert np.array_equal(P.cpu().numpy(), ref_P)
         got = out.cpu().numpy().astype(np.float64)
         assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
+
+
+# ------------------------------------------------------------------------------------------
+# full sizes, in the launch configuration the benchmark times
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,N,K,rotated", [("qkv", 12288, 4096, False), ("o", 4096, 4096, False),
+                                              ("gate_up", 22016, 4096, False), ("down", 4096, 11008, True)])
+def test_full_size_llama2_7b_launches_as_benchmarked(name, N, K, rotated):
+    """The four launches of a LLaMA-2-7B layer at full size, default work distribution, the calls bench.py makes
+    (rcp_rotate_act for the down input, then the fused quantise+GEMV): packed bytes, LUT, x_q / S (plain inputs) and
+    all N x 4 partial sums bit-exact, every output within the bar; the oracle runs the whole matrix."""
+    _say(f"full size {name} {N}x{K}")
+    W, lo, hi, part = rcp_synth.linear_layer(7, f"full/{name}", N, K)
+    x = rcp_synth.activation(7, f"full/{name}", 1, K)
+    packed, cb = rcp.pack_weights(_t(W), _t(lo), _t(hi), _t(part))
+    xq = torch.empty((1, K // 2), dtype=torch.uint8, device=DEV)
+    sc = torch.empty((1,), dtype=torch.float16, device=DEV)
+    if rotated:
+        Q = rcp_synth.orthogonal(7, 172)
+        rot = rcp.Rotation.kron(64, _t(Q))
+        y = rcp.rotate_act(_t(x), rot)
+        out, P = rcp.quant_w2a4_gemv(packed, cb, N, K, y, 1.0, out_dtype=torch.float16, xq_out=xq, scale_out=sc,
+                                     want_partial_sums=True)
+    else:
+        out, P = rcp.quant_w2a4_gemv(packed, cb, N, K, _t(x), 1.0, out_dtype=torch.float16, xq_out=xq, scale_out=sc,
+                                     want_partial_sums=True)
+    torch.cuda.synchronize()
+    ref_packed, ref_cb = oracle.pack_weights(W.astype(np.float32), lo, hi, part)
+    assert np.array_equal(packed.cpu().numpy(), ref_packed)
+    assert np.array_equal(cb.cpu().numpy().view(np.uint16), ref_cb)
+    xq_h, sc_h = xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16)
+    if rotated:
+        y64 = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=64, m=172, Q=Q.astype(np.float64))
+        _check_act_against_rotated(np.atleast_2d(y64), xq_h, sc_h, 1.0)
+    else:
+        oxq, osc, _ = oracle.quantize_act(x.astype(np.float32), 1.0)
+        assert np.array_equal(xq_h, oxq) and np.array_equal(sc_h, osc)
+    ref_O, ref_P = oracle.w2a4_gemv(ref_packed, ref_cb, N, K, xq_h, sc_h, 1)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64)
+    cond = _f16(sc_h)[:, None] * (np.abs(_f16(ref_cb))[None, :, :] * np.abs(ref_P)).sum(axis=2)
+    assert np.all(np.abs(got - ref_O) <= 1e-3 * cond + 2.0 ** -11 * np.abs(ref_O) + 1e-30)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
+
+
+@pytest.mark.parametrize("M", [4, 16])
+def test_full_size_small_batch_layer_matches_oracle(M):
+    """gate|up of a 7B layer (22016 x 4096) with M tokens as the benchmark runs it: P bit-exact, O within the bar."""
+    N, K = 22016, 4096
+    _say(f"full size small batch M={M}")
+    idx = rcp_synth.random_indices(8, "fullsb", N, K)
+    packed = oracle.pack_indices(idx)
+    rng = np.random.default_rng(8)
+    cb = np.sort(rng.standard_normal((N, 4)) * 0.03, axis=1).astype(np.float16).view(np.uint16)
+    x = rcp_synth.activation(8, "fullsb", M, K)
+    xq, sc = rcp.rotate_quant_act(_t(x))
+    out, P = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xq, sc, M, out_dtype=torch.float16, want_partial_sums=True)
+    torch.cuda.synchronize()
+    xq_h, sc_h = xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16)
+    oxq, osc, _ = oracle.quantize_act(x.astype(np.float32), 1.0)
+    assert np.array_equal(xq_h, oxq) and np.array_equal(sc_h, osc)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, xq_h, sc_h, M)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
