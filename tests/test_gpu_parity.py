@@ -804,3 +804,38 @@ def test_full_size_small_batch_layer_matches_oracle(M):
     assert np.array_equal(P.cpu().numpy(), ref_P)
     got = out.cpu().numpy().astype(np.float64)
     assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
+
+
+def test_full_size_grouped_and_weight_only_as_benchmarked():
+    """gate|up at full size (22016 x 4096) through the group-wise fused call and the weight-only call."""
+    N, K = 22016, 4096
+    NG = K // 128
+    _say("full size grouped / weight-only")
+    W, lo, hi, part = rcp_synth.linear_layer_grouped(9, "fullg", N, K)
+    x = rcp_synth.activation(9, "fullg", 1, K)
+    packed, cb = rcp.pack_weights_grouped(_t(W), _t(lo), _t(hi), _t(part))
+    xq = torch.empty((1, K // 2), dtype=torch.uint8, device=DEV)
+    sc = torch.empty((1,), dtype=torch.float16, device=DEV)
+    out, P = rcp.quant_w2a4_gemv_grouped(packed, cb, N, K, _t(x), 1.0, out_dtype=torch.float16, xq_out=xq, scale_out=sc,
+                                         want_partial_sums=True)
+    torch.cuda.synchronize()
+    ref_packed, ref_cb = oracle.pack_weights_grouped(W.astype(np.float32), lo, hi, part)
+    assert np.array_equal(packed.cpu().numpy(), ref_packed)
+    assert np.array_equal(cb.cpu().numpy().view(np.uint16).ravel(), ref_cb)
+    oxq, osc, _ = oracle.quantize_act(x.astype(np.float32), 1.0)
+    assert np.array_equal(xq.cpu().numpy(), oxq) and np.array_equal(sc.cpu().numpy().view(np.uint16), osc)
+    ref_O, ref_P = oracle.w2a4_gemv_grouped(ref_packed, ref_cb, N, K, oxq, osc)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64).ravel()
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
+
+    # weight-only on per-channel weights of the same size
+    Wc, loc, hic, partc = rcp_synth.linear_layer(9, "fullwo", N, K)
+    pk, lut = rcp.pack_weights(_t(Wc), _t(loc), _t(hic), _t(partc))
+    o16 = rcp.w2a16_gemv(pk, lut, N, K, _t(x), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    rp, rc = oracle.pack_weights(Wc.astype(np.float32), loc, hic, partc)
+    assert np.array_equal(pk.cpu().numpy(), rp)
+    ref = oracle.w2a16_gemv(rp, rc, N, K, x.astype(np.float64))[0]
+    g16 = o16.cpu().numpy().astype(np.float64).ravel()
+    assert np.linalg.norm(g16 - ref) <= 1e-3 * np.linalg.norm(ref)
