@@ -226,3 +226,56 @@ def w2a4_gemv_grouped(packed, codebook, N, K, xq, scale_bits, group=128, M=1):
     _check(lib().rcp_ref_w2a4_gemv_grouped(_p(pk), _p(cb), N, K, group, _p(xc), _p(sc), M, _p(out), _p(P)),
            "w2a4_gemv_grouped")
     return (out[0], P[0]) if M == 1 else (out, P)
+
+
+# ---- 3-bit variant (LDP on the asymmetric normal-float format, Section 4.3) -------------------
+def w3_grid(clip_lo, clip_hi, frac, grid):
+    """(thresholds float32[7], level bit patterns uint16[8]) of one quantisation unit."""
+    g = _c(grid, np.float32)
+    assert g.shape == (8,)
+    T = np.empty(7, dtype=np.float32)
+    L = np.empty(8, dtype=np.uint16)
+    f = lib().rcp_ref_w3_grid
+    f.restype = None
+    f.argtypes = [ctypes.c_float] * 3 + [ctypes.c_void_p] * 3
+    f(float(clip_lo), float(clip_hi), float(frac), _p(g), _p(T), _p(L))
+    return T, L
+
+
+def pack_weights_w3(W, clip_lo, clip_hi, frac, grid, want_idx=False):
+    W = _c(W, np.float32)
+    N, K = W.shape
+    packed = np.empty(N * K // 8 * 3, dtype=np.uint8)
+    codebook = np.empty((N, 8), dtype=np.uint16)
+    idx = np.empty((N, K), dtype=np.uint8) if want_idx else None
+    _check(lib().rcp_ref_pack_weights_w3(_p(W), N, K, _p(_c(clip_lo, np.float32)), _p(_c(clip_hi, np.float32)),
+                                         _p(_c(frac, np.float32)), _p(_c(grid, np.float32)), _p(packed),
+                                         _p(codebook), _p(idx) if want_idx else None), "pack_weights_w3")
+    return (packed, codebook, idx) if want_idx else (packed, codebook)
+
+
+def pack_indices_w3(idx) -> np.ndarray:
+    idx = _c(idx, np.uint8)
+    N, K = idx.shape
+    packed = np.empty(N * K // 8 * 3, dtype=np.uint8)
+    _check(lib().rcp_ref_pack_indices_w3(_p(idx), N, K, _p(packed)), "pack_indices_w3")
+    return packed
+
+
+def unpack_indices_w3(packed, N, K) -> np.ndarray:
+    packed = _c(packed, np.uint8)
+    idx = np.empty((N, K), dtype=np.uint8)
+    _check(lib().rcp_ref_unpack_indices_w3(_p(packed), N, K, _p(idx)), "unpack_indices_w3")
+    return idx
+
+
+def w3a4_gemv(packed, codebook, N, K, xq, scale_bits):
+    """(out float64[N], P int32[N][8]) for one token."""
+    packed = _c(packed, np.uint8)
+    codebook = _c(codebook, np.uint16)
+    xq = _c(xq, np.uint8)
+    sb = _c(np.atleast_1d(scale_bits), np.uint16)
+    out = np.empty(N, dtype=np.float64)
+    P = np.empty((N, 8), dtype=np.int32)
+    _check(lib().rcp_ref_w3a4_gemv(_p(packed), _p(codebook), N, K, _p(xq), _p(sb), _p(out), _p(P)), "w3a4_gemv")
+    return out, P

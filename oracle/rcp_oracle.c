@@ -15,7 +15,9 @@
  * it must reduce to the 2-bit asymmetric integer quantizer of Eqn. 1); the
  * fp16 conversions against numpy's; pack/unpack against each other; the
  * quantiser against its error bound; the GEMV against brute force and numpy
- * integer matmuls.  No function here is "parity unpinned".
+ * integer matmuls; the 3-bit variant against nearest-level brute force, the
+ * integer-grid case of its printed rounding rule and the 2-bit GEMV.  No
+ * function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -582,6 +584,151 @@ int rcp_ref_w2a4_gemv_grouped(const uint8_t* packed, const uint16_t* codebook, i
             }
             out[(size_t)t * N + h] = rcp_ref_f16_bits_to_f64(scale_bits[t]) * acc;
         }
+    free(q);
+    return RCP_REF_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * 3-bit variant: LDP applied to the asymmetric normal-float format (Section
+ * 4.3, paragraph "Application of LDP on NF3 format").  The clip values lo, hi
+ * (the learnt sigma(beta)*min(W), sigma(gamma)*max(W)) and one partition
+ * fraction p = sigma(s_1) give per quantisation unit
+ *     c = lo + (hi - lo) * p,   s_neg = |c - lo|,   s_pos = |hi - c|;
+ * a weight above c is divided by s_pos, any other by s_neg, and the result is
+ * rounded to the format's grid; dequantisation multiplies the scale back and
+ * adds c.  The paper does not print the grid (it is the cited format's): here
+ * it is an INPUT, eight ascending binary32 values.  With that,
+ *     L_j = c + (g_j < 0 ? s_neg : s_pos) * g_j            (the eight levels, binary16)
+ *     T_j = (L_{j-1} + L_j) / 2,  j = 1..7                  (binary32)
+ *     idx = number of T_j at or below w                      (u(0) = 1, as for 2 bits)
+ * When the grid holds 0 the level there is c itself, and counting thresholds is
+ * the same as rounding (w - c)/s to the nearest grid value on w's own side.
+ * ---------------------------------------------------------------------- */
+void rcp_ref_w3_grid(float clip_lo, float clip_hi, float p, const float grid[8], float thresholds[7],
+                     uint16_t levels[8])
+{
+    double lo = (double)clip_lo, hi = (double)clip_hi;
+    double c = lo + (hi - lo) * (double)p;
+    double s_neg = fabs(c - lo), s_pos = fabs(hi - c);
+    double L[8];
+    for (int j = 0; j < 8; ++j) {
+        double g = (double)grid[j];
+        L[j] = c + (g < 0.0 ? s_neg : s_pos) * g;
+        levels[j] = rcp_ref_f64_to_f16_bits(L[j]);
+    }
+    for (int j = 1; j < 8; ++j) thresholds[j - 1] = (float)((L[j - 1] + L[j]) / 2.0);
+}
+
+static inline int w3_index(float w, const float T[7])
+{
+    int idx = 0;
+    for (int j = 0; j < 7; ++j) idx += (w >= T[j]);
+    return idx;
+}
+
+/* Position of bit p of idx[h][k] in the 3-bit packed buffer (layout in include/rcp.h,
+ * restated from its text).  A row group (4 rows) is K/32 units of 4 rows x 32 columns;
+ * units go in blocks of 64; a block of R = min(64, units left) units stores plane 0 of
+ * all its units, then plane 1, then plane 2, 16 bytes per unit and plane: four
+ * little-endian words, word k%32/8, bit 4*(k%8) + h%4. */
+static inline void w3_position(int h, int k, int p, int K, size_t* byte, int* bit)
+{
+    int U = K / 32, u = k / 32, j = u / 64;
+    int R = U - 64 * j < 64 ? U - 64 * j : 64;
+    size_t group_base = (size_t)(h / 4) * (size_t)U * 48u;
+    size_t unit16 = group_base + 3072u * (size_t)j + 16u * (size_t)R * (size_t)p + 16u * (size_t)(u % 64);
+    int word = (k % 32) / 8, b = 4 * (k % 8) + (h % 4);
+    *byte = unit16 + 4u * (size_t)word + (size_t)(b / 8);
+    *bit = b % 8;
+}
+
+static inline int w3_get(const uint8_t* packed, int h, int k, int K)
+{
+    int idx = 0;
+    for (int p = 0; p < 3; ++p) {
+        size_t by;
+        int bit;
+        w3_position(h, k, p, K, &by, &bit);
+        idx |= ((packed[by] >> bit) & 1) << p;
+    }
+    return idx;
+}
+
+static inline void w3_set(uint8_t* packed, int h, int k, int K, int idx)
+{
+    for (int p = 0; p < 3; ++p) {
+        size_t by;
+        int bit;
+        w3_position(h, k, p, K, &by, &bit);
+        if ((idx >> p) & 1) packed[by] |= (uint8_t)(1u << bit);
+    }
+}
+
+/* W: N x K binary32; clip_lo, clip_hi, frac: N each; grid: 8.  Writes packed (3*N*K/8
+ * bytes), codebook (N*8 binary16 bit patterns) and optionally the plain indices. */
+int rcp_ref_pack_weights_w3(const float* W, int N, int K, const float* clip_lo, const float* clip_hi,
+                            const float* frac, const float* grid, uint8_t* packed,
+                            uint16_t* codebook, uint8_t* idx_or_null)
+{
+    if (N < 4 || N % 4 || K < 32 || K % 32) return RCP_REF_ERR_SHAPE;
+    memset(packed, 0, (size_t)N * K / 8 * 3);
+#pragma omp parallel for schedule(static)
+    for (int g = 0; g < N / 4; ++g) {
+        for (int r = 0; r < 4; ++r) {
+            int h = 4 * g + r;
+            float T[7];
+            rcp_ref_w3_grid(clip_lo[h], clip_hi[h], frac[h], grid, T, codebook + 8 * (size_t)h);
+            for (int k = 0; k < K; ++k) {
+                int idx = w3_index(W[(size_t)h * K + k], T);
+                w3_set(packed, h, k, K, idx);
+                if (idx_or_null) idx_or_null[(size_t)h * K + k] = (uint8_t)idx;
+            }
+        }
+    }
+    return RCP_REF_OK;
+}
+
+int rcp_ref_unpack_indices_w3(const uint8_t* packed, int N, int K, uint8_t* idx)
+{
+    if (N < 4 || N % 4 || K < 32 || K % 32) return RCP_REF_ERR_SHAPE;
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < N; ++h)
+        for (int k = 0; k < K; ++k) idx[(size_t)h * K + k] = (uint8_t)w3_get(packed, h, k, K);
+    return RCP_REF_OK;
+}
+
+int rcp_ref_pack_indices_w3(const uint8_t* idx, int N, int K, uint8_t* packed)
+{
+    if (N < 4 || N % 4 || K < 32 || K % 32) return RCP_REF_ERR_SHAPE;
+    memset(packed, 0, (size_t)N * K / 8 * 3);
+    for (int h = 0; h < N; ++h)
+        for (int k = 0; k < K; ++k) w3_set(packed, h, k, K, idx[(size_t)h * K + k] & 7);
+    return RCP_REF_OK;
+}
+
+/* The GEMV of Section 4.4 with an eight-entry LUT per output channel:
+ *   P[h][l] = sum over k with idx[h][k] = l of q[k]   (exact integers)
+ *   O[h]    = S * sum_l LUT[h][l] * P[h][l]           (binary64)
+ * P_or_null: int32 [N][8]. */
+int rcp_ref_w3a4_gemv(const uint8_t* packed, const uint16_t* codebook, int N, int K, const uint8_t* xq,
+                      const uint16_t* scale_bits, double* out, int32_t* P_or_null)
+{
+    if (N < 4 || N % 4 || K < 32 || K % 32) return RCP_REF_ERR_SHAPE;
+    int8_t* q = (int8_t*)malloc((size_t)K);
+    if (!q) return RCP_REF_ERR_SHAPE;
+    rcp_ref_unpack_act(xq, 1, K, q);
+    double S = rcp_ref_f16_bits_to_f64(scale_bits[0]);
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < N; ++h) {
+        int64_t P[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int k = 0; k < K; ++k) P[w3_get(packed, h, k, K)] += q[k];
+        double acc = 0.0;
+        for (int l = 0; l < 8; ++l) {
+            if (P_or_null) P_or_null[(size_t)h * 8 + l] = (int32_t)P[l];
+            acc += rcp_ref_f16_bits_to_f64(codebook[8 * (size_t)h + l]) * (double)P[l];
+        }
+        out[h] = S * acc;
+    }
     free(q);
     return RCP_REF_OK;
 }

@@ -14,8 +14,16 @@ no rotation, no quantisation).  The recipe:
   Q            m x m orthogonal: QR of a Gaussian matrix, signs fixed so that the
                diagonal of the triangular factor is positive, rounded to fp32
 
+  3-bit grid   a stand-in for the normal-float table of the 3-bit format (which the paper
+               cites and does not print): standard-normal quantiles at evenly spaced
+               probabilities, four from 3 % up to the median and four above it up to 97 %,
+               each side divided by its end value -> eight values in [-1, 1] with one 0
+  centre frac  per output row: logistic of a N(0, 0.5^2) logit (a stand-in for the learnt
+               centre point between the two clip values)
+
 Every tensor has its own random stream derived from (seed, tensor name).
 """
+import statistics
 import zlib
 
 import numpy as np
@@ -86,9 +94,9 @@ def orthogonal(seed: int, m: int) -> np.ndarray:
     return np.ascontiguousarray(q.astype(np.float32))
 
 
-def random_indices(seed: int, name: str, N: int, K: int) -> np.ndarray:
-    """uint8 N x K uniform in 0..3 (for tests that start from indices)."""
-    return _rng(seed, "idx:" + name).integers(0, 4, size=(N, K), dtype=np.uint8)
+def random_indices(seed: int, name: str, N: int, K: int, levels: int = 4) -> np.ndarray:
+    """uint8 N x K uniform in 0..levels-1 (for tests that start from indices)."""
+    return _rng(seed, "idx:" + name).integers(0, levels, size=(N, K), dtype=np.uint8)
 
 
 def random_int4(seed: int, name: str, M: int, K: int) -> np.ndarray:
@@ -113,3 +121,26 @@ def linear_layer_grouped(seed: int, name: str, N: int, K: int, group: int = 128)
     hi = np.quantile(Wg, 0.98, axis=2).astype(np.float32)
     part = partitions(seed, name + ":grouped", N * NG).reshape(N, NG, 3)
     return W, np.ascontiguousarray(lo), np.ascontiguousarray(hi), np.ascontiguousarray(part)
+
+
+def normal_quantile_grid() -> np.ndarray:
+    """float32 [8], ascending: -1, two negative values, 0, three positive values, 1."""
+    nd = statistics.NormalDist()
+    tail = 0.03
+    neg = [nd.inv_cdf(tail + (0.5 - tail) * i / 3) for i in range(3)]
+    pos = [nd.inv_cdf(0.5 + (0.5 - tail) * i / 4) for i in range(1, 5)]
+    g = [v / -neg[0] for v in neg] + [0.0] + [v / pos[-1] for v in pos]
+    return np.asarray(g, dtype=np.float32)
+
+
+def centre_fractions(seed: int, name: str, N: int) -> np.ndarray:
+    """float32 [N] in (0, 1), scattered around 1/2."""
+    z = _rng(seed, "centre:" + name).standard_normal(N) * 0.5
+    return (1.0 / (1.0 + np.exp(-z))).astype(np.float32)
+
+
+def linear_layer_w3(seed: int, name: str, N: int, K: int):
+    """Offline inputs of one 3-bit linear layer: (W fp16, lo, hi, centre fraction, grid)."""
+    W = weights(seed, name, N, K)
+    lo, hi = clip_range(W)
+    return W, lo, hi, centre_fractions(seed, name, N), normal_quantile_grid()
