@@ -71,6 +71,18 @@
  *   Grouped LUT: fp16 [N/4][NG][4 rows][4 levels]: level l of row h, group g at half-word
  *   (((h/4)*NG + g)*4 + h%4)*4 + l.  N*NG*8 bytes.
  *   Grouped partial sums: int32 [N][NG][4].
+ *
+ * 3-bit variant (the *_w3 calls; Section 4.3, paragraph on the asymmetric normal-float
+ * 3-bit format): eight levels per output channel, idx = b0 + 2*b1 + 4*b2.
+ *   3-bit packed indices, 3*N*K/8 bytes: three bit planes.  A group of four rows g4 = h/4 is
+ *   K/32 "units" of 4 rows x 32 columns and starts at byte g4 * (K/32) * 48.  Units go in
+ *   blocks of 64 (block j = u/64 starts 3072*j bytes into the row group); a block of
+ *   R = min(64, K/32 - 64*j) units stores plane 0 of its R units, then plane 1, then plane
+ *   2, so that the 64 lanes of a wavefront read each plane as one contiguous run: plane p
+ *   of unit u lies 16*R*p + 16*(u%64) bytes into its block.  Those 16 bytes are four
+ *   little-endian uint32 words; word (k%32)/8 covers eight columns, and its bit
+ *   4*(k%8) + h%4 is bit p of idx[h][k].
+ *   3-bit LUT: fp16 [N][8], ascending.  3-bit partial sums: int32 [N][8].
  */
 #ifndef RCP_H
 #define RCP_H
@@ -308,6 +320,41 @@ int rcp_quant_w2a4_gemv_grouped(const void* packed, const void* codebook, int N,
                                 void* out, rcp_dtype out_dtype,
                                 void* xq_out_or_null, void* scale_out_or_null,
                                 int32_t* partial_sums_or_null, void* stream);
+
+/*
+ * 3-bit variant: LDP applied to the asymmetric normal-float 3-bit format (Section 4.3,
+ * paragraph "Application of LDP on NF3 format": the centre point, the two scales of its
+ * scale equation, the side-wise rounding of its quantisation equation, and dequantisation
+ * as scale * grid value + centre).  The paper takes the format's grid from the work it
+ * cites and does not print it; here the grid is an argument.
+ *
+ * rcp_pack_weights_w3: per output row h, in double precision,
+ *     c = lo + (hi - lo) * frac,  s_neg = |c - lo|,  s_pos = |hi - c|
+ *     L_j = c + (grid[j] < 0 ? s_neg : s_pos) * grid[j]     -> fp16, the LUT
+ *     T_j = (L_{j-1} + L_j) / 2, j = 1..7                    -> fp32
+ *     idx[h][k] = number of T_j <= W[h][k]                   (compared in fp32)
+ *   which, when the grid holds 0, rounds (w - c)/s to the nearest grid value on w's side.
+ *   W: N x K of `w_dtype`.  clip_lo, clip_hi, frac: fp32 [N] (the learnt clip values and the
+ *   logistic of the learnt centre parameter).  grid: HOST pointer to eight strictly
+ *   ascending finite floats (RCP_ERR_UNSUPPORTED otherwise).  packed_out: 3*N*K/8 bytes,
+ *   codebook_out: N*16 bytes, in the 3-bit layouts above.
+ * rcp_unpack_indices_w3: 3-bit packed layout -> idx_out[h*K + k] in 0..7 (N*K bytes).
+ * rcp_w3a4_gemv (one token; the GEMV of Section 4.4 with an eight-entry LUT):
+ *     P[h][l] = sum_{k : idx[h][k] = l} q[k]                 (int32, exact)
+ *     O[h]    = S * sum_l LUT[h][l] * P[h][l]                (fp32, l ascending)
+ *   xq, scale: one token as written by rcp_rotate_quant_act.  out: N values of `out_dtype`
+ *   (RCP_F16 or RCP_F32).  partial_sums_or_null: when non-NULL receives int32 [N][8].
+ *   The packed matrix must stay below 2 GiB (RCP_ERR_SHAPE).
+ */
+int rcp_pack_weights_w3(const void* W, rcp_dtype w_dtype, int N, int K,
+                        const float* clip_lo, const float* clip_hi, const float* frac,
+                        const float* grid_host,
+                        void* packed_out, void* codebook_out, void* stream);
+int rcp_unpack_indices_w3(const void* packed, int N, int K, uint8_t* idx_out, void* stream);
+int rcp_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
+                  const void* xq, const void* scale,
+                  void* out, rcp_dtype out_dtype,
+                  int32_t* partial_sums_or_null, void* stream);
 
 #ifdef __cplusplus
 }

@@ -115,6 +115,12 @@ def lib():
                                                  vp, vp, vp, vp]
         L.rcp_w2a16_gemv.restype = ci
         L.rcp_w2a16_gemv.argtypes = [vp, vp, ci, ci, vp, ci, vp, ci, vp]
+        L.rcp_pack_weights_w3.restype = ci
+        L.rcp_pack_weights_w3.argtypes = [vp, ci, ci, ci, vp, vp, vp, ctypes.POINTER(ctypes.c_float), vp, vp, vp]
+        L.rcp_unpack_indices_w3.restype = ci
+        L.rcp_unpack_indices_w3.argtypes = [vp, ci, ci, vp, vp]
+        L.rcp_w3a4_gemv.restype = ci
+        L.rcp_w3a4_gemv.argtypes = [vp, vp, ci, ci, vp, vp, vp, ci, vp, vp]
         _lib = L
     return _lib
 
@@ -416,4 +422,59 @@ def rotate_quant_w2a4_gemv(packed, codebook, N, K, x, rot=None, clip_ratio=1.0, 
                                             ctypes.c_float(clip_ratio), _dev(out, "out"), _DTYPES[out.dtype],
                                             opt(xq_out, "xq_out"), opt(scale_out, "scale_out"),
                                             opt(partial_sums, "partial_sums"), _stream()))
+    return (out, partial_sums) if partial_sums is not None else out
+
+
+# ---- 3-bit variant (eight levels per output channel) ------------------------------------------
+def pack_weights_w3(W, clip_lo, clip_hi, frac, grid, packed_out=None, codebook_out=None):
+    """W [N, K] (fp16 / bf16 / fp32), clip_lo / clip_hi / frac [N] fp32 on the GPU, grid: eight ascending
+    host floats -> (packed uint8 [3*N*K/8], codebook fp16 [N, 8])."""
+    N, K = W.shape
+    if packed_out is None:
+        packed_out = torch.empty(max(3 * N * K // 8, 1), dtype=torch.uint8, device=W.device)
+    if codebook_out is None:
+        codebook_out = torch.empty((N, 8), dtype=torch.float16, device=W.device)
+    for t, name in ((clip_lo, "clip_lo"), (clip_hi, "clip_hi"), (frac, "frac")):
+        if t.dtype != torch.float32 or t.numel() != N:
+            raise ValueError(f"{name} must be float32 with N elements")
+    if W.dtype not in _DTYPES:
+        raise ValueError("W must be float16, bfloat16 or float32")
+    g = [float(v) for v in grid]
+    if len(g) != 8:
+        raise ValueError("grid must hold eight values")
+    if packed_out.numel() * packed_out.element_size() < 3 * N * K // 8 or codebook_out.numel() < 8 * N:
+        raise ValueError("packed_out / codebook_out buffers do not match N, K")
+    _check(lib().rcp_pack_weights_w3(_dev(W, "W"), _DTYPES[W.dtype], N, K, _dev(clip_lo, "clip_lo"),
+                                     _dev(clip_hi, "clip_hi"), _dev(frac, "frac"), (ctypes.c_float * 8)(*g),
+                                     _dev(packed_out, "packed_out"), _dev(codebook_out, "codebook_out"), _stream()))
+    return packed_out, codebook_out
+
+
+def unpack_indices_w3(packed, N, K, idx_out=None):
+    if idx_out is None:
+        idx_out = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    if packed.numel() * packed.element_size() < 3 * N * K // 8:
+        raise ValueError("packed buffer too small")
+    _check(lib().rcp_unpack_indices_w3(_dev(packed, "packed"), N, K, _dev(idx_out, "idx_out"), _stream()))
+    return idx_out
+
+
+def w3a4_gemv(packed, codebook, N, K, xq, scale, out=None, out_dtype=torch.float16, partial_sums=None,
+              want_partial_sums=False):
+    """One token -> out [1, N] (and the int32 [N, 8] per-level partial sums when asked for)."""
+    if out is None:
+        out = torch.empty((1, N), dtype=out_dtype, device=packed.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < N:
+        raise ValueError("out must be float16 or float32 with N elements")
+    if want_partial_sums and partial_sums is None:
+        partial_sums = torch.empty((N, 8), dtype=torch.int32, device=packed.device)
+    if packed.numel() * packed.element_size() < 3 * N * K // 8 or codebook.numel() < 8 * N:
+        raise ValueError("packed / codebook buffers do not match N, K")
+    if xq.numel() * xq.element_size() < K // 2 or scale.numel() < 1:
+        raise ValueError("xq / scale buffers do not match K")
+    if partial_sums is not None and (partial_sums.dtype != torch.int32 or partial_sums.numel() < 8 * N):
+        raise ValueError("partial_sums must be int32 [N, 8]")
+    _check(lib().rcp_w3a4_gemv(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, _dev(xq, "xq"),
+                               _dev(scale, "scale"), _dev(out, "out"), _DTYPES[out.dtype],
+                               _dev(partial_sums, "partial_sums") if partial_sums is not None else None, _stream()))
     return (out, partial_sums) if partial_sums is not None else out

@@ -408,4 +408,50 @@ int rcp_quant_w2a4_gemv_grouped(const void* packed, const void* codebook, int N,
     return launch_gemv_grouped(packed, codebook, N, K, xq_out_or_null, scale_out_or_null, out, out_dtype, partial_sums_or_null, st);
 }
 
+int rcp_pack_weights_w3(const void* W, rcp_dtype w_dtype, int N, int K, const float* clip_lo, const float* clip_hi,
+                        const float* frac, const float* grid_host, void* packed_out, void* codebook_out, void* stream)
+{
+    if (!W || !clip_lo || !clip_hi || !frac || !grid_host || !packed_out || !codebook_out)
+        return fail(RCP_ERR_NULL, "rcp_pack_weights_w3: NULL pointer argument");
+    if (int rc = check_shape("rcp_pack_weights_w3", N, K)) return rc;
+    if (w_dtype != RCP_F16 && w_dtype != RCP_F32 && w_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_pack_weights_w3: unknown dtype %d", static_cast<int>(w_dtype));
+    W3Grid grid;
+    for (int j = 0; j < 8; ++j) {
+        grid.g[j] = grid_host[j];
+        if (!(grid.g[j] - grid.g[j] == 0.0f) || (j > 0 && !(grid.g[j] > grid.g[j - 1])))
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_pack_weights_w3: the grid must be eight finite, strictly ascending values");
+    }
+    if (!aligned16(W) || !aligned16(packed_out) || !aligned16(codebook_out) || !aligned16(clip_lo) ||
+        !aligned16(clip_hi) || !aligned16(frac))
+        return fail(RCP_ERR_ALIGN, "rcp_pack_weights_w3: device buffers must be 16-byte aligned");
+    return launch_pack_w3(W, w_dtype, N, K, clip_lo, clip_hi, frac, grid, packed_out, codebook_out,
+                          static_cast<hipStream_t>(stream));
+}
+
+int rcp_unpack_indices_w3(const void* packed, int N, int K, uint8_t* idx_out, void* stream)
+{
+    if (!packed || !idx_out) return fail(RCP_ERR_NULL, "rcp_unpack_indices_w3: NULL pointer argument");
+    if (int rc = check_shape("rcp_unpack_indices_w3", N, K)) return rc;
+    if (!aligned16(packed) || !aligned16(idx_out))
+        return fail(RCP_ERR_ALIGN, "rcp_unpack_indices_w3: device buffers must be 16-byte aligned");
+    return launch_unpack_w3(packed, N, K, idx_out, static_cast<hipStream_t>(stream));
+}
+
+int rcp_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale, void* out,
+                  rcp_dtype out_dtype, int32_t* partial_sums_or_null, void* stream)
+{
+    if (!packed || !codebook || !xq || !scale || !out) return fail(RCP_ERR_NULL, "rcp_w3a4_gemv: NULL pointer argument");
+    if (int rc = check_shape("rcp_w3a4_gemv", N, K)) return rc;
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_w3a4_gemv: out_dtype must be RCP_F16 or RCP_F32");
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(xq) || !aligned16(out) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_w3a4_gemv: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_w3a4_gemv: scale must be 2-byte aligned");
+    return launch_w3a4_gemv(packed, codebook, N, K, xq, scale, out, out_dtype, partial_sums_or_null,
+                            static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -274,4 +274,154 @@ int launch_unpack_grouped(const void* packed, int N, int K, uint8_t* idx, hipStr
     return check_launch("rcp_unpack_indices_grouped");
 }
 
+// ---------------------------------------------------------------------------------------------
+// 3-bit variant: LDP on the asymmetric normal-float format (Section 4.3, paragraph on the NF3
+// format).  Eight levels per output row from the clip values, the centre fraction and the
+// format's grid; three bit planes per unit of 4 rows x 32 columns (layout in include/rcp.h).
+// ---------------------------------------------------------------------------------------------
+struct W3Levels {
+    float T[7];
+    uint16_t L[8];
+};
+
+__device__ static W3Levels w3_levels(float lo_f, float hi_f, float frac_f, const W3Grid& grid)
+{
+    const double lo = lo_f, hi = hi_f;
+    const double c = __dadd_rn(lo, __dmul_rn(__dsub_rn(hi, lo), static_cast<double>(frac_f)));
+    const double s_neg = fabs(__dsub_rn(c, lo)), s_pos = fabs(__dsub_rn(hi, c));
+    double L[8];
+    W3Levels out;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const double g = grid.g[j];
+        L[j] = __dadd_rn(c, __dmul_rn(g < 0.0 ? s_neg : s_pos, g));
+        out.L[j] = double_to_half_bits(L[j]);
+    }
+#pragma unroll
+    for (int j = 1; j < 8; ++j) out.T[j - 1] = __double2float_rn(__ddiv_rn(__dadd_rn(L[j - 1], L[j]), 2.0));
+    return out;
+}
+
+// byte offset of plane 0 of unit u inside its row group, and the distance between planes
+__device__ __forceinline__ size_t w3_unit_offset(int u, int U, int& plane_stride)
+{
+    const int j = u >> 6;
+    const int R = min(64, U - 64 * j);
+    plane_stride = 16 * R;
+    return static_cast<size_t>(3072) * j + 16 * (u & 63);
+}
+
+// One workgroup: one group of four rows x 256 units; one thread per unit.
+template <int DT>
+__global__ __launch_bounds__(PACK_THREADS) void pack_w3_kernel(const void* __restrict__ W, int N, int K,
+                                                               const float* __restrict__ clip_lo,
+                                                               const float* __restrict__ clip_hi,
+                                                               const float* __restrict__ frac, W3Grid grid,
+                                                               uint8_t* __restrict__ packed,
+                                                               uint16_t* __restrict__ codebook)
+{
+    __shared__ float sT[4][7];
+    const int g = blockIdx.y;
+    const int U = K / 32;
+    if (threadIdx.x < 4) {
+        const int h = 4 * g + threadIdx.x;
+        const W3Levels lv = w3_levels(clip_lo[h], clip_hi[h], frac[h], grid);
+#pragma unroll
+        for (int j = 0; j < 7; ++j) sT[threadIdx.x][j] = lv.T[j];
+        if (blockIdx.x == 0) {
+            uint4 lut;
+            lut.x = lv.L[0] | (static_cast<uint32_t>(lv.L[1]) << 16);
+            lut.y = lv.L[2] | (static_cast<uint32_t>(lv.L[3]) << 16);
+            lut.z = lv.L[4] | (static_cast<uint32_t>(lv.L[5]) << 16);
+            lut.w = lv.L[6] | (static_cast<uint32_t>(lv.L[7]) << 16);
+            reinterpret_cast<uint4*>(codebook)[h] = lut;
+        }
+    }
+    __syncthreads();
+    const int u = blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (u >= U) return;
+    uint32_t pl[3][4] = {};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float w[8];
+            load8_as_float<DT>(W, static_cast<size_t>(4 * g + r) * K + static_cast<size_t>(u) * 32 + 8 * c, w);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t idx = 0;
+#pragma unroll
+                for (int t = 0; t < 7; ++t) idx += static_cast<uint32_t>(w[j] >= sT[r][t]);
+                pl[0][c] |= (idx & 1u) << (4 * j + r);
+                pl[1][c] |= ((idx >> 1) & 1u) << (4 * j + r);
+                pl[2][c] |= (idx >> 2) << (4 * j + r);
+            }
+        }
+    }
+    int ps;
+    uint8_t* dst = packed + static_cast<size_t>(g) * U * 48 + w3_unit_offset(u, U, ps);
+#pragma unroll
+    for (int p = 0; p < 3; ++p)
+        *reinterpret_cast<uint4*>(dst + static_cast<size_t>(p) * ps) = make_uint4(pl[p][0], pl[p][1], pl[p][2], pl[p][3]);
+}
+
+__global__ __launch_bounds__(PACK_THREADS) void unpack_w3_kernel(const uint8_t* __restrict__ packed, int N, int K,
+                                                                 uint8_t* __restrict__ idx)
+{
+    const int g = blockIdx.y;
+    const int U = K / 32;
+    const int u = blockIdx.x * PACK_THREADS + threadIdx.x;
+    if (u >= U) return;
+    int ps;
+    const uint8_t* src = packed + static_cast<size_t>(g) * U * 48 + w3_unit_offset(u, U, ps);
+    uint32_t pl[3][4];
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        const uint4 v = *reinterpret_cast<const uint4*>(src + static_cast<size_t>(p) * ps);
+        pl[p][0] = v.x;
+        pl[p][1] = v.y;
+        pl[p][2] = v.z;
+        pl[p][3] = v.w;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t lo4 = 0, hi4 = 0;  // eight index bytes of row r, columns 8c .. 8c+7 of the unit
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int b = 4 * j + r;
+                const uint32_t v = ((pl[0][c] >> b) & 1u) | (((pl[1][c] >> b) & 1u) << 1) | (((pl[2][c] >> b) & 1u) << 2);
+                if (j < 4) lo4 |= v << (8 * j);
+                else hi4 |= v << (8 * (j - 4));
+            }
+            *reinterpret_cast<uint2*>(idx + static_cast<size_t>(4 * g + r) * K + static_cast<size_t>(u) * 32 + 8 * c) =
+                make_uint2(lo4, hi4);
+        }
+    }
+}
+
+int launch_pack_w3(const void* W, rcp_dtype dt, int N, int K, const float* lo, const float* hi, const float* frac,
+                   const W3Grid& grid, void* packed, void* codebook, hipStream_t st)
+{
+    if (N / 4 > 65535) return fail(RCP_ERR_SHAPE, "rcp_pack_weights_w3: N=%d exceeds 262140", N);
+    dim3 blocks((K / 32 + PACK_THREADS - 1) / PACK_THREADS, N / 4);
+    auto* pk = static_cast<uint8_t*>(packed);
+    auto* cb = static_cast<uint16_t*>(codebook);
+    switch (dt) {
+        case RCP_F16: pack_w3_kernel<RCP_F16><<<blocks, PACK_THREADS, 0, st>>>(W, N, K, lo, hi, frac, grid, pk, cb); break;
+        case RCP_F32: pack_w3_kernel<RCP_F32><<<blocks, PACK_THREADS, 0, st>>>(W, N, K, lo, hi, frac, grid, pk, cb); break;
+        default: pack_w3_kernel<RCP_BF16><<<blocks, PACK_THREADS, 0, st>>>(W, N, K, lo, hi, frac, grid, pk, cb); break;
+    }
+    return check_launch("rcp_pack_weights_w3");
+}
+
+int launch_unpack_w3(const void* packed, int N, int K, uint8_t* idx, hipStream_t st)
+{
+    if (N / 4 > 65535) return fail(RCP_ERR_SHAPE, "rcp_unpack_indices_w3: N=%d exceeds 262140", N);
+    dim3 blocks((K / 32 + PACK_THREADS - 1) / PACK_THREADS, N / 4);
+    unpack_w3_kernel<<<blocks, PACK_THREADS, 0, st>>>(static_cast<const uint8_t*>(packed), N, K, idx);
+    return check_launch("rcp_unpack_indices_w3");
+}
+
 }  // namespace rcp

@@ -53,6 +53,15 @@ int launch_quant_gemv_grouped(const void* packed, const void* codebook, int N, i
 // weight-only GEMV: 16- or 32-bit activations, no activation quantiser (w2a16_gemv.hip)
 int launch_w2a16_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
                       void* out, rcp_dtype out_dt, hipStream_t st);
+// 3-bit variant: eight levels per output row (pack.hip, w3a4_gemv.hip)
+struct W3Grid {
+    float g[8];
+};
+int launch_pack_w3(const void* W, rcp_dtype dt, int N, int K, const float* lo, const float* hi, const float* frac,
+                   const W3Grid& grid, void* packed, void* codebook, hipStream_t st);
+int launch_unpack_w3(const void* packed, int N, int K, uint8_t* idx, hipStream_t st);
+int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
+                     void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 // matrix-core kernel for several tokens (gemm_mfma.hip)
 int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
                      int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);

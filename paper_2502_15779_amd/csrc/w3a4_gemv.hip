@@ -1,0 +1,187 @@
+// Non-uniform W3A4 GEMV for CDNA4: the GEMV of Section 4.4 with the eight-level LUT of the
+// 3-bit variant (Section 4.3, paragraph on the asymmetric normal-float 3-bit format).  The
+// kernel design is this library's own and extends the 2-bit kernel's scheme.
+//
+// The product goes through exact integer per-level partial sums
+//     P[h][l] = sum_{k : idx[h][k] = l} q[k],   O[h] = S * sum_l LUT[h][l] * P[h][l],
+// and the partial sums through the monomials of the index bits idx = b0 + 2 b1 + 4 b2:
+//     F_s = sum_k q[k] * prod_{i in s} b_i[k]   for the seven non-empty subsets s,  F_0 = T = sum q,
+//     P_l = sum_{s >= l} (-1)^{|s| - |l|} F_s   (subset inversion: three rounds of subtractions).
+// The packed layout keeps each bit plane with the bits of FOUR rows in a nibble, so a plane
+// word (or the AND of plane words) and the packed int4 activation word go straight into
+// v_dot8_i32_i4; the nibble masks 1, 3, 7, F give a triangular system solved exactly for the
+// four rows, as in the 2-bit kernel.  Per 32 weights: 4 ANDs for the products, 21 for the
+// masks, 28 dot instructions; no shift, no table look-up and no float conversion in the loop.
+//
+// Work decomposition: one wavefront per group of four rows; its 64 lanes take the 64 units
+// (4 rows x 32 columns, three 16-byte plane pieces) of a block side by side, so each plane is
+// read as one contiguous kilobyte.  The loads of the next block (or of the wavefront's next
+// row group) are in flight while the current one is computed.
+#include "rcp_internal.hpp"
+
+namespace rcp {
+
+constexpr int W3_THREADS = 256;
+constexpr int W3_WAVES = W3_THREADS / 64;
+
+struct W3Planes {
+    u32x4 p[3];
+};
+
+// acc[s-1][m]: monomial s = 1..7 (bit i of s: plane i is a factor), nibble mask m in {1, 3, 7, F}
+__device__ __forceinline__ void w3_unit_update(const W3Planes& w, const u32x4& x, int (&acc)[7][4])
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t b0 = w.p[0][c], b1 = w.p[1][c], b2 = w.p[2][c];
+        const uint32_t b01 = b0 & b1;
+        const uint32_t pl[7] = {b0, b1, b01, b2, b0 & b2, b1 & b2, b01 & b2};
+#pragma unroll
+        for (int s = 0; s < 7; ++s) {
+            acc[s][0] = dot8(x[c], pl[s] & 0x11111111u, acc[s][0]);
+            acc[s][1] = dot8(x[c], pl[s] & 0x33333333u, acc[s][1]);
+            acc[s][2] = dot8(x[c], pl[s] & 0x77777777u, acc[s][2]);
+            acc[s][3] = dot8(x[c], pl[s], acc[s][3]);
+        }
+    }
+}
+
+template <bool OUT_F16>
+__global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __restrict__ packed,
+                                                               const uint4* __restrict__ codebook, int N, int K,
+                                                               const uint4* __restrict__ xq,
+                                                               const uint16_t* __restrict__ scale,
+                                                               void* __restrict__ out, int32_t* __restrict__ Pout)
+{
+    extern __shared__ uint4 smem4[];  // x: 64 * nblk pieces of 16 bytes (zero beyond K), then W3_WAVES sums
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int U = K / 32, G = N / 4;
+    const int nblk = (U + 63) >> 6;
+    const unsigned group_bytes = static_cast<unsigned>(U) * 48u;
+    // One buffer resource over the whole matrix: a row group beyond N lands past its end and
+    // reads zeros.  A lane beyond the last unit of a row group reads bytes of another plane or
+    // row group; its activations in LDS are zero, so it adds nothing.
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * group_bytes), 0x00020000);
+    const int gstride = gridDim.x * W3_WAVES;
+    auto load_block = [&](int gi, int j, W3Planes& w) {
+        const int R = min(64, U - 64 * j);
+        // the whole offset goes into the vector operand: only that one is range-checked
+        const unsigned base = static_cast<unsigned>(gi) * group_bytes + 3072u * j + 16u * lane;
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+            w.p[p] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(base + 16u * R * p), 0, 0);
+    };
+
+    int gi = blockIdx.x * W3_WAVES + wave;
+    int j = 0;
+    W3Planes wA, wB;
+    load_block(gi, 0, wA);  // in flight while the activations are staged
+    uint4 lut = codebook[min(4 * gi + (((lane >> 4) & 1) << 1 | (lane >> 5)), N - 1)];
+    const float S = half_bits_to_float(scale[0]);
+
+    int* tsum = reinterpret_cast<int*>(smem4 + 64 * nblk);
+    {
+        int s = 0;
+        for (int i = threadIdx.x; i < 64 * nblk; i += W3_THREADS) {
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (i < U) v = xq[i];
+            smem4[i] = v;
+            s = dot8(v.x, 0x11111111u, s);
+            s = dot8(v.y, 0x11111111u, s);
+            s = dot8(v.z, 0x11111111u, s);
+            s = dot8(v.w, 0x11111111u, s);
+        }
+        s = wave_sum(s);
+        if (lane == 0) tsum[wave] = s;
+    }
+    __syncthreads();
+    const int T = tsum[0] + tsum[1] + tsum[2] + tsum[3];
+    const int my_row = (((lane >> 4) & 1) << 1) | (lane >> 5);  // the row this lane holds after the folds
+
+    int acc[7][4];
+#pragma unroll
+    for (int s = 0; s < 7; ++s)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) acc[s][m] = 0;
+
+    // one pipeline step: issue the loads of the next position, compute the current one
+    auto step = [&](W3Planes& cur, W3Planes& nxt) {
+        int jn = j + 1, gn = gi;
+        if (jn == nblk) {
+            jn = 0;
+            gn = gi + gstride;
+        }
+        load_block(gn, jn, nxt);  // beyond the last row group: zeros
+        const uint4 xv = smem4[64 * j + lane];
+        const u32x4 x = {xv.x, xv.y, xv.z, xv.w};
+        w3_unit_update(cur, x, acc);
+        if (jn == 0) {  // row group finished (uniform)
+            // this lane's share of 2^r f_r, then the sum over the wavefront; lanes 0, 16, 32, 48
+            // end up with the seven monomial sums of rows 0, 2, 1, 3
+            int f[7];
+#pragma unroll
+            for (int s = 0; s < 7; ++s) {
+                const int g0 = acc[s][0], g1 = acc[s][1] - acc[s][0], g2 = acc[s][2] - acc[s][1], g3 = acc[s][2] - acc[s][3];
+                const int lo = fold32(g0, g1), hi = fold32(g2, g3);
+                f[s] = row_sum16(fold16(lo, hi)) >> my_row;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) acc[s][m] = 0;
+            }
+            if ((lane & 15) == 0) {
+                int F[8] = {T, f[0], f[1], f[2], f[3], f[4], f[5], f[6]};
+#pragma unroll
+                for (int bit = 1; bit < 8; bit <<= 1)
+#pragma unroll
+                    for (int l = 0; l < 8; ++l)
+                        if ((l & bit) == 0) F[l] -= F[l | bit];
+                const int h = 4 * gi + my_row;
+                const uint32_t lw[4] = {lut.x, lut.y, lut.z, lut.w};
+                float o = 0.0f;
+#pragma unroll
+                for (int l = 0; l < 8; ++l) {
+                    const float c = half_bits_to_float(static_cast<uint16_t>(l & 1 ? lw[l >> 1] >> 16 : lw[l >> 1] & 0xffffu));
+                    o = l == 0 ? c * static_cast<float>(F[0]) : fmaf(c, static_cast<float>(F[l]), o);
+                }
+                o *= S;
+                if constexpr (OUT_F16) static_cast<__half*>(out)[h] = __float2half_rn(o);
+                else static_cast<float*>(out)[h] = o;
+                if (Pout != nullptr) {
+                    reinterpret_cast<int4*>(Pout)[2 * h] = make_int4(F[0], F[1], F[2], F[3]);
+                    reinterpret_cast<int4*>(Pout)[2 * h + 1] = make_int4(F[4], F[5], F[6], F[7]);
+                }
+            }
+            if (gn < G) lut = codebook[min(4 * gn + my_row, N - 1)];
+        }
+        gi = gn;
+        j = jn;
+    };
+    while (gi < G) {
+        step(wA, wB);
+        if (gi >= G) break;
+        step(wB, wA);
+    }
+}
+
+int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
+                     void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
+{
+    if (static_cast<long long>(N) * K / 8 * 3 >= (1LL << 31))
+        return fail(RCP_ERR_SHAPE, "rcp_w3a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(N) * K / 8 * 3);
+    const int G = N / 4, U = K / 32;
+    const int nblk = (U + 63) / 64;
+    const size_t lds = static_cast<size_t>(nblk) * 64 * 16 + W3_WAVES * sizeof(int);
+    const int cus = num_compute_units();
+    const int nbatch = (G + W3_WAVES - 1) / W3_WAVES;
+    const int blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    auto launch = [&](auto kernel) {
+        kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(packed), static_cast<const uint4*>(codebook), N, K,
+                                                static_cast<const uint4*>(xq), static_cast<const uint16_t*>(scale), out, P);
+    };
+    if (out_dt == RCP_F16) launch(&w3a4_gemv_kernel<true>);
+    else launch(&w3a4_gemv_kernel<false>);
+    return check_launch("rcp_w3a4_gemv");
+}
+
+}  // namespace rcp

@@ -32,7 +32,7 @@ def test_every_declared_function_is_exported(lib):
             "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act", "rcp_stream_read",
             "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped",
             "rcp_w2a16_gemv", "rcp_quant_w2a4_gemv_grouped", "rcp_w2a4_gemm_grouped",
-            "rcp_rotate_quant_w2a4_gemv"} <= set(names)
+            "rcp_rotate_quant_w2a4_gemv", "rcp_pack_weights_w3", "rcp_unpack_indices_w3", "rcp_w3a4_gemv"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -124,6 +124,28 @@ def test_argument_errors_need_no_gpu(lib):
     qg.argtypes = [vp, vp, ci, ci, ci, vp, ci, ctypes.c_float, vp, ci, vp, vp, vp, vp]
     assert qg(fake, fake, 8, 256, 128, fake, 0, 0.0, fake, 0, None, None, None, None) == -4   # clip ratio
     assert qg(fake, fake, 8, 256, 128, None, 0, 1.0, fake, 0, None, None, None, None) == -1
+    # 3-bit variant: the grid is a host array and is checked before anything is launched
+    p3 = lib.rcp_pack_weights_w3
+    f8 = ctypes.c_float * 8
+    p3.argtypes = [vp, ci, ci, ci, vp, vp, vp, ctypes.POINTER(ctypes.c_float), vp, vp, vp]
+    good = f8(-1, -0.5, -0.2, 0, 0.15, 0.3, 0.6, 1)
+    assert p3(fake, 0, 8, 64, fake, fake, fake, None, fake, fake, None) == -1
+    assert p3(fake, 0, 8, 64, fake, fake, fake, f8(-1, -0.5, -0.5, 0, 0.15, 0.3, 0.6, 1), fake, fake, None) == -4
+    assert b"ascending" in lib.rcp_last_error()
+    assert p3(fake, 0, 8, 64, fake, fake, fake, f8(-1, -0.5, -0.2, 0, 0.15, 0.3, 0.6, float("inf")), fake, fake, None) == -4
+    assert p3(fake, 0, 8, 64, fake, fake, fake, f8(float("nan"), -0.5, -0.2, 0, 0.15, 0.3, 0.6, 1), fake, fake, None) == -4
+    assert p3(fake, 0, 6, 64, fake, fake, fake, good, fake, fake, None) == -2
+    assert p3(fake, 4, 8, 64, fake, fake, fake, good, fake, fake, None) == -4
+    assert p3(odd, 0, 8, 64, fake, fake, fake, good, fake, fake, None) == -3
+    g3 = lib.rcp_w3a4_gemv
+    g3.argtypes = [vp, vp, ci, ci, vp, vp, vp, ci, vp, vp]
+    assert g3(fake, fake, 8, 64, fake, None, fake, 0, None, None) == -1
+    assert g3(fake, fake, 8, 48, fake, fake, fake, 0, None, None) == -2
+    assert g3(fake, fake, 8, 64, fake, fake, fake, 2, None, None) == -4
+    assert g3(fake, fake, 8, 64, fake, vp(0x1001), fake, 0, None, None) == -3
+    u3 = lib.rcp_unpack_indices_w3
+    u3.argtypes = [vp, ci, ci, vp, vp]
+    assert u3(fake, 10, 64, fake, None) == -2
     ws = lib.rcp_act_workspace_bytes
     ws.restype = ctypes.c_size_t
     ws.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot)]
