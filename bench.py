@@ -468,6 +468,27 @@ def main():
         b = N * K // 4 + 8 * N + 2 * K + 2 * N
         weight_only[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1)}
 
+    # 3-bit variant (eight levels per output channel): pre-quantised activations, cold over L weight sets
+    w3 = {}
+    for label, i, N in side_shapes:
+        K = launches[i][2]
+        w3sets = [(torch.randint(0, 256, (3 * N * K // 8,), dtype=torch.uint8, device=dev),
+                   (torch.randn((N, 8), device=dev) * 0.03).sort(dim=1).values.to(torch.float16).contiguous())
+                  for _ in range(L)]
+        xq3 = torch.randint(0, 256, (K // 2,), dtype=torch.uint8, device=dev)
+        sc3 = torch.full((1,), 0.07, dtype=torch.float16, device=dev)
+
+        def w3sweep(i=i, N=N, K=K, w3sets=w3sets, xq3=xq3, sc3=sc3):
+            for pk, cb in w3sets:
+                rcp.w3a4_gemv(pk, cb, N, K, xq3, sc3, out=outs[i])
+        w3sweep()
+        fn = capture(w3sweep)
+        fn()
+        s = timed(torch, fn, reps) / L
+        b = 3 * N * K // 8 + 16 * N + K // 2 + 2 + 2 * N
+        w3[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1)}
+        del w3sets
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
     if os.path.exists(tpath):
@@ -504,6 +525,7 @@ def main():
         "grouped_128": grouped,
         "grouped_128_step": grouped_step,
         "weight_only_fp16": weight_only,
+        "w3a4": w3,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),

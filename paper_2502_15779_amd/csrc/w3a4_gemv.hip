@@ -46,25 +46,31 @@ __device__ __forceinline__ void w3_unit_update(const W3Planes& w, const u32x4& x
     }
 }
 
-template <bool OUT_F16>
+// WS wavefronts share one row group: wavefront w of them takes the blocks w, w + WS, ... and the
+// monomial sums meet in LDS.  A workgroup therefore works on W3_WAVES / WS row groups at a time.
+template <bool OUT_F16, int WS>
 __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __restrict__ packed,
                                                                const uint4* __restrict__ codebook, int N, int K,
                                                                const uint4* __restrict__ xq,
                                                                const uint16_t* __restrict__ scale,
                                                                void* __restrict__ out, int32_t* __restrict__ Pout)
 {
-    extern __shared__ uint4 smem4[];  // x: 64 * nblk pieces of 16 bytes (zero beyond K), then W3_WAVES sums
+    // x: 64 * nblk pieces of 16 bytes (zero beyond K); W3_WAVES sums of q; for WS > 1 the exchange
+    // slots int[2 parities][W3_WAVES][4 rows][8]
+    extern __shared__ uint4 smem4[];
+    constexpr int SLOTS = W3_WAVES / WS;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wsub = wave % WS, slot = wave / WS;
     const int U = K / 32, G = N / 4;
-    const int nblk = (U + 63) >> 6;
+    const int nblk = (U + 63) >> 6;  // the launcher guarantees nblk >= WS: every wavefront has a block
+    const int nbatch = (G + SLOTS - 1) / SLOTS;
     const unsigned group_bytes = static_cast<unsigned>(U) * 48u;
     // One buffer resource over the whole matrix: a row group beyond N lands past its end and
     // reads zeros.  A lane beyond the last unit of a row group reads bytes of another plane or
     // row group; its activations in LDS are zero, so it adds nothing.
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * group_bytes), 0x00020000);
-    const int gstride = gridDim.x * W3_WAVES;
     auto load_block = [&](int gi, int j, W3Planes& w) {
         const int R = min(64, U - 64 * j);
         // the whole offset goes into the vector operand: only that one is range-checked
@@ -74,14 +80,16 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
             w.p[p] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(base + 16u * R * p), 0, 0);
     };
 
-    int gi = blockIdx.x * W3_WAVES + wave;
-    int j = 0;
+    int b = blockIdx.x;  // this workgroup's current batch of SLOTS row groups
+    int j = wsub;
     W3Planes wA, wB;
-    load_block(gi, 0, wA);  // in flight while the activations are staged
-    uint4 lut = codebook[min(4 * gi + (((lane >> 4) & 1) << 1 | (lane >> 5)), N - 1)];
+    load_block(b * SLOTS + slot, j, wA);  // in flight while the activations are staged
+    const int my_row = (((lane >> 4) & 1) << 1) | (lane >> 5);  // the row this lane holds after the folds
+    uint4 lut = codebook[min(4 * (b * SLOTS + slot) + my_row, N - 1)];
     const float S = half_bits_to_float(scale[0]);
 
     int* tsum = reinterpret_cast<int*>(smem4 + 64 * nblk);
+    int* red = tsum + W3_WAVES;
     {
         int s = 0;
         for (int i = threadIdx.x; i < 64 * nblk; i += W3_THREADS) {
@@ -98,39 +106,59 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
     }
     __syncthreads();
     const int T = tsum[0] + tsum[1] + tsum[2] + tsum[3];
-    const int my_row = (((lane >> 4) & 1) << 1) | (lane >> 5);  // the row this lane holds after the folds
 
     int acc[7][4];
 #pragma unroll
     for (int s = 0; s < 7; ++s)
 #pragma unroll
         for (int m = 0; m < 4; ++m) acc[s][m] = 0;
+    int parity = 0;
 
     // one pipeline step: issue the loads of the next position, compute the current one
     auto step = [&](W3Planes& cur, W3Planes& nxt) {
-        int jn = j + 1, gn = gi;
-        if (jn == nblk) {
-            jn = 0;
-            gn = gi + gstride;
+        int jn = j + WS, bn = b;
+        const bool last = jn >= nblk;  // uniform
+        if (last) {
+            jn = wsub;
+            bn = b + gridDim.x;
         }
-        load_block(gn, jn, nxt);  // beyond the last row group: zeros
+        load_block(bn * SLOTS + slot, jn, nxt);  // beyond the last row group: zeros
         const uint4 xv = smem4[64 * j + lane];
         const u32x4 x = {xv.x, xv.y, xv.z, xv.w};
         w3_unit_update(cur, x, acc);
-        if (jn == 0) {  // row group finished (uniform)
+        if (last) {  // this wavefront's share of the row group is finished
             // this lane's share of 2^r f_r, then the sum over the wavefront; lanes 0, 16, 32, 48
             // end up with the seven monomial sums of rows 0, 2, 1, 3
-            int f[7];
+            int F[8];
+            F[0] = T;
 #pragma unroll
             for (int s = 0; s < 7; ++s) {
                 const int g0 = acc[s][0], g1 = acc[s][1] - acc[s][0], g2 = acc[s][2] - acc[s][1], g3 = acc[s][2] - acc[s][3];
                 const int lo = fold32(g0, g1), hi = fold32(g2, g3);
-                f[s] = row_sum16(fold16(lo, hi)) >> my_row;
+                F[s + 1] = row_sum16(fold16(lo, hi)) >> my_row;
 #pragma unroll
                 for (int m = 0; m < 4; ++m) acc[s][m] = 0;
             }
-            if ((lane & 15) == 0) {
-                int F[8] = {T, f[0], f[1], f[2], f[3], f[4], f[5], f[6]};
+            if constexpr (WS > 1) {
+                int* mine = red + ((parity * W3_WAVES + wave) * 4 + my_row) * 8;
+                if ((lane & 15) == 0 && wsub != 0) {
+                    reinterpret_cast<int4*>(mine)[0] = make_int4(0, F[1], F[2], F[3]);
+                    reinterpret_cast<int4*>(mine)[1] = make_int4(F[4], F[5], F[6], F[7]);
+                }
+                __syncthreads();  // every wavefront of the workgroup finishes a batch the same number of times
+                if ((lane & 15) == 0 && wsub == 0) {
+#pragma unroll
+                    for (int w = 1; w < WS; ++w) {
+                        const int4 a = reinterpret_cast<const int4*>(mine + w * 32)[0];
+                        const int4 c = reinterpret_cast<const int4*>(mine + w * 32)[1];
+                        F[1] += a.y; F[2] += a.z; F[3] += a.w;
+                        F[4] += c.x; F[5] += c.y; F[6] += c.z; F[7] += c.w;
+                    }
+                }
+                parity ^= 1;
+            }
+            const int gi = b * SLOTS + slot;
+            if ((lane & 15) == 0 && wsub == 0 && gi < G) {
 #pragma unroll
                 for (int bit = 1; bit < 8; bit <<= 1)
 #pragma unroll
@@ -152,16 +180,39 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
                     reinterpret_cast<int4*>(Pout)[2 * h + 1] = make_int4(F[4], F[5], F[6], F[7]);
                 }
             }
-            if (gn < G) lut = codebook[min(4 * gn + my_row, N - 1)];
+            if (bn < nbatch) lut = codebook[min(4 * (bn * SLOTS + slot) + my_row, N - 1)];
         }
-        gi = gn;
+        b = bn;
         j = jn;
     };
-    while (gi < G) {
+    while (b < nbatch) {
         step(wA, wB);
-        if (gi >= G) break;
+        if (b >= nbatch) break;
         step(wB, wA);
     }
+}
+
+template <int WS>
+static int launch_w3_ws(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
+                        void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
+{
+    const int G = N / 4, U = K / 32;
+    const int nblk = (U + 63) / 64;
+    const size_t lds = static_cast<size_t>(nblk) * 64 * 16 + W3_WAVES * sizeof(int) +
+                       (WS > 1 ? 2 * W3_WAVES * 4 * 8 * sizeof(int) : 0);
+    const int cus = num_compute_units();
+    constexpr int SLOTS = W3_WAVES / WS;
+    const int nbatch = (G + SLOTS - 1) / SLOTS;
+    int blocks = options().gemv_blocks;
+    if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    if (blocks > nbatch) blocks = nbatch;
+    auto launch = [&](auto kernel) {
+        kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(packed), static_cast<const uint4*>(codebook), N, K,
+                                                static_cast<const uint4*>(xq), static_cast<const uint16_t*>(scale), out, P);
+    };
+    if (out_dt == RCP_F16) launch(&w3a4_gemv_kernel<true, WS>);
+    else launch(&w3a4_gemv_kernel<false, WS>);
+    return check_launch("rcp_w3a4_gemv");
 }
 
 int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
@@ -169,19 +220,22 @@ int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, con
 {
     if (static_cast<long long>(N) * K / 8 * 3 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w3a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(N) * K / 8 * 3);
-    const int G = N / 4, U = K / 32;
-    const int nblk = (U + 63) / 64;
-    const size_t lds = static_cast<size_t>(nblk) * 64 * 16 + W3_WAVES * sizeof(int);
-    const int cus = num_compute_units();
-    const int nbatch = (G + W3_WAVES - 1) / W3_WAVES;
-    const int blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
-    auto launch = [&](auto kernel) {
-        kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(packed), static_cast<const uint4*>(codebook), N, K,
-                                                static_cast<const uint4*>(xq), static_cast<const uint16_t*>(scale), out, P);
-    };
-    if (out_dt == RCP_F16) launch(&w3a4_gemv_kernel<true>);
-    else launch(&w3a4_gemv_kernel<false>);
-    return check_launch("rcp_w3a4_gemv");
+    const int G = N / 4, nblk = (K / 32 + 63) / 64;
+    // wavefronts per row group: the "gemv_lanes" option (64, 128, 256) or, automatically, two when
+    // there are fewer than two row groups per SIMD and each wavefront still keeps a few blocks to
+    // pipeline (sweeps: 4096 x 11008 gains 15 %, 4096 x 4096 with its two blocks loses 10 %);
+    // never more than the row group has blocks
+    int ws = options().gemv_lanes >= 64 ? options().gemv_lanes / 64 : 0;
+    if (ws == 0) {
+        const int simds = 4 * num_compute_units();
+        ws = (G < 2 * simds && nblk >= 4) ? 2 : 1;
+    }
+    while (ws > 1 && ws > nblk) ws /= 2;
+    switch (ws) {
+        case 1: return launch_w3_ws<1>(packed, codebook, N, K, xq, scale, out, out_dt, P, st);
+        case 2: return launch_w3_ws<2>(packed, codebook, N, K, xq, scale, out, out_dt, P, st);
+        default: return launch_w3_ws<4>(packed, codebook, N, K, xq, scale, out, out_dt, P, st);
+    }
 }
 
 }  // namespace rcp

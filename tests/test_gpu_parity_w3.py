@@ -25,6 +25,13 @@ def _say(msg):
     print(msg, flush=True)
 
 
+@pytest.fixture(autouse=True)
+def _auto_options():
+    yield
+    for k in ("gemv_lanes", "gemv_blocks"):
+        rcp.set_option(k, 0)
+
+
 def _nibbles(q):
     return ((q[:, 0::2].astype(np.uint8) & 0xF) | ((q[:, 1::2].astype(np.uint8) & 0xF) << 4)).astype(np.uint8)
 
@@ -100,8 +107,10 @@ def _check_w3(packed, cb, N, K, xq, sc, out_dtype):
 
 @pytest.mark.parametrize("N,K", [(4, 32), (12, 96), (256, 512), (20, 2080), (1028, 4096), (72, 11008), (40, 14336),
                                  (2048, 2048), (16, 32768), (8200, 64)])
-def test_w3_gemv_partial_sums_bit_exact_and_output_close(N, K):
-    _say(f"w3 gemv N={N} K={K}")
+@pytest.mark.parametrize("lanes", [0, 64, 128, 256])
+def test_w3_gemv_partial_sums_bit_exact_and_output_close(N, K, lanes):
+    _say(f"w3 gemv N={N} K={K} lanes={lanes}")
+    rcp.set_option("gemv_lanes", lanes)   # wavefronts per row group: automatic, 1, 2, 4
     packed, cb, xq, sc = _w3_case(N + K, N, K)
     _check_w3(packed, cb, N, K, xq, sc, torch.float32)
     _check_w3(packed, cb, N, K, xq, sc, torch.float16)
@@ -124,6 +133,17 @@ def test_w3_gemv_extreme_activations_and_integer_codebook():
     assert np.array_equal(P.cpu().numpy(), ref_P)
     assert np.array_equal(out.cpu().numpy().astype(np.float64).ravel(), ref_O)
     assert ref_P[0, 7] == -8 * K
+
+
+@pytest.mark.parametrize("lanes", [64, 128, 256])
+@pytest.mark.parametrize("blocks", [1, 3, 64])
+def test_w3_gemv_grid_stride_with_few_workgroups(blocks, lanes):
+    _say(f"w3 gemv grid-stride blocks={blocks} lanes={lanes}")
+    rcp.set_option("gemv_blocks", blocks)
+    rcp.set_option("gemv_lanes", lanes)
+    N, K = 1028, 11008
+    packed, cb, xq, sc = _w3_case(3, N, K)
+    _check_w3(packed, cb, N, K, xq, sc, torch.float32)
 
 
 @pytest.mark.parametrize("N,K", [(64, 4096), (32, 11008)])
