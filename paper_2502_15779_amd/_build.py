@@ -17,6 +17,9 @@ LIB = os.path.join(HERE, "librcp.so")
 COMPILE_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # kernel arguments arrive in scalar registers with the wavefront launch instead of being
+    # fetched by its first instructions (these kernels run for a few microseconds)
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

@@ -249,10 +249,13 @@ __device__ __forceinline__ uint16_t scale_bits_from_amax(float a, float clip_rat
 }
 
 // Eight values -> one dword of int4: nibble j = clamp(rint(y[j] / s), -8, 7), where y/s is
-// the correctly rounded binary32 quotient.  t = y * (1/s) lies within a few units in the last
-// place of that quotient, so rint(t) is already the answer unless t sits within 1e-4 of a
-// rounding boundary n + 1/2 (|t| <= 16 matters only: the error is below 4e-6 there); in that
-// rare case the eight values are redone with the IEEE division.
+// the correctly rounded binary32 quotient.  t = y * (1/s) carries two roundings, the quotient
+// one: for |t| <= 16.5 the two differ by less than 3e-6, so rint(t) is already the answer
+// unless t sits within 1e-5 of a rounding boundary n + 1/2 (beyond 16 both clamp to the same
+// end); in that rare case the eight values are redone with the IEEE division.
+// The clamped integers r_j are packed four at a time in binary32, where
+// sum_j (r_j + 8) * 16^j < 2^16 is exact, and the offset-binary nibbles become two's
+// complement by flipping each nibble's top bit.
 __device__ __forceinline__ uint32_t quantize8(const float (&y)[8], float s)
 {
     const float rs = __frcp_rn(s);
@@ -262,19 +265,18 @@ __device__ __forceinline__ uint32_t quantize8(const float (&y)[8], float s)
     for (int j = 0; j < 8; ++j) {
         const float t = __fmul_rn(y[j], rs);
         n[j] = rintf(t);
-        doubt |= fabsf(t - n[j]) > 0.4999f;
+        doubt |= fabsf(t - n[j]) > 0.49999f;
     }
     if (__builtin_expect(doubt, 0)) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) n[j] = rintf(__fdiv_rn(y[j], s));
     }
-    uint32_t w = 0;
+    float r[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float r = fminf(fmaxf(n[j], -8.0f), 7.0f);
-        w |= (static_cast<uint32_t>(static_cast<int>(r)) & 0xfu) << (4 * j);
-    }
-    return w;
+    for (int j = 0; j < 8; ++j) r[j] = fminf(fmaxf(n[j], -8.0f), 7.0f);
+    const float lo = fmaf(r[3], 4096.0f, fmaf(r[2], 256.0f, fmaf(r[1], 16.0f, r[0] + 34952.0f)));  // + 0x8888
+    const float hi = fmaf(r[7], 4096.0f, fmaf(r[6], 256.0f, fmaf(r[5], 16.0f, r[4] + 34952.0f)));
+    return (static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16)) ^ 0x88888888u;
 }
 
 }  // namespace rcp
