@@ -22,8 +22,9 @@
 // t, t + LG, t + 2 LG, ...  Few lanes per row group make the cross-lane reduction cheap
 // (it is paid once per row group) and suit tall matrices; many lanes put a small matrix on
 // enough wavefronts.  The kernel is latency bound at LLaMA sizes, so the loop is software
-// pipelined over (row group, chunk of UNR units): the loads of the next step are in flight
-// while the current one is computed and reduced, and the very first loads are issued
+// pipelined over (row group, chunk of UNR units) two steps ahead: a register set is refilled
+// as soon as its chunk is consumed, so the loads of the next step are in flight while the
+// current one is computed and reduced, and the loads of the first two steps are issued
 // before the activations are staged.
 #include <math.h>
 
@@ -170,11 +171,11 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         return (static_cast<unsigned>(bb * SLOTS + slot) * U + tg) * 16u;
     };
     const unsigned batch_stride = static_cast<unsigned>(nblk) * SLOTS * U * 16u;
-    auto load_chunk = [&](unsigned base, int ch, u32x4 (&w)[UNR]) {
+    auto load_chunk = [&](unsigned base, int ch, bool valid, u32x4 (&w)[UNR]) {
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
             const int it = ch * UNR + i;
-            const unsigned off = it < my_units ? base : 0x80000000u;
+            const unsigned off = (valid && it < my_units) ? base : 0x80000000u;
             w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), it * LG * 16, 0);
         }
     };
@@ -204,10 +205,31 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         }
     }
 
+    // The pipeline runs two steps ahead: (b, ch) is the chunk being computed, (b1, ch1) and
+    // (b2, ch2) the next two; a step goes to the following chunk of its batch, else to the first
+    // chunk of this workgroup's next batch.  The loads of the first two steps are issued here,
+    // before the activations are staged; past the last batch loads are given the offset that
+    // reads zeros.
     int b = blockIdx.x;  // this workgroup's current batch of SLOTS row groups
+    int ch = 0;
     unsigned base = batch_offset(b);
+    auto advance = [&](int& bb, int& cc, unsigned& bs) {
+        if (cc + 1 == nchunk) {
+            bb += nblk;
+            cc = 0;
+            bs += batch_stride;
+        } else
+            ++cc;
+    };
+    int b1 = b, ch1 = 0;
+    unsigned base1 = base;
+    advance(b1, ch1, base1);
+    int b2 = b1, ch2 = ch1;
+    unsigned base2 = base1;
+    advance(b2, ch2, base2);
     u32x4 wA[UNR], wB[UNR];  // the two pipeline stages alternate between these
-    load_chunk(base, 0, wA);
+    load_chunk(base, 0, b < nbatch, wA);
+    load_chunk(base1, ch1, b1 < nbatch, wB);
     int lut_row = min(4 * (b * SLOTS + slot) + my_row, N - 1);  // clamped: lanes past N read a valid row
     uint2 lut_cur = codebook[lut_row];
 
@@ -321,19 +343,11 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
             for (int m = 0; m < 4; ++m) acc[t][p][m] = 0;
 
     int parity = 0;
-    int ch = 0;
-    // One pipeline step: start the loads of the next step (the following chunk of this
-    // batch, else the first chunk of this workgroup's next batch; past the end the loads
-    // read zeros and cost no traffic), then compute the current chunk from `w`.
-    auto step = [&](u32x4 (&w)[UNR], u32x4 (&wnext)[UNR]) {
+    // One pipeline step: compute the current chunk from `w` (the loads of the following chunk are
+    // in flight in the other register set), then start the loads of the chunk two steps ahead
+    // into `w`.
+    auto step = [&](u32x4 (&w)[UNR]) {
         const bool last = ch + 1 == nchunk;
-        const int b2 = last ? b + nblk : b;
-        const int ch2 = last ? 0 : ch + 1;
-        const unsigned base2 = base + (last ? batch_stride : 0u);
-        load_chunk(base2, ch2, wnext);
-        // keep the compiler from hoisting work on `w` above the loads just issued: it
-        // would have to wait for `w` to arrive first and the loads would start late
-        __builtin_amdgcn_sched_barrier(0);
 
         const uint2* xrow = sx2 + tg + ch * UNR * LG;
 #pragma unroll
@@ -348,6 +362,10 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
             cell_update<MT>(w[i].x, w[i].y, xa, acc);
             cell_update<MT>(w[i].z, w[i].w, xb, acc);
         }
+        // `w` is consumed: refill it, before the reduction and the epilogue below
+        __builtin_amdgcn_sched_barrier(0);
+        load_chunk(base2, ch2, b2 < nbatch, w);
+        __builtin_amdgcn_sched_barrier(0);
 
         if (last) {
             // The triangular solve is linear, so it is applied per lane before the reduction
@@ -424,14 +442,18 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
             lut_row = min(lut_row + 4 * nblk * SLOTS, N - 1);
             lut_cur = codebook[lut_row];
         }
-        b = b2;
-        ch = ch2;
-        base = base2;
+        b = b1;
+        ch = ch1;
+        base = base1;
+        b1 = b2;
+        ch1 = ch2;
+        base1 = base2;
+        advance(b2, ch2, base2);
     };
     while (true) {
-        step(wA, wB);
+        step(wA);
         if (b >= nbatch) break;
-        step(wB, wA);
+        step(wB);
         if (b >= nbatch) break;
     }
 }
