@@ -126,13 +126,15 @@ __device__ __forceinline__ void heads_columns(float* sy, int m, float norm)
     }
 }
 
+// The first 64 bytes of arguments reach the wavefront in scalar registers at launch; everything the
+// prologue needs at once (matrix, shape, activations) is among them.
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT>
 __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restrict__ packed,
                                                             const uint2* __restrict__ codebook, int N, int K,
+                                                            const void* __restrict__ xraw,
                                                             const uint4* __restrict__ xq,
-                                                            const uint16_t* __restrict__ scale, int M,
+                                                            const uint16_t* __restrict__ scale, int M, float clip_ratio,
                                                             void* __restrict__ out, int32_t* __restrict__ Pout,
-                                                            const void* __restrict__ xraw, float clip_ratio,
                                                             uint32_t* __restrict__ xq_out, uint16_t* __restrict__ scale_out,
                                                             int rot_n, int rot_m, float rot_norm)
 {
@@ -495,8 +497,8 @@ static int launch_one(const GemvArgs& a, int blocks, hipStream_t st)
         if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_w2a4_gemv: LDS opt-in failed: %s", hipGetErrorString(e));
     }
     kernel<<<blocks, GEMV_THREADS, lds, st>>>(
-        static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K,
-        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.M, a.out, a.P, a.xraw, a.clip_ratio,
+        static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K, a.xraw,
+        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.M, a.clip_ratio, a.out, a.P,
         static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out), a.rot_n, a.rot_m,
         a.rot_n > 0 ? static_cast<float>(1.0 / sqrt(static_cast<double>(a.rot_n))) : 1.0f);
     return check_launch("rcp_w2a4_gemv");
