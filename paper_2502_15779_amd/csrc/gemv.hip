@@ -188,7 +188,8 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
     const int per_token = xdw / 4;  // 16-byte pieces of one token's activations
     u32x4 xfirst[MT];
     float sc[MT];
-    float xr8[XDT >= 0 ? GEMV_XG : 1][8];  // raw activations of the fused path
+    float xr8[XDT >= 0 ? GEMV_XG : 1][8];  // raw activations of the fused path, widened to fp32 ...
+    Raw8<XT> xraw8[XDT >= 0 ? GEMV_XG : 1];  // ... and as they come from memory
     if constexpr (XDT < 0) {
 #pragma unroll
         for (int t = 0; t < MT; ++t) {
@@ -203,7 +204,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         for (int i = 0; i < GEMV_XG; ++i) {
             if (i * GEMV_THREADS >= xdw) break;  // uniform: whole blocks of 256 groups
             const int u8 = min(static_cast<int>(threadIdx.x) + i * GEMV_THREADS, xdw - 1);  // clamped: duplicates are harmless
-            load8_as_float<XT>(xraw, static_cast<size_t>(u8) * 8, xr8[i]);
+            xraw8[i] = load8_raw<XT>(xraw, static_cast<size_t>(u8) * 8);
         }
     }
 
@@ -234,6 +235,18 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
     load_chunk(base1, ch1, b1 < nbatch, wB);
     int lut_row = min(4 * (b * SLOTS + slot) + my_row, N - 1);  // clamped: lanes past N read a valid row
     uint2 lut_cur = codebook[lut_row];
+    // the arguments that did not arrive in registers are fetched while the loads above are in flight,
+    // not where the quantiser or the epilogue first needs them
+    asm volatile("" ::"s"(out), "s"(Pout), "s"(xq_out), "s"(scale_out));
+    if constexpr (XDT >= 0) {
+        // only now touch the activations: waiting for them any earlier would hold back the weight loads
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < GEMV_XG; ++i) {
+            if (i * GEMV_THREADS >= xdw) break;
+            widen8<XT>(xraw8[i], xr8[i]);
+        }
+    }
 
     // stage the activations and sum them: T[t] = sum_k q[t][k], the same for every row
     const int x_bytes = gemv_x_bytes(K, M, LG * UNR);

@@ -94,21 +94,41 @@ __device__ __forceinline__ float load_as_float(const void* p, size_t i)
     else return bf16_bits_to_float(static_cast<const uint16_t*>(p)[i]);
 }
 
-// Eight consecutive elements starting at element index i (a multiple of 8).
+// Eight consecutive elements starting at element index i (a multiple of 8), in two steps so that a
+// kernel can issue other loads between the memory access and the first use of its result:
+// the raw 16 (two-byte types) or 32 bytes, then the exact widening to fp32.
 template <int DT>
-__device__ __forceinline__ void load8_as_float(const void* p, size_t i, float (&v)[8])
+struct Raw8 {
+    uint4 a;
+    uint4 b;  // second half of eight fp32 values; unused for the two-byte types
+};
+
+template <int DT>
+__device__ __forceinline__ Raw8<DT> load8_raw(const void* p, size_t i)
+{
+    Raw8<DT> r;
+    if constexpr (DT == RCP_F32) {
+        const uint4* q = reinterpret_cast<const uint4*>(static_cast<const float*>(p) + i);
+        r.a = q[0];
+        r.b = q[1];
+    } else {
+        r.a = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p) + i);
+        r.b = make_uint4(0u, 0u, 0u, 0u);
+    }
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ void widen8(const Raw8<DT>& r, float (&v)[8])
 {
     if constexpr (DT == RCP_F32) {
-        const float4* q = reinterpret_cast<const float4*>(static_cast<const float*>(p) + i);
-        float4 a = q[0], b = q[1];
-        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        v[0] = __uint_as_float(r.a.x); v[1] = __uint_as_float(r.a.y); v[2] = __uint_as_float(r.a.z); v[3] = __uint_as_float(r.a.w);
+        v[4] = __uint_as_float(r.b.x); v[5] = __uint_as_float(r.b.y); v[6] = __uint_as_float(r.b.z); v[7] = __uint_as_float(r.b.w);
     } else {
-        uint4 raw = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p) + i);
-        uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            uint16_t lo16 = static_cast<uint16_t>(w[e] & 0xffffu), hi16 = static_cast<uint16_t>(w[e] >> 16);
+            const uint16_t lo16 = static_cast<uint16_t>(w[e] & 0xffffu), hi16 = static_cast<uint16_t>(w[e] >> 16);
             if constexpr (DT == RCP_F16) {
                 v[2 * e] = half_bits_to_float(lo16);
                 v[2 * e + 1] = half_bits_to_float(hi16);
@@ -118,6 +138,12 @@ __device__ __forceinline__ void load8_as_float(const void* p, size_t i, float (&
             }
         }
     }
+}
+
+template <int DT>
+__device__ __forceinline__ void load8_as_float(const void* p, size_t i, float (&v)[8])
+{
+    widen8<DT>(load8_raw<DT>(p, i), v);
 }
 
 // ---- wavefront-wide reductions without LDS traffic: DPP rotations inside each row of 16
@@ -260,20 +286,20 @@ __device__ __forceinline__ uint32_t quantize8(const float (&y)[8], float s)
 {
     const float rs = __frcp_rn(s);
     float n[8];
-    bool doubt = false;
+    float far = 0.0f;  // largest distance of a t from its rounded value (one maximum instead of eight tests)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const float t = __fmul_rn(y[j], rs);
         n[j] = rintf(t);
-        doubt |= fabsf(t - n[j]) > 0.49999f;
+        far = fmaxf(far, fabsf(t - n[j]));
     }
-    if (__builtin_expect(doubt, 0)) {
+    if (__builtin_expect(far > 0.49999f, 0)) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) n[j] = rintf(__fdiv_rn(y[j], s));
     }
     float r[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) r[j] = fminf(fmaxf(n[j], -8.0f), 7.0f);
+    for (int j = 0; j < 8; ++j) r[j] = __builtin_amdgcn_fmed3f(n[j], -8.0f, 7.0f);
     const float lo = fmaf(r[3], 4096.0f, fmaf(r[2], 256.0f, fmaf(r[1], 16.0f, r[0] + 34952.0f)));  // + 0x8888
     const float hi = fmaf(r[7], 4096.0f, fmaf(r[6], 256.0f, fmaf(r[5], 16.0f, r[4] + 34952.0f)));
     return (static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16)) ^ 0x88888888u;
