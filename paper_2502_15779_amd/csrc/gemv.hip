@@ -128,8 +128,8 @@ __device__ __forceinline__ void heads_columns(float* sy, int m, float norm)
 
 // The first 64 bytes of arguments reach the wavefront in scalar registers at launch; everything the
 // prologue needs at once (matrix, shape, activations) is among them.
-template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT>
-__global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restrict__ packed,
+template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT, int NW>
+__global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__ packed,
                                                             const uint2* __restrict__ codebook, int N, int K,
                                                             const void* __restrict__ xraw,
                                                             const uint4* __restrict__ xq,
@@ -139,12 +139,14 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
                                                             int rot_n, int rot_m, float rot_norm)
 {
     static_assert(WS == 1 || LW == 64, "several wavefronts per row group only with whole wavefronts");
+    static_assert(NW == 4 || (NW == 8 && XDT >= 0 && XDT < 4), "eight wavefronts: the fused quantiser without rotation");
+    constexpr int TH = NW * 64;  // threads of the workgroup
     static_assert(XDT < 0 || MT == 1, "the fused quantiser handles one token");
     constexpr bool ROT = XDT >= 4;              // Hadamard across heads in the prologue
     constexpr int XT = XDT >= 0 ? (XDT & 3) : 0;  // storage type of the raw activation
     extern __shared__ uint4 smem4[];
     constexpr int SW = 64 / LW;                     // row groups side by side in a wavefront
-    constexpr int SLOTS = (GEMV_WAVES / WS) * SW;   // row groups a workgroup works on at a time
+    constexpr int SLOTS = (NW / WS) * SW;   // row groups a workgroup works on at a time
     constexpr int LG = LW * WS;                     // lanes per row group
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -202,8 +204,8 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
     } else {
 #pragma unroll
         for (int i = 0; i < GEMV_XG; ++i) {
-            if (i * GEMV_THREADS >= xdw) break;  // uniform: whole blocks of 256 groups
-            const int u8 = min(static_cast<int>(threadIdx.x) + i * GEMV_THREADS, xdw - 1);  // clamped: duplicates are harmless
+            if (i * TH >= xdw) break;  // uniform: whole blocks of 256 groups
+            const int u8 = min(static_cast<int>(threadIdx.x) + i * TH, xdw - 1);  // clamped: duplicates are harmless
             xraw8[i] = load8_raw<XT>(xraw, static_cast<size_t>(u8) * 8);
         }
     }
@@ -243,15 +245,15 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < GEMV_XG; ++i) {
-            if (i * GEMV_THREADS >= xdw) break;
+            if (i * TH >= xdw) break;
             widen8<XT>(xraw8[i], xr8[i]);
         }
     }
 
     // stage the activations and sum them: T[t] = sum_k q[t][k], the same for every row
     const int x_bytes = gemv_x_bytes(K, M, LG * UNR);
-    int* tsum = reinterpret_cast<int*>(reinterpret_cast<char*>(smem4) + x_bytes);  // [GEMV_WAVES][MT]
-    int* red = tsum + GEMV_WAVES * MT + 4;  // 4 slots in between serve the fused quantiser's maximum
+    int* tsum = reinterpret_cast<int*>(reinterpret_cast<char*>(smem4) + x_bytes);  // [NW][MT]
+    int* red = tsum + NW * MT + NW;  // NW slots in between serve the fused quantiser's maximum
     if constexpr (XDT < 0) {
         u32x4* sx4 = reinterpret_cast<u32x4*>(smem4);
 #pragma unroll
@@ -264,7 +266,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
                 s = dot8(xfirst[t].y, 0x11111111u, s);
                 s = dot8(xfirst[t].z, 0x11111111u, s);
                 s = dot8(xfirst[t].w, 0x11111111u, s);
-                for (int i = threadIdx.x + GEMV_THREADS; i < per_token; i += GEMV_THREADS) {  // K > 8192 only
+                for (int i = threadIdx.x + TH; i < per_token; i += TH) {  // K > 8192 only
                     const uint4 v = xq[t * per_token + i];
                     smem4[t * per_token + i] = v;
                     s = dot8(v.x, 0x11111111u, s);
@@ -280,11 +282,11 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         if constexpr (ROT) {
             // y = (H_n (x) I_m) x through LDS: every thread parks its values, then takes whole columns
             // (the rot_n values x[i*m + j]) through the butterflies in ascending stride order
-            float* sy = reinterpret_cast<float*>(red + (WS > 1 ? 2 * GEMV_WAVES * 4 * 3 * MT : 0));
+            float* sy = reinterpret_cast<float*>(red + (WS > 1 ? 2 * NW * 4 * 3 * MT : 0));
 #pragma unroll
             for (int i = 0; i < GEMV_XG; ++i) {
-                if (i * GEMV_THREADS >= xdw) break;
-                const int u8 = threadIdx.x + i * GEMV_THREADS;
+                if (i * TH >= xdw) break;
+                const int u8 = threadIdx.x + i * TH;
                 if (u8 < xdw) {
                     reinterpret_cast<float4*>(sy)[2 * u8] = make_float4(xr8[i][0], xr8[i][1], xr8[i][2], xr8[i][3]);
                     reinterpret_cast<float4*>(sy)[2 * u8 + 1] = make_float4(xr8[i][4], xr8[i][5], xr8[i][6], xr8[i][7]);
@@ -302,8 +304,8 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < GEMV_XG; ++i) {
-                if (i * GEMV_THREADS >= xdw) break;
-                const int u8 = min(static_cast<int>(threadIdx.x) + i * GEMV_THREADS, xdw - 1);
+                if (i * TH >= xdw) break;
+                const int u8 = min(static_cast<int>(threadIdx.x) + i * TH, xdw - 1);
                 const float4 lo4 = reinterpret_cast<const float4*>(sy)[2 * u8], hi4 = reinterpret_cast<const float4*>(sy)[2 * u8 + 1];
                 xr8[i][0] = lo4.x; xr8[i][1] = lo4.y; xr8[i][2] = lo4.z; xr8[i][3] = lo4.w;
                 xr8[i][4] = hi4.x; xr8[i][5] = hi4.y; xr8[i][6] = hi4.z; xr8[i][7] = hi4.w;
@@ -313,15 +315,17 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         float a = 0.0f;
 #pragma unroll
         for (int i = 0; i < GEMV_XG; ++i) {
-            if (i * GEMV_THREADS >= xdw) break;
+            if (i * TH >= xdw) break;
 #pragma unroll
             for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(xr8[i][j]));
         }
         a = wave_max(a);
-        float* amax_slots = reinterpret_cast<float*>(tsum + GEMV_WAVES * MT);  // 4 floats after the sums
+        float* amax_slots = reinterpret_cast<float*>(tsum + NW * MT);  // NW floats after the sums
         if (lane == 0) amax_slots[wave] = a;
         __syncthreads();
         a = fmaxf(fmaxf(amax_slots[0], amax_slots[1]), fmaxf(amax_slots[2], amax_slots[3]));
+        if constexpr (NW == 8)
+            a = fmaxf(a, fmaxf(fmaxf(amax_slots[4], amax_slots[5]), fmaxf(amax_slots[6], amax_slots[7])));
         const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
         const float sq = half_bits_to_float(sb);
         sc[0] = sq;
@@ -330,8 +334,8 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
         int s = 0;
 #pragma unroll
         for (int i = 0; i < GEMV_XG; ++i) {
-            if (i * GEMV_THREADS >= xdw) break;
-            const int u8 = threadIdx.x + i * GEMV_THREADS;
+            if (i * TH >= xdw) break;
+            const int u8 = threadIdx.x + i * TH;
             if (u8 < xdw) {
                 const uint32_t qd = quantize8(xr8[i], sq);
                 sx1[u8] = qd;
@@ -347,7 +351,10 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
     const uint2* sx2 = reinterpret_cast<const uint2*>(smem4);
     int T[MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t) T[t] = tsum[t] + tsum[MT + t] + tsum[2 * MT + t] + tsum[3 * MT + t];
+    for (int t = 0; t < MT; ++t) {
+        T[t] = tsum[t] + tsum[MT + t] + tsum[2 * MT + t] + tsum[3 * MT + t];
+        if constexpr (NW == 8) T[t] += tsum[4 * MT + t] + tsum[5 * MT + t] + tsum[6 * MT + t] + tsum[7 * MT + t];
+    }
 
     int acc[MT][3][4];
 #pragma unroll
@@ -407,7 +414,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
                 // wavefront of the slot adds the others.  Two buffers alternate so that one
                 // barrier per batch is enough.
                 const int rho = lane >> 4;
-                int* mine = red + ((parity * GEMV_WAVES + wave) * 4 + rho) * (3 * MT);
+                int* mine = red + ((parity * NW + wave) * 4 + rho) * (3 * MT);
                 if ((lane & 15) == 0) {
 #pragma unroll
                     for (int t = 0; t < MT; ++t)
@@ -418,7 +425,7 @@ __global__ __launch_bounds__(GEMV_THREADS) void gemv_kernel(const uint4* __restr
                 if (wsub == 0 && (lane & 15) == 0) {
 #pragma unroll
                     for (int ws = 1; ws < WS; ++ws) {
-                        const int* other = red + ((parity * GEMV_WAVES + wave + ws) * 4 + rho) * (3 * MT);
+                        const int* other = red + ((parity * NW + wave + ws) * 4 + rho) * (3 * MT);
 #pragma unroll
                         for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -495,26 +502,41 @@ struct GemvArgs {
     int rot_n, rot_m;  // Hadamard across rot_n heads of rot_m channels in the prologue (0: none)
 };
 
-template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT>
+template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT, int NW = GEMV_WAVES>
 static int launch_one(const GemvArgs& a, int blocks, hipStream_t st)
 {
-    const size_t lds = gemv_x_bytes(a.K, a.M, LW * WS * UNR) + (GEMV_WAVES * MT + 4) * sizeof(int) +
-                       (WS > 1 ? 2 * GEMV_WAVES * 4 * 3 * MT * sizeof(int) : 0) +
+    const size_t lds = gemv_x_bytes(a.K, a.M, LW * WS * UNR) + (NW * MT + NW) * sizeof(int) +
+                       (WS > 1 ? 2 * NW * 4 * 3 * MT * sizeof(int) : 0) +
                        (XDT >= 4 ? static_cast<size_t>(a.K) * sizeof(float) + 16 : 0);
     if (lds > 160 * 1024)
         return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a4_gemv: M*K/2 = %d bytes of activations exceed the LDS budget", a.M * (a.K / 2));
-    auto kernel = &gemv_kernel<LW, WS, UNR, MT, OUT_F16, XDT>;
+    auto kernel = &gemv_kernel<LW, WS, UNR, MT, OUT_F16, XDT, NW>;
     if (lds > 65536) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
         if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_w2a4_gemv: LDS opt-in failed: %s", hipGetErrorString(e));
     }
-    kernel<<<blocks, GEMV_THREADS, lds, st>>>(
+    kernel<<<blocks, NW * 64, lds, st>>>(
         static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K, a.xraw,
         static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.M, a.clip_ratio, a.out, a.P,
         static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out), a.rot_n, a.rot_m,
         a.rot_n > 0 ? static_cast<float>(1.0 / sqrt(static_cast<double>(a.rot_n))) : 1.0f);
     return check_launch("rcp_w2a4_gemv");
+}
+
+// The fused one-token call on eight wavefronts, two per row group: for matrices with so few rows that
+// every compute unit gets a single workgroup, the quantiser and the dot products of that workgroup
+// then run on two wavefronts per SIMD.
+template <int UNR>
+static int launch_wide(const GemvArgs& a, int blocks, hipStream_t st)
+{
+#define RCP_GO8(XDT)                                                                       \
+    return a.out_dt == RCP_F16 ? launch_one<64, 2, UNR, 1, true, XDT, 8>(a, blocks, st)    \
+                               : launch_one<64, 2, UNR, 1, false, XDT, 8>(a, blocks, st)
+    if (a.x_dt == RCP_F16) RCP_GO8(RCP_F16);
+    if (a.x_dt == RCP_F32) RCP_GO8(RCP_F32);
+    RCP_GO8(RCP_BF16);
+#undef RCP_GO8
 }
 
 template <int LW, int WS, int UNR>
@@ -597,6 +619,21 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
         p.ws = 1;
         const int nbatch = (a.N / 4 + GEMV_WAVES - 1) / GEMV_WAVES;
         if (p.blocks > nbatch) p.blocks = nbatch;
+    }
+    // one token, fused quantiser, no rotation, a single workgroup per compute unit and a long input
+    // (the quantiser's share grows with K): eight wavefronts.  Sweeps: 4096 x 11008 gains 9 %,
+    // 4096 x 4096 nothing, matrices with more workgroups than compute units lose.
+    // ("gemv_waves" = 8 forces this form, 4 forbids it)
+    const int want_waves = options().gemv_waves;
+    const bool wide_ok = a.xraw != nullptr && a.rot_n == 0 && a.K / 16 >= 128 && options().gemv_lanes == 0;
+    // (with fp32 activations the two forms are within 2 % of each other: left on four wavefronts)
+    const bool wide_pays = (a.N / 4 + 3) / 4 <= num_compute_units() && a.K >= 8192 && a.x_dt != RCP_F32;
+    if (wide_ok && (want_waves == 8 || (want_waves == 0 && wide_pays))) {
+        const int nbatch = (a.N / 4 + 3) / 4;  // four row groups per workgroup, as with four wavefronts
+        int blocks = options().gemv_blocks;
+        if (blocks == 0 || blocks > nbatch) blocks = nbatch;
+        if (blocks > 2 * num_compute_units() && options().gemv_blocks == 0) blocks = 2 * num_compute_units();
+        return options().gemv_unroll == 4 ? launch_wide<4>(a, blocks, st) : launch_wide<2>(a, blocks, st);
     }
     if (p.unr == 2) {
         switch (p.lw * p.ws) {

@@ -22,6 +22,7 @@ struct Options {
     int gemv_blocks;     // workgroups launched by the GEMV
     int gemv_variant;    // 0 automatic, 1 plain-ALU kernel for every M, 2 matrix-core kernel for every M
     int gemm_waves;      // wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
+    int gemv_waves;      // wavefronts per workgroup of the fused one-token GEMV: 4 or 8
 };
 Options& options();
 int num_compute_units();

@@ -31,7 +31,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves"):
         rcp.set_option(k, 0)
 
 
@@ -460,12 +460,15 @@ def test_matrix_core_kernel_extreme_activations():
     assert np.array_equal(out.cpu().numpy().astype(np.float64), ref_O)
 
 
+@pytest.mark.parametrize("waves", [0, 4, 8])
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
 @pytest.mark.parametrize("N,K,ratio", [(256, 512, 1.0), (1028, 4096, 1.0), (40, 2080, 0.9), (64, 11008, 1.0),
-                                       (24, 16384, 1.0), (16, 32768, 1.0), (4, 32, 1.0)])
-def test_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype):
-    """rcp_quant_w2a4_gemv: x_q, S and P bit-exact against the oracle's quantiser + GEMV."""
-    _say(f"fused N={N} K={K} ratio={ratio} {dtype}")
+                                       (24, 16384, 1.0), (16, 32768, 1.0), (4, 32, 1.0), (2052, 2048, 1.0)])
+def test_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype, waves):
+    """rcp_quant_w2a4_gemv: x_q, S and P bit-exact against the oracle's quantiser + GEMV, with four and
+    with eight wavefronts per workgroup."""
+    _say(f"fused N={N} K={K} ratio={ratio} {dtype} waves={waves}")
+    rcp.set_option("gemv_waves", waves)
     packed, cb, _, _ = _gemv_case(N * 3 + K, N, K, 1)
     x16 = rcp_synth.activation(5, f"fused{K}", 1, K)
     if dtype == "f16":
