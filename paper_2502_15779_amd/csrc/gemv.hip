@@ -472,12 +472,18 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
         base1 = base2;
         advance(b2, ch2, base2);
     };
-    while (true) {
+    // The steps of this workgroup are counted up front and run in pairs, so that the loop has one
+    // body (wA, then wB) and one exit.  With an exit after either step the two exit branches are
+    // merged with the back edge, the wait-count analysis then sees a path "refill of wA just
+    // issued -> top of the loop" and makes every other step wait for all loads in flight, which
+    // undoes the prefetching.
+    const int my_batches = (nbatch - static_cast<int>(blockIdx.x) + nblk - 1) / nblk;
+    const int nsteps = my_batches * nchunk;
+    for (int i = 0; i < nsteps / 2; ++i) {
         step(wA);
-        if (b >= nbatch) break;
         step(wB);
-        if (b >= nbatch) break;
     }
+    if (nsteps & 1) step(wA);
 }
 
 constexpr int GEMM_MFMA_MIN_M = 4;  // fewer tokens always stay on the plain-ALU kernel
