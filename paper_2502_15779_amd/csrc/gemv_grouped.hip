@@ -89,7 +89,21 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
         s.lut[1] = __builtin_amdgcn_raw_buffer_load_b128(cres, static_cast<int>(coff), 16, 0);
     };
 
+    // The pipeline runs two steps ahead: (b, rd) is the step being computed, (b1, rd1) and (b2, rd2)
+    // the next two (the following round of 32 groups, else the first round of this workgroup's next
+    // batch); the loads of the first two steps are issued before the activations are staged.
     int b = blockIdx.x, rd = 0;
+    auto advance = [&](int& bb, int& rr) {
+        if (rr + 1 == nround) {
+            rr = 0;
+            bb += nblk;
+        } else
+            ++rr;
+    };
+    int b1 = b, rd1 = rd;
+    advance(b1, rd1);
+    int b2 = b1, rd2 = rd1;
+    advance(b2, rd2);
     GroupStep sA, sB;
     float S;
     if constexpr (XDT < 0) {
@@ -101,6 +115,8 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             xg[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, static_cast<int>(threadIdx.x) * 64, i * 16, 0);
         S = half_bits_to_float(scale[0]);
         load_step(b, rd, sA);
+        load_step(b1, rd1, sB);
+        asm volatile("" ::"s"(out), "s"(Pout));  // fetch the late arguments while the loads are in flight
 
         if (static_cast<int>(threadIdx.x) < NG) {
             const int g = threadIdx.x;
@@ -125,15 +141,29 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
         // in registers between the two passes (maximum, then quantisation), further ones (K > 4096)
         // are read again from cache.
         __shared__ float amax_slots[GG_THREADS / 64];
+        constexpr int XT = XDT >= 0 ? XDT : 0;
         float first[2][8];
         float a = 0.0f;
+        // the activations are requested first (memory answers in issue order), the weights of the
+        // first two steps right behind them, and only then is anything waited for
+        Raw8<XT> xr[GG_XU][2];
 #pragma unroll
         for (int i = 0; i < GG_XU; ++i) {
             if (i * GG_THREADS >= U) break;  // uniform
             const int u = min(static_cast<int>(threadIdx.x) + i * GG_THREADS, U - 1);  // clamped: duplicates are harmless
+            xr[i][0] = load8_raw<XT>(xraw, static_cast<size_t>(u) * 16);
+            xr[i][1] = load8_raw<XT>(xraw, static_cast<size_t>(u) * 16 + 8);
+        }
+        load_step(b, rd, sA);
+        load_step(b1, rd1, sB);
+        asm volatile("" ::"s"(out), "s"(Pout), "s"(xq_out), "s"(scale_out), "s"(clip_ratio));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < GG_XU; ++i) {
+            if (i * GG_THREADS >= U) break;
             float v[2][8];
-            load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16, v[0]);
-            load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16 + 8, v[1]);
+            widen8<XT>(xr[i][0], v[0]);
+            widen8<XT>(xr[i][1], v[1]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 a = fmaxf(a, fmaxf(fabsf(v[0][j]), fabsf(v[1][j])));
@@ -143,7 +173,6 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
                 }
             }
         }
-        load_step(b, rd, sA);
         for (int g = threadIdx.x; g < NG; g += GG_THREADS) tgs[g] = 0;
         a = wave_max(a);
         if (lane == 0) amax_slots[wave] = a;
@@ -181,15 +210,10 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
 
     float o[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 
-    // One pipeline step: start the loads of the next step, then compute the current one.
-    auto step = [&](GroupStep& cur, GroupStep& next) {
+    // One pipeline step: compute the current step from `cur` (the loads of the following step are in
+    // flight in the other register set), then refill `cur` with the step two ahead.
+    auto step = [&](GroupStep& cur) {
         const bool last = rd + 1 == nround;
-        const int b2 = last ? b + nblk : b;
-        const int rd2 = last ? 0 : rd + 1;
-        load_step(b2, rd2, next);
-        // no work on `cur` may move above the loads just issued (it would wait for `cur`
-        // first and start the loads late)
-        __builtin_amdgcn_sched_barrier(0);
 
         const int R = min(32, NG - 32 * rd);
         const uint2* xp = sx2 + 256 * rd + ln;
@@ -239,6 +263,11 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
                 reinterpret_cast<int4*>(Pout)[static_cast<size_t>(4 * rg + r) * NG + g] = make_int4(P0, P1, P2, P3);
         }
 
+        // `cur` is consumed: refill it, before the row totals below
+        __builtin_amdgcn_sched_barrier(0);
+        load_step(b2, rd2, cur);
+        __builtin_amdgcn_sched_barrier(0);
+
         if (last) {
             // row totals over the 32 lanes of the row group: even 16-lane rows end up with
             // rows 0 and 2, odd ones with rows 1 and 3
@@ -258,15 +287,21 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             }
             o[0] = o[1] = o[2] = o[3] = 0.0f;
         }
-        b = b2;
-        rd = rd2;
+        b = b1;
+        rd = rd1;
+        b1 = b2;
+        rd1 = rd2;
+        advance(b2, rd2);
     };
-    while (true) {
-        step(sA, sB);
-        if (b >= nbatch) break;
-        step(sB, sA);
-        if (b >= nbatch) break;
+    // steps counted up front and run in pairs: one loop body, one exit (with an exit after either
+    // step the merged exit branches make the wait-count analysis stall on all loads in flight)
+    const int my_batches = (nbatch - static_cast<int>(blockIdx.x) + nblk - 1) / nblk;
+    const int nsteps = my_batches * nround;
+    for (int i = 0; i < nsteps / 2; ++i) {
+        step(sA);
+        step(sB);
     }
+    if (nsteps & 1) step(sA);
 }
 
 struct GroupedArgs {

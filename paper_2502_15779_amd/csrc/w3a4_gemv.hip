@@ -73,17 +73,35 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
         const_cast<uint8_t*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * group_bytes), 0x00020000);
     auto load_block = [&](int gi, int j, W3Planes& w) {
         const int R = min(64, U - 64 * j);
-        // the whole offset goes into the vector operand: only that one is range-checked
-        const unsigned base = static_cast<unsigned>(gi) * group_bytes + 3072u * j + 16u * lane;
+        // the whole offset goes into the vector operand: only that one is range-checked; a row group
+        // past the end gets an offset beyond any matrix (they are below 2 GiB)
+        const unsigned base = gi < G ? static_cast<unsigned>(gi) * group_bytes + 3072u * j + 16u * lane : 0x80000000u;
 #pragma unroll
         for (int p = 0; p < 3; ++p)
             w.p[p] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(base + 16u * R * p), 0, 0);
     };
 
+    // The pipeline runs two steps ahead: (b, j) is the block being computed, (b1, j1) and (b2, j2)
+    // the next two; a wavefront goes to its following block of the row group, else to its first
+    // block in the workgroup's next batch.  The loads of the first two steps are issued here,
+    // before the activations are staged; row groups past the end read zeros.
     int b = blockIdx.x;  // this workgroup's current batch of SLOTS row groups
     int j = wsub;
+    const int bstride = gridDim.x;
+    auto advance = [&](int& bb, int& jj) {
+        jj += WS;
+        if (jj >= nblk) {
+            jj = wsub;
+            bb += bstride;
+        }
+    };
+    int b1 = b, j1 = j;
+    advance(b1, j1);
+    int b2 = b1, j2 = j1;
+    advance(b2, j2);
     W3Planes wA, wB;
-    load_block(b * SLOTS + slot, j, wA);  // in flight while the activations are staged
+    load_block(b * SLOTS + slot, j, wA);
+    load_block(b1 * SLOTS + slot, j1, wB);
     const int my_row = (((lane >> 4) & 1) << 1) | (lane >> 5);  // the row this lane holds after the folds
     uint4 lut = codebook[min(4 * (b * SLOTS + slot) + my_row, N - 1)];
     const float S = half_bits_to_float(scale[0]);
@@ -114,18 +132,17 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
         for (int m = 0; m < 4; ++m) acc[s][m] = 0;
     int parity = 0;
 
-    // one pipeline step: issue the loads of the next position, compute the current one
-    auto step = [&](W3Planes& cur, W3Planes& nxt) {
-        int jn = j + WS, bn = b;
-        const bool last = jn >= nblk;  // uniform
-        if (last) {
-            jn = wsub;
-            bn = b + gridDim.x;
-        }
-        load_block(bn * SLOTS + slot, jn, nxt);  // beyond the last row group: zeros
+    // one pipeline step: compute the current block from `cur` (the loads of the following block are
+    // in flight in the other register set), then refill `cur` with the block two steps ahead
+    auto step = [&](W3Planes& cur) {
+        const bool last = j + WS >= nblk;  // uniform
+        const int bn = b1;
         const uint4 xv = smem4[64 * j + lane];
         const u32x4 x = {xv.x, xv.y, xv.z, xv.w};
         w3_unit_update(cur, x, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        load_block(b2 * SLOTS + slot, j2, cur);
+        __builtin_amdgcn_sched_barrier(0);
         if (last) {  // this wavefront's share of the row group is finished
             // this lane's share of 2^r f_r, then the sum over the wavefront; lanes 0, 16, 32, 48
             // end up with the seven monomial sums of rows 0, 2, 1, 3
@@ -182,14 +199,21 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
             }
             if (bn < nbatch) lut = codebook[min(4 * (bn * SLOTS + slot) + my_row, N - 1)];
         }
-        b = bn;
-        j = jn;
+        b = b1;
+        j = j1;
+        b1 = b2;
+        j1 = j2;
+        advance(b2, j2);
     };
-    while (b < nbatch) {
-        step(wA, wB);
-        if (b >= nbatch) break;
-        step(wB, wA);
+    // steps counted up front and run in pairs: one loop body, one exit (with an exit after either
+    // step the merged exit branches make the wait-count analysis stall on all loads in flight)
+    const int my_batches = (nbatch - static_cast<int>(blockIdx.x) + static_cast<int>(gridDim.x) - 1) / static_cast<int>(gridDim.x);
+    const int nsteps = my_batches * ((nblk - wsub + WS - 1) / WS);
+    for (int i = 0; i < nsteps / 2; ++i) {
+        step(wA);
+        step(wB);
     }
+    if (nsteps & 1) step(wA);
 }
 
 template <int WS>
@@ -204,7 +228,7 @@ static int launch_w3_ws(const void* packed, const void* codebook, int N, int K, 
     constexpr int SLOTS = W3_WAVES / WS;
     const int nbatch = (G + SLOTS - 1) / SLOTS;
     int blocks = options().gemv_blocks;
-    if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    if (blocks == 0) blocks = nbatch <= cus * 2 ? nbatch : cus * 2;  // sweeps: two workgroups per compute unit
     if (blocks > nbatch) blocks = nbatch;
     auto launch = [&](auto kernel) {
         kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(packed), static_cast<const uint4*>(codebook), N, K,
@@ -220,16 +244,11 @@ int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, con
 {
     if (static_cast<long long>(N) * K / 8 * 3 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w3a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(N) * K / 8 * 3);
-    const int G = N / 4, nblk = (K / 32 + 63) / 64;
-    // wavefronts per row group: the "gemv_lanes" option (64, 128, 256) or, automatically, two when
-    // there are fewer than two row groups per SIMD and each wavefront still keeps a few blocks to
-    // pipeline (sweeps: 4096 x 11008 gains 15 %, 4096 x 4096 with its two blocks loses 10 %);
-    // never more than the row group has blocks
-    int ws = options().gemv_lanes >= 64 ? options().gemv_lanes / 64 : 0;
-    if (ws == 0) {
-        const int simds = 4 * num_compute_units();
-        ws = (G < 2 * simds && nblk >= 4) ? 2 : 1;
-    }
+    const int nblk = (K / 32 + 63) / 64;
+    // wavefronts per row group: one, unless the "gemv_lanes" option (64, 128, 256) asks for 1, 2 or 4
+    // (sweeps at LLaMA-2-7B sizes: with the two-steps-ahead pipeline a second wavefront per row group
+    // never pays for its exchange through LDS); never more than the row group has blocks
+    int ws = options().gemv_lanes >= 64 ? options().gemv_lanes / 64 : 1;
     while (ws > 1 && ws > nblk) ws /= 2;
     switch (ws) {
         case 1: return launch_w3_ws<1>(packed, codebook, N, K, xq, scale, out, out_dt, P, st);
