@@ -615,7 +615,12 @@ def test_kronecker_rotation_within_tie_band(M, n, m, ratio, dtype):
 
 @pytest.mark.parametrize("kind,M,n,m", [("none", 2, 2080, 1), ("wht", 1, 64, 1), ("wht", 2, 4096, 1), ("wht", 1, 16384, 1),
                                         ("kron", 1, 64, 172), ("kron", 2, 512, 28), ("kron", 1, 128, 12),
-                                        ("kron", 1, 1024, 8), ("kron", 1, 8, 12), ("kron", 1, 64, 7)])
+                                        ("kron", 1, 1024, 8), ("kron", 1, 8, 12), ("kron", 1, 64, 7),
+                                        # 64 Hadamard rows, the form with one workgroup per output column: smallest and
+                                        # largest Q, uneven shares of the four wavefronts, several tokens; 12 columns and 32 rows
+                                        # fall outside it
+                                        ("kron", 3, 64, 16), ("kron", 2, 64, 20), ("kron", 1, 64, 256), ("kron", 1, 64, 12),
+                                        ("kron", 16, 64, 172), ("kron", 1, 32, 256)])
 def test_rotation_only_entry_point(kind, M, n, m):
     _say(f"rotate-only {kind} M={M} n={n} m={m}")
     K = n * m
