@@ -144,6 +144,7 @@ int rcp_version(void);
  *   "gemv_blocks"  number of workgroups the GEMV launches
  *   "gemv_variant" 1 = plain-ALU kernel for every M, 2 = matrix-core kernel for every M
  *   "gemm_waves"   wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
+ *   "gemm_rows"    output rows per workgroup of the matrix-core kernel: 16, 64
  *   "gemv_waves"   wavefronts per workgroup of the fused one-token GEMV (rcp_quant_w2a4_gemv): 4, 8
  *                  (8 needs K >= 2048 and "gemv_lanes" left automatic; otherwise 4 is used)
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */

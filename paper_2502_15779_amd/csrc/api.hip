@@ -28,7 +28,7 @@ int check_launch(const char* what)
 
 Options& options()
 {
-    static Options o = {0, 0, 0, 0, 0, 0};
+    static Options o = {0, 0, 0, 0, 0, 0, 0};
     return o;
 }
 
@@ -142,6 +142,10 @@ int rcp_set_option(const char* name, int value)
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_waves must be 0, 1, 2, 4 or 8");
         o.gemm_waves = value;
+    } else if (strcmp(name, "gemm_rows") == 0) {
+        if (value != 0 && value != 16 && value != 64)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_rows must be 0, 16 or 64");
+        o.gemm_rows = value;
     } else if (strcmp(name, "gemv_waves") == 0) {
         if (value != 0 && value != 4 && value != 8)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_waves must be 0, 4 or 8");

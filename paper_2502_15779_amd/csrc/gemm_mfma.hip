@@ -40,7 +40,12 @@ struct MmStage {
 };
 
 // PACKED: M <= 8, lo and hi of token n in columns n and n + 8 of one B operand.
-template <bool OUT_F16, bool PACKED>
+// NARROW: the workgroup owns 4 row groups (16 output rows) instead of 16: the 16 rows of the A
+// operand are then (row group, row in the nibble) pairs, lane l supplying row group (l%16)/4 masked
+// down to row l%4, so one instruction per plane covers all four rows.  Four lanes load the same
+// weights and the activations are recoded once per 16 instead of once per 64 rows, but a matrix
+// of 4096 rows becomes 256 workgroups instead of 64.
+template <bool OUT_F16, bool PACKED, bool NARROW>
 __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* __restrict__ packed,
                                                                    const uint2* __restrict__ codebook, int N, int K,
                                                                    const uint4* __restrict__ xq,
@@ -55,7 +60,11 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     const int i = lane & 15, kb = lane >> 4;
     const int U = K / 16, G = N / 4;
     const int KS = (K + 127) >> 7;  // steps of 128 columns
-    const int rg = blockIdx.x * 16 + i;
+    constexpr int RB = NARROW ? 16 : 64;  // output rows of the workgroup
+    const int rg = NARROW ? static_cast<int>(blockIdx.x) * 4 + (i >> 2) : static_cast<int>(blockIdx.x) * 16 + i;
+    // NARROW: this lane's row of the nibble as a mask (the fourth row is the FP4 sign bit: shifted down first)
+    const uint32_t row_mask = (i & 3) == 0 ? 0x11111111u : (i & 3) == 1 ? 0x22222222u : 0x44444444u;
+    const int row_shift = (i & 3) == 3 ? 1 : 0;
 
     for (int j = tid; j < MM_SUMS; j += blockDim.x) red[j] = 0;
 
@@ -87,7 +96,7 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     // what the epilogue needs from memory is fetched now and parked in LDS after the loop
     uint2 lut_pre = make_uint2(0u, 0u);
     uint32_t scale_pre = 0;
-    if (tid < 64) lut_pre = codebook[min(static_cast<int>(blockIdx.x) * 64 + tid, N - 1)];
+    if (tid < RB) lut_pre = codebook[min(static_cast<int>(blockIdx.x) * RB + tid, N - 1)];
     if (tid < M) scale_pre = scale[tid];
     __syncthreads();  // LDS is zero before anyone adds to it
 
@@ -117,6 +126,27 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
         }
         const uint32_t p0[4] = {cur.wa.x, cur.wa.z, cur.wb.x, cur.wb.z};
         const uint32_t p1[4] = {cur.wa.y, cur.wa.w, cur.wb.y, cur.wb.w};
+        if constexpr (NARROW) {
+            v8i an[3];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) an[p] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                an[0][d] = static_cast<int>((p0[d] >> row_shift) & row_mask);
+                an[1][d] = static_cast<int>((p1[d] >> row_shift) & row_mask);
+                an[2][d] = an[0][d] & an[1][d];
+            }
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                if constexpr (PACKED) {
+                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[0], acc[p][0], 4, 4, 0, 0, 0, 0);
+                } else {
+                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[0], acc[p][0], 4, 4, 0, 0x7f, 0, 0x7f);
+                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[1], acc[p][0], 4, 4, 0, 0x7f, 0, 0x81);
+                }
+            }
+            return;
+        }
         // plane by plane, so that only two sets of masks are alive at a time
         v8i a[3][4];
 #pragma unroll
@@ -178,7 +208,19 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     // acc[p][r][v] = 2^(r - 1) (r < 3) or 2 (r = 3) times F_p (packed: its lo or hi part) of row
     // 4*(16*block + 4*kb + v) + r and this lane's token: rescale, add over the wavefronts (and,
     // when packed, lo + 4 hi over the two columns of a token).
-    {
+    if constexpr (NARROW) {
+        // acc[p][0][v]: row v of row group kb of the block, scaled by this row's mask value
+        int* dst = red + token * MM_STRIDE + 4 * kb;
+#pragma unroll
+        for (int p = 0; p < 3; ++p)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float unmask = v == 0 ? 2.0f : v == 1 ? 1.0f : 0.5f;
+                int f = static_cast<int>(acc[p][0][v] * unmask);
+                if (hi_lane) f *= 4;
+                atomicAdd(dst + p * MM_PLANE + v, f);
+            }
+    } else {
         int* dst = red + token * MM_STRIDE + 16 * kb;
 #pragma unroll
         for (int p = 0; p < 3; ++p)
@@ -192,8 +234,10 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
                     atomicAdd(dst + p * MM_PLANE + 4 * v + r, f);
                 }
             }
+    }
+    {
         if (!hi_lane) atomicAdd(red + 3 * MM_PLANE + token, tsum);
-        if (tid < 64) {
+        if (tid < RB) {
             red[MM_SUMS + 2 * tid] = static_cast<int>(lut_pre.x);
             red[MM_SUMS + 2 * tid + 1] = static_cast<int>(lut_pre.y);
         }
@@ -201,9 +245,9 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     }
     __syncthreads();
 
-    for (int o = tid; o < M * 64; o += blockDim.x) {
-        const int n = o >> 6, hh = o & 63;
-        const int h = blockIdx.x * 64 + hh;
+    for (int o = tid; o < M * RB; o += blockDim.x) {
+        const int n = o / RB, hh = o % RB;
+        const int h = blockIdx.x * RB + hh;
         if (h >= N) continue;
         const int F0 = red[n * MM_STRIDE + hh], F1 = red[MM_PLANE + n * MM_STRIDE + hh];
         const int F3 = red[2 * MM_PLANE + n * MM_STRIDE + hh];
@@ -229,8 +273,11 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
 int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
                      int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
 {
-    const int blocks = (N + 63) / 64;
     const int KS = (K + 127) / 128;
+    // 16-row workgroups when 64-row ones would leave most compute units idle ("gemm_rows" = 16 / 64 forces a form)
+    bool narrow = (N + 63) / 64 < num_compute_units() / 2;
+    if (options().gemm_rows != 0) narrow = options().gemm_rows == 16;
+    const int blocks = narrow ? (N + 15) / 16 : (N + 63) / 64;
     // 8 wavefronts per workgroup share the K steps of a row block (sweeps: 8 with one step per
     // pipeline stage beats 4 with deeper stages on every LLaMA shape), never more than there are steps
     int waves = 8;
@@ -241,13 +288,16 @@ int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, con
     auto* x4 = static_cast<const uint4*>(xq);
     auto* sc = static_cast<const uint16_t*>(scale);
     const dim3 grid(blocks), block(waves * 64);
-    if (M <= 8) {
-        if (out_dt == RCP_F16) gemm_mfma_kernel<true, true><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
-        else gemm_mfma_kernel<false, true><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+#define RCP_MM(F16, PK, NA) gemm_mfma_kernel<F16, PK, NA><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P)
+    const bool f16 = out_dt == RCP_F16, pkd = M <= 8;
+    if (narrow) {
+        if (pkd) { if (f16) RCP_MM(true, true, true); else RCP_MM(false, true, true); }
+        else     { if (f16) RCP_MM(true, false, true); else RCP_MM(false, false, true); }
     } else {
-        if (out_dt == RCP_F16) gemm_mfma_kernel<true, false><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
-        else gemm_mfma_kernel<false, false><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+        if (pkd) { if (f16) RCP_MM(true, true, false); else RCP_MM(false, true, false); }
+        else     { if (f16) RCP_MM(true, false, false); else RCP_MM(false, false, false); }
     }
+#undef RCP_MM
     return check_launch("rcp_w2a4_gemv");
 }
 

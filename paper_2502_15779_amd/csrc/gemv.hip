@@ -486,7 +486,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
     if (nsteps & 1) step(wA);
 }
 
-constexpr int GEMM_MFMA_MIN_M = 4;  // fewer tokens always stay on the plain-ALU kernel
+constexpr int GEMM_MFMA_MIN_M = 2;  // one token always stays on the plain-ALU kernel
 
 struct GemvPlan {
     int lw, ws, unr, blocks;
@@ -614,8 +614,9 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(a.N) * a.K / 4);
     // several tokens: the contraction goes to the matrix cores (the fused quantiser is one token only)
     const int variant = options().gemv_variant;
-    // (measured crossover on LLaMA-sized layers: 5 tokens, or 4 when the matrix is tall enough to
-    // fill the chip with 64-row blocks)
+    // (measured crossover on LLaMA-sized layers: 3 tokens, or 2 when the matrix is tall enough to
+    // fill the chip with 64-row blocks; below that many rows the matrix-core kernel runs with 16-row
+    // blocks and is level with the plain-ALU kernel at 2 tokens)
     const bool many = a.M > GEMM_MFMA_MIN_M || (a.M == GEMM_MFMA_MIN_M && a.N >= 8192);
     if (a.xraw == nullptr && variant != 1 && (variant == 2 || many))
         return launch_gemm_mfma(a.packed, a.codebook, a.N, a.K, a.xq, a.scale, a.M, a.out, a.out_dt, a.P, st);

@@ -23,6 +23,7 @@ struct Options {
     int gemv_variant;    // 0 automatic, 1 plain-ALU kernel for every M, 2 matrix-core kernel for every M
     int gemm_waves;      // wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
     int gemv_waves;      // wavefronts per workgroup of the fused one-token GEMV: 4 or 8
+    int gemm_rows;       // output rows per workgroup of the matrix-core kernel: 16 or 64
 };
 Options& options();
 int num_compute_units();

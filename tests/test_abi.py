@@ -115,6 +115,8 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.rcp_set_option(b"gemm_waves", 3) == -4
     assert lib.rcp_set_option(b"gemm_waves", 8) == 0 and lib.rcp_set_option(b"gemm_waves", 0) == 0
     assert lib.rcp_set_option(b"gemv_variant", 3) == -4
+    assert lib.rcp_set_option(b"gemm_rows", 32) == -4
+    assert lib.rcp_set_option(b"gemm_rows", 16) == 0 and lib.rcp_set_option(b"gemm_rows", 0) == 0
     assert lib.rcp_set_option(b"gemv_waves", 2) == -4
     assert lib.rcp_set_option(b"gemv_waves", 8) == 0 and lib.rcp_set_option(b"gemv_waves", 0) == 0
     gmm = lib.rcp_w2a4_gemm_grouped

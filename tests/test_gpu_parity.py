@@ -31,7 +31,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves", "gemm_rows"):
         rcp.set_option(k, 0)
 
 
@@ -429,21 +429,27 @@ def test_small_batch_matches_oracle(N, K, M, variant):
     _check_gemv(packed, cb, N, K, xq, sc, M, torch.float16)
 
 
+@pytest.mark.parametrize("rows", [16, 64])
 @pytest.mark.parametrize("waves", [1, 2, 4, 8])
-@pytest.mark.parametrize("N,K,M", [(4, 32, 1), (68, 96, 5), (1028, 4096, 16), (132, 14336, 9), (64, 32768, 16), (200, 160, 2)])
-def test_matrix_core_kernel_shapes_and_workgroup_sizes(N, K, M, waves):
-    """Ragged N (not a multiple of 64), K not a multiple of 128, fewer K steps than wavefronts, M = 1."""
-    _say(f"mfma gemm N={N} K={K} M={M} waves={waves}")
+@pytest.mark.parametrize("N,K,M", [(4, 32, 1), (68, 96, 5), (1028, 4096, 16), (132, 14336, 9), (64, 32768, 16), (200, 160, 2),
+                                   (24, 4224, 8)])
+def test_matrix_core_kernel_shapes_and_workgroup_sizes(N, K, M, waves, rows):
+    """Ragged N (not a multiple of 64 or 16), K not a multiple of 128, fewer K steps than wavefronts, M = 1;
+    64-row and 16-row workgroups."""
+    _say(f"mfma gemm N={N} K={K} M={M} waves={waves} rows={rows}")
     rcp.set_option("gemv_variant", 2)
     rcp.set_option("gemm_waves", waves)
+    rcp.set_option("gemm_rows", rows)
     packed, cb, xq, sc = _gemv_case(77 + M, N, K, M)
     _check_gemv(packed, cb, N, K, xq, sc, M, torch.float32)
 
 
-def test_matrix_core_kernel_extreme_activations():
+@pytest.mark.parametrize("rows", [16, 64])
+def test_matrix_core_kernel_extreme_activations(rows):
     """q = -8 everywhere and q = 7 everywhere: the largest sums the fp32 accumulators must hold exactly."""
     N, K, M = 64, 32768, 16
     rcp.set_option("gemv_variant", 2)
+    rcp.set_option("gemm_rows", rows)
     idx = rcp_synth.random_indices(31, "mfma_ext", N, K)
     packed = oracle.pack_indices(idx)
     xq = np.empty((M, K // 2), np.uint8)
