@@ -588,7 +588,9 @@ static GemvPlan plan_gemv(int N, int K, int M, bool fused)
         // Several tokens multiply the per-row-group reduction and epilogue: tall matrices then
         // do better with fewer lanes per row group, which pay them once for 2 or 4 row groups
         // (sweeps on 12288 x 4096 and 22016 x 4096 at M = 4, 8, 16).
-        if (M >= 4 && G >= 16 * cus) lanes = 32;
+        // (from 16 row groups per compute unit on the same holds for one token: 22016 x 4096 fused
+        // 7.2 -> 6.75 us, while 12288 x 4096 with 12 per unit is better off with whole wavefronts)
+        if (G >= 16 * cus) lanes = 32;
         else if (M > 8 && G >= 8 * cus) lanes = 16;
         while (lanes > 16 && U < lanes) lanes /= 2;  // never more lanes than a row group has units
     }
