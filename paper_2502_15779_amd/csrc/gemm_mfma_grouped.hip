@@ -40,7 +40,10 @@ struct MgStage {
     u32x4 lut;     // lanes 0..31: 16 bytes of the levels of (row group lane/2, this group)
 };
 
-template <bool OUT_F16>
+// NARROW: the workgroup owns 4 row groups (16 output rows): the 16 rows of the A operand are (row group,
+// row in the nibble) pairs as in gemm_mfma.hip, the mask and its E8M0 scale are per-lane values, and
+// one instruction per plane and activation part covers all four rows of a nibble.
+template <bool OUT_F16, bool NARROW>
 __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uint4* __restrict__ packed,
                                                                        const uint4* __restrict__ codebook, int N, int K,
                                                                        const uint4* __restrict__ xq,
@@ -55,7 +58,14 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     const int W = static_cast<int>(blockDim.x) >> 6;
     const int i = lane & 15, kb = lane >> 4;
     const int U = K / 16, G = N / 4, NG = K / RCP_GROUP;
-    const int rg = blockIdx.x * 16 + i;
+    constexpr int RB = NARROW ? 16 : 64;   // output rows of the workgroup
+    constexpr int RGB = RB / 4;            // its row groups
+    const int rg = NARROW ? static_cast<int>(blockIdx.x) * 4 + (i >> 2) : static_cast<int>(blockIdx.x) * 16 + i;
+    // NARROW: this lane's row of the nibble as a mask, the shift that brings the fourth row (the FP4 sign
+    // bit) down, and the scale that undoes the mask's 0.5 / 1 / 2
+    const uint32_t row_mask = (i & 3) == 0 ? 0x11111111u : (i & 3) == 1 ? 0x22222222u : 0x44444444u;
+    const int row_shift = (i & 3) == 3 ? 1 : 0;
+    const int row_scale = (i & 3) == 0 ? 0x80 : (i & 3) == 1 ? 0x7f : 0x7e;
 
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
@@ -67,8 +77,8 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     const unsigned row_base = rg < G ? static_cast<unsigned>(rg) * U * 16u : 0x80000000u;
     const unsigned xbase = static_cast<unsigned>(i) * (K / 2) + kb * 16u;
     // the piece of the levels this lane fetches: row group lane/2 of the block, half lane&1
-    const int lut_rg = blockIdx.x * 16 + (lane >> 1);
-    const unsigned lut_base = (lane < 32 && lut_rg < G) ? static_cast<unsigned>(lut_rg) * NG * 32u + (lane & 1) * 16u : 0x80000000u;
+    const int lut_rg = blockIdx.x * RGB + (lane >> 1);
+    const unsigned lut_base = (lane < 2 * RGB && lut_rg < G) ? static_cast<unsigned>(lut_rg) * NG * 32u + (lane & 1) * 16u : 0x80000000u;
 
     auto load = [&](int group_index, MgStage& st) {
         const int g = __builtin_amdgcn_readfirstlane(group_index);  // uniform: scalar offsets
@@ -88,7 +98,8 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     int g = wave;  // this wavefront's current group
     load(g, sA);
 
-    float o[4][4];  // [v][r]: output of row 4*(4*kb + v) + r of the block for token i
+    // [v][r]: output of row 4*(4*kb + v) + r of the block for token i; NARROW: [v][0], row 4*kb + v
+    float o[4][4];
 #pragma unroll
     for (int v = 0; v < 4; ++v)
 #pragma unroll
@@ -100,7 +111,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     constexpr int SC_ONE = 0x7f, SC_HI = 0x81;
 
     auto compute = [&](const MgStage& cur, int gcur) {
-        if (lane < 32) {
+        if (lane < 2 * RGB) {
             // two rows: 4 * (lane / 2) + 2 * (lane & 1) and the next one
             const uint32_t lw[4] = {cur.lut.x, cur.lut.y, cur.lut.z, cur.lut.w};
 #pragma unroll
@@ -128,6 +139,42 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
         const uint32_t p0[4] = {cur.wa.x, cur.wa.z, cur.wb.x, cur.wb.z};
         const uint32_t p1[4] = {cur.wa.y, cur.wa.w, cur.wb.y, cur.wb.w};
         v4f acc[3][4];
+        if constexpr (NARROW) {
+            v8i an[3];
+#pragma unroll
+            for (int p = 0; p < 3; ++p) an[p] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                an[0][d] = static_cast<int>((p0[d] >> row_shift) & row_mask);
+                an[1][d] = static_cast<int>((p1[d] >> row_shift) & row_mask);
+                an[2][d] = an[0][d] & an[1][d];
+            }
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], blo, zero, 4, 4, 0, row_scale, 0, SC_ONE);
+                acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bhi, acc[p][0], 4, 4, 0, row_scale, 0, SC_HI);
+            }
+            const bool store_pn = Pout != nullptr && i < M && gcur < NG;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float4 c = coef_lds[wave][4 * kb + v];
+                const float F0 = acc[0][0][v], F1 = acc[1][0][v], F3 = acc[2][0][v];
+                float val = o[v][0];
+                val = fmaf(c.x, tq[v], val);
+                val = fmaf(c.y, F0, val);
+                val = fmaf(c.z, F1, val);
+                val = fmaf(c.w, F3, val);
+                o[v][0] = val;
+                if (store_pn) {
+                    const int h = 4 * (static_cast<int>(blockIdx.x) * 4 + kb) + v;
+                    if (h < N)
+                        reinterpret_cast<int4*>(Pout)[(static_cast<size_t>(i) * N + h) * NG + gcur] =
+                            make_int4(static_cast<int>(tq[v] - F0 - F1 + F3), static_cast<int>(F0 - F3),
+                                      static_cast<int>(F1 - F3), static_cast<int>(F3));
+                }
+            }
+            return;
+        }
         v8i a[3][4];
 #pragma unroll
         for (int p = 0; p < 3; ++p) {
@@ -198,7 +245,11 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     const uint32_t keep = sA.wa.x | sA.wb.x | sA.xq.x | sA.lut.x | sB.wa.x | sB.wb.x | sB.xq.x | sB.lut.x;
     if (__builtin_expect(K < 0, 0)) slab[0] = __uint_as_float(keep);  // never true
 
-    {
+    if constexpr (NARROW) {
+        float* dst = slab + (wave * 16 + i) * MG_STRIDE + 4 * kb;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dst[v] = o[v][0];
+    } else {
         float* dst = slab + (wave * 16 + i) * MG_STRIDE + 16 * kb;
 #pragma unroll
         for (int v = 0; v < 4; ++v)
@@ -207,9 +258,9 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     }
     __syncthreads();
 
-    for (int idx = tid; idx < M * 64; idx += blockDim.x) {
-        const int n = idx >> 6, hh = idx & 63;
-        const int h = blockIdx.x * 64 + hh;
+    for (int idx = tid; idx < M * RB; idx += blockDim.x) {
+        const int n = idx / RB, hh = idx % RB;
+        const int h = blockIdx.x * RB + hh;
         if (h >= N) continue;
         float val = 0.0f;
         for (int w = 0; w < W; ++w) val += slab[(w * 16 + n) * MG_STRIDE + hh];  // fixed order
@@ -226,7 +277,10 @@ int launch_gemm_mfma_grouped(const void* packed, const void* codebook, int N, in
     if (static_cast<long long>(N) * K / 4 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemm_grouped: packed matrix of %lld bytes exceeds 2 GiB",
                     static_cast<long long>(N) * K / 4);
-    const int blocks = (N + 63) / 64;
+    // 16-row workgroups when 64-row ones would leave most compute units idle ("gemm_rows" = 16 / 64 forces a form)
+    bool narrow = (N + 63) / 64 < num_compute_units() / 2;
+    if (options().gemm_rows != 0) narrow = options().gemm_rows == 16;
+    const int blocks = narrow ? (N + 15) / 16 : (N + 63) / 64;
     const int NG = K / RCP_GROUP;
     int waves = MG_WAVES;
     if (options().gemm_waves != 0) waves = options().gemm_waves;
@@ -235,10 +289,17 @@ int launch_gemm_mfma_grouped(const void* packed, const void* codebook, int N, in
     auto* cb = static_cast<const uint4*>(codebook);
     auto* x4 = static_cast<const uint4*>(xq);
     auto* sc = static_cast<const uint16_t*>(scale);
-    if (out_dt == RCP_F16)
-        gemm_mfma_grouped_kernel<true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
-    else
-        gemm_mfma_grouped_kernel<false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+    if (narrow) {
+        if (out_dt == RCP_F16)
+            gemm_mfma_grouped_kernel<true, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+        else
+            gemm_mfma_grouped_kernel<false, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+    } else {
+        if (out_dt == RCP_F16)
+            gemm_mfma_grouped_kernel<true, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+        else
+            gemm_mfma_grouped_kernel<false, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+    }
     return check_launch("rcp_w2a4_gemm_grouped");
 }
 

@@ -195,13 +195,16 @@ def test_grouped_gemv_partial_sums_bit_exact_and_output_close(N, K, blocks):
     _check_grouped_gemv(packed, cb, N, K, xq, sc, torch.float32 if blocks else torch.float16)
 
 
+@pytest.mark.parametrize("rows", [16, 64])
 @pytest.mark.parametrize("waves", [0, 2])
 @pytest.mark.parametrize("M", [1, 2, 5, 8, 16])
 @pytest.mark.parametrize("N,K", [(4, 128), (68, 256), (1028, 4096), (72, 11008), (40, 14336), (12, 32768)])
-def test_grouped_gemm_several_tokens(N, K, M, waves):
-    """Group-wise LUTs with M tokens (matrix-core kernel; M = 1 takes the GEMV unless forced)."""
-    _say(f"grouped gemm N={N} K={K} M={M} waves={waves}")
+def test_grouped_gemm_several_tokens(N, K, M, waves, rows):
+    """Group-wise LUTs with M tokens (matrix-core kernel with 64-row and 16-row workgroups; M = 1 takes the
+    GEMV unless forced)."""
+    _say(f"grouped gemm N={N} K={K} M={M} waves={waves} rows={rows}")
     rcp.set_option("gemm_waves", waves)
+    rcp.set_option("gemm_rows", rows)
     if waves:
         rcp.set_option("gemv_variant", 2)   # the matrix-core kernel also for one token
     NG = K // 128
@@ -231,9 +234,11 @@ def test_grouped_gemm_several_tokens(N, K, M, waves):
         assert torch.equal(out, out2)
 
 
-def test_grouped_gemm_extreme_activations():
+@pytest.mark.parametrize("rows", [16, 64])
+def test_grouped_gemm_extreme_activations(rows):
     """q = -8 / +7 everywhere with integer levels: exact integer outputs for all 16 tokens."""
     N, K, M = 64, 14336, 16
+    rcp.set_option("gemm_rows", rows)
     NG = K // 128
     idx = rcp_synth.random_indices(73, "ggext", N, K)
     packed = oracle.pack_indices_grouped(idx)
