@@ -126,7 +126,7 @@ __device__ __forceinline__ void heads_columns(float* sy, int m, float norm)
     }
 }
 
-// The first 64 bytes of arguments reach the wavefront in scalar registers at launch; everything the
+// The first 56 bytes of arguments reach the wavefront in scalar registers at launch; everything the
 // prologue needs at once (matrix, shape, activations) is among them.
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT, int NW>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__ packed,

@@ -46,13 +46,15 @@ __host__ __device__ constexpr size_t gemv_grouped_lds_bytes(int K)
 // workgroup also writes x_q and S to xq_out / scale_out when those are given.
 constexpr int GG_XU = 4;  // 16-value units of raw activations per thread: K <= 16384
 
+// (The first 56 bytes of arguments reach the wavefront in scalar registers at launch: everything the
+// prologue needs at once is among them.)
 template <bool OUT_F16, int XDT>
 __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* __restrict__ packed,
                                                                   const uint4* __restrict__ codebook, int N, int K,
+                                                                  const void* __restrict__ xraw,
                                                                   const uint4* __restrict__ xq,
-                                                                  const uint16_t* __restrict__ scale,
+                                                                  const uint16_t* __restrict__ scale, float clip_ratio,
                                                                   void* __restrict__ out, int32_t* __restrict__ Pout,
-                                                                  const void* __restrict__ xraw, float clip_ratio,
                                                                   uint32_t* __restrict__ xq_out,
                                                                   uint16_t* __restrict__ scale_out)
 {
@@ -321,8 +323,8 @@ template <bool OUT_F16, int XDT>
 static int launch_grouped_one(const GroupedArgs& a, int blocks, size_t lds, hipStream_t st)
 {
     gemv_grouped_kernel<OUT_F16, XDT><<<blocks, GG_THREADS, lds, st>>>(
-        static_cast<const uint4*>(a.packed), static_cast<const uint4*>(a.codebook), a.N, a.K,
-        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.out, a.P, a.xraw, a.clip_ratio,
+        static_cast<const uint4*>(a.packed), static_cast<const uint4*>(a.codebook), a.N, a.K, a.xraw,
+        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.clip_ratio, a.out, a.P,
         static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
     return check_launch("rcp_w2a4_gemv_grouped");
 }
