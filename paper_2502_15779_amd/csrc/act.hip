@@ -333,87 +333,119 @@ __global__ __launch_bounds__(KRON_THREADS) void kron_wave_kernel(const void* __r
     }
 }
 
-// Form for n = 64 that spreads the work over the whole chip: one workgroup per column j' of Y (and
-// token), its four wavefronts split the sum over j.  Lane i owns row i: it reads its own stretch of
-// X[i][.] straight from memory (the whole token is 2m*64 bytes and stays in cache; no staging in
+// Form that spreads the work over the whole chip (n = 64 * RPL): one workgroup per column j' of Y (and
+// token), its four wavefronts split the sum over j.  Lane l owns rows l*RPL .. l*RPL + RPL-1: it reads
+// its own stretches of X[i][.] straight from memory (the whole token stays in cache; no staging in
 // LDS, no barrier before the arithmetic), the row of Q comes through scalar loads.  The four partial
-// sums meet in LDS in a fixed order, then the first wavefront runs the order-64 Hadamard transform
-// across its lanes (lane-swap and DPP exchanges) and stores the column.
-constexpr int KRON_SPLIT_MAXQ = 16;  // groups of four columns per wavefront: m <= 256
+// sums meet in LDS in a fixed order, then the first wavefront runs the order-n Hadamard transform in
+// registers (strides below RPL) and across its lanes (lane-swap and DPP exchanges) and stores the column.
+constexpr int KRON_SPLIT_MAXQ = 16;  // (rows per lane) x (groups of four columns per wavefront) kept in registers
 
-template <int DT>
+template <int DT, int RPL>
 __global__ __launch_bounds__(KRON_THREADS) void kron_split_kernel(const void* __restrict__ x, int m,
                                                                   const float* __restrict__ Q, float norm,
                                                                   float* __restrict__ y)
 {
-    __shared__ float part[4][64];
+    __shared__ float part[4][64 * RPL];
+    constexpr int QW = KRON_SPLIT_MAXQ / RPL;  // groups of four columns a wavefront can take
     using XT = typename XStore<DT>::type;
     const int token = blockIdx.y, jcol = blockIdx.x;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int K = 64 * m, quads = m / 4;
+    const int K = 64 * RPL * m, quads = m / 4;
     const int q0 = wave * quads / 4, q1 = (wave + 1) * quads / 4;  // this wavefront's groups of four columns
-    const XT* xr = static_cast<const XT*>(x) + static_cast<size_t>(token) * K + static_cast<size_t>(lane) * m;
+    const XT* xr = static_cast<const XT*>(x) + static_cast<size_t>(token) * K + static_cast<size_t>(lane) * RPL * m;
     const float* qrow = Q + static_cast<size_t>(jcol) * m;
 
     // all loads first, then the arithmetic
-    float4 raw[KRON_SPLIT_MAXQ];
+    float4 raw[RPL][QW];
 #pragma unroll
-    for (int t = 0; t < KRON_SPLIT_MAXQ; ++t) {
-        raw[t] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (q0 + t < q1) {  // uniform
-            if constexpr (sizeof(XT) == 4) {
-                raw[t] = reinterpret_cast<const float4*>(xr)[q0 + t];
-            } else {
-                const uint2 r = reinterpret_cast<const uint2*>(xr)[q0 + t];
-                raw[t].x = __uint_as_float(r.x);
-                raw[t].y = __uint_as_float(r.y);
+    for (int t = 0; t < QW; ++t) {
+#pragma unroll
+        for (int e = 0; e < RPL; ++e) {
+            raw[e][t] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (q0 + t < q1) {  // uniform
+                if constexpr (sizeof(XT) == 4) {
+                    raw[e][t] = reinterpret_cast<const float4*>(xr + static_cast<size_t>(e) * m)[q0 + t];
+                } else {
+                    const uint2 r = reinterpret_cast<const uint2*>(xr + static_cast<size_t>(e) * m)[q0 + t];
+                    raw[e][t].x = __uint_as_float(r.x);
+                    raw[e][t].y = __uint_as_float(r.y);
+                }
             }
         }
     }
-    float acc = 0.0f;
+    float acc[RPL];
 #pragma unroll
-    for (int t = 0; t < KRON_SPLIT_MAXQ; ++t) {
+    for (int e = 0; e < RPL; ++e) acc[e] = 0.0f;
+#pragma unroll
+    for (int t = 0; t < QW; ++t) {
         if (q0 + t < q1) {
             const float4 q4 = reinterpret_cast<const float4*>(qrow)[q0 + t];  // uniform address: scalar load
-            float x0, x1, x2, x3;
-            if constexpr (sizeof(XT) == 4) {
-                x0 = raw[t].x; x1 = raw[t].y; x2 = raw[t].z; x3 = raw[t].w;
-            } else {
-                const uint32_t a = __float_as_uint(raw[t].x), b = __float_as_uint(raw[t].y);
-                x0 = XStore<DT>::widen(static_cast<uint16_t>(a & 0xffffu));
-                x1 = XStore<DT>::widen(static_cast<uint16_t>(a >> 16));
-                x2 = XStore<DT>::widen(static_cast<uint16_t>(b & 0xffffu));
-                x3 = XStore<DT>::widen(static_cast<uint16_t>(b >> 16));
+#pragma unroll
+            for (int e = 0; e < RPL; ++e) {
+                float x0, x1, x2, x3;
+                if constexpr (sizeof(XT) == 4) {
+                    x0 = raw[e][t].x; x1 = raw[e][t].y; x2 = raw[e][t].z; x3 = raw[e][t].w;
+                } else {
+                    const uint32_t a = __float_as_uint(raw[e][t].x), b = __float_as_uint(raw[e][t].y);
+                    x0 = XStore<DT>::widen(static_cast<uint16_t>(a & 0xffffu));
+                    x1 = XStore<DT>::widen(static_cast<uint16_t>(a >> 16));
+                    x2 = XStore<DT>::widen(static_cast<uint16_t>(b & 0xffffu));
+                    x3 = XStore<DT>::widen(static_cast<uint16_t>(b >> 16));
+                }
+                acc[e] = fmaf(x0, q4.x, acc[e]);
+                acc[e] = fmaf(x1, q4.y, acc[e]);
+                acc[e] = fmaf(x2, q4.z, acc[e]);
+                acc[e] = fmaf(x3, q4.w, acc[e]);
             }
-            acc = fmaf(x0, q4.x, acc);
-            acc = fmaf(x1, q4.y, acc);
-            acc = fmaf(x2, q4.z, acc);
-            acc = fmaf(x3, q4.w, acc);
         }
     }
-    part[wave][lane] = acc;
+#pragma unroll
+    for (int e = 0; e < RPL; ++e) part[wave][e * 64 + lane] = acc[e];
     __syncthreads();
     if (wave != 0) return;
-    float z = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
-    // Hadamard transform over the row index = lane, ascending stride: z <- z + p in the lane with the
-    // stride bit clear, p - z in its partner
-    {
-        const float p1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0xB1, 0xf, 0xf, false));  // lane ^ 1
-        z = (lane & 1) ? p1 - z : z + p1;
-        const float p2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x4E, 0xf, 0xf, false));  // lane ^ 2
-        z = (lane & 2) ? p2 - z : z + p2;
-        const float p4 = __shfl_xor(z, 4, 64);
-        z = (lane & 4) ? p4 - z : z + p4;
-        const float p8 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(z), 0x128, 0xf, 0xf, false));  // row_ror 8 = lane ^ 8
-        z = (lane & 8) ? p8 - z : z + p8;
+    float z[RPL];
+#pragma unroll
+    for (int e = 0; e < RPL; ++e)
+        z[e] = ((part[0][e * 64 + lane] + part[1][e * 64 + lane]) + part[2][e * 64 + lane]) + part[3][e * 64 + lane];
+    // Hadamard transform over the row index i = lane*RPL + e, ascending stride: first inside the lane ...
+#pragma unroll
+    for (int st = 1; st < RPL; st <<= 1)
+#pragma unroll
+        for (int e = 0; e < RPL; ++e)
+            if ((e & st) == 0) {
+                const float a = z[e], b = z[e + st];
+                z[e] = a + b;
+                z[e + st] = a - b;
+            }
+    // ... then across lanes: z <- z + p in the lane with the stride bit clear, p - z in its partner
+#pragma unroll
+    for (int e = 0; e < RPL; ++e) {
+        float v = z[e];
+        const float p1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));  // lane ^ 1
+        v = (lane & 1) ? p1 - v : v + p1;
+        const float p2 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));  // lane ^ 2
+        v = (lane & 2) ? p2 - v : v + p2;
+        const float p4 = __shfl_xor(v, 4, 64);
+        v = (lane & 4) ? p4 - v : v + p4;
+        const float p8 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));  // row_ror 8 = lane ^ 8
+        v = (lane & 8) ? p8 - v : v + p8;
         // the swaps leave (value of the lane with the bit clear, value of the lane with it set) in every lane
-        auto r16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(z), __float_as_uint(z), false, false);
-        z = (lane & 16) ? __uint_as_float(r16[0]) - __uint_as_float(r16[1]) : __uint_as_float(r16[0]) + __uint_as_float(r16[1]);
-        auto r32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(z), __float_as_uint(z), false, false);
-        z = (lane & 32) ? __uint_as_float(r32[0]) - __uint_as_float(r32[1]) : __uint_as_float(r32[0]) + __uint_as_float(r32[1]);
+        auto r16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = (lane & 16) ? __uint_as_float(r16[0]) - __uint_as_float(r16[1]) : __uint_as_float(r16[0]) + __uint_as_float(r16[1]);
+        auto r32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+        v = (lane & 32) ? __uint_as_float(r32[0]) - __uint_as_float(r32[1]) : __uint_as_float(r32[0]) + __uint_as_float(r32[1]);
+        y[static_cast<size_t>(token) * K + static_cast<size_t>(lane * RPL + e) * m + jcol] = v * norm;
     }
-    y[static_cast<size_t>(token) * K + static_cast<size_t>(lane) * m + jcol] = z * norm;
+}
+
+template <int DT, int RPL>
+static int launch_kron_split(const void* x, int M, const rcp_rotation* rot, float* y, float norm, hipStream_t st)
+{
+    dim3 grid(rot->m, M);
+    kron_split_kernel<DT, RPL><<<grid, KRON_THREADS, 0, st>>>(x, rot->m, rot->Q, norm, y);
+    return check_launch("rcp_rotate_quant_act(kron)");
 }
 
 // ---------------------------------------------------------------------------------------
@@ -559,10 +591,16 @@ static int launch_kron(const void* x, int M, int K, const rcp_rotation* rot, flo
     const int n = rot->n_wht, m = rot->m;
     const float norm = static_cast<float>(1.0 / sqrt(static_cast<double>(n)));
     const size_t xbytes = static_cast<size_t>(K) * sizeof(typename XStore<DT>::type);
-    if (n == 64 && m % 4 == 0 && m >= 16 && m <= 4 * 4 * KRON_SPLIT_MAXQ) {
-        dim3 grid(m, M);
-        kron_split_kernel<DT><<<grid, KRON_THREADS, 0, st>>>(x, m, rot->Q, norm, y);
-        return check_launch("rcp_rotate_quant_act(kron)");
+    // one workgroup per output column when a wavefront's share of the columns fits in registers:
+    // (n/64) rows per lane x ceil(m/16) groups of four columns <= KRON_SPLIT_MAXQ
+    if (m % 4 == 0 && m >= 8 && n >= 64 && n <= 1024 && (n / 64) * ((m / 4 + 3) / 4) <= KRON_SPLIT_MAXQ) {
+        switch (n / 64) {
+            case 1: return launch_kron_split<DT, 1>(x, M, rot, y, norm, st);
+            case 2: return launch_kron_split<DT, 2>(x, M, rot, y, norm, st);
+            case 4: return launch_kron_split<DT, 4>(x, M, rot, y, norm, st);
+            case 8: return launch_kron_split<DT, 8>(x, M, rot, y, norm, st);
+            default: return launch_kron_split<DT, 16>(x, M, rot, y, norm, st);
+        }
     }
     if (m % 4 == 0 && n >= 64 && n <= 1024 && xbytes + 16 * m <= 160 * 1024) {
         switch (n / 64) {

@@ -611,7 +611,7 @@ def test_hadamard_rotation_bit_exact_against_binary32_butterfly(M, n):
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 @pytest.mark.parametrize("M,n,m,ratio", [(1, 64, 172, 1.0), (1, 512, 28, 1.0), (2, 8, 12, 0.9), (1, 2, 16, 1.0),
-                                         (3, 64, 172, 1.0)])
+                                         (3, 64, 172, 1.0), (1, 128, 172, 1.0), (2, 1024, 16, 0.9)])
 def test_kronecker_rotation_within_tie_band(M, n, m, ratio, dtype):
     _say(f"kron M={M} n={n} m={m} {dtype}")
     K = n * m
@@ -628,10 +628,12 @@ def test_kronecker_rotation_within_tie_band(M, n, m, ratio, dtype):
                                         ("kron", 1, 64, 172), ("kron", 2, 512, 28), ("kron", 1, 128, 12),
                                         ("kron", 1, 1024, 8), ("kron", 1, 8, 12), ("kron", 1, 64, 7),
                                         # 64 Hadamard rows, the form with one workgroup per output column: smallest and
-                                        # largest Q, uneven shares of the four wavefronts, several tokens; 12 columns and 32 rows
+                                        # largest Q, uneven shares of the four wavefronts, several tokens; 32 rows
                                         # fall outside it
                                         ("kron", 3, 64, 16), ("kron", 2, 64, 20), ("kron", 1, 64, 256), ("kron", 1, 64, 12),
-                                        ("kron", 16, 64, 172), ("kron", 1, 32, 256)])
+                                        ("kron", 16, 64, 172), ("kron", 1, 32, 256),
+                                        # too many columns per wavefront for that form: one wavefront per column, token in LDS
+                                        ("kron", 2, 128, 172), ("kron", 1, 512, 36), ("kron", 1, 256, 68)])
 def test_rotation_only_entry_point(kind, M, n, m):
     _say(f"rotate-only {kind} M={M} n={n} m={m}")
     K = n * m
