@@ -115,7 +115,11 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             xg[i] = __builtin_amdgcn_raw_buffer_load_b128(xres, static_cast<int>(threadIdx.x) * 64, i * 16, 0);
-        S = half_bits_to_float(scale[0]);
+        const uint16_t sbits = scale[0];
+        // the activation loads stay in front of the weight loads (memory answers in issue order, and the
+        // staging must not have to wait for weights)
+        __builtin_amdgcn_sched_barrier(0);
+        S = half_bits_to_float(sbits);
         load_step(b, rd, sA);
         load_step(b1, rd1, sB);
         asm volatile("" ::"s"(out), "s"(Pout));  // fetch the late arguments while the loads are in flight

@@ -99,20 +99,29 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
     advance(b1, j1);
     int b2 = b1, j2 = j1;
     advance(b2, j2);
+    // memory answers loads in issue order: this thread's first piece of the activations goes first, so that
+    // staging them does not have to wait for the weights
+    const int xpieces = 64 * nblk;  // pieces of 16 bytes in LDS (zero beyond K)
+    const uint16_t sbits = scale[0];
+    uint4 xfirst = make_uint4(0u, 0u, 0u, 0u);
+    if (static_cast<int>(threadIdx.x) < U) xfirst = xq[threadIdx.x];
+    __builtin_amdgcn_sched_barrier(0);
     W3Planes wA, wB;
     load_block(b * SLOTS + slot, j, wA);
     load_block(b1 * SLOTS + slot, j1, wB);
     const int my_row = (((lane >> 4) & 1) << 1) | (lane >> 5);  // the row this lane holds after the folds
     uint4 lut = codebook[min(4 * (b * SLOTS + slot) + my_row, N - 1)];
-    const float S = half_bits_to_float(scale[0]);
 
     int* tsum = reinterpret_cast<int*>(smem4 + 64 * nblk);
     int* red = tsum + W3_WAVES;
     {
         int s = 0;
-        for (int i = threadIdx.x; i < 64 * nblk; i += W3_THREADS) {
-            uint4 v = make_uint4(0u, 0u, 0u, 0u);
-            if (i < U) v = xq[i];
+        for (int i = threadIdx.x; i < xpieces; i += W3_THREADS) {
+            uint4 v = xfirst;
+            if (i >= W3_THREADS) {  // K > 8192 only
+                v = make_uint4(0u, 0u, 0u, 0u);
+                if (i < U) v = xq[i];
+            }
             smem4[i] = v;
             s = dot8(v.x, 0x11111111u, s);
             s = dot8(v.y, 0x11111111u, s);
@@ -189,7 +198,7 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
                     const float c = half_bits_to_float(static_cast<uint16_t>(l & 1 ? lw[l >> 1] >> 16 : lw[l >> 1] & 0xffffu));
                     o = l == 0 ? c * static_cast<float>(F[0]) : fmaf(c, static_cast<float>(F[l]), o);
                 }
-                o *= S;
+                o *= half_bits_to_float(sbits);
                 if constexpr (OUT_F16) static_cast<__half*>(out)[h] = __float2half_rn(o);
                 else static_cast<float*>(out)[h] = o;
                 if (Pout != nullptr) {
