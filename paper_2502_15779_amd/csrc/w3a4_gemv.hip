@@ -116,12 +116,18 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
     int* red = tsum + W3_WAVES;
     {
         int s = 0;
-        for (int i = threadIdx.x; i < xpieces; i += W3_THREADS) {
-            uint4 v = xfirst;
-            if (i >= W3_THREADS) {  // K > 8192 only
-                v = make_uint4(0u, 0u, 0u, 0u);
-                if (i < U) v = xq[i];
-            }
+        // the first piece apart from the loop: behind a join with the loop's own loads the compiler would
+        // wait for every load in flight, the weights included
+        if (static_cast<int>(threadIdx.x) < xpieces) {
+            smem4[threadIdx.x] = xfirst;
+            s = dot8(xfirst.x, 0x11111111u, s);
+            s = dot8(xfirst.y, 0x11111111u, s);
+            s = dot8(xfirst.z, 0x11111111u, s);
+            s = dot8(xfirst.w, 0x11111111u, s);
+        }
+        for (int i = threadIdx.x + W3_THREADS; i < xpieces; i += W3_THREADS) {  // K > 8192 only
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (i < U) v = xq[i];
             smem4[i] = v;
             s = dot8(v.x, 0x11111111u, s);
             s = dot8(v.y, 0x11111111u, s);
