@@ -131,9 +131,9 @@ __device__ __forceinline__ void heads_columns(float* sy, int m, float norm)
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT, int NW>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__ packed,
                                                             const uint2* __restrict__ codebook, int N, int K,
-                                                            const void* __restrict__ xraw,
-                                                            const uint4* __restrict__ xq,
+                                                            const void* __restrict__ x_in,
                                                             const uint16_t* __restrict__ scale, int M, float clip_ratio,
+                                                            int nblk,
                                                             void* __restrict__ out, int32_t* __restrict__ Pout,
                                                             uint32_t* __restrict__ xq_out, uint16_t* __restrict__ scale_out,
                                                             int rot_n, int rot_m, float rot_norm)
@@ -141,6 +141,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
     static_assert(WS == 1 || LW == 64, "several wavefronts per row group only with whole wavefronts");
     static_assert(NW == 4 || (NW == 8 && XDT >= 0 && XDT < 4), "eight wavefronts: the fused quantiser without rotation");
     constexpr int TH = NW * 64;  // threads of the workgroup
+    // one pointer for the activations: quantised (XDT < 0) or raw; the number of workgroups comes as an
+    // argument (nblk) because the launch dimensions would have to be fetched from memory first
+    const uint4* __restrict__ xq = static_cast<const uint4*>(x_in);
+    const void* __restrict__ xraw = x_in;
     static_assert(XDT < 0 || MT == 1, "the fused quantiser handles one token");
     constexpr bool ROT = XDT >= 4;              // Hadamard across heads in the prologue
     constexpr int XT = XDT >= 0 ? (XDT & 3) : 0;  // storage type of the raw activation
@@ -164,7 +168,6 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
     // select on the data in the loop.
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
-    const int nblk = gridDim.x;
     // Lane t owns units t, t + LG, ... of a row group: my_units of them.  When K fills every
     // chunk exactly no lane ever runs past K and the test below is always true.
     const int my_units = (U % (LG * UNR)) != 0 ? (U - tg + LG - 1) / LG : 0x7fffffff;
@@ -530,8 +533,8 @@ static int launch_one(const GemvArgs& a, int blocks, hipStream_t st)
         if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_w2a4_gemv: LDS opt-in failed: %s", hipGetErrorString(e));
     }
     kernel<<<blocks, NW * 64, lds, st>>>(
-        static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K, a.xraw,
-        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.M, a.clip_ratio, a.out, a.P,
+        static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K,
+        a.xraw != nullptr ? a.xraw : a.xq, static_cast<const uint16_t*>(a.scale), a.M, a.clip_ratio, blocks, a.out, a.P,
         static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out), a.rot_n, a.rot_m,
         a.rot_n > 0 ? static_cast<float>(1.0 / sqrt(static_cast<double>(a.rot_n))) : 1.0f);
     return check_launch("rcp_w2a4_gemv");
