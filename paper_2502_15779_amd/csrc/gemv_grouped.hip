@@ -54,6 +54,7 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
                                                                   const void* __restrict__ xraw,
                                                                   const uint4* __restrict__ xq,
                                                                   const uint16_t* __restrict__ scale, float clip_ratio,
+                                                                  int nblk,
                                                                   void* __restrict__ out, int32_t* __restrict__ Pout,
                                                                   uint32_t* __restrict__ xq_out,
                                                                   uint16_t* __restrict__ scale_out)
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
     const int U = K / 16, G = N / 4, NG = K / GG_GROUP;
     const int nround = (NG + 31) >> 5;
     const int nbatch = (G + GG_SLOTS - 1) / GG_SLOTS;
-    const int nblk = gridDim.x;
+    // (nblk, the number of workgroups, is an argument: the launch dimensions would have to be fetched from memory)
     int* tgs = reinterpret_cast<int*>(sx2 + U + 32);
 
     // Buffer resources: an offset past the end is answered with zeros, so neither idle lanes
@@ -328,7 +329,7 @@ static int launch_grouped_one(const GroupedArgs& a, int blocks, size_t lds, hipS
 {
     gemv_grouped_kernel<OUT_F16, XDT><<<blocks, GG_THREADS, lds, st>>>(
         static_cast<const uint4*>(a.packed), static_cast<const uint4*>(a.codebook), a.N, a.K, a.xraw,
-        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.clip_ratio, a.out, a.P,
+        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.clip_ratio, blocks, a.out, a.P,
         static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
     return check_launch("rcp_w2a4_gemv_grouped");
 }

@@ -68,7 +68,7 @@ template <bool XF32, int XDT, int WS, int UNR>
 __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restrict__ packed,
                                                            const uint2* __restrict__ codebook, int N, int K,
                                                            const void* __restrict__ x, void* __restrict__ out,
-                                                           int out_f16)
+                                                           int out_f16, int nblk)
 {
     constexpr int WO_UNR = UNR;
     constexpr int SLOTS = WO_WAVES / WS;  // row groups a workgroup works on at a time
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     const int tg = wsub * 64 + lane;  // this lane's position among the LG lanes of its row group
     const int nbatch = (G + SLOTS - 1) / SLOTS;
     const int nchunk = (U + LG * WO_UNR - 1) / (LG * WO_UNR);
-    const int nblk = gridDim.x;
+    // (nblk, the number of workgroups, is an argument: the launch dimensions would have to be fetched from memory)
     uint32_t* tab = wo_smem + wave * WO_TABLE_DWORDS;
     const uint32_t wave_bits = 0x40404040u * static_cast<uint32_t>(wave);
     uint32_t* sx = wo_smem + WO_WAVES * WO_TABLE_DWORDS;
@@ -297,7 +297,7 @@ static int launch_wo_one(const void* packed, const void* codebook, int N, int K,
         if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_w2a16_gemv: LDS opt-in failed: %s", hipGetErrorString(e));
     }
     kernel<<<blocks, WO_THREADS, lds, st>>>(static_cast<const uint4*>(packed), static_cast<const uint2*>(codebook), N, K, x, out,
-                                            out_dt == RCP_F16 ? 1 : 0);
+                                            out_dt == RCP_F16 ? 1 : 0, blocks);
     return check_launch("rcp_w2a16_gemv");
 }
 

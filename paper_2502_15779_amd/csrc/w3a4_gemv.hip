@@ -52,7 +52,7 @@ template <bool OUT_F16, int WS>
 __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __restrict__ packed,
                                                                const uint4* __restrict__ codebook, int N, int K,
                                                                const uint4* __restrict__ xq,
-                                                               const uint16_t* __restrict__ scale,
+                                                               const uint16_t* __restrict__ scale, int nblocks,
                                                                void* __restrict__ out, int32_t* __restrict__ Pout)
 {
     // x: 64 * nblk pieces of 16 bytes (zero beyond K); W3_WAVES sums of q; for WS > 1 the exchange
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
     // before the activations are staged; row groups past the end read zeros.
     int b = blockIdx.x;  // this workgroup's current batch of SLOTS row groups
     int j = wsub;
-    const int bstride = gridDim.x;
+    const int bstride = nblocks;  // an argument: the launch dimensions would have to be fetched from memory
     auto advance = [&](int& bb, int& jj) {
         jj += WS;
         if (jj >= nblk) {
@@ -222,7 +222,7 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
     };
     // steps counted up front and run in pairs: one loop body, one exit (with an exit after either
     // step the merged exit branches make the wait-count analysis stall on all loads in flight)
-    const int my_batches = (nbatch - static_cast<int>(blockIdx.x) + static_cast<int>(gridDim.x) - 1) / static_cast<int>(gridDim.x);
+    const int my_batches = (nbatch - static_cast<int>(blockIdx.x) + nblocks - 1) / nblocks;
     const int nsteps = my_batches * ((nblk - wsub + WS - 1) / WS);
     for (int i = 0; i < nsteps / 2; ++i) {
         step(wA);
@@ -247,7 +247,7 @@ static int launch_w3_ws(const void* packed, const void* codebook, int N, int K, 
     if (blocks > nbatch) blocks = nbatch;
     auto launch = [&](auto kernel) {
         kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(packed), static_cast<const uint4*>(codebook), N, K,
-                                                static_cast<const uint4*>(xq), static_cast<const uint16_t*>(scale), out, P);
+                                                static_cast<const uint4*>(xq), static_cast<const uint16_t*>(scale), blocks, out, P);
     };
     if (out_dt == RCP_F16) launch(&w3a4_gemv_kernel<true, WS>);
     else launch(&w3a4_gemv_kernel<false, WS>);
