@@ -49,14 +49,14 @@ template <bool OUT_F16, bool PACKED, bool NARROW>
 __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* __restrict__ packed,
                                                                    const uint2* __restrict__ codebook, int N, int K,
                                                                    const uint4* __restrict__ xq,
-                                                                   const uint16_t* __restrict__ scale, int M,
+                                                                   const uint16_t* __restrict__ scale, int M, int W,
                                                                    void* __restrict__ out, int32_t* __restrict__ Pout)
 {
     __shared__ int red[MM_LDS_INTS];  // F sums [plane][token][row of the block], T[token]; LUT rows, scales
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int W = static_cast<int>(blockDim.x) >> 6;
+    // (W, the wavefronts of the workgroup, is an argument: the launch dimensions would have to be fetched from memory)
     const int i = lane & 15, kb = lane >> 4;
     const int U = K / 16, G = N / 4;
     const int KS = (K + 127) >> 7;  // steps of 128 columns
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     const uint32_t row_mask = (i & 3) == 0 ? 0x11111111u : (i & 3) == 1 ? 0x22222222u : 0x44444444u;
     const int row_shift = (i & 3) == 3 ? 1 : 0;
 
-    for (int j = tid; j < MM_SUMS; j += blockDim.x) red[j] = 0;
+    for (int j = tid; j < MM_SUMS; j += 64 * W) red[j] = 0;
 
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     }
     __syncthreads();
 
-    for (int o = tid; o < M * RB; o += blockDim.x) {
+    for (int o = tid; o < M * RB; o += 64 * W) {
         const int n = o / RB, hh = o % RB;
         const int h = blockIdx.x * RB + hh;
         if (h >= N) continue;
@@ -288,7 +288,7 @@ int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, con
     auto* x4 = static_cast<const uint4*>(xq);
     auto* sc = static_cast<const uint16_t*>(scale);
     const dim3 grid(blocks), block(waves * 64);
-#define RCP_MM(F16, PK, NA) gemm_mfma_kernel<F16, PK, NA><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P)
+#define RCP_MM(F16, PK, NA) gemm_mfma_kernel<F16, PK, NA><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P)
     const bool f16 = out_dt == RCP_F16, pkd = M <= 8;
     if (narrow) {
         if (pkd) { if (f16) RCP_MM(true, true, true); else RCP_MM(false, true, true); }

@@ -47,7 +47,7 @@ template <bool OUT_F16, bool NARROW>
 __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uint4* __restrict__ packed,
                                                                        const uint4* __restrict__ codebook, int N, int K,
                                                                        const uint4* __restrict__ xq,
-                                                                       const uint16_t* __restrict__ scale, int M,
+                                                                       const uint16_t* __restrict__ scale, int M, int W,
                                                                        void* __restrict__ out, int32_t* __restrict__ Pout)
 {
     __shared__ float slab[MG_WAVES * 16 * MG_STRIDE];  // [wavefront][token][row of the block]
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int W = static_cast<int>(blockDim.x) >> 6;
+    // (W, the wavefronts of the workgroup, is an argument: the launch dimensions would have to be fetched from memory)
     const int i = lane & 15, kb = lane >> 4;
     const int U = K / 16, G = N / 4, NG = K / RCP_GROUP;
     constexpr int RB = NARROW ? 16 : 64;   // output rows of the workgroup
@@ -258,7 +258,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
     }
     __syncthreads();
 
-    for (int idx = tid; idx < M * RB; idx += blockDim.x) {
+    for (int idx = tid; idx < M * RB; idx += 64 * W) {
         const int n = idx / RB, hh = idx % RB;
         const int h = blockIdx.x * RB + hh;
         if (h >= N) continue;
@@ -291,14 +291,14 @@ int launch_gemm_mfma_grouped(const void* packed, const void* codebook, int N, in
     auto* sc = static_cast<const uint16_t*>(scale);
     if (narrow) {
         if (out_dt == RCP_F16)
-            gemm_mfma_grouped_kernel<true, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+            gemm_mfma_grouped_kernel<true, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
         else
-            gemm_mfma_grouped_kernel<false, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+            gemm_mfma_grouped_kernel<false, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
     } else {
         if (out_dt == RCP_F16)
-            gemm_mfma_grouped_kernel<true, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+            gemm_mfma_grouped_kernel<true, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
         else
-            gemm_mfma_grouped_kernel<false, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, out, P);
+            gemm_mfma_grouped_kernel<false, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
     }
     return check_launch("rcp_w2a4_gemm_grouped");
 }
