@@ -16,10 +16,12 @@ namespace rcp {
 // shared pieces
 // ---------------------------------------------------------------------------------------
 // Maximum over the workgroup; every thread gets the result.  `red` holds 16 floats.
-__device__ __forceinline__ float block_max(float v, float* red)
+// `nw` is the number of wavefronts of the workgroup (an argument: the launch dimensions would
+// have to be fetched from memory first).
+__device__ __forceinline__ float block_max(float v, float* red, int nw)
 {
     v = wave_max(v);
-    const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) red[wave] = v;
     __syncthreads();
     float r = red[0];
@@ -32,7 +34,7 @@ __device__ __forceinline__ float block_max(float v, float* red)
 // One workgroup per token; a thread owns ITERS groups of eight consecutive elements.
 // ---------------------------------------------------------------------------------------
 template <int DT, int ITERS>
-__global__ __launch_bounds__(1024) void quant_kernel(const void* __restrict__ x, int K, float clip_ratio,
+__global__ __launch_bounds__(1024) void quant_kernel(const void* __restrict__ x, int K, float clip_ratio, int threads,
                                                      uint32_t* __restrict__ xq, uint16_t* __restrict__ scale)
 {
     __shared__ float red[16];
@@ -42,19 +44,19 @@ __global__ __launch_bounds__(1024) void quant_kernel(const void* __restrict__ x,
     float a = 0.0f;
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
-        const int u = threadIdx.x + it * blockDim.x;
+        const int u = threadIdx.x + it * threads;
         if (u < units) {
             load8_as_float<DT>(x, static_cast<size_t>(token) * K + static_cast<size_t>(u) * 8, v[it]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(v[it][j]));
         }
     }
-    a = block_max(a, red);
+    a = block_max(a, red, threads >> 6);
     const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
     const float s = half_bits_to_float(sb);
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
-        const int u = threadIdx.x + it * blockDim.x;
+        const int u = threadIdx.x + it * threads;
         if (u < units) xq[static_cast<size_t>(token) * units + u] = quantize8(v[it], s);
     }
     if (threadIdx.x == 0) scale[token] = sb;
@@ -96,7 +98,7 @@ __device__ __forceinline__ int wht_slot(int a)
 
 template <int DT, int LE, bool QUANT>
 __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict__ x, int n, int log2n, float norm,
-                                                         float clip_ratio, uint32_t* __restrict__ xq,
+                                                         float clip_ratio, int waves, uint32_t* __restrict__ xq,
                                                          uint16_t* __restrict__ scale, float* __restrict__ y_out)
 {
     constexpr int EPT = 1 << LE;
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict_
         }
         return;
     }
-    a = block_max(a, red);
+    a = block_max(a, red, waves);
     const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
     const float s = half_bits_to_float(sb);
     if (active) {
@@ -499,7 +501,7 @@ __global__ __launch_bounds__(HEADS_THREADS) void heads_wht_kernel(const void* __
     }
     float a = 0.0f;
     for (int u = threadIdx.x; u < K; u += HEADS_THREADS) a = fmaxf(a, fabsf(sy[u]));
-    a = block_max(a, red);
+    a = block_max(a, red, HEADS_THREADS / 64);
     const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
     const float sc = half_bits_to_float(sb);
     for (int u = threadIdx.x; u < K / 8; u += HEADS_THREADS) {
@@ -540,9 +542,9 @@ static int launch_quant(const void* x, int M, int K, float clip_ratio, void* xq,
     const int iters = (units + threads - 1) / threads;
     auto* q = static_cast<uint32_t*>(xq);
     auto* s = static_cast<uint16_t*>(scale);
-    if (iters == 1) quant_kernel<DT, 1><<<M, threads, 0, st>>>(x, K, clip_ratio, q, s);
-    else if (iters == 2) quant_kernel<DT, 2><<<M, threads, 0, st>>>(x, K, clip_ratio, q, s);
-    else if (iters <= 4) quant_kernel<DT, 4><<<M, threads, 0, st>>>(x, K, clip_ratio, q, s);
+    if (iters == 1) quant_kernel<DT, 1><<<M, threads, 0, st>>>(x, K, clip_ratio, threads, q, s);
+    else if (iters == 2) quant_kernel<DT, 2><<<M, threads, 0, st>>>(x, K, clip_ratio, threads, q, s);
+    else if (iters <= 4) quant_kernel<DT, 4><<<M, threads, 0, st>>>(x, K, clip_ratio, threads, q, s);
     else return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act: K=%d too large for the quantiser", K);
     return check_launch("rcp_rotate_quant_act(quantise)");
 }
@@ -558,14 +560,14 @@ static int launch_wht(const void* x, int M, int n, float clip_ratio, void* xq, v
     const size_t lds = static_cast<size_t>(n) * sizeof(float);
     if (n <= 8192) {  // (16 elements per thread save an LDS pass but are not faster at 4096 / 8192 points)
         const int threads = ((n / 8 + 63) / 64) * 64;
-        wht_quant_kernel<DT, 3, QUANT><<<M, threads, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s, y);
+        wht_quant_kernel<DT, 3, QUANT><<<M, threads, lds, st>>>(x, n, log2n, norm, clip_ratio, threads / 64, q, s, y);
     } else {
         if (lds + 64 > 65536) {  // 64 KiB of dynamic LDS plus the static reduction slots: above the default limit
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&wht_quant_kernel<DT, 4, QUANT>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
             if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));
         }
-        wht_quant_kernel<DT, 4, QUANT><<<M, n / 16, lds, st>>>(x, n, log2n, norm, clip_ratio, q, s, y);
+        wht_quant_kernel<DT, 4, QUANT><<<M, n / 16, lds, st>>>(x, n, log2n, norm, clip_ratio, n / 1024, q, s, y);
     }
     return check_launch("rcp_rotate_quant_act(wht)");
 }
