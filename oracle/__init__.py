@@ -279,3 +279,46 @@ def w3a4_gemv(packed, codebook, N, K, xq, scale_bits):
     P = np.empty((N, 8), dtype=np.int32)
     _check(lib().rcp_ref_w3a4_gemv(_p(packed), _p(codebook), N, K, _p(xq), _p(sb), _p(out), _p(P)), "w3a4_gemv")
     return out, P
+
+
+# ---- 4-bit KV cache and one-token attention over it ---------------------------------------
+KV_D = 128
+
+
+def kv4_new_cache(H, S_max):
+    """(codes uint8[H][S_max][64], params uint8[H][S_max][4]) zero-filled."""
+    return np.zeros((H, S_max, KV_D // 2), dtype=np.uint8), np.zeros((H, S_max, 4), dtype=np.uint8)
+
+
+def kv4_append(x, pos, clip_ratio, codes, params):
+    """Quantise x float32[n][H][128] into cache positions pos .. pos + n - 1 (in place)."""
+    x = _c(x, np.float32)
+    n, H, d = x.shape
+    assert d == KV_D and codes.shape[0] == H and codes.flags.c_contiguous and params.flags.c_contiguous
+    S_max = codes.shape[1]
+    _check(lib().rcp_ref_kv4_append(_p(x), n, H, S_max, int(pos), ctypes.c_float(clip_ratio), _p(codes), _p(params)),
+           "kv4_append")
+
+
+def kv4_params(params):
+    """(scale_bits uint16[H][S_max], zero int16[H][S_max]) views of the parameter bytes."""
+    return params.view(np.uint16)[..., 0], params.view(np.int16)[..., 1]
+
+
+def kv4_dequant(codes, params, pos, n):
+    """float64[n][H][128]: the values the stored codes stand for."""
+    H, S_max = codes.shape[:2]
+    out = np.empty((n, H, KV_D), dtype=np.float64)
+    _check(lib().rcp_ref_kv4_dequant(_p(codes), _p(params), H, S_max, int(pos), int(n), _p(out)), "kv4_dequant")
+    return out
+
+
+def kv4_attn_decode(q, S, k_codes, k_params, v_codes, v_params, softmax_scale):
+    """float64[H_q][128]: one query token against the first S cached tokens."""
+    q = _c(q, np.float64)
+    H_q = q.shape[0]
+    H_kv, S_max = k_codes.shape[:2]
+    out = np.empty((H_q, KV_D), dtype=np.float64)
+    _check(lib().rcp_ref_kv4_attn_decode(_p(q), H_q, H_kv, S_max, int(S), _p(k_codes), _p(k_params), _p(v_codes),
+                                         _p(v_params), ctypes.c_double(softmax_scale), _p(out)), "kv4_attn_decode")
+    return out

@@ -16,8 +16,11 @@
  * fp16 conversions against numpy's; pack/unpack against each other; the
  * quantiser against its error bound; the GEMV against brute force and numpy
  * integer matmuls; the 3-bit variant against nearest-level brute force, the
- * integer-grid case of its printed rounding rule and the 2-bit GEMV.  No
- * function here is "parity unpinned".
+ * integer-grid case of its printed rounding rule and the 2-bit GEMV; the 4-bit
+ * KV cache against exact reproduction of integer grids, nearest-point brute
+ * force and the half-step error bound, and attention over it against scipy's
+ * softmax and its closed-form special cases.  No function here is "parity
+ * unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -731,4 +734,139 @@ int rcp_ref_w3a4_gemv(const uint8_t* packed, const uint16_t* codebook, int N, in
     }
     free(q);
     return RCP_REF_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * 4-bit KV cache (Appendix table of quantisation configurations: asymmetric,
+ * groups of 128 = one head vector, clipping ratio 0.95; quantiser of Eqn. 1
+ * with N = 4) and one-token attention over it (Section 2.1: R3 rotates Q and
+ * K so that the cache can be compressed without changing attention outputs).
+ *
+ * Cache of one tensor (K or V) of one layer, HEAD_DIM = 128:
+ *   codes  uint8 [H][S_max][64]   element j of a head vector in byte j / 2,
+ *                                 bits 4 * (j % 2) .. 4 * (j % 2) + 3
+ *   params       [H][S_max][4 B]  bytes 0..1 the binary16 step size s,
+ *                                 bytes 2..3 the int16 zero point z
+ * The rounding decisions are taken in binary32, the precision of the GPU
+ * kernel:
+ *   lo = ratio * min(x), hi = ratio * max(x), s = fp16((hi - lo) / 15)
+ *       [s = 1 if that is 0; capped at 65504]
+ *   z = -rint(lo / s)                       [clamped to the int16 range]
+ *   code = clamp(rint(x / s) + z, 0, 15)    [rint = round half to even]
+ * and a code stands for the value s * (code - z).  The zero point is taken
+ * from min / s (the printed equation divides the minimum by the range h, which
+ * would make z one of -1, 0, 1 whatever the data; s is what makes the codes of
+ * the minimum and the maximum land on 0 and 15).
+ * ---------------------------------------------------------------------- */
+#define KV_D 128
+
+static inline size_t kv_code_byte(int h, int t, int j, int S_max)
+{
+    return ((size_t)h * S_max + t) * (KV_D / 2) + (size_t)(j / 2);
+}
+static inline size_t kv_param_byte(int h, int t, int S_max) { return ((size_t)h * S_max + t) * 4; }
+
+/* x: [n_tokens][H][128] binary32; writes tokens pos .. pos + n_tokens - 1 */
+int rcp_ref_kv4_append(const float* x, int n_tokens, int H, int S_max, int pos, float clip_ratio, uint8_t* codes,
+                       uint8_t* params)
+{
+    if (n_tokens < 0 || H < 1 || S_max < 1 || pos < 0 || pos + n_tokens > S_max) return RCP_REF_ERR_SHAPE;
+    for (int i = 0; i < n_tokens; ++i)
+        for (int h = 0; h < H; ++h) {
+            const float* v = x + ((size_t)i * H + h) * KV_D;
+            float lo = v[0], hi = v[0];
+            for (int j = 1; j < KV_D; ++j) {
+                if (v[j] < lo) lo = v[j];
+                if (v[j] > hi) hi = v[j];
+            }
+            float lo_c = clip_ratio * lo, hi_c = clip_ratio * hi;
+            float range = hi_c - lo_c;
+            float raw = range / 15.0f;
+            uint16_t sb = rcp_ref_f64_to_f16_bits((double)raw);
+            if ((sb & 0x7fffu) == 0) sb = 0x3c00u;       /* 1.0 */
+            if ((sb & 0x7fffu) >= 0x7c00u) sb = 0x7bffu; /* 65504 */
+            float s = (float)rcp_ref_f16_bits_to_f64(sb);
+            float zf = -rintf(lo_c / s);
+            if (zf > 32767.0f) zf = 32767.0f;
+            if (zf < -32768.0f) zf = -32768.0f;
+            int16_t z = (int16_t)zf;
+            zf = (float)z; /* drops the sign of a negative zero */
+            const int t = pos + i;
+            uint8_t* pp = params + kv_param_byte(h, t, S_max);
+            pp[0] = (uint8_t)(sb & 0xff);
+            pp[1] = (uint8_t)(sb >> 8);
+            pp[2] = (uint8_t)((uint16_t)z & 0xff);
+            pp[3] = (uint8_t)((uint16_t)z >> 8);
+            for (int j = 0; j < KV_D; ++j) {
+                float r = rintf(v[j] / s) + zf;
+                if (r > 15.0f) r = 15.0f;
+                if (r < 0.0f) r = 0.0f;
+                uint8_t c = (uint8_t)r;
+                uint8_t* b = codes + kv_code_byte(h, t, j, S_max);
+                if (j % 2 == 0) *b = (uint8_t)((*b & 0xf0u) | c);
+                else *b = (uint8_t)((*b & 0x0fu) | (c << 4));
+            }
+        }
+    return RCP_REF_OK;
+}
+
+static inline double kv_value(const uint8_t* codes, const uint8_t* params, int h, int t, int j, int S_max)
+{
+    const uint8_t* pp = params + kv_param_byte(h, t, S_max);
+    double s = rcp_ref_f16_bits_to_f64((uint16_t)(pp[0] | (pp[1] << 8)));
+    int z = (int16_t)(uint16_t)(pp[2] | (pp[3] << 8));
+    uint8_t b = codes[kv_code_byte(h, t, j, S_max)];
+    int c = (j % 2 == 0) ? (b & 0xf) : (b >> 4);
+    return s * (double)(c - z);
+}
+
+/* out: [n_tokens][H][128] double, the values the codes stand for */
+int rcp_ref_kv4_dequant(const uint8_t* codes, const uint8_t* params, int H, int S_max, int pos, int n_tokens,
+                        double* out)
+{
+    if (n_tokens < 0 || H < 1 || S_max < 1 || pos < 0 || pos + n_tokens > S_max) return RCP_REF_ERR_SHAPE;
+    for (int i = 0; i < n_tokens; ++i)
+        for (int h = 0; h < H; ++h)
+            for (int j = 0; j < KV_D; ++j)
+                out[((size_t)i * H + h) * KV_D + j] = kv_value(codes, params, h, pos + i, j, S_max);
+    return RCP_REF_OK;
+}
+
+/* One query token against the first S cached tokens.  q, out: [H_q][128] double.  Query head
+ * h reads cache head h / (H_q / H_kv).  out_h = sum_t softmax_t(scale * q_h . K_t) * V_t. */
+int rcp_ref_kv4_attn_decode(const double* q, int H_q, int H_kv, int S_max, int S, const uint8_t* k_codes,
+                            const uint8_t* k_params, const uint8_t* v_codes, const uint8_t* v_params,
+                            double softmax_scale, double* out)
+{
+    if (H_q < 1 || H_kv < 1 || H_q % H_kv != 0 || S < 1 || S > S_max) return RCP_REF_ERR_SHAPE;
+    const int rep = H_q / H_kv;
+    int rc = RCP_REF_OK;
+#pragma omp parallel for schedule(static)
+    for (int h = 0; h < H_q; ++h) {
+        const int hk = h / rep;
+        double* score = (double*)malloc((size_t)S * sizeof(double));
+        if (!score) {
+            rc = RCP_REF_ERR_OVERFLOW;
+            continue;
+        }
+        double top = -INFINITY;
+        for (int t = 0; t < S; ++t) {
+            double acc = 0.0;
+            for (int j = 0; j < KV_D; ++j) acc += q[(size_t)h * KV_D + j] * kv_value(k_codes, k_params, hk, t, j, S_max);
+            score[t] = softmax_scale * acc;
+            if (score[t] > top) top = score[t];
+        }
+        double denom = 0.0;
+        for (int t = 0; t < S; ++t) {
+            score[t] = exp(score[t] - top);
+            denom += score[t];
+        }
+        for (int j = 0; j < KV_D; ++j) {
+            double acc = 0.0;
+            for (int t = 0; t < S; ++t) acc += score[t] * kv_value(v_codes, v_params, hk, t, j, S_max);
+            out[(size_t)h * KV_D + j] = acc / denom;
+        }
+        free(score);
+    }
+    return rc;
 }

@@ -21,6 +21,11 @@ no rotation, no quantisation).  The recipe:
   centre frac  per output row: logistic of a N(0, 0.5^2) logit (a stand-in for the learnt
                centre point between the two clip values)
 
+  KV vectors   head vectors of 128 values for the 4-bit cache, fp16: N(mu_h, sigma_h^2) with a
+               per-head spread sigma_h = exp(N(0, 0.4^2)) and a per-head offset
+               mu_h = 0.3 * sigma_h * N(0,1) (rotated keys and values are near-Gaussian; the
+               offset makes the zero points differ from the mid code); queries: fp16 N(0,1)
+
 Every tensor has its own random stream derived from (seed, tensor name).
 """
 import statistics
@@ -144,3 +149,17 @@ def linear_layer_w3(seed: int, name: str, N: int, K: int):
     W = weights(seed, name, N, K)
     lo, hi = clip_range(W)
     return W, lo, hi, centre_fractions(seed, name, N), normal_quantile_grid()
+
+
+def kv_vectors(seed: int, name: str, n_tokens: int, H: int, d: int = 128) -> np.ndarray:
+    """n_tokens x H x d fp16 head vectors (keys or values after their rotation)."""
+    g = _rng(seed, "kv:" + name)
+    sigma = np.exp(0.4 * g.standard_normal(H)).astype(np.float32)
+    mu = 0.3 * sigma * g.standard_normal(H).astype(np.float32)
+    x = g.standard_normal((n_tokens, H, d), dtype=np.float32) * sigma[None, :, None] + mu[None, :, None]
+    return x.astype(np.float16)
+
+
+def query_vectors(seed: int, name: str, H: int, d: int = 128) -> np.ndarray:
+    """H x d fp16 query head vectors."""
+    return _rng(seed, "query:" + name).standard_normal((H, d), dtype=np.float32).astype(np.float16)
