@@ -359,6 +359,42 @@ int rcp_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
                   void* out, rcp_dtype out_dtype,
                   int32_t* partial_sums_or_null, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * 4-bit KV cache and one-token attention over it.  Appendix, table of quantisation
+ * configurations: the KV cache uses an asymmetric quantiser on groups of 128 with clipping
+ * ratio 0.95; the quantiser is Eqn. 1 with N = 4.  Section 2.1: the online rotation R3 is
+ * applied to queries and keys so that the cache can be held in 4 bits without changing the
+ * attention output; apply it with rcp_rotate_act (an order-128 WHT over rows of 128) before
+ * the calls below.  Head size is RCP_KV_HEAD_DIM = 128 = one group.
+ *
+ * Layout of one cached tensor (keys or values) of one layer, both device buffers, caller-owned:
+ *   codes   [H][S_max][64 bytes]  element j of a head vector in byte j / 2, bits 4*(j%2) .. 4*(j%2)+3
+ *   params  [H][S_max][4 bytes]   bytes 0..1 the binary16 step size s, bytes 2..3 the int16 zero point z
+ * A code c stands for the value s * (c - z).
+ *
+ * rcp_kv4_append: x is [n_tokens][H][128] of `x_dtype`; token i goes to cache position pos + i
+ *   (0 <= pos, pos + n_tokens <= S_max, else RCP_ERR_SHAPE; n_tokens = 0 is a no-op).  In binary32:
+ *     lo = ratio * min(x), hi = ratio * max(x), s = fp16((hi - lo) / 15)   [1 when that is 0; capped at 65504]
+ *     z = -rint(lo / s)  [clamped to int16],  c_j = clamp(rint(x_j / s) + z, 0, 15)
+ *   with correctly rounded divisions and round-half-to-even.  Other cache positions are not touched.
+ * rcp_kv4_attn_decode: one query token against cache positions 0 .. S-1 (1 <= S <= S_max):
+ *     out[h] = sum_t softmax_t(softmax_scale * q[h] . K[g][t]) * V[g][t],   g = h / (H_q / H_kv)
+ *   q: [H_q][128] of `q_dtype`; out: [H_q][128] of `out_dtype` (RCP_F16 or RCP_F32); H_q a multiple of
+ *   H_kv.  Sums are binary32.  workspace: rcp_kv4_workspace_bytes(H_q, S) bytes of device memory
+ *   (RCP_ERR_WORKSPACE when missing or smaller), overwritten by every call.  S above
+ *   RCP_KV_MAX_S returns RCP_ERR_UNSUPPORTED.
+ */
+#define RCP_KV_HEAD_DIM 128
+#define RCP_KV_MAX_S 262144
+size_t rcp_kv4_workspace_bytes(int H_q, int S);
+int rcp_kv4_append(const void* x, rcp_dtype x_dtype, int n_tokens, int H, int S_max, int pos,
+                   float clip_ratio, void* codes, void* params, void* stream);
+int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int S_max, int S,
+                        const void* k_codes, const void* k_params,
+                        const void* v_codes, const void* v_params,
+                        float softmax_scale, void* out, rcp_dtype out_dtype,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -121,6 +121,13 @@ def lib():
         L.rcp_unpack_indices_w3.argtypes = [vp, ci, ci, vp, vp]
         L.rcp_w3a4_gemv.restype = ci
         L.rcp_w3a4_gemv.argtypes = [vp, vp, ci, ci, vp, vp, vp, ci, vp, vp]
+        L.rcp_kv4_workspace_bytes.restype = ctypes.c_size_t
+        L.rcp_kv4_workspace_bytes.argtypes = [ci, ci]
+        L.rcp_kv4_append.restype = ci
+        L.rcp_kv4_append.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
+        L.rcp_kv4_attn_decode.restype = ci
+        L.rcp_kv4_attn_decode.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp,
+                                          ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -478,3 +485,56 @@ def w3a4_gemv(packed, codebook, N, K, xq, scale, out=None, out_dtype=torch.float
                                _dev(scale, "scale"), _dev(out, "out"), _DTYPES[out.dtype],
                                _dev(partial_sums, "partial_sums") if partial_sums is not None else None, _stream()))
     return (out, partial_sums) if partial_sums is not None else out
+
+
+# ---- 4-bit KV cache ------------------------------------------------------------------------
+KV_HEAD_DIM = 128
+
+
+def kv4_new_cache(H, S_max, device):
+    """(codes uint8 [H, S_max, 64], params uint8 [H, S_max, 4]) zero-filled device buffers."""
+    return (torch.zeros((H, S_max, KV_HEAD_DIM // 2), dtype=torch.uint8, device=device),
+            torch.zeros((H, S_max, 4), dtype=torch.uint8, device=device))
+
+
+def kv4_workspace_bytes(H_q, S):
+    return int(lib().rcp_kv4_workspace_bytes(H_q, S))
+
+
+def kv4_append(x, pos, codes, params, clip_ratio=0.95):
+    """Quantise x [n_tokens, H, 128] into cache positions pos .. pos + n_tokens - 1 (in place)."""
+    if x.dim() != 3 or x.shape[2] != KV_HEAD_DIM or not x.is_contiguous():
+        raise ValueError("x must be contiguous [n_tokens, H, 128]")
+    n, H = int(x.shape[0]), int(x.shape[1])
+    if codes.dtype != torch.uint8 or params.dtype != torch.uint8 or codes.dim() != 3 or codes.shape[0] != H or \
+            codes.shape[2] != KV_HEAD_DIM // 2 or tuple(params.shape) != (H, codes.shape[1], 4) or \
+            not codes.is_contiguous() or not params.is_contiguous():
+        raise ValueError("codes must be uint8 [H, S_max, 64] and params uint8 [H, S_max, 4], contiguous")
+    if n == 0:      # an empty tensor has no device pointer to hand over
+        return
+    _check(lib().rcp_kv4_append(_dev(x, "x"), _DTYPES[x.dtype], n, H, int(codes.shape[1]), int(pos),
+                                ctypes.c_float(clip_ratio), _dev(codes, "codes"), _dev(params, "params"), _stream()))
+
+
+def kv4_attn_decode(q, S, k_codes, k_params, v_codes, v_params, softmax_scale, out=None, out_dtype=torch.float32,
+                    workspace=None):
+    """One query token [H_q, 128] against the first S cached tokens -> out [H_q, 128]."""
+    if q.dim() != 2 or q.shape[1] != KV_HEAD_DIM or not q.is_contiguous():
+        raise ValueError("q must be contiguous [H_q, 128]")
+    H_q, H_kv, S_max = int(q.shape[0]), int(k_codes.shape[0]), int(k_codes.shape[1])
+    for c, p in ((k_codes, k_params), (v_codes, v_params)):
+        if c.dtype != torch.uint8 or p.dtype != torch.uint8 or tuple(c.shape) != (H_kv, S_max, KV_HEAD_DIM // 2) or \
+                tuple(p.shape) != (H_kv, S_max, 4) or not c.is_contiguous() or not p.is_contiguous():
+            raise ValueError("cache buffers must be uint8 [H_kv, S_max, 64] / [H_kv, S_max, 4], contiguous")
+    if out is None:
+        out = torch.empty((H_q, KV_HEAD_DIM), dtype=out_dtype, device=q.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < H_q * KV_HEAD_DIM:
+        raise ValueError("out must be float16 or float32 [H_q, 128]")
+    if workspace is None:
+        workspace = torch.empty(max(kv4_workspace_bytes(H_q, S), 16), dtype=torch.uint8, device=q.device)
+    _check(lib().rcp_kv4_attn_decode(_dev(q, "q"), _DTYPES[q.dtype], H_q, H_kv, S_max, int(S), _dev(k_codes, "k_codes"),
+                                     _dev(k_params, "k_params"), _dev(v_codes, "v_codes"), _dev(v_params, "v_params"),
+                                     ctypes.c_float(softmax_scale), _dev(out, "out"), _DTYPES[out.dtype],
+                                     _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                     _stream()))
+    return out

@@ -1,0 +1,323 @@
+// 4-bit KV cache (Appendix table of quantisation configurations: asymmetric, groups of 128 = one
+// head vector, clipping ratio 0.95; the quantiser is Eqn. 1 with N = 4) and one-token attention
+// over it (Section 2.1: R3 rotates queries and keys so that the cache can be held in 4 bits).
+//
+// Layout of one cached tensor (keys or values) of one layer, head size 128:
+//   codes   [H][S_max][64 bytes]  element j of a head vector in byte j / 2, bits 4 * (j % 2) ...
+//   params  [H][S_max] dwords     bits 0..15 the binary16 step s, bits 16..31 the int16 zero point z
+// Head-major, so that the tokens one head attends to are contiguous: a wavefront reads 1 KiB
+// (16 tokens) per load instruction.
+#include <math.h>
+
+#include "rcp_internal.hpp"
+
+namespace rcp {
+
+constexpr int KV_D = 128;
+
+// ---------------------------------------------------------------------------------------
+// append: quantise n_tokens x H head vectors into cache positions pos ...
+// Sixteen lanes (one DPP row) own a head vector, eight consecutive elements each.
+// ---------------------------------------------------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict__ x, int rows, int H, int S_max, int pos,
+                                                         float clip_ratio, uint32_t* __restrict__ codes,
+                                                         uint32_t* __restrict__ params)
+{
+    // every product and difference below is rounded on its own (hi_c - lo_c must not become a
+    // fused multiply-add: for a constant vector it has to be exactly zero).  The pragma covers
+    // the operators written in this body, hence plain * and - rather than the __f*_rn wrappers.
+#pragma clang fp contract(off)
+    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int l = threadIdx.x & 15;
+    const bool have = row < rows;
+    const int rr = have ? row : rows - 1;  // surplus lanes repeat the last vector and store nothing
+    float v[8];
+    load8_as_float<DT>(x, static_cast<size_t>(rr) * KV_D + 8 * l, v);
+    float lo = v[0], hi = v[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) {
+        lo = fminf(lo, v[j]);
+        hi = fmaxf(hi, v[j]);
+    }
+#define RCP_ROW_MINMAX(ctrl)                                                                                        \
+    lo = fminf(lo, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(lo), ctrl, 0xf, 0xf, false)));    \
+    hi = fmaxf(hi, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(hi), ctrl, 0xf, 0xf, false)))
+    RCP_ROW_MINMAX(0x128);
+    RCP_ROW_MINMAX(0x124);
+    RCP_ROW_MINMAX(0x122);
+    RCP_ROW_MINMAX(0x121);
+#undef RCP_ROW_MINMAX
+    const float lo_c = clip_ratio * lo, hi_c = clip_ratio * hi;
+    const float range = hi_c - lo_c;
+    const float raw = __fdiv_rn(range, 15.0f);
+    uint16_t sb = __half_as_ushort(__float2half_rn(raw));
+    if ((sb & 0x7fffu) == 0) sb = 0x3c00u;
+    if ((sb & 0x7fffu) >= 0x7c00u) sb = 0x7bffu;
+    const float s = half_bits_to_float(sb);
+    float zf = -rintf(__fdiv_rn(lo_c, s));
+    zf = fminf(fmaxf(zf, -32768.0f), 32767.0f);
+    const int z = static_cast<int>(zf);
+    zf = static_cast<float>(z);
+    uint32_t word = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float r = __builtin_amdgcn_fmed3f(rintf(__fdiv_rn(v[j], s)) + zf, 0.0f, 15.0f);
+        word |= static_cast<uint32_t>(r) << (4 * j);
+    }
+    if (have) {
+        const int i = row / H, h = row - i * H;
+        const size_t slot = static_cast<size_t>(h) * S_max + (pos + i);
+        codes[slot * 16 + l] = word;
+        if (l == 0) params[slot] = static_cast<uint32_t>(sb) | (static_cast<uint32_t>(z & 0xffff) << 16);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// one-token attention, split along the sequence.
+// Workgroup (split, query head): L cached tokens.  Four lanes own a token, 16 bytes (32
+// elements) of its vector each; a wavefront covers 16 tokens per load, the workgroup 64.
+//   pass 1  scores q . K_t into LDS, their maximum m
+//   pass 2  p_t = exp(score_t - m), l = sum p_t, acc_j = sum_t p_t * V_tj
+// and (m, l, acc) go to the workspace; kv4_combine_kernel merges the splits.
+// With x_tj = s_t * (c_tj - z_t):  q . K_t = s_t * (sum_j q_j c_tj - z_t * sum_j q_j)  and
+// sum_t p_t V_tj = sum_t (p_t s_t) c_tj - sum_t p_t s_t z_t, so the codes enter as plain integers.
+//
+// Register r = 8 d + 4 e + b of a lane stands for element 8 d + 2 b + e of its 32 (dword d of
+// the 16 bytes, byte b, nibble e): the order in which the nibbles come out of two masks.
+// ---------------------------------------------------------------------------------------
+constexpr int KV_THREADS = 256;
+constexpr int KV_MAX_L = 1024;         // tokens per workgroup at most (scores held in LDS)
+constexpr int KV_PART = KV_D + 4;      // floats per partial result: acc[128], m, l, 2 unused
+
+__device__ __forceinline__ int kv_elem_of_reg(int r) { return 8 * (r >> 3) + 2 * (r & 3) + ((r >> 2) & 1); }
+
+__device__ __forceinline__ float quad_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));  // lanes 1,0,3,2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));  // lanes 2,3,0,1
+    return v;
+}
+
+// sum over the four tokens of a row of 16 lanes (lanes 4 apart hold the same piece)
+__device__ __forceinline__ float row_tokens_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x124, 0xf, 0xf, false));  // row_ror 4
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x128, 0xf, 0xf, false));  // row_ror 8
+    return v;
+}
+
+template <int QDT>
+__global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __restrict__ q, int S, int S_max, int L, int rep,
+                                                              int splits, float softmax_scale,
+                                                              const u32x4* __restrict__ k_codes,
+                                                              const uint32_t* __restrict__ k_params,
+                                                              const u32x4* __restrict__ v_codes,
+                                                              const uint32_t* __restrict__ v_params,
+                                                              float* __restrict__ part)
+{
+    __shared__ float sc[KV_MAX_L];
+    __shared__ float red[4][KV_D];
+    __shared__ float wmax[4], lrow[4][4], zrow[4][4];
+    const int split = blockIdx.x, h = blockIdx.y, hk = h / rep;
+    const int tid = threadIdx.x, slot = tid >> 2, piece = tid & 3, wave = tid >> 6;
+    const int t0 = split * L;
+    const int t_end = min(S, t0 + L);
+    const int iters = (t_end - t0 + 63) >> 6;
+    const size_t head_base = static_cast<size_t>(hk) * S_max;
+
+    // this lane's 32 query values, times the softmax scale, in register order
+    float qr[32];
+    float qsum = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        float t8[8];
+        load8_as_float<QDT>(q, static_cast<size_t>(h) * KV_D + 32 * piece + 8 * d, t8);
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                qr[8 * d + 4 * e + b] = t8[2 * b + e] * softmax_scale;
+                qsum += qr[8 * d + 4 * e + b];
+            }
+    }
+
+    // ---- pass 1: scores ----
+    float top = -INFINITY;
+    for (int it = 0; it < iters; ++it) {
+        const int t = t0 + it * 64 + slot;
+        const bool valid = t < t_end;
+        const size_t at = head_base + (valid ? t : t_end - 1);
+        const u32x4 kw = k_codes[at * 4 + piece];
+        const uint32_t kp = k_params[at];
+        float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = kw[d] & 0x0f0f0f0fu, hi = (kw[d] >> 4) & 0x0f0f0f0fu;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                dot[d] = fmaf(qr[8 * d + b], static_cast<float>((lo >> (8 * b)) & 0xffu), dot[d]);
+                dot[d] = fmaf(qr[8 * d + 4 + b], static_cast<float>((hi >> (8 * b)) & 0xffu), dot[d]);
+            }
+        }
+        const float s = half_bits_to_float(static_cast<uint16_t>(kp & 0xffffu));
+        const float z = static_cast<float>(static_cast<int>(kp) >> 16);
+        float score = s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum);
+        score = quad_sum(score);
+        if (!valid) score = -INFINITY;
+        if (piece == 0) sc[it * 64 + slot] = score;
+        top = fmaxf(top, score);
+    }
+    top = wave_max(top);
+    if ((tid & 63) == 0) wmax[wave] = top;
+    __syncthreads();
+    const float m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+
+    // ---- pass 2: weights and the value sum ----
+    float acc[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) acc[r] = 0.0f;
+    float lsum = 0.0f, zacc = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+        const int t = t0 + it * 64 + slot;
+        const bool valid = t < t_end;
+        const size_t at = head_base + (valid ? t : t_end - 1);
+        const u32x4 vw = v_codes[at * 4 + piece];
+        const uint32_t vp = v_params[at];
+        const float p = __expf(sc[it * 64 + slot] - m);  // exp(-inf) = 0 for the surplus slots
+        const float w = p * half_bits_to_float(static_cast<uint16_t>(vp & 0xffffu));
+        lsum += p;
+        zacc = fmaf(w, static_cast<float>(static_cast<int>(vp) >> 16), zacc);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = vw[d] & 0x0f0f0f0fu, hi = (vw[d] >> 4) & 0x0f0f0f0fu;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                acc[8 * d + b] = fmaf(w, static_cast<float>((lo >> (8 * b)) & 0xffu), acc[8 * d + b]);
+                acc[8 * d + 4 + b] = fmaf(w, static_cast<float>((hi >> (8 * b)) & 0xffu), acc[8 * d + 4 + b]);
+            }
+        }
+    }
+
+    // ---- the 64 tokens of a workgroup pass are summed: rows of 16 lanes by DPP, the four rows
+    // by two register folds (after which a lane of row w holds registers 4 k + w), the four
+    // wavefronts through LDS ----
+#pragma unroll
+    for (int r = 0; r < 32; ++r) acc[r] = row_tokens_sum(acc[r]);
+    lsum = row_tokens_sum(lsum);
+    zacc = row_tokens_sum(zacc);
+    float f16v[16], f32v[8];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) f16v[k] = fold16f(acc[2 * k], acc[2 * k + 1]);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) f32v[k] = fold32f(f16v[2 * k], f16v[2 * k + 1]);
+    const int rw = (tid >> 4) & 3;
+    if ((tid & 12) == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) red[wave][32 * piece + kv_elem_of_reg(4 * k + rw)] = f32v[k];
+        if (piece == 0) {
+            lrow[wave][rw] = lsum;
+            zrow[wave][rw] = zacc;
+        }
+    }
+    __syncthreads();
+    float* dst = part + (static_cast<size_t>(h) * splits + split) * KV_PART;
+    if (tid < KV_D) {
+        float zs = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) zs += zrow[w][r];
+        dst[tid] = ((red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid])) - zs;
+    } else if (tid == KV_D) {
+        float ls = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ls += lrow[w][r];
+        dst[KV_D] = m;
+        dst[KV_D + 1] = ls;
+    }
+}
+
+// out_hj = sum_i e^(m_i - M) acc_ij / sum_i e^(m_i - M) l_i over the splits i of head h
+template <bool OUT_F16>
+__global__ __launch_bounds__(KV_D) void kv4_combine_kernel(const float* __restrict__ part, int splits, void* __restrict__ out)
+{
+    const int h = blockIdx.x, j = threadIdx.x;
+    const float* src = part + static_cast<size_t>(h) * splits * KV_PART;
+    float M = -INFINITY;
+    for (int i = 0; i < splits; ++i) M = fmaxf(M, src[i * KV_PART + KV_D]);
+    float num = 0.0f, den = 0.0f;
+    for (int i = 0; i < splits; ++i) {
+        const float e = __expf(src[i * KV_PART + KV_D] - M);
+        num = fmaf(e, src[i * KV_PART + j], num);
+        den = fmaf(e, src[i * KV_PART + KV_D + 1], den);
+    }
+    const float r = num / den;
+    if (OUT_F16) static_cast<__half*>(out)[h * KV_D + j] = __float2half_rn(r);
+    else static_cast<float*>(out)[h * KV_D + j] = r;
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+// Tokens per workgroup: a multiple of 64 that gives about two workgroups per compute unit of a
+// 256-unit device, between 64 and KV_MAX_L.
+static int kv4_split_length(int H_q, int S)
+{
+    long long want = (static_cast<long long>(S) * H_q + 511) / 512;
+    int L = static_cast<int>((want + 63) / 64) * 64;
+    if (L < 64) L = 64;
+    if (L > KV_MAX_L) L = KV_MAX_L;
+    return L;
+}
+
+size_t kv4_workspace_bytes(int H_q, int S)
+{
+    const int L = kv4_split_length(H_q, S);
+    const int splits = (S + L - 1) / L;
+    return static_cast<size_t>(H_q) * splits * KV_PART * sizeof(float);
+}
+
+int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, float clip_ratio, void* codes,
+                      void* params, hipStream_t st)
+{
+    const int rows = n_tokens * H;
+    if (rows == 0) return RCP_OK;
+    const unsigned grid = static_cast<unsigned>((rows + 15) / 16);
+    auto* c = static_cast<uint32_t*>(codes);
+    auto* p = static_cast<uint32_t*>(params);
+    if (dt == RCP_F32) kv4_append_kernel<RCP_F32><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);
+    else if (dt == RCP_F16) kv4_append_kernel<RCP_F16><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);
+    else kv4_append_kernel<RCP_BF16><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);
+    return check_launch("rcp_kv4_append");
+}
+
+int launch_kv4_attn(const void* q, rcp_dtype q_dt, int H_q, int H_kv, int S_max, int S, const void* k_codes,
+                    const void* k_params, const void* v_codes, const void* v_params, float softmax_scale, void* out,
+                    rcp_dtype out_dt, void* workspace, hipStream_t st)
+{
+    const int L = kv4_split_length(H_q, S);
+    const int splits = (S + L - 1) / L;
+    const dim3 grid(static_cast<unsigned>(splits), static_cast<unsigned>(H_q));
+    const int rep = H_q / H_kv;
+    auto* kc = static_cast<const u32x4*>(k_codes);
+    auto* vc = static_cast<const u32x4*>(v_codes);
+    auto* kp = static_cast<const uint32_t*>(k_params);
+    auto* vp = static_cast<const uint32_t*>(v_params);
+    auto* part = static_cast<float*>(workspace);
+    if (q_dt == RCP_F32)
+        kv4_attn_kernel<RCP_F32><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, L, rep, splits, softmax_scale, kc, kp, vc, vp, part);
+    else if (q_dt == RCP_F16)
+        kv4_attn_kernel<RCP_F16><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, L, rep, splits, softmax_scale, kc, kp, vc, vp, part);
+    else
+        kv4_attn_kernel<RCP_BF16><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, L, rep, splits, softmax_scale, kc, kp, vc, vp, part);
+    int rc = check_launch("rcp_kv4_attn_decode");
+    if (rc != RCP_OK) return rc;
+    if (out_dt == RCP_F16) kv4_combine_kernel<true><<<H_q, KV_D, 0, st>>>(part, splits, out);
+    else kv4_combine_kernel<false><<<H_q, KV_D, 0, st>>>(part, splits, out);
+    return check_launch("rcp_kv4_attn_decode(combine)");
+}
+
+}  // namespace rcp

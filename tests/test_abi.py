@@ -32,7 +32,8 @@ def test_every_declared_function_is_exported(lib):
             "rcp_set_option", "rcp_quant_w2a4_gemv", "rcp_rotate_act", "rcp_stream_read",
             "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped",
             "rcp_w2a16_gemv", "rcp_quant_w2a4_gemv_grouped", "rcp_w2a4_gemm_grouped",
-            "rcp_rotate_quant_w2a4_gemv", "rcp_pack_weights_w3", "rcp_unpack_indices_w3", "rcp_w3a4_gemv"} <= set(names)
+            "rcp_rotate_quant_w2a4_gemv", "rcp_pack_weights_w3", "rcp_unpack_indices_w3", "rcp_w3a4_gemv",
+            "rcp_kv4_workspace_bytes", "rcp_kv4_append", "rcp_kv4_attn_decode"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -150,6 +151,38 @@ def test_argument_errors_need_no_gpu(lib):
     u3 = lib.rcp_unpack_indices_w3
     u3.argtypes = [vp, ci, ci, vp, vp]
     assert u3(fake, 10, 64, fake, None) == -2
+    # 4-bit KV cache
+    ap = lib.rcp_kv4_append
+    ap.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
+    assert ap(None, 0, 1, 2, 8, 0, 0.95, fake, fake, None) == -1
+    assert ap(fake, 7, 1, 2, 8, 0, 0.95, fake, fake, None) == -4
+    assert ap(fake, 0, 3, 2, 8, 6, 0.95, fake, fake, None) == -2          # runs past S_max
+    assert ap(fake, 0, 1, 2, 8, -1, 0.95, fake, fake, None) == -2
+    assert ap(fake, 0, 1, 0, 8, 0, 0.95, fake, fake, None) == -2
+    assert ap(fake, 0, 1, 2, 8, 0, 0.0, fake, fake, None) == -4
+    assert ap(fake, 0, 1, 2, 8, 0, 1.5, fake, fake, None) == -4
+    assert ap(odd, 0, 1, 2, 8, 0, 0.95, fake, fake, None) == -3
+    kws = lib.rcp_kv4_workspace_bytes
+    kws.restype = ctypes.c_size_t
+    kws.argtypes = [ci, ci]
+    assert kws(0, 10) == 0 and kws(4, 0) == 0 and kws(4, 262145) == 0
+    assert kws(32, 1) == 32 * 132 * 4 and kws(32, 65) == 2 * 32 * 132 * 4
+    assert kws(32, 4096) == 32 * 16 * 132 * 4                          # 256 tokens per workgroup
+    assert kws(1, 262144) == 512 * 132 * 4 and kws(32, 262144) == 32 * 256 * 132 * 4   # 1024 tokens per workgroup at most
+    at = lib.rcp_kv4_attn_decode
+    at.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp, ctypes.c_size_t, vp]
+    big = 1 << 30
+    assert at(fake, 0, 4, 4, 8, 8, fake, fake, fake, None, 0.1, fake, 1, fake, big, None) == -1
+    assert at(fake, 0, 4, 3, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -2
+    assert at(fake, 0, 4, 4, 8, 9, fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -2
+    assert at(fake, 0, 4, 4, 8, 0, fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -2
+    assert at(fake, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 2, fake, big, None) == -4      # bf16 output
+    assert at(fake, 9, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -4
+    assert at(fake, 0, 4, 4, 1 << 19, 1 << 19, fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -4
+    assert at(fake, 0, 4, 4, 8, 8, fake, odd, fake, fake, 0.1, fake, 1, fake, big, None) == -3
+    assert at(fake, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, None, 0, None) == -5
+    assert at(fake, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, 4 * 132 * 4 - 1, None) == -5
+    assert b"workspace" in lib.rcp_last_error()
     ws = lib.rcp_act_workspace_bytes
     ws.restype = ctypes.c_size_t
     ws.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot)]

@@ -1,0 +1,195 @@
+"""GPU-vs-oracle parity of the 4-bit KV cache through the C ABI: codes, step sizes and zero points
+bit-exact, attention outputs within 1e-3 of the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2502_15779_amd as rcp
+import rcp_synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+D = 128
+TOL = 1e-3
+
+
+def _t(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _as_dtype(x16, dtype):
+    """(device tensor, the same values as float32 numpy)."""
+    if dtype == "f16":
+        return _t(x16), x16.astype(np.float32)
+    if dtype == "f32":
+        x32 = x16.astype(np.float32) * np.float32(1.0009765)
+        return _t(x32), x32
+    xb = _t(x16.astype(np.float32)).to(torch.bfloat16)
+    return xb, xb.float().cpu().numpy()
+
+
+def _oracle_cache(x32, S_max, pos=0, clip=0.95):
+    codes, params = oracle.kv4_new_cache(x32.shape[1], S_max)
+    oracle.kv4_append(x32, pos, clip, codes, params)
+    return codes, params
+
+
+@pytest.mark.parametrize("n,H,dtype", [(1, 1, "f16"), (1, 32, "f16"), (3, 5, "f32"), (17, 8, "bf16"), (300, 32, "f16"),
+                                       (64, 3, "f32")])
+def test_append_bit_exact(n, H, dtype):
+    _say(f"kv4 append n={n} H={H} {dtype}")
+    xd, x32 = _as_dtype(rcp_synth.kv_vectors(2, f"app{n}x{H}", n, H), dtype)
+    S_max, pos = n + 7, 4
+    codes, params = rcp.kv4_new_cache(H, S_max, DEV)
+    codes.fill_(0xEE)
+    params.fill_(0x77)
+    rcp.kv4_append(xd, pos, codes, params)
+    torch.cuda.synchronize()
+    rc, rp = oracle.kv4_new_cache(H, S_max)
+    rc[:], rp[:] = 0xEE, 0x77
+    oracle.kv4_append(x32, pos, 0.95, rc, rp)
+    assert np.array_equal(params.cpu().numpy(), rp)
+    assert np.array_equal(codes.cpu().numpy(), rc)
+
+
+def test_append_values_on_rounding_boundaries_and_degenerate_groups():
+    _say("kv4 append boundaries")
+    rng = np.random.default_rng(3)
+    n, H = 40, 4
+    x = np.zeros((n, H, D), dtype=np.float32)
+    for i in range(n):
+        for h in range(H):
+            step = np.float32(2.0 ** rng.integers(-6, 3))
+            base = np.float32(rng.integers(-40, 10)) * step
+            k = rng.integers(0, 16, size=D).astype(np.float32)
+            k[:2] = (0, 15)
+            half = rng.integers(0, 2, size=D).astype(np.float32) * np.float32(0.5)   # exact ties: round half to even
+            half[:2] = 0
+            x[i, h] = base + step * (k + half)
+    x[0, 0] = 0.0                 # zero range
+    x[1, 1] = -7.25               # constant group
+    x[2, 2] = 6.0e4               # large constant
+    x[3, 3, :] = 1e-9             # step underflows in fp16
+    x[3, 3, 5] = -1e-9
+    for clip in (1.0, 0.95, 0.5):
+        codes, params = rcp.kv4_new_cache(H, n, DEV)
+        rcp.kv4_append(_t(x), 0, codes, params, clip_ratio=clip)
+        torch.cuda.synchronize()
+        rc, rp = _oracle_cache(x, n, clip=clip)
+        assert np.array_equal(params.cpu().numpy(), rp)
+        assert np.array_equal(codes.cpu().numpy(), rc)
+
+
+def test_append_token_by_token_equals_one_call():
+    _say("kv4 append incremental")
+    H, n = 8, 21
+    x = _t(rcp_synth.kv_vectors(4, "inc", n, H))
+    c1, p1 = rcp.kv4_new_cache(H, 32, DEV)
+    c2, p2 = rcp.kv4_new_cache(H, 32, DEV)
+    rcp.kv4_append(x, 5, c1, p1)
+    for i in range(n):
+        rcp.kv4_append(x[i:i + 1], 5 + i, c2, p2)
+    rcp.kv4_append(x[:0], 0, c2, p2)          # nothing to append
+    torch.cuda.synchronize()
+    assert torch.equal(c1, c2) and torch.equal(p1, p2)
+
+
+def _build_cache(seed, S, H_kv, S_max):
+    k = rcp_synth.kv_vectors(seed, "k", S, H_kv)
+    v = rcp_synth.kv_vectors(seed, "v", S, H_kv)
+    kc, kp = rcp.kv4_new_cache(H_kv, S_max, DEV)
+    vc, vp = rcp.kv4_new_cache(H_kv, S_max, DEV)
+    rcp.kv4_append(_t(k), 0, kc, kp)
+    rcp.kv4_append(_t(v), 0, vc, vp)
+    torch.cuda.synchronize()
+    return kc, kp, vc, vp
+
+
+def _check_attention(q_dev, q64, S, cache, scale, out_dtype=torch.float32, heads=None):
+    kc, kp, vc, vp = cache
+    out = rcp.kv4_attn_decode(q_dev, S, kc, kp, vc, vp, scale, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    host = [a.cpu().numpy() for a in cache]
+    if heads is None:
+        ref = oracle.kv4_attn_decode(q64, S, *host, scale)
+    else:       # sampled query heads (full-size case)
+        rep = q64.shape[0] // host[0].shape[0]
+        ref = np.stack([oracle.kv4_attn_decode(q64[h:h + 1], S, *[np.ascontiguousarray(a[h // rep:h // rep + 1]) for a in host],
+                                               scale)[0] for h in heads])
+        got = got[heads]
+    tol = TOL if out_dtype == torch.float32 else 2 * TOL
+    bound = tol * (1.0 + np.abs(ref))
+    assert np.all(np.isfinite(got))
+    assert np.all(np.abs(got - ref) <= bound), float(np.max(np.abs(got - ref) / (1.0 + np.abs(ref))))
+
+
+@pytest.mark.parametrize("H_q,H_kv,S,S_max", [(1, 1, 1, 1), (2, 2, 3, 8), (4, 4, 63, 64), (4, 4, 64, 64), (4, 4, 65, 70),
+                                              (8, 8, 257, 300), (32, 32, 700, 1024), (32, 8, 333, 400), (16, 2, 1500, 1500),
+                                              (3, 1, 5000, 5003), (1, 1, 9000, 9000)])
+@pytest.mark.parametrize("q_dtype", ["f16", "f32", "bf16"])
+def test_attention_matches_oracle(H_q, H_kv, S, S_max, q_dtype):
+    if q_dtype != "f16" and S > 1000:
+        pytest.skip("the widened query types are covered at the smaller sizes")
+    _say(f"kv4 attn H_q={H_q} H_kv={H_kv} S={S} S_max={S_max} {q_dtype}")
+    cache = _build_cache(5, S, H_kv, S_max)
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(5, f"q{H_q}", H_q), q_dtype)
+    _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D))
+
+
+def test_attention_reads_only_the_first_S_tokens_and_fp16_output():
+    _say("kv4 attn prefix / fp16 out")
+    H, S_max = 4, 512
+    cache = _build_cache(6, S_max, H, S_max)
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(6, "q", H), "f16")
+    for S in (1, 100, 320, 512):
+        _check_attention(qd, q32.astype(np.float64), S, cache, 0.09)
+    _check_attention(qd, q32.astype(np.float64), 200, cache, 0.09, out_dtype=torch.float16)
+
+
+def test_attention_peaked_and_flat_score_distributions():
+    _say("kv4 attn peaked / flat")
+    H, S = 4, 900
+    cache = _build_cache(7, S, H, S)
+    K = oracle.kv4_dequant(cache[0].cpu().numpy(), cache[1].cpu().numpy(), 0, S)
+    # a query along one key: scores of several hundred, one weight near 1
+    q = (3.0 * K[123]).astype(np.float16)
+    _check_attention(_t(q), q.astype(np.float64), S, cache, 1.0)
+    # zero query: uniform weights
+    z = np.zeros((H, D), dtype=np.float16)
+    _check_attention(_t(z), z.astype(np.float64), S, cache, 1.0)
+    # large negative and positive scores in different splits
+    q = (-2.0 * K[800]).astype(np.float16)
+    _check_attention(_t(q), q.astype(np.float64), S, cache, 1.0)
+
+
+def test_attention_full_size_sampled_heads():
+    # LLaMA-2-7B: 32 heads of 128, 4096 cached tokens; the oracle checks four of the 32 heads
+    _say("kv4 attn full size")
+    H, S = 32, 4096
+    cache = _build_cache(8, S, H, S)
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(8, "q", H), "f16")
+    _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D), heads=[0, 7, 18, 31])
+
+
+def test_workspace_is_reusable_and_too_small_is_refused():
+    _say("kv4 attn workspace")
+    H, S = 4, 300
+    cache = _build_cache(9, S, H, S)
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(9, "q", H), "f16")
+    need = rcp.kv4_workspace_bytes(H, S)
+    ws = torch.full((need,), 0xFF, dtype=torch.uint8, device=DEV)     # NaN bit patterns: nothing may be read before written
+    a = rcp.kv4_attn_decode(qd, S, *cache, 0.1, workspace=ws)
+    b = rcp.kv4_attn_decode(qd, 40, *cache, 0.1, workspace=ws)
+    c = rcp.kv4_attn_decode(qd, S, *cache, 0.1, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, c) and torch.isfinite(b).all()
+    with pytest.raises(rcp.RcpError):
+        rcp.kv4_attn_decode(qd, S, *cache, 0.1, workspace=ws[:need - 16])
+    with pytest.raises(rcp.RcpError):
+        rcp.kv4_attn_decode(qd, S + 1, *cache, 0.1)
