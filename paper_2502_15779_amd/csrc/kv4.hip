@@ -75,9 +75,9 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict_
 
 // ---------------------------------------------------------------------------------------
 // one-token attention, split along the sequence.
-// Workgroup (split, query head): L cached tokens.  Four lanes own a token, 16 bytes (32
+// Workgroup (split, query head): L = 64, 128 or 256 cached tokens.  Four lanes own a token, 16 bytes (32
 // elements) of its vector each; a wavefront covers 16 tokens per load, the workgroup 64.
-//   pass 1  scores q . K_t into LDS, their maximum m
+//   pass 1  scores q . K_t (kept in registers), their maximum m
 //   pass 2  p_t = exp(score_t - m), l = sum p_t, acc_j = sum_t p_t * V_tj
 // and (m, l, acc) go to the workspace; kv4_combine_kernel merges the splits.
 // With x_tj = s_t * (c_tj - z_t):  q . K_t = s_t * (sum_j q_j c_tj - z_t * sum_j q_j)  and
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict_
 // the 16 bytes, byte b, nibble e): the order in which the nibbles come out of two masks.
 // ---------------------------------------------------------------------------------------
 constexpr int KV_THREADS = 256;
-constexpr int KV_MAX_L = 1024;         // tokens per workgroup at most (scores held in LDS)
+constexpr int KV_MAX_L = 256;          // tokens per workgroup at most: four per lane group, all loads in flight at once
 constexpr int KV_PART = KV_D + 4;      // floats per partial result: acc[128], m, l, 2 unused
 
 __device__ __forceinline__ int kv_elem_of_reg(int r) { return 8 * (r >> 3) + 2 * (r & 3) + ((r >> 2) & 1); }
@@ -107,24 +107,46 @@ __device__ __forceinline__ float row_tokens_sum(float v)
     return v;
 }
 
-template <int QDT>
-__global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __restrict__ q, int S, int S_max, int L, int rep,
-                                                              int splits, float softmax_scale,
-                                                              const u32x4* __restrict__ k_codes,
+template <int QDT, int ITERS>
+__global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __restrict__ q, int S, int S_max, int rep, int splits,
+                                                              float softmax_scale, const u32x4* __restrict__ k_codes,
                                                               const uint32_t* __restrict__ k_params,
                                                               const u32x4* __restrict__ v_codes,
                                                               const uint32_t* __restrict__ v_params,
                                                               float* __restrict__ part)
 {
-    __shared__ float sc[KV_MAX_L];
     __shared__ float red[4][KV_D];
     __shared__ float wmax[4], lrow[4][4], zrow[4][4];
+    constexpr int L = 64 * ITERS;
     const int split = blockIdx.x, h = blockIdx.y, hk = h / rep;
     const int tid = threadIdx.x, slot = tid >> 2, piece = tid & 3, wave = tid >> 6;
     const int t0 = split * L;
     const int t_end = min(S, t0 + L);
-    const int iters = (t_end - t0 + 63) >> 6;
     const size_t head_base = static_cast<size_t>(hk) * S_max;
+
+    // every load of the workgroup is issued before the first use: the query, then the keys,
+    // then the values (slots past the end repeat the last token and get weight 0)
+    Raw8<QDT> qraw[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) qraw[d] = load8_raw<QDT>(q, static_cast<size_t>(h) * KV_D + 32 * piece + 8 * d);
+    u32x4 kw[ITERS], vw[ITERS];
+    uint32_t kp[ITERS], vp[ITERS];
+    bool valid[ITERS];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int t = t0 + it * 64 + slot;
+        valid[it] = t < t_end;
+        const size_t at = head_base + (valid[it] ? t : t_end - 1);
+        kw[it] = k_codes[at * 4 + piece];
+        kp[it] = k_params[at];
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int t = t0 + it * 64 + slot;
+        const size_t at = head_base + (valid[it] ? t : t_end - 1);
+        vw[it] = v_codes[at * 4 + piece];
+        vp[it] = v_params[at];
+    }
 
     // this lane's 32 query values, times the softmax scale, in register order
     float qr[32];
@@ -132,7 +154,7 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
         float t8[8];
-        load8_as_float<QDT>(q, static_cast<size_t>(h) * KV_D + 32 * piece + 8 * d, t8);
+        widen8<QDT>(qraw[d], t8);
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -142,31 +164,27 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
             }
     }
 
-    // ---- pass 1: scores ----
+    // ---- pass 1: scores (all four lanes of a token end up holding its score) ----
+    float score[ITERS];
     float top = -INFINITY;
-    for (int it = 0; it < iters; ++it) {
-        const int t = t0 + it * 64 + slot;
-        const bool valid = t < t_end;
-        const size_t at = head_base + (valid ? t : t_end - 1);
-        const u32x4 kw = k_codes[at * 4 + piece];
-        const uint32_t kp = k_params[at];
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
         float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
-            const uint32_t lo = kw[d] & 0x0f0f0f0fu, hi = (kw[d] >> 4) & 0x0f0f0f0fu;
+            const uint32_t lo = kw[it][d] & 0x0f0f0f0fu, hi = (kw[it][d] >> 4) & 0x0f0f0f0fu;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 dot[d] = fmaf(qr[8 * d + b], static_cast<float>((lo >> (8 * b)) & 0xffu), dot[d]);
                 dot[d] = fmaf(qr[8 * d + 4 + b], static_cast<float>((hi >> (8 * b)) & 0xffu), dot[d]);
             }
         }
-        const float s = half_bits_to_float(static_cast<uint16_t>(kp & 0xffffu));
-        const float z = static_cast<float>(static_cast<int>(kp) >> 16);
-        float score = s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum);
-        score = quad_sum(score);
-        if (!valid) score = -INFINITY;
-        if (piece == 0) sc[it * 64 + slot] = score;
-        top = fmaxf(top, score);
+        const float s = half_bits_to_float(static_cast<uint16_t>(kp[it] & 0xffffu));
+        const float z = static_cast<float>(static_cast<int>(kp[it]) >> 16);
+        float sc = s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum);
+        sc = quad_sum(sc);
+        score[it] = valid[it] ? sc : -INFINITY;
+        top = fmaxf(top, score[it]);
     }
     top = wave_max(top);
     if ((tid & 63) == 0) wmax[wave] = top;
@@ -178,19 +196,15 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
 #pragma unroll
     for (int r = 0; r < 32; ++r) acc[r] = 0.0f;
     float lsum = 0.0f, zacc = 0.0f;
-    for (int it = 0; it < iters; ++it) {
-        const int t = t0 + it * 64 + slot;
-        const bool valid = t < t_end;
-        const size_t at = head_base + (valid ? t : t_end - 1);
-        const u32x4 vw = v_codes[at * 4 + piece];
-        const uint32_t vp = v_params[at];
-        const float p = __expf(sc[it * 64 + slot] - m);  // exp(-inf) = 0 for the surplus slots
-        const float w = p * half_bits_to_float(static_cast<uint16_t>(vp & 0xffffu));
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const float p = __expf(score[it] - m);  // exp(-inf) = 0 for the surplus slots
+        const float w = p * half_bits_to_float(static_cast<uint16_t>(vp[it] & 0xffffu));
         lsum += p;
-        zacc = fmaf(w, static_cast<float>(static_cast<int>(vp) >> 16), zacc);
+        zacc = fmaf(w, static_cast<float>(static_cast<int>(vp[it]) >> 16), zacc);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
-            const uint32_t lo = vw[d] & 0x0f0f0f0fu, hi = (vw[d] >> 4) & 0x0f0f0f0fu;
+            const uint32_t lo = vw[it][d] & 0x0f0f0f0fu, hi = (vw[it][d] >> 4) & 0x0f0f0f0fu;
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 acc[8 * d + b] = fmaf(w, static_cast<float>((lo >> (8 * b)) & 0xffu), acc[8 * d + b]);
@@ -240,37 +254,71 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
     }
 }
 
-// out_hj = sum_i e^(m_i - M) acc_ij / sum_i e^(m_i - M) l_i over the splits i of head h
+// out_hj = sum_i e^(m_i - M) acc_ij / sum_i e^(m_i - M) l_i over the splits i of head h.
+// One workgroup per head: thread (g, j) sums the splits i = g, g + 8, ... of column j, four
+// at a time so that their loads are in flight together; the eight groups meet in LDS.
+constexpr int KV_CT = 1024;
+
 template <bool OUT_F16>
-__global__ __launch_bounds__(KV_D) void kv4_combine_kernel(const float* __restrict__ part, int splits, void* __restrict__ out)
+__global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restrict__ part, int splits, void* __restrict__ out)
 {
-    const int h = blockIdx.x, j = threadIdx.x;
+    __shared__ float red[8][KV_D];
+    __shared__ float dred[8], wm[KV_CT / 64];
+    const int h = blockIdx.x, tid = threadIdx.x, j = tid & (KV_D - 1), g = tid >> 7;
     const float* src = part + static_cast<size_t>(h) * splits * KV_PART;
     float M = -INFINITY;
-    for (int i = 0; i < splits; ++i) M = fmaxf(M, src[i * KV_PART + KV_D]);
+    for (int i = tid; i < splits; i += KV_CT) M = fmaxf(M, src[i * KV_PART + KV_D]);
+    M = wave_max(M);
+    if ((tid & 63) == 0) wm[tid >> 6] = M;
+    __syncthreads();
+    M = wm[0];
+#pragma unroll
+    for (int w = 1; w < KV_CT / 64; ++w) M = fmaxf(M, wm[w]);
+
     float num = 0.0f, den = 0.0f;
-    for (int i = 0; i < splits; ++i) {
-        const float e = __expf(src[i * KV_PART + KV_D] - M);
-        num = fmaf(e, src[i * KV_PART + j], num);
-        den = fmaf(e, src[i * KV_PART + KV_D + 1], den);
+    for (int i0 = g; i0 < splits; i0 += 32) {
+        float mi[4], li[4], ai[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = min(i0 + 8 * u, splits - 1);
+            mi[u] = src[i * KV_PART + KV_D];
+            li[u] = src[i * KV_PART + KV_D + 1];
+            ai[u] = src[i * KV_PART + j];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float e = (i0 + 8 * u < splits) ? __expf(mi[u] - M) : 0.0f;
+            num = fmaf(e, ai[u], num);
+            den = fmaf(e, li[u], den);
+        }
     }
-    const float r = num / den;
-    if (OUT_F16) static_cast<__half*>(out)[h * KV_D + j] = __float2half_rn(r);
-    else static_cast<float*>(out)[h * KV_D + j] = r;
+    red[g][j] = num;
+    if (j == 0) dred[g] = den;
+    __syncthreads();
+    if (tid < KV_D) {
+        float n = 0.0f, d = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            n += red[w][tid];
+            d += dred[w];
+        }
+        const float r = n / d;
+        if (OUT_F16) static_cast<__half*>(out)[h * KV_D + tid] = __float2half_rn(r);
+        else static_cast<float*>(out)[h * KV_D + tid] = r;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-// Tokens per workgroup: a multiple of 64 that gives about two workgroups per compute unit of a
-// 256-unit device, between 64 and KV_MAX_L.
+// Tokens per workgroup: 64, 128 or 256, the smallest that leaves at most about two workgroups
+// per compute unit of a 256-unit device.
 static int kv4_split_length(int H_q, int S)
 {
-    long long want = (static_cast<long long>(S) * H_q + 511) / 512;
-    int L = static_cast<int>((want + 63) / 64) * 64;
-    if (L < 64) L = 64;
-    if (L > KV_MAX_L) L = KV_MAX_L;
-    return L;
+    const long long want = (static_cast<long long>(S) * H_q + 511) / 512;
+    if (want <= 64) return 64;
+    if (want <= 128) return 128;
+    return KV_MAX_L;
 }
 
 size_t kv4_workspace_bytes(int H_q, int S)
@@ -307,16 +355,23 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int H_q, int H_kv, int S_max,
     auto* kp = static_cast<const uint32_t*>(k_params);
     auto* vp = static_cast<const uint32_t*>(v_params);
     auto* part = static_cast<float*>(workspace);
-    if (q_dt == RCP_F32)
-        kv4_attn_kernel<RCP_F32><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, L, rep, splits, softmax_scale, kc, kp, vc, vp, part);
-    else if (q_dt == RCP_F16)
-        kv4_attn_kernel<RCP_F16><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, L, rep, splits, softmax_scale, kc, kp, vc, vp, part);
-    else
-        kv4_attn_kernel<RCP_BF16><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, L, rep, splits, softmax_scale, kc, kp, vc, vp, part);
+#define RCP_KV_LAUNCH(QDT, ITERS) \
+    kv4_attn_kernel<QDT, ITERS><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, rep, splits, softmax_scale, kc, kp, vc, vp, part)
+#define RCP_KV_DISPATCH(QDT)             \
+    do {                                 \
+        if (L == 64) RCP_KV_LAUNCH(QDT, 1);       \
+        else if (L == 128) RCP_KV_LAUNCH(QDT, 2); \
+        else RCP_KV_LAUNCH(QDT, 4);      \
+    } while (0)
+    if (q_dt == RCP_F32) RCP_KV_DISPATCH(RCP_F32);
+    else if (q_dt == RCP_F16) RCP_KV_DISPATCH(RCP_F16);
+    else RCP_KV_DISPATCH(RCP_BF16);
+#undef RCP_KV_DISPATCH
+#undef RCP_KV_LAUNCH
     int rc = check_launch("rcp_kv4_attn_decode");
     if (rc != RCP_OK) return rc;
-    if (out_dt == RCP_F16) kv4_combine_kernel<true><<<H_q, KV_D, 0, st>>>(part, splits, out);
-    else kv4_combine_kernel<false><<<H_q, KV_D, 0, st>>>(part, splits, out);
+    if (out_dt == RCP_F16) kv4_combine_kernel<true><<<H_q, KV_CT, 0, st>>>(part, splits, out);
+    else kv4_combine_kernel<false><<<H_q, KV_CT, 0, st>>>(part, splits, out);
     return check_launch("rcp_kv4_attn_decode(combine)");
 }
 

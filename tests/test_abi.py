@@ -168,7 +168,7 @@ def test_argument_errors_need_no_gpu(lib):
     assert kws(0, 10) == 0 and kws(4, 0) == 0 and kws(4, 262145) == 0
     assert kws(32, 1) == 32 * 132 * 4 and kws(32, 65) == 2 * 32 * 132 * 4
     assert kws(32, 4096) == 32 * 16 * 132 * 4                          # 256 tokens per workgroup
-    assert kws(1, 262144) == 512 * 132 * 4 and kws(32, 262144) == 32 * 256 * 132 * 4   # 1024 tokens per workgroup at most
+    assert kws(1, 262144) == 1024 * 132 * 4 and kws(32, 262144) == 32 * 1024 * 132 * 4   # 256 tokens per workgroup at most
     at = lib.rcp_kv4_attn_decode
     at.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp, ctypes.c_size_t, vp]
     big = 1 << 30
