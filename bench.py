@@ -489,6 +489,42 @@ def main():
         w3[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1)}
         del w3sets
 
+    # 4-bit KV cache, one query token (LLaMA-2-7B: 32 heads of 128), cold over L layers' caches.  One layer's
+    # keys and values are drawn and quantised by the library, then copied into L separate caches.
+    kv4 = {}
+    Hh = 32
+    for S in (1024, 4096):
+        kx = torch.from_numpy(rcp_synth.kv_vectors(args.seed, f"bench_k{S}", S, Hh)).to(dev)
+        vx = torch.from_numpy(rcp_synth.kv_vectors(args.seed, f"bench_v{S}", S, Hh)).to(dev)
+        kc0, kp0 = rcp.kv4_new_cache(Hh, S, dev)
+        vc0, vp0 = rcp.kv4_new_cache(Hh, S, dev)
+        rcp.kv4_append(kx, 0, kc0, kp0)
+        rcp.kv4_append(vx, 0, vc0, vp0)
+        kcaches = [(kc0.clone(), kp0.clone(), vc0.clone(), vp0.clone()) for _ in range(L)]
+        qv = torch.from_numpy(rcp_synth.query_vectors(args.seed, "bench_q", Hh)).to(dev)
+        ov = torch.empty((Hh, 128), dtype=torch.float32, device=dev)
+        wsk = torch.empty(rcp.kv4_workspace_bytes(Hh, S), dtype=torch.uint8, device=dev)
+
+        def ksweep(S=S, kcaches=kcaches, qv=qv, ov=ov, wsk=wsk):
+            for c in kcaches:
+                rcp.kv4_attn_decode(qv, S, *c, 0.08838834764831845, out=ov, workspace=wsk)
+        ksweep()
+        fn = capture(ksweep)
+        fn()
+        s = timed(torch, fn, reps) / L
+        b = 2 * S * Hh * 68 + Hh * 128 * (2 + 4)
+
+        def asweep_kv(kx=kx, kcaches=kcaches, S=S):
+            for c in kcaches:
+                rcp.kv4_append(kx[:1], S - 1, c[0], c[1])
+        asweep_kv()
+        fn = capture(asweep_kv)
+        fn()
+        sa = timed(torch, fn, reps) / L
+        kv4[f"S{S}"] = {"attn_us": round(s * 1e6, 3), "attn_GBps": round(b / s / 1e9, 1),
+                        "append_one_token_us": round(sa * 1e6, 3)}
+        del kcaches
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
     if os.path.exists(tpath):
@@ -526,6 +562,7 @@ def main():
         "grouped_128_step": grouped_step,
         "weight_only_fp16": weight_only,
         "w3a4": w3,
+        "kv4_attention_32_heads": kv4,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),

@@ -145,6 +145,7 @@ int rcp_version(void);
  *   "gemv_variant" 1 = plain-ALU kernel for every M, 2 = matrix-core kernel for every M
  *   "gemm_waves"   wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
  *   "gemm_rows"    output rows per workgroup of the matrix-core kernel: 16, 64
+ *   "kv_tokens"    cached tokens per workgroup of rcp_kv4_attn_decode: 64, 128, 256
  *   "gemv_waves"   wavefronts per workgroup of the fused one-token GEMV (rcp_quant_w2a4_gemv): 4, 8
  *                  (8 needs K >= 2048 and "gemv_lanes" left automatic; otherwise 4 is used)
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */
@@ -381,7 +382,7 @@ int rcp_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
  *     out[h] = sum_t softmax_t(softmax_scale * q[h] . K[g][t]) * V[g][t],   g = h / (H_q / H_kv)
  *   q: [H_q][128] of `q_dtype`; out: [H_q][128] of `out_dtype` (RCP_F16 or RCP_F32); H_q a multiple of
  *   H_kv.  Sums are binary32.  workspace: rcp_kv4_workspace_bytes(H_q, S) bytes of device memory
- *   (RCP_ERR_WORKSPACE when missing or smaller), overwritten by every call.  S above
+ *   (RCP_ERR_WORKSPACE when missing or smaller; the size covers every "kv_tokens" setting), overwritten by every call.  S above
  *   RCP_KV_MAX_S returns RCP_ERR_UNSUPPORTED.
  */
 #define RCP_KV_HEAD_DIM 128

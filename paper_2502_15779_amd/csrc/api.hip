@@ -28,7 +28,7 @@ int check_launch(const char* what)
 
 Options& options()
 {
-    static Options o = {0, 0, 0, 0, 0, 0, 0};
+    static Options o = {0, 0, 0, 0, 0, 0, 0, 0};
     return o;
 }
 
@@ -146,6 +146,10 @@ int rcp_set_option(const char* name, int value)
         if (value != 0 && value != 16 && value != 64)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_rows must be 0, 16 or 64");
         o.gemm_rows = value;
+    } else if (strcmp(name, "kv_tokens") == 0) {
+        if (value != 0 && value != 64 && value != 128 && value != 256)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: kv_tokens must be 0, 64, 128 or 256");
+        o.kv_tokens = value;
     } else if (strcmp(name, "gemv_waves") == 0) {
         if (value != 0 && value != 4 && value != 8)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_waves must be 0, 4 or 8");

@@ -24,6 +24,7 @@ struct Options {
     int gemm_waves;      // wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
     int gemv_waves;      // wavefronts per workgroup of the fused one-token GEMV: 4 or 8
     int gemm_rows;       // output rows per workgroup of the matrix-core kernel: 16 or 64
+    int kv_tokens;       // cached tokens per workgroup of the KV4 attention kernel: 64, 128 or 256
 };
 Options& options();
 int num_compute_units();

@@ -116,6 +116,8 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.rcp_set_option(b"gemm_waves", 3) == -4
     assert lib.rcp_set_option(b"gemm_waves", 8) == 0 and lib.rcp_set_option(b"gemm_waves", 0) == 0
     assert lib.rcp_set_option(b"gemv_variant", 3) == -4
+    assert lib.rcp_set_option(b"kv_tokens", 96) == -4
+    assert lib.rcp_set_option(b"kv_tokens", 128) == 0 and lib.rcp_set_option(b"kv_tokens", 0) == 0
     assert lib.rcp_set_option(b"gemm_rows", 32) == -4
     assert lib.rcp_set_option(b"gemm_rows", 16) == 0 and lib.rcp_set_option(b"gemm_rows", 0) == 0
     assert lib.rcp_set_option(b"gemv_waves", 2) == -4
@@ -167,8 +169,8 @@ def test_argument_errors_need_no_gpu(lib):
     kws.argtypes = [ci, ci]
     assert kws(0, 10) == 0 and kws(4, 0) == 0 and kws(4, 262145) == 0
     assert kws(32, 1) == 32 * 132 * 4 and kws(32, 65) == 2 * 32 * 132 * 4
-    assert kws(32, 4096) == 32 * 16 * 132 * 4                          # 256 tokens per workgroup
-    assert kws(1, 262144) == 1024 * 132 * 4 and kws(32, 262144) == 32 * 1024 * 132 * 4   # 256 tokens per workgroup at most
+    assert kws(32, 4096) == 32 * 64 * 132 * 4                          # sized for 64 tokens per workgroup
+    assert kws(1, 262144) == 4096 * 132 * 4
     at = lib.rcp_kv4_attn_decode
     at.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp, ctypes.c_size_t, vp]
     big = 1 << 30

@@ -22,6 +22,12 @@ def _say(msg):
     print(msg, flush=True)
 
 
+@pytest.fixture(autouse=True)
+def _auto_options():
+    yield
+    rcp.set_option("kv_tokens", 0)
+
+
 def _as_dtype(x16, dtype):
     """(device tensor, the same values as float32 numpy)."""
     if dtype == "f16":
@@ -139,6 +145,16 @@ def test_attention_matches_oracle(H_q, H_kv, S, S_max, q_dtype):
     _say(f"kv4 attn H_q={H_q} H_kv={H_kv} S={S} S_max={S_max} {q_dtype}")
     cache = _build_cache(5, S, H_kv, S_max)
     qd, q32 = _as_dtype(rcp_synth.query_vectors(5, f"q{H_q}", H_q), q_dtype)
+    _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D))
+
+
+@pytest.mark.parametrize("tokens", [64, 128, 256])
+@pytest.mark.parametrize("H_q,H_kv,S", [(4, 4, 1), (4, 2, 130), (8, 8, 1000), (2, 1, 3333)])
+def test_attention_every_split_length(tokens, H_q, H_kv, S):
+    _say(f"kv4 attn tokens/workgroup={tokens} H_q={H_q} H_kv={H_kv} S={S}")
+    cache = _build_cache(11, S, H_kv, S + 3)
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(11, f"q{H_q}", H_q), "f16")
+    rcp.set_option("kv_tokens", tokens)
     _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D))
 
 
