@@ -159,7 +159,7 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
         vp[it] = v_params[at];
     }
 
-    // this lane's 32 query values, times the softmax scale, in register order
+    // this lane's 32 query values in register order (the softmax scale goes onto the score)
     float qr[32];
     float qsum = 0.0f;
 #pragma unroll
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
-                qr[8 * d + 4 * e + b] = t8[2 * b + e] * softmax_scale;
+                qr[8 * d + 4 * e + b] = t8[2 * b + e];
                 qsum += qr[8 * d + 4 * e + b];
             }
     }
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
                 dot[d] = fmaf(qr[8 * d + 4 + b], static_cast<float>((hi >> (8 * b)) & 0xffu), dot[d]);
             }
         }
-        const float s = half_bits_to_float(static_cast<uint16_t>(kp[it] & 0xffffu));
+        const float s = half_bits_to_float(static_cast<uint16_t>(kp[it] & 0xffffu)) * softmax_scale;
         const float z = static_cast<float>(static_cast<int>(kp[it]) >> 16);
         float sc = s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum);
         sc = quad_sum(sc);
@@ -268,52 +268,58 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
 }
 
 // out_hj = sum_i e^(m_i - M) acc_ij / sum_i e^(m_i - M) l_i over the splits i of head h.
-// One workgroup per head: thread (g, j) sums the splits i = g, g + 8, ... of column j, four
-// at a time so that their loads are in flight together; the eight groups meet in LDS.
+// One workgroup of `groups` x 128 threads per head: thread (g, j) merges the splits
+// i = g, g + groups, ... of column j, four at a time so that their loads are in flight together,
+// against its own running maximum; the groups meet in LDS and are merged the same way.
 constexpr int KV_CT = 1024;
 
 template <bool OUT_F16>
-__global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restrict__ part, int splits, void* __restrict__ out)
+__global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restrict__ part, int splits, int groups,
+                                                            void* __restrict__ out)
 {
-    __shared__ float red[8][KV_D];
-    __shared__ float dred[8], wm[KV_CT / 64];
+    __shared__ float red[KV_CT / KV_D][KV_D];
+    __shared__ float dred[KV_CT / KV_D], mred[KV_CT / KV_D];
     const int h = blockIdx.x, tid = threadIdx.x, j = tid & (KV_D - 1), g = tid >> 7;
     const float* src = part + static_cast<size_t>(h) * splits * KV_PART;
-    float M = -INFINITY;
-    for (int i = tid; i < splits; i += KV_CT) M = fmaxf(M, src[i * KV_PART + KV_D]);
-    M = wave_max(M);
-    if ((tid & 63) == 0) wm[tid >> 6] = M;
-    __syncthreads();
-    M = wm[0];
-#pragma unroll
-    for (int w = 1; w < KV_CT / 64; ++w) M = fmaxf(M, wm[w]);
-
-    float num = 0.0f, den = 0.0f;
-    for (int i0 = g; i0 < splits; i0 += 32) {
+    float M = -INFINITY, num = 0.0f, den = 0.0f;
+    for (int i0 = g; i0 < splits; i0 += 4 * groups) {
         float mi[4], li[4], ai[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int i = min(i0 + 8 * u, splits - 1);
+            const int i = min(i0 + groups * u, splits - 1);
             mi[u] = src[i * KV_PART + KV_D];
             li[u] = src[i * KV_PART + KV_D + 1];
             ai[u] = src[i * KV_PART + j];
         }
+        float mb = M;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + groups * u < splits) mb = fmaxf(mb, mi[u]);
+        const float r = __expf(M - mb);  // 0 on the first round (M = -inf, mb finite)
+        num *= r;
+        den *= r;
+        M = mb;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float e = (i0 + 8 * u < splits) ? __expf(mi[u] - M) : 0.0f;
+            const float e = (i0 + groups * u < splits) ? __expf(mi[u] - M) : 0.0f;
             num = fmaf(e, ai[u], num);
             den = fmaf(e, li[u], den);
         }
     }
-    red[g][j] = num;
-    if (j == 0) dred[g] = den;
+    red[g][j] = num;  // a group without a split leaves M = -inf, num = den = 0
+    if (j == 0) {
+        dred[g] = den;
+        mred[g] = M;
+    }
     __syncthreads();
     if (tid < KV_D) {
+        float Mt = mred[0];
+        for (int w = 1; w < groups; ++w) Mt = fmaxf(Mt, mred[w]);
         float n = 0.0f, d = 0.0f;
-#pragma unroll
-        for (int w = 0; w < 8; ++w) {
-            n += red[w][tid];
-            d += dred[w];
+        for (int w = 0; w < groups; ++w) {
+            const float e = __expf(mred[w] - Mt);
+            n = fmaf(e, red[w][tid], n);
+            d = fmaf(e, dred[w], d);
         }
         const float r = n / d;
         if (OUT_F16) static_cast<__half*>(out)[h * KV_D + tid] = __float2half_rn(r);
@@ -380,8 +386,10 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int H_q, int H_kv, int S_max,
 #undef RCP_KV_LAUNCH
     int rc = check_launch("rcp_kv4_attn_decode");
     if (rc != RCP_OK) return rc;
-    if (out_dt == RCP_F16) kv4_combine_kernel<true><<<H_q, KV_CT, 0, st>>>(part, splits, out);
-    else kv4_combine_kernel<false><<<H_q, KV_CT, 0, st>>>(part, splits, out);
+    int groups = (splits + 3) / 4;
+    if (groups > KV_CT / KV_D) groups = KV_CT / KV_D;
+    if (out_dt == RCP_F16) kv4_combine_kernel<true><<<H_q, groups * KV_D, 0, st>>>(part, splits, groups, out);
+    else kv4_combine_kernel<false><<<H_q, groups * KV_D, 0, st>>>(part, splits, groups, out);
     return check_launch("rcp_kv4_attn_decode(combine)");
 }
 
