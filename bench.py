@@ -493,7 +493,7 @@ def main():
     # keys and values are drawn and quantised by the library, then copied into L separate caches.
     kv4 = {}
     Hh = 32
-    for S in (1024, 4096):
+    for S in (() if args.step_only else (1024, 4096)):
         kx = torch.from_numpy(rcp_synth.kv_vectors(args.seed, f"bench_k{S}", S, Hh)).to(dev)
         vx = torch.from_numpy(rcp_synth.kv_vectors(args.seed, f"bench_v{S}", S, Hh)).to(dev)
         kc0, kp0 = rcp.kv4_new_cache(Hh, S, dev)
