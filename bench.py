@@ -422,7 +422,7 @@ def main():
         del gl
 
     # activation preparation alone (latency-bound: microseconds only): rotation + int4 quantiser
-    # as one call, one token, at the rotation sizes of the BASELINE configs
+    # as one call, one token, at the rotation sizes of the benchmark configurations
     act_us = {}
     if not args.step_only:
         cases = [("quant_only_4096", 4096, None), ("wht_512", 512, ("wht", 512, 1)), ("wht_2048", 2048, ("wht", 2048, 1)),

@@ -359,6 +359,16 @@ int rcp_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
                   const void* xq, const void* scale,
                   void* out, rcp_dtype out_dtype,
                   int32_t* partial_sums_or_null, void* stream);
+/* rcp_quant_w3a4_gemv: the per-token int4 quantiser of rcp_rotate_quant_act (no rotation; Appendix table of
+ * quantisation configurations) fused into the prologue of rcp_w3a4_gemv: one launch instead of two, results
+ * bit-identical to the two calls.  x: one token of K values of `x_dtype` (for a rotated input, the fp32 output
+ * of rcp_rotate_act).  clip_ratio in (0, 1] (RCP_ERR_UNSUPPORTED otherwise).  xq_out_or_null (K/2 bytes) and
+ * scale_out_or_null (fp16 [1]) receive x_q and S when given.  Other arguments as for rcp_w3a4_gemv. */
+int rcp_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
+                        const void* x, rcp_dtype x_dtype, float clip_ratio,
+                        void* out, rcp_dtype out_dtype,
+                        void* xq_out_or_null, void* scale_out_or_null,
+                        int32_t* partial_sums_or_null, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * 4-bit KV cache and one-token attention over it.  Appendix, table of quantisation

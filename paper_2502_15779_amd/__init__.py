@@ -121,6 +121,8 @@ def lib():
         L.rcp_unpack_indices_w3.argtypes = [vp, ci, ci, vp, vp]
         L.rcp_w3a4_gemv.restype = ci
         L.rcp_w3a4_gemv.argtypes = [vp, vp, ci, ci, vp, vp, vp, ci, vp, vp]
+        L.rcp_quant_w3a4_gemv.restype = ci
+        L.rcp_quant_w3a4_gemv.argtypes = [vp, vp, ci, ci, vp, ci, ctypes.c_float, vp, ci, vp, vp, vp, vp]
         L.rcp_kv4_workspace_bytes.restype = ctypes.c_size_t
         L.rcp_kv4_workspace_bytes.argtypes = [ci, ci]
         L.rcp_kv4_append.restype = ci
@@ -484,6 +486,31 @@ def w3a4_gemv(packed, codebook, N, K, xq, scale, out=None, out_dtype=torch.float
     _check(lib().rcp_w3a4_gemv(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, _dev(xq, "xq"),
                                _dev(scale, "scale"), _dev(out, "out"), _DTYPES[out.dtype],
                                _dev(partial_sums, "partial_sums") if partial_sums is not None else None, _stream()))
+    return (out, partial_sums) if partial_sums is not None else out
+
+
+def quant_w3a4_gemv(packed, codebook, N, K, x, clip_ratio=1.0, out=None, out_dtype=torch.float16, xq_out=None,
+                    scale_out=None, partial_sums=None, want_partial_sums=False):
+    """One token, 3-bit weights: quantise x (no rotation) and run the eight-level GEMV in a single launch."""
+    if x.numel() != K or x.dtype not in _DTYPES:
+        raise ValueError("x must hold K values of float16, bfloat16 or float32")
+    if out is None:
+        out = torch.empty((1, N), dtype=out_dtype, device=packed.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < N:
+        raise ValueError("out must be float16 or float32 with N elements")
+    if want_partial_sums and partial_sums is None:
+        partial_sums = torch.empty((N, 8), dtype=torch.int32, device=packed.device)
+    if packed.numel() * packed.element_size() < 3 * N * K // 8 or codebook.numel() < 8 * N:
+        raise ValueError("packed / codebook buffers do not match N, K")
+    if xq_out is not None and xq_out.numel() * xq_out.element_size() < K // 2:
+        raise ValueError("xq_out too small")
+    if partial_sums is not None and (partial_sums.dtype != torch.int32 or partial_sums.numel() < 8 * N):
+        raise ValueError("partial_sums must be int32 [N, 8]")
+    opt = lambda t, name: _dev(t, name) if t is not None else None
+    _check(lib().rcp_quant_w3a4_gemv(_dev(packed, "packed"), _dev(codebook, "codebook"), N, K, _dev(x, "x"),
+                                     _DTYPES[x.dtype], ctypes.c_float(clip_ratio), _dev(out, "out"), _DTYPES[out.dtype],
+                                     opt(xq_out, "xq_out"), opt(scale_out, "scale_out"), opt(partial_sums, "partial_sums"),
+                                     _stream()))
     return (out, partial_sums) if partial_sums is not None else out
 
 

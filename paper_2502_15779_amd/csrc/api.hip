@@ -466,6 +466,27 @@ int rcp_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const 
                             static_cast<hipStream_t>(stream));
 }
 
+int rcp_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dtype,
+                        float clip_ratio, void* out, rcp_dtype out_dtype, void* xq_out_or_null, void* scale_out_or_null,
+                        int32_t* partial_sums_or_null, void* stream)
+{
+    if (!packed || !codebook || !x || !out) return fail(RCP_ERR_NULL, "rcp_quant_w3a4_gemv: NULL pointer argument");
+    if (int rc = check_shape("rcp_quant_w3a4_gemv", N, K)) return rc;
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w3a4_gemv: unknown dtype %d", static_cast<int>(x_dtype));
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w3a4_gemv: out_dtype must be RCP_F16 or RCP_F32");
+    if (!(clip_ratio > 0.0f) || !(clip_ratio <= 1.0f))
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w3a4_gemv: clip_ratio %g outside (0, 1]", static_cast<double>(clip_ratio));
+    if (!aligned16(packed) || !aligned16(codebook) || !aligned16(x) || !aligned16(out) || !aligned16(xq_out_or_null) ||
+        !aligned16(partial_sums_or_null))
+        return fail(RCP_ERR_ALIGN, "rcp_quant_w3a4_gemv: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale_out_or_null) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_quant_w3a4_gemv: scale_out must be 2-byte aligned");
+    return launch_quant_w3a4_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
+                                  scale_out_or_null, partial_sums_or_null, static_cast<hipStream_t>(stream));
+}
+
 size_t rcp_kv4_workspace_bytes(int H_q, int S)
 {
     if (H_q <= 0 || S <= 0 || S > RCP_KV_MAX_S) return 0;

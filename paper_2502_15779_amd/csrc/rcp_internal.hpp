@@ -66,6 +66,9 @@ int launch_unpack_w3(const void* packed, int N, int K, uint8_t* idx, hipStream_t
 int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
                      void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 // matrix-core kernel for several tokens (gemm_mfma.hip)
+int launch_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                           float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                           hipStream_t st);
 size_t kv4_workspace_bytes(int H_q, int S);
 int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, float clip_ratio, void* codes,
                       void* params, hipStream_t st);

@@ -48,13 +48,24 @@ __device__ __forceinline__ void w3_unit_update(const W3Planes& w, const u32x4& x
 
 // WS wavefronts share one row group: wavefront w of them takes the blocks w, w + WS, ... and the
 // monomial sums meet in LDS.  A workgroup therefore works on W3_WAVES / WS row groups at a time.
-template <bool OUT_F16, int WS>
+//
+// XDT < 0: `x_in` / `scale` are the quantised activations of one token.  XDT = RCP_F16 / RCP_F32 /
+// RCP_BF16: `x_in` is the token itself; every workgroup quantises it in its prologue (thread t takes
+// the 16-value units t, t + 256, ...; maximum, then the shared int4 quantiser), which is bit-identical
+// to the separate quantiser launch, and workgroup 0 also writes x_q and S to `xq_out` / `scale_out`
+// when those are given.
+constexpr int W3_XR = 2;  // 16-value units per thread requested ahead of the weights (all of them up to K = 8192)
+
+template <bool OUT_F16, int WS, int XDT>
 __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __restrict__ packed,
                                                                const uint4* __restrict__ codebook, int N, int K,
-                                                               const uint4* __restrict__ xq,
-                                                               const uint16_t* __restrict__ scale, int nblocks,
-                                                               void* __restrict__ out, int32_t* __restrict__ Pout)
+                                                               const void* __restrict__ x_in,
+                                                               const uint16_t* __restrict__ scale, float clip_ratio,
+                                                               int nblocks, void* __restrict__ out,
+                                                               int32_t* __restrict__ Pout, uint2* __restrict__ xq_out,
+                                                               uint16_t* __restrict__ scale_out)
 {
+    const uint4* xq = static_cast<const uint4*>(x_in);
     // x: 64 * nblk pieces of 16 bytes (zero beyond K); W3_WAVES sums of q; for WS > 1 the exchange
     // slots int[2 parities][W3_WAVES][4 rows][8]
     extern __shared__ uint4 smem4[];
@@ -99,22 +110,24 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
     advance(b1, j1);
     int b2 = b1, j2 = j1;
     advance(b2, j2);
-    // memory answers loads in issue order: this thread's first piece of the activations goes first, so that
-    // staging them does not have to wait for the weights
     const int xpieces = 64 * nblk;  // pieces of 16 bytes in LDS (zero beyond K)
-    const uint16_t sbits = scale[0];
-    uint4 xfirst = make_uint4(0u, 0u, 0u, 0u);
-    if (static_cast<int>(threadIdx.x) < U) xfirst = xq[threadIdx.x];
-    __builtin_amdgcn_sched_barrier(0);
-    W3Planes wA, wB;
-    load_block(b * SLOTS + slot, j, wA);
-    load_block(b1 * SLOTS + slot, j1, wB);
-    const int my_row = (((lane >> 4) & 1) << 1) | (lane >> 5);  // the row this lane holds after the folds
-    uint4 lut = codebook[min(4 * (b * SLOTS + slot) + my_row, N - 1)];
-
     int* tsum = reinterpret_cast<int*>(smem4 + 64 * nblk);
     int* red = tsum + W3_WAVES;
-    {
+    W3Planes wA, wB;
+    const int my_row = (((lane >> 4) & 1) << 1) | (lane >> 5);  // the row this lane holds after the folds
+    uint4 lut;
+    uint16_t sbits;
+    if constexpr (XDT < 0) {
+        // memory answers loads in issue order: this thread's first piece of the activations goes first, so that
+        // staging them does not have to wait for the weights
+        sbits = scale[0];
+        uint4 xfirst = make_uint4(0u, 0u, 0u, 0u);
+        if (static_cast<int>(threadIdx.x) < U) xfirst = xq[threadIdx.x];
+        __builtin_amdgcn_sched_barrier(0);
+        load_block(b * SLOTS + slot, j, wA);
+        load_block(b1 * SLOTS + slot, j1, wB);
+        lut = codebook[min(4 * (b * SLOTS + slot) + my_row, N - 1)];
+
         int s = 0;
         // the first piece apart from the loop: behind a join with the loop's own loads the compiler would
         // wait for every load in flight, the weights included
@@ -134,6 +147,78 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
             s = dot8(v.z, 0x11111111u, s);
             s = dot8(v.w, 0x11111111u, s);
         }
+        s = wave_sum(s);
+        if (lane == 0) tsum[wave] = s;
+    } else {
+        // Fused quantiser: the raw activations are requested first, the weights of the first two steps
+        // right behind them, and only then is anything waited for.  The first unit of a thread stays in
+        // registers between the two passes; further ones (K > 4096) are read again from cache.
+        __shared__ float amax_slots[W3_WAVES];
+        constexpr int XT = XDT >= 0 ? XDT : 0;
+        const int U16 = K / 16;  // 16-value units (uint2 of x_q); K is a multiple of 32
+        Raw8<XT> xr[W3_XR][2];
+#pragma unroll
+        for (int i = 0; i < W3_XR; ++i) {
+            if (i * W3_THREADS >= U16) break;  // uniform
+            const int u = min(static_cast<int>(threadIdx.x) + i * W3_THREADS, U16 - 1);  // clamped: duplicates are harmless
+            xr[i][0] = load8_raw<XT>(x_in, static_cast<size_t>(u) * 16);
+            xr[i][1] = load8_raw<XT>(x_in, static_cast<size_t>(u) * 16 + 8);
+        }
+        load_block(b * SLOTS + slot, j, wA);
+        load_block(b1 * SLOTS + slot, j1, wB);
+        lut = codebook[min(4 * (b * SLOTS + slot) + my_row, N - 1)];
+        asm volatile("" ::"s"(out), "s"(Pout), "s"(xq_out), "s"(scale_out));  // fetch the late arguments now
+        __builtin_amdgcn_sched_barrier(0);
+        float first[2][8];
+        float a = 0.0f;
+#pragma unroll
+        for (int i = 0; i < W3_XR; ++i) {
+            if (i * W3_THREADS >= U16) break;
+            float v[2][8];
+            widen8<XT>(xr[i][0], v[0]);
+            widen8<XT>(xr[i][1], v[1]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                a = fmaxf(a, fmaxf(fabsf(v[0][e]), fabsf(v[1][e])));
+                if (i == 0) {
+                    first[0][e] = v[0][e];
+                    first[1][e] = v[1][e];
+                }
+            }
+        }
+        for (int u = threadIdx.x + W3_XR * W3_THREADS; u < U16; u += W3_THREADS) {  // K > 8192 only
+            float v[2][8];
+            load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16, v[0]);
+            load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16 + 8, v[1]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a = fmaxf(a, fmaxf(fabsf(v[0][e]), fabsf(v[1][e])));
+        }
+        a = wave_max(a);
+        if (lane == 0) amax_slots[wave] = a;
+        __syncthreads();
+        a = fmaxf(fmaxf(amax_slots[0], amax_slots[1]), fmaxf(amax_slots[2], amax_slots[3]));
+        sbits = scale_bits_from_amax(a, clip_ratio);
+        const float S = half_bits_to_float(sbits);
+        const bool publish = blockIdx.x == 0 && xq_out != nullptr;
+        uint2* sx2 = reinterpret_cast<uint2*>(smem4);
+        int s = 0;
+        for (int u = threadIdx.x; u < 2 * xpieces; u += W3_THREADS) {  // the padding up to whole blocks is zeroed too
+            uint2 qv = make_uint2(0u, 0u);
+            if (u < U16) {
+                if (u == static_cast<int>(threadIdx.x)) {
+                    qv = make_uint2(quantize8(first[0], S), quantize8(first[1], S));
+                } else {
+                    float v[2][8];
+                    load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16, v[0]);
+                    load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16 + 8, v[1]);
+                    qv = make_uint2(quantize8(v[0], S), quantize8(v[1], S));
+                }
+                s = dot8(qv.y, 0x11111111u, dot8(qv.x, 0x11111111u, s));
+                if (publish) xq_out[u] = qv;
+            }
+            sx2[u] = qv;
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out != nullptr) scale_out[0] = sbits;
         s = wave_sum(s);
         if (lane == 0) tsum[wave] = s;
     }
@@ -231,11 +316,25 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
     if (nsteps & 1) step(wA);
 }
 
-template <int WS>
-static int launch_w3_ws(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
-                        void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
+struct W3Args {
+    const void* packed;
+    const void* codebook;
+    int N, K;
+    const void* x;          // quantised activations (x_dt < 0) or the raw token
+    const void* scale;      // S of the quantised activations, unused otherwise
+    int x_dt;               // -1 or an rcp_dtype
+    float clip_ratio;
+    void* out;
+    rcp_dtype out_dt;
+    int32_t* P;
+    void* xq_out;
+    void* scale_out;
+};
+
+template <int WS, int XDT>
+static int launch_w3_ws(const W3Args& a, hipStream_t st)
 {
-    const int G = N / 4, U = K / 32;
+    const int G = a.N / 4, U = a.K / 32;
     const int nblk = (U + 63) / 64;
     const size_t lds = static_cast<size_t>(nblk) * 64 * 16 + W3_WAVES * sizeof(int) +
                        (WS > 1 ? 2 * W3_WAVES * 4 * 8 * sizeof(int) : 0);
@@ -246,12 +345,29 @@ static int launch_w3_ws(const void* packed, const void* codebook, int N, int K, 
     if (blocks == 0) blocks = nbatch <= cus * 2 ? nbatch : cus * 2;  // sweeps: two workgroups per compute unit
     if (blocks > nbatch) blocks = nbatch;
     auto launch = [&](auto kernel) {
-        kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(packed), static_cast<const uint4*>(codebook), N, K,
-                                                static_cast<const uint4*>(xq), static_cast<const uint16_t*>(scale), blocks, out, P);
+        kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(a.packed), static_cast<const uint4*>(a.codebook), a.N,
+                                                a.K, a.x, static_cast<const uint16_t*>(a.scale), a.clip_ratio, blocks, a.out, a.P,
+                                                static_cast<uint2*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
     };
-    if (out_dt == RCP_F16) launch(&w3a4_gemv_kernel<true, WS>);
-    else launch(&w3a4_gemv_kernel<false, WS>);
-    return check_launch("rcp_w3a4_gemv");
+    if (a.out_dt == RCP_F16) launch(&w3a4_gemv_kernel<true, WS, XDT>);
+    else launch(&w3a4_gemv_kernel<false, WS, XDT>);
+    return check_launch(XDT < 0 ? "rcp_w3a4_gemv" : "rcp_quant_w3a4_gemv");
+}
+
+template <int XDT>
+static int launch_w3_any(const W3Args& a, hipStream_t st)
+{
+    const int nblk = (a.K / 32 + 63) / 64;
+    // wavefronts per row group: one, unless the "gemv_lanes" option (64, 128, 256) asks for 1, 2 or 4
+    // (sweeps at LLaMA-2-7B sizes: with the two-steps-ahead pipeline a second wavefront per row group
+    // never pays for its exchange through LDS); never more than the row group has blocks
+    int ws = options().gemv_lanes >= 64 ? options().gemv_lanes / 64 : 1;
+    while (ws > 1 && ws > nblk) ws /= 2;
+    switch (ws) {
+        case 1: return launch_w3_ws<1, XDT>(a, st);
+        case 2: return launch_w3_ws<2, XDT>(a, st);
+        default: return launch_w3_ws<4, XDT>(a, st);
+    }
 }
 
 int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
@@ -259,17 +375,21 @@ int launch_w3a4_gemv(const void* packed, const void* codebook, int N, int K, con
 {
     if (static_cast<long long>(N) * K / 8 * 3 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w3a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(N) * K / 8 * 3);
-    const int nblk = (K / 32 + 63) / 64;
-    // wavefronts per row group: one, unless the "gemv_lanes" option (64, 128, 256) asks for 1, 2 or 4
-    // (sweeps at LLaMA-2-7B sizes: with the two-steps-ahead pipeline a second wavefront per row group
-    // never pays for its exchange through LDS); never more than the row group has blocks
-    int ws = options().gemv_lanes >= 64 ? options().gemv_lanes / 64 : 1;
-    while (ws > 1 && ws > nblk) ws /= 2;
-    switch (ws) {
-        case 1: return launch_w3_ws<1>(packed, codebook, N, K, xq, scale, out, out_dt, P, st);
-        case 2: return launch_w3_ws<2>(packed, codebook, N, K, xq, scale, out, out_dt, P, st);
-        default: return launch_w3_ws<4>(packed, codebook, N, K, xq, scale, out, out_dt, P, st);
-    }
+    const W3Args a = {packed, codebook, N, K, xq, scale, -1, 1.0f, out, out_dt, P, nullptr, nullptr};
+    return launch_w3_any<-1>(a, st);
+}
+
+int launch_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                           float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                           hipStream_t st)
+{
+    if (static_cast<long long>(N) * K / 8 * 3 >= (1LL << 31))
+        return fail(RCP_ERR_SHAPE, "rcp_quant_w3a4_gemv: packed matrix of %lld bytes exceeds 2 GiB",
+                    static_cast<long long>(N) * K / 8 * 3);
+    const W3Args a = {packed, codebook, N, K, x, nullptr, static_cast<int>(x_dt), clip_ratio, out, out_dt, P, xq_out, scale_out};
+    if (x_dt == RCP_F16) return launch_w3_any<RCP_F16>(a, st);
+    if (x_dt == RCP_F32) return launch_w3_any<RCP_F32>(a, st);
+    return launch_w3_any<RCP_BF16>(a, st);
 }
 
 }  // namespace rcp

@@ -33,7 +33,7 @@ def test_every_declared_function_is_exported(lib):
             "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped",
             "rcp_w2a16_gemv", "rcp_quant_w2a4_gemv_grouped", "rcp_w2a4_gemm_grouped",
             "rcp_rotate_quant_w2a4_gemv", "rcp_pack_weights_w3", "rcp_unpack_indices_w3", "rcp_w3a4_gemv",
-            "rcp_kv4_workspace_bytes", "rcp_kv4_append", "rcp_kv4_attn_decode"} <= set(names)
+            "rcp_kv4_workspace_bytes", "rcp_kv4_append", "rcp_kv4_attn_decode", "rcp_quant_w3a4_gemv"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -150,6 +150,15 @@ def test_argument_errors_need_no_gpu(lib):
     assert g3(fake, fake, 8, 48, fake, fake, fake, 0, None, None) == -2
     assert g3(fake, fake, 8, 64, fake, fake, fake, 2, None, None) == -4
     assert g3(fake, fake, 8, 64, fake, vp(0x1001), fake, 0, None, None) == -3
+    q3 = lib.rcp_quant_w3a4_gemv
+    q3.argtypes = [vp, vp, ci, ci, vp, ci, ctypes.c_float, vp, ci, vp, vp, vp, vp]
+    assert q3(fake, fake, 8, 64, None, 0, 1.0, fake, 0, None, None, None, None) == -1
+    assert q3(fake, fake, 8, 48, fake, 0, 1.0, fake, 0, None, None, None, None) == -2
+    assert q3(fake, fake, 8, 64, fake, 5, 1.0, fake, 0, None, None, None, None) == -4
+    assert q3(fake, fake, 8, 64, fake, 0, 0.0, fake, 0, None, None, None, None) == -4
+    assert q3(fake, fake, 8, 64, fake, 0, 1.0, fake, 2, None, None, None, None) == -4
+    assert q3(fake, fake, 8, 64, odd, 0, 1.0, fake, 0, None, None, None, None) == -3
+    assert q3(fake, fake, 8, 64, fake, 0, 1.0, fake, 0, None, vp(0x1001), None, None) == -3
     u3 = lib.rcp_unpack_indices_w3
     u3.argtypes = [vp, ci, ci, vp, vp]
     assert u3(fake, 10, 64, fake, None) == -2

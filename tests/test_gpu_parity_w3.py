@@ -168,11 +168,78 @@ def test_w3_whole_path(N, K):
     assert cos > 0.8
 
 
+def _x_as(x16, dtype):
+    if dtype == "f16":
+        return _t(x16), x16.astype(np.float32)
+    if dtype == "f32":
+        x32 = x16.astype(np.float32) * np.float32(1.0009765)
+        return _t(x32), x32
+    xb = _t(x16.astype(np.float32)).to(torch.bfloat16)
+    return xb, xb.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("N,K", [(4, 32), (12, 96), (256, 512), (20, 2080), (1028, 4096), (72, 11008), (40, 14336),
+                                 (16, 32768), (8, 32736)])
+@pytest.mark.parametrize("dtype,clip", [("f16", 1.0), ("f32", 0.9), ("bf16", 1.0)])
+def test_w3_fused_quantiser_matches_oracle_and_the_two_calls(N, K, dtype, clip):
+    """rcp_quant_w3a4_gemv: x_q, S and the per-level sums bit-exact against the oracle's quantiser + GEMV,
+    output bits equal to rcp_rotate_quant_act followed by rcp_w3a4_gemv."""
+    _say(f"w3 fused N={N} K={K} {dtype} clip={clip}")
+    packed, cb, _, _ = _w3_case(N + K + 1, N, K)
+    xd, x32 = _x_as(rcp_synth.activation(6, f"w3fused{K}", 1, K), dtype)
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, clip)
+    ref_O, ref_P = oracle.w3a4_gemv(packed, cb, N, K, ref_xq, ref_sc)
+    pk, cbd = _t(packed), _t(cb.view(np.float16))
+    xq_out = torch.zeros(K // 2, dtype=torch.uint8, device=DEV)
+    sc_out = torch.zeros(1, dtype=torch.float16, device=DEV)
+    for out_dtype in (torch.float32, torch.float16):
+        out, P = rcp.quant_w3a4_gemv(pk, cbd, N, K, xd, clip, out_dtype=out_dtype, xq_out=xq_out, scale_out=sc_out,
+                                     want_partial_sums=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(xq_out.cpu().numpy(), ref_xq.ravel())
+        assert np.array_equal(sc_out.cpu().numpy().view(np.uint16), ref_sc)
+        assert np.array_equal(P.cpu().numpy(), ref_P)
+        got = out.cpu().numpy().astype(np.float64).ravel()
+        cond = _f16(ref_sc)[0] * (np.abs(_f16(cb)) * np.abs(ref_P)).sum(axis=1)
+        half = 2.0 ** -11 * np.abs(ref_O) if out_dtype == torch.float16 else 0.0
+        assert np.all(np.abs(got - ref_O) <= 1e-3 * cond + half + 1e-30)
+        xq2, sc2 = rcp.rotate_quant_act(xd, None, clip)
+        two = rcp.w3a4_gemv(pk, cbd, N, K, xq2, sc2, out_dtype=out_dtype)
+        one = rcp.quant_w3a4_gemv(pk, cbd, N, K, xd, clip, out_dtype=out_dtype)     # without the optional outputs
+        torch.cuda.synchronize()
+        assert torch.equal(out, two) and torch.equal(one, two)
+
+
+@pytest.mark.parametrize("lanes,blocks", [(128, 0), (256, 3), (64, 1)])
+def test_w3_fused_quantiser_other_work_splits(lanes, blocks):
+    _say(f"w3 fused lanes={lanes} blocks={blocks}")
+    rcp.set_option("gemv_lanes", lanes)
+    rcp.set_option("gemv_blocks", blocks)
+    N, K = 1028, 11008
+    packed, cb, _, _ = _w3_case(9, N, K)
+    xd, x32 = _x_as(rcp_synth.activation(9, "w3fusedsplit", 1, K), "f16")
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, 1.0)
+    _, ref_P = oracle.w3a4_gemv(packed, cb, N, K, ref_xq, ref_sc)
+    _, P = rcp.quant_w3a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, 1.0, out_dtype=torch.float32,
+                               want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+
+
 @pytest.mark.parametrize("N,K", [(4096, 4096), (11008, 4096), (4096, 11008)])
 def test_w3_full_size_as_benchmarked(N, K):
     _say(f"w3 full size N={N} K={K}")
     packed, cb, xq, sc = _w3_case(5, N, K)
     _check_w3(packed, cb, N, K, xq, sc, torch.float16)
+    # the fused call on the same weights
+    xd, x32 = _x_as(rcp_synth.activation(5, f"w3full{K}", 1, K), "f16")
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, 1.0)
+    ref_O, ref_P = oracle.w3a4_gemv(packed, cb, N, K, ref_xq, ref_sc)
+    out, P = rcp.quant_w3a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, 1.0, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.float().cpu().numpy().astype(np.float64).ravel()
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O) + 1e-30
 
 
 def test_w3_argument_errors():
