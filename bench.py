@@ -487,7 +487,40 @@ def main():
         s = timed(torch, fn, reps) / L
         b = 3 * N * K // 8 + 16 * N + K // 2 + 2 + 2 * N
         w3[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1)}
+
+        def w3fused(i=i, N=N, K=K, w3sets=w3sets):   # quantiser fused into the prologue, raw fp16 activations
+            for pk, cb in w3sets:
+                rcp.quant_w3a4_gemv(pk, cb, N, K, xs[i] if not launches[i][3] else ybuf, 1.0, out=outs[i])
+        w3fused()
+        fn = capture(w3fused)
+        fn()
+        s = timed(torch, fn, reps) / L
+        w3[label]["fused_us"] = round(s * 1e6, 3)
         del w3sets
+
+    # the whole one-token step with 3-bit weights: the launch structure of the headline step (rotation kernel +
+    # four fused quantise+GEMV launches per layer), 32 different layers of random indices and levels
+    w3_step = None
+    if not args.step_only:
+        wl = [[(torch.randint(0, 256, (3 * N * K // 8,), dtype=torch.uint8, device=dev),
+                (torch.randn((N, 8), device=dev) * 0.03).sort(dim=1).values.to(torch.float16).contiguous())
+               for (_, N, K, _) in launches] for _ in range(L)]
+
+        def w3step():
+            for l in range(L):
+                for i, (_, N, K, rotated) in enumerate(launches):
+                    if rotated:
+                        rcp.rotate_act(xs[i], rot_down, y_out=ybuf)
+                    pk, cb = wl[l][i]
+                    rcp.quant_w3a4_gemv(pk, cb, N, K, ybuf if rotated else xs[i], 1.0, out=outs[i])
+        w3step()
+        fn = capture(w3step)
+        fn()
+        s = timed(torch, fn, max(3, args.steps // 2))
+        wbytes = L * sum(3 * N * K // 8 + 16 * N + K // 2 + 2 + 2 * N for (_, N, K, _) in launches)
+        w3_step = {"ms_per_step": round(s * 1e3, 4), "GBps": round(wbytes / s / 1e9, 1),
+                   "pct_of_hbm_peak": round(100.0 * wbytes / s / 1e9 / HBM_PEAK_GBPS, 2), "bytes_per_step": wbytes}
+        del wl
 
     # 4-bit KV cache, one query token (LLaMA-2-7B: 32 heads of 128), cold over L layers' caches.  One layer's
     # keys and values are drawn and quantised by the library, then copied into L separate caches.
@@ -562,6 +595,7 @@ def main():
         "grouped_128_step": grouped_step,
         "weight_only_fp16": weight_only,
         "w3a4": w3,
+        "w3a4_step": w3_step,
         "kv4_attention_32_heads": kv4,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},

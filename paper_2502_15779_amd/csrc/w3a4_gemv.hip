@@ -54,7 +54,7 @@ __device__ __forceinline__ void w3_unit_update(const W3Planes& w, const u32x4& x
 // the 16-value units t, t + 256, ...; maximum, then the shared int4 quantiser), which is bit-identical
 // to the separate quantiser launch, and workgroup 0 also writes x_q and S to `xq_out` / `scale_out`
 // when those are given.
-constexpr int W3_XR = 2;  // 16-value units per thread requested ahead of the weights (all of them up to K = 8192)
+constexpr int W3_XR = 3;  // 16-value units per thread requested ahead of the weights (all of them up to K = 12288)
 
 template <bool OUT_F16, int WS, int XDT>
 __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __restrict__ packed,
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
                 }
             }
         }
-        for (int u = threadIdx.x + W3_XR * W3_THREADS; u < U16; u += W3_THREADS) {  // K > 8192 only
+        for (int u = threadIdx.x + W3_XR * W3_THREADS; u < U16; u += W3_THREADS) {  // K > 12288 only
             float v[2][8];
             load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16, v[0]);
             load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16 + 8, v[1]);
