@@ -531,7 +531,7 @@ def main():
         vx = torch.from_numpy(rcp_synth.kv_vectors(args.seed, f"bench_v{S}", S, Hh)).to(dev)
         kc0, kp0 = rcp.kv4_new_cache(Hh, S, dev)
         vc0, vp0 = rcp.kv4_new_cache(Hh, S, dev)
-        rcp.kv4_append(kx, 0, kc0, kp0)
+        rcp.kv4_append(kx, 0, kc0, kp0, rotate=True)
         rcp.kv4_append(vx, 0, vc0, vp0)
         kcaches = [(kc0.clone(), kp0.clone(), vc0.clone(), vp0.clone()) for _ in range(L)]
         qv = torch.from_numpy(rcp_synth.query_vectors(args.seed, "bench_q", Hh)).to(dev)
@@ -549,7 +549,7 @@ def main():
 
         def asweep_kv(kx=kx, kcaches=kcaches, S=S):
             for c in kcaches:
-                rcp.kv4_append(kx[:1], S - 1, c[0], c[1])
+                rcp.kv4_append(kx[:1], S - 1, c[0], c[1], rotate=True)   # a new key: R3, then the quantiser
         asweep_kv()
         fn = capture(asweep_kv)
         fn()

@@ -128,6 +128,7 @@ typedef struct {
 
 /* Limits of this build. */
 #define RCP_MAX_M 16          /* tokens per call                                    */
+#define RCP_MAX_ROTATE_ROWS 4096 /* rows per rcp_rotate_act call                      */
 #define RCP_MAX_K 32768       /* input channels                                     */
 #define RCP_MAX_WHT 16384     /* largest Hadamard order of a pure WHT rotation      */
 #define RCP_MAX_KRON_M 256    /* largest order of Q                                 */
@@ -209,7 +210,8 @@ int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K,
 /*
  * The rotation step alone: y = R x in fp32 (the same kernels and arithmetic as the first half
  * of rcp_rotate_quant_act).  y_out: fp32 [M][K].  Meant to be followed by
- * rcp_quant_w2a4_gemv, which quantises in the prologue of the GEMV kernel.
+ * rcp_quant_w2a4_gemv, which quantises in the prologue of the GEMV kernel.  M counts rows here and may
+ * reach RCP_MAX_ROTATE_ROWS (e.g. the H_q query head vectors of a token, rotated one by one with K = 128).
  */
 int rcp_rotate_act(const void* x, rcp_dtype x_dtype, int M, int K,
                    const rcp_rotation* rot, float* y_out, void* stream);
@@ -375,8 +377,9 @@ int rcp_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
  * configurations: the KV cache uses an asymmetric quantiser on groups of 128 with clipping
  * ratio 0.95; the quantiser is Eqn. 1 with N = 4.  Section 2.1: the online rotation R3 is
  * applied to queries and keys so that the cache can be held in 4 bits without changing the
- * attention output; apply it with rcp_rotate_act (an order-128 WHT over rows of 128) before
- * the calls below.  Head size is RCP_KV_HEAD_DIM = 128 = one group.
+ * attention output: rcp_kv4_append applies it to the keys when `rotate` is set, and the query
+ * goes through rcp_rotate_act (an order-128 WHT over H_q rows of 128) before rcp_kv4_attn_decode.
+ * Head size is RCP_KV_HEAD_DIM = 128 = one group.
  *
  * Layout of one cached tensor (keys or values) of one layer, both device buffers, caller-owned:
  *   codes   [H][S_max][64 bytes]  element j of a head vector in byte j / 2, bits 4*(j%2) .. 4*(j%2)+3
@@ -384,7 +387,10 @@ int rcp_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
  * A code c stands for the value s * (c - z).
  *
  * rcp_kv4_append: x is [n_tokens][H][128] of `x_dtype`; token i goes to cache position pos + i
- *   (0 <= pos, pos + n_tokens <= S_max, else RCP_ERR_SHAPE; n_tokens = 0 is a no-op).  In binary32:
+ *   (0 <= pos, pos + n_tokens <= S_max, else RCP_ERR_SHAPE; n_tokens = 0 is a no-op).  rotate != 0: every head
+ *   vector is first replaced by its normalised order-128 Hadamard transform, computed in binary32 with the
+ *   butterflies in ascending stride order and one multiplication by (float)(1/sqrt(128)) (keys; values are
+ *   stored unrotated here, their rotation being folded into the projection weights).  Then, in binary32:
  *     lo = ratio * min(x), hi = ratio * max(x), s = fp16((hi - lo) / 15)   [1 when that is 0; capped at 65504]
  *     z = -rint(lo / s)  [clamped to int16],  c_j = clamp(rint(x_j / s) + z, 0, 15)
  *   with correctly rounded divisions and round-half-to-even.  Other cache positions are not touched.
@@ -399,7 +405,7 @@ int rcp_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
 #define RCP_KV_MAX_S 262144
 size_t rcp_kv4_workspace_bytes(int H_q, int S);
 int rcp_kv4_append(const void* x, rcp_dtype x_dtype, int n_tokens, int H, int S_max, int pos,
-                   float clip_ratio, void* codes, void* params, void* stream);
+                   int rotate, float clip_ratio, void* codes, void* params, void* stream);
 int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int S_max, int S,
                         const void* k_codes, const void* k_params,
                         const void* v_codes, const void* v_params,

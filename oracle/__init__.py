@@ -290,13 +290,15 @@ def kv4_new_cache(H, S_max):
     return np.zeros((H, S_max, KV_D // 2), dtype=np.uint8), np.zeros((H, S_max, 4), dtype=np.uint8)
 
 
-def kv4_append(x, pos, clip_ratio, codes, params):
-    """Quantise x float32[n][H][128] into cache positions pos .. pos + n - 1 (in place)."""
+def kv4_append(x, pos, clip_ratio, codes, params, rotate=False):
+    """Quantise x float32[n][H][128] into cache positions pos .. pos + n - 1 (in place); rotate: order-128
+    Hadamard transform of every head vector first."""
     x = _c(x, np.float32)
     n, H, d = x.shape
     assert d == KV_D and codes.shape[0] == H and codes.flags.c_contiguous and params.flags.c_contiguous
     S_max = codes.shape[1]
-    _check(lib().rcp_ref_kv4_append(_p(x), n, H, S_max, int(pos), ctypes.c_float(clip_ratio), _p(codes), _p(params)),
+    _check(lib().rcp_ref_kv4_append(_p(x), n, H, S_max, int(pos), int(bool(rotate)), ctypes.c_float(clip_ratio), _p(codes),
+                                    _p(params)),
            "kv4_append")
 
 

@@ -766,14 +766,18 @@ static inline size_t kv_code_byte(int h, int t, int j, int S_max)
 }
 static inline size_t kv_param_byte(int h, int t, int S_max) { return ((size_t)h * S_max + t) * 4; }
 
-/* x: [n_tokens][H][128] binary32; writes tokens pos .. pos + n_tokens - 1 */
-int rcp_ref_kv4_append(const float* x, int n_tokens, int H, int S_max, int pos, float clip_ratio, uint8_t* codes,
-                       uint8_t* params)
+/* x: [n_tokens][H][128] binary32; writes tokens pos .. pos + n_tokens - 1.  rotate != 0: every head
+ * vector first goes through the normalised order-128 Hadamard transform in binary32 (R3 of Section
+ * 2.1 on the keys; the butterflies of rcp_ref_fwht_f32). */
+int rcp_ref_kv4_append(const float* x, int n_tokens, int H, int S_max, int pos, int rotate, float clip_ratio,
+                       uint8_t* codes, uint8_t* params)
 {
     if (n_tokens < 0 || H < 1 || S_max < 1 || pos < 0 || pos + n_tokens > S_max) return RCP_REF_ERR_SHAPE;
     for (int i = 0; i < n_tokens; ++i)
         for (int h = 0; h < H; ++h) {
-            const float* v = x + ((size_t)i * H + h) * KV_D;
+            float v[KV_D];
+            memcpy(v, x + ((size_t)i * H + h) * KV_D, sizeof(v));
+            if (rotate) rcp_ref_fwht_f32(v, KV_D);
             float lo = v[0], hi = v[0];
             for (int j = 1; j < KV_D; ++j) {
                 if (v[j] < lo) lo = v[j];

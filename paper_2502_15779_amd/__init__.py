@@ -126,7 +126,7 @@ def lib():
         L.rcp_kv4_workspace_bytes.restype = ctypes.c_size_t
         L.rcp_kv4_workspace_bytes.argtypes = [ci, ci]
         L.rcp_kv4_append.restype = ci
-        L.rcp_kv4_append.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
+        L.rcp_kv4_append.argtypes = [vp, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
         L.rcp_kv4_attn_decode.restype = ci
         L.rcp_kv4_attn_decode.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp,
                                           ctypes.c_size_t, vp]
@@ -528,8 +528,9 @@ def kv4_workspace_bytes(H_q, S):
     return int(lib().rcp_kv4_workspace_bytes(H_q, S))
 
 
-def kv4_append(x, pos, codes, params, clip_ratio=0.95):
-    """Quantise x [n_tokens, H, 128] into cache positions pos .. pos + n_tokens - 1 (in place)."""
+def kv4_append(x, pos, codes, params, clip_ratio=0.95, rotate=False):
+    """Quantise x [n_tokens, H, 128] into cache positions pos .. pos + n_tokens - 1 (in place); rotate: the
+    order-128 Hadamard transform of every head vector first (keys)."""
     if x.dim() != 3 or x.shape[2] != KV_HEAD_DIM or not x.is_contiguous():
         raise ValueError("x must be contiguous [n_tokens, H, 128]")
     n, H = int(x.shape[0]), int(x.shape[1])
@@ -539,7 +540,7 @@ def kv4_append(x, pos, codes, params, clip_ratio=0.95):
         raise ValueError("codes must be uint8 [H, S_max, 64] and params uint8 [H, S_max, 4], contiguous")
     if n == 0:      # an empty tensor has no device pointer to hand over
         return
-    _check(lib().rcp_kv4_append(_dev(x, "x"), _DTYPES[x.dtype], n, H, int(codes.shape[1]), int(pos),
+    _check(lib().rcp_kv4_append(_dev(x, "x"), _DTYPES[x.dtype], n, H, int(codes.shape[1]), int(pos), int(bool(rotate)),
                                 ctypes.c_float(clip_ratio), _dev(codes, "codes"), _dev(params, "params"), _stream()))
 
 

@@ -220,7 +220,8 @@ int rcp_stream_read(const void* buffer, size_t bytes, void* sink_or_null, void* 
 int rcp_rotate_act(const void* x, rcp_dtype x_dtype, int M, int K, const rcp_rotation* rot, float* y_out, void* stream)
 {
     if (!x || !y_out) return fail(RCP_ERR_NULL, "rcp_rotate_act: NULL pointer argument");
-    if (M <= 0 || M > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_rotate_act: M=%d outside 1..%d", M, RCP_MAX_M);
+    if (M <= 0 || M > RCP_MAX_ROTATE_ROWS)
+        return fail(RCP_ERR_SHAPE, "rcp_rotate_act: M=%d outside 1..%d", M, RCP_MAX_ROTATE_ROWS);
     if (K <= 0 || K % 32 != 0 || K > RCP_MAX_K)
         return fail(RCP_ERR_SHAPE, "rcp_rotate_act: K=%d must be a positive multiple of 32, at most %d", K, RCP_MAX_K);
     if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
@@ -493,8 +494,8 @@ size_t rcp_kv4_workspace_bytes(int H_q, int S)
     return kv4_workspace_bytes(H_q, S);
 }
 
-int rcp_kv4_append(const void* x, rcp_dtype x_dtype, int n_tokens, int H, int S_max, int pos, float clip_ratio,
-                   void* codes, void* params, void* stream)
+int rcp_kv4_append(const void* x, rcp_dtype x_dtype, int n_tokens, int H, int S_max, int pos, int rotate,
+                   float clip_ratio, void* codes, void* params, void* stream)
 {
     if (!x || !codes || !params) return fail(RCP_ERR_NULL, "rcp_kv4_append: NULL pointer argument");
     if (x_dtype != RCP_F16 && x_dtype != RCP_BF16 && x_dtype != RCP_F32)
@@ -507,7 +508,8 @@ int rcp_kv4_append(const void* x, rcp_dtype x_dtype, int n_tokens, int H, int S_
         return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_append: clip_ratio must be in (0, 1]");
     if (!aligned16(x) || !aligned16(codes) || !aligned16(params))
         return fail(RCP_ERR_ALIGN, "rcp_kv4_append: device buffers must be 16-byte aligned");
-    return launch_kv4_append(x, x_dtype, n_tokens, H, S_max, pos, clip_ratio, codes, params, static_cast<hipStream_t>(stream));
+    return launch_kv4_append(x, x_dtype, n_tokens, H, S_max, pos, rotate != 0, clip_ratio, codes, params,
+                             static_cast<hipStream_t>(stream));
 }
 
 int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int S_max, int S, const void* k_codes,

@@ -18,8 +18,11 @@ constexpr int KV_D = 128;
 // ---------------------------------------------------------------------------------------
 // append: quantise n_tokens x H head vectors into cache positions pos ...
 // Sixteen lanes (one DPP row) own a head vector, eight consecutive elements each.
+// ROT: the vector first goes through the normalised order-128 Hadamard transform: butterflies in
+// ascending stride order (1, 2, 4 in registers, 8 .. 64 between the sixteen lanes), each output
+// one IEEE add or subtract, then one multiplication by (float)(1/sqrt(128)).
 // ---------------------------------------------------------------------------------------
-template <int DT>
+template <int DT, bool ROT>
 __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict__ x, int rows, int H, int S_max, int pos,
                                                          float clip_ratio, uint32_t* __restrict__ codes,
                                                          uint32_t* __restrict__ params)
@@ -34,6 +37,29 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict_
     const int rr = have ? row : rows - 1;  // surplus lanes repeat the last vector and store nothing
     float v[8];
     load8_as_float<DT>(x, static_cast<size_t>(rr) * KV_D + 8 * l, v);
+    if constexpr (ROT) {
+#pragma unroll
+        for (int st = 1; st < 8; st <<= 1)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if ((e & st) == 0) {
+                    const float a = v[e], b = v[e + st];
+                    v[e] = a + b;
+                    v[e + st] = a - b;
+                }
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) {  // element stride 8 * m: the partner is lane l ^ m of the row
+            const bool upper = (l & m) != 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float other = __shfl_xor(v[e], m, 16);
+                v[e] = upper ? other - v[e] : v[e] + other;
+            }
+        }
+        const float norm = 0.088388347648318440550f;  // (float)(1 / sqrt(128))
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = v[e] * norm;
+    }
     float lo = v[0], hi = v[0];
 #pragma unroll
     for (int j = 1; j < 8; ++j) {
@@ -344,17 +370,23 @@ size_t kv4_workspace_bytes(int H_q, int S)
     return static_cast<size_t>(H_q) * splits * KV_PART * sizeof(float);
 }
 
-int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, float clip_ratio, void* codes,
-                      void* params, hipStream_t st)
+int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, bool rotate, float clip_ratio,
+                      void* codes, void* params, hipStream_t st)
 {
     const int rows = n_tokens * H;
     if (rows == 0) return RCP_OK;
     const unsigned grid = static_cast<unsigned>((rows + 15) / 16);
     auto* c = static_cast<uint32_t*>(codes);
     auto* p = static_cast<uint32_t*>(params);
-    if (dt == RCP_F32) kv4_append_kernel<RCP_F32><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);
-    else if (dt == RCP_F16) kv4_append_kernel<RCP_F16><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);
-    else kv4_append_kernel<RCP_BF16><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);
+#define RCP_KV_APPEND(DT)                                                                                      \
+    do {                                                                                                       \
+        if (rotate) kv4_append_kernel<DT, true><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p); \
+        else kv4_append_kernel<DT, false><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);      \
+    } while (0)
+    if (dt == RCP_F32) RCP_KV_APPEND(RCP_F32);
+    else if (dt == RCP_F16) RCP_KV_APPEND(RCP_F16);
+    else RCP_KV_APPEND(RCP_BF16);
+#undef RCP_KV_APPEND
     return check_launch("rcp_kv4_append");
 }
 

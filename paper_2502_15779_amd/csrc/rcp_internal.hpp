@@ -70,8 +70,8 @@ int launch_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int 
                            float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
                            hipStream_t st);
 size_t kv4_workspace_bytes(int H_q, int S);
-int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, float clip_ratio, void* codes,
-                      void* params, hipStream_t st);
+int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, bool rotate, float clip_ratio,
+                      void* codes, void* params, hipStream_t st);
 int launch_kv4_attn(const void* q, rcp_dtype q_dt, int H_q, int H_kv, int S_max, int S, const void* k_codes,
                     const void* k_params, const void* v_codes, const void* v_params, float softmax_scale, void* out,
                     rcp_dtype out_dt, void* workspace, hipStream_t st);

@@ -164,15 +164,15 @@ def test_argument_errors_need_no_gpu(lib):
     assert u3(fake, 10, 64, fake, None) == -2
     # 4-bit KV cache
     ap = lib.rcp_kv4_append
-    ap.argtypes = [vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
-    assert ap(None, 0, 1, 2, 8, 0, 0.95, fake, fake, None) == -1
-    assert ap(fake, 7, 1, 2, 8, 0, 0.95, fake, fake, None) == -4
-    assert ap(fake, 0, 3, 2, 8, 6, 0.95, fake, fake, None) == -2          # runs past S_max
-    assert ap(fake, 0, 1, 2, 8, -1, 0.95, fake, fake, None) == -2
-    assert ap(fake, 0, 1, 0, 8, 0, 0.95, fake, fake, None) == -2
-    assert ap(fake, 0, 1, 2, 8, 0, 0.0, fake, fake, None) == -4
-    assert ap(fake, 0, 1, 2, 8, 0, 1.5, fake, fake, None) == -4
-    assert ap(odd, 0, 1, 2, 8, 0, 0.95, fake, fake, None) == -3
+    ap.argtypes = [vp, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
+    assert ap(None, 0, 1, 2, 8, 0, 0, 0.95, fake, fake, None) == -1
+    assert ap(fake, 7, 1, 2, 8, 0, 0, 0.95, fake, fake, None) == -4
+    assert ap(fake, 0, 3, 2, 8, 6, 0, 0.95, fake, fake, None) == -2          # runs past S_max
+    assert ap(fake, 0, 1, 2, 8, -1, 0, 0.95, fake, fake, None) == -2
+    assert ap(fake, 0, 1, 0, 8, 0, 0, 0.95, fake, fake, None) == -2
+    assert ap(fake, 0, 1, 2, 8, 0, 0, 0.0, fake, fake, None) == -4
+    assert ap(fake, 0, 1, 2, 8, 0, 0, 1.5, fake, fake, None) == -4
+    assert ap(odd, 0, 1, 2, 8, 0, 1, 0.95, fake, fake, None) == -3
     kws = lib.rcp_kv4_workspace_bytes
     kws.restype = ctypes.c_size_t
     kws.argtypes = [ci, ci]

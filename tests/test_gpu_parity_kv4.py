@@ -91,6 +91,52 @@ def test_append_values_on_rounding_boundaries_and_degenerate_groups():
         assert np.array_equal(codes.cpu().numpy(), rc)
 
 
+@pytest.mark.parametrize("n,H,dtype", [(1, 1, "f16"), (1, 32, "f16"), (5, 3, "f32"), (33, 8, "bf16"), (200, 32, "f16")])
+def test_rotated_append_bit_exact(n, H, dtype):
+    """rotate = 1: the order-128 Hadamard transform of every head vector (R3 on the keys), then the quantiser."""
+    _say(f"kv4 rotated append n={n} H={H} {dtype}")
+    xd, x32 = _as_dtype(rcp_synth.kv_vectors(13, f"rot{n}x{H}", n, H), dtype)
+    codes, params = rcp.kv4_new_cache(H, n + 2, DEV)
+    rcp.kv4_append(xd, 1, codes, params, rotate=True)
+    torch.cuda.synchronize()
+    rc, rp = oracle.kv4_new_cache(H, n + 2)
+    oracle.kv4_append(x32, 1, 0.95, rc, rp, rotate=True)
+    assert np.array_equal(params.cpu().numpy(), rp)
+    assert np.array_equal(codes.cpu().numpy(), rc)
+
+
+def test_rotated_queries_and_keys_through_the_whole_path():
+    """q and k rotated online (rcp_rotate_act over the 32 query head vectors, rotate = 1 in the append), values
+    as they are: against the oracle doing the same, and close to attention over the unquantised vectors."""
+    _say("kv4 whole path with R3")
+    H, S = 32, 600
+    k = rcp_synth.kv_vectors(14, "k", S, H)
+    v = rcp_synth.kv_vectors(14, "v", S, H)
+    q = rcp_synth.query_vectors(14, "q", H)
+    kc, kp = rcp.kv4_new_cache(H, S, DEV)
+    vc, vp = rcp.kv4_new_cache(H, S, DEV)
+    rcp.kv4_append(_t(k), 0, kc, kp, rotate=True)
+    rcp.kv4_append(_t(v), 0, vc, vp)
+    q_rot = rcp.rotate_act(_t(q), rcp.Rotation.wht(D))           # 32 rows of 128
+    out = rcp.kv4_attn_decode(q_rot, S, kc, kp, vc, vp, 1.0 / np.sqrt(D))
+    torch.cuda.synchronize()
+    rkc, rkp = oracle.kv4_new_cache(H, S)
+    rvc, rvp = oracle.kv4_new_cache(H, S)
+    oracle.kv4_append(k.astype(np.float32), 0, 0.95, rkc, rkp, rotate=True)
+    oracle.kv4_append(v.astype(np.float32), 0, 0.95, rvc, rvp)
+    q64 = oracle.rotate(q.astype(np.float64), oracle.ROT_WHT, D, 1)
+    ref = oracle.kv4_attn_decode(q64, S, rkc, rkp, rvc, rvp, 1.0 / np.sqrt(D))
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - ref) <= TOL * (1.0 + np.abs(ref)))
+    # the rotation leaves q . k unchanged, so the result stays near full-precision attention (4-bit noise only)
+    k64, v64, qf = k.astype(np.float64), v.astype(np.float64), q.astype(np.float64)
+    sc = np.einsum("hd,thd->ht", qf, k64) / np.sqrt(D)
+    p = np.exp(sc - sc.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    full = np.einsum("ht,thd->hd", p, v64)
+    assert np.linalg.norm(got - full) <= 0.1 * np.linalg.norm(full)
+
+
 def test_append_token_by_token_equals_one_call():
     _say("kv4 append incremental")
     H, n = 8, 21

@@ -119,6 +119,34 @@ def test_layout_and_append_positions():
     assert pb[0] == 0x00 and pb[1] == 0x3C and pb[2] == 1 and pb[3] == 0
 
 
+def test_rotated_append_is_the_append_of_the_rotated_vectors():
+    # R3 (Section 2.1): with the flag set, what is quantised is H x / sqrt(128) per head vector; the
+    # transform itself is pinned to the dense definition in the rotation tests
+    x = rcp_synth.kv_vectors(12, "k", 9, 3).astype(np.float32)
+    c1, p1 = oracle.kv4_new_cache(3, 9)
+    oracle.kv4_append(x, 0, 0.95, c1, p1, rotate=True)
+    dense = oracle.rotate(x.reshape(-1, D).astype(np.float64), oracle.ROT_WHT, D, 1).reshape(x.shape)
+    fast = np.stack([oracle.fwht_f32(v) for v in x.reshape(-1, D)]).reshape(x.shape)
+    assert np.allclose(fast, dense, rtol=0, atol=1e-5 * np.abs(dense).max())
+    c2, p2 = _quantise(fast)
+    assert np.array_equal(c1, c2) and np.array_equal(p1, p2)
+    # scores are unchanged when queries and keys are both rotated (up to the quantisation of the keys):
+    # the dequantised rotated keys stay within half a step of the rotated vectors inside the clip range
+    deq = oracle.kv4_dequant(c1, p1, 0, 9)
+    s = _f16(oracle.kv4_params(p1)[0]).T[:, :, None]
+    inside = (dense >= 0.95 * dense.min(axis=-1, keepdims=True)) & (dense <= 0.95 * dense.max(axis=-1, keepdims=True))
+    assert np.all(np.abs(deq - dense)[inside] <= (0.5 + 1e-3) * np.broadcast_to(s, dense.shape)[inside] + 1e-6)
+    q = rcp_synth.query_vectors(12, "q", 3).astype(np.float64)
+    qr = oracle.rotate(q, oracle.ROT_WHT, D, 1)
+    assert np.allclose(np.einsum("hd,thd->th", qr, dense), np.einsum("hd,thd->th", q, x.astype(np.float64)), atol=1e-9)
+    # a constant vector rotates onto its first coordinate
+    one = np.full((1, 1, D), 0.5, dtype=np.float32)
+    c3, p3 = oracle.kv4_new_cache(1, 1)
+    oracle.kv4_append(one, 0, 1.0, c3, p3, rotate=True)
+    d3 = oracle.kv4_dequant(c3, p3, 0, 1)[0, 0]
+    assert abs(d3[0] - 0.5 * np.sqrt(128.0)) <= 0.5 * _f16(oracle.kv4_params(p3)[0])[0, 0] and np.all(d3[1:] == 0.0)
+
+
 def _cache(seed, S, H, S_max=None):
     k = rcp_synth.kv_vectors(seed, "k", S, H).astype(np.float32)
     v = rcp_synth.kv_vectors(seed, "v", S, H).astype(np.float32)
