@@ -558,6 +558,53 @@ def main():
                         "append_one_token_us": round(sa * 1e6, 3)}
         del kcaches
 
+    # The linear layers and the KV-cache launches of a W2A4KV4 decode step chained as in a decoder layer, 4096
+    # cached tokens: q|k|v GEMV -> R3 on the query heads -> append k (rotated) and v -> attention over the 4-bit
+    # cache -> o GEMV on its output -> gate|up GEMV -> Kronecker rotation -> down GEMV: 11 launches per layer.
+    # (RoPE, norms, the gated activation and the residual adds are not part of this library: the o input is the
+    # attention output itself, the other GEMVs read the synthetic activations of the headline step.)
+    kv_layer = None
+    if not args.step_only:
+        S_ctx = 4096
+        kx = torch.from_numpy(rcp_synth.kv_vectors(args.seed, "layer_k", S_ctx, Hh)).to(dev)
+        vx = torch.from_numpy(rcp_synth.kv_vectors(args.seed, "layer_v", S_ctx, Hh)).to(dev)
+        kc0, kp0 = rcp.kv4_new_cache(Hh, S_ctx, dev)
+        vc0, vp0 = rcp.kv4_new_cache(Hh, S_ctx, dev)
+        rcp.kv4_append(kx, 0, kc0, kp0, rotate=True)
+        rcp.kv4_append(vx, 0, vc0, vp0)
+        lcaches = [(kc0.clone(), kp0.clone(), vc0.clone(), vp0.clone()) for _ in range(L)]
+        rot_head = rcp.Rotation.wht(128)
+        q_rot = torch.empty((Hh, 128), dtype=torch.float32, device=dev)
+        attn_out = torch.empty((Hh, 128), dtype=torch.float32, device=dev)
+        wsl = torch.empty(rcp.kv4_workspace_bytes(Hh, S_ctx), dtype=torch.uint8, device=dev)
+        i_qkv, i_o, i_gu, i_down = 0, 1, 2, 3
+        assert launches[i_qkv][1] == 3 * HIDDEN and launches[i_o][1:3] == (HIDDEN, HIDDEN) and launches[i_down][3]
+        qkv = outs[i_qkv]
+
+        def kvstep():
+            for l in range(L):
+                pk, cb = layers[l][i_qkv]
+                rcp.quant_w2a4_gemv(pk, cb, 3 * HIDDEN, HIDDEN, xs[i_qkv], 1.0, out=qkv)
+                rcp.rotate_act(qkv[0, :HIDDEN].view(Hh, 128), rot_head, y_out=q_rot)
+                kc, kp, vc, vp = lcaches[l]
+                rcp.kv4_append(qkv[0, HIDDEN:2 * HIDDEN].view(1, Hh, 128), S_ctx - 1, kc, kp, rotate=True)
+                rcp.kv4_append(qkv[0, 2 * HIDDEN:].view(1, Hh, 128), S_ctx - 1, vc, vp)
+                rcp.kv4_attn_decode(q_rot, S_ctx, kc, kp, vc, vp, 0.08838834764831845, out=attn_out, workspace=wsl)
+                pk, cb = layers[l][i_o]
+                rcp.quant_w2a4_gemv(pk, cb, HIDDEN, HIDDEN, attn_out.view(1, HIDDEN), 1.0, out=outs[i_o])
+                pk, cb = layers[l][i_gu]
+                rcp.quant_w2a4_gemv(pk, cb, launches[i_gu][1], HIDDEN, xs[i_gu], 1.0, out=outs[i_gu])
+                rcp.rotate_act(xs[i_down], rot_down, y_out=ybuf)
+                pk, cb = layers[l][i_down]
+                rcp.quant_w2a4_gemv(pk, cb, HIDDEN, INTER, ybuf, 1.0, out=outs[i_down])
+        kvstep()
+        fn = capture(kvstep)
+        fn()
+        s = timed(torch, fn, max(3, args.steps // 2))
+        kv_layer = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2), "launches_per_layer": 11,
+                    "cached_tokens": S_ctx, "heads": Hh}
+        del lcaches
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
     if os.path.exists(tpath):
@@ -597,6 +644,7 @@ def main():
         "w3a4": w3,
         "w3a4_step": w3_step,
         "kv4_attention_32_heads": kv4,
+        "w2a4kv4_layer_launches": kv_layer,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),
