@@ -558,6 +558,44 @@ def main():
                         "append_one_token_us": round(sa * 1e6, 3)}
         del kcaches
 
+    # several sequences in one call (pooled caches), 4 layers' worth of distinct caches per measurement
+    kv4_batched = {}
+    for B, S in (() if args.step_only else ((8, 1024), (16, 1024), (8, 4096), (16, 4096))):
+        nl = 4
+        pools = []
+        for _ in range(nl):
+            kc = torch.randint(0, 256, (B * Hh, S, 64), dtype=torch.uint8, device=dev)
+            vc = torch.randint(0, 256, (B * Hh, S, 64), dtype=torch.uint8, device=dev)
+            par = torch.empty((B * Hh, S, 2), dtype=torch.int16, device=dev)
+            par[..., 0] = 0x2C00   # step 1/16
+            par[..., 1] = 8
+            kp = par.view(torch.uint8).reshape(B * Hh, S, 4).contiguous()
+            pools.append((kc, kp, vc, kp.clone()))
+        qb = torch.randn((B, Hh, 128), device=dev).to(torch.float16)
+        ob = torch.empty((B, Hh, 128), dtype=torch.float32, device=dev)
+        wsb = torch.empty(B * rcp.kv4_workspace_bytes(Hh, S), dtype=torch.uint8, device=dev)
+        newtok = torch.randn((B, Hh, 128), device=dev).to(torch.float16)
+
+        def bsweep(pools=pools, qb=qb, ob=ob, wsb=wsb, B=B, S=S):
+            for c in pools:
+                rcp.kv4_attn_decode_batched(qb, [S] * B, *c, 0.08838834764831845, out=ob, workspace=wsb)
+        bsweep()
+        fn = capture(bsweep)
+        fn()
+        s = timed(torch, fn, reps) / nl
+
+        def basweep(pools=pools, newtok=newtok, B=B, S=S):
+            for c in pools:
+                rcp.kv4_append_batched(newtok, [S - 1] * B, c[0], c[1], rotate=True)
+        basweep()
+        fn = capture(basweep)
+        fn()
+        sa = timed(torch, fn, reps) / nl
+        bb = 2 * B * S * Hh * 68
+        kv4_batched[f"B{B}_S{S}"] = {"attn_us": round(s * 1e6, 3), "attn_GBps": round(bb / s / 1e9, 1),
+                                    "append_us": round(sa * 1e6, 3)}
+        del pools
+
     # The linear layers and the KV-cache launches of a W2A4KV4 decode step chained as in a decoder layer, 4096
     # cached tokens: q|k|v GEMV -> R3 on the query heads -> append k (rotated) and v -> attention over the 4-bit
     # cache -> o GEMV on its output -> gate|up GEMV -> Kronecker rotation -> down GEMV: 11 launches per layer.
@@ -644,6 +682,7 @@ def main():
         "w3a4": w3,
         "w3a4_step": w3_step,
         "kv4_attention_32_heads": kv4,
+        "kv4_attention_batched": kv4_batched,
         "w2a4kv4_layer_launches": kv_layer,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},

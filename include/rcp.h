@@ -412,6 +412,25 @@ int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int
                         float softmax_scale, void* out, rcp_dtype out_dtype,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* Several sequences at once (the small-batch decode of Section 4.4's GEMM discussion applied to the cache):
+ * B <= RCP_MAX_M sequences share pooled buffers, sequence b owning heads b*H .. b*H + H - 1 of
+ * codes [B*H][S_max][64] / params [B*H][S_max][4].  pos_host / S_host are HOST arrays of B ints, read
+ * before the call returns.
+ * rcp_kv4_append_batched: x is [B][H][128]; row b is the new token of sequence b and goes to its position
+ *   pos_host[b] (0 <= pos_host[b] < S_max, else RCP_ERR_SHAPE).  Arithmetic as rcp_kv4_append.
+ * rcp_kv4_attn_decode_batched: q and out are [B][H_q][128]; sequence b attends to its first S_host[b] tokens
+ *   (1 <= S_host[b] <= S_max).  Each row equals what rcp_kv4_attn_decode gives for that sequence alone
+ *   (bit for bit when the "kv_tokens" option fixes the split length).  workspace: B * rcp_kv4_workspace_bytes(H_q, max_b S_host[b])
+ *   bytes.  H_q <= 4095. */
+int rcp_kv4_append_batched(const void* x, rcp_dtype x_dtype, int B, int H, int S_max, const int* pos_host,
+                           int rotate, float clip_ratio, void* codes, void* params, void* stream);
+int rcp_kv4_attn_decode_batched(const void* q, rcp_dtype q_dtype, int B, int H_q, int H_kv, int S_max,
+                                const int* S_host,
+                                const void* k_codes, const void* k_params,
+                                const void* v_codes, const void* v_params,
+                                float softmax_scale, void* out, rcp_dtype out_dtype,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -127,6 +127,12 @@ def lib():
         L.rcp_kv4_workspace_bytes.argtypes = [ci, ci]
         L.rcp_kv4_append.restype = ci
         L.rcp_kv4_append.argtypes = [vp, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp]
+        ip = ctypes.POINTER(ctypes.c_int)
+        L.rcp_kv4_append_batched.restype = ci
+        L.rcp_kv4_append_batched.argtypes = [vp, ci, ci, ci, ci, ip, ci, ctypes.c_float, vp, vp, vp]
+        L.rcp_kv4_attn_decode_batched.restype = ci
+        L.rcp_kv4_attn_decode_batched.argtypes = [vp, ci, ci, ci, ci, ci, ip, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp,
+                                                  ctypes.c_size_t, vp]
         L.rcp_kv4_attn_decode.restype = ci
         L.rcp_kv4_attn_decode.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp,
                                           ctypes.c_size_t, vp]
@@ -565,4 +571,51 @@ def kv4_attn_decode(q, S, k_codes, k_params, v_codes, v_params, softmax_scale, o
                                      ctypes.c_float(softmax_scale), _dev(out, "out"), _DTYPES[out.dtype],
                                      _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                      _stream()))
+    return out
+
+
+def kv4_append_batched(x, positions, codes, params, clip_ratio=0.95, rotate=False):
+    """One new token for each of B sequences: x [B, H, 128] into the pooled cache codes [B*H, S_max, 64] /
+    params [B*H, S_max, 4], sequence b at positions[b] (a host list of ints)."""
+    if x.dim() != 3 or x.shape[2] != KV_HEAD_DIM or not x.is_contiguous():
+        raise ValueError("x must be contiguous [B, H, 128]")
+    B, H = int(x.shape[0]), int(x.shape[1])
+    if len(positions) != B:
+        raise ValueError("one position per sequence")
+    if codes.dtype != torch.uint8 or params.dtype != torch.uint8 or codes.dim() != 3 or codes.shape[0] != B * H or \
+            codes.shape[2] != KV_HEAD_DIM // 2 or tuple(params.shape) != (B * H, codes.shape[1], 4) or \
+            not codes.is_contiguous() or not params.is_contiguous():
+        raise ValueError("codes must be uint8 [B*H, S_max, 64] and params uint8 [B*H, S_max, 4], contiguous")
+    pos = (ctypes.c_int * B)(*[int(p) for p in positions])
+    _check(lib().rcp_kv4_append_batched(_dev(x, "x"), _DTYPES[x.dtype], B, H, int(codes.shape[1]), pos, int(bool(rotate)),
+                                        ctypes.c_float(clip_ratio), _dev(codes, "codes"), _dev(params, "params"), _stream()))
+
+
+def kv4_attn_decode_batched(q, lengths, k_codes, k_params, v_codes, v_params, softmax_scale, out=None,
+                            out_dtype=torch.float32, workspace=None):
+    """B sequences: q [B, H_q, 128], sequence b against its first lengths[b] cached tokens of the pooled cache
+    [B*H_kv, S_max, ...] -> out [B, H_q, 128]."""
+    if q.dim() != 3 or q.shape[2] != KV_HEAD_DIM or not q.is_contiguous():
+        raise ValueError("q must be contiguous [B, H_q, 128]")
+    B, H_q = int(q.shape[0]), int(q.shape[1])
+    if len(lengths) != B or k_codes.shape[0] % B != 0:
+        raise ValueError("one length per sequence, and a pooled cache of B * H_kv heads")
+    H_kv, S_max = int(k_codes.shape[0]) // B, int(k_codes.shape[1])
+    for c, p in ((k_codes, k_params), (v_codes, v_params)):
+        if c.dtype != torch.uint8 or p.dtype != torch.uint8 or tuple(c.shape) != (B * H_kv, S_max, KV_HEAD_DIM // 2) or \
+                tuple(p.shape) != (B * H_kv, S_max, 4) or not c.is_contiguous() or not p.is_contiguous():
+            raise ValueError("cache buffers must be uint8 [B*H_kv, S_max, 64] / [B*H_kv, S_max, 4], contiguous")
+    if out is None:
+        out = torch.empty((B, H_q, KV_HEAD_DIM), dtype=out_dtype, device=q.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < B * H_q * KV_HEAD_DIM:
+        raise ValueError("out must be float16 or float32 [B, H_q, 128]")
+    if workspace is None:
+        workspace = torch.empty(max(B * kv4_workspace_bytes(H_q, max(int(n) for n in lengths)), 16), dtype=torch.uint8,
+                                device=q.device)
+    lens = (ctypes.c_int * B)(*[int(n) for n in lengths])
+    _check(lib().rcp_kv4_attn_decode_batched(_dev(q, "q"), _DTYPES[q.dtype], B, H_q, H_kv, S_max, lens,
+                                             _dev(k_codes, "k_codes"), _dev(k_params, "k_params"), _dev(v_codes, "v_codes"),
+                                             _dev(v_params, "v_params"), ctypes.c_float(softmax_scale), _dev(out, "out"),
+                                             _DTYPES[out.dtype], _dev(workspace, "workspace"),
+                                             workspace.numel() * workspace.element_size(), _stream()))
     return out

@@ -508,7 +508,27 @@ int rcp_kv4_append(const void* x, rcp_dtype x_dtype, int n_tokens, int H, int S_
         return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_append: clip_ratio must be in (0, 1]");
     if (!aligned16(x) || !aligned16(codes) || !aligned16(params))
         return fail(RCP_ERR_ALIGN, "rcp_kv4_append: device buffers must be 16-byte aligned");
-    return launch_kv4_append(x, x_dtype, n_tokens, H, S_max, pos, rotate != 0, clip_ratio, codes, params,
+    return launch_kv4_append(x, x_dtype, n_tokens, H, S_max, pos, nullptr, rotate != 0, clip_ratio, codes, params,
+                             static_cast<hipStream_t>(stream));
+}
+
+int rcp_kv4_append_batched(const void* x, rcp_dtype x_dtype, int B, int H, int S_max, const int* pos_host, int rotate,
+                           float clip_ratio, void* codes, void* params, void* stream)
+{
+    if (!x || !codes || !params || !pos_host) return fail(RCP_ERR_NULL, "rcp_kv4_append_batched: NULL pointer argument");
+    if (x_dtype != RCP_F16 && x_dtype != RCP_BF16 && x_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_append_batched: unknown x_dtype %d", static_cast<int>(x_dtype));
+    if (B < 1 || B > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_kv4_append_batched: B=%d outside 1..%d", B, RCP_MAX_M);
+    if (H <= 0 || S_max <= 0 || H > 0x7fffffff / RCP_KV_HEAD_DIM / RCP_MAX_M)
+        return fail(RCP_ERR_SHAPE, "rcp_kv4_append_batched: H=%d, S_max=%d out of range", H, S_max);
+    for (int b = 0; b < B; ++b)
+        if (pos_host[b] < 0 || pos_host[b] >= S_max)
+            return fail(RCP_ERR_SHAPE, "rcp_kv4_append_batched: position %d of sequence %d outside 0..%d", pos_host[b], b, S_max - 1);
+    if (!(clip_ratio > 0.0f) || clip_ratio > 1.0f)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_append_batched: clip_ratio must be in (0, 1]");
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(params))
+        return fail(RCP_ERR_ALIGN, "rcp_kv4_append_batched: device buffers must be 16-byte aligned");
+    return launch_kv4_append(x, x_dtype, B, H, S_max, 0, pos_host, rotate != 0, clip_ratio, codes, params,
                              static_cast<hipStream_t>(stream));
 }
 
@@ -534,8 +554,43 @@ int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int
     if (workspace == nullptr || workspace_bytes < need)
         return fail(RCP_ERR_WORKSPACE, "rcp_kv4_attn_decode: workspace of %zu bytes needed, %zu given", need,
                     workspace ? workspace_bytes : static_cast<size_t>(0));
-    return launch_kv4_attn(q, q_dtype, H_q, H_kv, S_max, S, k_codes, k_params, v_codes, v_params, softmax_scale, out,
-                           out_dtype, workspace, static_cast<hipStream_t>(stream));
+    return launch_kv4_attn(q, q_dtype, 1, H_q, H_kv, S_max, S, nullptr, k_codes, k_params, v_codes, v_params, softmax_scale,
+                           out, out_dtype, workspace, static_cast<hipStream_t>(stream));
+}
+
+int rcp_kv4_attn_decode_batched(const void* q, rcp_dtype q_dtype, int B, int H_q, int H_kv, int S_max, const int* S_host,
+                                const void* k_codes, const void* k_params, const void* v_codes, const void* v_params,
+                                float softmax_scale, void* out, rcp_dtype out_dtype, void* workspace,
+                                size_t workspace_bytes, void* stream)
+{
+    if (!q || !k_codes || !k_params || !v_codes || !v_params || !out || !S_host)
+        return fail(RCP_ERR_NULL, "rcp_kv4_attn_decode_batched: NULL pointer argument");
+    if (q_dtype != RCP_F16 && q_dtype != RCP_BF16 && q_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_attn_decode_batched: unknown q_dtype %d", static_cast<int>(q_dtype));
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_attn_decode_batched: out_dtype must be RCP_F16 or RCP_F32");
+    if (B < 1 || B > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_kv4_attn_decode_batched: B=%d outside 1..%d", B, RCP_MAX_M);
+    if (H_q <= 0 || H_kv <= 0 || H_q % H_kv != 0 || H_q > 65535 / RCP_MAX_M)
+        return fail(RCP_ERR_SHAPE, "rcp_kv4_attn_decode_batched: H_q=%d must be a positive multiple of H_kv=%d (at most %d)", H_q,
+                    H_kv, 65535 / RCP_MAX_M);
+    if (S_max <= 0) return fail(RCP_ERR_SHAPE, "rcp_kv4_attn_decode_batched: S_max=%d", S_max);
+    int longest = 0;
+    for (int b = 0; b < B; ++b) {
+        if (S_host[b] < 1 || S_host[b] > S_max)
+            return fail(RCP_ERR_SHAPE, "rcp_kv4_attn_decode_batched: length %d of sequence %d outside 1..S_max=%d", S_host[b], b, S_max);
+        longest = S_host[b] > longest ? S_host[b] : longest;
+    }
+    if (longest > RCP_KV_MAX_S)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_attn_decode_batched: length %d exceeds RCP_KV_MAX_S=%d", longest, RCP_KV_MAX_S);
+    if (!aligned16(q) || !aligned16(k_codes) || !aligned16(k_params) || !aligned16(v_codes) || !aligned16(v_params) ||
+        !aligned16(out) || !aligned16(workspace))
+        return fail(RCP_ERR_ALIGN, "rcp_kv4_attn_decode_batched: device buffers must be 16-byte aligned");
+    const size_t need = static_cast<size_t>(B) * kv4_workspace_bytes(H_q, longest);
+    if (workspace == nullptr || workspace_bytes < need)
+        return fail(RCP_ERR_WORKSPACE, "rcp_kv4_attn_decode_batched: workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : static_cast<size_t>(0));
+    return launch_kv4_attn(q, q_dtype, B, H_q, H_kv, S_max, longest, S_host, k_codes, k_params, v_codes, v_params,
+                           softmax_scale, out, out_dtype, workspace, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

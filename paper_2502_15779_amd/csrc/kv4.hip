@@ -15,6 +15,12 @@ namespace rcp {
 
 constexpr int KV_D = 128;
 
+// Batched calls: per-sequence lengths (attention) or positions (append) travel by value.
+struct KvBatch {
+    int v[RCP_MAX_M];
+    int H_q, H_kv;
+};
+
 // ---------------------------------------------------------------------------------------
 // append: quantise n_tokens x H head vectors into cache positions pos ...
 // Sixteen lanes (one DPP row) own a head vector, eight consecutive elements each.
@@ -22,10 +28,12 @@ constexpr int KV_D = 128;
 // ascending stride order (1, 2, 4 in registers, 8 .. 64 between the sixteen lanes), each output
 // one IEEE add or subtract, then one multiplication by (float)(1/sqrt(128)).
 // ---------------------------------------------------------------------------------------
-template <int DT, bool ROT>
+// BATCHED: row i of x belongs to sequence i (one new token each), whose cache starts at head
+// i * H of the pooled cache and whose position is batch.v[i].
+template <int DT, bool ROT, bool BATCHED>
 __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict__ x, int rows, int H, int S_max, int pos,
                                                          float clip_ratio, uint32_t* __restrict__ codes,
-                                                         uint32_t* __restrict__ params)
+                                                         uint32_t* __restrict__ params, KvBatch batch)
 {
     // every product and difference below is rounded on its own (hi_c - lo_c must not become a
     // fused multiply-add: for a constant vector it has to be exactly zero).  The pragma covers
@@ -93,7 +101,8 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict_
     }
     if (have) {
         const int i = row / H, h = row - i * H;
-        const size_t slot = static_cast<size_t>(h) * S_max + (pos + i);
+        const size_t slot = BATCHED ? static_cast<size_t>(row) * S_max + batch.v[i]
+                                    : static_cast<size_t>(h) * S_max + (pos + i);
         codes[slot * 16 + l] = word;
         if (l == 0) params[slot] = static_cast<uint32_t>(sb) | (static_cast<uint32_t>(z & 0xffff) << 16);
     }
@@ -144,20 +153,30 @@ __device__ __forceinline__ float row_tokens_sum(float v)
     return v;
 }
 
-template <int QDT, int ITERS>
+// BATCHED: blockIdx.z is the sequence; its length is batch.v[z], its caches start at head z * H_kv of
+// the pooled buffers, its query and partial results at row z * H_q; workgroups past its end leave.
+template <int QDT, int ITERS, bool BATCHED>
 __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __restrict__ q, int S, int S_max, int rep, int splits,
                                                               float softmax_scale, const u32x4* __restrict__ k_codes,
                                                               const uint32_t* __restrict__ k_params,
                                                               const u32x4* __restrict__ v_codes,
                                                               const uint32_t* __restrict__ v_params,
-                                                              float* __restrict__ part)
+                                                              float* __restrict__ part, KvBatch batch)
 {
     __shared__ float red[4][KV_D];
     __shared__ float wmax[4], lrow[4][4], zrow[4][4];
     constexpr int L = 64 * ITERS;
-    const int split = blockIdx.x, h = blockIdx.y, hk = h / rep;
+    const int split = blockIdx.x;
+    int h = blockIdx.y, hk = h / rep;
     const int tid = threadIdx.x, slot = tid >> 2, piece = tid & 3, wave = tid >> 6;
     const int t0 = split * L;
+    if constexpr (BATCHED) {
+        const int seq = blockIdx.z;
+        S = batch.v[seq];
+        if (t0 >= S) return;  // the whole workgroup: this sequence has fewer splits
+        h += seq * batch.H_q;
+        hk += seq * batch.H_kv;
+    }
     const int t_end = min(S, t0 + L);
     const size_t head_base = static_cast<size_t>(hk) * S_max;
 
@@ -299,16 +318,24 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
 // against its own running maximum; the groups meet in LDS and are merged the same way.
 constexpr int KV_CT = 1024;
 
-template <bool OUT_F16>
+// BATCHED: blockIdx.x = sequence * H_q + head; a sequence of length batch.v[z] has written only its
+// first ceil(length / L) of the `splits` slots of each head.
+template <bool OUT_F16, bool BATCHED>
 __global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restrict__ part, int splits, int groups,
-                                                            void* __restrict__ out)
+                                                            void* __restrict__ out, int L, KvBatch batch)
 {
     __shared__ float red[KV_CT / KV_D][KV_D];
     __shared__ float dred[KV_CT / KV_D], mred[KV_CT / KV_D];
     const int h = blockIdx.x, tid = threadIdx.x, j = tid & (KV_D - 1), g = tid >> 7;
     const float* src = part + static_cast<size_t>(h) * splits * KV_PART;
+    if constexpr (BATCHED) {
+        // the sequence's own number of splits and thread groups, so that the merge runs in the same order
+        // as in a call for this sequence alone
+        splits = (batch.v[h / batch.H_q] + L - 1) / L;
+        groups = min(groups, (splits + 3) / 4);
+    }
     float M = -INFINITY, num = 0.0f, den = 0.0f;
-    for (int i0 = g; i0 < splits; i0 += 4 * groups) {
+    for (int i0 = g < groups ? g : splits; i0 < splits; i0 += 4 * groups) {
         float mi[4], li[4], ai[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -356,32 +383,39 @@ __global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restr
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-// Tokens per workgroup: 128 up to 4096 tokens x 32 heads, 256 beyond (measured: 64 never wins,
-// the per-workgroup reduction then weighs too much; 256 wins once the device is full anyway).
-static int kv4_split_length(int H_q, int S)
-{
-    if (options().kv_tokens != 0) return options().kv_tokens;
-    return static_cast<long long>(S) * H_q <= 131072 ? 128 : KV_MAX_L;
-}
-
+// Tokens per workgroup (chosen in launch_kv4_attn): 128 up to 4096 tokens x 32 heads in total, 256 beyond
+// (measured: 64 never wins, the per-workgroup reduction then weighs too much; 256 wins once the device is
+// full anyway); the "kv_tokens" option overrides.
 size_t kv4_workspace_bytes(int H_q, int S)
 {
     const int splits = (S + 63) / 64;  // the most any split length needs
     return static_cast<size_t>(H_q) * splits * KV_PART * sizeof(float);
 }
 
-int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, bool rotate, float clip_ratio,
-                      void* codes, void* params, hipStream_t st)
+// positions == nullptr: n_tokens tokens of one sequence from `pos` on; otherwise one token for each of
+// n_tokens sequences of a pooled cache, at positions[i]
+int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, const int* positions, bool rotate,
+                      float clip_ratio, void* codes, void* params, hipStream_t st)
 {
     const int rows = n_tokens * H;
     if (rows == 0) return RCP_OK;
     const unsigned grid = static_cast<unsigned>((rows + 15) / 16);
     auto* c = static_cast<uint32_t*>(codes);
     auto* p = static_cast<uint32_t*>(params);
-#define RCP_KV_APPEND(DT)                                                                                      \
-    do {                                                                                                       \
-        if (rotate) kv4_append_kernel<DT, true><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p); \
-        else kv4_append_kernel<DT, false><<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p);      \
+    KvBatch batch = {};
+    const bool batched = positions != nullptr;
+    if (batched)
+        for (int i = 0; i < n_tokens; ++i) batch.v[i] = positions[i];
+    auto launch = [&](auto kernel) { kernel<<<grid, 256, 0, st>>>(x, rows, H, S_max, pos, clip_ratio, c, p, batch); };
+#define RCP_KV_APPEND(DT)                                                   \
+    do {                                                                    \
+        if (batched) {                                                      \
+            if (rotate) launch(&kv4_append_kernel<DT, true, true>);         \
+            else launch(&kv4_append_kernel<DT, false, true>);               \
+        } else {                                                            \
+            if (rotate) launch(&kv4_append_kernel<DT, true, false>);        \
+            else launch(&kv4_append_kernel<DT, false, false>);              \
+        }                                                                   \
     } while (0)
     if (dt == RCP_F32) RCP_KV_APPEND(RCP_F32);
     else if (dt == RCP_F16) RCP_KV_APPEND(RCP_F16);
@@ -390,26 +424,47 @@ int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_ma
     return check_launch("rcp_kv4_append");
 }
 
-int launch_kv4_attn(const void* q, rcp_dtype q_dt, int H_q, int H_kv, int S_max, int S, const void* k_codes,
-                    const void* k_params, const void* v_codes, const void* v_params, float softmax_scale, void* out,
-                    rcp_dtype out_dt, void* workspace, hipStream_t st)
+// lengths == nullptr: one sequence of S tokens; otherwise B sequences of a pooled cache, lengths[b] tokens each
+int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int S_max, int S, const int* lengths,
+                    const void* k_codes, const void* k_params, const void* v_codes, const void* v_params,
+                    float softmax_scale, void* out, rcp_dtype out_dt, void* workspace, hipStream_t st)
 {
-    const int L = kv4_split_length(H_q, S);
+    const bool batched = lengths != nullptr;
+    KvBatch batch = {};
+    long long total = S;
+    if (batched) {
+        S = 0;
+        total = 0;
+        for (int b = 0; b < B; ++b) {
+            batch.v[b] = lengths[b];
+            S = lengths[b] > S ? lengths[b] : S;  // the longest sequence sizes the grid
+            total += lengths[b];
+        }
+        batch.H_q = H_q;
+        batch.H_kv = H_kv;
+    }
+    const int L = options().kv_tokens != 0 ? options().kv_tokens : (total * H_q <= 131072 ? 128 : KV_MAX_L);
     const int splits = (S + L - 1) / L;
-    const dim3 grid(static_cast<unsigned>(splits), static_cast<unsigned>(H_q));
+    const dim3 grid(static_cast<unsigned>(splits), static_cast<unsigned>(H_q), static_cast<unsigned>(batched ? B : 1));
     const int rep = H_q / H_kv;
     auto* kc = static_cast<const u32x4*>(k_codes);
     auto* vc = static_cast<const u32x4*>(v_codes);
     auto* kp = static_cast<const uint32_t*>(k_params);
     auto* vp = static_cast<const uint32_t*>(v_params);
     auto* part = static_cast<float*>(workspace);
-#define RCP_KV_LAUNCH(QDT, ITERS) \
-    kv4_attn_kernel<QDT, ITERS><<<grid, KV_THREADS, 0, st>>>(q, S, S_max, rep, splits, softmax_scale, kc, kp, vc, vp, part)
-#define RCP_KV_DISPATCH(QDT)             \
-    do {                                 \
+    auto launch = [&](auto kernel) {
+        kernel<<<grid, KV_THREADS, 0, st>>>(q, S, S_max, rep, splits, softmax_scale, kc, kp, vc, vp, part, batch);
+    };
+#define RCP_KV_LAUNCH(QDT, ITERS)                                        \
+    do {                                                                 \
+        if (batched) launch(&kv4_attn_kernel<QDT, ITERS, true>);         \
+        else launch(&kv4_attn_kernel<QDT, ITERS, false>);                \
+    } while (0)
+#define RCP_KV_DISPATCH(QDT)                      \
+    do {                                          \
         if (L == 64) RCP_KV_LAUNCH(QDT, 1);       \
         else if (L == 128) RCP_KV_LAUNCH(QDT, 2); \
-        else RCP_KV_LAUNCH(QDT, 4);      \
+        else RCP_KV_LAUNCH(QDT, 4);               \
     } while (0)
     if (q_dt == RCP_F32) RCP_KV_DISPATCH(RCP_F32);
     else if (q_dt == RCP_F16) RCP_KV_DISPATCH(RCP_F16);
@@ -420,8 +475,15 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int H_q, int H_kv, int S_max,
     if (rc != RCP_OK) return rc;
     int groups = (splits + 3) / 4;
     if (groups > KV_CT / KV_D) groups = KV_CT / KV_D;
-    if (out_dt == RCP_F16) kv4_combine_kernel<true><<<H_q, groups * KV_D, 0, st>>>(part, splits, groups, out);
-    else kv4_combine_kernel<false><<<H_q, groups * KV_D, 0, st>>>(part, splits, groups, out);
+    const unsigned cgrid = static_cast<unsigned>(H_q) * (batched ? B : 1);
+    auto combine = [&](auto kernel) { kernel<<<cgrid, groups * KV_D, 0, st>>>(part, splits, groups, out, L, batch); };
+    if (batched) {
+        if (out_dt == RCP_F16) combine(&kv4_combine_kernel<true, true>);
+        else combine(&kv4_combine_kernel<false, true>);
+    } else {
+        if (out_dt == RCP_F16) combine(&kv4_combine_kernel<true, false>);
+        else combine(&kv4_combine_kernel<false, false>);
+    }
     return check_launch("rcp_kv4_attn_decode(combine)");
 }
 

@@ -33,7 +33,8 @@ def test_every_declared_function_is_exported(lib):
             "rcp_pack_weights_grouped", "rcp_unpack_indices_grouped", "rcp_w2a4_gemv_grouped",
             "rcp_w2a16_gemv", "rcp_quant_w2a4_gemv_grouped", "rcp_w2a4_gemm_grouped",
             "rcp_rotate_quant_w2a4_gemv", "rcp_pack_weights_w3", "rcp_unpack_indices_w3", "rcp_w3a4_gemv",
-            "rcp_kv4_workspace_bytes", "rcp_kv4_append", "rcp_kv4_attn_decode", "rcp_quant_w3a4_gemv"} <= set(names)
+            "rcp_kv4_workspace_bytes", "rcp_kv4_append", "rcp_kv4_attn_decode", "rcp_quant_w3a4_gemv",
+            "rcp_kv4_append_batched", "rcp_kv4_attn_decode_batched"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -194,6 +195,26 @@ def test_argument_errors_need_no_gpu(lib):
     assert at(fake, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, None, 0, None) == -5
     assert at(fake, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, 4 * 132 * 4 - 1, None) == -5
     assert b"workspace" in lib.rcp_last_error()
+    ip = ctypes.POINTER(ctypes.c_int)
+    i3 = ctypes.c_int * 3
+    apb = lib.rcp_kv4_append_batched
+    apb.argtypes = [vp, ci, ci, ci, ci, ip, ci, ctypes.c_float, vp, vp, vp]
+    assert apb(fake, 0, 3, 2, 8, None, 0, 0.95, fake, fake, None) == -1
+    assert apb(fake, 0, 17, 2, 8, i3(0, 1, 2), 0, 0.95, fake, fake, None) == -2
+    assert apb(fake, 0, 3, 2, 8, i3(0, 8, 2), 0, 0.95, fake, fake, None) == -2       # position past the end
+    assert apb(fake, 0, 3, 2, 8, i3(0, -1, 2), 0, 0.95, fake, fake, None) == -2
+    assert apb(fake, 0, 3, 2, 8, i3(0, 1, 2), 0, 2.0, fake, fake, None) == -4
+    assert apb(fake, 0, 3, 2, 8, i3(0, 1, 2), 0, 0.95, odd, fake, None) == -3
+    atb = lib.rcp_kv4_attn_decode_batched
+    atb.argtypes = [vp, ci, ci, ci, ci, ci, ip, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp, ctypes.c_size_t, vp]
+    assert atb(fake, 0, 3, 4, 4, 8, None, fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -1
+    assert atb(fake, 0, 0, 4, 4, 8, i3(1, 2, 3), fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -2
+    assert atb(fake, 0, 3, 4, 4, 8, i3(1, 9, 3), fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -2
+    assert atb(fake, 0, 3, 4, 4, 8, i3(1, 0, 3), fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -2
+    assert atb(fake, 0, 3, 4, 3, 8, i3(1, 2, 3), fake, fake, fake, fake, 0.1, fake, 1, fake, big, None) == -2
+    assert atb(fake, 0, 3, 4, 4, 8, i3(1, 2, 3), fake, fake, fake, fake, 0.1, fake, 2, fake, big, None) == -4
+    assert atb(fake, 0, 3, 4, 4, 8, i3(1, 2, 3), fake, fake, fake, fake, 0.1, fake, 1, fake, 3 * 4 * 132 * 4 - 1, None) == -5
+    assert atb(fake, 0, 3, 4, 4, 8, i3(1, 2, 3), fake, fake, fake, odd, 0.1, fake, 1, fake, big, None) == -3
     ws = lib.rcp_act_workspace_bytes
     ws.restype = ctypes.c_size_t
     ws.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot)]

@@ -255,3 +255,68 @@ def test_workspace_is_reusable_and_too_small_is_refused():
         rcp.kv4_attn_decode(qd, S, *cache, 0.1, workspace=ws[:need - 16])
     with pytest.raises(rcp.RcpError):
         rcp.kv4_attn_decode(qd, S + 1, *cache, 0.1)
+
+
+# ---- several sequences at once -------------------------------------------------------------------------
+def _pooled(seed, lengths, H_kv, S_max):
+    """Pooled device caches of len(lengths) sequences filled through single-sequence appends, and the host
+    copies per sequence for the oracle."""
+    B = len(lengths)
+    kc, kp = rcp.kv4_new_cache(B * H_kv, S_max, DEV)
+    vc, vp = rcp.kv4_new_cache(B * H_kv, S_max, DEV)
+    for b, S in enumerate(lengths):
+        k = rcp_synth.kv_vectors(seed, f"k{b}", S, H_kv)
+        v = rcp_synth.kv_vectors(seed, f"v{b}", S, H_kv)
+        sl = slice(b * H_kv, (b + 1) * H_kv)
+        rcp.kv4_append(_t(k), 0, kc[sl], kp[sl], rotate=True)
+        rcp.kv4_append(_t(v), 0, vc[sl], vp[sl])
+    torch.cuda.synchronize()
+    return kc, kp, vc, vp
+
+
+@pytest.mark.parametrize("lengths,H_q,H_kv,S_max", [([5], 4, 4, 8), ([1, 64, 65, 700], 8, 8, 700), ([300, 2, 129, 128, 127], 8, 2, 512),
+                                                    ([1500] * 3 + [1], 32, 32, 1500), (list(range(1, 17)), 4, 4, 16),
+                                                    ([2100, 40], 16, 4, 2100)])
+@pytest.mark.parametrize("tokens", [0, 64, 256])
+def test_batched_attention_matches_the_oracle_sequence_by_sequence(lengths, H_q, H_kv, S_max, tokens):
+    _say(f"kv4 batched attn lengths={lengths[:5]}.. H_q={H_q} H_kv={H_kv} tokens/workgroup={tokens}")
+    B = len(lengths)
+    cache = _pooled(20, lengths, H_kv, S_max)
+    q16 = np.stack([rcp_synth.query_vectors(20, f"q{b}", H_q) for b in range(B)])
+    rcp.set_option("kv_tokens", tokens)
+    out = rcp.kv4_attn_decode_batched(_t(q16), lengths, *cache, 1.0 / np.sqrt(D))
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    host = [a.cpu().numpy() for a in cache]
+    for b, S in enumerate(lengths):
+        sl = slice(b * H_kv, (b + 1) * H_kv)
+        ref = oracle.kv4_attn_decode(q16[b].astype(np.float64), S, *[np.ascontiguousarray(a[sl]) for a in host], 1.0 / np.sqrt(D))
+        assert np.all(np.abs(got[b] - ref) <= TOL * (1.0 + np.abs(ref))), (b, S)
+        if tokens:      # with the split length fixed, the batched rows are the single-sequence results
+            single = rcp.kv4_attn_decode(_t(q16[b]), S, *[a[sl] for a in cache], 1.0 / np.sqrt(D))
+            torch.cuda.synchronize()
+            assert torch.equal(single, out[b])
+
+
+def test_batched_append_equals_single_appends():
+    _say("kv4 batched append")
+    B, H, S_max = 5, 8, 40
+    positions = [0, 39, 7, 7, 20]
+    x = rcp_synth.kv_vectors(21, "newtok", B, H)
+    for rotate in (False, True):
+        c1, p1 = rcp.kv4_new_cache(B * H, S_max, DEV)
+        c2, p2 = rcp.kv4_new_cache(B * H, S_max, DEV)
+        c1.fill_(0x5A), p1.fill_(0x33), c2.fill_(0x5A), p2.fill_(0x33)
+        rcp.kv4_append_batched(_t(x), positions, c1, p1, rotate=rotate)
+        for b in range(B):
+            sl = slice(b * H, (b + 1) * H)
+            rcp.kv4_append(_t(x[b:b + 1]), positions[b], c2[sl], p2[sl], rotate=rotate)
+        torch.cuda.synchronize()
+        assert torch.equal(c1, c2) and torch.equal(p1, p2)
+        # and against the oracle for one of the sequences
+        rc, rp = oracle.kv4_new_cache(H, S_max)
+        rc[:], rp[:] = 0x5A, 0x33
+        oracle.kv4_append(x[2:3].astype(np.float32), positions[2], 0.95, rc, rp, rotate=rotate)
+        assert np.array_equal(c1[2 * H:3 * H].cpu().numpy(), rc) and np.array_equal(p1[2 * H:3 * H].cpu().numpy(), rp)
+    with pytest.raises(rcp.RcpError):
+        rcp.kv4_append_batched(_t(x), [0, 40, 1, 2, 3], c1, p1)
