@@ -2,6 +2,8 @@
 on groups of 128 (Appendix table of quantisation configurations: asymmetric, group size 128,
 clipping ratio 0.95) and one-token attention over the cache (Section 2.1: the cache is
 compressed, attention itself is the usual softmax(q K^T) V)."""
+import os
+
 import numpy as np
 import pytest
 import scipy.special
@@ -10,6 +12,35 @@ import oracle
 import rcp_synth
 
 D = 128
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "kv_cache_quant_config.txt")
+
+
+def _config():
+    for line in open(GOLDEN):
+        if line.strip() and not line.startswith("#"):
+            bits, sym, group, ratio = line.split()
+            return int(bits), sym == "yes", int(group), float(ratio)
+    raise AssertionError("no data line in the fixture")
+
+
+def test_configuration_is_the_papers():
+    bits, symmetric, group, ratio = _config()
+    assert (bits, symmetric, group, ratio) == (4, False, 128, 0.95)
+    assert oracle.KV_D == group                                 # one head vector is one group
+    x = rcp_synth.kv_vectors(2, "cfg", 50, 2).astype(np.float32)
+    codes, params = _quantise(x, clip=ratio)
+    c = _codes(codes)
+    assert c.min() == 0 and c.max() == 2 ** bits - 1            # N bits, both ends used
+    sb, z = oracle.kv4_params(params)
+    lo, hi = ratio * x.min(axis=-1).T, ratio * x.max(axis=-1).T
+    assert np.allclose(_f16(sb), (hi - lo) / (2 ** bits - 1), rtol=2.0 ** -10)      # s = h / (2^N - 1) on the clipped range
+    assert np.all(np.abs(z + lo / _f16(sb)) <= 0.5 + 1e-4)                          # asymmetric: zero point -round(min / s)
+    assert (z != 8).any()                                                           # not a symmetric grid
+    # the product binding's default clipping ratio is the table's
+    import inspect
+    import paper_2502_15779_amd
+    assert inspect.signature(paper_2502_15779_amd.kv4_append).parameters["clip_ratio"].default == ratio
+    assert inspect.signature(paper_2502_15779_amd.kv4_append_batched).parameters["clip_ratio"].default == ratio
 
 
 def _f16(bits):
