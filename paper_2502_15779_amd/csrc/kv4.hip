@@ -136,6 +136,23 @@ __device__ __forceinline__ void nibble_bytes(uint32_t w, uint32_t& lo, uint32_t&
     asm("" : "+v"(lo), "+v"(hi));
 }
 
+// Four bytes b in 0..15 -> four floats b * unit in two instructions: read as FP8 (E4M3) numbers, the codes
+// 0..7 are subnormals and 8..15 the first binade, both linear in b, so v_cvt_pk_f32_fp8 converts two at a
+// time; `kv_fp8_unit()` is what it gives for the byte 1 (a power of two), divided out again by the callers.
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void bytes_to_floats(uint32_t x, float (&f)[4])
+{
+    const v2f a = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(x), false);
+    const v2f b = __builtin_amdgcn_cvt_pk_f32_fp8(static_cast<int>(x), true);
+    f[0] = a[0];
+    f[1] = a[1];
+    f[2] = b[0];
+    f[3] = b[1];
+}
+
+__device__ __forceinline__ float kv_fp8_unit() { return __builtin_amdgcn_cvt_pk_f32_fp8(1, false)[0]; }
+
 __device__ __forceinline__ int kv_elem_of_reg(int r) { return 8 * (r >> 3) + 2 * (r & 3) + ((r >> 2) & 1); }
 
 __device__ __forceinline__ float quad_sum(float v)
@@ -220,6 +237,9 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
             }
     }
 
+    const float unit = kv_fp8_unit(), inv_unit = 1.0f / unit;
+    const float scale_by_unit = softmax_scale * inv_unit, qsum_unit = qsum * unit;
+
     // ---- pass 1: scores (all four lanes of a token end up holding its score) ----
     float score[ITERS];
     float top = -INFINITY;
@@ -230,15 +250,19 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
         for (int d = 0; d < 4; ++d) {
             uint32_t lo, hi;
             nibble_bytes(kw[it][d], lo, hi);
+            float fl[4], fh[4];
+            bytes_to_floats(lo, fl);
+            bytes_to_floats(hi, fh);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                dot[d] = fmaf(qr[8 * d + b], static_cast<float>((lo >> (8 * b)) & 0xffu), dot[d]);
-                dot[d] = fmaf(qr[8 * d + 4 + b], static_cast<float>((hi >> (8 * b)) & 0xffu), dot[d]);
+                dot[d] = fmaf(qr[8 * d + b], fl[b], dot[d]);
+                dot[d] = fmaf(qr[8 * d + 4 + b], fh[b], dot[d]);
             }
         }
-        const float s = half_bits_to_float(static_cast<uint16_t>(kp[it] & 0xffffu)) * softmax_scale;
+        // dot = unit * sum q c: the unit (a power of two) is taken out exactly
+        const float s = half_bits_to_float(static_cast<uint16_t>(kp[it] & 0xffffu)) * scale_by_unit;
         const float z = static_cast<float>(static_cast<int>(kp[it]) >> 16);
-        float sc = s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum);
+        float sc = s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum_unit);
         sc = quad_sum(sc);
         score[it] = valid[it] ? sc : -INFINITY;
         top = fmaxf(top, score[it]);
@@ -256,17 +280,21 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const float p = __expf(score[it] - m);  // exp(-inf) = 0 for the surplus slots
-        const float w = p * half_bits_to_float(static_cast<uint16_t>(vp[it] & 0xffffu));
+        const float w0 = p * half_bits_to_float(static_cast<uint16_t>(vp[it] & 0xffffu));
+        const float w = w0 * inv_unit;  // the converted codes carry the factor unit
         lsum += p;
-        zacc = fmaf(w, static_cast<float>(static_cast<int>(vp[it]) >> 16), zacc);
+        zacc = fmaf(w0, static_cast<float>(static_cast<int>(vp[it]) >> 16), zacc);
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             uint32_t lo, hi;
             nibble_bytes(vw[it][d], lo, hi);
+            float fl[4], fh[4];
+            bytes_to_floats(lo, fl);
+            bytes_to_floats(hi, fh);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                acc[8 * d + b] = fmaf(w, static_cast<float>((lo >> (8 * b)) & 0xffu), acc[8 * d + b]);
-                acc[8 * d + 4 + b] = fmaf(w, static_cast<float>((hi >> (8 * b)) & 0xffu), acc[8 * d + 4 + b]);
+                acc[8 * d + b] = fmaf(w, fl[b], acc[8 * d + b]);
+                acc[8 * d + 4 + b] = fmaf(w, fh[b], acc[8 * d + 4 + b]);
             }
         }
     }
