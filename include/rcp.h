@@ -146,7 +146,8 @@ int rcp_version(void);
  *   "gemv_variant" 1 = plain-ALU kernel for every M, 2 = matrix-core kernel for every M
  *   "gemm_waves"   wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
  *   "gemm_rows"    output rows per workgroup of the matrix-core kernel: 16, 64
- *   "kv_tokens"    cached tokens per workgroup of rcp_kv4_attn_decode: 64, 128, 256
+ *   "kv_tokens"    cached tokens per workgroup of rcp_kv4_attn_decode: 64, 128, 256 (all loads of a workgroup
+ *                  issued at once), 512, 1024, 2048 (the streaming kernel for long contexts and batches)
  *   "gemv_waves"   wavefronts per workgroup of the fused one-token GEMV (rcp_quant_w2a4_gemv): 4, 8
  *                  (8 needs K >= 2048 and "gemv_lanes" left automatic; otherwise 4 is used)
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */

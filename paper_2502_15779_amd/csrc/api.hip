@@ -147,8 +147,8 @@ int rcp_set_option(const char* name, int value)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_rows must be 0, 16 or 64");
         o.gemm_rows = value;
     } else if (strcmp(name, "kv_tokens") == 0) {
-        if (value != 0 && value != 64 && value != 128 && value != 256)
-            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: kv_tokens must be 0, 64, 128 or 256");
+        if (value != 0 && value != 64 && value != 128 && value != 256 && value != 512 && value != 1024 && value != 2048)
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: kv_tokens must be 0, 64, 128, 256, 512, 1024 or 2048");
         o.kv_tokens = value;
     } else if (strcmp(name, "gemv_waves") == 0) {
         if (value != 0 && value != 4 && value != 8)

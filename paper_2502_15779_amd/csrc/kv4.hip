@@ -124,6 +124,7 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict_
 constexpr int KV_THREADS = 256;
 constexpr int KV_MAX_L = 256;          // tokens per workgroup at most: four per lane group, all loads in flight at once
 constexpr int KV_PART = KV_D + 4;      // floats per partial result: acc[128], m, l, 2 unused
+constexpr int KV_STREAM_L = 1024;      // tokens per workgroup of the streaming kernel unless the option says otherwise
 
 // The four low nibbles and the four high nibbles of a dword as bytes.  The empty asm keeps the
 // compiler from folding the mask into each later byte extraction (a 4-bit field extract plus a
@@ -340,6 +341,195 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The streaming form for long contexts and batches, where the device is refilled many times and
+// a workgroup that loads, waits, computes and leaves keeps too few bytes in flight.  Workgroup =
+// (split of L tokens, head [, sequence]), L = 512 ... 2048.  The split is cut into chunks of 16
+// tokens; wavefront w takes chunks w, w + 4, ... and walks them on its own: no workgroup barrier
+// inside the loop, the loads of its next two chunks in flight while it computes one.  Each
+// wavefront keeps a running maximum m (uniform over the wavefront) and rescales its sums when a
+// chunk raises it:  acc <- acc * e^(m_old - m_new);  p_t = e^(score_t - m_new).
+// At the end the four wavefronts merge in LDS with the same rule and (m, l, acc) of the split
+// goes to the workspace for kv4_combine_kernel.
+// ---------------------------------------------------------------------------------------
+struct KvChunk {
+    u32x4 kw, vw;
+    uint32_t kp, vp;
+    bool valid;
+};
+
+template <int QDT, bool BATCHED>
+__global__ __launch_bounds__(KV_THREADS) void kv4_attn_stream_kernel(const void* __restrict__ q, int S, int S_max, int rep,
+                                                                     int splits, float softmax_scale,
+                                                                     const u32x4* __restrict__ k_codes,
+                                                                     const uint32_t* __restrict__ k_params,
+                                                                     const u32x4* __restrict__ v_codes,
+                                                                     const uint32_t* __restrict__ v_params, int L,
+                                                                     float* __restrict__ part, KvBatch batch)
+{
+    __shared__ float red[4][KV_D];
+    __shared__ float wm[4], lrow[4][4], zrow[4][4];
+    const int split = blockIdx.x;
+    int h = blockIdx.y, hk = h / rep;
+    const int tid = threadIdx.x, lane = tid & 63, slot = lane >> 2, piece = tid & 3;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int t0 = split * L;
+    if constexpr (BATCHED) {
+        const int seq = blockIdx.z;
+        S = batch.v[seq];
+        if (t0 >= S) return;  // the whole workgroup: this sequence has fewer splits
+        h += seq * batch.H_q;
+        hk += seq * batch.H_kv;
+    }
+    const int t_end = min(S, t0 + L);
+    const size_t head_base = static_cast<size_t>(hk) * S_max;
+    // chunks of this wavefront that hold at least one cached token
+    const int span = t_end - t0 - 16 * wave;
+    const int nchunks = span > 0 ? (span + 63) >> 6 : 0;
+
+    auto load = [&](int c, KvChunk& r) {  // chunk c of this wavefront: tokens t0 + 16 (4 c + wave) ...; past the end: the last token, weight 0
+        const int t = t0 + 16 * (4 * c + wave) + slot;
+        r.valid = t < t_end;
+        const size_t at = head_base + (r.valid ? t : t_end - 1);
+        r.kw = k_codes[at * 4 + piece];
+        r.kp = k_params[at];
+        r.vw = v_codes[at * 4 + piece];
+        r.vp = v_params[at];
+    };
+
+    Raw8<QDT> qraw[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) qraw[d] = load8_raw<QDT>(q, static_cast<size_t>(h) * KV_D + 32 * piece + 8 * d);
+    KvChunk cA, cB;
+    load(0, cA);
+    load(1, cB);
+
+    float qr[32];
+    float qsum = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        float t8[8];
+        widen8<QDT>(qraw[d], t8);
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                qr[8 * d + 4 * e + b] = t8[2 * b + e];
+                qsum += qr[8 * d + 4 * e + b];
+            }
+    }
+    const float unit = kv_fp8_unit(), inv_unit = 1.0f / unit;
+    const float scale_by_unit = softmax_scale * inv_unit, qsum_unit = qsum * unit;
+
+    float acc[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) acc[r] = 0.0f;
+    float lsum = 0.0f, zacc = 0.0f;
+    float m = -INFINITY;  // uniform over the wavefront
+    int chunk = 0;
+
+    auto step = [&](KvChunk& cur) {
+        float dot[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t lo, hi;
+            nibble_bytes(cur.kw[d], lo, hi);
+            float fl[4], fh[4];
+            bytes_to_floats(lo, fl);
+            bytes_to_floats(hi, fh);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                dot[d] = fmaf(qr[8 * d + b], fl[b], dot[d]);
+                dot[d] = fmaf(qr[8 * d + 4 + b], fh[b], dot[d]);
+            }
+        }
+        const float s = half_bits_to_float(static_cast<uint16_t>(cur.kp & 0xffffu)) * scale_by_unit;
+        const float z = static_cast<float>(static_cast<int>(cur.kp) >> 16);
+        float sc = quad_sum(s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum_unit));
+        sc = cur.valid ? sc : -INFINITY;
+        // every chunk that is stepped holds a cached token, so its maximum is finite
+        const float m_new = fmaxf(m, wave_max(sc));
+        if (m_new > m) {  // uniform
+            const float alpha = __expf(m - m_new);  // 0 on the first chunk
+#pragma unroll
+            for (int r = 0; r < 32; ++r) acc[r] *= alpha;
+            lsum *= alpha;
+            zacc *= alpha;
+            m = m_new;
+        }
+        const float p = __expf(sc - m);
+        const float w0 = p * half_bits_to_float(static_cast<uint16_t>(cur.vp & 0xffffu));
+        const float w = w0 * inv_unit;
+        lsum += p;
+        zacc = fmaf(w0, static_cast<float>(static_cast<int>(cur.vp) >> 16), zacc);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t lo, hi;
+            nibble_bytes(cur.vw[d], lo, hi);
+            float fl[4], fh[4];
+            bytes_to_floats(lo, fl);
+            bytes_to_floats(hi, fh);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                acc[8 * d + b] = fmaf(w, fl[b], acc[8 * d + b]);
+                acc[8 * d + 4 + b] = fmaf(w, fh[b], acc[8 * d + 4 + b]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        load(chunk + 2, cur);  // refill with the chunk two steps ahead (past the end: a harmless repeat of the last token)
+        __builtin_amdgcn_sched_barrier(0);
+        ++chunk;
+    };
+    // steps counted up front and run in pairs: one loop body, one exit (four chunks in flight instead of
+    // two: 130 registers and no gain)
+    for (int i = 0; i < nchunks / 2; ++i) {
+        step(cA);
+        step(cB);
+    }
+    if (nchunks & 1) step(cA);
+
+    // ---- the 16 tokens of a wavefront's chunks are summed as in kv4_attn_kernel; the four wavefronts
+    // merge through LDS, each weighted by e^(its m - the largest m) ----
+#pragma unroll
+    for (int r = 0; r < 32; ++r) acc[r] = row_tokens_sum(acc[r]);
+    lsum = row_tokens_sum(lsum);
+    zacc = row_tokens_sum(zacc);
+    float f16v[16], f32v[8];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) f16v[k] = fold16f(acc[2 * k], acc[2 * k + 1]);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) f32v[k] = fold32f(f16v[2 * k], f16v[2 * k + 1]);
+    const int rw = (tid >> 4) & 3;
+    if ((tid & 12) == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) red[wave][32 * piece + kv_elem_of_reg(4 * k + rw)] = f32v[k];
+        if (piece == 0) {
+            lrow[wave][rw] = lsum;
+            zrow[wave][rw] = zacc;
+        }
+    }
+    if (lane == 0) wm[wave] = m;
+    __syncthreads();
+    float* dst = part + (static_cast<size_t>(h) * splits + split) * KV_PART;
+    if (tid <= KV_D) {
+        const float M = fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3]));  // wavefront 0 always has a token: finite
+        float total = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float e = __expf(wm[w] - M);  // 0 for a wavefront without tokens
+            float v;
+            if (tid < KV_D) v = red[w][tid] - ((zrow[w][0] + zrow[w][1]) + (zrow[w][2] + zrow[w][3]));
+            else v = (lrow[w][0] + lrow[w][1]) + (lrow[w][2] + lrow[w][3]);
+            total = fmaf(e, v, total);
+        }
+        if (tid < KV_D) dst[tid] = total;
+        else {
+            dst[KV_D] = M;
+            dst[KV_D + 1] = total;
+        }
+    }
+}
+
 // out_hj = sum_i e^(m_i - M) acc_ij / sum_i e^(m_i - M) l_i over the splits i of head h.
 // One workgroup of `groups` x 128 threads per head: thread (g, j) merges the splits
 // i = g, g + groups, ... of column j, four at a time so that their loads are in flight together,
@@ -471,7 +661,11 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int
         batch.H_q = H_q;
         batch.H_kv = H_kv;
     }
-    const int L = options().kv_tokens != 0 ? options().kv_tokens : (total * H_q <= 131072 ? 128 : KV_MAX_L);
+    // 128 tokens per workgroup up to 4096 x 32 (token, head) pairs, 256 up to twice that (the device is
+    // filled about once), the streaming kernel on splits of 1024 tokens beyond (sweeps at 32 heads)
+    int L = options().kv_tokens;
+    if (L == 0) L = total * H_q <= 131072 ? 128 : total * H_q <= 262144 ? KV_MAX_L : KV_STREAM_L;
+    const bool stream = L > KV_MAX_L;
     const int splits = (S + L - 1) / L;
     const dim3 grid(static_cast<unsigned>(splits), static_cast<unsigned>(H_q), static_cast<unsigned>(batched ? B : 1));
     const int rep = H_q / H_kv;
@@ -488,11 +682,17 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int
         if (batched) launch(&kv4_attn_kernel<QDT, ITERS, true>);         \
         else launch(&kv4_attn_kernel<QDT, ITERS, false>);                \
     } while (0)
-#define RCP_KV_DISPATCH(QDT)                      \
-    do {                                          \
-        if (L == 64) RCP_KV_LAUNCH(QDT, 1);       \
-        else if (L == 128) RCP_KV_LAUNCH(QDT, 2); \
-        else RCP_KV_LAUNCH(QDT, 4);               \
+    auto launch_stream = [&](auto kernel) {
+        kernel<<<grid, KV_THREADS, 0, st>>>(q, S, S_max, rep, splits, softmax_scale, kc, kp, vc, vp, L, part, batch);
+    };
+#define RCP_KV_DISPATCH(QDT)                                                   \
+    do {                                                                       \
+        if (stream) {                                                          \
+            if (batched) launch_stream(&kv4_attn_stream_kernel<QDT, true>);    \
+            else launch_stream(&kv4_attn_stream_kernel<QDT, false>);           \
+        } else if (L == 64) RCP_KV_LAUNCH(QDT, 1);                             \
+        else if (L == 128) RCP_KV_LAUNCH(QDT, 2);                              \
+        else RCP_KV_LAUNCH(QDT, 4);                                            \
     } while (0)
     if (q_dt == RCP_F32) RCP_KV_DISPATCH(RCP_F32);
     else if (q_dt == RCP_F16) RCP_KV_DISPATCH(RCP_F16);

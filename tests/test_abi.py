@@ -118,7 +118,8 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.rcp_set_option(b"gemm_waves", 8) == 0 and lib.rcp_set_option(b"gemm_waves", 0) == 0
     assert lib.rcp_set_option(b"gemv_variant", 3) == -4
     assert lib.rcp_set_option(b"kv_tokens", 96) == -4
-    assert lib.rcp_set_option(b"kv_tokens", 128) == 0 and lib.rcp_set_option(b"kv_tokens", 0) == 0
+    assert lib.rcp_set_option(b"kv_tokens", 128) == 0 and lib.rcp_set_option(b"kv_tokens", 1024) == 0
+    assert lib.rcp_set_option(b"kv_tokens", 4096) == -4 and lib.rcp_set_option(b"kv_tokens", 0) == 0
     assert lib.rcp_set_option(b"gemm_rows", 32) == -4
     assert lib.rcp_set_option(b"gemm_rows", 16) == 0 and lib.rcp_set_option(b"gemm_rows", 0) == 0
     assert lib.rcp_set_option(b"gemv_waves", 2) == -4

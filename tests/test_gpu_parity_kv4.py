@@ -194,8 +194,8 @@ def test_attention_matches_oracle(H_q, H_kv, S, S_max, q_dtype):
     _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D))
 
 
-@pytest.mark.parametrize("tokens", [64, 128, 256])
-@pytest.mark.parametrize("H_q,H_kv,S", [(4, 4, 1), (4, 2, 130), (8, 8, 1000), (2, 1, 3333)])
+@pytest.mark.parametrize("tokens", [64, 128, 256, 512, 1024, 2048])
+@pytest.mark.parametrize("H_q,H_kv,S", [(4, 4, 1), (4, 2, 130), (8, 8, 1000), (2, 1, 3333), (2, 2, 17), (1, 1, 2049), (2, 1, 5000)])
 def test_attention_every_split_length(tokens, H_q, H_kv, S):
     _say(f"kv4 attn tokens/workgroup={tokens} H_q={H_q} H_kv={H_kv} S={S}")
     cache = _build_cache(11, S, H_kv, S + 3)
@@ -214,8 +214,10 @@ def test_attention_reads_only_the_first_S_tokens_and_fp16_output():
     _check_attention(qd, q32.astype(np.float64), 200, cache, 0.09, out_dtype=torch.float16)
 
 
-def test_attention_peaked_and_flat_score_distributions():
-    _say("kv4 attn peaked / flat")
+@pytest.mark.parametrize("tokens", [0, 512])
+def test_attention_peaked_and_flat_score_distributions(tokens):
+    _say(f"kv4 attn peaked / flat, tokens/workgroup={tokens}")
+    rcp.set_option("kv_tokens", tokens)
     H, S = 4, 900
     cache = _build_cache(7, S, H, S)
     K = oracle.kv4_dequant(cache[0].cpu().numpy(), cache[1].cpu().numpy(), 0, S)
@@ -277,7 +279,7 @@ def _pooled(seed, lengths, H_kv, S_max):
 @pytest.mark.parametrize("lengths,H_q,H_kv,S_max", [([5], 4, 4, 8), ([1, 64, 65, 700], 8, 8, 700), ([300, 2, 129, 128, 127], 8, 2, 512),
                                                     ([1500] * 3 + [1], 32, 32, 1500), (list(range(1, 17)), 4, 4, 16),
                                                     ([2100, 40], 16, 4, 2100)])
-@pytest.mark.parametrize("tokens", [0, 64, 256])
+@pytest.mark.parametrize("tokens", [0, 64, 256, 512, 1024])
 def test_batched_attention_matches_the_oracle_sequence_by_sequence(lengths, H_q, H_kv, S_max, tokens):
     _say(f"kv4 batched attn lengths={lengths[:5]}.. H_q={H_q} H_kv={H_kv} tokens/workgroup={tokens}")
     B = len(lengths)
