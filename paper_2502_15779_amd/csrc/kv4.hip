@@ -601,9 +601,8 @@ __global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restr
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-// Tokens per workgroup (chosen in launch_kv4_attn): 128 up to 4096 tokens x 32 heads in total, 256 beyond
-// (measured: 64 never wins, the per-workgroup reduction then weighs too much; 256 wins once the device is
-// full anyway); the "kv_tokens" option overrides.
+// Tokens per workgroup are chosen in launch_kv4_attn (measured: 64 never wins, the per-workgroup
+// reduction then weighs too much); the "kv_tokens" option overrides.
 size_t kv4_workspace_bytes(int H_q, int S)
 {
     const int splits = (S + 63) / 64;  // the most any split length needs
@@ -661,10 +660,10 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int
         batch.H_q = H_q;
         batch.H_kv = H_kv;
     }
-    // 128 tokens per workgroup up to 4096 x 32 (token, head) pairs, 256 up to twice that (the device is
+    // 128 tokens per workgroup below 2048 x 32 (token, head) pairs, 256 up to 8192 x 32 (the device is
     // filled about once), the streaming kernel on splits of 1024 tokens beyond (sweeps at 32 heads)
     int L = options().kv_tokens;
-    if (L == 0) L = total * H_q <= 131072 ? 128 : total * H_q <= 262144 ? KV_MAX_L : KV_STREAM_L;
+    if (L == 0) L = total * H_q < 65536 ? 128 : total * H_q <= 262144 ? KV_MAX_L : KV_STREAM_L;
     const bool stream = L > KV_MAX_L;
     const int splits = (S + L - 1) / L;
     const dim3 grid(static_cast<unsigned>(splits), static_cast<unsigned>(H_q), static_cast<unsigned>(batched ? B : 1));

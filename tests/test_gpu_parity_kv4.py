@@ -183,7 +183,7 @@ def _check_attention(q_dev, q64, S, cache, scale, out_dtype=torch.float32, heads
 
 @pytest.mark.parametrize("H_q,H_kv,S,S_max", [(1, 1, 1, 1), (2, 2, 3, 8), (4, 4, 63, 64), (4, 4, 64, 64), (4, 4, 65, 70),
                                               (8, 8, 257, 300), (32, 32, 700, 1024), (32, 8, 333, 400), (16, 2, 1500, 1500),
-                                              (3, 1, 5000, 5003), (1, 1, 9000, 9000)])
+                                              (3, 1, 5000, 5003), (1, 1, 9000, 9000), (1, 1, 70001, 70001), (32, 32, 8200, 8200)])
 @pytest.mark.parametrize("q_dtype", ["f16", "f32", "bf16"])
 def test_attention_matches_oracle(H_q, H_kv, S, S_max, q_dtype):
     if q_dtype != "f16" and S > 1000:
