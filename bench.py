@@ -558,10 +558,12 @@ def main():
                         "append_one_token_us": round(sa * 1e6, 3)}
         del kcaches
 
-    # several sequences in one call (pooled caches), 4 layers' worth of distinct caches per measurement
+    # several sequences in one call (pooled caches): enough distinct pools to exceed the 256 MB memory-side cache
+    # several times (at least 1.2 GB in total), and at least 32 launches per graph replay
     kv4_batched = {}
     for B, S in (() if args.step_only else ((8, 1024), (16, 1024), (8, 4096), (16, 4096))):
-        nl = 4
+        nl = min(32, max(4, int(1.2e9 // (2 * B * Hh * S * 68))))
+        nrep = (32 + nl - 1) // nl
         pools = []
         for _ in range(nl):
             kc = torch.randint(0, 256, (B * Hh, S, 64), dtype=torch.uint8, device=dev)
@@ -576,24 +578,26 @@ def main():
         wsb = torch.empty(B * rcp.kv4_workspace_bytes(Hh, S), dtype=torch.uint8, device=dev)
         newtok = torch.randn((B, Hh, 128), device=dev).to(torch.float16)
 
-        def bsweep(pools=pools, qb=qb, ob=ob, wsb=wsb, B=B, S=S):
-            for c in pools:
-                rcp.kv4_attn_decode_batched(qb, [S] * B, *c, 0.08838834764831845, out=ob, workspace=wsb)
+        def bsweep(pools=pools, qb=qb, ob=ob, wsb=wsb, B=B, S=S, nrep=nrep):
+            for _ in range(nrep):
+                for c in pools:
+                    rcp.kv4_attn_decode_batched(qb, [S] * B, *c, 0.08838834764831845, out=ob, workspace=wsb)
         bsweep()
         fn = capture(bsweep)
         fn()
-        s = timed(torch, fn, reps) / nl
+        s = timed(torch, fn, reps) / (nl * nrep)
 
-        def basweep(pools=pools, newtok=newtok, B=B, S=S):
-            for c in pools:
-                rcp.kv4_append_batched(newtok, [S - 1] * B, c[0], c[1], rotate=True)
+        def basweep(pools=pools, newtok=newtok, B=B, S=S, nrep=nrep):
+            for _ in range(nrep):
+                for c in pools:
+                    rcp.kv4_append_batched(newtok, [S - 1] * B, c[0], c[1], rotate=True)
         basweep()
         fn = capture(basweep)
         fn()
-        sa = timed(torch, fn, reps) / nl
+        sa = timed(torch, fn, reps) / (nl * nrep)
         bb = 2 * B * S * Hh * 68
         kv4_batched[f"B{B}_S{S}"] = {"attn_us": round(s * 1e6, 3), "attn_GBps": round(bb / s / 1e9, 1),
-                                    "append_us": round(sa * 1e6, 3)}
+                                    "append_us": round(sa * 1e6, 3), "pools": nl}
         del pools
 
     # The linear layers and the KV-cache launches of a W2A4KV4 decode step chained as in a decoder layer, 4096
