@@ -173,6 +173,23 @@ __device__ __forceinline__ float row_tokens_sum(float v)
 
 // BATCHED: blockIdx.z is the sequence; its length is batch.v[z], its caches start at head z * H_kv of
 // the pooled buffers, its query and partial results at row z * H_q; workgroups past its end leave.
+// Which (split, query head, cache head) a workgroup works on.  Workgroups go to the eight dies (each with
+// its own L2) in turn by their index, so the H_q / H_kv query heads that read the same cache head over the
+// same split are given indices 8 apart: they run on one die at about the same time and the cache bytes come
+// from HBM once instead of once per query head.  Unit u = (split, cache head); index = u % 8 + 8 * (rep * (u / 8) + r)
+// for query head r of the group.  With rep = 1 this is the plain order.  False for the padding of the grid.
+__device__ __forceinline__ bool kv_place(unsigned index, int splits, int rep, int H_kv, int& split, int& h, int& hk)
+{
+    const unsigned die = index & 7u, t = index >> 3;
+    const unsigned r = t % static_cast<unsigned>(rep), k = t / static_cast<unsigned>(rep);
+    const unsigned u = 8u * k + die;
+    if (u >= static_cast<unsigned>(splits) * static_cast<unsigned>(H_kv)) return false;
+    split = static_cast<int>(u % static_cast<unsigned>(splits));
+    hk = static_cast<int>(u / static_cast<unsigned>(splits));
+    h = hk * rep + static_cast<int>(r);
+    return true;
+}
+
 template <int QDT, int ITERS, bool BATCHED>
 __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __restrict__ q, int S, int S_max, int rep, int splits,
                                                               float softmax_scale, const u32x4* __restrict__ k_codes,
@@ -184,8 +201,8 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
     __shared__ float red[4][KV_D];
     __shared__ float wmax[4], lrow[4][4], zrow[4][4];
     constexpr int L = 64 * ITERS;
-    const int split = blockIdx.x;
-    int h = blockIdx.y, hk = h / rep;
+    int split, h, hk;
+    if (!kv_place(blockIdx.x, splits, rep, batch.H_kv, split, h, hk)) return;  // padding of the grid
     const int tid = threadIdx.x, slot = tid >> 2, piece = tid & 3, wave = tid >> 6;
     const int t0 = split * L;
     if constexpr (BATCHED) {
@@ -369,8 +386,8 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_stream_kernel(const void*
 {
     __shared__ float red[4][KV_D];
     __shared__ float wm[4], lrow[4][4], zrow[4][4];
-    const int split = blockIdx.x;
-    int h = blockIdx.y, hk = h / rep;
+    int split, h, hk;
+    if (!kv_place(blockIdx.x, splits, rep, batch.H_kv, split, h, hk)) return;  // padding of the grid
     const int tid = threadIdx.x, lane = tid & 63, slot = lane >> 2, piece = tid & 3;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int t0 = split * L;
@@ -666,8 +683,12 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int
     if (L == 0) L = total * H_q < 65536 ? 128 : total * H_q <= 262144 ? KV_MAX_L : KV_STREAM_L;
     const bool stream = L > KV_MAX_L;
     const int splits = (S + L - 1) / L;
-    const dim3 grid(static_cast<unsigned>(splits), static_cast<unsigned>(H_q), static_cast<unsigned>(batched ? B : 1));
     const int rep = H_q / H_kv;
+    batch.H_q = H_q;
+    batch.H_kv = H_kv;
+    // one index per (split, query head), padded to whole groups of 8 * rep (see kv_place)
+    const unsigned units = static_cast<unsigned>(splits) * static_cast<unsigned>(H_kv);
+    const dim3 grid(8u * static_cast<unsigned>(rep) * ((units + 7u) / 8u), 1u, static_cast<unsigned>(batched ? B : 1));
     auto* kc = static_cast<const u32x4*>(k_codes);
     auto* vc = static_cast<const u32x4*>(v_codes);
     auto* kp = static_cast<const uint32_t*>(k_params);
