@@ -124,6 +124,7 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict_
 constexpr int KV_THREADS = 256;
 constexpr int KV_MAX_L = 256;          // tokens per workgroup at most: four per lane group, all loads in flight at once
 constexpr int KV_PART = KV_D + 4;      // floats per partial result: acc[128], m, l, 2 unused
+constexpr float KV_LAZY = 30.0f;       // how far a score may exceed the streaming kernel's reference before it is raised
 constexpr int KV_STREAM_L = 1024;      // tokens per workgroup of the streaming kernel unless the option says otherwise
 
 // The four low nibbles and the four high nibbles of a dword as bytes.  The empty asm keeps the
@@ -364,8 +365,8 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
 // (split of L tokens, head [, sequence]), L = 512 ... 2048.  The split is cut into chunks of 16
 // tokens; wavefront w takes chunks w, w + 4, ... and walks them on its own: no workgroup barrier
 // inside the loop, the loads of its next two chunks in flight while it computes one.  Each
-// wavefront keeps a running maximum m (uniform over the wavefront) and rescales its sums when a
-// chunk raises it:  acc <- acc * e^(m_old - m_new);  p_t = e^(score_t - m_new).
+// wavefront keeps a reference m (uniform over the wavefront; the running maximum, raised lazily)
+// and rescales its sums when a chunk raises it:  acc <- acc * e^(m_old - m_new);  p_t = e^(score_t - m_new).
 // At the end the four wavefronts merge in LDS with the same rule and (m, l, acc) of the split
 // goes to the workspace for kv4_combine_kernel.
 // ---------------------------------------------------------------------------------------
@@ -464,9 +465,12 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_stream_kernel(const void*
         const float z = static_cast<float>(static_cast<int>(cur.kp) >> 16);
         float sc = quad_sum(s * (((dot[0] + dot[1]) + (dot[2] + dot[3])) - z * qsum_unit));
         sc = cur.valid ? sc : -INFINITY;
-        // every chunk that is stepped holds a cached token, so its maximum is finite
-        const float m_new = fmaxf(m, wave_max(sc));
-        if (m_new > m) {  // uniform
+        // The reference m only has to keep the exponentials in range, so it is raised lazily: when some score
+        // of the chunk exceeds it by more than KV_LAZY (always on the first chunk, where m = -inf; every chunk
+        // that is stepped holds a cached token, so the new maximum is finite).  Weights then stay below
+        // e^KV_LAZY and the sums of a split far inside the binary32 range.
+        if (__builtin_amdgcn_ballot_w64(sc > m + KV_LAZY) != 0) {  // uniform
+            const float m_new = fmaxf(m, wave_max(sc));
             const float alpha = __expf(m - m_new);  // 0 on the first chunk
 #pragma unroll
             for (int r = 0; r < 32; ++r) acc[r] *= alpha;
