@@ -520,7 +520,6 @@ def main():
         wbytes = L * sum(3 * N * K // 8 + 16 * N + K // 2 + 2 + 2 * N for (_, N, K, _) in launches)
         w3_step = {"ms_per_step": round(s * 1e3, 4), "GBps": round(wbytes / s / 1e9, 1),
                    "pct_of_hbm_peak": round(100.0 * wbytes / s / 1e9 / HBM_PEAK_GBPS, 2), "bytes_per_step": wbytes}
-        del wl
 
     # 4-bit KV cache, one query token (LLaMA-2-7B: 32 heads of 128), cold over L layers' caches.  One layer's
     # keys and values are drawn and quantised by the library, then copied into L separate caches.
@@ -623,29 +622,34 @@ def main():
         assert launches[i_qkv][1] == 3 * HIDDEN and launches[i_o][1:3] == (HIDDEN, HIDDEN) and launches[i_down][3]
         qkv = outs[i_qkv]
 
-        def kvstep():
+        def w2(l, i, x, N, K, out):
+            pk, cb = layers[l][i]
+            rcp.quant_w2a4_gemv(pk, cb, N, K, x, 1.0, out=out)
+
+        def w3g(l, i, x, N, K, out):
+            pk, cb = wl[l][i]
+            rcp.quant_w3a4_gemv(pk, cb, N, K, x, 1.0, out=out)
+
+        def kvstep(gemv_call):
             for l in range(L):
-                pk, cb = layers[l][i_qkv]
-                rcp.quant_w2a4_gemv(pk, cb, 3 * HIDDEN, HIDDEN, xs[i_qkv], 1.0, out=qkv)
+                gemv_call(l, i_qkv, xs[i_qkv], 3 * HIDDEN, HIDDEN, qkv)
                 rcp.rotate_act(qkv[0, :HIDDEN].view(Hh, 128), rot_head, y_out=q_rot)
                 kc, kp, vc, vp = lcaches[l]
                 rcp.kv4_append(qkv[0, HIDDEN:2 * HIDDEN].view(1, Hh, 128), S_ctx - 1, kc, kp, rotate=True)
                 rcp.kv4_append(qkv[0, 2 * HIDDEN:].view(1, Hh, 128), S_ctx - 1, vc, vp)
                 rcp.kv4_attn_decode(q_rot, S_ctx, kc, kp, vc, vp, 0.08838834764831845, out=attn_out, workspace=wsl)
-                pk, cb = layers[l][i_o]
-                rcp.quant_w2a4_gemv(pk, cb, HIDDEN, HIDDEN, attn_out.view(1, HIDDEN), 1.0, out=outs[i_o])
-                pk, cb = layers[l][i_gu]
-                rcp.quant_w2a4_gemv(pk, cb, launches[i_gu][1], HIDDEN, xs[i_gu], 1.0, out=outs[i_gu])
+                gemv_call(l, i_o, attn_out.view(1, HIDDEN), HIDDEN, HIDDEN, outs[i_o])
+                gemv_call(l, i_gu, xs[i_gu], launches[i_gu][1], HIDDEN, outs[i_gu])
                 rcp.rotate_act(xs[i_down], rot_down, y_out=ybuf)
-                pk, cb = layers[l][i_down]
-                rcp.quant_w2a4_gemv(pk, cb, HIDDEN, INTER, ybuf, 1.0, out=outs[i_down])
-        kvstep()
-        fn = capture(kvstep)
-        fn()
-        s = timed(torch, fn, max(3, args.steps // 2))
-        kv_layer = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2), "launches_per_layer": 11,
-                    "cached_tokens": S_ctx, "heads": Hh}
-        del lcaches
+                gemv_call(l, i_down, ybuf, HIDDEN, INTER, outs[i_down])
+        kv_layer = {"launches_per_layer": 11, "cached_tokens": S_ctx, "heads": Hh}
+        for label, call in (("w2a4kv4", w2), ("w3a4kv4", w3g)):
+            kvstep(call)
+            fn = capture(lambda call=call: kvstep(call))
+            fn()
+            s = timed(torch, fn, max(3, args.steps // 2))
+            kv_layer[label] = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2)}
+        del lcaches, wl
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
@@ -687,7 +691,7 @@ def main():
         "w3a4_step": w3_step,
         "kv4_attention_32_heads": kv4,
         "kv4_attention_batched": kv4_batched,
-        "w2a4kv4_layer_launches": kv_layer,
+        "kv4_layer_launches": kv_layer,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),
