@@ -805,6 +805,78 @@ def test_full_size_llama2_7b_launches_as_benchmarked(name, N, K, rotated):
     assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
 
 
+@pytest.mark.parametrize("config,name,N,K,rot", [
+    ("llama32_1b", "q_o", 2048, 2048, None), ("llama32_1b", "gate_up", 8192, 2048, None),
+    ("llama32_1b", "down", 2048, 8192, ("wht", 8192)),
+    ("llama3_8b", "k_v", 1024, 4096, None), ("llama3_8b", "gate_up", 14336, 4096, None),
+    ("llama3_8b", "down", 4096, 14336, ("kron", 512, 28))])
+def test_full_size_llama32_1b_and_llama3_8b_layers_as_benchmarked(config, name, N, K, rot):
+    """The layer sizes of the LLaMA-3.2-1B and LLaMA-3-8B configurations at full size through the calls the benchmark
+    times: plain inputs -> fused quantise+GEMV; order-8192 Hadamard -> rcp_rotate_quant_act (bit-exact against the
+    binary32 butterfly) then the GEMV; H_512 (x) Q_28 -> rcp_rotate_act then the fused quantise+GEMV.  Packed bytes,
+    LUT and all N x 4 partial sums bit-exact against the oracle on the whole matrix, every output inside the bar."""
+    _say(f"full size {config}/{name} {N}x{K} rot={rot}")
+    W, lo, hi, part = rcp_synth.linear_layer(11, f"full/{config}/{name}", N, K)
+    x = rcp_synth.activation(11, f"full/{config}/{name}", 1, K)
+    packed, cb = rcp.pack_weights(_t(W), _t(lo), _t(hi), _t(part))
+    xq = torch.empty((1, K // 2), dtype=torch.uint8, device=DEV)
+    sc = torch.empty((1,), dtype=torch.float16, device=DEV)
+    if rot is None:
+        out, P = rcp.quant_w2a4_gemv(packed, cb, N, K, _t(x), 1.0, out_dtype=torch.float16, xq_out=xq, scale_out=sc,
+                                     want_partial_sums=True)
+    elif rot[0] == "wht":
+        rcp.rotate_quant_act(_t(x), rcp.Rotation.wht(K), 1.0, xq_out=xq, scale_out=sc)
+        out, P = rcp.w2a4_gemv(packed, cb, N, K, xq, sc, 1, out_dtype=torch.float16, want_partial_sums=True)
+    else:
+        Q = rcp_synth.orthogonal(11, rot[2])
+        y = rcp.rotate_act(_t(x), rcp.Rotation.kron(rot[1], _t(Q)))
+        out, P = rcp.quant_w2a4_gemv(packed, cb, N, K, y, 1.0, out_dtype=torch.float16, xq_out=xq, scale_out=sc,
+                                     want_partial_sums=True)
+    torch.cuda.synchronize()
+    ref_packed, ref_cb = oracle.pack_weights(W.astype(np.float32), lo, hi, part)
+    assert np.array_equal(packed.cpu().numpy(), ref_packed)
+    assert np.array_equal(cb.cpu().numpy().view(np.uint16), ref_cb)
+    xq_h, sc_h = xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16)
+    if rot is None:
+        oxq, osc, _ = oracle.quantize_act(x.astype(np.float32), 1.0)
+        assert np.array_equal(xq_h, oxq) and np.array_equal(sc_h, osc)
+    elif rot[0] == "wht":
+        oxq, osc, _ = oracle.quantize_act(oracle.fwht_f32(x.astype(np.float32)), 1.0)
+        assert np.array_equal(xq_h, oxq) and np.array_equal(sc_h, osc)
+    else:
+        y64 = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=rot[1], m=rot[2], Q=Q.astype(np.float64))
+        _check_act_against_rotated(np.atleast_2d(y64), xq_h, sc_h, 1.0)
+    ref_O, ref_P = oracle.w2a4_gemv(ref_packed, ref_cb, N, K, xq_h, sc_h, 1)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64)
+    cond = _f16(sc_h)[:, None] * (np.abs(_f16(ref_cb))[None, :, :] * np.abs(ref_P)).sum(axis=2)
+    assert np.all(np.abs(got - ref_O) <= 1e-3 * cond + 2.0 ** -11 * np.abs(ref_O) + 1e-30)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
+
+
+@pytest.mark.parametrize("N,K,M", [(4096, 4096, 8), (4096, 4096, 16), (4096, 11008, 8), (12288, 4096, 8)])
+def test_full_size_small_batch_other_layers_match_oracle(N, K, M):
+    """The out-projection and the down projection of a 7B layer with several tokens (4096 rows: the matrix-core
+    kernel's 16-row workgroups; 8 tokens: low and high activation parts share one B operand), and q|k|v at 8 tokens,
+    at full size with the automatic choice of kernel: P bit-exact, O within the bar."""
+    _say(f"full size small batch {N}x{K} M={M}")
+    idx = rcp_synth.random_indices(12, f"fullsb{N}x{K}", N, K)
+    packed = oracle.pack_indices(idx)
+    rng = np.random.default_rng(12)
+    cb = np.sort(rng.standard_normal((N, 4)) * 0.03, axis=1).astype(np.float16).view(np.uint16)
+    x = rcp_synth.activation(12, f"fullsb{N}x{K}", M, K)
+    xq, sc = rcp.rotate_quant_act(_t(x))
+    out, P = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xq, sc, M, out_dtype=torch.float16, want_partial_sums=True)
+    torch.cuda.synchronize()
+    xq_h, sc_h = xq.cpu().numpy(), sc.cpu().numpy().view(np.uint16)
+    oxq, osc, _ = oracle.quantize_act(x.astype(np.float32), 1.0)
+    assert np.array_equal(xq_h, oxq) and np.array_equal(sc_h, osc)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, xq_h, sc_h, M)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
+
+
 @pytest.mark.parametrize("M", [4, 16])
 def test_full_size_small_batch_layer_matches_oracle(M):
     """gate|up of a 7B layer (22016 x 4096) with M tokens as the benchmark runs it: P bit-exact, O within the bar."""

@@ -186,8 +186,6 @@ def _check_attention(q_dev, q64, S, cache, scale, out_dtype=torch.float32, heads
                                               (3, 1, 5000, 5003), (1, 1, 9000, 9000), (1, 1, 70001, 70001), (32, 32, 8200, 8200)])
 @pytest.mark.parametrize("q_dtype", ["f16", "f32", "bf16"])
 def test_attention_matches_oracle(H_q, H_kv, S, S_max, q_dtype):
-    if q_dtype != "f16" and S > 1000:
-        pytest.skip("the widened query types are covered at the smaller sizes")
     _say(f"kv4 attn H_q={H_q} H_kv={H_kv} S={S} S_max={S_max} {q_dtype}")
     cache = _build_cache(5, S, H_kv, S_max)
     qd, q32 = _as_dtype(rcp_synth.query_vectors(5, f"q{H_q}", H_q), q_dtype)
@@ -196,10 +194,12 @@ def test_attention_matches_oracle(H_q, H_kv, S, S_max, q_dtype):
 
 @pytest.mark.parametrize("tokens", [64, 128, 256, 512, 1024, 2048])
 @pytest.mark.parametrize("H_q,H_kv,S", [(4, 4, 1), (4, 2, 130), (8, 8, 1000), (2, 1, 3333), (2, 2, 17), (1, 1, 2049), (2, 1, 5000)])
-def test_attention_every_split_length(tokens, H_q, H_kv, S):
-    _say(f"kv4 attn tokens/workgroup={tokens} H_q={H_q} H_kv={H_kv} S={S}")
+@pytest.mark.parametrize("q_dtype", ["f16", "f32", "bf16"])
+def test_attention_every_split_length(tokens, H_q, H_kv, S, q_dtype):
+    # every (query type, tokens per workgroup) instantiation of the per-split and of the streaming kernel
+    _say(f"kv4 attn tokens/workgroup={tokens} H_q={H_q} H_kv={H_kv} S={S} {q_dtype}")
     cache = _build_cache(11, S, H_kv, S + 3)
-    qd, q32 = _as_dtype(rcp_synth.query_vectors(11, f"q{H_q}", H_q), "f16")
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(11, f"q{H_q}", H_q), q_dtype)
     rcp.set_option("kv_tokens", tokens)
     _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D))
 
@@ -239,6 +239,17 @@ def test_attention_full_size_sampled_heads():
     cache = _build_cache(8, S, H, S)
     qd, q32 = _as_dtype(rcp_synth.query_vectors(8, "q", H), "f16")
     _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D), heads=[0, 7, 18, 31])
+
+
+@pytest.mark.parametrize("q_dtype", ["f32", "bf16"])
+def test_attention_full_size_as_benchmarked(q_dtype):
+    # the call of bench.py's chained decoder-layer step: binary32 (rotated) queries of 32 heads over 4096 cached
+    # tokens, automatic split length (256 tokens per workgroup); the oracle checks four of the 32 heads
+    _say(f"kv4 attn full size, {q_dtype} queries, automatic split")
+    H, S = 32, 4096
+    cache = _build_cache(12, S, H, S)
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(12, "q", H), q_dtype)
+    _check_attention(qd, q32.astype(np.float64), S, cache, 1.0 / np.sqrt(D), heads=[1, 9, 22, 30])
 
 
 def test_workspace_is_reusable_and_too_small_is_refused():
