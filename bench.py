@@ -306,7 +306,7 @@ def main():
         per_shape[label]["plain_read_GBps"] = round(N * K // 4 / s / 1e9, 1)
 
     # small-batch decode (M = 4, 8, 16 tokens): the same four launches per layer with M tokens,
-    # activations prepared by rcp_rotate_quant_act; the GEMMs run on the matrix cores from 4-5 tokens on
+    # activations prepared by rcp_rotate_quant_act; with three or more tokens the GEMMs run on the matrix cores
     small_batch = {}
     for M in (() if args.step_only else (4, 8, 16)):
         xm = [make_activation(torch, dev, 1000 + M * 7 + i, K).repeat(M, 1).contiguous() for i, (_, _, K, _) in enumerate(launches)]

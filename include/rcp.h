@@ -137,9 +137,13 @@ typedef struct {
 /* Library version, major*10000 + minor*100 + patch. */
 int rcp_version(void);
 
-/* Tuning knobs for benchmarks and sweeps; they change how work is spread over the
- * GPU, never a result.  Value 0 restores the automatic choice.  Process-wide, not
- * thread-safe against concurrent launches.
+/* Tuning knobs for benchmarks, sweeps and tests: a measurement hook outside the contract of the
+ * compute calls, which keep no other state than the thread-local error string.  The knobs change how
+ * work is spread over the GPU; integer results (packed bytes, x_q, S, partial sums) never depend on
+ * them, binary32 / fp16 outputs only through "kv_tokens" (the split length of the attention sum fixes
+ * its summation order, within the stated tolerance).  Value 0 restores the automatic choice of one
+ * knob, rcp_set_option("reset", 0) that of all.  The settings are process-wide and are read by every
+ * launch: do not change them while another host thread is inside a call.
  *   "gemv_lanes"   lanes that share one group of four rows: 16, 32, 64, 128, 256
  *   "gemv_unroll"  16-byte loads per lane and pipeline stage: 2, 4
  *   "gemv_blocks"  number of workgroups the GEMV launches
@@ -150,6 +154,7 @@ int rcp_version(void);
  *                  issued at once), 512, 1024, 2048 (the streaming kernel for long contexts and batches)
  *   "gemv_waves"   wavefronts per workgroup of the fused one-token GEMV (rcp_quant_w2a4_gemv): 4, 8
  *                  (8 needs K >= 2048 and "gemv_lanes" left automatic; otherwise 4 is used)
+ *   "reset"        (value ignored) every knob back to automatic
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */
 int rcp_set_option(const char* name, int value);
 
@@ -226,14 +231,19 @@ int rcp_rotate_act(const void* x, rcp_dtype x_dtype, int M, int K,
  * packed, codebook: as written by rcp_pack_weights.  xq, scale: as written by
  * rcp_rotate_quant_act.  out: M x N of `out_dtype` (RCP_F16 or RCP_F32).
  * partial_sums_or_null: when non-NULL receives int32 [M][N][4].
- * Up to 4 tokens run on the vector ALUs (packed-int4 dot products on the bit planes); from
- * 4-5 tokens on the plane sums are formed on the matrix cores (the masked plane words are
- * FP4 operands); the per-level sums are exact integers either way.
+ * One token always runs on the vector ALUs (packed-int4 dot products on the bit planes), two
+ * tokens too when N < 8192; two tokens with N >= 8192 and three or more tokens form the plane
+ * sums on the matrix cores (the masked plane words are FP4 operands).  The per-level sums are
+ * exact integers either way.  rcp_w2a4_gemv_variant reports that choice.
  */
 int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
                   const void* xq, const void* scale, int M,
                   void* out, rcp_dtype out_dtype,
                   int32_t* partial_sums_or_null, void* stream);
+
+/* Which kernel rcp_w2a4_gemv runs for this shape under the current options (host only, nothing is
+ * launched): 1 = vector-ALU kernel, 2 = matrix-core kernel; RCP_ERR_SHAPE for an unsupported shape. */
+int rcp_w2a4_gemv_variant(int N, int K, int M);
 
 /*
  * One-token fusion of the two calls above for an input that needs no online rotation

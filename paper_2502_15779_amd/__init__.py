@@ -92,6 +92,8 @@ def lib():
         L.rcp_unpack_indices.argtypes = [vp, ci, ci, vp, vp]
         L.rcp_rotate_quant_act.restype = ci
         L.rcp_rotate_quant_act.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, vp, vp, cz, vp]
+        L.rcp_w2a4_gemv_variant.restype = ci
+        L.rcp_w2a4_gemv_variant.argtypes = [ci, ci, ci]
         L.rcp_stream_read.restype = ci
         L.rcp_stream_read.argtypes = [vp, cz, vp, vp]
         L.rcp_rotate_act.restype = ci
@@ -223,6 +225,14 @@ def rotate_quant_act(x, rot: Rotation = None, clip_ratio: float = 1.0, xq_out=No
                                       ctypes.c_float(clip_ratio), _dev(xq_out, "xq_out"), _dev(scale_out, "scale_out"),
                                       ws_ptr, ws_bytes, _stream()))
     return xq_out, scale_out
+
+
+def w2a4_gemv_variant(N: int, K: int, M: int) -> int:
+    """1 = vector-ALU kernel, 2 = matrix-core kernel: what w2a4_gemv runs for this shape under the current options."""
+    rc = int(lib().rcp_w2a4_gemv_variant(N, K, M))
+    if rc < 0:
+        _check(rc)
+    return rc
 
 
 def w2a4_gemv(packed, codebook, N, K, xq, scale, M=1, out=None, out_dtype=torch.float16, partial_sums=None,

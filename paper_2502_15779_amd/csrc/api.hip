@@ -124,6 +124,10 @@ int rcp_set_option(const char* name, int value)
 {
     if (name == nullptr) return fail(RCP_ERR_NULL, "rcp_set_option: name is NULL");
     Options& o = options();
+    if (strcmp(name, "reset") == 0) {
+        o = Options{0, 0, 0, 0, 0, 0, 0, 0};
+        return RCP_OK;
+    }
     if (strcmp(name, "gemv_lanes") == 0) {
         if (value != 0 && value != 16 && value != 32 && value != 64 && value != 128 && value != 256)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_lanes must be 0, 16, 32, 64, 128 or 256");
@@ -248,6 +252,13 @@ int rcp_w2a4_gemv(const void* packed, const void* codebook, int N, int K, const 
         return fail(RCP_ERR_ALIGN, "rcp_w2a4_gemv: scale must be 2-byte aligned");
     return launch_gemv(packed, codebook, N, K, xq, scale, M, out, out_dtype, partial_sums_or_null,
                        static_cast<hipStream_t>(stream));
+}
+
+int rcp_w2a4_gemv_variant(int N, int K, int M)
+{
+    if (int rc = check_shape("rcp_w2a4_gemv_variant", N, K)) return rc;
+    if (M <= 0 || M > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv_variant: M=%d outside 1..%d", M, RCP_MAX_M);
+    return gemv_variant(N, K, M);
 }
 
 int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K, const void* x,

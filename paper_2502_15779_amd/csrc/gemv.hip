@@ -622,17 +622,23 @@ static GemvPlan plan_gemv(int N, int K, int M, bool fused)
     return p;
 }
 
+// Measured crossover on LLaMA-sized layers: 3 tokens, or 2 when the matrix is tall enough to fill the
+// chip with 64-row blocks; below that many rows the matrix-core kernel runs with 16-row blocks and is
+// level with the plain-ALU kernel at 2 tokens.
+int gemv_variant(int N, int /*K*/, int M)
+{
+    const int forced = options().gemv_variant;
+    if (forced == 1 || forced == 2) return forced;
+    const bool many = M > GEMM_MFMA_MIN_M || (M == GEMM_MFMA_MIN_M && N >= 8192);
+    return many ? 2 : 1;
+}
+
 static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
 {
     if (static_cast<long long>(a.N) * a.K / 4 >= (1LL << 31))
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv: packed matrix of %lld bytes exceeds 2 GiB", static_cast<long long>(a.N) * a.K / 4);
     // several tokens: the contraction goes to the matrix cores (the fused quantiser is one token only)
-    const int variant = options().gemv_variant;
-    // (measured crossover on LLaMA-sized layers: 3 tokens, or 2 when the matrix is tall enough to
-    // fill the chip with 64-row blocks; below that many rows the matrix-core kernel runs with 16-row
-    // blocks and is level with the plain-ALU kernel at 2 tokens)
-    const bool many = a.M > GEMM_MFMA_MIN_M || (a.M == GEMM_MFMA_MIN_M && a.N >= 8192);
-    if (a.xraw == nullptr && variant != 1 && (variant == 2 || many))
+    if (a.xraw == nullptr && gemv_variant(a.N, a.K, a.M) == 2)
         return launch_gemm_mfma(a.packed, a.codebook, a.N, a.K, a.xq, a.scale, a.M, a.out, a.out_dt, a.P, st);
     GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
     if (a.rot_n > 0) {  // rotating prologue: one wavefront per row group

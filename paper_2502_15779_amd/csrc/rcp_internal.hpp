@@ -85,6 +85,7 @@ int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, co
                       float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
                       int rot_heads, int rot_head_dim, hipStream_t st);
 bool quant_gemv_supported(int K);
+int gemv_variant(int N, int K, int M);  // 1 vector-ALU kernel, 2 matrix-core kernel: what launch_gemv picks
 
 // ---- small device helpers ------------------------------------------------------------
 __device__ __forceinline__ float half_bits_to_float(uint16_t h)

@@ -237,3 +237,22 @@ def test_product_path_has_no_cpu_fallback():
     finally:
         rcp.LIB_PATH = rcp.LIB_PATH[: -len(".absent")]
         rcp._lib = saved
+
+
+def test_documented_kernel_crossover_with_nothing_forced(lib):
+    """include/rcp.h: one token on the vector ALUs, two tokens too below 8192 rows; two tokens from 8192 rows on and
+    three or more tokens on the matrix cores.  Read from the library's own choice, with every option automatic."""
+    lib.rcp_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
+    assert lib.rcp_set_option(b"reset", 0) == 0
+    v = lib.rcp_w2a4_gemv_variant
+    v.argtypes = [ctypes.c_int] * 3
+    header = re.sub(r"\s*\*\s*", " ", open(HEADER).read())
+    assert "two tokens too when N < 8192" in header and "three or more tokens" in header
+    for N in (256, 4096, 8188):
+        assert v(N, 4096, 1) == 1 and v(N, 4096, 2) == 1 and v(N, 4096, 3) == 2 and v(N, 4096, 16) == 2
+    for N in (8192, 12288, 22016):
+        assert v(N, 4096, 1) == 1 and v(N, 4096, 2) == 2 and v(N, 4096, 3) == 2 and v(N, 4096, 16) == 2
+    assert v(6, 4096, 1) == -2 and v(8, 4096, 17) == -2
+    # a forced variant is reported, and "reset" takes it back
+    assert lib.rcp_set_option(b"gemv_variant", 1) == 0 and v(22016, 4096, 16) == 1
+    assert lib.rcp_set_option(b"reset", 0) == 0 and v(22016, 4096, 16) == 2
