@@ -214,6 +214,24 @@ int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K,
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * rcp_rotate_quant_act for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, arithmetic and results as rcp_rotate_quant_act (the same kernels run), but the scratch a
+ * Kronecker rotation needs between its two kernels (M*K binary32 values) lives in a fixed array of
+ * RCP_ACT_STATIC_SCRATCH_BYTES inside the library's device image -- each GPU the library runs on
+ * holds that array until the process ends.  The call allocates nothing and frees nothing.
+ * Returns RCP_ERR_WORKSPACE (nothing launched) when rcp_act_workspace_bytes(M, K, rot) exceeds
+ * RCP_ACT_STATIC_SCRATCH_BYTES.  All calls on one GPU share the array: calls that may overlap on a GPU
+ * (different streams, several host threads) race on it and must be serialised by the caller; calls on
+ * one stream are ordered and safe.  Nothing in the array has to be cleared between calls (every value
+ * read has been written by the same call).
+ */
+#define RCP_ACT_STATIC_SCRATCH_BYTES (1u << 20) /* 262144 binary32 values, e.g. 16 tokens x 14336 channels */
+int rcp_rotate_quant_act_static(const void* x, rcp_dtype x_dtype, int M, int K,
+                                const rcp_rotation* rot, float clip_ratio,
+                                void* xq_out, void* scale_out, void* stream);
+
+/*
  * The rotation step alone: y = R x in fp32 (the same kernels and arithmetic as the first half
  * of rcp_rotate_quant_act).  y_out: fp32 [M][K].  Meant to be followed by
  * rcp_quant_w2a4_gemv, which quantises in the prologue of the GEMV kernel.  M counts rows here and may

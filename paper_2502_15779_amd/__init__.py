@@ -92,6 +92,8 @@ def lib():
         L.rcp_unpack_indices.argtypes = [vp, ci, ci, vp, vp]
         L.rcp_rotate_quant_act.restype = ci
         L.rcp_rotate_quant_act.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, vp, vp, cz, vp]
+        L.rcp_rotate_quant_act_static.restype = ci
+        L.rcp_rotate_quant_act_static.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, vp, vp]
         L.rcp_w2a4_gemv_variant.restype = ci
         L.rcp_w2a4_gemv_variant.argtypes = [ci, ci, ci]
         L.rcp_stream_read.restype = ci
@@ -224,6 +226,24 @@ def rotate_quant_act(x, rot: Rotation = None, clip_ratio: float = 1.0, xq_out=No
                                       ctypes.byref(rot._c) if rot is not None else None,
                                       ctypes.c_float(clip_ratio), _dev(xq_out, "xq_out"), _dev(scale_out, "scale_out"),
                                       ws_ptr, ws_bytes, _stream()))
+    return xq_out, scale_out
+
+
+ACT_STATIC_SCRATCH_BYTES = 1 << 20
+
+
+def rotate_quant_act_static(x, rot: Rotation, clip_ratio: float, xq_out, scale_out):
+    """rotate_quant_act through the entry point that allocates nothing: the caller passes both outputs and the
+    Kronecker scratch is the library's fixed device array (at most ACT_STATIC_SCRATCH_BYTES)."""
+    if x.dim() == 1:
+        x = x.unsqueeze(0)
+    M, K = x.shape
+    if x.dtype not in _DTYPES:
+        raise ValueError("x must be float16, bfloat16 or float32")
+    _check(lib().rcp_rotate_quant_act_static(_dev(x, "x"), _DTYPES[x.dtype], M, K,
+                                             ctypes.byref(rot._c) if rot is not None else None,
+                                             ctypes.c_float(clip_ratio), _dev(xq_out, "xq_out"),
+                                             _dev(scale_out, "scale_out"), _stream()))
     return xq_out, scale_out
 
 

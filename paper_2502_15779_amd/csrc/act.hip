@@ -8,6 +8,8 @@
 // depend on how the stages are spread over registers, lanes and LDS.
 #include <math.h>
 
+#include <mutex>
+
 #include "rcp_internal.hpp"
 
 namespace rcp {
@@ -679,6 +681,52 @@ int launch_act(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* ro
         case RCP_F32: return launch_act_typed<RCP_F32>(x, M, K, rot, clip_ratio, xq, scale, ws, st);
         default: return launch_act_typed<RCP_BF16>(x, M, K, rot, clip_ratio, xq, scale, ws, st);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// The rotated activations of a Kronecker rotation without a caller's workspace: callers that cannot
+// allocate (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc) get the
+// M x K binary32 values between the rotation kernel and the quantiser placed in a fixed array in device
+// memory.  Every GPU the library runs on holds its own copy of the array until the process ends; the
+// array's name is only a host-side handle, so the device address is looked up once per device and that
+// pointer is what the kernels receive.  The rotation kernels write all M*K values before the quantiser
+// reads them, so nothing has to be cleared between calls; two calls that overlap on one GPU (different
+// streams) would share the array and race.
+// ---------------------------------------------------------------------------------------
+constexpr size_t ACT_SCRATCH_BYTES = RCP_ACT_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[ACT_SCRATCH_BYTES];
+
+static int static_scratch(void** ptr)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static void* addr[MAX_DEVICES] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act_static: hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act_static: device %d outside 0..%d", dev, MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(mu);
+    if (addr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // this device's copy (the current device)
+        if (e != hipSuccess || p == nullptr)
+            return fail(RCP_ERR_HIP, "rcp_rotate_quant_act_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return RCP_OK;
+}
+
+int launch_act_static(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float clip_ratio, void* xq,
+                      void* scale, hipStream_t st)
+{
+    const size_t need = act_workspace_bytes(M, K, rot);
+    if (need > ACT_SCRATCH_BYTES)
+        return fail(RCP_ERR_WORKSPACE, "rcp_rotate_quant_act_static: M*K*4 = %zu bytes exceed the fixed scratch of %zu bytes; "
+                                       "use rcp_rotate_quant_act with a workspace", need, ACT_SCRATCH_BYTES);
+    void* ws = nullptr;
+    if (int rc = static_scratch(&ws)) return rc;
+    return launch_act(x, dt, M, K, rot, clip_ratio, xq, scale, ws, ACT_SCRATCH_BYTES, st);
 }
 
 template <int DT>

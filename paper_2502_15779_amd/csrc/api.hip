@@ -213,6 +213,25 @@ int rcp_rotate_quant_act(const void* x, rcp_dtype x_dtype, int M, int K, const r
                       static_cast<hipStream_t>(stream));
 }
 
+int rcp_rotate_quant_act_static(const void* x, rcp_dtype x_dtype, int M, int K, const rcp_rotation* rot,
+                                float clip_ratio, void* xq_out, void* scale_out, void* stream)
+{
+    if (!x || !xq_out || !scale_out) return fail(RCP_ERR_NULL, "rcp_rotate_quant_act_static: NULL pointer argument");
+    if (M <= 0 || M > RCP_MAX_M) return fail(RCP_ERR_SHAPE, "rcp_rotate_quant_act_static: M=%d outside 1..%d", M, RCP_MAX_M);
+    if (K <= 0 || K % 32 != 0 || K > RCP_MAX_K)
+        return fail(RCP_ERR_SHAPE, "rcp_rotate_quant_act_static: K=%d must be a positive multiple of 32, at most %d", K, RCP_MAX_K);
+    if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act_static: unknown dtype %d", static_cast<int>(x_dtype));
+    if (!(clip_ratio > 0.0f) || !(clip_ratio <= 1.0f))
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_act_static: clip_ratio %g outside (0, 1]", static_cast<double>(clip_ratio));
+    if (int rc = check_rotation("rcp_rotate_quant_act_static", K, rot)) return rc;
+    if (!aligned16(x) || !aligned16(xq_out))
+        return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_act_static: device buffers must be 16-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(scale_out) & 1u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_act_static: scale_out must be 2-byte aligned");
+    return launch_act_static(x, x_dtype, M, K, rot, clip_ratio, xq_out, scale_out, static_cast<hipStream_t>(stream));
+}
+
 int rcp_stream_read(const void* buffer, size_t bytes, void* sink_or_null, void* stream)
 {
     if (!buffer) return fail(RCP_ERR_NULL, "rcp_stream_read: NULL pointer argument");

@@ -43,6 +43,9 @@ int launch_gemv_grouped(const void* packed, const void* codebook, int N, int K, 
 size_t act_workspace_bytes(int M, int K, const rcp_rotation* rot);
 int launch_act(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float clip_ratio,
                void* xq, void* scale, void* ws, size_t ws_bytes, hipStream_t st);
+// the same with the Kronecker scratch in the library's own fixed device array (allocates nothing)
+int launch_act_static(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float clip_ratio, void* xq,
+                      void* scale, hipStream_t st);
 
 int launch_stream_read(const void* p, size_t bytes, uint32_t* sink, hipStream_t st);
 int launch_rotate(const void* x, rcp_dtype dt, int M, int K, const rcp_rotation* rot, float* y, hipStream_t st);

@@ -256,3 +256,18 @@ def test_documented_kernel_crossover_with_nothing_forced(lib):
     # a forced variant is reported, and "reset" takes it back
     assert lib.rcp_set_option(b"gemv_variant", 1) == 0 and v(22016, 4096, 16) == 1
     assert lib.rcp_set_option(b"reset", 0) == 0 and v(22016, 4096, 16) == 2
+
+
+def test_static_scratch_entry_point_rejects_before_touching_the_device(lib):
+    lib.rcp_last_error.restype = ctypes.c_char_p
+    vp = ctypes.c_void_p
+    fake = vp(0x1000)
+    act = lib.rcp_rotate_quant_act_static
+    act.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(Rot), ctypes.c_float, vp, vp, vp]
+    assert act(None, 0, 1, 64, None, 1.0, fake, fake, None) == -1
+    assert act(fake, 0, 17, 64, None, 1.0, fake, fake, None) == -2
+    assert act(fake, 0, 1, 64, None, 0.0, fake, fake, None) == -4
+    assert act(fake, 0, 1, 96, ctypes.byref(Rot(2, 32, 4, fake)), 1.0, fake, fake, None) == -2
+    # 16 tokens x 32768 channels x 4 bytes = 2 MiB of Kronecker scratch: beyond the fixed 1 MiB array
+    assert act(fake, 0, 16, 32768, ctypes.byref(Rot(2, 128, 256, fake)), 1.0, fake, fake, None) == -5
+    assert b"exceed" in lib.rcp_last_error()
