@@ -154,6 +154,7 @@ int rcp_version(void);
  *                  issued at once), 512, 1024, 2048 (the streaming kernel for long contexts and batches)
  *   "gemv_waves"   wavefronts per workgroup of the fused one-token GEMV (rcp_quant_w2a4_gemv): 4, 8
  *                  (8 needs K >= 2048 and "gemv_lanes" left automatic; otherwise 4 is used)
+ *   "seq_blocks"   workgroups of rcp_quant_w2a4_gemv_sequence (refused when they could not all be resident)
  *   "reset"        (value ignored) every knob back to automatic
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */
 int rcp_set_option(const char* name, int value);
@@ -290,6 +291,51 @@ int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, 
                                void* out, rcp_dtype out_dtype,
                                void* xq_out_or_null, void* scale_out_or_null,
                                int32_t* partial_sums_or_null, void* stream);
+
+/*
+ * Several dependent one-token GEMVs in ONE launch (Section 4.4; the layers of a decoder are applied one
+ * after the other, Section 2.1 names the online rotation R_4 in front of the down projection).
+ * Entry i computes exactly
+ *     y_i   = rcp_rotate_act(x_i, rot_i)                    (rot_i: RCP_ROT_NONE or RCP_ROT_KRON)
+ *     out_i = rcp_quant_w2a4_gemv(packed_i, codebook_i, N_i, K_i, y_i, clip_ratio_i)
+ * bit for bit, in the order of the array, and entry i may read anything an earlier entry wrote (x_i may
+ * point into out_j, j < i): all workgroups meet between consecutive entries, while the weights of the
+ * next entry are already being fetched.  A caller that applies other operations between two linear
+ * layers (attention, normalisation, gating) ends the sequence there.
+ *
+ * steps: HOST array of n entries, 1 <= n <= RCP_SEQ_MAX_STEPS, read before the call returns.  Per entry:
+ * packed / codebook as written by rcp_pack_weights for N x K; x: K values of x_dtype (device);
+ * rot.kind RCP_ROT_NONE, or RCP_ROT_KRON with n_wht in 64..1024 and (n_wht/64)*ceil(m/16) <= 16 (other
+ * rotations: RCP_ERR_UNSUPPORTED); K <= 16384; out: N values of out_dtype (RCP_F16 / RCP_F32);
+ * xq_out_or_null (K/2 bytes) / scale_out_or_null (one fp16) receive the quantised activation.
+ * Buffers are 16-byte aligned; an output must not overlap any weight buffer or another output.
+ *
+ * workspace: rcp_gemv_sequence_workspace_bytes(steps, n) bytes of device memory that were ZERO when the
+ * workspace was first used and have since been touched by this call only (the call leaves its
+ * counters at zero again).  Word 0 (uint32) is an error flag: it stays 0 unless a wait inside the
+ * kernel ran out of its bound -- only possible when the launch's workgroups were not all resident
+ * at once, e.g. next to another kernel on the same GPU -- in which case the outputs are undefined and the
+ * workspace has to be zeroed again.  Calls sharing a workspace must not overlap.  The grid (two
+ * workgroups per compute unit, or "seq_blocks") is checked against the kernel's occupancy on the
+ * host and refused with RCP_ERR_UNSUPPORTED when it could not be resident at once.
+ */
+#define RCP_SEQ_MAX_STEPS 16
+typedef struct {
+    const void* packed;      /* device */
+    const void* codebook;    /* device, fp16 [N][4] */
+    int N, K;
+    const void* x;           /* device, K values of x_dtype */
+    int x_dtype;             /* rcp_dtype */
+    rcp_rotation rot;        /* RCP_ROT_NONE or RCP_ROT_KRON */
+    float clip_ratio;        /* in (0, 1] */
+    void* out;               /* device, N values of out_dtype */
+    int out_dtype;           /* RCP_F16 or RCP_F32 */
+    void* xq_out_or_null;    /* device, K/2 bytes */
+    void* scale_out_or_null; /* device, one fp16 */
+} rcp_gemv_step;
+size_t rcp_gemv_sequence_workspace_bytes(const rcp_gemv_step* steps, int n);
+int rcp_quant_w2a4_gemv_sequence(const rcp_gemv_step* steps, int n, void* workspace, size_t workspace_bytes,
+                                 void* stream);
 
 /*
  * Weight-only GEMV (the W2-only decode variant of the paper's inference-latency section:

@@ -59,6 +59,55 @@ class Rotation:
         return Rotation(ROT_KRON, n_wht=n_wht, m=Q.shape[0], Q=Q)
 
 
+class _GemvStep(ctypes.Structure):
+    _fields_ = [("packed", ctypes.c_void_p), ("codebook", ctypes.c_void_p), ("N", ctypes.c_int), ("K", ctypes.c_int),
+                ("x", ctypes.c_void_p), ("x_dtype", ctypes.c_int), ("rot", _Rotation), ("clip_ratio", ctypes.c_float),
+                ("out", ctypes.c_void_p), ("out_dtype", ctypes.c_int), ("xq_out", ctypes.c_void_p),
+                ("scale_out", ctypes.c_void_p)]
+
+
+class GemvStep:
+    """One entry of quant_w2a4_gemv_sequence; keeps its tensors alive.  x may be (a view into) the `out` of an earlier entry."""
+
+    def __init__(self, packed, codebook, N, K, x, out, rot: Rotation = None, clip_ratio: float = 1.0, xq_out=None,
+                 scale_out=None):
+        if x.numel() != K or x.dtype not in _DTYPES:
+            raise ValueError("x must hold K values of float16, bfloat16 or float32")
+        if out.dtype not in (torch.float16, torch.float32) or out.numel() != N:
+            raise ValueError("out must hold N values of float16 or float32")
+        if packed.numel() * packed.element_size() < N * K // 4 or codebook.numel() < 4 * N:
+            raise ValueError("packed / codebook buffers do not match N, K")
+        if xq_out is not None and xq_out.numel() * xq_out.element_size() < K // 2:
+            raise ValueError("xq_out too small")
+        self.tensors = (packed, codebook, x, out, rot, xq_out, scale_out)
+        opt = lambda t, name: _dev(t, name).value if t is not None else None
+        r = rot._c if rot is not None else _Rotation(ROT_NONE, 0, 1, None)
+        self.c = _GemvStep(_dev(packed, "packed").value, _dev(codebook, "codebook").value, int(N), int(K), _dev(x, "x").value,
+                           _DTYPES[x.dtype], r, float(clip_ratio), _dev(out, "out").value, _DTYPES[out.dtype],
+                           opt(xq_out, "xq_out"), opt(scale_out, "scale_out"))
+
+
+def _step_array(steps):
+    arr = (_GemvStep * len(steps))()
+    for i, s in enumerate(steps):
+        arr[i] = s.c
+    return arr
+
+
+def gemv_sequence_workspace(steps, device="cuda:0"):
+    """A zeroed workspace for quant_w2a4_gemv_sequence(steps); word 0 (int32) is the error flag."""
+    need = int(lib().rcp_gemv_sequence_workspace_bytes(_step_array(steps), len(steps)))
+    if need == 0:
+        raise RcpError(-2, lib().rcp_last_error().decode())
+    return torch.zeros((need + 3) // 4, dtype=torch.int32, device=device)
+
+
+def quant_w2a4_gemv_sequence(steps, workspace):
+    """The entries of `steps` (GemvStep) in order in one launch; an entry may read what an earlier one wrote."""
+    _check(lib().rcp_quant_w2a4_gemv_sequence(_step_array(steps), len(steps), _dev(workspace, "workspace"),
+                                              workspace.numel() * workspace.element_size(), _stream()))
+
+
 _lib = None
 
 
@@ -96,6 +145,10 @@ def lib():
         L.rcp_rotate_quant_act_static.argtypes = [vp, ci, ci, ci, ctypes.POINTER(_Rotation), ctypes.c_float, vp, vp, vp]
         L.rcp_w2a4_gemv_variant.restype = ci
         L.rcp_w2a4_gemv_variant.argtypes = [ci, ci, ci]
+        L.rcp_gemv_sequence_workspace_bytes.restype = cz
+        L.rcp_gemv_sequence_workspace_bytes.argtypes = [ctypes.POINTER(_GemvStep), ci]
+        L.rcp_quant_w2a4_gemv_sequence.restype = ci
+        L.rcp_quant_w2a4_gemv_sequence.argtypes = [ctypes.POINTER(_GemvStep), ci, vp, cz, vp]
         L.rcp_stream_read.restype = ci
         L.rcp_stream_read.argtypes = [vp, cz, vp, vp]
         L.rcp_rotate_act.restype = ci

@@ -28,7 +28,7 @@ int check_launch(const char* what)
 
 Options& options()
 {
-    static Options o = {0, 0, 0, 0, 0, 0, 0, 0};
+    static Options o = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     return o;
 }
 
@@ -125,7 +125,7 @@ int rcp_set_option(const char* name, int value)
     if (name == nullptr) return fail(RCP_ERR_NULL, "rcp_set_option: name is NULL");
     Options& o = options();
     if (strcmp(name, "reset") == 0) {
-        o = Options{0, 0, 0, 0, 0, 0, 0, 0};
+        o = Options{0, 0, 0, 0, 0, 0, 0, 0, 0};
         return RCP_OK;
     }
     if (strcmp(name, "gemv_lanes") == 0) {
@@ -158,6 +158,9 @@ int rcp_set_option(const char* name, int value)
         if (value != 0 && value != 4 && value != 8)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_waves must be 0, 4 or 8");
         o.gemv_waves = value;
+    } else if (strcmp(name, "seq_blocks") == 0) {
+        if (value < 0 || value > 4096) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: seq_blocks out of range");
+        o.seq_blocks = value;
     } else
         return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: unknown option '%s'", name);
     return RCP_OK;
@@ -336,6 +339,50 @@ int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, 
         return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_w2a4_gemv: scale_out must be 2-byte aligned");
     return launch_quant_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
                              scale_out_or_null, partial_sums_or_null, rot->n_wht, rot->m, static_cast<hipStream_t>(stream));
+}
+
+static int check_sequence(const char* fn, const rcp_gemv_step* steps, int n)
+{
+    if (!steps) return fail(RCP_ERR_NULL, "%s: steps is NULL", fn);
+    if (n < 1 || n > RCP_SEQ_MAX_STEPS) return fail(RCP_ERR_SHAPE, "%s: n=%d outside 1..%d", fn, n, RCP_SEQ_MAX_STEPS);
+    for (int i = 0; i < n; ++i) {
+        const rcp_gemv_step& s = steps[i];
+        if (!s.packed || !s.codebook || !s.x || !s.out) return fail(RCP_ERR_NULL, "%s: entry %d: NULL pointer", fn, i);
+        if (int rc = check_shape(fn, s.N, s.K)) return rc;
+        if (s.K > 16384) return fail(RCP_ERR_UNSUPPORTED, "%s: entry %d: K=%d exceeds 16384", fn, i, s.K);
+        if (s.x_dtype != RCP_F16 && s.x_dtype != RCP_F32 && s.x_dtype != RCP_BF16)
+            return fail(RCP_ERR_UNSUPPORTED, "%s: entry %d: unknown x_dtype %d", fn, i, s.x_dtype);
+        if (s.out_dtype != RCP_F16 && s.out_dtype != RCP_F32)
+            return fail(RCP_ERR_UNSUPPORTED, "%s: entry %d: out_dtype must be RCP_F16 or RCP_F32", fn, i);
+        if (!(s.clip_ratio > 0.0f) || !(s.clip_ratio <= 1.0f))
+            return fail(RCP_ERR_UNSUPPORTED, "%s: entry %d: clip_ratio %g outside (0, 1]", fn, i, static_cast<double>(s.clip_ratio));
+        if (s.rot.kind != RCP_ROT_NONE && s.rot.kind != RCP_ROT_KRON)
+            return fail(RCP_ERR_UNSUPPORTED, "%s: entry %d: only RCP_ROT_NONE and RCP_ROT_KRON run inside a sequence", fn, i);
+        if (int rc = check_rotation(fn, s.K, &s.rot)) return rc;
+        if (!aligned16(s.packed) || !aligned16(s.codebook) || !aligned16(s.x) || !aligned16(s.out) || !aligned16(s.xq_out_or_null))
+            return fail(RCP_ERR_ALIGN, "%s: entry %d: device buffers must be 16-byte aligned", fn, i);
+        if ((reinterpret_cast<uintptr_t>(s.scale_out_or_null) & 1u) != 0)
+            return fail(RCP_ERR_ALIGN, "%s: entry %d: scale_out must be 2-byte aligned", fn, i);
+    }
+    return RCP_OK;
+}
+
+size_t rcp_gemv_sequence_workspace_bytes(const rcp_gemv_step* steps, int n)
+{
+    if (check_sequence("rcp_gemv_sequence_workspace_bytes", steps, n) != RCP_OK) return 0;
+    return gemv_sequence_workspace_bytes(steps, n);
+}
+
+int rcp_quant_w2a4_gemv_sequence(const rcp_gemv_step* steps, int n, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (int rc = check_sequence("rcp_quant_w2a4_gemv_sequence", steps, n)) return rc;
+    if (!workspace) return fail(RCP_ERR_NULL, "rcp_quant_w2a4_gemv_sequence: workspace is NULL");
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+        return fail(RCP_ERR_ALIGN, "rcp_quant_w2a4_gemv_sequence: workspace must be 256-byte aligned");
+    const size_t need = gemv_sequence_workspace_bytes(steps, n);
+    if (workspace_bytes < need)
+        return fail(RCP_ERR_WORKSPACE, "rcp_quant_w2a4_gemv_sequence: workspace of %zu bytes needed, %zu given", need, workspace_bytes);
+    return launch_gemv_sequence(steps, n, workspace, static_cast<hipStream_t>(stream));
 }
 
 int rcp_w2a16_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dtype,

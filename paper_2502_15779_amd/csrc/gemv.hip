@@ -35,65 +35,6 @@ namespace rcp {
 constexpr int GEMV_THREADS = 256;
 constexpr int GEMV_WAVES = GEMV_THREADS / 64;
 
-// The row (0..3 within its row group) whose sums lane `lane` ends up holding after
-// reduce_rows<LW>, and whether the lane is one of those that write a result.
-template <int LW>
-__device__ __forceinline__ int lane_row(int lane)
-{
-    const int rho = lane >> 4;
-    if constexpr (LW == 64) return ((rho & 1) << 1) | (rho >> 1);
-    else if constexpr (LW == 32) return (rho & 1) + 2 * (lane & 1);
-    else return lane & 3;
-}
-template <int LW>
-__device__ __forceinline__ bool lane_writes(int lane)
-{
-    if constexpr (LW == 64) return (lane & 15) == 0;
-    else if constexpr (LW == 32) return (lane & 15) < 2;
-    else return (lane & 15) < 4;
-}
-
-// g[4p + r] is this lane's share of 2^r * f_r of plane p.  Sums over the LW lanes that
-// share the row group and leaves in f[p] the total for row lane_row<LW>(lane).
-template <int LW>
-__device__ __forceinline__ void reduce_rows(const int (&g)[12], int lane, int (&f)[3])
-{
-    if constexpr (LW == 64) {
-        int s[6];
-#pragma unroll
-        for (int i = 0; i < 6; ++i) s[i] = fold32(g[2 * i], g[2 * i + 1]);
-#pragma unroll
-        for (int p = 0; p < 3; ++p) f[p] = row_sum16(fold16(s[2 * p], s[2 * p + 1]));
-    } else if constexpr (LW == 32) {
-        const bool odd = lane & 1;
-#pragma unroll
-        for (int p = 0; p < 3; ++p) {
-            const int lo = row_sum16(fold16(g[4 * p + 0], g[4 * p + 1]));  // rows r = 0 | 1
-            const int hi = row_sum16(fold16(g[4 * p + 2], g[4 * p + 3]));  // rows r = 2 | 3
-            f[p] = odd ? hi : lo;
-        }
-    } else {
-        const int j = lane & 3;
-#pragma unroll
-        for (int p = 0; p < 3; ++p) {
-            const int a0 = row_sum16(g[4 * p + 0]), a1 = row_sum16(g[4 * p + 1]);
-            const int a2 = row_sum16(g[4 * p + 2]), a3 = row_sum16(g[4 * p + 3]);
-            f[p] = (j == 0) ? a0 : (j == 1) ? a1 : (j == 2) ? a2 : a3;
-        }
-    }
-}
-
-// LDS: quantised activations, token t at dword t*(K/8), padded so that the reads of a
-// lane whose unit lies beyond K stay inside the allocation (their weights are zero);
-// then 4*MT ints of per-wavefront sums of q; then, for WS > 1, the cross-wavefront
-// reduction slots int[2][4 waves][4 rows][3*MT].
-__host__ __device__ constexpr int gemv_x_bytes(int K, int M, int span /* LG * UNR */)
-{
-    const int U = K / 16;
-    const int padded_units = ((U + span - 1) / span) * span;
-    return ((M - 1) * U + padded_units) * 8;
-}
-
 // XDT < 0: `xq` / `scale` are the quantised activations.  XDT = RCP_F16 / RCP_F32 / RCP_BF16
 // (one token only): `xraw` is the raw activation of that type and the workgroup quantises it
 // itself, exactly as quant_kernel would (amax, S = fp16(ratio*amax/7), q = rint(x/S)); the
@@ -464,7 +405,7 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
                     o = fmaf(c3, static_cast<float>(P3), o);
                     o *= sc[t];
                     const size_t oi = static_cast<size_t>(t) * N + h;
-                    if constexpr (OUT_F16) static_cast<__half*>(out)[oi] = __float2half_rn(o);
+                    if constexpr (OUT_F16) static_cast<__half*>(out)[oi] = round_to_half(o);
                     else static_cast<float*>(out)[oi] = o;
                     if (Pout != nullptr)
                         reinterpret_cast<int4*>(Pout)[oi] = make_int4(P0, P1, P2, P3);

@@ -25,6 +25,7 @@ struct Options {
     int gemv_waves;      // wavefronts per workgroup of the fused one-token GEMV: 4 or 8
     int gemm_rows;       // output rows per workgroup of the matrix-core kernel: 16 or 64
     int kv_tokens;       // cached tokens per workgroup of the KV4 attention kernel: 64, 128 or 256
+    int seq_blocks;      // workgroups of the GEMV sequence kernel
 };
 Options& options();
 int num_compute_units();
@@ -88,6 +89,9 @@ int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, co
                       float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
                       int rot_heads, int rot_head_dim, hipStream_t st);
 bool quant_gemv_supported(int K);
+// several dependent one-token GEMVs in one launch (gemv_seq.hip)
+size_t gemv_sequence_workspace_bytes(const rcp_gemv_step* steps, int n);
+int launch_gemv_sequence(const rcp_gemv_step* steps, int n, void* workspace, hipStream_t st);
 int gemv_variant(int N, int K, int M);  // 1 vector-ALU kernel, 2 matrix-core kernel: what launch_gemv picks
 
 // ---- small device helpers ------------------------------------------------------------
@@ -99,6 +103,16 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h)
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b)
 {
     return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// The binary32 value `o` (already rounded to binary32) rounded once more, to nearest even, to fp16.  The value is
+// made opaque first: otherwise the compiler may merge the multiplication that produced it with the conversion
+// into one instruction with a single rounding, and two kernels computing the same output could then differ in the
+// last fp16 bit depending on how each was compiled.
+__device__ __forceinline__ __half round_to_half(float o)
+{
+    asm volatile("" : "+v"(o));
+    return __float2half_rn(o);
 }
 
 // Load element i of a tensor of 16- or 32-bit floats as fp32 (the widening is exact).
@@ -258,6 +272,66 @@ __device__ __forceinline__ void cell_update(uint32_t b0, uint32_t b1, const uint
             acc[t][p][3] = dot8(x[t], pl[p], acc[t][p][3]);
         }
     }
+}
+
+// ---- pieces shared by the one-launch-per-matrix GEMV and the sequence kernel ------------------
+// The row (0..3 within its row group) whose sums lane `lane` ends up holding after
+// reduce_rows<LW>, and whether the lane is one of those that write a result.
+template <int LW>
+__device__ __forceinline__ int lane_row(int lane)
+{
+    const int rho = lane >> 4;
+    if constexpr (LW == 64) return ((rho & 1) << 1) | (rho >> 1);
+    else if constexpr (LW == 32) return (rho & 1) + 2 * (lane & 1);
+    else return lane & 3;
+}
+template <int LW>
+__device__ __forceinline__ bool lane_writes(int lane)
+{
+    if constexpr (LW == 64) return (lane & 15) == 0;
+    else if constexpr (LW == 32) return (lane & 15) < 2;
+    else return (lane & 15) < 4;
+}
+
+// g[4p + r] is this lane's share of 2^r * f_r of plane p.  Sums over the LW lanes that
+// share the row group and leaves in f[p] the total for row lane_row<LW>(lane).
+template <int LW>
+__device__ __forceinline__ void reduce_rows(const int (&g)[12], int lane, int (&f)[3])
+{
+    if constexpr (LW == 64) {
+        int s[6];
+#pragma unroll
+        for (int i = 0; i < 6; ++i) s[i] = fold32(g[2 * i], g[2 * i + 1]);
+#pragma unroll
+        for (int p = 0; p < 3; ++p) f[p] = row_sum16(fold16(s[2 * p], s[2 * p + 1]));
+    } else if constexpr (LW == 32) {
+        const bool odd = lane & 1;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int lo = row_sum16(fold16(g[4 * p + 0], g[4 * p + 1]));  // rows r = 0 | 1
+            const int hi = row_sum16(fold16(g[4 * p + 2], g[4 * p + 3]));  // rows r = 2 | 3
+            f[p] = odd ? hi : lo;
+        }
+    } else {
+        const int j = lane & 3;
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const int a0 = row_sum16(g[4 * p + 0]), a1 = row_sum16(g[4 * p + 1]);
+            const int a2 = row_sum16(g[4 * p + 2]), a3 = row_sum16(g[4 * p + 3]);
+            f[p] = (j == 0) ? a0 : (j == 1) ? a1 : (j == 2) ? a2 : a3;
+        }
+    }
+}
+
+// LDS: quantised activations, token t at dword t*(K/8), padded so that the reads of a
+// lane whose unit lies beyond K stay inside the allocation (their weights are zero);
+// then 4*MT ints of per-wavefront sums of q; then, for WS > 1, the cross-wavefront
+// reduction slots int[2][4 waves][4 rows][3*MT].
+__host__ __device__ constexpr int gemv_x_bytes(int K, int M, int span /* LG * UNR */)
+{
+    const int U = K / 16;
+    const int padded_units = ((U + span - 1) / span) * span;
+    return ((M - 1) * U + padded_units) * 8;
 }
 
 // ---- FP4 (E2M1) operands of the 16x16x128 matrix instruction -------------------------------

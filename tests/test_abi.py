@@ -271,3 +271,33 @@ def test_static_scratch_entry_point_rejects_before_touching_the_device(lib):
     # 16 tokens x 32768 channels x 4 bytes = 2 MiB of Kronecker scratch: beyond the fixed 1 MiB array
     assert act(fake, 0, 16, 32768, ctypes.byref(Rot(2, 128, 256, fake)), 1.0, fake, fake, None) == -5
     assert b"exceed" in lib.rcp_last_error()
+
+
+def test_sequence_entry_point_rejects_before_touching_the_device(lib):
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+
+    class Step(ctypes.Structure):
+        _fields_ = [("packed", vp), ("codebook", vp), ("N", ci), ("K", ci), ("x", vp), ("x_dtype", ci), ("rot", Rot),
+                    ("clip_ratio", ctypes.c_float), ("out", vp), ("out_dtype", ci), ("xq_out", vp), ("scale_out", vp)]
+    seq = lib.rcp_quant_w2a4_gemv_sequence
+    seq.argtypes = [ctypes.POINTER(Step), ci, vp, ctypes.c_size_t, vp]
+    need = lib.rcp_gemv_sequence_workspace_bytes
+    need.argtypes = [ctypes.POINTER(Step), ci]
+    need.restype = ctypes.c_size_t
+    fake = 0x1000
+    good = Step(fake, fake, 64, 128, fake, 0, Rot(0, 0, 1, None), 1.0, fake, 0, None, None)
+    arr = (Step * 2)(good, good)
+    assert need(arr, 2) > 0 and need(arr, 0) == 0 and need(arr, 17) == 0
+    assert seq(None, 1, vp(fake), 1 << 20, None) == -1
+    assert seq(arr, 0, vp(fake), 1 << 20, None) == -2
+    assert seq(arr, 2, None, 1 << 20, None) == -1
+    assert seq(arr, 2, vp(fake), 16, None) == -5
+    assert seq(arr, 2, vp(fake + 16), 1 << 20, None) == -3          # workspace not 256-byte aligned
+    bad = (Step * 1)(Step(fake, fake, 64, 32768, fake, 0, Rot(0, 0, 1, None), 1.0, fake, 0, None, None))
+    assert seq(bad, 1, vp(fake), 1 << 20, None) == -4               # K beyond the in-kernel quantiser
+    bad = (Step * 1)(Step(fake, fake, 64, 128, fake, 0, Rot(1, 128, 1, None), 1.0, fake, 0, None, None))
+    assert seq(bad, 1, vp(fake), 1 << 20, None) == -4               # pure Hadamard rotation
+    bad = (Step * 1)(Step(fake, fake, 64, 128, fake, 0, Rot(0, 0, 1, None), 1.0, fake, 2, None, None))
+    assert seq(bad, 1, vp(fake), 1 << 20, None) == -4               # bf16 output
+    bad = (Step * 1)(Step(fake, fake, 62, 128, fake, 0, Rot(0, 0, 1, None), 1.0, fake, 0, None, None))
+    assert seq(bad, 1, vp(fake), 1 << 20, None) == -2
