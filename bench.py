@@ -89,38 +89,51 @@ def timed(torch, fn, reps):
 
 
 def cpu_baseline():
-    """The oracle as it stands, on the host cores: one GEMV of each LLaMA-2-7B shape plus the
-    activation preparation, scaled to one decoder layer (4 x qkvo + 2 x gate/up + 1 x down)."""
+    """The oracle as it stands, on the host cores: GEMVs of each LLaMA-2-7B shape plus the activation preparation,
+    scaled to one decoder layer (4 x qkvo + 2 x gate/up + 1 x down); with all OpenMP threads (`value`, best of
+    five per shape; the median beside it) and once more on a single thread."""
     import numpy as np
 
     import oracle
     import rcp_synth
     cores = oracle.max_threads()
-    t_layer, b_layer = 0.0, 0
+    cases = []
     for (name, N, K, rot), count in zip(rcp_synth.CONFIGS["llama2_7b"], (4, 2, 1)):
         W, lo, hi, part = rcp_synth.linear_layer(0, "bench/" + name, N, K)
         packed, cb = oracle.pack_weights(W.astype(np.float32), lo, hi, part)
         x = rcp_synth.activation(0, "bench/" + name, 1, K)
-        t0 = time.perf_counter()
-        if rot is None:
-            y = x.astype(np.float64)
-        else:
-            Q = rcp_synth.orthogonal(0, rot[2]).astype(np.float64)
-            y = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=rot[1], m=rot[2], Q=Q)
-        xq, sc, _ = oracle.quantize_act(y.astype(np.float32), 1.0)
-        t_act = time.perf_counter() - t0
-        reps = []
-        for _ in range(5):  # median of five: the box's cores are shared and single timings scatter
+        cases.append((N, K, rot, count, packed, cb, x))
+    b_layer = sum(count * gemv_bytes(N, K) for (N, K, _, count, _, _, _) in cases)
+
+    def layer_time(reps, pick):
+        t_layer = 0.0
+        for (N, K, rot, count, packed, cb, x) in cases:
             t0 = time.perf_counter()
-            oracle.w2a4_gemv(packed, cb, N, K, xq, sc, 1)
-            reps.append(time.perf_counter() - t0)
-        t_gemv = sorted(reps)[2]
-        t_layer += count * t_gemv + t_act
-        b_layer += count * gemv_bytes(N, K)
-    return {"value": round(b_layer / t_layer / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": "one GEMV of each llama2_7b shape (4096x4096, 11008x4096, 4096x11008; median of 5 runs each) + "
+            if rot is None:
+                y = x.astype(np.float64)
+            else:
+                Q = rcp_synth.orthogonal(0, rot[2]).astype(np.float64)
+                y = oracle.rotate(x.astype(np.float64), oracle.ROT_KRON, n_wht=rot[1], m=rot[2], Q=Q)
+            xq, sc, _ = oracle.quantize_act(y.astype(np.float32), 1.0)
+            t_act = time.perf_counter() - t0
+            ts = []
+            for _ in range(reps):
+                t0 = time.perf_counter()
+                oracle.w2a4_gemv(packed, cb, N, K, xq, sc, 1)
+                ts.append(time.perf_counter() - t0)
+            t_layer += count * pick(sorted(ts)) + t_act
+        return t_layer
+    t_min = layer_time(5, lambda ts: ts[0])
+    t_med = layer_time(5, lambda ts: ts[len(ts) // 2])
+    oracle.set_threads(1)
+    t_one = layer_time(2, lambda ts: ts[0])
+    oracle.set_threads(cores)
+    return {"value": round(b_layer / t_min / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": "one GEMV of each llama2_7b shape (4096x4096, 11008x4096, 4096x11008; best of 5 runs each) + "
                       "activation preparation, scaled to one decoder layer (4+2+1 linears); oracle C code, fp64, OpenMP",
-            "ms_per_layer": round(t_layer * 1e3, 2)}
+            "ms_per_layer": round(t_min * 1e3, 2), "ms_per_layer_median": round(t_med * 1e3, 2),
+            "single_thread_ms_per_layer": round(t_one * 1e3, 2),
+            "single_thread_GBps": round(b_layer / t_one / 1e9, 4)}
 
 
 def main():
@@ -651,6 +664,171 @@ def main():
             kv_layer[label] = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2)}
         del lcaches, wl
 
+    # The other layer sizes of the paper's GEMV-latency tables (LLaMA-3.2-1B and LLaMA-3-8B configurations, and the
+    # tiny configuration), each with the rotation its input needs, cold over L different weight buffers (random
+    # indices and levels: the kernel's time does not depend on their values), a plain read of the same bytes beside it.
+    other = {}
+    if not args.step_only:
+        ocases = [("256x512_wht512", 256, 512, ("wht", 512)), ("2048x2048", 2048, 2048, None), ("8192x2048", 8192, 2048, None),
+                  ("2048x8192_wht8192", 2048, 8192, ("wht", 8192)), ("1024x4096", 1024, 4096, None),
+                  ("14336x4096", 14336, 4096, None), ("4096x14336_kron512x28", 4096, 14336, ("kron", 512, 28))]
+        for label, N, K, r in ocases:
+            nbuf = max(L, min(256, int(3.0e8 // (N * K // 4)) + 1))      # more than the 256 MB memory-side cache in total
+            bufs = [(torch.randint(0, 256, (N * K // 4,), dtype=torch.uint8, device=dev),
+                     (torch.randn((N, 4), device=dev) * 0.03).sort(dim=1).values.to(torch.float16).contiguous()) for _ in range(nbuf)]
+            xa = make_activation(torch, dev, 777 + K, K)
+            oo = torch.empty((1, N), dtype=torch.float16, device=dev)
+            xqo = torch.empty((1, K // 2), dtype=torch.uint8, device=dev)
+            sco = torch.empty((1,), dtype=torch.float16, device=dev)
+            yo = torch.empty((1, K), dtype=torch.float32, device=dev)
+            if r is None:
+                rot = None
+            elif r[0] == "wht":
+                rot = rcp.Rotation.wht(K)
+            else:
+                rot = rcp.Rotation.kron(r[1], torch.from_numpy(rcp_synth.orthogonal(args.seed, r[2])).to(dev))
+
+            def osweep(bufs=bufs, N=N, K=K, rot=rot, r=r, xa=xa, oo=oo, xqo=xqo, sco=sco, yo=yo, gemv_only=False):
+                for pk, lv in bufs:
+                    if r is None:
+                        rcp.quant_w2a4_gemv(pk, lv, N, K, xa, 1.0, out=oo)
+                    elif r[0] == "wht":        # rotate + quantise in one kernel, then the GEMV
+                        if not gemv_only:
+                            rcp.rotate_quant_act(xa, rot, 1.0, xq_out=xqo, scale_out=sco)
+                        rcp.w2a4_gemv(pk, lv, N, K, xqo, sco, 1, out=oo)
+                    else:                      # rotation kernel, then the fused quantise + GEMV
+                        if not gemv_only:
+                            rcp.rotate_act(xa, rot, y_out=yo)
+                        rcp.quant_w2a4_gemv(pk, lv, N, K, yo, 1.0, out=oo)
+            osweep()
+            fn = capture(osweep)
+            fn()
+            sec = timed(torch, fn, reps) / nbuf
+            b = gemv_bytes(N, K)
+            other[label] = {"us": round(sec * 1e6, 3), "GBps": round(b / sec / 1e9, 1), "buffers": nbuf}
+            if r is not None:
+                fn = capture(lambda: osweep(gemv_only=True))
+                fn()
+                other[label]["gemv_launch_only_us"] = round(timed(torch, fn, reps) / nbuf * 1e6, 3)
+
+            def orsweep(bufs=bufs, N=N, K=K):
+                for pk, _ in bufs:
+                    rcp.stream_read(pk, N * K // 4, sink)
+            fn = capture(orsweep)
+            fn()
+            other[label]["plain_read_us"] = round(timed(torch, fn, reps) / nbuf * 1e6, 3)
+            del bufs
+
+    # What a dependent launch costs on this machine, and what the same dependency costs inside one launch:
+    # (a) a chain of launches that read 16 bytes each; (b) a chain of the smallest fused GEMV (64 x 128) as launches;
+    # (c) the same 16 GEMVs as one rcp_quant_w2a4_gemv_sequence call -- per entry that is one meeting of all
+    # workgroups plus the quantiser on 128 values.
+    floor = {}
+    if not args.step_only:
+        tiny = torch.zeros(64, dtype=torch.uint8, device=dev)
+
+        def fsweep():
+            for _ in range(64):
+                rcp.stream_read(tiny, 16, sink)
+        fn = capture(fsweep)
+        fn()
+        floor["dependent_16_byte_read_launch_us"] = round(timed(torch, fn, reps * 4) / 64 * 1e6, 3)
+        tw = torch.randint(0, 256, (64 * 128 // 4,), dtype=torch.uint8, device=dev)
+        tl = (torch.randn((64, 4), device=dev) * 0.03).sort(dim=1).values.to(torch.float16).contiguous()
+        ta = [torch.randn((1, 128), device=dev).to(torch.float16)] + [torch.zeros((1, 128), dtype=torch.float16, device=dev) for _ in range(16)]
+
+        def tsweep():
+            for _ in range(4):
+                for i in range(16):
+                    rcp.quant_w2a4_gemv(tw, tl, 64, 128, ta[i], 1.0, out=ta[i + 1][:, :64])
+        tsweep()
+        fn = capture(tsweep)
+        fn()
+        floor["dependent_smallest_gemv_launch_us"] = round(timed(torch, fn, reps * 4) / 64 * 1e6, 3)
+        tsteps = [rcp.GemvStep(tw, tl, 64, 128, ta[i], ta[i + 1][0, :64]) for i in range(16)]
+        tws = rcp.gemv_sequence_workspace(tsteps)
+
+        def ssweep():
+            for _ in range(4):
+                rcp.quant_w2a4_gemv_sequence(tsteps, tws)
+        ssweep()
+        fn = capture(ssweep)
+        fn()
+        t_seq = timed(torch, fn, reps * 4) / 4
+        floor["sequence_of_16_smallest_gemvs_us_per_entry"] = round(t_seq / 16 * 1e6, 3)
+        floor["sequence_error_word"] = int(tws[0].item())
+
+    # The four GEMVs of a layer as a real chain (o reads q, gate|up reads o's output, down reads the rotated gate half
+    # of gate|up's output; every layer starts from the same synthetic input): launched one by one (5 launches per
+    # layer) and as one rcp_quant_w2a4_gemv_sequence launch per layer (and per 4 layers).  Same bits either way.
+    persistent = None
+    if not args.step_only:
+        co = [torch.zeros((1, N), dtype=torch.float16, device=dev) for (_, N, _, _) in launches]
+
+        def chain_launches():
+            for l in range(L):
+                w = layers[l]
+                rcp.quant_w2a4_gemv(w[0][0], w[0][1], 3 * HIDDEN, HIDDEN, xs[0], 1.0, out=co[0])
+                rcp.quant_w2a4_gemv(w[1][0], w[1][1], HIDDEN, HIDDEN, co[0][0, :HIDDEN], 1.0, out=co[1])
+                rcp.quant_w2a4_gemv(w[2][0], w[2][1], 2 * INTER, HIDDEN, co[1], 1.0, out=co[2])
+                rcp.rotate_act(co[2][:, :INTER], rot_down, y_out=ybuf)
+                rcp.quant_w2a4_gemv(w[3][0], w[3][1], HIDDEN, INTER, ybuf, 1.0, out=co[3])
+
+        def chain_steps(l):
+            w = layers[l]
+            return [rcp.GemvStep(w[0][0], w[0][1], 3 * HIDDEN, HIDDEN, xs[0], co[0]),
+                    rcp.GemvStep(w[1][0], w[1][1], HIDDEN, HIDDEN, co[0][0, :HIDDEN], co[1]),
+                    rcp.GemvStep(w[2][0], w[2][1], 2 * INTER, HIDDEN, co[1], co[2]),
+                    rcp.GemvStep(w[3][0], w[3][1], HIDDEN, INTER, co[2][0, :INTER], co[3], rot=rot_down)]
+        per_layer = [chain_steps(l) for l in range(L)]
+        per_four = [sum(per_layer[l:l + 4], []) for l in range(0, L - L % 4, 4)]
+        wsq = rcp.gemv_sequence_workspace(per_four[0] if per_four else per_layer[0])
+
+        def chain_sequence():
+            for st in per_layer:
+                rcp.quant_w2a4_gemv_sequence(st, wsq)
+
+        def chain_sequence4():
+            for st in per_four:
+                rcp.quant_w2a4_gemv_sequence(st, wsq)
+        chain_launches()
+        fn = capture(chain_launches)
+        fn()
+        t_l = timed(torch, fn, max(3, args.steps // 2)) / L
+        ref_out = co[3].clone()
+        chain_sequence()
+        fn = capture(chain_sequence)
+        fn()
+        t_s = timed(torch, fn, max(3, args.steps // 2)) / L
+        same = bool(torch.equal(ref_out, co[3]))
+        layer_bytes = sum(gemv_bytes(N, K) for (_, N, K, _) in launches)
+        persistent = {"chained_launches_us_per_layer": round(t_l * 1e6, 2), "chained_launches_GBps": round(layer_bytes / t_l / 1e9, 1),
+                      "sequence_us_per_layer": round(t_s * 1e6, 2), "sequence_GBps": round(layer_bytes / t_s / 1e9, 1),
+                      "sequence_pct_of_hbm_peak": round(100.0 * layer_bytes / t_s / 1e9 / HBM_PEAK_GBPS, 2),
+                      "same_bits_as_launches": same}
+        if per_four:
+            fn = capture(chain_sequence4)
+            fn()
+            t4 = timed(torch, fn, max(3, args.steps // 2)) / (4 * len(per_four))
+            persistent["sequence_4_layers_per_launch_us_per_layer"] = round(t4 * 1e6, 2)
+        persistent["error_word"] = int(wsq[0].item())
+
+    # The down projection's prologue: the fused call quantises the 11008 rotated binary32 values in every workgroup;
+    # the same GEMV on activations quantised beforehand shows what that costs (cold, same 32 weight buffers).
+    down_split = None
+    if not args.step_only:
+        rcp.rotate_quant_act(xs[3], rot_down, 1.0, xq_out=xqs[3], scale_out=scs[3], workspace=ws)
+
+        def dsweep():
+            for l in range(L):
+                packed, cb = layers[l][3]
+                rcp.w2a4_gemv(packed, cb, HIDDEN, INTER, xqs[3], scs[3], 1, out=outs[3])
+        fn = capture(dsweep)
+        fn()
+        down_split = {"prequantised_gemv_us": round(timed(torch, fn, reps) / L * 1e6, 3)}
+        if "4096x11008" in per_shape:
+            down_split["fused_quantise_gemv_us"] = per_shape["4096x11008"]["us"]
+
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
     if os.path.exists(tpath):
@@ -692,6 +870,10 @@ def main():
         "kv4_attention_32_heads": kv4,
         "kv4_attention_batched": kv4_batched,
         "kv4_layer_launches": kv_layer,
+        "per_shape_other": other,
+        "launch_floor": floor,
+        "persistent_layer": persistent,
+        "down_projection_prologue": down_split,
         "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
         "setup_s": round(t_setup, 1),

@@ -315,7 +315,8 @@ int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, 
  * counters at zero again).  Word 0 (uint32) is an error flag: it stays 0 unless a wait inside the
  * kernel ran out of its bound -- only possible when the launch's workgroups were not all resident
  * at once, e.g. next to another kernel on the same GPU -- in which case the outputs are undefined and the
- * workspace has to be zeroed again.  Calls sharing a workspace must not overlap.  The grid (two
+ * workspace has to be zeroed again.  Calls sharing a workspace must not overlap; sequences of different
+ * length may share one (its layout does not depend on n), sized for the largest rotated K among them.  The grid (two
  * workgroups per compute unit, or "seq_blocks") is checked against the kernel's occupancy on the
  * host and refused with RCP_ERR_UNSUPPORTED when it could not be resident at once.
  */

@@ -565,6 +565,14 @@ __global__ __launch_bounds__(SEQ_THREADS) void gemv_sequence_kernel(const SeqArg
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
+// The layout of a workspace does not depend on the number of entries (header, the hops of the longest sequence, then
+// the rotated vector), so that calls with different sequences may share one workspace.
+static size_t seq_hop_area_bytes()
+{
+    const size_t bytes = SEQ_HEADER_BYTES + static_cast<size_t>(2 * RCP_SEQ_MAX_STEPS + 1) * SEQ_HOP_DWORDS * 4;
+    return (bytes + 255) & ~static_cast<size_t>(255);
+}
+
 static bool kron_fits(int n, int m)
 {
     return m % 4 == 0 && m >= 8 && n >= 64 && n <= 1024 && (n / 64) * ((m / 4 + 3) / 4) <= SEQ_KRON_MAXQ;
@@ -575,9 +583,7 @@ size_t gemv_sequence_workspace_bytes(const rcp_gemv_step* steps, int n)
     size_t max_rot = 0;
     for (int i = 0; i < n; ++i)
         if (steps[i].rot.kind == RCP_ROT_KRON && static_cast<size_t>(steps[i].K) > max_rot) max_rot = steps[i].K;
-    size_t bytes = SEQ_HEADER_BYTES + static_cast<size_t>(2 * n + 1) * SEQ_HOP_DWORDS * 4;
-    bytes = (bytes + 255) & ~static_cast<size_t>(255);
-    return bytes + max_rot * sizeof(float);
+    return seq_hop_area_bytes() + max_rot * sizeof(float);
 }
 
 int launch_gemv_sequence(const rcp_gemv_step* steps, int n, void* workspace, hipStream_t st)
@@ -658,9 +664,7 @@ int launch_gemv_sequence(const rcp_gemv_step* steps, int n, void* workspace, hip
             return fail(RCP_ERR_UNSUPPORTED, "rcp_quant_w2a4_gemv_sequence: entry %d: %d rotation columns need as many workgroups (%d)", i,
                         a.s[i].rot_m, a.nwg);
     uint32_t* ws = static_cast<uint32_t*>(workspace);
-    size_t hop_bytes = SEQ_HEADER_BYTES + static_cast<size_t>(2 * n + 1) * SEQ_HOP_DWORDS * 4;
-    hop_bytes = (hop_bytes + 255) & ~static_cast<size_t>(255);
-    float* ybuf = reinterpret_cast<float*>(static_cast<char*>(workspace) + hop_bytes);
+    float* ybuf = reinterpret_cast<float*>(static_cast<char*>(workspace) + seq_hop_area_bytes());
 #ifdef RCP_SEQ_TRACE
     gemv_sequence_kernel<<<a.nwg, SEQ_THREADS, lds, st>>>(a, ws, ybuf, g_seq_trace);
 #else

@@ -110,7 +110,6 @@ def test_small_ragged_chain_every_type_and_few_workgroups(x_dtype, out_dtype, bl
     entry, bf16 / fp32 first inputs, and grids far smaller than the number of row groups."""
     _say(f"sequence: small chain {x_dtype} -> {out_dtype}, seq_blocks={blocks}")
     rcp.set_option("seq_blocks", blocks)
-    shapes = [(1028, 608), (608, 1028 - 4), (96, 608)]
     shapes = [(1028, 608), (608, 1024), (96, 608)]
     w = _random_layer(9, shapes)
     x = _t(rcp_synth.activation(9, "seq_small", 1, 608)).to(x_dtype)
@@ -167,6 +166,37 @@ def test_rotated_entries_equal_rotate_act_then_the_fused_call(n, m, x_dtype):
     assert torch.equal(o1_g, o1_r)
 
 
+def test_sequences_of_different_length_share_one_workspace():
+    """A rotated 2-entry sequence and a 12-entry sequence take turns on one workspace (the rotated vector of the first
+    must not land where the second keeps its counters)."""
+    _say("sequence: two sequences, one workspace")
+    n, m = 64, 28
+    K = n * m
+    w = _random_layer(31, [(K, 256), (128, K), (256, 256)])
+    Q = _t(rcp_synth.orthogonal(6, m))
+    rot = rcp.Rotation.kron(n, Q)
+    x = _t(rcp_synth.activation(31, "share", 1, 256))
+    a0 = torch.zeros((1, K), dtype=torch.float16, device=DEV)
+    a1 = torch.zeros((1, 128), dtype=torch.float16, device=DEV)
+    short = [rcp.GemvStep(w[0][0], w[0][1], K, 256, x, a0), rcp.GemvStep(w[1][0], w[1][1], 128, K, a0, a1, rot=rot)]
+    bufs = [x] + [torch.zeros((1, 256), dtype=torch.float16, device=DEV) for _ in range(12)]
+    long_ = [rcp.GemvStep(w[2][0], w[2][1], 256, 256, bufs[i], bufs[i + 1]) for i in range(12)]
+    ws = rcp.gemv_sequence_workspace(short)
+    assert ws.numel() >= rcp.gemv_sequence_workspace(long_).numel()
+    for _ in range(3):
+        rcp.quant_w2a4_gemv_sequence(short, ws)
+        rcp.quant_w2a4_gemv_sequence(long_, ws)
+    _sync_and_check(ws, K)
+    r0 = rcp.quant_w2a4_gemv(w[0][0], w[0][1], K, 256, x, 1.0)
+    r1 = rcp.quant_w2a4_gemv(w[1][0], w[1][1], 128, K, rcp.rotate_act(r0, rot), 1.0)
+    cur = x
+    for i in range(12):
+        cur = rcp.quant_w2a4_gemv(w[2][0], w[2][1], 256, 256, cur, 1.0)
+        torch.cuda.synchronize()
+        assert torch.equal(cur, bufs[i + 1]), i
+    assert torch.equal(r0, a0) and torch.equal(r1, a1)
+
+
 def test_chain_against_the_oracle():
     """Export -> chain of two entries (the second rotated) on the GPU; the oracle takes the same steps on the CPU, its
     GEMVs consuming the GPU's (x_q, S) so that a legal tie flip of the Kronecker rotation cannot leak in."""
@@ -219,7 +249,7 @@ def test_argument_errors_and_limits():
     with pytest.raises(rcp.RcpError):      # too many entries
         rcp.quant_w2a4_gemv_sequence([step] * 17, torch.zeros(1 << 18, dtype=torch.int32, device=DEV))
     with pytest.raises(rcp.RcpError):      # workspace too small
-        rcp.quant_w2a4_gemv_sequence([step, step], ws)
+        rcp.quant_w2a4_gemv_sequence([step, step], ws[:ws.numel() - 64])
     with pytest.raises(rcp.RcpError):      # a pure Hadamard rotation is not rotated inside a sequence
         rcp.quant_w2a4_gemv_sequence([rcp.GemvStep(w[0][0], w[0][1], 64, 128, x, o, rot=rcp.Rotation.wht(128))], ws)
     rcp.set_option("seq_blocks", 4096)
