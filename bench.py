@@ -669,7 +669,8 @@ def main():
     # indices and levels: the kernel's time does not depend on their values), a plain read of the same bytes beside it.
     other = {}
     if not args.step_only:
-        ocases = [("256x512_wht512", 256, 512, ("wht", 512)), ("2048x2048", 2048, 2048, None), ("8192x2048", 8192, 2048, None),
+        ocases = [("256x512_wht512", 256, 512, ("wht", 512)), ("2048x2048", 2048, 2048, None),
+                  ("2048x2048_wht2048", 2048, 2048, ("wht", 2048)), ("8192x2048", 8192, 2048, None),
                   ("2048x8192_wht8192", 2048, 8192, ("wht", 8192)), ("1024x4096", 1024, 4096, None),
                   ("14336x4096", 14336, 4096, None), ("4096x14336_kron512x28", 4096, 14336, ("kron", 512, 28))]
         for label, N, K, r in ocases:
@@ -688,10 +689,12 @@ def main():
             else:
                 rot = rcp.Rotation.kron(r[1], torch.from_numpy(rcp_synth.orthogonal(args.seed, r[2])).to(dev))
 
-            def osweep(bufs=bufs, N=N, K=K, rot=rot, r=r, xa=xa, oo=oo, xqo=xqo, sco=sco, yo=yo, gemv_only=False):
+            def osweep(bufs=bufs, N=N, K=K, rot=rot, r=r, xa=xa, oo=oo, xqo=xqo, sco=sco, yo=yo, gemv_only=False, two=False):
                 for pk, lv in bufs:
                     if r is None:
                         rcp.quant_w2a4_gemv(pk, lv, N, K, xa, 1.0, out=oo)
+                    elif r[0] == "wht" and K <= 2048 and not two and not gemv_only:   # short rotation: inside the GEMV launch
+                        rcp.rotate_quant_w2a4_gemv(pk, lv, N, K, xa, rot, 1.0, out=oo)
                     elif r[0] == "wht":        # rotate + quantise in one kernel, then the GEMV
                         if not gemv_only:
                             rcp.rotate_quant_act(xa, rot, 1.0, xq_out=xqo, scale_out=sco)
@@ -710,6 +713,10 @@ def main():
                 fn = capture(lambda: osweep(gemv_only=True))
                 fn()
                 other[label]["gemv_launch_only_us"] = round(timed(torch, fn, reps) / nbuf * 1e6, 3)
+                if r[0] == "wht" and K <= 2048:
+                    fn = capture(lambda: osweep(two=True))
+                    fn()
+                    other[label]["rotation_as_its_own_launch_us"] = round(timed(torch, fn, reps) / nbuf * 1e6, 3)
 
             def orsweep(bufs=bufs, N=N, K=K):
                 for pk, _ in bufs:

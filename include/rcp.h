@@ -283,8 +283,10 @@ int rcp_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
  * rcp_quant_w2a4_gemv with an online rotation inside the same launch: rot = NULL / RCP_ROT_NONE is
  * rcp_quant_w2a4_gemv; RCP_ROT_HEADS (K <= 16384) applies the Hadamard matrix across heads in
  * the prologue of the GEMV kernel and is bit-identical to rcp_rotate_quant_act(RCP_ROT_HEADS)
- * followed by rcp_w2a4_gemv.  The other kinds return RCP_ERR_UNSUPPORTED: a transform over all of
- * K would be repeated by every workgroup; run rcp_rotate_act first.  rot: host pointer.
+ * followed by rcp_w2a4_gemv; RCP_ROT_WHT with K <= 2048 (the order-K Hadamard rotation of a short input,
+ * Appendix definition of H_n) runs in the prologue too, bit-identical to rcp_rotate_quant_act(RCP_ROT_WHT)
+ * followed by rcp_w2a4_gemv.  Longer pure rotations and RCP_ROT_KRON return RCP_ERR_UNSUPPORTED: a long
+ * transform over all of K would be repeated by every workgroup; run rcp_rotate_act first.  rot: host pointer.
  */
 int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, int K,
                                const void* x, rcp_dtype x_dtype, const rcp_rotation* rot, float clip_ratio,

@@ -71,33 +71,6 @@ __global__ __launch_bounds__(1024) void quant_kernel(const void* __restrict__ x,
 // later pass gathers, through LDS, the EPT elements whose indices differ in the next LE
 // index bits and does those strides in registers.
 // ---------------------------------------------------------------------------------------
-template <int LE>
-__device__ __forceinline__ void register_stages(float (&v)[1 << LE], int first_bit)
-{
-#pragma unroll
-    for (int b = 0; b < LE; ++b) {
-        if (b < first_bit) continue;
-        const int s = 1 << b;
-#pragma unroll
-        for (int i = 0; i < (1 << LE); ++i)
-            if ((i & s) == 0) {
-                const float p = v[i], q = v[i + s];
-                v[i] = p + q;
-                v[i + s] = p - q;
-            }
-    }
-}
-
-// Where element a of the transform lives in LDS.  Every access pattern of the kernel (EPT
-// consecutive elements per thread, and elements 2^lo apart per thread with neighbouring threads
-// on neighbouring low bits) has some index bits fixed across the lanes of a wavefront; folding
-// bits 3..5 into bits 0..2 and bits 6..7 into bits 3..4 makes each of them hit 32 different
-// banks per half wavefront (without it the first and last pass are 8- to 16-way conflicted).
-__device__ __forceinline__ int wht_slot(int a)
-{
-    return a ^ ((a >> 3) & 7) ^ (((a >> 6) & 3) << 3);
-}
-
 template <int DT, int LE, bool QUANT>
 __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict__ x, int n, int log2n, float norm,
                                                          float clip_ratio, int waves, uint32_t* __restrict__ xq,

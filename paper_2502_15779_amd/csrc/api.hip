@@ -322,9 +322,10 @@ int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, 
                                    scale_out_or_null, partial_sums_or_null, stream);
     if (!packed || !codebook || !x || !out) return fail(RCP_ERR_NULL, "rcp_rotate_quant_w2a4_gemv: NULL pointer argument");
     if (int rc = check_shape("rcp_rotate_quant_w2a4_gemv", N, K)) return rc;
-    if (rot->kind != RCP_ROT_HEADS)
-        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_w2a4_gemv: only RCP_ROT_NONE and RCP_ROT_HEADS run inside the "
-                                         "GEMV; use rcp_rotate_act + rcp_quant_w2a4_gemv for kind %d", rot->kind);
+    const bool short_wht = rot->kind == RCP_ROT_WHT && wht_gemv_supported(K);
+    if (rot->kind != RCP_ROT_HEADS && !short_wht)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_w2a4_gemv: only RCP_ROT_NONE, RCP_ROT_HEADS and RCP_ROT_WHT with "
+                                         "K <= 2048 run inside the GEMV; use rcp_rotate_act + rcp_quant_w2a4_gemv for kind %d", rot->kind);
     if (int rc = check_rotation("rcp_rotate_quant_w2a4_gemv", K, rot)) return rc;
     if (x_dtype != RCP_F16 && x_dtype != RCP_F32 && x_dtype != RCP_BF16)
         return fail(RCP_ERR_UNSUPPORTED, "rcp_rotate_quant_w2a4_gemv: unknown dtype %d", static_cast<int>(x_dtype));
@@ -337,6 +338,9 @@ int rcp_rotate_quant_w2a4_gemv(const void* packed, const void* codebook, int N, 
         return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_w2a4_gemv: device buffers must be 16-byte aligned");
     if ((reinterpret_cast<uintptr_t>(scale_out_or_null) & 1u) != 0)
         return fail(RCP_ERR_ALIGN, "rcp_rotate_quant_w2a4_gemv: scale_out must be 2-byte aligned");
+    if (short_wht)
+        return launch_wht_quant_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
+                                     scale_out_or_null, partial_sums_or_null, static_cast<hipStream_t>(stream));
     return launch_quant_gemv(packed, codebook, N, K, x, x_dtype, clip_ratio, out, out_dtype, xq_out_or_null,
                              scale_out_or_null, partial_sums_or_null, rot->n_wht, rot->m, static_cast<hipStream_t>(stream));
 }

@@ -42,6 +42,10 @@ constexpr int GEMV_WAVES = GEMV_THREADS / 64;
 // XDT = 4 + type: before quantising, the workgroup also applies the Hadamard rotation across
 // heads, y = (H_n (x) I_m) x (rot_n heads of rot_m channels), with the butterflies and the final
 // scaling of heads_wht_kernel, i.e. bit-identical to rcp_rotate_quant_act with RCP_ROT_HEADS.
+// XDT = 8 + type: the order-K Hadamard rotation itself, K <= 2048 (a thread holds eight consecutive
+// values, as in wht_quant_kernel): the same butterflies in the same passes, bit-identical to
+// rcp_rotate_quant_act with RCP_ROT_WHT.  For such short inputs the transform costs a workgroup less than
+// the launch of a rotation kernel costs the chain.
 constexpr int GEMV_XG = 8;  // groups of eight raw activations a thread can hold: K <= 16384
 
 // Order-NH Hadamard transform down the columns of the NH x m matrix in LDS (ascending stride, one
@@ -87,7 +91,8 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
     const uint4* __restrict__ xq = static_cast<const uint4*>(x_in);
     const void* __restrict__ xraw = x_in;
     static_assert(XDT < 0 || MT == 1, "the fused quantiser handles one token");
-    constexpr bool ROT = XDT >= 4;              // Hadamard across heads in the prologue
+    constexpr bool ROT = XDT >= 4 && XDT < 8;   // Hadamard across heads in the prologue
+    constexpr bool ROTW = XDT >= 8;             // order-K Hadamard rotation in the prologue (K <= 2048)
     constexpr int XT = XDT >= 0 ? (XDT & 3) : 0;  // storage type of the raw activation
     extern __shared__ uint4 smem4[];
     constexpr int SW = 64 / LW;                     // row groups side by side in a wavefront
@@ -261,6 +266,38 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
                 xr8[i][0] = lo4.x; xr8[i][1] = lo4.y; xr8[i][2] = lo4.z; xr8[i][3] = lo4.w;
                 xr8[i][4] = hi4.x; xr8[i][5] = hi4.y; xr8[i][6] = hi4.z; xr8[i][7] = hi4.w;
             }
+        }
+        if constexpr (ROTW) {
+            // y = H_K x: this thread's eight consecutive values take the strides 1, 2, 4 in registers, every
+            // later pass gathers through LDS the eight values whose indices differ in the next three bits
+            // (rot_n = K, rot_m = log2 K)
+            float* sy = reinterpret_cast<float*>(red + (WS > 1 ? 2 * NW * 4 * 3 * MT : 0));
+            const int tid = threadIdx.x;
+            const int log2n = rot_m;
+            const bool active = tid < xdw;
+            if (active) {
+                register_stages<3>(xr8[0], 0);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sy[wht_slot(tid * 8 + e)] = xr8[0][e];
+            }
+            int done = 3;
+            while (done < log2n) {  // uniform
+                const int lo = (done <= log2n - 3) ? done : (log2n - 3);
+                const int low = tid & ((1 << lo) - 1), high = tid >> lo;
+                const int base = (high << (lo + 3)) | low;
+                __syncthreads();
+                if (active) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) xr8[0][e] = sy[wht_slot(base | (e << lo))];
+                    register_stages<3>(xr8[0], done - lo);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) sy[wht_slot(base | (e << lo))] = xr8[0][e];
+                }
+                done = lo + 3;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xr8[0][e] = active ? __fmul_rn(sy[wht_slot(tid * 8 + e)], rot_norm) : 0.0f;
         }
         // per-token symmetric int4 quantiser, the same arithmetic as quant_kernel
         float a = 0.0f;
@@ -457,6 +494,7 @@ struct GemvArgs {
     float clip_ratio;
     void *xq_out, *scale_out;
     int rot_n, rot_m;  // Hadamard across rot_n heads of rot_m channels in the prologue (0: none)
+    bool rot_wht;      // instead: the order-K Hadamard rotation (rot_n = K, rot_m = log2 K)
 };
 
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT, int NW = GEMV_WAVES>
@@ -504,6 +542,11 @@ static int launch_mt(const GemvArgs& a, int blocks, hipStream_t st)
                                : launch_one<LW, WS, UNR, MT, false, XDT>(a, blocks, st)
     if (a.xraw != nullptr) {
         if constexpr (LW == 64 && WS == 1) {  // the rotating prologue exists for one wavefront per row group only
+            if (a.rot_n > 0 && a.rot_wht) {
+                if (a.x_dt == RCP_F16) RCP_GO(1, 8 + RCP_F16);
+                if (a.x_dt == RCP_F32) RCP_GO(1, 8 + RCP_F32);
+                RCP_GO(1, 8 + RCP_BF16);
+            }
             if (a.rot_n > 0) {
                 if (a.x_dt == RCP_F16) RCP_GO(1, 4 + RCP_F16);
                 if (a.x_dt == RCP_F32) RCP_GO(1, 4 + RCP_F32);
@@ -624,7 +667,7 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
 int launch_gemv(const void* packed, const void* codebook, int N, int K, const void* xq,
                 const void* scale, int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
 {
-    const GemvArgs a = {packed, codebook, N, K, xq, scale, M, out, out_dt, P, nullptr, RCP_F16, 1.0f, nullptr, nullptr, 0, 0};
+    const GemvArgs a = {packed, codebook, N, K, xq, scale, M, out, out_dt, P, nullptr, RCP_F16, 1.0f, nullptr, nullptr, 0, 0, false};
     return dispatch_gemv(a, st);
 }
 
@@ -635,7 +678,20 @@ int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, co
                       int rot_heads, int rot_head_dim, hipStream_t st)
 {
     const GemvArgs a = {packed, codebook, N, K, nullptr, nullptr, 1, out, out_dt, P, x, x_dt, clip_ratio, xq_out, scale_out,
-                        rot_heads, rot_head_dim};
+                        rot_heads, rot_head_dim, false};
+    return dispatch_gemv(a, st);
+}
+
+bool wht_gemv_supported(int K) { return K >= 32 && K <= 2048 && (K & (K - 1)) == 0; }
+
+int launch_wht_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                          float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                          hipStream_t st)
+{
+    int log2n = 0;
+    while ((1 << log2n) < K) ++log2n;
+    const GemvArgs a = {packed, codebook, N, K, nullptr, nullptr, 1, out, out_dt, P, x, x_dt, clip_ratio, xq_out, scale_out,
+                        K, log2n, true};
     return dispatch_gemv(a, st);
 }
 

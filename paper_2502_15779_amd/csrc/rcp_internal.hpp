@@ -89,6 +89,11 @@ int launch_quant_gemv(const void* packed, const void* codebook, int N, int K, co
                       float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
                       int rot_heads, int rot_head_dim, hipStream_t st);
 bool quant_gemv_supported(int K);
+// the same with the order-K Hadamard rotation in the prologue (K a power of two, at most 2048)
+bool wht_gemv_supported(int K);
+int launch_wht_quant_gemv(const void* packed, const void* codebook, int N, int K, const void* x, rcp_dtype x_dt,
+                          float clip_ratio, void* out, rcp_dtype out_dt, void* xq_out, void* scale_out, int32_t* P,
+                          hipStream_t st);
 // several dependent one-token GEMVs in one launch (gemv_seq.hip)
 size_t gemv_sequence_workspace_bytes(const rcp_gemv_step* steps, int n);
 int launch_gemv_sequence(const rcp_gemv_step* steps, int n, void* workspace, hipStream_t st);
@@ -272,6 +277,34 @@ __device__ __forceinline__ void cell_update(uint32_t b0, uint32_t b1, const uint
             acc[t][p][3] = dot8(x[t], pl[p], acc[t][p][3]);
         }
     }
+}
+
+// ---- Walsh-Hadamard butterflies shared by the activation kernels and the rotating GEMV prologue ----
+template <int LE>
+__device__ __forceinline__ void register_stages(float (&v)[1 << LE], int first_bit)
+{
+#pragma unroll
+    for (int b = 0; b < LE; ++b) {
+        if (b < first_bit) continue;
+        const int s = 1 << b;
+#pragma unroll
+        for (int i = 0; i < (1 << LE); ++i)
+            if ((i & s) == 0) {
+                const float p = v[i], q = v[i + s];
+                v[i] = p + q;
+                v[i + s] = p - q;
+            }
+    }
+}
+
+// Where element a of the transform lives in LDS.  Every access pattern of the kernel (EPT
+// consecutive elements per thread, and elements 2^lo apart per thread with neighbouring threads
+// on neighbouring low bits) has some index bits fixed across the lanes of a wavefront; folding
+// bits 3..5 into bits 0..2 and bits 6..7 into bits 3..4 makes each of them hit 32 different
+// banks per half wavefront (without it the first and last pass are 8- to 16-way conflicted).
+__device__ __forceinline__ int wht_slot(int a)
+{
+    return a ^ ((a >> 3) & 7) ^ (((a >> 6) & 3) << 3);
 }
 
 // ---- pieces shared by the one-launch-per-matrix GEMV and the sequence kernel ------------------

@@ -717,6 +717,46 @@ def test_fused_heads_rotation_quantise_gemv_equals_the_separate_calls(N, n, m, r
             rcp.rotate_quant_w2a4_gemv(pk, lv, N, K, xd, rcp.Rotation.wht(K), ratio)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("N,K,ratio", [(256, 512, 1.0), (64, 32, 1.0), (1028, 64, 0.9), (40, 128, 1.0), (2048, 2048, 1.0),
+                                       (516, 1024, 0.9), (8192, 2048, 1.0), (12, 256, 1.0)])
+def test_fused_short_hadamard_rotation_quantise_gemv(N, K, ratio, dtype):
+    """The order-K Hadamard rotation (K <= 2048) inside the fused quantise+GEMV launch: x_q and S bit-exact against the
+    oracle's binary32 butterfly + quantiser, P bit-exact against the oracle's GEMV, and every bit equal to the two
+    separate calls."""
+    _say(f"fused short WHT N={N} K={K} ratio={ratio} {dtype}")
+    packed, cb, _, _ = _gemv_case(93, N, K, 1)
+    x16 = rcp_synth.activation(93, f"fw{K}", 1, K)
+    xd = {"f16": _t(x16), "bf16": _t(x16.astype(np.float32)).to(torch.bfloat16),
+          "f32": _t(x16.astype(np.float32) * np.float32(1.0009765))}[dtype]
+    x32 = xd.to(torch.float32).cpu().numpy()
+    pk, lv = _t(packed), _t(cb.view(np.float16))
+    rot = rcp.Rotation.wht(K)
+    xq, sc = rcp.rotate_quant_act(xd, rot, ratio)
+    ref_out, ref_P = rcp.w2a4_gemv(pk, lv, N, K, xq, sc, 1, out_dtype=torch.float32, want_partial_sums=True)
+    xq2, sc2 = torch.zeros_like(xq), torch.zeros_like(sc)
+    out, P = rcp.rotate_quant_w2a4_gemv(pk, lv, N, K, xd, rot, ratio, out_dtype=torch.float32, xq_out=xq2, scale_out=sc2,
+                                        want_partial_sums=True)
+    o16 = rcp.rotate_quant_w2a4_gemv(pk, lv, N, K, xd, rot, ratio, out_dtype=torch.float16)
+    r16 = rcp.w2a4_gemv(pk, lv, N, K, xq, sc, 1, out_dtype=torch.float16)
+    torch.cuda.synchronize()
+    oxq, osc, _ = oracle.quantize_act(oracle.fwht_f32(x32), ratio)
+    assert np.array_equal(xq2.cpu().numpy(), oxq) and np.array_equal(sc2.cpu().numpy().view(np.uint16), osc)
+    assert torch.equal(xq2, xq) and torch.equal(sc2.view(torch.int16), sc.view(torch.int16))
+    _, oP = oracle.w2a4_gemv(packed, cb, N, K, oxq, osc, 1)
+    assert np.array_equal(P.cpu().numpy(), oP)
+    assert torch.equal(P, ref_P) and torch.equal(out, ref_out) and torch.equal(o16, r16)
+
+
+def test_long_hadamard_rotation_is_not_fused():
+    pk = torch.zeros(64 * 4096 // 4, dtype=torch.uint8, device=DEV)
+    lv = torch.zeros((64, 4), dtype=torch.float16, device=DEV)
+    x = torch.zeros((1, 4096), dtype=torch.float16, device=DEV)
+    with pytest.raises(rcp.RcpError) as e:
+        rcp.rotate_quant_w2a4_gemv(pk, lv, 64, 4096, x, rcp.Rotation.wht(4096), 1.0)
+    assert e.value.code == -4
+
+
 def test_heads_rotation_argument_errors():
     x = torch.zeros((1, 4096), dtype=torch.float16, device=DEV)
     for n, m in ((128, 32), (32, 100), (3, 1024)):
