@@ -472,6 +472,14 @@ int rcp_quant_w3a4_gemv(const void* packed, const void* codebook, int N, int K,
  *     lo = ratio * min(x), hi = ratio * max(x), s = fp16((hi - lo) / 15)   [1 when that is 0; capped at 65504]
  *     z = -rint(lo / s)  [clamped to int16],  c_j = clamp(rint(x_j / s) + z, 0, 15)
  *   with correctly rounded divisions and round-half-to-even.  Other cache positions are not touched.
+ *   The one clipping ratio scales the minimum and the maximum (the form of the paper's clipping equation):
+ *   the range of a group whose values all have one sign moves towards zero instead of shrinking about the
+ *   data, and what lies beyond ratio*max (ratio*min) takes the end code -- harmless for rotated keys and
+ *   values, which are centred near zero; pass clip_ratio = 1 for data that is not.  z is held in 16 bits: a group
+ *   with |lo / s| above 32767 (a range 2000 times narrower than its offset) saturates z and is misrepresented.
+ *   pos, n_tokens (and S below) are call arguments that the kernels receive by value: a captured HIP graph
+ *   replays the positions and lengths it was captured with, so a decode loop under graph capture must update
+ *   these kernel-node arguments (or re-capture) every step.
  * rcp_kv4_attn_decode: one query token against cache positions 0 .. S-1 (1 <= S <= S_max):
  *     out[h] = sum_t softmax_t(softmax_scale * q[h] . K[g][t]) * V[g][t],   g = h / (H_q / H_kv)
  *   q: [H_q][128] of `q_dtype`; out: [H_q][128] of `out_dtype` (RCP_F16 or RCP_F32); H_q a multiple of
@@ -498,7 +506,9 @@ int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int
  *   pos_host[b] (0 <= pos_host[b] < S_max, else RCP_ERR_SHAPE).  Arithmetic as rcp_kv4_append.
  * rcp_kv4_attn_decode_batched: q and out are [B][H_q][128]; sequence b attends to its first S_host[b] tokens
  *   (1 <= S_host[b] <= S_max).  Each row equals what rcp_kv4_attn_decode gives for that sequence alone
- *   (bit for bit when the "kv_tokens" option fixes the split length).  workspace: B * rcp_kv4_workspace_bytes(H_q, max_b S_host[b])
+ *   up to the order of its binary32 sums: the automatic split length is chosen from the total number of
+ *   cached tokens of the call, so a batched row and the single call agree bit for bit only when the
+ *   "kv_tokens" option fixes the split length, and within the stated tolerance otherwise.  workspace: B * rcp_kv4_workspace_bytes(H_q, max_b S_host[b])
  *   bytes.  H_q <= 4095. */
 int rcp_kv4_append_batched(const void* x, rcp_dtype x_dtype, int B, int H, int S_max, const int* pos_host,
                            int rotate, float clip_ratio, void* codes, void* params, void* stream);

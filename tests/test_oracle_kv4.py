@@ -100,6 +100,47 @@ def test_codes_are_the_nearest_points_of_the_grid_inside_the_clip_range():
     assert inside.mean() > 0.9
 
 
+def test_offset_groups_follow_eqn_1_on_the_clipped_range_in_double():
+    """Groups far from zero (either sign), checked in binary64 against Eqn. 1 with the stored (s, z): every code whose
+    value lies inside the clipped range [ratio*min, ratio*max] is within half a step of x/s + z and dequantises to
+    within s/2 of x; values outside that range take the end codes.  Because the one clipping ratio of the table scales
+    the minimum and the maximum (the form of the paper's clipping equation for weights), the range of a group that does
+    not straddle zero moves towards zero instead of shrinking about the data: for x in [a, a + w] with a > 0 only values
+    up to ratio*(a + w) keep their half-step accuracy.  That consequence of the reading is pinned here too."""
+    rng = np.random.default_rng(12)
+    for offset, width, ratio in [(0.0, 1.0, 0.95), (3.0, 1.0, 0.95), (-3.0, 2.0, 0.95), (40.0, 8.0, 1.0), (-250.0, 3.0, 1.0),
+                                 (7.5, 0.25, 0.9), (1000.0, 0.9, 1.0)]:
+        x = (offset + width * rng.random((6, 3, D))).astype(np.float32)
+        codes, params = _quantise(x, clip=ratio)
+        sb, z = oracle.kv4_params(params)
+        s = _f16(sb).T[:, :, None]
+        zz = z.T.astype(np.float64)[:, :, None]
+        c = _codes(codes).transpose(1, 0, 2).astype(np.float64)
+        x64 = x.astype(np.float64)
+        lo = ratio * x64.min(axis=-1, keepdims=True)
+        hi = ratio * x64.max(axis=-1, keepdims=True)
+        assert np.all(np.abs(zz + lo / s) <= 0.5 + 1e-3)                 # z = -round(lo / s), |z| far below the int16 limit
+        assert np.all(np.abs(s - (hi - lo) / 15.0) <= 2.0 ** -10 * s + 1e-12)
+        t = x64 / s + zz                                                 # Eqn. 1 before rounding and clamping
+        free = (t >= -0.5) & (t <= 15.5)                                 # rounds to a code without clamping
+        eps = 1e-4 + 2.0 ** -22 * np.abs(x64 / s)                        # the rounding decision is taken in binary32
+        assert np.all((np.abs(c - t) <= 0.5 + eps)[free])
+        assert np.all((np.abs(s * (c - zz) - x64) <= (0.5 + eps) * s)[free])
+        assert np.all(c[t < -0.5] == 0) and np.all(c[t > 15.5] == 15)
+        if ratio == 1.0:
+            assert free.mean() > 0.999           # nothing is clipped: the whole group keeps half-step accuracy
+        elif offset > 0:
+            clipped = x64 > hi + s               # the top of a positive group lies beyond ratio*max and saturates
+            assert clipped.any() and np.all(c[clipped] == 15)
+            if width < (1.0 - ratio) * offset:   # the whole group lies above ratio*max: every value takes the top code
+                assert np.all(c == 15)
+    # the zero point is stored in 16 bits: beyond |lo / s| = 32767 it saturates (both sides do the same)
+    x = np.full((1, 1, D), 60000.0, dtype=np.float32)
+    x[0, 0, 0] = 59999.0
+    _, params = _quantise(x, clip=1.0)
+    assert oracle.kv4_params(params)[1][0, 0] == -32768
+
+
 def test_zero_point_follows_the_minimum():
     # shifting a group by a whole number of steps shifts the zero point and leaves the codes
     rng = np.random.default_rng(4)
