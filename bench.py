@@ -147,6 +147,8 @@ def main():
     ap.add_argument("--split", action="store_true",
                     help="separate rcp_rotate_quant_act + rcp_w2a4_gemv launches instead of the fused quantise+GEMV call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sequence-only", action="store_true",
+                    help="run only the chained layer as one rcp_quant_w2a4_gemv_sequence launch per layer (used for profiles)")
     ap.add_argument("--step-only", action="store_true",
                     help="skip the per-shape, plain-read and small-batch side measurements (used for profiles)")
     args = ap.parse_args()
@@ -232,6 +234,33 @@ def main():
         for i in range(4):  # the GEMV-only sweeps of the split path read these
             rot = rot_down if launches[i][3] else None
             rcp.rotate_quant_act(xs[i], rot, 1.0, xq_out=xqs[i], scale_out=scs[i], workspace=ws if rot else None)
+    if args.sequence_only:
+        co = [torch.zeros((1, N), dtype=torch.float16, device=dev) for (_, N, _, _) in launches]
+        seqs = []
+        for l in range(L):
+            w = layers[l]
+            seqs.append([rcp.GemvStep(w[0][0], w[0][1], 3 * HIDDEN, HIDDEN, xs[0], co[0]),
+                         rcp.GemvStep(w[1][0], w[1][1], HIDDEN, HIDDEN, co[0][0, :HIDDEN], co[1]),
+                         rcp.GemvStep(w[2][0], w[2][1], 2 * INTER, HIDDEN, co[1], co[2]),
+                         rcp.GemvStep(w[3][0], w[3][1], HIDDEN, INTER, co[2][0, :INTER], co[3], rot=rot_down)])
+        wsq = rcp.gemv_sequence_workspace(seqs[0])
+
+        def seq_step():
+            for st in seqs:
+                rcp.quant_w2a4_gemv_sequence(st, wsq)
+        seq_step()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            seq_step()
+        for _ in range(args.warmup):
+            g.replay()
+        sec = timed(torch, g.replay, args.steps)
+        lb = sum(gemv_bytes(N, K) for (_, N, K, _) in launches)
+        print(json.dumps({"sequence_us_per_layer": round(sec / L * 1e6, 2), "GBps": round(L * lb / sec / 1e9, 1),
+                          "layers": L, "steps": args.steps, "error_word": int(wsq[0].item())}))
+        return
+
     step_eager()  # warm every code path before capture
     torch.cuda.synchronize()
     step = capture(step_eager)
