@@ -154,6 +154,10 @@ int rcp_version(void);
  *                  issued at once), 512, 1024, 2048 (the streaming kernel for long contexts and batches)
  *   "gemv_waves"   wavefronts per workgroup of the fused one-token GEMV (rcp_quant_w2a4_gemv): 4, 8
  *                  (8 needs K >= 2048 and "gemv_lanes" left automatic; otherwise 4 is used)
+ *   "gemv_oneshot" one-token kernel that issues every weight load of a workgroup up front (one group of four rows
+ *                  per wavefront, K <= 16384): 1 = for every such shape, 2 = never; automatic = matrices that give
+ *                  every compute unit one or two workgroups.  Ignored while "gemv_lanes", "gemv_blocks" or
+ *                  "gemv_unroll" is set (those address the general kernel).
  *   "seq_blocks"   workgroups of rcp_quant_w2a4_gemv_sequence (refused when they could not all be resident)
  *   "reset"        (value ignored) every knob back to automatic
  * Returns RCP_ERR_UNSUPPORTED for an unknown name or a value outside its set. */

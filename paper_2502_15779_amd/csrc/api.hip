@@ -28,7 +28,7 @@ int check_launch(const char* what)
 
 Options& options()
 {
-    static Options o = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    static Options o = {};
     return o;
 }
 
@@ -125,7 +125,7 @@ int rcp_set_option(const char* name, int value)
     if (name == nullptr) return fail(RCP_ERR_NULL, "rcp_set_option: name is NULL");
     Options& o = options();
     if (strcmp(name, "reset") == 0) {
-        o = Options{0, 0, 0, 0, 0, 0, 0, 0, 0};
+        o = Options{};
         return RCP_OK;
     }
     if (strcmp(name, "gemv_lanes") == 0) {
@@ -158,6 +158,9 @@ int rcp_set_option(const char* name, int value)
         if (value != 0 && value != 4 && value != 8)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_waves must be 0, 4 or 8");
         o.gemv_waves = value;
+    } else if (strcmp(name, "gemv_oneshot") == 0) {
+        if (value < 0 || value > 2) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_oneshot must be 0, 1 or 2");
+        o.gemv_oneshot = value;
     } else if (strcmp(name, "seq_blocks") == 0) {
         if (value < 0 || value > 4096) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: seq_blocks out of range");
         o.seq_blocks = value;

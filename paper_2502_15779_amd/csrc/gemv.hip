@@ -628,6 +628,12 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
     // several tokens: the contraction goes to the matrix cores (the fused quantiser is one token only)
     if (a.xraw == nullptr && gemv_variant(a.N, a.K, a.M) == 2)
         return launch_gemm_mfma(a.packed, a.codebook, a.N, a.K, a.xq, a.scale, a.M, a.out, a.out_dt, a.P, st);
+    // one token, no rotation in the prologue, one row group per wavefront: every load issued up front
+    if (a.M == 1 && a.rot_n == 0 && options().gemv_variant != 2 && options().gemv_waves != 8 &&
+        gemv_oneshot_applies(a.N, a.K, a.xraw != nullptr))
+        return launch_gemv_oneshot(a.packed, a.codebook, a.N, a.K, a.xraw != nullptr ? a.xraw : a.xq,
+                                   a.xraw != nullptr ? static_cast<int>(a.x_dt) : -1, a.scale, a.clip_ratio, a.out, a.out_dt, a.P,
+                                   a.xq_out, a.scale_out, st);
     GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
     if (a.rot_n > 0) {  // rotating prologue: one wavefront per row group
         p.lw = 64;

@@ -26,6 +26,7 @@ struct Options {
     int gemm_rows;       // output rows per workgroup of the matrix-core kernel: 16 or 64
     int kv_tokens;       // cached tokens per workgroup of the KV4 attention kernel: 64, 128 or 256
     int seq_blocks;      // workgroups of the GEMV sequence kernel
+    int gemv_oneshot;    // one-token GEMV with all loads issued up front: 0 automatic, 1 whenever the shape fits, 2 never
 };
 Options& options();
 int num_compute_units();
@@ -97,6 +98,10 @@ int launch_wht_quant_gemv(const void* packed, const void* codebook, int N, int K
 // several dependent one-token GEMVs in one launch (gemv_seq.hip)
 size_t gemv_sequence_workspace_bytes(const rcp_gemv_step* steps, int n);
 int launch_gemv_sequence(const rcp_gemv_step* steps, int n, void* workspace, hipStream_t st);
+// one-token GEMV with every load of a workgroup issued up front (gemv_oneshot.hip); x_dt < 0: quantised activations
+bool gemv_oneshot_applies(int N, int K, bool fused);
+int launch_gemv_oneshot(const void* packed, const void* codebook, int N, int K, const void* x, int x_dt, const void* scale,
+                        float clip_ratio, void* out, rcp_dtype out_dt, int32_t* P, void* xq_out, void* scale_out, hipStream_t st);
 int gemv_variant(int N, int K, int M);  // 1 vector-ALU kernel, 2 matrix-core kernel: what launch_gemv picks
 
 // ---- small device helpers ------------------------------------------------------------

@@ -124,6 +124,8 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.rcp_set_option(b"gemm_rows", 16) == 0 and lib.rcp_set_option(b"gemm_rows", 0) == 0
     assert lib.rcp_set_option(b"gemv_waves", 2) == -4
     assert lib.rcp_set_option(b"gemv_waves", 8) == 0 and lib.rcp_set_option(b"gemv_waves", 0) == 0
+    assert lib.rcp_set_option(b"gemv_oneshot", 3) == -4
+    assert lib.rcp_set_option(b"gemv_oneshot", 2) == 0 and lib.rcp_set_option(b"gemv_oneshot", 0) == 0
     gmm = lib.rcp_w2a4_gemm_grouped
     gmm.argtypes = [vp, vp, ci, ci, ci, vp, vp, ci, vp, ci, vp, vp]
     assert gmm(fake, fake, 8, 256, 128, fake, fake, 0, fake, 0, None, None) == -2

@@ -31,7 +31,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves", "gemm_rows"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves", "gemm_rows", "gemv_oneshot"):
         rcp.set_option(k, 0)
 
 
@@ -505,6 +505,75 @@ def test_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype, waves):
         out2 = rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, ratio, out_dtype=torch.float32)
         torch.cuda.synchronize()
         assert torch.equal(out, out2)
+
+
+@pytest.mark.parametrize("oneshot", [1, 2])
+@pytest.mark.parametrize("N,K", [(4, 1024), (1028, 1024), (72, 2080), (1028, 4096), (40, 5120), (72, 11008), (40, 14336),
+                                 (24, 16384), (1100, 8192)])
+def test_oneshot_gemv_partial_sums_bit_exact_and_output_close(N, K, oneshot):
+    """The kernel that issues every weight load up front (forced on: 1) and the general kernel on the same
+    shapes (2): ragged N, K that fills 1 .. 16 units per lane with a ragged last one."""
+    _say(f"one-shot gemv N={N} K={K} oneshot={oneshot}")
+    rcp.set_option("gemv_oneshot", oneshot)
+    packed, cb, xq, sc = _gemv_case(N + K + 1, N, K, 1)
+    _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32)
+    _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float16)
+
+
+def test_oneshot_gemv_extreme_activations_and_integer_codebook():
+    """q = -8 everywhere with index 3 everywhere: the largest accumulator magnitudes, exact integer output."""
+    rcp.set_option("gemv_oneshot", 1)
+    N, K = 16, 14336
+    idx = np.full((N, K), 3, np.uint8)
+    idx[1::2] = rcp_synth.random_indices(0, "ext1", N // 2, K)
+    cb = np.tile(np.array([0, 1, 2, 3], np.float16).view(np.uint16), (N, 1))
+    xq = np.full((1, K // 2), 0x88, np.uint8)
+    one = np.array([1.0], np.float16).view(np.uint16)
+    packed = oracle.pack_indices(idx)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, xq, one, 1)
+    out, P = rcp.w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, _t(xq), _t(one.view(np.float16)), 1,
+                           out_dtype=torch.float32, want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    assert np.array_equal(out.cpu().numpy().astype(np.float64), ref_O)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("N,K,ratio", [(1028, 1024, 1.0), (1028, 4096, 1.0), (40, 2080, 0.9), (64, 11008, 1.0), (24, 16384, 1.0),
+                                       (2052, 2048, 1.0)])
+def test_oneshot_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype):
+    """rcp_quant_w2a4_gemv through the one-shot kernel: x_q, S and P bit-exact against the oracle's quantiser +
+    GEMV, and the output bit-identical to the general kernel's."""
+    _say(f"one-shot fused N={N} K={K} ratio={ratio} {dtype}")
+    packed, cb, _, _ = _gemv_case(N * 5 + K, N, K, 1)
+    x16 = rcp_synth.activation(6, f"fused1{K}", 1, K)
+    if dtype == "f16":
+        xd = _t(x16)
+    elif dtype == "bf16":
+        xd = _t(x16.astype(np.float32)).to(torch.bfloat16)
+    else:
+        xd = _t(x16.astype(np.float32) * np.float32(0.99963))
+    x32 = xd.to(torch.float32).cpu().numpy()
+    res = {}
+    for oneshot in (1, 2):
+        rcp.set_option("gemv_oneshot", oneshot)
+        xq = torch.zeros((1, K // 2), dtype=torch.uint8, device=DEV)
+        sc = torch.zeros((1,), dtype=torch.float16, device=DEV)
+        out, P = rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, ratio, out_dtype=torch.float32,
+                                     xq_out=xq, scale_out=sc, want_partial_sums=True)
+        out16 = rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, ratio, out_dtype=torch.float16)
+        torch.cuda.synchronize()
+        res[oneshot] = (out, P, xq, sc, out16)
+    out, P, xq, sc, _ = res[1]
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, ratio)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, ref_xq, ref_sc, 1)
+    assert np.array_equal(P.cpu().numpy(), ref_P)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O) + 1e-30
+    for a, b in zip(res[1], res[2]):
+        assert torch.equal(a, b), "the one-shot kernel and the general kernel differ"
 
 
 # ------------------------------------------------------------------------------------------
