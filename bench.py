@@ -315,6 +315,21 @@ def main():
         per_shape[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1),
                             "pct_hbm_peak": round(100.0 * b / s / 1e9 / HBM_PEAK_GBPS, 2)}
 
+    # the same GEMV on activations quantised beforehand (rcp_w2a4_gemv): what the quantiser in the prologue costs
+    if fused:
+        for label, i, N in side_shapes:
+            K = launches[i][2]
+            rot = rot_down if launches[i][3] else None
+            rcp.rotate_quant_act(xs[i], rot, 1.0, xq_out=xqs[i], scale_out=scs[i], workspace=ws if rot else None)
+
+            def psweep(i=i, N=N, K=K):
+                for l in range(L):
+                    packed, cb = layers[l][i]
+                    rcp.w2a4_gemv(packed, cb, N, K, xqs[i], scs[i], 1, out=outs[i])
+            fn = capture(psweep)
+            fn()
+            per_shape[label]["prequantised_us"] = round(timed(torch, fn, reps) / L * 1e6, 3)
+
     # warm: the same launch on ONE layer's buffer over and over (weights resident in the 256 MB
     # memory-side cache after the first pass) -- reported apart from the cold numbers above
     for label, i, N in side_shapes:
@@ -865,13 +880,42 @@ def main():
         if "4096x11008" in per_shape:
             down_split["fused_quantise_gemv_us"] = per_shape["4096x11008"]["us"]
 
+    # Stored profiler figures (profiles/gemv_traffic.json, written from rocprofv3 runs of this file; its "commit" field
+    # names the build they were taken on): HBM bytes per GEMV launch from the FETCH_SIZE / WRITE_SIZE counters, and the
+    # kernel-trace durations, whose clock differs from the events used here (see "clocks").
     traffic = None
+    stored = {}
     tpath = os.path.join(ROOT, "profiles", "gemv_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            stored = json.load(open(tpath))
+            traffic = stored.get("hbm_bytes_per_launch")
         except Exception:
-            traffic = None
+            stored, traffic = {}, None
+    roofline = {"bound": "hbm", "kernel": "gemv_kernel / gemv_oneshot_kernel (the four GEMV launches of a layer)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "frac_events": round(achieved / HBM_PEAK_GBPS, 4),
+                "clocks": "achieved / frac / frac_events: algorithmic bytes per GEMV launch over the mean launch-to-launch time of "
+                          "a GEMV-only graph replay, HIP events on the launch stream (dispatch gaps included); frac_rocprof: the "
+                          "same bytes over the stored rocprofv3 kernel-trace mean duration",
+                "traffic_source": "stored: profiles/gemv_traffic.json" + (" @ " + str(stored.get("commit")) if stored.get("commit") else "")}
+    kt = stored.get("gemv_kernel_trace") or {}
+    if kt.get("call_weighted_mean_ns"):
+        roofline["frac_rocprof"] = round((step_bytes / n_gemv) / (kt["call_weighted_mean_ns"] * 1e-9) / 1e9 / HBM_PEAK_GBPS, 4)
+        per_kernel = {}
+        byname = {"qkv 12288x4096": (3 * HIDDEN, HIDDEN), "o 4096x4096": (HIDDEN, HIDDEN),
+                  "gate_up 22016x4096": (2 * INTER, HIDDEN), "down 4096x11008": (HIDDEN, INTER)}
+        for name, ns in (kt.get("avg_ns") or {}).items():
+            if name in byname:
+                b = gemv_bytes(*byname[name])
+                per_kernel[name] = {"rocprof_avg_us": round(ns * 1e-3, 3), "frac_rocprof": round(b / (ns * 1e-9) / 1e9 / HBM_PEAK_GBPS, 4)}
+        for name, label in (("qkv 12288x4096", "12288x4096_qkv"), ("o 4096x4096", "4096x4096"),
+                            ("gate_up 22016x4096", "22016x4096_gate_up"), ("down 4096x11008", "4096x11008")):
+            if name in per_kernel and label in per_shape:
+                per_kernel[name]["events_us"] = per_shape[label]["us"]
+                per_kernel[name]["frac_events"] = round(per_shape[label]["pct_hbm_peak"] / 100.0, 4)
+        roofline["per_kernel"] = per_kernel
 
     line = {
         "metric": "w2a4_gemv_effective_hbm_bandwidth_llama2_7b_bs1",
@@ -910,8 +954,7 @@ def main():
         "launch_floor": floor,
         "persistent_layer": persistent,
         "down_projection_prologue": down_split,
-        "roofline": {"bound": "hbm", "kernel": "gemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic},
+        "roofline": roofline,
         "setup_s": round(t_setup, 1),
     }
     if not args.no_cpu_baseline:
