@@ -610,8 +610,26 @@ def main():
         fn = capture(asweep_kv)
         fn()
         sa = timed(torch, fn, reps) / L
+        qraw = qv.to(torch.float16)
+
+        def ksweep_rot(S=S, kcaches=kcaches, qraw=qraw, ov=ov, wsk=wsk):   # R3 on the query inside the attention launch
+            for c in kcaches:
+                rcp.kv4_rotate_attn_decode(qraw, S, *c, 0.08838834764831845, out=ov, workspace=wsk)
+        ksweep_rot()
+        fn = capture(ksweep_rot)
+        fn()
+        sf = timed(torch, fn, reps) / L
+
+        def asweep_kv2(kx=kx, vx=vx, kcaches=kcaches, S=S):   # new key and new value in one launch
+            for c in kcaches:
+                rcp.kv4_append_kv(kx[:1], vx[:1], S - 1, c[0], c[1], c[2], c[3], rotate_k=True)
+        asweep_kv2()
+        fn = capture(asweep_kv2)
+        fn()
+        sa2 = timed(torch, fn, reps) / L
         kv4[f"S{S}"] = {"attn_us": round(s * 1e6, 3), "attn_GBps": round(b / s / 1e9, 1),
-                        "append_one_token_us": round(sa * 1e6, 3)}
+                        "rotate_attn_us": round(sf * 1e6, 3),
+                        "append_one_token_us": round(sa * 1e6, 3), "append_key_and_value_one_launch_us": round(sa2 * 1e6, 3)}
         del kcaches
 
     # several sequences in one call (pooled caches): enough distinct pools to exceed the 256 MB memory-side cache
@@ -699,13 +717,35 @@ def main():
                 gemv_call(l, i_gu, xs[i_gu], launches[i_gu][1], HIDDEN, outs[i_gu])
                 rcp.rotate_act(xs[i_down], rot_down, y_out=ybuf)
                 gemv_call(l, i_down, ybuf, HIDDEN, INTER, outs[i_down])
-        kv_layer = {"launches_per_layer": 11, "cached_tokens": S_ctx, "heads": Hh}
+
+        def kvstep_fused(gemv_call):
+            # the same chain in 8 launches: keys and values appended together, R3 on the query inside the attention
+            # launch
+            for l in range(L):
+                gemv_call(l, i_qkv, xs[i_qkv], 3 * HIDDEN, HIDDEN, qkv)
+                kc, kp, vc, vp = lcaches[l]
+                rcp.kv4_append_kv(qkv[0, HIDDEN:2 * HIDDEN].view(1, Hh, 128), qkv[0, 2 * HIDDEN:].view(1, Hh, 128), S_ctx - 1,
+                                  kc, kp, vc, vp, rotate_k=True)
+                rcp.kv4_rotate_attn_decode(qkv[0, :HIDDEN].view(Hh, 128), S_ctx, kc, kp, vc, vp, 0.08838834764831845,
+                                           out=attn_out, workspace=wsl)
+                gemv_call(l, i_o, attn_out.view(1, HIDDEN), HIDDEN, HIDDEN, outs[i_o])
+                gemv_call(l, i_gu, xs[i_gu], launches[i_gu][1], HIDDEN, outs[i_gu])
+                rcp.rotate_act(xs[i_down], rot_down, y_out=ybuf)
+                gemv_call(l, i_down, ybuf, HIDDEN, INTER, outs[i_down])
+        kv_layer = {"launches_per_layer": 11, "launches_per_layer_fused": 8, "cached_tokens": S_ctx, "heads": Hh}
         for label, call in (("w2a4kv4", w2), ("w3a4kv4", w3g)):
             kvstep(call)
             fn = capture(lambda call=call: kvstep(call))
             fn()
             s = timed(torch, fn, max(3, args.steps // 2))
-            kv_layer[label] = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2)}
+            ref_attn = attn_out.clone()
+            kvstep_fused(call)
+            fn = capture(lambda call=call: kvstep_fused(call))
+            fn()
+            sfu = timed(torch, fn, max(3, args.steps // 2))
+            kv_layer[label] = {"ms_per_step": round(s * 1e3, 4), "us_per_layer": round(s / L * 1e6, 2),
+                               "fused_ms_per_step": round(sfu * 1e3, 4), "fused_us_per_layer": round(sfu / L * 1e6, 2),
+                               "fused_same_bits": bool(torch.equal(ref_attn, attn_out))}
         del lcaches, wl
 
     # The other layer sizes of the paper's GEMV-latency tables (LLaMA-3.2-1B and LLaMA-3-8B configurations, and the

@@ -502,6 +502,23 @@ int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int
                         float softmax_scale, void* out, rcp_dtype out_dtype,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Fewer launches for a decode step over the 4-bit cache (same arithmetic, same bits as the calls above):
+ * rcp_kv4_append_kv: the new keys and the new values of the same n_tokens tokens in ONE launch -- exactly
+ *   rcp_kv4_append(k, ..., rotate_k, clip_ratio, k_codes, k_params) and rcp_kv4_append(v, ..., 0, clip_ratio, v_codes, v_params).
+ *   k and v: [n_tokens][H][128] of `x_dtype`.
+ * rcp_kv4_rotate_attn_decode: rcp_kv4_attn_decode on the UN-rotated query: the order-128 Hadamard rotation R3 of every
+ *   query head runs inside the attention kernel (while the cache loads are in flight), bit for bit what rcp_rotate_act
+ *   (RCP_ROT_WHT, n = 128, over the H_q rows of q) followed by rcp_kv4_attn_decode on its binary32 output gives.
+ */
+int rcp_kv4_append_kv(const void* k, const void* v, rcp_dtype x_dtype, int n_tokens, int H, int S_max, int pos,
+                      int rotate_k, float clip_ratio, void* k_codes, void* k_params, void* v_codes, void* v_params,
+                      void* stream);
+int rcp_kv4_rotate_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int S_max, int S,
+                               const void* k_codes, const void* k_params, const void* v_codes, const void* v_params,
+                               float softmax_scale, void* out, rcp_dtype out_dtype,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* Several sequences at once (the small-batch decode of Section 4.4's GEMM discussion applied to the cache):
  * B <= RCP_MAX_M sequences share pooled buffers, sequence b owning heads b*H .. b*H + H - 1 of
  * codes [B*H][S_max][64] / params [B*H][S_max][4].  pos_host / S_host are HOST arrays of B ints, read

@@ -190,6 +190,11 @@ def lib():
         L.rcp_kv4_attn_decode_batched.restype = ci
         L.rcp_kv4_attn_decode_batched.argtypes = [vp, ci, ci, ci, ci, ci, ip, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp,
                                                   ctypes.c_size_t, vp]
+        L.rcp_kv4_append_kv.restype = ci
+        L.rcp_kv4_append_kv.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp, vp]
+        L.rcp_kv4_rotate_attn_decode.restype = ci
+        L.rcp_kv4_rotate_attn_decode.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp,
+                                                 ctypes.c_size_t, vp]
         L.rcp_kv4_attn_decode.restype = ci
         L.rcp_kv4_attn_decode.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp,
                                           ctypes.c_size_t, vp]
@@ -654,6 +659,49 @@ def kv4_attn_decode(q, S, k_codes, k_params, v_codes, v_params, softmax_scale, o
                                      ctypes.c_float(softmax_scale), _dev(out, "out"), _DTYPES[out.dtype],
                                      _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                      _stream()))
+    return out
+
+
+def kv4_append_kv(k, v, pos, k_codes, k_params, v_codes, v_params, clip_ratio=0.95, rotate_k=False):
+    """The new keys and values k, v [n_tokens, H, 128] of the same tokens into both caches in one launch."""
+    if k.dim() != 3 or k.shape[2] != KV_HEAD_DIM or not k.is_contiguous() or v.shape != k.shape or v.dtype != k.dtype or \
+            not v.is_contiguous():
+        raise ValueError("k and v must be contiguous [n_tokens, H, 128] of one dtype")
+    n, H = int(k.shape[0]), int(k.shape[1])
+    for codes, params in ((k_codes, k_params), (v_codes, v_params)):
+        if codes.dtype != torch.uint8 or params.dtype != torch.uint8 or codes.dim() != 3 or codes.shape[0] != H or \
+                codes.shape[2] != KV_HEAD_DIM // 2 or tuple(params.shape) != (H, codes.shape[1], 4) or \
+                not codes.is_contiguous() or not params.is_contiguous() or codes.shape[1] != k_codes.shape[1]:
+            raise ValueError("codes must be uint8 [H, S_max, 64] and params uint8 [H, S_max, 4], contiguous, one S_max")
+    if n == 0:
+        return
+    _check(lib().rcp_kv4_append_kv(_dev(k, "k"), _dev(v, "v"), _DTYPES[k.dtype], n, H, int(k_codes.shape[1]), int(pos),
+                                   int(bool(rotate_k)), ctypes.c_float(clip_ratio), _dev(k_codes, "k_codes"),
+                                   _dev(k_params, "k_params"), _dev(v_codes, "v_codes"), _dev(v_params, "v_params"), _stream()))
+
+
+def kv4_rotate_attn_decode(q, S, k_codes, k_params, v_codes, v_params, softmax_scale, out=None, out_dtype=torch.float32,
+                           workspace=None):
+    """kv4_attn_decode on the un-rotated query: the order-128 Hadamard rotation of every query head runs inside the
+    attention kernel."""
+    if q.dim() != 2 or q.shape[1] != KV_HEAD_DIM or not q.is_contiguous():
+        raise ValueError("q must be contiguous [H_q, 128]")
+    H_q, H_kv, S_max = int(q.shape[0]), int(k_codes.shape[0]), int(k_codes.shape[1])
+    for c, p in ((k_codes, k_params), (v_codes, v_params)):
+        if c.dtype != torch.uint8 or p.dtype != torch.uint8 or tuple(c.shape) != (H_kv, S_max, KV_HEAD_DIM // 2) or \
+                tuple(p.shape) != (H_kv, S_max, 4) or not c.is_contiguous() or not p.is_contiguous():
+            raise ValueError("cache buffers must be uint8 [H_kv, S_max, 64] / [H_kv, S_max, 4], contiguous")
+    if out is None:
+        out = torch.empty((H_q, KV_HEAD_DIM), dtype=out_dtype, device=q.device)
+    if out.dtype not in (torch.float16, torch.float32) or out.numel() < H_q * KV_HEAD_DIM:
+        raise ValueError("out must be float16 or float32 [H_q, 128]")
+    if workspace is None:
+        workspace = torch.empty(max(kv4_workspace_bytes(H_q, S), 16), dtype=torch.uint8, device=q.device)
+    _check(lib().rcp_kv4_rotate_attn_decode(_dev(q, "q"), _DTYPES[q.dtype], H_q, H_kv, S_max, int(S), _dev(k_codes, "k_codes"),
+                                            _dev(k_params, "k_params"), _dev(v_codes, "v_codes"), _dev(v_params, "v_params"),
+                                            ctypes.c_float(softmax_scale), _dev(out, "out"), _DTYPES[out.dtype],
+                                            _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                            _stream()))
     return out
 
 

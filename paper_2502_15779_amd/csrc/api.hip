@@ -596,6 +596,24 @@ int rcp_kv4_append(const void* x, rcp_dtype x_dtype, int n_tokens, int H, int S_
                              static_cast<hipStream_t>(stream));
 }
 
+int rcp_kv4_append_kv(const void* k, const void* v, rcp_dtype x_dtype, int n_tokens, int H, int S_max, int pos, int rotate_k,
+                      float clip_ratio, void* k_codes, void* k_params, void* v_codes, void* v_params, void* stream)
+{
+    if (!k || !v || !k_codes || !k_params || !v_codes || !v_params) return fail(RCP_ERR_NULL, "rcp_kv4_append_kv: NULL pointer argument");
+    if (x_dtype != RCP_F16 && x_dtype != RCP_BF16 && x_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_append_kv: unknown x_dtype %d", static_cast<int>(x_dtype));
+    if (H <= 0 || S_max <= 0 || n_tokens < 0 || pos < 0 || static_cast<long long>(pos) + n_tokens > S_max)
+        return fail(RCP_ERR_SHAPE, "rcp_kv4_append_kv: H=%d, S_max=%d, pos=%d, n_tokens=%d do not fit", H, S_max, pos, n_tokens);
+    if (static_cast<long long>(n_tokens) * H > 0x7fffffffLL / RCP_KV_HEAD_DIM)
+        return fail(RCP_ERR_SHAPE, "rcp_kv4_append_kv: n_tokens * H too large");
+    if (!(clip_ratio > 0.0f) || clip_ratio > 1.0f)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_append_kv: clip_ratio must be in (0, 1]");
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_codes) || !aligned16(k_params) || !aligned16(v_codes) || !aligned16(v_params))
+        return fail(RCP_ERR_ALIGN, "rcp_kv4_append_kv: device buffers must be 16-byte aligned");
+    return launch_kv4_append_kv(k, v, x_dtype, n_tokens, H, S_max, pos, rotate_k != 0, clip_ratio, k_codes, k_params, v_codes, v_params,
+                                static_cast<hipStream_t>(stream));
+}
+
 int rcp_kv4_append_batched(const void* x, rcp_dtype x_dtype, int B, int H, int S_max, const int* pos_host, int rotate,
                            float clip_ratio, void* codes, void* params, void* stream)
 {
@@ -640,6 +658,32 @@ int rcp_kv4_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int
                     workspace ? workspace_bytes : static_cast<size_t>(0));
     return launch_kv4_attn(q, q_dtype, 1, H_q, H_kv, S_max, S, nullptr, k_codes, k_params, v_codes, v_params, softmax_scale,
                            out, out_dtype, workspace, static_cast<hipStream_t>(stream));
+}
+
+int rcp_kv4_rotate_attn_decode(const void* q, rcp_dtype q_dtype, int H_q, int H_kv, int S_max, int S, const void* k_codes,
+                               const void* k_params, const void* v_codes, const void* v_params, float softmax_scale, void* out,
+                               rcp_dtype out_dtype, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!q || !k_codes || !k_params || !v_codes || !v_params || !out)
+        return fail(RCP_ERR_NULL, "rcp_kv4_rotate_attn_decode: NULL pointer argument");
+    if (q_dtype != RCP_F16 && q_dtype != RCP_BF16 && q_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_rotate_attn_decode: unknown q_dtype %d", static_cast<int>(q_dtype));
+    if (out_dtype != RCP_F16 && out_dtype != RCP_F32)
+        return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_rotate_attn_decode: out_dtype must be RCP_F16 or RCP_F32");
+    if (H_q <= 0 || H_kv <= 0 || H_q % H_kv != 0 || H_q > 65535)
+        return fail(RCP_ERR_SHAPE, "rcp_kv4_rotate_attn_decode: H_q=%d must be a positive multiple of H_kv=%d", H_q, H_kv);
+    if (S_max <= 0 || S < 1 || S > S_max)
+        return fail(RCP_ERR_SHAPE, "rcp_kv4_rotate_attn_decode: S=%d must lie in 1 .. S_max=%d", S, S_max);
+    if (S > RCP_KV_MAX_S) return fail(RCP_ERR_UNSUPPORTED, "rcp_kv4_rotate_attn_decode: S=%d exceeds RCP_KV_MAX_S=%d", S, RCP_KV_MAX_S);
+    if (!aligned16(q) || !aligned16(k_codes) || !aligned16(k_params) || !aligned16(v_codes) || !aligned16(v_params) ||
+        !aligned16(out) || !aligned16(workspace))
+        return fail(RCP_ERR_ALIGN, "rcp_kv4_rotate_attn_decode: device buffers must be 16-byte aligned");
+    const size_t need = kv4_workspace_bytes(H_q, S);
+    if (workspace == nullptr || workspace_bytes < need)
+        return fail(RCP_ERR_WORKSPACE, "rcp_kv4_rotate_attn_decode: workspace of %zu bytes needed, %zu given", need,
+                    workspace ? workspace_bytes : static_cast<size_t>(0));
+    return launch_kv4_attn(q, q_dtype, 1, H_q, H_kv, S_max, S, nullptr, k_codes, k_params, v_codes, v_params, softmax_scale,
+                           out, out_dtype, workspace, static_cast<hipStream_t>(stream), true);
 }
 
 int rcp_kv4_attn_decode_batched(const void* q, rcp_dtype q_dtype, int B, int H_q, int H_kv, int S_max, const int* S_host,

@@ -31,15 +31,15 @@ struct KvBatch {
 // BATCHED: row i of x belongs to sequence i (one new token each), whose cache starts at head
 // i * H of the pooled cache and whose position is batch.v[i].
 template <int DT, bool ROT, bool BATCHED>
-__global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict__ x, int rows, int H, int S_max, int pos,
-                                                         float clip_ratio, uint32_t* __restrict__ codes,
-                                                         uint32_t* __restrict__ params, KvBatch batch)
+__device__ __forceinline__ void kv4_append_rows(const void* __restrict__ x, int rows, int H, int S_max, int pos, float clip_ratio,
+                                                uint32_t* __restrict__ codes, uint32_t* __restrict__ params, const KvBatch& batch,
+                                                int block)
 {
     // every product and difference below is rounded on its own (hi_c - lo_c must not become a
     // fused multiply-add: for a constant vector it has to be exactly zero).  The pragma covers
     // the operators written in this body, hence plain * and - rather than the __f*_rn wrappers.
 #pragma clang fp contract(off)
-    const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int row = block * 16 + (threadIdx.x >> 4);
     const int l = threadIdx.x & 15;
     const bool have = row < rows;
     const int rr = have ? row : rows - 1;  // surplus lanes repeat the last vector and store nothing
@@ -108,6 +108,31 @@ __global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict_
     }
 }
 
+template <int DT, bool ROT, bool BATCHED>
+__global__ __launch_bounds__(256) void kv4_append_kernel(const void* __restrict__ x, int rows, int H, int S_max, int pos,
+                                                         float clip_ratio, uint32_t* __restrict__ codes,
+                                                         uint32_t* __restrict__ params, KvBatch batch)
+{
+    kv4_append_rows<DT, ROT, BATCHED>(x, rows, H, S_max, pos, clip_ratio, codes, params, batch, blockIdx.x);
+}
+
+// The new keys and the new values of the same tokens in one launch: blockIdx.y = 0 quantises the keys (rotated when
+// rotate_k is set), blockIdx.y = 1 the values (never rotated) -- the arithmetic of kv4_append_kernel on each.
+template <int DT>
+__global__ __launch_bounds__(256) void kv4_append_kv_kernel(const void* __restrict__ k, const void* __restrict__ v, int rows, int H,
+                                                            int S_max, int pos, int rotate_k, float clip_ratio,
+                                                            uint32_t* __restrict__ k_codes, uint32_t* __restrict__ k_params,
+                                                            uint32_t* __restrict__ v_codes, uint32_t* __restrict__ v_params)
+{
+    const KvBatch none = {};
+    if (blockIdx.y == 0) {
+        if (rotate_k) kv4_append_rows<DT, true, false>(k, rows, H, S_max, pos, clip_ratio, k_codes, k_params, none, blockIdx.x);
+        else kv4_append_rows<DT, false, false>(k, rows, H, S_max, pos, clip_ratio, k_codes, k_params, none, blockIdx.x);
+    } else {
+        kv4_append_rows<DT, false, false>(v, rows, H, S_max, pos, clip_ratio, v_codes, v_params, none, blockIdx.x);
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // one-token attention, split along the sequence.
 // Workgroup (split, query head): L = 64, 128 or 256 cached tokens.  Four lanes own a token, 16 bytes (32
@@ -172,6 +197,126 @@ __device__ __forceinline__ float row_tokens_sum(float v)
     return v;
 }
 
+// The query values of a lane (32 consecutive elements of a head vector, the four lanes of a quad hold all 128) through
+// the normalised order-128 Hadamard transform: butterflies in ascending stride order (1 .. 16 in registers, 32 and 64
+// between the lanes of the quad), each output one IEEE add or subtract, then one multiplication by (float)(1/sqrt(128)):
+// bit for bit what rcp_rotate_act gives for a row of 128.
+__device__ __forceinline__ void kv_rotate_query(float (&t)[32], int piece)
+{
+#pragma clang fp contract(off)
+#pragma unroll
+    for (int st = 1; st < 32; st <<= 1)
+#pragma unroll
+        for (int e = 0; e < 32; ++e)
+            if ((e & st) == 0) {
+                const float a = t[e], b = t[e + st];
+                t[e] = a + b;
+                t[e + st] = a - b;
+            }
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {  // stride 32: the partner is lane piece ^ 1 of the quad
+        const float other = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(t[e]), 0xB1, 0xf, 0xf, false));
+        t[e] = (piece & 1) ? other - t[e] : t[e] + other;
+    }
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {  // stride 64: lane piece ^ 2
+        const float other = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(t[e]), 0x4E, 0xf, 0xf, false));
+        t[e] = (piece & 2) ? other - t[e] : t[e] + other;
+    }
+    const float norm = 0.088388347648318440550f;  // (float)(1 / sqrt(128))
+#pragma unroll
+    for (int e = 0; e < 32; ++e) t[e] = t[e] * norm;
+}
+
+// This lane's 32 query values in register order (r = 8 d + 4 e + b <-> element 8 d + 2 b + e) and their sum.
+template <int QDT>
+__device__ __forceinline__ float kv_query_registers(const Raw8<QDT> (&qraw)[4], bool rotate, int piece, float (&qr)[32])
+{
+    float t[32];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        float t8[8];
+        widen8<QDT>(qraw[d], t8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t[8 * d + e] = t8[e];
+    }
+    if (rotate) kv_rotate_query(t, piece);  // uniform
+    float qsum = 0.0f;
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                qr[8 * d + 4 * e + b] = t[8 * d + 2 * b + e];
+                qsum += qr[8 * d + 4 * e + b];
+            }
+    return qsum;
+}
+
+// out_hj = sum_i e^(m_i - M) acc_ij / sum_i e^(m_i - M) l_i over the splits i of one head (src: its partial results).
+// `groups` x 128 (virtual) threads: thread (g, j) merges the splits i = g, g + groups, ... of column j, four at a time so
+// that their loads are in flight together, against its own running maximum; the groups meet in LDS and are merged the
+// same way.
+constexpr int KV_CT = 1024;
+struct KvMergeLds {
+    float red[KV_CT / KV_D][KV_D];
+    float dred[KV_CT / KV_D], mred[KV_CT / KV_D];
+};
+
+__device__ __forceinline__ void kv_merge_head(const float* __restrict__ src, int splits, int groups, void* __restrict__ out,
+                                              bool out_f16, int h, KvMergeLds& lds, int nthreads)
+{
+    for (int vt = threadIdx.x; vt < groups * KV_D; vt += nthreads) {
+        const int j = vt & (KV_D - 1), g = vt >> 7;
+        float M = -INFINITY, num = 0.0f, den = 0.0f;
+        for (int i0 = g; i0 < splits; i0 += 4 * groups) {
+            float mi[4], li[4], ai[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = min(i0 + groups * u, splits - 1);
+                mi[u] = *(src + i * KV_PART + KV_D);
+                li[u] = *(src + i * KV_PART + KV_D + 1);
+                ai[u] = *(src + i * KV_PART + j);
+            }
+            float mb = M;
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + groups * u < splits) mb = fmaxf(mb, mi[u]);
+            const float r = __expf(M - mb);  // 0 on the first round (M = -inf, mb finite)
+            num *= r;
+            den *= r;
+            M = mb;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float e = (i0 + groups * u < splits) ? __expf(mi[u] - M) : 0.0f;
+                num = fmaf(e, ai[u], num);
+                den = fmaf(e, li[u], den);
+            }
+        }
+        lds.red[g][j] = num;  // a group without a split leaves M = -inf, num = den = 0
+        if (j == 0) {
+            lds.dred[g] = den;
+            lds.mred[g] = M;
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < KV_D) {
+        const int tid = threadIdx.x;
+        float Mt = lds.mred[0];
+        for (int w = 1; w < groups; ++w) Mt = fmaxf(Mt, lds.mred[w]);
+        float n = 0.0f, d = 0.0f;
+        for (int w = 0; w < groups; ++w) {
+            const float e = __expf(lds.mred[w] - Mt);
+            n = fmaf(e, lds.red[w][tid], n);
+            d = fmaf(e, lds.dred[w], d);
+        }
+        const float r = n / d;
+        if (out_f16) static_cast<__half*>(out)[h * KV_D + tid] = __float2half_rn(r);
+        else static_cast<float*>(out)[h * KV_D + tid] = r;
+    }
+}
+
 // BATCHED: blockIdx.z is the sequence; its length is batch.v[z], its caches start at head z * H_kv of
 // the pooled buffers, its query and partial results at row z * H_q; workgroups past its end leave.
 // Which (split, query head, cache head) a workgroup works on.  Workgroups go to the eight dies (each with
@@ -191,7 +336,9 @@ __device__ __forceinline__ bool kv_place(unsigned index, int splits, int rep, in
     return true;
 }
 
-template <int QDT, int ITERS, bool BATCHED>
+// QROT: the query first goes through the order-128 Hadamard transform (R3), in the prologue, while the cache loads are
+// in flight.
+template <int QDT, int ITERS, bool BATCHED, bool QROT = false>
 __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __restrict__ q, int S, int S_max, int rep, int splits,
                                                               float softmax_scale, const u32x4* __restrict__ k_codes,
                                                               const uint32_t* __restrict__ k_params,
@@ -242,19 +389,7 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
 
     // this lane's 32 query values in register order (the softmax scale goes onto the score)
     float qr[32];
-    float qsum = 0.0f;
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        float t8[8];
-        widen8<QDT>(qraw[d], t8);
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                qr[8 * d + 4 * e + b] = t8[2 * b + e];
-                qsum += qr[8 * d + 4 * e + b];
-            }
-    }
+    const float qsum = kv_query_registers<QDT>(qraw, QROT, piece, qr);
 
     const float unit = kv_fp8_unit(), inv_unit = 1.0f / unit;
     const float scale_by_unit = softmax_scale * inv_unit, qsum_unit = qsum * unit;
@@ -376,7 +511,7 @@ struct KvChunk {
     bool valid;
 };
 
-template <int QDT, bool BATCHED>
+template <int QDT, bool BATCHED, bool QROT = false>
 __global__ __launch_bounds__(KV_THREADS) void kv4_attn_stream_kernel(const void* __restrict__ q, int S, int S_max, int rep,
                                                                      int splits, float softmax_scale,
                                                                      const u32x4* __restrict__ k_codes,
@@ -423,19 +558,7 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_stream_kernel(const void*
     load(1, cB);
 
     float qr[32];
-    float qsum = 0.0f;
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        float t8[8];
-        widen8<QDT>(qraw[d], t8);
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                qr[8 * d + 4 * e + b] = t8[2 * b + e];
-                qsum += qr[8 * d + 4 * e + b];
-            }
-    }
+    const float qsum = kv_query_registers<QDT>(qraw, QROT, piece, qr);
     const float unit = kv_fp8_unit(), inv_unit = 1.0f / unit;
     const float scale_by_unit = softmax_scale * inv_unit, qsum_unit = qsum * unit;
 
@@ -551,21 +674,15 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_stream_kernel(const void*
     }
 }
 
-// out_hj = sum_i e^(m_i - M) acc_ij / sum_i e^(m_i - M) l_i over the splits i of head h.
-// One workgroup of `groups` x 128 threads per head: thread (g, j) merges the splits
-// i = g, g + groups, ... of column j, four at a time so that their loads are in flight together,
-// against its own running maximum; the groups meet in LDS and are merged the same way.
-constexpr int KV_CT = 1024;
-
+// The merge of the splits as a kernel of its own: one workgroup of `groups` x 128 threads per head (kv_merge_head).
 // BATCHED: blockIdx.x = sequence * H_q + head; a sequence of length batch.v[z] has written only its
 // first ceil(length / L) of the `splits` slots of each head.
 template <bool OUT_F16, bool BATCHED>
 __global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restrict__ part, int splits, int groups,
                                                             void* __restrict__ out, int L, KvBatch batch)
 {
-    __shared__ float red[KV_CT / KV_D][KV_D];
-    __shared__ float dred[KV_CT / KV_D], mred[KV_CT / KV_D];
-    const int h = blockIdx.x, tid = threadIdx.x, j = tid & (KV_D - 1), g = tid >> 7;
+    __shared__ KvMergeLds lds;
+    const int h = blockIdx.x;
     const float* src = part + static_cast<size_t>(h) * splits * KV_PART;
     if constexpr (BATCHED) {
         // the sequence's own number of splits and thread groups, so that the merge runs in the same order
@@ -573,50 +690,7 @@ __global__ __launch_bounds__(KV_CT) void kv4_combine_kernel(const float* __restr
         splits = (batch.v[h / batch.H_q] + L - 1) / L;
         groups = min(groups, (splits + 3) / 4);
     }
-    float M = -INFINITY, num = 0.0f, den = 0.0f;
-    for (int i0 = g < groups ? g : splits; i0 < splits; i0 += 4 * groups) {
-        float mi[4], li[4], ai[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = min(i0 + groups * u, splits - 1);
-            mi[u] = src[i * KV_PART + KV_D];
-            li[u] = src[i * KV_PART + KV_D + 1];
-            ai[u] = src[i * KV_PART + j];
-        }
-        float mb = M;
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            if (i0 + groups * u < splits) mb = fmaxf(mb, mi[u]);
-        const float r = __expf(M - mb);  // 0 on the first round (M = -inf, mb finite)
-        num *= r;
-        den *= r;
-        M = mb;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float e = (i0 + groups * u < splits) ? __expf(mi[u] - M) : 0.0f;
-            num = fmaf(e, ai[u], num);
-            den = fmaf(e, li[u], den);
-        }
-    }
-    red[g][j] = num;  // a group without a split leaves M = -inf, num = den = 0
-    if (j == 0) {
-        dred[g] = den;
-        mred[g] = M;
-    }
-    __syncthreads();
-    if (tid < KV_D) {
-        float Mt = mred[0];
-        for (int w = 1; w < groups; ++w) Mt = fmaxf(Mt, mred[w]);
-        float n = 0.0f, d = 0.0f;
-        for (int w = 0; w < groups; ++w) {
-            const float e = __expf(mred[w] - Mt);
-            n = fmaf(e, red[w][tid], n);
-            d = fmaf(e, dred[w], d);
-        }
-        const float r = n / d;
-        if (OUT_F16) static_cast<__half*>(out)[h * KV_D + tid] = __float2half_rn(r);
-        else static_cast<float*>(out)[h * KV_D + tid] = r;
-    }
+    kv_merge_head(src, splits, groups, out, OUT_F16, h, lds, groups * KV_D);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -662,12 +736,31 @@ int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_ma
     return check_launch("rcp_kv4_append");
 }
 
+// keys and values of the same n_tokens tokens in one launch
+int launch_kv4_append_kv(const void* k, const void* v, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, bool rotate_k,
+                         float clip_ratio, void* k_codes, void* k_params, void* v_codes, void* v_params, hipStream_t st)
+{
+    const int rows = n_tokens * H;
+    if (rows == 0) return RCP_OK;
+    const dim3 grid(static_cast<unsigned>((rows + 15) / 16), 2u);
+    auto launch = [&](auto kernel) {
+        kernel<<<grid, 256, 0, st>>>(k, v, rows, H, S_max, pos, rotate_k ? 1 : 0, clip_ratio, static_cast<uint32_t*>(k_codes),
+                                     static_cast<uint32_t*>(k_params), static_cast<uint32_t*>(v_codes), static_cast<uint32_t*>(v_params));
+    };
+    if (dt == RCP_F32) launch(&kv4_append_kv_kernel<RCP_F32>);
+    else if (dt == RCP_F16) launch(&kv4_append_kv_kernel<RCP_F16>);
+    else launch(&kv4_append_kv_kernel<RCP_BF16>);
+    return check_launch("rcp_kv4_append_kv");
+}
+
 // lengths == nullptr: one sequence of S tokens; otherwise B sequences of a pooled cache, lengths[b] tokens each
+// rotate_q (single sequence only): the order-128 Hadamard rotation of the query inside the attention kernel
 int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int S_max, int S, const int* lengths,
                     const void* k_codes, const void* k_params, const void* v_codes, const void* v_params,
-                    float softmax_scale, void* out, rcp_dtype out_dt, void* workspace, hipStream_t st)
+                    float softmax_scale, void* out, rcp_dtype out_dt, void* workspace, hipStream_t st, bool rotate_q)
 {
     const bool batched = lengths != nullptr;
+    const bool fused = !batched && rotate_q;
     KvBatch batch = {};
     long long total = S;
     if (batched) {
@@ -704,6 +797,7 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int
 #define RCP_KV_LAUNCH(QDT, ITERS)                                        \
     do {                                                                 \
         if (batched) launch(&kv4_attn_kernel<QDT, ITERS, true>);         \
+        else if (fused) launch(&kv4_attn_kernel<QDT, ITERS, false, true>); \
         else launch(&kv4_attn_kernel<QDT, ITERS, false>);                \
     } while (0)
     auto launch_stream = [&](auto kernel) {
@@ -713,6 +807,7 @@ int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int
     do {                                                                       \
         if (stream) {                                                          \
             if (batched) launch_stream(&kv4_attn_stream_kernel<QDT, true>);    \
+            else if (fused) launch_stream(&kv4_attn_stream_kernel<QDT, false, true>); \
             else launch_stream(&kv4_attn_stream_kernel<QDT, false>);           \
         } else if (L == 64) RCP_KV_LAUNCH(QDT, 1);                             \
         else if (L == 128) RCP_KV_LAUNCH(QDT, 2);                              \

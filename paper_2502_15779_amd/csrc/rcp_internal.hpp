@@ -79,7 +79,9 @@ int launch_kv4_append(const void* x, rcp_dtype dt, int n_tokens, int H, int S_ma
                       float clip_ratio, void* codes, void* params, hipStream_t st);
 int launch_kv4_attn(const void* q, rcp_dtype q_dt, int B, int H_q, int H_kv, int S_max, int S, const int* lengths,
                     const void* k_codes, const void* k_params, const void* v_codes, const void* v_params,
-                    float softmax_scale, void* out, rcp_dtype out_dt, void* workspace, hipStream_t st);
+                    float softmax_scale, void* out, rcp_dtype out_dt, void* workspace, hipStream_t st, bool rotate_q = false);
+int launch_kv4_append_kv(const void* k, const void* v, rcp_dtype dt, int n_tokens, int H, int S_max, int pos, bool rotate_k,
+                         float clip_ratio, void* k_codes, void* k_params, void* v_codes, void* v_params, hipStream_t st);
 int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, const void* xq, const void* scale,
                      int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st);
 int launch_gemm_mfma_grouped(const void* packed, const void* codebook, int N, int K, const void* xq,

@@ -34,7 +34,8 @@ def test_every_declared_function_is_exported(lib):
             "rcp_w2a16_gemv", "rcp_quant_w2a4_gemv_grouped", "rcp_w2a4_gemm_grouped",
             "rcp_rotate_quant_w2a4_gemv", "rcp_pack_weights_w3", "rcp_unpack_indices_w3", "rcp_w3a4_gemv",
             "rcp_kv4_workspace_bytes", "rcp_kv4_append", "rcp_kv4_attn_decode", "rcp_quant_w3a4_gemv",
-            "rcp_kv4_append_batched", "rcp_kv4_attn_decode_batched"} <= set(names)
+            "rcp_kv4_append_batched", "rcp_kv4_attn_decode_batched", "rcp_kv4_append_kv",
+            "rcp_kv4_rotate_attn_decode"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
@@ -177,6 +178,19 @@ def test_argument_errors_need_no_gpu(lib):
     assert ap(fake, 0, 1, 2, 8, 0, 0, 0.0, fake, fake, None) == -4
     assert ap(fake, 0, 1, 2, 8, 0, 0, 1.5, fake, fake, None) == -4
     assert ap(odd, 0, 1, 2, 8, 0, 1, 0.95, fake, fake, None) == -3
+    akv = lib.rcp_kv4_append_kv
+    akv.argtypes = [vp, vp, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp, vp]
+    assert akv(fake, None, 0, 1, 2, 8, 0, 1, 0.95, fake, fake, fake, fake, None) == -1
+    assert akv(fake, fake, 0, 3, 2, 8, 6, 1, 0.95, fake, fake, fake, fake, None) == -2     # runs past S_max
+    assert akv(fake, fake, 5, 1, 2, 8, 0, 1, 0.95, fake, fake, fake, fake, None) == -4
+    assert akv(fake, odd, 0, 1, 2, 8, 0, 1, 0.95, fake, fake, fake, fake, None) == -3
+    adf = lib.rcp_kv4_rotate_attn_decode
+    adf.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp, vp, vp, ctypes.c_float, vp, ci, vp, ctypes.c_size_t, vp]
+    assert adf(None, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, 1 << 20, None) == -1
+    assert adf(fake, 0, 4, 3, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, 1 << 20, None) == -2   # H_q % H_kv
+    assert adf(fake, 0, 4, 4, 8, 9, fake, fake, fake, fake, 0.1, fake, 1, fake, 1 << 20, None) == -2   # S > S_max
+    assert adf(fake, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, 16, None) == -5        # workspace
+    assert adf(odd, 0, 4, 4, 8, 8, fake, fake, fake, fake, 0.1, fake, 1, fake, 1 << 20, None) == -3
     kws = lib.rcp_kv4_workspace_bytes
     kws.restype = ctypes.c_size_t
     kws.argtypes = [ci, ci]

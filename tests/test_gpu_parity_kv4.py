@@ -333,3 +333,88 @@ def test_batched_append_equals_single_appends():
         assert np.array_equal(c1[2 * H:3 * H].cpu().numpy(), rc) and np.array_equal(p1[2 * H:3 * H].cpu().numpy(), rp)
     with pytest.raises(rcp.RcpError):
         rcp.kv4_append_batched(_t(x), [0, 40, 1, 2, 3], c1, p1)
+
+
+# ------------------------------------------------------------------------------------------
+# fewer launches: keys and values appended together, rotation of the query and the merge of the splits
+# inside the attention launch
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("rotate_k", [False, True])
+@pytest.mark.parametrize("n,H,dtype", [(1, 32, "f16"), (1, 1, "f32"), (5, 3, "bf16"), (70, 8, "f16")])
+def test_append_kv_equals_the_two_appends(n, H, dtype, rotate_k):
+    """rcp_kv4_append_kv: bit for bit the two rcp_kv4_append calls, and the oracle's codes and parameters."""
+    _say(f"kv4 append_kv n={n} H={H} {dtype} rotate_k={rotate_k}")
+    kd, k32 = _as_dtype(rcp_synth.kv_vectors(21, f"akv_k{n}x{H}", n, H), dtype)
+    vd, v32 = _as_dtype(rcp_synth.kv_vectors(21, f"akv_v{n}x{H}", n, H), dtype)
+    S_max, pos = n + 5, 3
+    kc, kp = rcp.kv4_new_cache(H, S_max, DEV)
+    vc, vp = rcp.kv4_new_cache(H, S_max, DEV)
+    for t in (kc, kp, vc, vp):
+        t.fill_(0x5A)
+    rcp.kv4_append_kv(kd, vd, pos, kc, kp, vc, vp, rotate_k=rotate_k)
+    torch.cuda.synchronize()
+    for x32, rot, c, p in ((k32, rotate_k, kc, kp), (v32, False, vc, vp)):
+        rc, rp = oracle.kv4_new_cache(H, S_max)
+        rc[:], rp[:] = 0x5A, 0x5A
+        oracle.kv4_append(x32, pos, 0.95, rc, rp, rotate=rot)
+        assert np.array_equal(p.cpu().numpy(), rp)
+        assert np.array_equal(c.cpu().numpy(), rc)
+    kc2, kp2 = rcp.kv4_new_cache(H, S_max, DEV)
+    kc2.fill_(0x5A)
+    kp2.fill_(0x5A)
+    rcp.kv4_append(kd, pos, kc2, kp2, rotate=rotate_k)
+    torch.cuda.synchronize()
+    assert torch.equal(kc, kc2) and torch.equal(kp, kp2)
+
+
+@pytest.mark.parametrize("tokens", [0, 128, 256, 1024])
+@pytest.mark.parametrize("qdtype", ["f16", "f32", "bf16"])
+@pytest.mark.parametrize("S,H_q,H_kv", [(1, 4, 4), (129, 8, 2), (600, 32, 32), (2100, 8, 8), (4096, 32, 8)])
+def test_rotating_attention_equals_the_separate_launches(S, H_q, H_kv, qdtype, tokens):
+    """rcp_kv4_rotate_attn_decode = rcp_rotate_act on the query followed by rcp_kv4_attn_decode, bit for bit, and within
+    the tolerance of the oracle on queries it rotated itself."""
+    _say(f"kv4 rotating attention S={S} H_q={H_q} H_kv={H_kv} {qdtype} kv_tokens={tokens}")
+    rcp.set_option("kv_tokens", tokens)
+    k = rcp_synth.kv_vectors(31, f"fk{S}", S, H_kv)
+    v = rcp_synth.kv_vectors(31, f"fv{S}", S, H_kv)
+    qd, q32 = _as_dtype(rcp_synth.query_vectors(31, f"fq{S}x{H_q}", H_q), qdtype)
+    kc, kp = rcp.kv4_new_cache(H_kv, S, DEV)
+    vc, vp = rcp.kv4_new_cache(H_kv, S, DEV)
+    rcp.kv4_append_kv(_t(k), _t(v), 0, kc, kp, vc, vp, rotate_k=True)
+    scale = 0.08838834764831845
+    q_rot = rcp.rotate_act(qd, rcp.Rotation.wht(D))
+    ref = rcp.kv4_attn_decode(q_rot, S, kc, kp, vc, vp, scale)
+    ref16 = rcp.kv4_attn_decode(q_rot, S, kc, kp, vc, vp, scale, out_dtype=torch.float16)
+    a = rcp.kv4_rotate_attn_decode(qd, S, kc, kp, vc, vp, scale)
+    a16 = rcp.kv4_rotate_attn_decode(qd, S, kc, kp, vc, vp, scale, out_dtype=torch.float16)
+    torch.cuda.synchronize()
+    assert torch.equal(a, ref) and torch.equal(a16, ref16), "query rotation inside the kernel differs from rcp_rotate_act"
+    # against the oracle (its own rotation of the query, in binary32 as the kernels do)
+    ok, okp = oracle.kv4_new_cache(H_kv, S)
+    ov, ovp = oracle.kv4_new_cache(H_kv, S)
+    oracle.kv4_append(k.astype(np.float32), 0, 0.95, ok, okp, rotate=True)
+    oracle.kv4_append(v.astype(np.float32), 0, 0.95, ov, ovp)
+    qr = np.stack([oracle.fwht_f32(q32[h]) for h in range(H_q)])
+    want = oracle.kv4_attn_decode(qr, S, ok, okp, ov, ovp, scale)
+    got = a.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= TOL * (1.0 + np.abs(want)))
+
+
+def test_rotating_attention_full_size_as_benchmarked():
+    """32 heads x 4096 cached tokens, fp16 query rotated inside the kernel: the bits of the path with the rotation as a
+    launch of its own, on a workspace filled with NaN patterns beforehand."""
+    H, S = 32, 4096
+    k = rcp_synth.kv_vectors(41, "full_k", S, H)
+    v = rcp_synth.kv_vectors(41, "full_v", S, H)
+    q = _t(rcp_synth.query_vectors(41, "full_q", H))
+    kc, kp = rcp.kv4_new_cache(H, S, DEV)
+    vc, vp = rcp.kv4_new_cache(H, S, DEV)
+    rcp.kv4_append_kv(_t(k), _t(v), 0, kc, kp, vc, vp, rotate_k=True)
+    scale = 0.08838834764831845
+    ref = rcp.kv4_attn_decode(rcp.rotate_act(q, rcp.Rotation.wht(D)), S, kc, kp, vc, vp, scale)
+    ws = torch.empty(rcp.kv4_workspace_bytes(H, S), dtype=torch.uint8, device=DEV)
+    for _ in range(3):
+        ws.fill_(0xFF)   # NaN patterns: nothing stale may be read
+        out = rcp.kv4_rotate_attn_decode(q, S, kc, kp, vc, vp, scale, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
