@@ -149,7 +149,11 @@ int rcp_version(void);
  *   "gemv_blocks"  number of workgroups the GEMV launches
  *   "gemv_variant" 1 = plain-ALU kernel for every M, 2 = matrix-core kernel for every M
  *   "gemm_waves"   wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
- *   "gemm_rows"    output rows per workgroup of the matrix-core kernel: 16, 64
+ *   "gemm_stage"   128-column steps per pipeline stage of the matrix-core kernel: 1, 2 (automatic: 2 from eight steps
+ *                  per wavefront on)
+ *   "gemm_rows"    output rows per workgroup of the matrix-core kernel: 16 (four lanes per group of four rows), or
+ *                  20, 24 .. 64 (one lane per group); automatic = 16 up to 8192 rows, else the smallest count that
+ *                  gives every compute unit the same number of workgroups
  *   "kv_tokens"    cached tokens per workgroup of rcp_kv4_attn_decode: 64, 128, 256 (all loads of a workgroup
  *                  issued at once), 512, 1024, 2048 (the streaming kernel for long contexts and batches)
  *   "gemv_waves"   wavefronts per workgroup of the fused one-token GEMV (rcp_quant_w2a4_gemv): 4, 8

@@ -146,9 +146,12 @@ int rcp_set_option(const char* name, int value)
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_waves must be 0, 1, 2, 4 or 8");
         o.gemm_waves = value;
+    } else if (strcmp(name, "gemm_stage") == 0) {
+        if (value < 0 || value > 2) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_stage must be 0, 1 or 2");
+        o.gemm_stage = value;
     } else if (strcmp(name, "gemm_rows") == 0) {
-        if (value != 0 && value != 16 && value != 64)
-            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_rows must be 0, 16 or 64");
+        if (value != 0 && (value < 16 || value > 64 || value % 4 != 0))
+            return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_rows must be 0 or a multiple of 4 from 16 to 64");
         o.gemm_rows = value;
     } else if (strcmp(name, "kv_tokens") == 0) {
         if (value != 0 && value != 64 && value != 128 && value != 256 && value != 512 && value != 1024 && value != 2048)

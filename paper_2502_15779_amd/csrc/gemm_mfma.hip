@@ -10,11 +10,11 @@
 //     bit 0 -> 0.5,  bit 1 -> 1.0,  bit 2 -> 2.0   (bit 3 is the sign: it is shifted to bit 2)
 // so a plane word ANDed with 0x1111.., 0x2222.., 0x4444.. is the A operand of
 // v_mfma_f32_16x16x128_f8f6f4 for rows r = 0, 1, 2 (and (w >> 1) & 0x4444.. for r = 3) without
-// any expansion; the factors 0.5 / 1 / 2 are taken out again when the sums leave the registers.
+// any expansion; the factors 0.5 / 1 / 2 are taken out again by the instruction's E8M0 scale of the A operand.
 // The int4 activation q = 4*hi + lo, lo in {0..3}, hi in {-2..1}, is recoded into two FP4
 // operands.  Up to 8 tokens they share one B operand (columns 0..7 carry lo, columns 8..15 hi of
-// the same tokens); beyond that lo and hi are two B operands, hi weighted by the instruction's
-// per-lane E8M0 scale (2^2), accumulating into the same registers.
+// the same tokens, the hi columns weighted 2^2 by the per-lane E8M0 scale of the B operand); beyond
+// that lo and hi are two B operands, hi weighted the same way, accumulating into the same registers.
 // Every product and every sum is a small multiple of 1/2, so the fp32 accumulators are exact
 // (|F_p| <= 8K < 2^24) and the per-level sums stay bit-exact.
 //
@@ -28,7 +28,6 @@
 namespace rcp {
 
 constexpr int MM_MAX_THREADS = 512;
-constexpr int MM_NS = 1;             // K steps per pipeline stage
 constexpr int MM_STRIDE = 65;       // LDS row stride (ints): conflict-free for both phases
 constexpr int MM_PLANE = 16 * MM_STRIDE;
 constexpr int MM_SUMS = 3 * MM_PLANE + 16;          // ints that are accumulated into (zeroed first)
@@ -45,11 +44,12 @@ struct MmStage {
 // down to row l%4, so one instruction per plane covers all four rows.  Four lanes load the same
 // weights and the activations are recoded once per 16 instead of once per 64 rows, but a matrix
 // of 4096 rows becomes 256 workgroups instead of 64.
-template <bool OUT_F16, bool PACKED, bool NARROW>
+// MM_NS: K steps per pipeline stage.
+template <bool OUT_F16, bool PACKED, bool NARROW, int MM_NS>
 __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* __restrict__ packed,
                                                                    const uint2* __restrict__ codebook, int N, int K,
                                                                    const uint4* __restrict__ xq,
-                                                                   const uint16_t* __restrict__ scale, int M, int W,
+                                                                   const uint16_t* __restrict__ scale, int M, int W, int RG,
                                                                    void* __restrict__ out, int32_t* __restrict__ Pout)
 {
     __shared__ int red[MM_LDS_INTS];  // F sums [plane][token][row of the block], T[token]; LUT rows, scales
@@ -60,11 +60,15 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     const int i = lane & 15, kb = lane >> 4;
     const int U = K / 16, G = N / 4;
     const int KS = (K + 127) >> 7;  // steps of 128 columns
-    constexpr int RB = NARROW ? 16 : 64;  // output rows of the workgroup
-    const int rg = NARROW ? static_cast<int>(blockIdx.x) * 4 + (i >> 2) : static_cast<int>(blockIdx.x) * 16 + i;
+    // RG row groups per workgroup (wide form: 1..16, chosen by the launcher so that the grid fills the compute units
+    // evenly; lanes with i >= RG load nothing and their rows of the A operand are zero)
+    const int RB = NARROW ? 16 : 4 * RG;  // output rows of the workgroup
+    const int rg = NARROW ? static_cast<int>(blockIdx.x) * 4 + (i >> 2) : static_cast<int>(blockIdx.x) * RG + i;
     // NARROW: this lane's row of the nibble as a mask (the fourth row is the FP4 sign bit: shifted down first)
     const uint32_t row_mask = (i & 3) == 0 ? 0x11111111u : (i & 3) == 1 ? 0x22222222u : 0x44444444u;
     const int row_shift = (i & 3) == 3 ? 1 : 0;
+    // E8M0 scale that takes the mask's value (0.5, 1, 2, 2 for rows 0..3 of a nibble) out of the products again
+    const int row_scale = (i & 3) == 0 ? 0x80 : (i & 3) == 1 ? 0x7f : 0x7e;
 
     for (int j = tid; j < MM_SUMS; j += 64 * W) red[j] = 0;
 
@@ -73,9 +77,10 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     // tokens beyond M start beyond the end of the resource and read as zero
     const __amdgpu_buffer_rsrc_t xres =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(xq), 0, M * (K / 2), 0x00020000);
-    const unsigned wbase = rg < G ? (static_cast<unsigned>(rg) * U + 2u * kb) * 16u : 0x80000000u;
+    const unsigned wbase = (rg < G && (NARROW || i < RG)) ? (static_cast<unsigned>(rg) * U + 2u * kb) * 16u : 0x80000000u;
     const int token = PACKED ? (i & 7) : i;  // the token whose activations this lane feeds into B
     const bool hi_lane = PACKED && i >= 8;
+    const int col_scale = hi_lane ? 0x81 : 0x7f;  // E8M0 scale of this lane's B values: 2^2 for a hi column
     const unsigned xbase = static_cast<unsigned>(token) * (K / 2) + kb * 16u;
 
     auto load = [&](int step_index, MmStage& st) {
@@ -139,10 +144,10 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
 #pragma unroll
             for (int p = 0; p < 3; ++p) {
                 if constexpr (PACKED) {
-                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[0], acc[p][0], 4, 4, 0, 0, 0, 0);
+                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[0], acc[p][0], 4, 4, 0, row_scale, 0, col_scale);
                 } else {
-                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[0], acc[p][0], 4, 4, 0, 0x7f, 0, 0x7f);
-                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[1], acc[p][0], 4, 4, 0, 0x7f, 0, 0x81);
+                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[0], acc[p][0], 4, 4, 0, row_scale, 0, 0x7f);
+                    acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bop[1], acc[p][0], 4, 4, 0, row_scale, 0, 0x81);
                 }
             }
             return;
@@ -169,15 +174,15 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
             if constexpr (PACKED) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[0], acc[p][r], 4, 4, 0, 0, 0, 0);
+                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[0], acc[p][r], 4, 4, 0, r == 0 ? 0x80 : r == 1 ? 0x7f : 0x7e, 0, col_scale);
             } else {
-                // E8M0 scales (byte 0): 2^0 for A and lo, 2^2 for hi
+                // E8M0 scales (byte 0): the inverse of the mask's value for A, 2^0 for lo, 2^2 for hi
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[0], acc[p][r], 4, 4, 0, 0x7f, 0, 0x7f);
+                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[0], acc[p][r], 4, 4, 0, r == 0 ? 0x80 : r == 1 ? 0x7f : 0x7e, 0, 0x7f);
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[1], acc[p][r], 4, 4, 0, 0x7f, 0, 0x81);
+                    acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bop[1], acc[p][r], 4, 4, 0, r == 0 ? 0x80 : r == 1 ? 0x7f : 0x7e, 0, 0x81);
             }
         }
     };
@@ -205,38 +210,28 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     for (int j = 0; j < MM_NS; ++j) keep |= sA[j].wa.x | sA[j].wb.x | sA[j].xq.x | sB[j].wa.x | sB[j].wb.x | sB[j].xq.x;
     if (__builtin_expect(K < 0, 0)) red[0] = static_cast<int>(keep);  // never true
 
-    // acc[p][r][v] = 2^(r - 1) (r < 3) or 2 (r = 3) times F_p (packed: its lo or hi part) of row
-    // 4*(16*block + 4*kb + v) + r and this lane's token: rescale, add over the wavefronts (and,
-    // when packed, lo + 4 hi over the two columns of a token).
+    // acc[p][r][v] = F_p (packed: its lo part, or four times its hi part) of row 4*(RG*block + 4*kb + v) + r and this
+    // lane's token, an integer: the instruction's scales have taken out the mask's power of two and weighted the hi
+    // columns.  The wavefronts (and, when packed, the two columns of a token) add them up in LDS (integer adds: the
+    // binary32 LDS add is far slower).
     if constexpr (NARROW) {
-        // acc[p][0][v]: row v of row group kb of the block, scaled by this row's mask value
+        // acc[p][0][v]: row v of row group kb of the block
         int* dst = red + token * MM_STRIDE + 4 * kb;
 #pragma unroll
         for (int p = 0; p < 3; ++p)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float unmask = v == 0 ? 2.0f : v == 1 ? 1.0f : 0.5f;
-                int f = static_cast<int>(acc[p][0][v] * unmask);
-                if (hi_lane) f *= 4;
-                atomicAdd(dst + p * MM_PLANE + v, f);
-            }
+            for (int v = 0; v < 4; ++v) atomicAdd(dst + p * MM_PLANE + v, static_cast<int>(acc[p][0][v]));
     } else {
         int* dst = red + token * MM_STRIDE + 16 * kb;
 #pragma unroll
         for (int p = 0; p < 3; ++p)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float unmask = r == 0 ? 2.0f : r == 1 ? 1.0f : 0.5f;
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    int f = static_cast<int>(acc[p][r][v] * unmask);
-                    if (hi_lane) f *= 4;
-                    atomicAdd(dst + p * MM_PLANE + 4 * v + r, f);
-                }
-            }
+                for (int v = 0; v < 4; ++v) atomicAdd(dst + p * MM_PLANE + 4 * v + r, static_cast<int>(acc[p][r][v]));
     }
+    if (!hi_lane) atomicAdd(red + 3 * MM_PLANE + token, tsum);
     {
-        if (!hi_lane) atomicAdd(red + 3 * MM_PLANE + token, tsum);
         if (tid < RB) {
             red[MM_SUMS + 2 * tid] = static_cast<int>(lut_pre.x);
             red[MM_SUMS + 2 * tid + 1] = static_cast<int>(lut_pre.y);
@@ -245,10 +240,10 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     }
     __syncthreads();
 
-    for (int o = tid; o < M * RB; o += 64 * W) {
-        const int n = o / RB, hh = o % RB;
+    for (int o = tid; o < M * 64; o += 64 * W) {
+        const int n = o >> 6, hh = o & 63;
         const int h = blockIdx.x * RB + hh;
-        if (h >= N) continue;
+        if (hh >= RB || h >= N) continue;
         const int F0 = red[n * MM_STRIDE + hh], F1 = red[MM_PLANE + n * MM_STRIDE + hh];
         const int F3 = red[2 * MM_PLANE + n * MM_STRIDE + hh];
         const int T = red[3 * MM_PLANE + n];
@@ -274,10 +269,24 @@ int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, con
                      int M, void* out, rcp_dtype out_dt, int32_t* P, hipStream_t st)
 {
     const int KS = (K + 127) / 128;
-    // 16-row workgroups when 64-row ones would leave most compute units idle ("gemm_rows" = 16 / 64 forces a form)
-    bool narrow = (N + 63) / 64 < num_compute_units() / 2;
-    if (options().gemm_rows != 0) narrow = options().gemm_rows == 16;
-    const int blocks = narrow ? (N + 15) / 16 : (N + 63) / 64;
+    // 16-row workgroups when 64-row ones would leave most compute units idle; otherwise the wide form with the fewest
+    // row groups per workgroup (<= 16) that still gives a whole number of workgroups per compute unit, so that no unit
+    // carries twice the work of its neighbour ("gemm_rows" = 16 forces the first form, 20, 24 .. 64 the second)
+    const int cus = num_compute_units(), G = N / 4;
+    bool narrow = G <= 8 * cus;  // up to 8192 rows on 256 units (sweeps: 8192 x 2048 4.0 against 4.35 us)
+    int RG = 16;
+    for (int per_cu = 1; per_cu <= 64; ++per_cu) {
+        const int want = (G + per_cu * cus - 1) / (per_cu * cus);
+        if (want <= 16) {
+            RG = want;
+            break;
+        }
+    }
+    if (options().gemm_rows != 0) {
+        narrow = options().gemm_rows == 16;
+        if (!narrow) RG = options().gemm_rows / 4;
+    }
+    const int blocks = narrow ? (N + 15) / 16 : (G + RG - 1) / RG;
     // 8 wavefronts per workgroup share the K steps of a row block (sweeps: 8 with one step per
     // pipeline stage beats 4 with deeper stages on every LLaMA shape), never more than there are steps
     int waves = 8;
@@ -288,7 +297,14 @@ int launch_gemm_mfma(const void* packed, const void* codebook, int N, int K, con
     auto* x4 = static_cast<const uint4*>(xq);
     auto* sc = static_cast<const uint16_t*>(scale);
     const dim3 grid(blocks), block(waves * 64);
-#define RCP_MM(F16, PK, NA) gemm_mfma_kernel<F16, PK, NA><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P)
+    // two steps per pipeline stage once a wavefront has eight or more steps to walk (4096 x 11008: 6.9 against 7.6 us;
+    // slower on the short loops of K = 4096)
+    const bool deep = options().gemm_stage != 0 ? options().gemm_stage == 2 : KS >= 8 * waves;
+#define RCP_MM(F16, PK, NA)                                                                                   \
+    do {                                                                                                      \
+        if (deep) gemm_mfma_kernel<F16, PK, NA, 2><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, RG, out, P); \
+        else gemm_mfma_kernel<F16, PK, NA, 1><<<grid, block, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, RG, out, P);      \
+    } while (0)
     const bool f16 = out_dt == RCP_F16, pkd = M <= 8;
     if (narrow) {
         if (pkd) { if (f16) RCP_MM(true, true, true); else RCP_MM(false, true, true); }

@@ -31,7 +31,8 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves", "gemm_rows", "gemv_oneshot"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves", "gemm_rows", "gemv_oneshot",
+              "gemm_stage"):
         rcp.set_option(k, 0)
 
 
@@ -434,19 +435,21 @@ def test_small_batch_matches_oracle(N, K, M, variant):
     _check_gemv(packed, cb, N, K, xq, sc, M, torch.float16)
 
 
-@pytest.mark.parametrize("rows", [16, 64])
+@pytest.mark.parametrize("rows", [16, 20, 44, 64])
 @pytest.mark.parametrize("waves", [1, 2, 4, 8])
 @pytest.mark.parametrize("N,K,M", [(4, 32, 1), (68, 96, 5), (1028, 4096, 16), (132, 14336, 9), (64, 32768, 16), (200, 160, 2),
                                    (24, 4224, 8)])
 def test_matrix_core_kernel_shapes_and_workgroup_sizes(N, K, M, waves, rows):
-    """Ragged N (not a multiple of 64 or 16), K not a multiple of 128, fewer K steps than wavefronts, M = 1;
-    64-row and 16-row workgroups."""
+    """Ragged N (not a multiple of the rows of a workgroup), K not a multiple of 128, fewer K steps than wavefronts,
+    M = 1; 16-row workgroups and workgroups of 5, 11 and 16 groups of four rows."""
     _say(f"mfma gemm N={N} K={K} M={M} waves={waves} rows={rows}")
     rcp.set_option("gemv_variant", 2)
     rcp.set_option("gemm_waves", waves)
     rcp.set_option("gemm_rows", rows)
     packed, cb, xq, sc = _gemv_case(77 + M, N, K, M)
-    _check_gemv(packed, cb, N, K, xq, sc, M, torch.float32)
+    for stage in (1, 2):    # one and two 128-column steps per pipeline stage
+        rcp.set_option("gemm_stage", stage)
+        _check_gemv(packed, cb, N, K, xq, sc, M, torch.float32)
 
 
 @pytest.mark.parametrize("rows", [16, 64])
