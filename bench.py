@@ -810,6 +810,42 @@ def main():
             other[label]["plain_read_us"] = round(timed(torch, fn, reps) / nbuf * 1e6, 3)
             del bufs
 
+    # The same kernel where the launch is a small part of the time: a matrix of 131072 x 4096 (134 MB of packed weights, the
+    # size of a LLaMA-3 vocabulary projection), cold over 8 buffers, against a plain read of the same bytes -- what the
+    # kernel sustains once a launch is long enough to stream.
+    large = {}
+    if not args.step_only:
+        N, K, nbuf = 131072, HIDDEN, 8
+        bufs = [(torch.randint(0, 256, (N * K // 4,), dtype=torch.uint8, device=dev),
+                 (torch.randn((N, 4), device=dev) * 0.03).sort(dim=1).values.to(torch.float16).contiguous()) for _ in range(nbuf)]
+        xl = torch.randn((1, K), device=dev).to(torch.float16)
+        xql, scl = rcp.rotate_quant_act(xl)
+        ol = torch.empty((1, N), dtype=torch.float16, device=dev)
+        b = gemv_bytes(N, K)
+
+        def lsweep_q():
+            for pk, cb in bufs:
+                rcp.w2a4_gemv(pk, cb, N, K, xql, scl, 1, out=ol)
+
+        def lsweep_f():
+            for pk, cb in bufs:
+                rcp.quant_w2a4_gemv(pk, cb, N, K, xl, 1.0, out=ol)
+
+        def lsweep_r():
+            for pk, _ in bufs:
+                rcp.stream_read(pk, N * K // 4, sink)
+        for key, sweep in (("prequantised", lsweep_q), ("fused_quantise", lsweep_f), ("plain_read", lsweep_r)):
+            sweep()
+            fn = capture(sweep)
+            fn()
+            sec = min(timed(torch, fn, 3), timed(torch, fn, 3)) / nbuf
+            bb = b if key != "plain_read" else N * K // 4
+            large[key + "_us"] = round(sec * 1e6, 2)
+            large[key + "_GBps"] = round(bb / sec / 1e9, 1)
+        large.update({"shape": f"{N}x{K}", "bytes": b, "buffers": nbuf,
+                      "pct_of_hbm_peak": round(large["prequantised_GBps"] / HBM_PEAK_GBPS * 100, 1)})
+        del bufs
+
     # What a dependent launch costs on this machine, and what the same dependency costs inside one launch:
     # (a) a chain of launches that read 16 bytes each; (b) a chain of the smallest fused GEMV (64 x 128) as launches;
     # (c) the same 16 GEMVs as one rcp_quant_w2a4_gemv_sequence call -- per entry that is one meeting of all
@@ -991,6 +1027,7 @@ def main():
         "kv4_attention_batched": kv4_batched,
         "kv4_layer_launches": kv_layer,
         "per_shape_other": other,
+        "large_matrix": large,
         "launch_floor": floor,
         "persistent_layer": persistent,
         "down_projection_prologue": down_split,

@@ -146,6 +146,9 @@ int rcp_set_option(const char* name, int value)
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
             return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_waves must be 0, 1, 2, 4 or 8");
         o.gemm_waves = value;
+    } else if (strcmp(name, "gemv_nt") == 0) {
+        if (value < 0 || value > 2) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemv_nt must be 0, 1 or 2");
+        o.gemv_nt = value;
     } else if (strcmp(name, "gemm_stage") == 0) {
         if (value < 0 || value > 2) return fail(RCP_ERR_UNSUPPORTED, "rcp_set_option: gemm_stage must be 0, 1 or 2");
         o.gemm_stage = value;

@@ -23,6 +23,7 @@ struct Options {
     int gemv_variant;    // 0 automatic, 1 plain-ALU kernel for every M, 2 matrix-core kernel for every M
     int gemm_waves;      // wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
     int gemm_stage;      // K steps per pipeline stage of the matrix-core kernel: 1, 2
+    int gemv_nt;         // non-temporal weight loads in the general one-token kernel: 1 = always, 2 = never
     int gemv_waves;      // wavefronts per workgroup of the fused one-token GEMV: 4 or 8
     int gemm_rows;       // output rows per workgroup of the matrix-core kernel: 16 or 64
     int kv_tokens;       // cached tokens per workgroup of the KV4 attention kernel: 64, 128 or 256

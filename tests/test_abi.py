@@ -121,6 +121,7 @@ def test_argument_errors_need_no_gpu(lib):
     assert lib.rcp_set_option(b"kv_tokens", 96) == -4
     assert lib.rcp_set_option(b"kv_tokens", 128) == 0 and lib.rcp_set_option(b"kv_tokens", 1024) == 0
     assert lib.rcp_set_option(b"kv_tokens", 4096) == -4 and lib.rcp_set_option(b"kv_tokens", 0) == 0
+    assert lib.rcp_set_option(b"gemv_nt", 3) == -4 and lib.rcp_set_option(b"gemv_nt", 1) == 0 and lib.rcp_set_option(b"gemv_nt", 0) == 0
     assert lib.rcp_set_option(b"gemm_stage", 3) == -4 and lib.rcp_set_option(b"gemm_stage", 2) == 0
     assert lib.rcp_set_option(b"gemm_stage", 0) == 0
     assert lib.rcp_set_option(b"gemm_rows", 30) == -4 and lib.rcp_set_option(b"gemm_rows", 12) == -4

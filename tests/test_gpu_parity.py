@@ -32,7 +32,7 @@ def _say(msg):
 def _auto_options():
     yield
     for k in ("gemv_lanes", "gemv_blocks", "gemv_unroll", "gemv_variant", "gemm_waves", "gemv_waves", "gemm_rows", "gemv_oneshot",
-              "gemm_stage"):
+              "gemm_stage", "gemv_nt"):
         rcp.set_option(k, 0)
 
 
@@ -368,6 +368,32 @@ def test_gemv_partial_sums_bit_exact_and_output_close(N, K, lanes):
     packed, cb, xq, sc = _gemv_case(N + K, N, K, 1)
     _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32)
     _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float16)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32", "bf16"])
+@pytest.mark.parametrize("N,K", [(12, 96), (1028, 4096), (72, 11008), (260, 2080), (4100, 2048)])
+def test_gemv_with_non_temporal_weight_loads(N, K, dtype):
+    """The form the launcher takes for matrices of 32 MB and more (32 lanes per row group, four loads per stage,
+    non-temporal weight loads), forced on small ones: pre-quantised and fused calls, same results."""
+    _say(f"gemv non-temporal N={N} K={K} {dtype}")
+    rcp.set_option("gemv_lanes", 32)
+    rcp.set_option("gemv_unroll", 4)
+    rcp.set_option("gemv_nt", 1)
+    rcp.set_option("gemv_oneshot", 2)
+    packed, cb, xq, sc = _gemv_case(N + K + 5, N, K, 1)
+    _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32 if dtype == "f32" else torch.float16)
+    x16 = rcp_synth.activation(5, f"nt{K}", 1, K)
+    xd = _t(x16) if dtype == "f16" else _t(x16.astype(np.float32)) if dtype == "f32" else _t(x16.astype(np.float32)).to(torch.bfloat16)
+    ref_xq, ref_sc, _ = oracle.quantize_act(xd.to(torch.float32).cpu().numpy(), 1.0)
+    ref_O, ref_P = oracle.w2a4_gemv(packed, cb, N, K, ref_xq, ref_sc, 1)
+    out, P = rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, 1.0, out_dtype=torch.float32,
+                                 want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy().reshape(ref_P.shape), ref_P)
+    rcp.set_option("gemv_nt", 2)
+    out2 = rcp.quant_w2a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, 1.0, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
 
 
 def test_largest_row_count_the_packer_accepts():
