@@ -376,15 +376,17 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_kernel(const void* __rest
         const int t = t0 + it * 64 + slot;
         valid[it] = t < t_end;
         const size_t at = head_base + (valid[it] ? t : t_end - 1);
-        kw[it] = k_codes[at * 4 + piece];
-        kp[it] = k_params[at];
+        // the cache is read once per call: loads with the non-temporal hint (6.6 -> 6.0 us at 1024 tokens, 13.2 -> 12.5 at
+        // 8192, 57 -> 51 us for 16 sequences of 4096 in the streaming kernel)
+        kw[it] = __builtin_nontemporal_load(k_codes + (at * 4 + piece));
+        kp[it] = __builtin_nontemporal_load(k_params + at);
     }
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int t = t0 + it * 64 + slot;
         const size_t at = head_base + (valid[it] ? t : t_end - 1);
-        vw[it] = v_codes[at * 4 + piece];
-        vp[it] = v_params[at];
+        vw[it] = __builtin_nontemporal_load(v_codes + (at * 4 + piece));
+        vp[it] = __builtin_nontemporal_load(v_params + at);
     }
 
     // this lane's 32 query values in register order (the softmax scale goes onto the score)
@@ -544,10 +546,11 @@ __global__ __launch_bounds__(KV_THREADS) void kv4_attn_stream_kernel(const void*
         const int t = t0 + 16 * (4 * c + wave) + slot;
         r.valid = t < t_end;
         const size_t at = head_base + (r.valid ? t : t_end - 1);
-        r.kw = k_codes[at * 4 + piece];
-        r.kp = k_params[at];
-        r.vw = v_codes[at * 4 + piece];
-        r.vp = v_params[at];
+        // read once per call: non-temporal loads, as in kv4_attn_kernel
+        r.kw = __builtin_nontemporal_load(k_codes + (at * 4 + piece));
+        r.kp = __builtin_nontemporal_load(k_params + at);
+        r.vw = __builtin_nontemporal_load(v_codes + (at * 4 + piece));
+        r.vp = __builtin_nontemporal_load(v_params + at);
     };
 
     Raw8<QDT> qraw[4];
