@@ -28,7 +28,7 @@ def _say(msg):
 @pytest.fixture(autouse=True)
 def _auto_options():
     yield
-    for k in ("gemv_lanes", "gemv_blocks"):
+    for k in ("gemv_lanes", "gemv_blocks", "gemv_nt"):
         rcp.set_option(k, 0)
 
 
@@ -114,6 +114,23 @@ def test_w3_gemv_partial_sums_bit_exact_and_output_close(N, K, lanes):
     packed, cb, xq, sc = _w3_case(N + K, N, K)
     _check_w3(packed, cb, N, K, xq, sc, torch.float32)
     _check_w3(packed, cb, N, K, xq, sc, torch.float16)
+
+
+@pytest.mark.parametrize("N,K", [(12, 96), (1028, 4096), (72, 11008), (8200, 64)])
+def test_w3_gemv_with_non_temporal_weight_loads(N, K):
+    """The weight loads' cache hint that the launcher adds from 16 MB on, forced on small matrices: pre-quantised and
+    fused calls, same partial sums."""
+    _say(f"w3 gemv non-temporal N={N} K={K}")
+    rcp.set_option("gemv_nt", 1)
+    packed, cb, xq, sc = _w3_case(N + K + 1, N, K)
+    _check_w3(packed, cb, N, K, xq, sc, torch.float32)
+    xd, x32 = _x_as(rcp_synth.activation(9, f"w3nt{K}", 1, K), "f16")
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, 1.0)
+    _, ref_P = oracle.w3a4_gemv(packed, cb, N, K, ref_xq, ref_sc)
+    _, P = rcp.quant_w3a4_gemv(_t(packed), _t(cb.view(np.float16)), N, K, xd, 1.0, out_dtype=torch.float32,
+                               want_partial_sums=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(P.cpu().numpy(), ref_P)
 
 
 def test_w3_gemv_extreme_activations_and_integer_codebook():
