@@ -70,7 +70,6 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     // E8M0 scale that takes the mask's value (0.5, 1, 2, 2 for rows 0..3 of a nibble) out of the products again
     const int row_scale = (i & 3) == 0 ? 0x80 : (i & 3) == 1 ? 0x7f : 0x7e;
 
-    for (int j = tid; j < MM_SUMS; j += 64 * W) red[j] = 0;
 
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint4*>(packed), 0, static_cast<int>(static_cast<unsigned>(G) * static_cast<unsigned>(U) * 16u), 0x00020000);
@@ -103,6 +102,8 @@ __global__ __launch_bounds__(MM_MAX_THREADS) void gemm_mfma_kernel(const uint4* 
     uint32_t scale_pre = 0;
     if (tid < RB) lut_pre = codebook[min(static_cast<int>(blockIdx.x) * RB + tid, N - 1)];
     if (tid < M) scale_pre = scale[tid];
+    __builtin_amdgcn_sched_barrier(0);  // the loads leave before the LDS is cleared
+    for (int j = tid; j < MM_SUMS; j += 64 * W) red[j] = 0;
     __syncthreads();  // LDS is zero before anyone adds to it
 
     constexpr int NB = PACKED ? 1 : 2;  // B operands per A operand
