@@ -163,7 +163,8 @@ int rcp_version(void);
  *                  (8 needs K >= 2048 and "gemv_lanes" left automatic; otherwise 4 is used)
  *   "gemv_oneshot" one-token kernel that issues every weight load of a workgroup up front (one group of four rows
  *                  per wavefront, K <= 16384): 1 = for every such shape, 2 = never; automatic = matrices that give
- *                  every compute unit one or two workgroups.  Ignored while "gemv_lanes", "gemv_blocks" or
+ *                  every compute unit one or two workgroups, and with activations quantised beforehand every matrix
+ *                  of at least one workgroup per unit with K >= 4096 below 32 MB.  Ignored while "gemv_lanes", "gemv_blocks" or
  *                  "gemv_unroll" is set (those address the general kernel).
  *   "seq_blocks"   workgroups of rcp_quant_w2a4_gemv_sequence (refused when they could not all be resident)
  *   "reset"        (value ignored) every knob back to automatic

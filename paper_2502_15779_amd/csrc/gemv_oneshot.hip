@@ -219,7 +219,14 @@ bool gemv_oneshot_applies(int N, int K, bool fused)
     if (opt.gemv_oneshot == 1) return true;
     const int nbatch = (N / 4 + ONE_WAVES - 1) / ONE_WAVES;
     const int cus = num_compute_units();
-    if (nbatch < cus || nbatch > 2 * cus) return false;
+    if (nbatch < cus) return false;
+    // activations quantised beforehand: any number of workgroups per compute unit once a row group is four loads or more
+    // per lane -- the queue of short workgroups keeps the loads coming to the end (sweeps: 14336 x 4096 5.1 -> 4.8 us,
+    // 22016 x 4096 6.2 -> 6.0, 28672 x 4096 7.5 -> 6.9, 16384 x 4096 5.5 -> 5.0, 12288 x 8192 6.6 -> 6.2; K = 2048 level) --
+    // up to the size from which the general kernel's non-temporal form takes over
+    if (!fused && K >= 4096 && static_cast<long long>(N) * K / 4 < (32LL << 20)) return true;
+    // otherwise at most two workgroups per unit: with the quantiser in the prologue every further workgroup repeats it
+    if (nbatch > 2 * cus) return false;
     return !fused || K <= 8192;
 }
 
