@@ -151,7 +151,8 @@ int rcp_version(void);
  *   "gemm_waves"   wavefronts per workgroup of the matrix-core kernel: 1, 2, 4, 8
  *   "gemv_nt"      weight loads of the one-token kernel with the non-temporal cache hint (the form with 32 lanes per
  *                  group of rows and four loads per stage only): 1 = whenever that form runs, 2 = never; automatic =
- *                  from 32 MB of packed weights on; the 3-bit kernel likewise (from 16 MB on)
+ *                  from 32 MB of packed weights on; the 3-bit kernel (from 16 MB on) and the kernel for
+ *                  group-wise tables (from 10 MB on) likewise
  *   "gemm_stage"   128-column steps per pipeline stage of the matrix-core kernel: 1, 2 (automatic: 2 from eight steps
  *                  per wavefront on)
  *   "gemm_rows"    output rows per workgroup of the matrix-core kernel: 16 (four lanes per group of four rows), or

@@ -194,6 +194,8 @@ def test_grouped_gemv_partial_sums_bit_exact_and_output_close(N, K, blocks):
     rcp.set_option("gemv_blocks", blocks)
     packed, cb, xq, sc = _grouped_gemv_case(21, N, K)
     _check_grouped_gemv(packed, cb, N, K, xq, sc, torch.float32 if blocks else torch.float16)
+    rcp.set_option("gemv_nt", 1)     # the weight loads' cache hint of large matrices, forced
+    _check_grouped_gemv(packed, cb, N, K, xq, sc, torch.float32)
 
 
 @pytest.mark.parametrize("rows", [16, 64])
