@@ -71,6 +71,58 @@ __global__ __launch_bounds__(1024) void quant_kernel(const void* __restrict__ x,
 // later pass gathers, through LDS, the EPT elements whose indices differ in the next LE
 // index bits and does those strides in registers.
 // ---------------------------------------------------------------------------------------
+// The butterflies whose stride is a lane distance: element index bits LE .. LE + nbits - 1 are the low bits of the lane
+// number (thread t owns elements t * EPT ...), so stage b exchanges with lane ^ (1 << b) -- DPP for 1, 2 and 8, a lane
+// permutation for 4, the 16- and 32-lane swaps for the last two.  z <- z + partner in the lane with the bit clear,
+// partner - z in the other: the additions of the plain butterfly, no LDS and no barrier.
+template <int EPT>
+__device__ __forceinline__ void lane_stages(float (&v)[EPT], int lane, int nbits)
+{
+    // stage by stage, the EPT values of a stage side by side: their exchanges are independent and overlap
+    if (nbits > 0) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0xB1, 0xf, 0xf, false));  // lane ^ 1
+            v[e] = (lane & 1) ? p - v[e] : v[e] + p;
+        }
+    }
+    if (nbits > 1) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x4E, 0xf, 0xf, false));  // lane ^ 2
+            v[e] = (lane & 2) ? p - v[e] : v[e] + p;
+        }
+    }
+    if (nbits > 2) {
+        float p[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) p[e] = __shfl_xor(v[e], 4, 64);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) v[e] = (lane & 4) ? p[e] - v[e] : v[e] + p[e];
+    }
+    if (nbits > 3) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x128, 0xf, 0xf, false));  // row_ror 8 = lane ^ 8
+            v[e] = (lane & 8) ? p - v[e] : v[e] + p;
+        }
+    }
+    if (nbits > 4) {  // the swaps leave (value of the lane with the bit clear, value of the lane with it set) in every lane
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[e]), __float_as_uint(v[e]), false, false);
+            v[e] = (lane & 16) ? __uint_as_float(r[0]) - __uint_as_float(r[1]) : __uint_as_float(r[0]) + __uint_as_float(r[1]);
+        }
+    }
+    if (nbits > 5) {
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[e]), __float_as_uint(v[e]), false, false);
+            v[e] = (lane & 32) ? __uint_as_float(r[0]) - __uint_as_float(r[1]) : __uint_as_float(r[0]) + __uint_as_float(r[1]);
+        }
+    }
+}
+
 template <int DT, int LE, bool QUANT>
 __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict__ x, int n, int log2n, float norm,
                                                          float clip_ratio, int waves, uint32_t* __restrict__ xq,
@@ -96,11 +148,16 @@ __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict_
             for (int j = 0; j < 8; ++j) v[8 * c + j] = t8[j];
         }
         register_stages<LE>(v, 0);
+    }
+    // the next (up to six) index bits are the lane number: those strides run between lanes, without LDS
+    const int nlane = min(6, log2n - LE);
+    lane_stages<EPT>(v, tid & 63, nlane);  // threads without data hold zeros and only ever meet each other
+    int done = LE + nlane;  // index bits whose stage is finished
+    const bool more = done < log2n;  // uniform: strides beyond a wavefront go through LDS
+    if (more && active) {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) sy[wht_slot(tid * EPT + e)] = v[e];
     }
-
-    int done = LE;  // index bits whose stage is finished
     while (done < log2n) {
         // the LE register bits sit at index bits [lo, lo + LE); the last pass may overlap
         // bits that are already done and then skips their stages
@@ -118,13 +175,13 @@ __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict_
         }
         done = lo + LE;
     }
-    __syncthreads();
+    if (more) __syncthreads();
 
     float a = 0.0f;
     if (active) {
 #pragma unroll
         for (int e = 0; e < EPT; ++e) {
-            v[e] = __fmul_rn(sy[wht_slot(tid * EPT + e)], norm);
+            v[e] = __fmul_rn(more ? sy[wht_slot(tid * EPT + e)] : v[e], norm);
             a = fmaxf(a, fabsf(v[e]));
         }
     }
@@ -533,7 +590,9 @@ static int launch_wht(const void* x, int M, int n, float clip_ratio, void* xq, v
     auto* q = static_cast<uint32_t*>(xq);
     auto* s = static_cast<uint16_t*>(scale);
     const size_t lds = static_cast<size_t>(n) * sizeof(float);
-    if (n <= 8192) {  // (16 elements per thread save an LDS pass but are not faster at 4096 / 8192 points)
+    // 8 elements per thread below 8192 points, 16 from there on (one LDS pass less after the lane stages: 8192 points
+    // 5.15 -> 4.87 us; at 4096 and 2048 points 16 per thread are 20-30 % slower)
+    if (n < 8192) {
         const int threads = ((n / 8 + 63) / 64) * 64;
         wht_quant_kernel<DT, 3, QUANT><<<M, threads, lds, st>>>(x, n, log2n, norm, clip_ratio, threads / 64, q, s, y);
     } else {
@@ -542,7 +601,8 @@ static int launch_wht(const void* x, int M, int n, float clip_ratio, void* xq, v
                                                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
             if (e != hipSuccess) return fail(RCP_ERR_HIP, "rcp_rotate_quant_act: LDS opt-in failed: %s", hipGetErrorString(e));
         }
-        wht_quant_kernel<DT, 4, QUANT><<<M, n / 16, lds, st>>>(x, n, log2n, norm, clip_ratio, n / 1024, q, s, y);
+        const int threads = ((n / 16 + 63) / 64) * 64;
+        wht_quant_kernel<DT, 4, QUANT><<<M, threads, lds, st>>>(x, n, log2n, norm, clip_ratio, threads / 64, q, s, y);
     }
     return check_launch("rcp_rotate_quant_act(wht)");
 }
