@@ -71,58 +71,6 @@ __global__ __launch_bounds__(1024) void quant_kernel(const void* __restrict__ x,
 // later pass gathers, through LDS, the EPT elements whose indices differ in the next LE
 // index bits and does those strides in registers.
 // ---------------------------------------------------------------------------------------
-// The butterflies whose stride is a lane distance: element index bits LE .. LE + nbits - 1 are the low bits of the lane
-// number (thread t owns elements t * EPT ...), so stage b exchanges with lane ^ (1 << b) -- DPP for 1, 2 and 8, a lane
-// permutation for 4, the 16- and 32-lane swaps for the last two.  z <- z + partner in the lane with the bit clear,
-// partner - z in the other: the additions of the plain butterfly, no LDS and no barrier.
-template <int EPT>
-__device__ __forceinline__ void lane_stages(float (&v)[EPT], int lane, int nbits)
-{
-    // stage by stage, the EPT values of a stage side by side: their exchanges are independent and overlap
-    if (nbits > 0) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0xB1, 0xf, 0xf, false));  // lane ^ 1
-            v[e] = (lane & 1) ? p - v[e] : v[e] + p;
-        }
-    }
-    if (nbits > 1) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x4E, 0xf, 0xf, false));  // lane ^ 2
-            v[e] = (lane & 2) ? p - v[e] : v[e] + p;
-        }
-    }
-    if (nbits > 2) {
-        float p[EPT];
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) p[e] = __shfl_xor(v[e], 4, 64);
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) v[e] = (lane & 4) ? p[e] - v[e] : v[e] + p[e];
-    }
-    if (nbits > 3) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x128, 0xf, 0xf, false));  // row_ror 8 = lane ^ 8
-            v[e] = (lane & 8) ? p - v[e] : v[e] + p;
-        }
-    }
-    if (nbits > 4) {  // the swaps leave (value of the lane with the bit clear, value of the lane with it set) in every lane
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[e]), __float_as_uint(v[e]), false, false);
-            v[e] = (lane & 16) ? __uint_as_float(r[0]) - __uint_as_float(r[1]) : __uint_as_float(r[0]) + __uint_as_float(r[1]);
-        }
-    }
-    if (nbits > 5) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[e]), __float_as_uint(v[e]), false, false);
-            v[e] = (lane & 32) ? __uint_as_float(r[0]) - __uint_as_float(r[1]) : __uint_as_float(r[0]) + __uint_as_float(r[1]);
-        }
-    }
-}
-
 template <int DT, int LE, bool QUANT>
 __global__ __launch_bounds__(1024) void wht_quant_kernel(const void* __restrict__ x, int n, int log2n, float norm,
                                                          float clip_ratio, int waves, uint32_t* __restrict__ xq,

@@ -72,7 +72,7 @@ __device__ __forceinline__ void heads_columns(float* sy, int m, float norm)
 }
 
 // The first 56 bytes of arguments reach the wavefront in scalar registers at launch; everything the
-// prologue needs at once (matrix, shape, activations) is among them.
+// prologue needs at once (matrix, shape, activations, the rotation) is among them.
 // NT: the weight loads carry the non-temporal hint -- a matrix of tens of megabytes is read once and need not displace
 // anything in the caches (134 MB: 25.8 -> 24.2 us; matrices of 4 - 12 MB are slower with it).
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT, int NW, bool NT = false>
@@ -80,12 +80,20 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
                                                             const uint2* __restrict__ codebook, int N, int K,
                                                             const void* __restrict__ x_in,
                                                             const uint16_t* __restrict__ scale, int M, float clip_ratio,
-                                                            int nblk,
+                                                            int nblk, int rot,
                                                             void* __restrict__ out, int32_t* __restrict__ Pout,
-                                                            uint32_t* __restrict__ xq_out, uint16_t* __restrict__ scale_out,
-                                                            int rot_n, int rot_m, float rot_norm)
+                                                            uint32_t* __restrict__ xq_out, uint16_t* __restrict__ scale_out)
 {
     static_assert(WS == 1 || LW == 64, "several wavefronts per row group only with whole wavefronts");
+    // `rot` is the last argument that arrives in registers: heads | channels per head << 8 for the rotation across heads,
+    // log2 K for the order-K rotation; the factor 1/sqrt(n) of a power of two n is put together from its exponent
+    // ((float)(1/sqrt 2) times a power of two: what the host's (float)(1.0 / sqrt((double)n)) gives)
+    auto inv_sqrt_pow2 = [](int k) {
+        return __uint_as_float(((k & 1) ? 0x3F3504F3u : 0x3F800000u) - (static_cast<uint32_t>(k >> 1) << 23));
+    };
+    const int rot_n = XDT >= 8 ? 0 : (rot & 0xff);
+    const int rot_m = XDT >= 8 ? rot : (rot >> 8);
+    const float rot_norm = XDT >= 8 ? inv_sqrt_pow2(rot) : (XDT >= 4 ? inv_sqrt_pow2(__ffs(rot_n) - 1) : 1.0f);
     static_assert(NW == 4 || (NW == 8 && XDT >= 0 && XDT < 4), "eight wavefronts: the fused quantiser without rotation");
     constexpr int TH = NW * 64;  // threads of the workgroup
     // one pointer for the activations: quantised (XDT < 0) or raw; the number of workgroups comes as an
@@ -270,19 +278,25 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
             }
         }
         if constexpr (ROTW) {
-            // y = H_K x: this thread's eight consecutive values take the strides 1, 2, 4 in registers, every
-            // later pass gathers through LDS the eight values whose indices differ in the next three bits
+            // y = H_K x: this thread's eight consecutive values take the strides 1, 2, 4 in registers, the next six
+            // strides run between lanes, every later pass gathers through LDS the eight values whose indices differ in
+            // the next three bits
             // (rot_n = K, rot_m = log2 K)
             float* sy = reinterpret_cast<float*>(red + (WS > 1 ? 2 * NW * 4 * 3 * MT : 0));
             const int tid = threadIdx.x;
             const int log2n = rot_m;
             const bool active = tid < xdw;
-            if (active) {
-                register_stages<3>(xr8[0], 0);
+            if (active) register_stages<3>(xr8[0], 0);
+            // the next (up to six) index bits are the lane number: those strides run between lanes (threads without
+            // data only ever meet each other there)
+            const int nlane = min(6, log2n - 3);
+            lane_stages<8>(xr8[0], lane, nlane);
+            int done = 3 + nlane;
+            const bool more = done < log2n;  // uniform: strides beyond a wavefront go through LDS
+            if (more && active) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) sy[wht_slot(tid * 8 + e)] = xr8[0][e];
             }
-            int done = 3;
             while (done < log2n) {  // uniform
                 const int lo = (done <= log2n - 3) ? done : (log2n - 3);
                 const int low = tid & ((1 << lo) - 1), high = tid >> lo;
@@ -297,9 +311,9 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
                 }
                 done = lo + 3;
             }
-            __syncthreads();
+            if (more) __syncthreads();
 #pragma unroll
-            for (int e = 0; e < 8; ++e) xr8[0][e] = active ? __fmul_rn(sy[wht_slot(tid * 8 + e)], rot_norm) : 0.0f;
+            for (int e = 0; e < 8; ++e) xr8[0][e] = active ? __fmul_rn(more ? sy[wht_slot(tid * 8 + e)] : xr8[0][e], rot_norm) : 0.0f;
         }
         // per-token symmetric int4 quantiser, the same arithmetic as quant_kernel
         float a = 0.0f;
@@ -515,9 +529,9 @@ static int launch_one(const GemvArgs& a, int blocks, hipStream_t st)
     }
     kernel<<<blocks, NW * 64, lds, st>>>(
         static_cast<const uint4*>(a.packed), static_cast<const uint2*>(a.codebook), a.N, a.K,
-        a.xraw != nullptr ? a.xraw : a.xq, static_cast<const uint16_t*>(a.scale), a.M, a.clip_ratio, blocks, a.out, a.P,
-        static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out), a.rot_n, a.rot_m,
-        a.rot_n > 0 ? static_cast<float>(1.0 / sqrt(static_cast<double>(a.rot_n))) : 1.0f);
+        a.xraw != nullptr ? a.xraw : a.xq, static_cast<const uint16_t*>(a.scale), a.M, a.clip_ratio, blocks,
+        a.rot_n > 0 ? (a.rot_wht ? a.rot_m : (a.rot_n | (a.rot_m << 8))) : 0, a.out, a.P,
+        static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
     return check_launch("rcp_w2a4_gemv");
 }
 
