@@ -313,49 +313,50 @@ __device__ __forceinline__ void register_stages(float (&v)[1 << LE], int first_b
 template <int EPT>
 __device__ __forceinline__ void lane_stages(float (&v)[EPT], int lane, int nbits)
 {
-    // stage by stage, the EPT values of a stage side by side: their exchanges are independent and overlap
-    if (nbits > 0) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0xB1, 0xf, 0xf, false));  // lane ^ 1
-            v[e] = (lane & 1) ? p - v[e] : v[e] + p;
-        }
+    // stage by stage, the EPT values of a stage side by side: their exchanges are independent and overlap.
+    // partner - z is written partner + (-z): the sign of z is flipped in the lanes with the stage's bit set (one XOR
+    // with a per-lane mask), which leaves one addition for both halves.
+    auto flip = [](float z, uint32_t sign) { return __uint_as_float(__float_as_uint(z) ^ sign); };
+    // (all exchanges of a stage first, then all additions: written as two loops so that the eight chains are issued
+    // interleaved instead of one after the other)
+#define RCP_LANE_STAGE_DPP(BIT, CTRL)                                                                                   \
+    if (nbits > BIT) {                                                                                                   \
+        const uint32_t sg = static_cast<uint32_t>((lane >> BIT) & 1) << 31;                                              \
+        float p[EPT];                                                                                                    \
+        _Pragma("unroll") for (int e = 0; e < EPT; ++e)                                                                  \
+            p[e] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), CTRL, 0xf, 0xf, false));          \
+        __builtin_amdgcn_sched_barrier(0);                                                                               \
+        _Pragma("unroll") for (int e = 0; e < EPT; ++e) v[e] = p[e] + flip(v[e], sg);                                    \
     }
-    if (nbits > 1) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x4E, 0xf, 0xf, false));  // lane ^ 2
-            v[e] = (lane & 2) ? p - v[e] : v[e] + p;
-        }
-    }
+    RCP_LANE_STAGE_DPP(0, 0xB1)  // lane ^ 1
+    RCP_LANE_STAGE_DPP(1, 0x4E)  // lane ^ 2
     if (nbits > 2) {
+        const uint32_t sg = static_cast<uint32_t>((lane >> 2) & 1) << 31;
         float p[EPT];
 #pragma unroll
         for (int e = 0; e < EPT; ++e) p[e] = __shfl_xor(v[e], 4, 64);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) v[e] = (lane & 4) ? p[e] - v[e] : v[e] + p[e];
+        for (int e = 0; e < EPT; ++e) v[e] = p[e] + flip(v[e], sg);
     }
-    if (nbits > 3) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            const float p = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v[e]), 0x128, 0xf, 0xf, false));  // row_ror 8 = lane ^ 8
-            v[e] = (lane & 8) ? p - v[e] : v[e] + p;
-        }
+    RCP_LANE_STAGE_DPP(3, 0x128)  // row_ror 8 = lane ^ 8
+#undef RCP_LANE_STAGE_DPP
+    // the swaps leave (value of the lane with the bit clear, value of the lane with it set) in every lane
+#define RCP_LANE_STAGE_SWAP(BIT, SWAP)                                                                                   \
+    if (nbits > BIT) {                                                                                                   \
+        const uint32_t sg = static_cast<uint32_t>((lane >> BIT) & 1) << 31;                                              \
+        uint32_t lo[EPT], hi[EPT];                                                                                       \
+        _Pragma("unroll") for (int e = 0; e < EPT; ++e) {                                                                \
+            auto r = SWAP(__float_as_uint(v[e]), __float_as_uint(v[e]), false, false);                                   \
+            lo[e] = r[0];                                                                                                \
+            hi[e] = r[1];                                                                                                \
+        }                                                                                                                \
+        __builtin_amdgcn_sched_barrier(0);                                                                               \
+        _Pragma("unroll") for (int e = 0; e < EPT; ++e) v[e] = __uint_as_float(lo[e]) + __uint_as_float(hi[e] ^ sg);     \
     }
-    if (nbits > 4) {  // the swaps leave (value of the lane with the bit clear, value of the lane with it set) in every lane
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v[e]), __float_as_uint(v[e]), false, false);
-            v[e] = (lane & 16) ? __uint_as_float(r[0]) - __uint_as_float(r[1]) : __uint_as_float(r[0]) + __uint_as_float(r[1]);
-        }
-    }
-    if (nbits > 5) {
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[e]), __float_as_uint(v[e]), false, false);
-            v[e] = (lane & 32) ? __uint_as_float(r[0]) - __uint_as_float(r[1]) : __uint_as_float(r[0]) + __uint_as_float(r[1]);
-        }
-    }
+    RCP_LANE_STAGE_SWAP(4, __builtin_amdgcn_permlane16_swap)
+    RCP_LANE_STAGE_SWAP(5, __builtin_amdgcn_permlane32_swap)
+#undef RCP_LANE_STAGE_SWAP
 }
 
 // Where element a of the transform lives in LDS.  Every access pattern of the kernel (EPT
