@@ -570,12 +570,14 @@ static int launch_mt(const GemvArgs& a, int blocks, hipStream_t st)
     return a.out_dt == RCP_F16 ? launch_one<LW, WS, UNR, MT, true, XDT>(a, blocks, st)    \
                                : launch_one<LW, WS, UNR, MT, false, XDT>(a, blocks, st)
     if (a.xraw != nullptr) {
-        if constexpr (LW == 64 && WS == 1) {  // the rotating prologue exists for one wavefront per row group only
+        if constexpr (WS == 1) {  // the order-K rotation works on thread numbers only: any lanes per row group
             if (a.rot_n > 0 && a.rot_wht) {
                 if (a.x_dt == RCP_F16) RCP_GO(1, 8 + RCP_F16);
                 if (a.x_dt == RCP_F32) RCP_GO(1, 8 + RCP_F32);
                 RCP_GO(1, 8 + RCP_BF16);
             }
+        }
+        if constexpr (LW == 64 && WS == 1) {  // the rotation across heads exists for one wavefront per row group only
             if (a.rot_n > 0) {
                 if (a.x_dt == RCP_F16) RCP_GO(1, 4 + RCP_F16);
                 if (a.x_dt == RCP_F32) RCP_GO(1, 4 + RCP_F32);
@@ -664,7 +666,7 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
                                    a.xraw != nullptr ? static_cast<int>(a.x_dt) : -1, a.scale, a.clip_ratio, a.out, a.out_dt, a.P,
                                    a.xq_out, a.scale_out, st);
     GemvPlan p = plan_gemv(a.N, a.K, a.M, a.xraw != nullptr);
-    if (a.rot_n > 0) {  // rotating prologue: one wavefront per row group
+    if (a.rot_n > 0 && (!a.rot_wht || p.ws > 1)) {  // rotating prologue: one wavefront per row group at most
         p.lw = 64;
         p.ws = 1;
         const int nbatch = (a.N / 4 + GEMV_WAVES - 1) / GEMV_WAVES;
