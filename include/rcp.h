@@ -144,7 +144,8 @@ int rcp_version(void);
  * its summation order, within the stated tolerance).  Value 0 restores the automatic choice of one
  * knob, rcp_set_option("reset", 0) that of all.  The settings are process-wide and are read by every
  * launch: do not change them while another host thread is inside a call.
- *   "gemv_lanes"   lanes that share one group of four rows: 16, 32, 64, 128, 256
+ *   "gemv_lanes"   lanes that share one group of four rows: 16, 32, 64, 128, 256 (the kernel for group-wise tables
+ *                  knows 32 = a lane owns whole quantisation groups, and 64 = two lanes share one, its automatic choice)
  *   "gemv_unroll"  16-byte loads per lane and pipeline stage: 2, 4
  *   "gemv_blocks"  number of workgroups the GEMV launches
  *   "gemv_variant" 1 = plain-ALU kernel for every M, 2 = matrix-core kernel for every M

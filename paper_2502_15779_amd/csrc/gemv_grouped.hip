@@ -24,20 +24,20 @@
 namespace rcp {
 
 constexpr int GG_THREADS = 256;
-constexpr int GG_SLOTS = 8;     // row groups a workgroup works on at a time
 constexpr int GG_GROUP = 128;   // input channels per quantisation unit
 constexpr int GG_UNITS = 8;     // 16-byte units per (row group, quantisation group)
 
+template <int UPL>
 struct GroupStep {
-    u32x4 w[GG_UNITS];  // the eight units of this lane's group: 4 rows x 128 columns
-    u32x4 lut[2];       // levels of rows 0,1 | rows 2,3 (four fp16 each)
+    u32x4 w[UPL];   // this lane's units of its group: 4 rows x 16 columns each
+    u32x4 lut[2];   // levels of rows 0,1 | rows 2,3 (four fp16 each)
 };
 
 // LDS: activations in grouped unit order (one uint2 per unit, padded by 32 so that idle lanes
-// of a short round read inside the allocation), then the per-group sums of q.
+// of a short round read inside the allocation), then the sums of q per half group.
 __host__ __device__ constexpr size_t gemv_grouped_lds_bytes(int K)
 {
-    return static_cast<size_t>(K / 16 + 32) * 8 + static_cast<size_t>(K / GG_GROUP) * 4;
+    return static_cast<size_t>(K / 16 + 32) * 8 + static_cast<size_t>(K / GG_GROUP) * 8;
 }
 
 // XDT < 0: `xq` / `scale` are the quantised activations.  XDT = RCP_F16 / RCP_F32 / RCP_BF16:
@@ -50,7 +50,11 @@ constexpr int GG_XU = 4;  // 16-value units of raw activations per thread: K <= 
 // prologue needs at once is among them.)
 // NT: weight loads with the non-temporal hint (matrices of 10 MB and more: 22016 x 4096 8.15 -> 7.95 us, 4096 x 11008
 // 6.84 -> 6.67; the 4 MB of 4096 x 4096 are 11 % slower with it).
-template <bool OUT_F16, int XDT, bool NT = false>
+// LG: lanes per group of four rows.  32: a lane owns whole quantisation groups.  64 (matrices with too few rows to give
+// every compute unit a workgroup otherwise): two lanes share a group, four units each -- the sum over levels is linear
+// in the per-level sums, so each lane multiplies the sums over its own 64 columns by the group's levels and nothing but
+// the four fp32 row totals ever crosses lanes (the per-group sums are put together only for the optional P output).
+template <bool OUT_F16, int XDT, bool NT = false, int LG = 32>
 __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* __restrict__ packed,
                                                                   const uint4* __restrict__ codebook, int N, int K,
                                                                   const void* __restrict__ xraw,
@@ -64,8 +68,12 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
     extern __shared__ uint2 sx2[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int SPL = LG / 32;            // lanes that share a quantisation group
+    constexpr int UPL = GG_UNITS / SPL;     // 16-byte units per lane and group
+    constexpr int GG_SLOTS = GG_THREADS / LG;  // row groups a workgroup works on at a time
     const int ln = lane & 31;
-    const int slot = wave * 2 + (lane >> 5);
+    const int half = SPL == 2 ? lane >> 5 : 0;  // which units of the group this lane owns
+    const int slot = SPL == 2 ? wave : wave * 2 + (lane >> 5);
     const int U = K / 16, G = N / 4, NG = K / GG_GROUP;
     const int nround = (NG + 31) >> 5;
     const int nbatch = (G + GG_SLOTS - 1) / GG_SLOTS;
@@ -81,13 +89,13 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
     const __amdgpu_buffer_rsrc_t xres =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4*>(xq), 0, K / 2, 0x00020000);
 
-    auto load_step = [&](int b, int rd, GroupStep& s) {
+    auto load_step = [&](int b, int rd, GroupStep<UPL>& s) {
         const int rg = b * GG_SLOTS + slot;
         const int R = min(32, NG - 32 * rd);
         const bool valid = ln < R && rg < G;
-        const unsigned woff = valid ? (static_cast<unsigned>(rg) * U + 256u * rd + ln) * 16u : 0x80000000u;
+        const unsigned woff = valid ? (static_cast<unsigned>(rg) * U + 256u * rd + half * UPL * R + ln) * 16u : 0x80000000u;
 #pragma unroll
-        for (int i = 0; i < GG_UNITS; ++i)
+        for (int i = 0; i < UPL; ++i)
             s.w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(woff), i * R * 16, NT ? 2 : 0);
         const unsigned coff = valid ? (static_cast<unsigned>(rg) * NG + 32u * rd + ln) * 32u : 0x80000000u;
         s.lut[0] = __builtin_amdgcn_raw_buffer_load_b128(cres, static_cast<int>(coff), 0, 0);
@@ -109,7 +117,7 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
     advance(b1, rd1);
     int b2 = b1, rd2 = rd1;
     advance(b2, rd2);
-    GroupStep sA, sB;
+    GroupStep<UPL> sA, sB;
     float S;
     if constexpr (XDT < 0) {
         // Small loads first (memory answers in issue order): this thread's group of activations
@@ -132,26 +140,29 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             const int r0 = g >> 5;
             const int R = min(32, NG - 32 * r0);
             uint2* dst = sx2 + 256 * r0 + (g & 31);
-            int t = 0;
+            int t[2] = {0, 0};  // units 0..3 | units 4..7
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 dst[(2 * i) * R] = make_uint2(xg[i].x, xg[i].y);
                 dst[(2 * i + 1) * R] = make_uint2(xg[i].z, xg[i].w);
-                t = dot8(xg[i].x, 0x11111111u, t);
-                t = dot8(xg[i].y, 0x11111111u, t);
-                t = dot8(xg[i].z, 0x11111111u, t);
-                t = dot8(xg[i].w, 0x11111111u, t);
+                int& ti = t[i >> 1];
+                ti = dot8(xg[i].x, 0x11111111u, ti);
+                ti = dot8(xg[i].y, 0x11111111u, ti);
+                ti = dot8(xg[i].z, 0x11111111u, ti);
+                ti = dot8(xg[i].w, 0x11111111u, ti);
             }
-            tgs[g] = t;
+            if constexpr (SPL == 2) {
+                tgs[2 * g] = t[0];
+                tgs[2 * g + 1] = t[1];
+            } else
+                tgs[g] = t[0] + t[1];
         }
         __syncthreads();
     } else {
-        // Fused quantiser.  Thread t takes the 16-value units t, t + 256, ...; the first one stays
-        // in registers between the two passes (maximum, then quantisation), further ones (K > 4096)
-        // are read again from cache.
+        // Fused quantiser.  Thread t takes the 16-value units t, t + 256, ...; they stay in registers, as they came
+        // from memory, between the two passes (maximum, then quantisation).
         __shared__ float amax_slots[GG_THREADS / 64];
         constexpr int XT = XDT >= 0 ? XDT : 0;
-        float first[2][8];
         float a = 0.0f;
         // the activations are requested first (memory answers in issue order), the weights of the
         // first two steps right behind them, and only then is anything waited for
@@ -174,15 +185,9 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             widen8<XT>(xr[i][0], v[0]);
             widen8<XT>(xr[i][1], v[1]);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                a = fmaxf(a, fmaxf(fabsf(v[0][j]), fabsf(v[1][j])));
-                if (i == 0) {
-                    first[0][j] = v[0][j];
-                    first[1][j] = v[1][j];
-                }
-            }
+            for (int j = 0; j < 8; ++j) a = fmaxf(a, fmaxf(fabsf(v[0][j]), fabsf(v[1][j])));
         }
-        for (int g = threadIdx.x; g < NG; g += GG_THREADS) tgs[g] = 0;
+        for (int g = threadIdx.x; g < NG * SPL; g += GG_THREADS) tgs[g] = 0;
         a = wave_max(a);
         if (lane == 0) amax_slots[wave] = a;
         __syncthreads();
@@ -195,21 +200,14 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             if (i * GG_THREADS >= U) break;
             const int u = threadIdx.x + i * GG_THREADS;
             if (u < U) {
-                uint32_t q0, q1;
-                if (i == 0) {
-                    q0 = quantize8(first[0], S);
-                    q1 = quantize8(first[1], S);
-                } else {
-                    float v[2][8];
-                    load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16, v[0]);
-                    load8_as_float<(XDT >= 0 ? XDT : 0)>(xraw, static_cast<size_t>(u) * 16 + 8, v[1]);
-                    q0 = quantize8(v[0], S);
-                    q1 = quantize8(v[1], S);
-                }
+                float v[2][8];
+                widen8<XT>(xr[i][0], v[0]);
+                widen8<XT>(xr[i][1], v[1]);
+                const uint32_t q0 = quantize8(v[0], S), q1 = quantize8(v[1], S);
                 const int g = u >> 3, r0 = g >> 5;
                 const int R = min(32, NG - 32 * r0);
                 sx2[256 * r0 + (u & 7) * R + (g & 31)] = make_uint2(q0, q1);
-                atomicAdd(&tgs[g], dot8(q1, 0x11111111u, dot8(q0, 0x11111111u, 0)));
+                atomicAdd(&tgs[SPL == 2 ? 2 * g + ((u & 7) >> 2) : g], dot8(q1, 0x11111111u, dot8(q0, 0x11111111u, 0)));
                 if (publish) reinterpret_cast<uint2*>(xq_out)[u] = make_uint2(q0, q1);
             }
         }
@@ -221,18 +219,18 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
 
     // One pipeline step: compute the current step from `cur` (the loads of the following step are in
     // flight in the other register set), then refill `cur` with the step two ahead.
-    auto step = [&](GroupStep& cur) {
+    auto step = [&](GroupStep<UPL>& cur) {
         const bool last = rd + 1 == nround;
 
         const int R = min(32, NG - 32 * rd);
-        const uint2* xp = sx2 + 256 * rd + ln;
+        const uint2* xp = sx2 + 256 * rd + half * UPL * R + ln;
         int acc[1][3][4];
 #pragma unroll
         for (int p = 0; p < 3; ++p)
 #pragma unroll
             for (int m = 0; m < 4; ++m) acc[0][p][m] = 0;
 #pragma unroll
-        for (int i = 0; i < GG_UNITS; ++i) {
+        for (int i = 0; i < UPL; ++i) {
             const uint2 xv = xp[i * R];
             const uint32_t xa[1] = {xv.x}, xb[1] = {xv.y};
             cell_update<1>(cur.w[i].x, cur.w[i].y, xa, acc);
@@ -240,7 +238,7 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
         }
         const bool valid = ln < R;
         const int g = 32 * rd + ln;
-        const int Tg = valid ? tgs[g] : 0;
+        const int Tg = valid ? tgs[SPL == 2 ? 2 * g + half : g] : 0;
         const int rg = b * GG_SLOTS + slot;
         const uint32_t lw[8] = {cur.lut[0].x, cur.lut[0].y, cur.lut[0].z, cur.lut[0].w,
                                 cur.lut[1].x, cur.lut[1].y, cur.lut[1].z, cur.lut[1].w};
@@ -268,8 +266,16 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             v = fmaf(c2, static_cast<float>(P2), v);
             v = fmaf(c3, static_cast<float>(P3), v);
             o[r] = v;
-            if (Pout != nullptr && valid && rg < G)
-                reinterpret_cast<int4*>(Pout)[static_cast<size_t>(4 * rg + r) * NG + g] = make_int4(P0, P1, P2, P3);
+            if (Pout != nullptr) {  // uniform
+                int4 Pg = make_int4(P0, P1, P2, P3);
+                if constexpr (SPL == 2) {  // the group's sums: this lane's 64 columns plus the other lane's
+                    Pg.x += __shfl_xor(P0, 32, 64);
+                    Pg.y += __shfl_xor(P1, 32, 64);
+                    Pg.z += __shfl_xor(P2, 32, 64);
+                    Pg.w += __shfl_xor(P3, 32, 64);
+                }
+                if (valid && rg < G && half == 0) reinterpret_cast<int4*>(Pout)[static_cast<size_t>(4 * rg + r) * NG + g] = Pg;
+            }
         }
 
         // `cur` is consumed: refill it, before the row totals below
@@ -278,11 +284,15 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
         __builtin_amdgcn_sched_barrier(0);
 
         if (last) {
-            // row totals over the 32 lanes of the row group: even 16-lane rows end up with
+            // row totals over the lanes of the row group: even 16-lane rows end up with
             // rows 0 and 2, odd ones with rows 1 and 3
-            const float s01 = row_sum16f(fold16f(o[0], o[1]));
-            const float s23 = row_sum16f(fold16f(o[2], o[3]));
-            if (rg < G && (lane & 15) == 0) {
+            float s01 = row_sum16f(fold16f(o[0], o[1]));
+            float s23 = row_sum16f(fold16f(o[2], o[3]));
+            if constexpr (SPL == 2) {
+                s01 += __shfl_xor(s01, 32, 64);
+                s23 += __shfl_xor(s23, 32, 64);
+            }
+            if (rg < G && (lane & 15) == 0 && half == 0) {
                 const int odd = (lane >> 4) & 1;
                 const int h = 4 * rg + odd;
                 const float v0 = s01 * S, v1 = s23 * S;
@@ -326,10 +336,10 @@ struct GroupedArgs {
     void *xq_out, *scale_out;
 };
 
-template <bool OUT_F16, int XDT, bool NT>
+template <bool OUT_F16, int XDT, bool NT, int LG = 32>
 static int launch_grouped_nt(const GroupedArgs& a, int blocks, size_t lds, hipStream_t st)
 {
-    gemv_grouped_kernel<OUT_F16, XDT, NT><<<blocks, GG_THREADS, lds, st>>>(
+    gemv_grouped_kernel<OUT_F16, XDT, NT, LG><<<blocks, GG_THREADS, lds, st>>>(
         static_cast<const uint4*>(a.packed), static_cast<const uint4*>(a.codebook), a.N, a.K, a.xraw,
         static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.clip_ratio, blocks, a.out, a.P,
         static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
@@ -337,8 +347,13 @@ static int launch_grouped_nt(const GroupedArgs& a, int blocks, size_t lds, hipSt
 }
 
 template <bool OUT_F16, int XDT>
-static int launch_grouped_one(const GroupedArgs& a, int blocks, size_t lds, hipStream_t st)
+static int launch_grouped_one(const GroupedArgs& a, int blocks, size_t lds, bool two_lanes, hipStream_t st)
 {
+    if (two_lanes) {
+        const bool nt2 = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(a.N) * a.K / 4 >= (10LL << 20);
+        return nt2 ? launch_grouped_nt<OUT_F16, XDT, true, 64>(a, blocks, lds, st)
+                   : launch_grouped_nt<OUT_F16, XDT, false, 64>(a, blocks, lds, st);
+    }
     // ("gemv_nt": 1 = non-temporal weight loads always, 2 = never; automatic: from 10 MB of packed weights on)
     const bool nt = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(a.N) * a.K / 4 >= (10LL << 20);
     return nt ? launch_grouped_nt<OUT_F16, XDT, true>(a, blocks, lds, st) : launch_grouped_nt<OUT_F16, XDT, false>(a, blocks, lds, st);
@@ -350,17 +365,26 @@ static int dispatch_grouped(const GroupedArgs& a, hipStream_t st)
         return fail(RCP_ERR_SHAPE, "rcp_w2a4_gemv_grouped: packed matrix of %lld bytes exceeds 2 GiB",
                     static_cast<long long>(a.N) * a.K / 4);
     const int G = a.N / 4;
-    const int nbatch = (G + GG_SLOTS - 1) / GG_SLOTS;
     const int cus = num_compute_units();
+    // two lanes per quantisation group, four row groups per workgroup: twice the wavefronts for the same loads
+    // (sweeps: 4096 x 4096 3.97 -> 3.48 us, 4096 x 11008 6.43 -> 5.20, 12288 x 4096 5.81 -> 5.24, 22016 x 4096
+    // 7.98 -> 7.68 with activations quantised beforehand); "gemv_lanes" = 32 asks for the other form
+    const bool two_lanes = options().gemv_lanes != 32;
+    const int slots = two_lanes ? 4 : 8;
+    const int nbatch = (G + slots - 1) / slots;
     int blocks = options().gemv_blocks;
-    if (blocks == 0) blocks = nbatch <= cus * 8 ? nbatch : cus * 4;
+    // one workgroup per compute unit walks its batches with the loads of the next two in flight (sweeps with two lanes
+    // per group, fused: 12288 x 4096 5.7 us with 512 or 768 workgroups, 5.3 with 256; 22016 x 4096 8.2 -> 7.95;
+    // 14336 x 4096 6.9 -> 6.1; counts between one and two per unit are worst)
+    if (blocks == 0) blocks = two_lanes ? cus : (nbatch <= cus * 8 ? nbatch : cus * 4);
     // every workgroup quantises x itself: fewer, longer-lived workgroups
     if (options().gemv_blocks == 0 && a.xraw != nullptr && blocks > cus * 2) blocks = cus * 2;
     if (blocks > nbatch) blocks = nbatch;
     if (blocks < 1) blocks = 1;
     const size_t lds = gemv_grouped_lds_bytes(a.K);
 #define RCP_GG(XDT) \
-    return a.out_dt == RCP_F16 ? launch_grouped_one<true, XDT>(a, blocks, lds, st) : launch_grouped_one<false, XDT>(a, blocks, lds, st)
+    return a.out_dt == RCP_F16 ? launch_grouped_one<true, XDT>(a, blocks, lds, two_lanes, st) \
+                               : launch_grouped_one<false, XDT>(a, blocks, lds, two_lanes, st)
     if (a.xraw == nullptr) RCP_GG(-1);
     if (a.x_dt == RCP_F16) RCP_GG(RCP_F16);
     if (a.x_dt == RCP_F32) RCP_GG(RCP_F32);

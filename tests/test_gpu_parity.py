@@ -189,9 +189,12 @@ def _check_grouped_gemv(packed, cb, N, K, xq, sc, out_dtype):
 @pytest.mark.parametrize("blocks", [0, 1, 5])
 @pytest.mark.parametrize("N,K", [(4, 128), (8, 256), (36, 4096), (1028, 4096), (72, 11008), (40, 14336), (20, 4224),
                                  (12, 32768)])
-def test_grouped_gemv_partial_sums_bit_exact_and_output_close(N, K, blocks):
-    _say(f"grouped gemv N={N} K={K} blocks={blocks}")
+@pytest.mark.parametrize("lanes", [32, 64])
+def test_grouped_gemv_partial_sums_bit_exact_and_output_close(N, K, blocks, lanes):
+    """Both forms of the kernel: a lane owns whole groups (32 lanes per four rows), two lanes share a group (64)."""
+    _say(f"grouped gemv N={N} K={K} blocks={blocks} lanes={lanes}")
     rcp.set_option("gemv_blocks", blocks)
+    rcp.set_option("gemv_lanes", lanes)
     packed, cb, xq, sc = _grouped_gemv_case(21, N, K)
     _check_grouped_gemv(packed, cb, N, K, xq, sc, torch.float32 if blocks else torch.float16)
     rcp.set_option("gemv_nt", 1)     # the weight loads' cache hint of large matrices, forced
@@ -280,9 +283,11 @@ def test_grouped_gemv_extreme_activations_and_integer_levels():
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
 @pytest.mark.parametrize("N,K,ratio", [(8, 128, 1.0), (36, 4096, 1.0), (1028, 4096, 0.9), (72, 11008, 1.0), (40, 14336, 1.0),
                                        (16, 16384, 1.0), (8, 32768, 1.0)])
-def test_grouped_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype):
+@pytest.mark.parametrize("lanes", [32, 64])
+def test_grouped_fused_quantise_gemv_equals_the_two_calls(N, K, ratio, dtype, lanes):
     """One launch (quantiser in the prologue of the grouped GEMV) must give the bits of the two calls."""
-    _say(f"grouped fused quant+gemv N={N} K={K} ratio={ratio} {dtype}")
+    _say(f"grouped fused quant+gemv N={N} K={K} ratio={ratio} {dtype} lanes={lanes}")
+    rcp.set_option("gemv_lanes", lanes)
     packed, cb, _, _ = _grouped_gemv_case(61, N, K)
     x16 = rcp_synth.activation(61, f"gfq{K}", 1, K)
     xd = {"f16": _t(x16), "bf16": _t(x16.astype(np.float32)).to(torch.bfloat16),
