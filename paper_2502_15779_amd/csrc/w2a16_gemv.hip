@@ -106,9 +106,17 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     auto load_lut = [&](int bb) -> uint2 { return codebook[min(4 * (bb * SLOTS + slot) + ent_r, N - 1)]; };
     auto build_table = [&](uint2 row) { tab[lane] = lut_half(row, ent_lo) | (lut_half(row, ent_hi) << 16); };
 
-    // memory answers loads in issue order: this thread's first eight activations go first, so that staging
-    // them does not have to wait for the weights
-    Raw8<XDT> xfirst = load8_raw<XDT>(x, static_cast<size_t>(min(static_cast<int>(threadIdx.x), K / 8 - 1)) * 8);
+    // memory answers loads in issue order: this thread's activations (up to WO_XG pieces of eight, K <= 12288; a longer
+    // token's remaining pieces are fetched in the staging loop) go first, so that staging them does not have to wait
+    // for the weights
+    constexpr int WO_XG = 6;
+    const int xpieces = min((K / 8 + WO_THREADS - 1) / WO_THREADS, WO_XG);  // pieces held in registers
+    Raw8<XDT> xr[WO_XG];
+#pragma unroll
+    for (int i = 0; i < WO_XG; ++i) {
+        if (i * WO_THREADS >= K / 8) break;  // uniform
+        xr[i] = load8_raw<XDT>(x, static_cast<size_t>(min(static_cast<int>(threadIdx.x) + i * WO_THREADS, K / 8 - 1)) * 8);
+    }
     int b = blockIdx.x;
     uint2 lut_row = load_lut(b);  // needed for the table before the first step: ahead of the weights too
     __builtin_amdgcn_sched_barrier(0);
@@ -116,7 +124,7 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     u32x4 wA[WO_UNR], wB[WO_UNR];
     load_chunk(base, 0, b, wA);
     // (a use right here keeps the compiler from moving the activation load down into the staging branch)
-    asm volatile("" ::"v"(xfirst.a.x), "v"(xfirst.a.w), "v"(lut_row.x));
+    asm volatile("" ::"v"(xr[0].a.x), "v"(xr[0].a.w), "v"(lut_row.x));
 
     // stage the activations, zero beyond K
     const int padded = wo_padded_units(K, LG * WO_UNR);
@@ -126,22 +134,31 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     if constexpr (!XF32) {
         const uint4* x4 = static_cast<const uint4*>(x);  // eight fp16 per uint4: two per unit
         uint4* s4 = reinterpret_cast<uint4*>(sx);
-        // the first piece apart from the loop: behind a join with the loop's own loads the compiler would
+        // the pieces in registers apart from the loop: behind a join with the loop's own loads the compiler would
         // wait for every load in flight, the weights included
-        if (static_cast<int>(threadIdx.x) < padded * 2)
-            s4[threadIdx.x] = static_cast<int>(threadIdx.x) < K / 8 ? xfirst.a : make_uint4(0u, 0u, 0u, 0u);
-        for (int j = threadIdx.x + WO_THREADS; j < padded * 2; j += WO_THREADS)
+#pragma unroll
+        for (int i = 0; i < WO_XG; ++i) {
+            if (i * WO_THREADS >= K / 8) break;  // uniform
+            const int j = threadIdx.x + i * WO_THREADS;
+            if (j < padded * 2) s4[j] = j < K / 8 ? xr[i].a : make_uint4(0u, 0u, 0u, 0u);
+        }
+        for (int j = threadIdx.x + xpieces * WO_THREADS; j < padded * 2; j += WO_THREADS)
             s4[j] = j < K / 8 ? x4[j] : make_uint4(0u, 0u, 0u, 0u);
     } else {
         float4* s4 = reinterpret_cast<float4*>(sx);
-        if (static_cast<int>(threadIdx.x) < padded * 2) {  // the first piece apart from the loop, as above
-            float v[8];
-            widen8<XDT>(xfirst, v);
-            const bool in = static_cast<int>(threadIdx.x) < K / 8;
-            s4[2 * threadIdx.x] = in ? make_float4(v[0], v[1], v[2], v[3]) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            s4[2 * threadIdx.x + 1] = in ? make_float4(v[4], v[5], v[6], v[7]) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll
+        for (int i = 0; i < WO_XG; ++i) {  // the pieces in registers apart from the loop, as above
+            if (i * WO_THREADS >= K / 8) break;  // uniform
+            const int j = threadIdx.x + i * WO_THREADS;
+            if (j < padded * 2) {
+                float v[8];
+                widen8<XDT>(xr[i], v);
+                const bool in = j < K / 8;
+                s4[2 * j] = in ? make_float4(v[0], v[1], v[2], v[3]) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                s4[2 * j + 1] = in ? make_float4(v[4], v[5], v[6], v[7]) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
         }
-        for (int j = threadIdx.x + WO_THREADS; j < padded * 2; j += WO_THREADS) {  // eight values per step
+        for (int j = threadIdx.x + xpieces * WO_THREADS; j < padded * 2; j += WO_THREADS) {  // eight values per step
             float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
             if (j < K / 8) load8_as_float<XDT>(x, static_cast<size_t>(j) * 8, v);
             s4[2 * j] = make_float4(v[0], v[1], v[2], v[3]);
