@@ -153,8 +153,9 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
         if (lane == 0) tsum[wave] = s;
     } else {
         // Fused quantiser: the raw activations are requested first, the weights of the first two steps
-        // right behind them, and only then is anything waited for.  The first unit of a thread stays in
-        // registers between the two passes; further ones (K > 4096) are read again from cache.
+        // right behind them, and only then is anything waited for.  A thread's units stay in registers, as they came
+        // from memory, between the two passes (re-reading them from cache for the second pass cost about a microsecond
+        // on K = 11008); only beyond 12288 values are the remaining ones read again.
         __shared__ float amax_slots[W3_WAVES];
         constexpr int XT = XDT >= 0 ? XDT : 0;
         const int U16 = K / 16;  // 16-value units (uint2 of x_q); K is a multiple of 32
@@ -171,7 +172,6 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
         lut = codebook[min(4 * (b * SLOTS + slot) + my_row, N - 1)];
         asm volatile("" ::"s"(out), "s"(Pout), "s"(xq_out), "s"(scale_out));  // fetch the late arguments now
         __builtin_amdgcn_sched_barrier(0);
-        float first[2][8];
         float a = 0.0f;
 #pragma unroll
         for (int i = 0; i < W3_XR; ++i) {
@@ -180,13 +180,7 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
             widen8<XT>(xr[i][0], v[0]);
             widen8<XT>(xr[i][1], v[1]);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                a = fmaxf(a, fmaxf(fabsf(v[0][e]), fabsf(v[1][e])));
-                if (i == 0) {
-                    first[0][e] = v[0][e];
-                    first[1][e] = v[1][e];
-                }
-            }
+            for (int e = 0; e < 8; ++e) a = fmaxf(a, fmaxf(fabsf(v[0][e]), fabsf(v[1][e])));
         }
         for (int u = threadIdx.x + W3_XR * W3_THREADS; u < U16; u += W3_THREADS) {  // K > 12288 only
             float v[2][8];
@@ -204,17 +198,30 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
         const bool publish = blockIdx.x == 0 && xq_out != nullptr;
         uint2* sx2 = reinterpret_cast<uint2*>(smem4);
         int s = 0;
-        for (int u = threadIdx.x; u < 2 * xpieces; u += W3_THREADS) {  // the padding up to whole blocks is zeroed too
+#pragma unroll
+        for (int i = 0; i < W3_XR; ++i) {  // the padding up to whole blocks is zeroed too
+            if (i * W3_THREADS >= 2 * xpieces) break;  // uniform
+            const int u = threadIdx.x + i * W3_THREADS;
+            if (u < 2 * xpieces) {
+                uint2 qv = make_uint2(0u, 0u);
+                if (u < U16) {
+                    float v[2][8];
+                    widen8<XT>(xr[i][0], v[0]);
+                    widen8<XT>(xr[i][1], v[1]);
+                    qv = make_uint2(quantize8(v[0], S), quantize8(v[1], S));
+                    s = dot8(qv.y, 0x11111111u, dot8(qv.x, 0x11111111u, s));
+                    if (publish) xq_out[u] = qv;
+                }
+                sx2[u] = qv;
+            }
+        }
+        for (int u = threadIdx.x + W3_XR * W3_THREADS; u < 2 * xpieces; u += W3_THREADS) {  // K > 12288 only
             uint2 qv = make_uint2(0u, 0u);
             if (u < U16) {
-                if (u == static_cast<int>(threadIdx.x)) {
-                    qv = make_uint2(quantize8(first[0], S), quantize8(first[1], S));
-                } else {
-                    float v[2][8];
-                    load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16, v[0]);
-                    load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16 + 8, v[1]);
-                    qv = make_uint2(quantize8(v[0], S), quantize8(v[1], S));
-                }
+                float v[2][8];
+                load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16, v[0]);
+                load8_as_float<XT>(x_in, static_cast<size_t>(u) * 16 + 8, v[1]);
+                qv = make_uint2(quantize8(v[0], S), quantize8(v[1], S));
                 s = dot8(qv.y, 0x11111111u, dot8(qv.x, 0x11111111u, s));
                 if (publish) xq_out[u] = qv;
             }
