@@ -844,7 +844,41 @@ def main():
             large[key + "_GBps"] = round(bb / sec / 1e9, 1)
         large.update({"shape": f"{N}x{K}", "bytes": b, "buffers": nbuf,
                       "pct_of_hbm_peak": round(large["prequantised_GBps"] / HBM_PEAK_GBPS * 100, 1)})
-        del bufs
+        # the widened kernels on the same shape (activations quantised beforehand where they are quantised at all)
+        NG = K // rcp.GROUP
+        lvs = [(torch.randn((N // 4, NG, 4, 4), device=dev) * 0.03).sort(dim=3).values.to(torch.float16).contiguous()
+               for _ in range(nbuf)]
+
+        def lsweep_g():
+            for (pk, _), lv in zip(bufs, lvs):
+                rcp.w2a4_gemv_grouped(pk, lv, N, K, xql, scl, out=ol)
+
+        def lsweep_wo():
+            for pk, cb in bufs:
+                rcp.w2a16_gemv(pk, cb, N, K, xl, out=ol)
+        others = {}
+        for key, sweep, bb in (("grouped_128", lsweep_g, N * K // 4 + 8 * N * NG + K // 2 + 2 + 2 * N),
+                               ("weight_only_fp16", lsweep_wo, N * K // 4 + 8 * N + 2 * K + 2 * N)):
+            sweep()
+            fn = capture(sweep)
+            fn()
+            sec = min(timed(torch, fn, 3), timed(torch, fn, 3)) / nbuf
+            others[key] = {"us": round(sec * 1e6, 2), "GBps": round(bb / sec / 1e9, 1), "bytes": bb}
+        del bufs, lvs
+        bufs3 = [(torch.randint(0, 256, (3 * N * K // 8,), dtype=torch.uint8, device=dev),
+                  (torch.randn((N, 8), device=dev) * 0.03).sort(dim=1).values.to(torch.float16).contiguous()) for _ in range(nbuf)]
+
+        def lsweep_3():
+            for pk, cb in bufs3:
+                rcp.w3a4_gemv(pk, cb, N, K, xql, scl, out=ol)
+        lsweep_3()
+        fn = capture(lsweep_3)
+        fn()
+        sec = min(timed(torch, fn, 3), timed(torch, fn, 3)) / nbuf
+        bb = 3 * N * K // 8 + 16 * N + K // 2 + 2 + 2 * N
+        others["w3a4"] = {"us": round(sec * 1e6, 2), "GBps": round(bb / sec / 1e9, 1), "bytes": bb}
+        large["other_kernels"] = others
+        del bufs3
 
     # What a dependent launch costs on this machine, and what the same dependency costs inside one launch:
     # (a) a chain of launches that read 16 bytes each; (b) a chain of the smallest fused GEMV (64 x 128) as launches;

@@ -351,7 +351,9 @@ static int launch_w3_ws(const W3Args& a, hipStream_t st)
     constexpr int SLOTS = W3_WAVES / WS;
     const int nbatch = (G + SLOTS - 1) / SLOTS;
     int blocks = options().gemv_blocks;
-    if (blocks == 0) blocks = nbatch <= cus * 2 ? nbatch : cus * 2;  // sweeps: two workgroups per compute unit
+    // sweeps: two workgroups per compute unit on LLaMA-sized layers; a matrix with 16 and more batches per unit streams
+    // 5 - 7 % faster from eight (65536 x 4096 24.4 -> 23.1 us, 131072 x 4096 46.5 -> 43.1)
+    if (blocks == 0) blocks = nbatch >= cus * 16 ? cus * 8 : (nbatch <= cus * 2 ? nbatch : cus * 2);
     if (blocks > nbatch) blocks = nbatch;
     auto launch = [&](auto kernel) {
         kernel<<<blocks, W3_THREADS, lds, st>>>(static_cast<const uint8_t*>(a.packed), static_cast<const uint4*>(a.codebook), a.N,

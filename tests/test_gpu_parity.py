@@ -1044,6 +1044,33 @@ def test_full_size_small_batch_layer_matches_oracle(M):
     assert np.linalg.norm(got - ref_O) <= 1e-3 * np.linalg.norm(ref_O)
 
 
+def test_large_matrix_as_benchmarked():
+    """131072 x 4096 (the bench line's `large_matrix`): the non-temporal form of the one-token kernel, the fused call and
+    the kernel for group-wise tables in the launch configurations that size selects, every output against the oracle.
+    Any byte string is a valid packed matrix, so the weights are random bytes."""
+    N, K = 131072, 4096
+    NG = K // 128
+    _say("large matrix 131072 x 4096")
+    rng = np.random.default_rng(131)
+    packed = rng.integers(0, 256, size=N * K // 4, dtype=np.uint8)
+    cb = np.sort(rng.standard_normal((N, 4)) * 0.03, axis=1).astype(np.float16).view(np.uint16)
+    x = rcp_synth.activation(131, "large", 1, K)
+    xq_t, sc_t = rcp.rotate_quant_act(_t(x))
+    torch.cuda.synchronize()
+    xq, sc = xq_t.cpu().numpy(), sc_t.cpu().numpy().view(np.uint16)
+    oxq, osc, _ = oracle.quantize_act(x.astype(np.float32), 1.0)
+    assert np.array_equal(xq, oxq) and np.array_equal(sc, osc)
+    _check_gemv(packed, cb, N, K, xq, sc, 1, torch.float32)
+    pk, lut = _t(packed), _t(cb.view(np.float16))
+    ref = rcp.w2a4_gemv(pk, lut, N, K, xq_t, sc_t, 1, out_dtype=torch.float32)
+    fused = rcp.quant_w2a4_gemv(pk, lut, N, K, _t(x), 1.0, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, ref)
+    del pk, lut, ref, fused
+    lv = np.sort(rng.standard_normal((N // 4, NG, 4, 4)) * 0.03, axis=3).astype(np.float16).view(np.uint16)
+    _check_grouped_gemv(packed, lv, N, K, xq, sc, torch.float32)
+
+
 def test_full_size_grouped_and_weight_only_as_benchmarked():
     """gate|up at full size (22016 x 4096) through the group-wise fused call and the weight-only call."""
     N, K = 22016, 4096

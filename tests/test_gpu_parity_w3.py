@@ -278,3 +278,16 @@ def test_w3_argument_errors():
     out = rcp.w3a4_gemv(packed, cb, N, K, xq, sc)
     torch.cuda.synchronize()
     assert not out.any()
+
+
+def test_w3_large_matrix_as_benchmarked():
+    """131072 x 4096 (the bench line's `large_matrix.other_kernels.w3a4`): the launch configuration that size selects,
+    every output against the oracle.  Any byte string is a valid packed matrix, so the weights are random bytes."""
+    N, K = 131072, 4096
+    _say("w3 large matrix 131072 x 4096")
+    rng = np.random.default_rng(133)
+    packed = rng.integers(0, 256, size=3 * N * K // 8, dtype=np.uint8)
+    cb = np.sort(rng.standard_normal((N, 8)) * 0.03, axis=1).astype(np.float16).view(np.uint16)
+    q = rcp_synth.random_int4(133, "w3large", 1, K)
+    sc = np.array([0.07], np.float16).view(np.uint16)
+    _check_w3(packed, cb, N, K, _nibbles(q), sc, torch.float32)
