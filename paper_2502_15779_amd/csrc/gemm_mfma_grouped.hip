@@ -43,7 +43,9 @@ struct MgStage {
 // NARROW: the workgroup owns 4 row groups (16 output rows): the 16 rows of the A operand are (row group,
 // row in the nibble) pairs as in gemm_mfma.hip, the mask and its E8M0 scale are per-lane values, and
 // one instruction per plane and activation part covers all four rows of a nibble.
-template <bool OUT_F16, bool NARROW>
+// WANTP: the per-group sums are written to Pout as well (a verification output: with its stores and branches in the
+// loop the wide form needs 221 registers instead of 102, which leaves room for a single workgroup on a compute unit).
+template <bool OUT_F16, bool NARROW, bool WANTP>
 __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uint4* __restrict__ packed,
                                                                        const uint4* __restrict__ codebook, int N, int K,
                                                                        const uint4* __restrict__ xq,
@@ -138,8 +140,8 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
 
         const uint32_t p0[4] = {cur.wa.x, cur.wa.z, cur.wb.x, cur.wb.z};
         const uint32_t p1[4] = {cur.wa.y, cur.wa.w, cur.wb.y, cur.wb.w};
-        v4f acc[3][4];
         if constexpr (NARROW) {
+            v4f acc[3][1];
             v8i an[3];
 #pragma unroll
             for (int p = 0; p < 3; ++p) an[p] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
@@ -154,7 +156,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
                 acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], blo, zero, 4, 4, 0, row_scale, 0, SC_ONE);
                 acc[p][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(an[p], bhi, acc[p][0], 4, 4, 0, row_scale, 0, SC_HI);
             }
-            const bool store_pn = Pout != nullptr && i < M && gcur < NG;
+            const bool store_pn = WANTP && i < M && gcur < NG;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float4 c = coef_lds[wave][4 * kb + v];
@@ -165,7 +167,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
                 val = fmaf(c.z, F1, val);
                 val = fmaf(c.w, F3, val);
                 o[v][0] = val;
-                if (store_pn) {
+                if constexpr (WANTP) if (store_pn) {
                     const int h = 4 * (static_cast<int>(blockIdx.x) * 4 + kb) + v;
                     if (h < N)
                         reinterpret_cast<int4*>(Pout)[(static_cast<size_t>(i) * N + h) * NG + gcur] =
@@ -175,47 +177,39 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
             }
             return;
         }
-        v8i a[3][4];
+        // one row of the nibble at a time: its three plane operands, six instructions, and the products with the
+        // coefficients of its 16 rows of the block
+        const bool store_p = WANTP && i < M && gcur < NG;
 #pragma unroll
-        for (int p = 0; p < 3; ++p) {
+        for (int r = 0; r < 4; ++r) {
+            v8i a[3];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) a[p][r] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
+            for (int p = 0; p < 3; ++p) a[p] = v8i{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                if (p < 2) {
-                    const uint32_t w = p == 0 ? p0[d] : p1[d];
-                    a[p][0][d] = static_cast<int>(w & 0x11111111u);
-                    a[p][1][d] = static_cast<int>(w & 0x22222222u);
-                    a[p][2][d] = static_cast<int>(w & 0x44444444u);
-                    a[p][3][d] = static_cast<int>((w >> 1) & 0x44444444u);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) a[2][r][d] = a[0][r][d] & a[1][r][d];  // the masks of b0 & b1
-                }
+                const uint32_t m = r == 0 ? 0x11111111u : r == 1 ? 0x22222222u : 0x44444444u;
+                a[0][d] = static_cast<int>((p0[d] >> (r == 3 ? 1 : 0)) & m);
+                a[1][d] = static_cast<int>((p1[d] >> (r == 3 ? 1 : 0)) & m);
+                a[2][d] = a[0][d] & a[1][d];  // the mask of b0 & b1
             }
+            v4f ar[3];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], blo, zero, 4, 4, 0, SC_A[r], 0, SC_ONE);
+            for (int p = 0; p < 3; ++p) {
+                ar[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p], blo, zero, 4, 4, 0, SC_A[r], 0, SC_ONE);
+                ar[p] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p], bhi, ar[p], 4, 4, 0, SC_A[r], 0, SC_HI);
+            }
+            // plane sums (exact small integers in binary32) times the coefficients of (row, group)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc[p][r] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a[p][r], bhi, acc[p][r], 4, 4, 0, SC_A[r], 0, SC_HI);
-        }
-
-        // plane sums (exact small integers in binary32) times the coefficients of (row, group)
-        const bool store_p = Pout != nullptr && i < M && gcur < NG;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int v = 0; v < 4; ++v) {
                 const float4 c = coef_lds[wave][4 * (4 * kb + v) + r];
-                const float F0 = acc[0][r][v], F1 = acc[1][r][v], F3 = acc[2][r][v];
+                const float F0 = ar[0][v], F1 = ar[1][v], F3 = ar[2][v];
                 float val = o[v][r];
                 val = fmaf(c.x, tq[v], val);
                 val = fmaf(c.y, F0, val);
                 val = fmaf(c.z, F1, val);
                 val = fmaf(c.w, F3, val);
                 o[v][r] = val;
-                if (store_p) {
+                if constexpr (WANTP) if (store_p) {
                     const int h = 4 * (blockIdx.x * 16 + 4 * kb + v) + r;
                     if (h < N)
                         reinterpret_cast<int4*>(Pout)[(static_cast<size_t>(i) * N + h) * NG + gcur] =
@@ -223,6 +217,7 @@ __global__ __launch_bounds__(MG_THREADS) void gemm_mfma_grouped_kernel(const uin
                                       static_cast<int>(F1 - F3), static_cast<int>(F3));
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);  // rows are not interleaved: one row's operands and sums live at a time
         }
     };
     // Two register sets alternate: the next group's loads are in flight while the current one is
@@ -289,17 +284,19 @@ int launch_gemm_mfma_grouped(const void* packed, const void* codebook, int N, in
     auto* cb = static_cast<const uint4*>(codebook);
     auto* x4 = static_cast<const uint4*>(xq);
     auto* sc = static_cast<const uint16_t*>(scale);
+#define RCP_MG(F16, NA)                                                                                                  \
+    do {                                                                                                                 \
+        if (P != nullptr) gemm_mfma_grouped_kernel<F16, NA, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P); \
+        else gemm_mfma_grouped_kernel<F16, NA, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);             \
+    } while (0)
     if (narrow) {
-        if (out_dt == RCP_F16)
-            gemm_mfma_grouped_kernel<true, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
-        else
-            gemm_mfma_grouped_kernel<false, true><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
+        if (out_dt == RCP_F16) RCP_MG(true, true);
+        else RCP_MG(false, true);
     } else {
-        if (out_dt == RCP_F16)
-            gemm_mfma_grouped_kernel<true, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
-        else
-            gemm_mfma_grouped_kernel<false, false><<<blocks, waves * 64, 0, st>>>(pk, cb, N, K, x4, sc, M, waves, out, P);
+        if (out_dt == RCP_F16) RCP_MG(true, false);
+        else RCP_MG(false, false);
     }
+#undef RCP_MG
     return check_launch("rcp_w2a4_gemm_grouped");
 }
 
