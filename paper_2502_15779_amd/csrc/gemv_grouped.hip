@@ -54,7 +54,9 @@ constexpr int GG_XU = 4;  // 16-value units of raw activations per thread: K <= 
 // every compute unit a workgroup otherwise): two lanes share a group, four units each -- the sum over levels is linear
 // in the per-level sums, so each lane multiplies the sums over its own 64 columns by the group's levels and nothing but
 // the four fp32 row totals ever crosses lanes (the per-group sums are put together only for the optional P output).
-template <bool OUT_F16, int XDT, bool NT = false, int LG = 32>
+// WANTP: the per-group sums go to Pout as well (a verification output; its stores and exchanges stay out of the loop of
+// the production instantiation).
+template <bool OUT_F16, int XDT, bool NT = false, int LG = 32, bool WANTP = false>
 __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* __restrict__ packed,
                                                                   const uint4* __restrict__ codebook, int N, int K,
                                                                   const void* __restrict__ xraw,
@@ -266,7 +268,7 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             v = fmaf(c2, static_cast<float>(P2), v);
             v = fmaf(c3, static_cast<float>(P3), v);
             o[r] = v;
-            if (Pout != nullptr) {  // uniform
+            if constexpr (WANTP) {
                 int4 Pg = make_int4(P0, P1, P2, P3);
                 if constexpr (SPL == 2) {  // the group's sums: this lane's 64 columns plus the other lane's
                     Pg.x += __shfl_xor(P0, 32, 64);
@@ -339,10 +341,14 @@ struct GroupedArgs {
 template <bool OUT_F16, int XDT, bool NT, int LG = 32>
 static int launch_grouped_nt(const GroupedArgs& a, int blocks, size_t lds, hipStream_t st)
 {
-    gemv_grouped_kernel<OUT_F16, XDT, NT, LG><<<blocks, GG_THREADS, lds, st>>>(
-        static_cast<const uint4*>(a.packed), static_cast<const uint4*>(a.codebook), a.N, a.K, a.xraw,
-        static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.clip_ratio, blocks, a.out, a.P,
-        static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
+    auto launch = [&](auto kernel) {
+        kernel<<<blocks, GG_THREADS, lds, st>>>(
+            static_cast<const uint4*>(a.packed), static_cast<const uint4*>(a.codebook), a.N, a.K, a.xraw,
+            static_cast<const uint4*>(a.xq), static_cast<const uint16_t*>(a.scale), a.clip_ratio, blocks, a.out, a.P,
+            static_cast<uint32_t*>(a.xq_out), static_cast<uint16_t*>(a.scale_out));
+    };
+    if (a.P != nullptr) launch(&gemv_grouped_kernel<OUT_F16, XDT, NT, LG, true>);
+    else launch(&gemv_grouped_kernel<OUT_F16, XDT, NT, LG, false>);
     return check_launch("rcp_w2a4_gemv_grouped");
 }
 
