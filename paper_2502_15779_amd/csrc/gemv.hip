@@ -336,15 +336,38 @@ __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__
         uint32_t* sx1 = reinterpret_cast<uint32_t*>(smem4);
         const bool publish = blockIdx.x == 0 && xq_out != nullptr;
         int s = 0;
+        // all groups of eight are rounded first, without branches, so that their instruction chains interleave
+        // (a thread past the end of the token works on a duplicate of the last group and stores nothing)
+        uint32_t qd[GEMV_XG];
+        const float rs = __frcp_rn(sq);
+        float far = 0.0f;
+#pragma unroll
+        for (int i = 0; i < GEMV_XG; ++i) {
+            if (i * TH >= xdw) break;
+            qd[i] = quantize8_fast(xr8[i], rs, far);
+        }
+        if (__builtin_expect(far > 0.49999f, 0)) {
+#pragma unroll
+            for (int i = 0; i < GEMV_XG; ++i) {
+                if (i * TH >= xdw) break;
+                qd[i] = quantize8_exact(xr8[i], sq);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < GEMV_XG; ++i) {
             if (i * TH >= xdw) break;
             const int u8 = threadIdx.x + i * TH;
             if (u8 < xdw) {
-                const uint32_t qd = quantize8(xr8[i], sq);
-                sx1[u8] = qd;
-                if (publish) xq_out[u8] = qd;
-                s = dot8(qd, 0x11111111u, s);
+                sx1[u8] = qd[i];
+                s = dot8(qd[i], 0x11111111u, s);
+            }
+        }
+        if (publish) {
+#pragma unroll
+            for (int i = 0; i < GEMV_XG; ++i) {
+                if (i * TH >= xdw) break;
+                const int u8 = threadIdx.x + i * TH;
+                if (u8 < xdw) xq_out[u8] = qd[i];
             }
         }
         if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out != nullptr) scale_out[0] = sb;

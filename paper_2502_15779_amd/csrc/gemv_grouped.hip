@@ -197,20 +197,46 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
         const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
         S = half_bits_to_float(sb);
         const bool publish = blockIdx.x == 0 && xq_out != nullptr;
+        // all units are rounded first, without branches, so that their instruction chains interleave (a thread past the
+        // end of the token works on a duplicate of the last unit and stores nothing)
+        uint2 qv[GG_XU];
+        const float rs = __frcp_rn(S);
+        float far = 0.0f;
+#pragma unroll
+        for (int i = 0; i < GG_XU; ++i) {
+            if (i * GG_THREADS >= U) break;
+            float v[2][8];
+            widen8<XT>(xr[i][0], v[0]);
+            widen8<XT>(xr[i][1], v[1]);
+            qv[i] = make_uint2(quantize8_fast(v[0], rs, far), quantize8_fast(v[1], rs, far));
+        }
+        if (__builtin_expect(far > 0.49999f, 0)) {
+#pragma unroll
+            for (int i = 0; i < GG_XU; ++i) {
+                if (i * GG_THREADS >= U) break;
+                float v[2][8];
+                widen8<XT>(xr[i][0], v[0]);
+                widen8<XT>(xr[i][1], v[1]);
+                qv[i] = make_uint2(quantize8_exact(v[0], S), quantize8_exact(v[1], S));
+            }
+        }
 #pragma unroll
         for (int i = 0; i < GG_XU; ++i) {
             if (i * GG_THREADS >= U) break;
             const int u = threadIdx.x + i * GG_THREADS;
             if (u < U) {
-                float v[2][8];
-                widen8<XT>(xr[i][0], v[0]);
-                widen8<XT>(xr[i][1], v[1]);
-                const uint32_t q0 = quantize8(v[0], S), q1 = quantize8(v[1], S);
                 const int g = u >> 3, r0 = g >> 5;
                 const int R = min(32, NG - 32 * r0);
-                sx2[256 * r0 + (u & 7) * R + (g & 31)] = make_uint2(q0, q1);
-                atomicAdd(&tgs[SPL == 2 ? 2 * g + ((u & 7) >> 2) : g], dot8(q1, 0x11111111u, dot8(q0, 0x11111111u, 0)));
-                if (publish) reinterpret_cast<uint2*>(xq_out)[u] = make_uint2(q0, q1);
+                sx2[256 * r0 + (u & 7) * R + (g & 31)] = qv[i];
+                atomicAdd(&tgs[SPL == 2 ? 2 * g + ((u & 7) >> 2) : g], dot8(qv[i].y, 0x11111111u, dot8(qv[i].x, 0x11111111u, 0)));
+            }
+        }
+        if (publish) {
+#pragma unroll
+            for (int i = 0; i < GG_XU; ++i) {
+                if (i * GG_THREADS >= U) break;
+                const int u = threadIdx.x + i * GG_THREADS;
+                if (u < U) reinterpret_cast<uint2*>(xq_out)[u] = qv[i];
             }
         }
         if (blockIdx.x == 0 && threadIdx.x == 0 && scale_out != nullptr) scale_out[0] = sb;

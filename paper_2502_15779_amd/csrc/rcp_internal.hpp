@@ -467,6 +467,40 @@ __device__ __forceinline__ uint16_t scale_bits_from_amax(float a, float clip_rat
 // The clamped integers r_j are packed four at a time in binary32, where
 // sum_j (r_j + 8) * 16^j < 2^16 is exact, and the offset-binary nibbles become two's
 // complement by flipping each nibble's top bit.
+// The same in two pieces for callers that quantise several groups of eight and want their instruction chains
+// interleaved: quantize8_fast rounds through the reciprocal without any branch and keeps, in `far`, the largest distance
+// of a scaled value from its rounded value; if that ends up above 0.49999 for a lane, the caller redoes that lane's
+// groups with quantize8_exact (one rarely taken branch for all groups instead of one per group).
+__device__ __forceinline__ uint32_t pack8_int4(const float (&n)[8])
+{
+    float r[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) r[j] = __builtin_amdgcn_fmed3f(n[j], -8.0f, 7.0f);
+    const float lo = fmaf(r[3], 4096.0f, fmaf(r[2], 256.0f, fmaf(r[1], 16.0f, r[0] + 34952.0f)));  // + 0x8888
+    const float hi = fmaf(r[7], 4096.0f, fmaf(r[6], 256.0f, fmaf(r[5], 16.0f, r[4] + 34952.0f)));
+    return (static_cast<uint32_t>(lo) | (static_cast<uint32_t>(hi) << 16)) ^ 0x88888888u;
+}
+
+__device__ __forceinline__ uint32_t quantize8_fast(const float (&y)[8], float rs, float& far)
+{
+    float n[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float t = __fmul_rn(y[j], rs);
+        n[j] = rintf(t);
+        far = fmaxf(far, fabsf(t - n[j]));
+    }
+    return pack8_int4(n);
+}
+
+__device__ __forceinline__ uint32_t quantize8_exact(const float (&y)[8], float s)
+{
+    float n[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) n[j] = rintf(__fdiv_rn(y[j], s));
+    return pack8_int4(n);
+}
+
 __device__ __forceinline__ uint32_t quantize8(const float (&y)[8], float s)
 {
     const float rs = __frcp_rn(s);

@@ -198,6 +198,29 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
         const bool publish = blockIdx.x == 0 && xq_out != nullptr;
         uint2* sx2 = reinterpret_cast<uint2*>(smem4);
         int s = 0;
+        // the units in registers are rounded first, without branches, so that their instruction chains interleave (a
+        // thread past the end of the token works on a duplicate of the last unit and stores zeros)
+        uint2 qr[W3_XR];
+        const float rs = __frcp_rn(S);
+        float far = 0.0f;
+#pragma unroll
+        for (int i = 0; i < W3_XR; ++i) {
+            if (i * W3_THREADS >= U16) break;  // uniform
+            float v[2][8];
+            widen8<XT>(xr[i][0], v[0]);
+            widen8<XT>(xr[i][1], v[1]);
+            qr[i] = make_uint2(quantize8_fast(v[0], rs, far), quantize8_fast(v[1], rs, far));
+        }
+        if (__builtin_expect(far > 0.49999f, 0)) {
+#pragma unroll
+            for (int i = 0; i < W3_XR; ++i) {
+                if (i * W3_THREADS >= U16) break;
+                float v[2][8];
+                widen8<XT>(xr[i][0], v[0]);
+                widen8<XT>(xr[i][1], v[1]);
+                qr[i] = make_uint2(quantize8_exact(v[0], S), quantize8_exact(v[1], S));
+            }
+        }
 #pragma unroll
         for (int i = 0; i < W3_XR; ++i) {  // the padding up to whole blocks is zeroed too
             if (i * W3_THREADS >= 2 * xpieces) break;  // uniform
@@ -205,10 +228,7 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
             if (u < 2 * xpieces) {
                 uint2 qv = make_uint2(0u, 0u);
                 if (u < U16) {
-                    float v[2][8];
-                    widen8<XT>(xr[i][0], v[0]);
-                    widen8<XT>(xr[i][1], v[1]);
-                    qv = make_uint2(quantize8(v[0], S), quantize8(v[1], S));
+                    qv = qr[i];
                     s = dot8(qv.y, 0x11111111u, dot8(qv.x, 0x11111111u, s));
                     if (publish) xq_out[u] = qv;
                 }
