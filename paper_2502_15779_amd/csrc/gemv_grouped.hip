@@ -201,6 +201,8 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
         // end of the token works on a duplicate of the last unit and stores nothing)
         uint2 qv[GG_XU];
         const float rs = __frcp_rn(S);
+        // fp16 / bf16 values straight from memory take the form of the quantiser that needs no second pass
+        constexpr bool SHORT_IN = (XT == RCP_F16 || XT == RCP_BF16);
         float far = 0.0f;
 #pragma unroll
         for (int i = 0; i < GG_XU; ++i) {
@@ -208,9 +210,10 @@ __global__ __launch_bounds__(GG_THREADS) void gemv_grouped_kernel(const uint4* _
             float v[2][8];
             widen8<XT>(xr[i][0], v[0]);
             widen8<XT>(xr[i][1], v[1]);
-            qv[i] = make_uint2(quantize8_fast(v[0], rs, far), quantize8_fast(v[1], rs, far));
+            qv[i] = SHORT_IN ? make_uint2(quantize8_short(v[0], S, rs), quantize8_short(v[1], S, rs))
+                             : make_uint2(quantize8_fast(v[0], rs, far), quantize8_fast(v[1], rs, far));
         }
-        if (__builtin_expect(far > 0.49999f, 0)) {
+        if (!SHORT_IN && __builtin_expect(far > 0.49999f, 0)) {
 #pragma unroll
             for (int i = 0; i < GG_XU; ++i) {
                 if (i * GG_THREADS >= U) break;

@@ -138,13 +138,15 @@ __global__ __launch_bounds__(ONE_WAVES * 64) void gemv_oneshot_kernel(const uint
         // (a thread past the end of the token works on a duplicate of the last group and stores nothing)
         uint32_t qd[ONE_XG];
         const float rs = __frcp_rn(sc);
+        // fp16 / bf16 values straight from memory take the form of the quantiser that needs no second pass
+        constexpr bool SHORT_IN = (XT == RCP_F16 || XT == RCP_BF16);
         float far = 0.0f;
 #pragma unroll
         for (int i = 0; i < ONE_XG; ++i) {
             if (i * TH >= xdw) break;
-            qd[i] = quantize8_fast(xr8[i], rs, far);
+            qd[i] = SHORT_IN ? quantize8_short(xr8[i], sc, rs) : quantize8_fast(xr8[i], rs, far);
         }
-        if (__builtin_expect(far > 0.49999f, 0)) {
+        if (!SHORT_IN && __builtin_expect(far > 0.49999f, 0)) {
 #pragma unroll
             for (int i = 0; i < ONE_XG; ++i) {
                 if (i * TH >= xdw) break;

@@ -470,7 +470,9 @@ __device__ __forceinline__ uint16_t scale_bits_from_amax(float a, float clip_rat
 // The same in two pieces for callers that quantise several groups of eight and want their instruction chains
 // interleaved: quantize8_fast rounds through the reciprocal without any branch and keeps, in `far`, the largest distance
 // of a scaled value from its rounded value; if that ends up above 0.49999 for a lane, the caller redoes that lane's
-// groups with quantize8_exact (one rarely taken branch for all groups instead of one per group).
+// groups with quantize8_exact (one branch for all groups instead of one per group).  That is for binary32 inputs, where
+// a value that close to a boundary is a one-in-50000 event; 16-bit inputs, where exact ties are a one-in-a-thousand
+// event per value and most wavefronts would take the branch, go through quantize8_short instead.
 __device__ __forceinline__ uint32_t pack8_int4(const float (&n)[8])
 {
     float r[8];
@@ -489,6 +491,26 @@ __device__ __forceinline__ uint32_t quantize8_fast(const float (&y)[8], float rs
         const float t = __fmul_rn(y[j], rs);
         n[j] = rintf(t);
         far = fmaxf(far, fabsf(t - n[j]));
+    }
+    return pack8_int4(n);
+}
+
+// For y that holds fp16 or bf16 numbers as they came from memory (no rotation in between): no second pass at all.  With
+// at most 11 significant bits in y and in the fp16 scale, the exact quotient y/s is either exactly a half-integer k + 1/2
+// or at least 2^-13 away from every one of them up to 16.5 ((2 m_y 2^e - (2k+1) m_s) / (2 m_s) with integers m < 2^11 is
+// zero or at least that large).  One Newton step on the quotient, q1 = q0 + (y - q0 s) (1/s) with the residual taken
+// exactly by a fused multiply-add, lands on k + 1/2 itself in the first case (the residual's share of the error of 1/s is
+// far below half a unit in the last place), where rint breaks the tie to even exactly like the correctly rounded
+// quotient would; in the second case q1 and the correctly rounded quotient are both within 2e-6 of the exact one and on
+// the same side of every boundary.  Beyond 16.5 both clamp to the same end.
+__device__ __forceinline__ uint32_t quantize8_short(const float (&y)[8], float s, float rs)
+{
+    float n[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float q0 = __fmul_rn(y[j], rs);
+        const float q1 = __fmaf_rn(__fmaf_rn(-q0, s, y[j]), rs, q0);
+        n[j] = rintf(q1);
     }
     return pack8_int4(n);
 }

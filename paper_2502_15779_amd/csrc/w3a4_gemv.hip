@@ -202,6 +202,8 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
         // thread past the end of the token works on a duplicate of the last unit and stores zeros)
         uint2 qr[W3_XR];
         const float rs = __frcp_rn(S);
+        // fp16 / bf16 values straight from memory take the form of the quantiser that needs no second pass
+        constexpr bool SHORT_IN = (XT == RCP_F16 || XT == RCP_BF16);
         float far = 0.0f;
 #pragma unroll
         for (int i = 0; i < W3_XR; ++i) {
@@ -209,9 +211,10 @@ __global__ __launch_bounds__(W3_THREADS) void w3a4_gemv_kernel(const uint8_t* __
             float v[2][8];
             widen8<XT>(xr[i][0], v[0]);
             widen8<XT>(xr[i][1], v[1]);
-            qr[i] = make_uint2(quantize8_fast(v[0], rs, far), quantize8_fast(v[1], rs, far));
+            qr[i] = SHORT_IN ? make_uint2(quantize8_short(v[0], S, rs), quantize8_short(v[1], S, rs))
+                             : make_uint2(quantize8_fast(v[0], rs, far), quantize8_fast(v[1], rs, far));
         }
-        if (__builtin_expect(far > 0.49999f, 0)) {
+        if (!SHORT_IN && __builtin_expect(far > 0.49999f, 0)) {
 #pragma unroll
             for (int i = 0; i < W3_XR; ++i) {
                 if (i * W3_THREADS >= U16) break;

@@ -507,6 +507,67 @@ def test_matrix_core_kernel_extreme_activations(rows):
     assert np.array_equal(out.cpu().numpy().astype(np.float64), ref_O)
 
 
+def _tie_activations(kind, dtype, K):
+    """One token whose scaled values sit on or next to the quantiser's rounding boundaries k + 1/2."""
+    rng = np.random.default_rng(77 + K)
+    if kind == "exact":
+        # S = 0.25 exactly (amax 1.75); every other value is an odd multiple of S/2: all of them exact ties
+        x = (0.125 * (2 * rng.integers(-7, 7, size=K) + 1)).astype(np.float32)
+        x[0] = 1.75
+    else:
+        # an arbitrary scale; values are (k + 1/2) S rounded to the storage type, and their neighbours one step up or down
+        amax = np.float32(3.3711)
+        S = np.float16(amax / np.float32(7.0)).astype(np.float32)
+        x = ((rng.integers(-7, 7, size=K) + 0.5) * S).astype(np.float32)
+        x[0] = amax
+    if dtype == "f16":
+        x = x.astype(np.float16)
+        if kind == "near":
+            step = rng.integers(-1, 2, size=K).astype(np.int16)
+            step[0] = 0
+            x = (x.view(np.int16) + step).view(np.float16)
+        return _t(x)
+    if dtype == "bf16":
+        return _t(x).to(torch.bfloat16)
+    if kind == "near":
+        x = np.nextafter(x, x + rng.integers(-1, 2, size=K).astype(np.float32), dtype=np.float32)
+        x[0] = np.float32(3.3711)
+    return _t(x)
+
+
+@pytest.mark.parametrize("kind", ["exact", "near"])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("path", ["general", "oneshot", "grouped", "w3"])
+@pytest.mark.parametrize("K", [4096, 11008])
+def test_fused_quantisers_on_rounding_ties(path, dtype, kind, K):
+    """x / S on and around the boundaries k + 1/2: the fused prologues (which resolve ties of 16-bit inputs arithmetically
+    and redo 32-bit inputs with the IEEE division) must give the oracle's x_q and S bit for bit."""
+    N = 1028
+    _say(f"fused quantisers on ties {path} {dtype} {kind} K={K}")
+    xd = _tie_activations(kind, dtype, K)
+    x32 = xd.to(torch.float32).cpu().numpy().reshape(1, K)
+    ref_xq, ref_sc, _ = oracle.quantize_act(x32, 1.0)
+    xq = torch.zeros((1, K // 2), dtype=torch.uint8, device=DEV)
+    sc = torch.zeros((1,), dtype=torch.float16, device=DEV)
+    rng = np.random.default_rng(5)
+    if path in ("general", "oneshot"):
+        rcp.set_option("gemv_oneshot", 1 if path == "oneshot" else 2)
+        pk = torch.randint(0, 256, (N * K // 4,), dtype=torch.uint8, device=DEV)
+        cb = _t(np.sort(rng.standard_normal((N, 4)) * 0.03, axis=1).astype(np.float16))
+        rcp.quant_w2a4_gemv(pk, cb, N, K, xd, 1.0, xq_out=xq, scale_out=sc)
+    elif path == "grouped":
+        pk = torch.randint(0, 256, (N * K // 4,), dtype=torch.uint8, device=DEV)
+        cb = _t(np.sort(rng.standard_normal((N // 4, K // 128, 4, 4)) * 0.03, axis=3).astype(np.float16))
+        rcp.quant_w2a4_gemv_grouped(pk, cb, N, K, xd, 1.0, xq_out=xq, scale_out=sc)
+    else:
+        pk = torch.randint(0, 256, (3 * N * K // 8,), dtype=torch.uint8, device=DEV)
+        cb = _t(np.sort(rng.standard_normal((N, 8)) * 0.03, axis=1).astype(np.float16))
+        rcp.quant_w3a4_gemv(pk, cb, N, K, xd, 1.0, xq_out=xq, scale_out=sc)
+    torch.cuda.synchronize()
+    assert np.array_equal(sc.cpu().numpy().view(np.uint16), ref_sc)
+    assert np.array_equal(xq.cpu().numpy(), ref_xq)
+
+
 @pytest.mark.parametrize("waves", [0, 4, 8])
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
 @pytest.mark.parametrize("N,K,ratio", [(256, 512, 1.0), (1028, 4096, 1.0), (40, 2080, 0.9), (64, 11008, 1.0),
