@@ -56,10 +56,13 @@ __global__ __launch_bounds__(1024) void quant_kernel(const void* __restrict__ x,
     a = block_max(a, red, threads >> 6);
     const uint16_t sb = scale_bits_from_amax(a, clip_ratio);
     const float s = half_bits_to_float(sb);
+    const float rs = __frcp_rn(s);
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int u = threadIdx.x + it * threads;
-        if (u < units) xq[static_cast<size_t>(token) * units + u] = quantize8(v[it], s);
+        // (16-bit inputs: the form of the quantiser that lands exactly on rounding ties and never needs a division)
+        if (u < units)
+            xq[static_cast<size_t>(token) * units + u] = DT == RCP_F32 ? quantize8(v[it], s) : quantize8_short(v[it], s, rs);
     }
     if (threadIdx.x == 0) scale[token] = sb;
 }

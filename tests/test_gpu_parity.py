@@ -537,7 +537,7 @@ def _tie_activations(kind, dtype, K):
 
 @pytest.mark.parametrize("kind", ["exact", "near"])
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
-@pytest.mark.parametrize("path", ["general", "oneshot", "grouped", "w3"])
+@pytest.mark.parametrize("path", ["general", "oneshot", "grouped", "w3", "act"])
 @pytest.mark.parametrize("K", [4096, 11008])
 def test_fused_quantisers_on_rounding_ties(path, dtype, kind, K):
     """x / S on and around the boundaries k + 1/2: the fused prologues (which resolve ties of 16-bit inputs arithmetically
@@ -550,7 +550,9 @@ def test_fused_quantisers_on_rounding_ties(path, dtype, kind, K):
     xq = torch.zeros((1, K // 2), dtype=torch.uint8, device=DEV)
     sc = torch.zeros((1,), dtype=torch.float16, device=DEV)
     rng = np.random.default_rng(5)
-    if path in ("general", "oneshot"):
+    if path == "act":  # the quantiser as a launch of its own
+        xq, sc = rcp.rotate_quant_act(xd.reshape(1, K))
+    elif path in ("general", "oneshot"):
         rcp.set_option("gemv_oneshot", 1 if path == "oneshot" else 2)
         pk = torch.randint(0, 256, (N * K // 4,), dtype=torch.uint8, device=DEV)
         cb = _t(np.sort(rng.standard_normal((N, 4)) * 0.03, axis=1).astype(np.float16))
