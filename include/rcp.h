@@ -217,6 +217,8 @@ int rcp_pack_weights(const void* W, rcp_dtype w_dtype, int N, int K,
  *     q_k    = clamp( round_half_even( y_k / S ), -8, 7 )
  * The Hadamard factor is the Sylvester matrix in natural order scaled by
  * 1/sqrt(n) (Appendix definition), with no random sign vector.
+ * Activations must be finite: the codes of a token that holds an infinity or a NaN
+ * are unspecified (here and in the calls that quantise in their prologue).
  *
  * x: row-major M x K in `x_dtype`.  rot: host pointer, NULL = RCP_ROT_NONE.
  * clip_ratio in (0, 1] (the paper's table uses 0.9).  xq_out: M*K/2 bytes.
