@@ -335,6 +335,9 @@ __global__ __launch_bounds__(KRON_THREADS) void kron_split_kernel(const void* __
     constexpr int QW = KRON_SPLIT_MAXQ / RPL;  // groups of four columns a wavefront can take
     using XT = typename XStore<DT>::type;
     const int token = blockIdx.y, jcol = blockIdx.x;
+    // the grid is rounded up to a multiple of eight workgroups, one per die in turn (whole workgroups leave here;
+    // step 0.744 -> 0.741 ms)
+    if (jcol >= m) return;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int K = 64 * RPL * m, quads = m / 4;
@@ -428,7 +431,7 @@ __global__ __launch_bounds__(KRON_THREADS) void kron_split_kernel(const void* __
 template <int DT, int RPL>
 static int launch_kron_split(const void* x, int M, const rcp_rotation* rot, float* y, float norm, hipStream_t st)
 {
-    dim3 grid(rot->m, M);
+    dim3 grid((rot->m + 7) / 8 * 8, M);
     kron_split_kernel<DT, RPL><<<grid, KRON_THREADS, 0, st>>>(x, rot->m, rot->Q, norm, y);
     return check_launch("rcp_rotate_quant_act(kron)");
 }
