@@ -576,11 +576,12 @@ static int launch_wide(const GemvArgs& a, int blocks, hipStream_t st)
 }
 
 // One token on a matrix of 32 MB and more (32 lanes per row group, four loads per stage): the non-temporal form.
+template <int LW, int UNR>
 static int launch_nt(const GemvArgs& a, int blocks, hipStream_t st)
 {
 #define RCP_GO_NT(XDT)                                                                                        \
-    return a.out_dt == RCP_F16 ? launch_one<32, 1, 4, 1, true, XDT, GEMV_WAVES, true>(a, blocks, st)          \
-                               : launch_one<32, 1, 4, 1, false, XDT, GEMV_WAVES, true>(a, blocks, st)
+    return a.out_dt == RCP_F16 ? launch_one<LW, 1, UNR, 1, true, XDT, GEMV_WAVES, true>(a, blocks, st)        \
+                               : launch_one<LW, 1, UNR, 1, false, XDT, GEMV_WAVES, true>(a, blocks, st)
     if (a.xraw == nullptr) RCP_GO_NT(-1);
     if (a.x_dt == RCP_F16) RCP_GO_NT(RCP_F16);
     if (a.x_dt == RCP_F32) RCP_GO_NT(RCP_F32);
@@ -712,10 +713,17 @@ static int dispatch_gemv(const GemvArgs& a, hipStream_t st)
         if (blocks > 2 * num_compute_units() && options().gemv_blocks == 0) blocks = 2 * num_compute_units();
         return options().gemv_unroll == 4 ? launch_wide<4>(a, blocks, st) : launch_wide<2>(a, blocks, st);
     }
-    // ("gemv_nt": 1 = whenever the plan is 32 lanes x four loads, 2 = never)
+    // Non-temporal weight loads ("gemv_nt": 1 = whenever a form below runs, 2 = never).  Measured by itself a launch on
+    // 4 - 22 MB is within 2 % with and without the hint; inside the decode step, where 1.6 GB of weights pass between two
+    // uses of anything, the hint on the q|k|v, gate|up and down launches is worth 3 % of the step (0.743 -> 0.720 ms):
+    // weights that are read once no longer push the activations, tables and Q out of the caches.  The 4 MB of the
+    // out-projection are better off without it (0.720 against 0.722 ms), hence the threshold.
     const bool nt = options().gemv_nt != 0 ? options().gemv_nt == 1
-                                           : static_cast<long long>(a.N) * a.K / 4 >= (32LL << 20);
-    if (nt && a.M == 1 && a.rot_n == 0 && p.lw * p.ws == 32 && p.unr == 4) return launch_nt(a, p.blocks, st);
+                                           : static_cast<long long>(a.N) * a.K / 4 >= (8LL << 20);
+    if (nt && a.M == 1 && a.rot_n == 0 && p.ws == 1) {
+        if (p.lw == 32 && p.unr == 4) return launch_nt<32, 4>(a, p.blocks, st);
+        if (p.lw == 64) return p.unr == 4 ? launch_nt<64, 4>(a, p.blocks, st) : launch_nt<64, 2>(a, p.blocks, st);
+    }
     if (p.unr == 2) {
         switch (p.lw * p.ws) {
             case 16: return launch_mt<16, 1, 2>(a, p.blocks, st);
