@@ -48,8 +48,9 @@ constexpr int GG_XU = 4;  // 16-value units of raw activations per thread: K <= 
 
 // (The first 56 bytes of arguments reach the wavefront in scalar registers at launch: everything the
 // prologue needs at once is among them.)
-// NT: weight loads with the non-temporal hint (matrices of 10 MB and more: 22016 x 4096 8.15 -> 7.95 us, 4096 x 11008
-// 6.84 -> 6.67; the 4 MB of 4096 x 4096 are 11 % slower with it).
+// NT: weight loads with the non-temporal hint (22016 x 4096 8.15 -> 7.95 us, 4096 x 11008 6.84 -> 6.67; the 5 MB of
+// 4096 x 4096 are 11 % slower with it on a sweep of their own, but inside the decode step, where weights that bypass the
+// caches leave the activations and tables in them, the hint on that launch too is worth 1.2 % of the step: on from 4 MB).
 // LG: lanes per group of four rows.  32: a lane owns whole quantisation groups.  64 (matrices with too few rows to give
 // every compute unit a workgroup otherwise): two lanes share a group, four units each -- the sum over levels is linear
 // in the per-level sums, so each lane multiplies the sums over its own 64 columns by the group's levels and nothing but
@@ -385,12 +386,12 @@ template <bool OUT_F16, int XDT>
 static int launch_grouped_one(const GroupedArgs& a, int blocks, size_t lds, bool two_lanes, hipStream_t st)
 {
     if (two_lanes) {
-        const bool nt2 = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(a.N) * a.K / 4 >= (10LL << 20);
+        const bool nt2 = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(a.N) * a.K / 4 >= (4LL << 20);
         return nt2 ? launch_grouped_nt<OUT_F16, XDT, true, 64>(a, blocks, lds, st)
                    : launch_grouped_nt<OUT_F16, XDT, false, 64>(a, blocks, lds, st);
     }
-    // ("gemv_nt": 1 = non-temporal weight loads always, 2 = never; automatic: from 10 MB of packed weights on)
-    const bool nt = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(a.N) * a.K / 4 >= (10LL << 20);
+    // ("gemv_nt": 1 = non-temporal weight loads always, 2 = never; automatic: from 4 MB of packed weights on)
+    const bool nt = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(a.N) * a.K / 4 >= (4LL << 20);
     return nt ? launch_grouped_nt<OUT_F16, XDT, true>(a, blocks, lds, st) : launch_grouped_nt<OUT_F16, XDT, false>(a, blocks, lds, st);
 }
 
