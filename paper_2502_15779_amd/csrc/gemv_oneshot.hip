@@ -28,7 +28,8 @@ constexpr int ONE_WAVES = 4;  // wavefronts (= row groups) per workgroup
 // XDT = RCP_F16 / RCP_F32 / RCP_BF16: x_in is the raw activation; the workgroup quantises it itself exactly as
 // quant_kernel would, and the first workgroup publishes x_q and S when xq_out / scale_out are given.
 // The first 56 bytes of arguments reach the wavefront in scalar registers at launch.
-template <int UPL, int XDT>
+// NT: the weight loads carry the non-temporal hint (see the launcher).
+template <int UPL, int XDT, bool NT = false>
 __global__ __launch_bounds__(ONE_WAVES * 64) void gemv_oneshot_kernel(const uint4* __restrict__ packed,
                                                                       const uint2* __restrict__ codebook, int N, int K,
                                                                       const void* __restrict__ x_in,
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(ONE_WAVES * 64) void gemv_oneshot_kernel(const uint
 #pragma unroll
         for (int i = 0; i < UPL; ++i) {
             const unsigned off = i < my_units ? base : 0x80000000u;
-            w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), i * 64 * 16, 0);
+            w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), i * 64 * 16, NT ? 2 : 0);
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -261,9 +262,16 @@ static int launch_oneshot_one(const void* packed, const void* codebook, int N, i
 {
     const size_t lds = static_cast<size_t>(UPL) * 64 * 8 + 2 * ONE_WAVES * sizeof(int);
     const int blocks = (N / 4 + ONE_WAVES - 1) / ONE_WAVES;
-    gemv_oneshot_kernel<UPL, XDT><<<blocks, ONE_WAVES * 64, lds, st>>>(
-        static_cast<const uint4*>(packed), static_cast<const uint2*>(codebook), N, K, x, static_cast<const uint16_t*>(scale),
-        out_dt == RCP_F16 ? 1 : 0, clip_ratio, out, P, static_cast<uint32_t*>(xq_out), static_cast<uint16_t*>(scale_out));
+    auto launch = [&](auto kernel) {
+        kernel<<<blocks, ONE_WAVES * 64, lds, st>>>(
+            static_cast<const uint4*>(packed), static_cast<const uint2*>(codebook), N, K, x, static_cast<const uint16_t*>(scale),
+            out_dt == RCP_F16 ? 1 : 0, clip_ratio, out, P, static_cast<uint32_t*>(xq_out), static_cast<uint16_t*>(scale_out));
+    };
+    // Non-temporal weight loads from 8 MB of packed weights on, as in the general kernel ("gemv_nt": 1 = always,
+    // 2 = never): judged inside a decode step, not on a sweep of this kernel.
+    const bool nt = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(N) * K / 4 >= (8LL << 20);
+    if (nt) launch(&gemv_oneshot_kernel<UPL, XDT, true>);
+    else launch(&gemv_oneshot_kernel<UPL, XDT, false>);
     return check_launch("rcp_w2a4_gemv");
 }
 
