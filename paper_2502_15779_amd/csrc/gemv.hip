@@ -73,8 +73,9 @@ __device__ __forceinline__ void heads_columns(float* sy, int m, float norm)
 
 // The first 56 bytes of arguments reach the wavefront in scalar registers at launch; everything the
 // prologue needs at once (matrix, shape, activations, the rotation) is among them.
-// NT: the weight loads carry the non-temporal hint -- a matrix of tens of megabytes is read once and need not displace
-// anything in the caches (134 MB: 25.8 -> 24.2 us; matrices of 4 - 12 MB are slower with it).
+// NT: the weight loads carry the non-temporal hint -- a matrix is read once and need not displace anything in the
+// caches (134 MB: 25.8 -> 24.2 us; on a sweep of their own matrices of 4 - 22 MB are level or slower with it, inside a
+// decode step the hint on launches of 8 MB and more is worth 3 % of the step: see the launcher).
 template <int LW, int WS, int UNR, int MT, bool OUT_F16, int XDT, int NW, bool NT = false>
 __global__ __launch_bounds__(NW * 64) void gemv_kernel(const uint4* __restrict__ packed,
                                                             const uint2* __restrict__ codebook, int N, int K,
@@ -575,7 +576,7 @@ static int launch_wide(const GemvArgs& a, int blocks, hipStream_t st)
 #undef RCP_GO8
 }
 
-// One token on a matrix of 32 MB and more (32 lanes per row group, four loads per stage): the non-temporal form.
+// One token, one wavefront or half a wavefront per row group, 8 MB of packed weights and more: the non-temporal form.
 template <int LW, int UNR>
 static int launch_nt(const GemvArgs& a, int blocks, hipStream_t st)
 {
