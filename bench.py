@@ -525,6 +525,25 @@ def main():
         b = N * K // 4 + 8 * N + 2 * K + 2 * N
         weight_only[label] = {"us": round(s * 1e6, 3), "GBps": round(b / s / 1e9, 1)}
 
+    # the whole one-token step with 16-bit activations (the paper's W2-only decode setting): rotation kernel + four
+    # rcp_w2a16_gemv launches per layer on the headline step's weights, the down input as the rotated binary32 vector
+    weight_only_step = None
+    if not args.step_only:
+        def wostep():
+            for l in range(L):
+                for i, (_, N, K, rotated) in enumerate(launches):
+                    if rotated:
+                        rcp.rotate_act(xs[i], rot_down, y_out=ybuf)
+                    packed, cb = layers[l][i]
+                    rcp.w2a16_gemv(packed, cb, N, K, ybuf if rotated else xs[i], out=outs[i])
+        wostep()
+        fn = capture(wostep)
+        fn()
+        s = timed(torch, fn, max(3, args.steps // 2))
+        wobytes = L * sum(N * K // 4 + 8 * N + (4 if rotated else 2) * K + 2 * N for (_, N, K, rotated) in launches)
+        weight_only_step = {"ms_per_step": round(s * 1e3, 4), "GBps": round(wobytes / s / 1e9, 1),
+                            "pct_of_hbm_peak": round(100.0 * wobytes / s / 1e9 / HBM_PEAK_GBPS, 2), "bytes_per_step": wobytes}
+
     # 3-bit variant (eight levels per output channel): pre-quantised activations, cold over L weight sets
     w3 = {}
     for label, i, N in side_shapes:
@@ -1055,6 +1074,7 @@ def main():
         "grouped_128": grouped,
         "grouped_128_step": grouped_step,
         "weight_only_fp16": weight_only,
+        "weight_only_step": weight_only_step,
         "w3a4": w3,
         "w3a4_step": w3_step,
         "kv4_attention_32_heads": kv4,

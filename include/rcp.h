@@ -153,7 +153,7 @@ int rcp_version(void);
  *   "gemv_nt"      weight loads of the one-token kernels with the non-temporal cache hint (the one-shot form and the
  *                  forms with one wavefront or half a wavefront per group of rows): 1 = whenever such a form runs, 2 = never; automatic =
  *                  from 8 MB of packed weights on; the 3-bit kernel (from 16 MB on) and the kernel for
- *                  group-wise tables (from 4 MB on) likewise
+ *                  group-wise tables (from 4 MB on) and the weight-only kernel (from 4 MB on) likewise
  *   "gemm_stage"   128-column steps per pipeline stage of the matrix-core kernel: 1, 2 (automatic: 2 from eight steps
  *                  per wavefront on)
  *   "gemm_rows"    output rows per workgroup of the matrix-core kernel: 16 (four lanes per group of four rows), or

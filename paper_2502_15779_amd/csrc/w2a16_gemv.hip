@@ -64,7 +64,9 @@ __device__ __forceinline__ uint32_t lut_half(uint2 row, int l)
 // WS wavefronts share one row group (each with a table of its own; one LDS exchange of the four
 // row totals per row group): short, wide matrices would otherwise put a single wavefront on a
 // SIMD, which issues an instruction only every ~7 cycles.  UNR: 16-byte loads per lane and stage.
-template <bool XF32, int XDT, int WS, int UNR>
+// NT: weight loads with the non-temporal hint (launches of 4 MB and more: on a sweep of its own the kernel is level with
+// and without it, inside a decode step of 32 layers the hint is worth 1.6 %, 1.094 -> 1.077 ms).
+template <bool XF32, int XDT, int WS, int UNR, bool NT = false>
 __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restrict__ packed,
                                                            const uint2* __restrict__ codebook, int N, int K,
                                                            const void* __restrict__ x, void* __restrict__ out,
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
         for (int i = 0; i < WO_UNR; ++i) {
             const int it = ch * WO_UNR + i;
             const unsigned off = (it < my_units && row_ok) ? base : 0x80000000u;
-            w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), it * LG * 16, 0);
+            w[i] = __builtin_amdgcn_raw_buffer_load_b128(wres, static_cast<int>(off), it * LG * 16, NT ? 2 : 0);
         }
     };
     // the four LUT rows of a row group, one per 16 table entries: lane d builds entry d
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(WO_THREADS) void w2a16_kernel(const uint4* __restri
     }
 }
 
-template <bool XF32, int XDT, int WS, int UNR>
+template <bool XF32, int XDT, int WS, int UNR, bool NT>
 static int launch_wo_one(const void* packed, const void* codebook, int N, int K, const void* x, void* out, rcp_dtype out_dt,
                          hipStream_t st)
 {
@@ -296,7 +298,7 @@ static int launch_wo_one(const void* packed, const void* codebook, int N, int K,
                         static_cast<size_t>(wo_padded_units(K, 64 * WS * UNR)) * (XF32 ? 16 : 8) + 2 * WO_WAVES * 4) * 4;
     if (lds > 160 * 1024)
         return fail(RCP_ERR_UNSUPPORTED, "rcp_w2a16_gemv: K=%d needs %zu bytes of LDS for the activations", K, lds);
-    auto kernel = &w2a16_kernel<XF32, XDT, WS, UNR>;
+    auto kernel = &w2a16_kernel<XF32, XDT, WS, UNR, NT>;
     // the look-ups address the tables by absolute LDS offset: dynamic LDS must start at 0 (checked once
     // per kernel variant; the answer is a property of the compiled code)
     static int lds_checked = 0;  // 1 once the variant is known to have no static LDS
@@ -338,7 +340,12 @@ static int launch_wo(const void* packed, const void* codebook, int N, int K, con
     int unr = 1;
     for (int c = 2; c <= 4; c *= 2)
         if (((per_lane + c - 1) / c) * c * 10 <= per_lane * 11) unr = c;
-#define RCP_WO(WS, UNR) return launch_wo_one<XF32, XDT, WS, UNR>(packed, codebook, N, K, x, out, out_dt, st)
+    // ("gemv_nt": 1 = non-temporal weight loads always, 2 = never; automatic: from 4 MB of packed weights on -- with
+    // the out-projection's 4 MB left out the step takes 1.089 ms, with them in 1.077)
+    const bool nt = options().gemv_nt != 0 ? options().gemv_nt == 1 : static_cast<long long>(N) * K / 4 >= (4LL << 20);
+#define RCP_WO(WS, UNR)                                                                                      \
+    return nt ? launch_wo_one<XF32, XDT, WS, UNR, true>(packed, codebook, N, K, x, out, out_dt, st)          \
+              : launch_wo_one<XF32, XDT, WS, UNR, false>(packed, codebook, N, K, x, out, out_dt, st)
     if (ws == 1) { if (unr == 4) RCP_WO(1, 4); if (unr == 2) RCP_WO(1, 2); RCP_WO(1, 1); }
     if (ws == 2) { if (unr == 4) RCP_WO(2, 4); if (unr == 2) RCP_WO(2, 2); RCP_WO(2, 1); }
     if (unr == 4) RCP_WO(4, 4);
